@@ -1,0 +1,15 @@
+"""MI355X-native GSPN line-scan propagation (GSPN-2, Sec. 3.2 / 4): Python face of the C-ABI library.
+
+The compute lives in ``libgspn.so`` (hand-written HIP for gfx950); this
+package only marshals arguments.  Importing it is cheap; the shared library is
+loaded on first use and a missing library raises (there is no CPU fallback).
+"""
+from . import workloads  # noqa: F401
+
+
+def __getattr__(name):
+    if name in ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_status_string", "gspn_version",
+                "load_library", "lib_path", "GspnError"):
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(name)

@@ -1,0 +1,87 @@
+"""The seeded input generator: weight normalisation, storage rounding, slicing."""
+import numpy as np
+import pytest
+
+from oracle import gspn_oracle as O
+from paper_2512_07884_amd import workloads as WL
+
+
+def test_configs_match_the_benchmark_definition():
+    c = WL.CONFIGS
+    assert (c["unit16"].B, c["unit16"].C, c["unit16"].H, c["unit16"].W, c["unit16"].G) == (1, 8, 16, 16, 1)
+    assert c["unit16"].dir_mask == 1 and c["unit16"].dtype == "f32" and c["unit16"].seed == 0
+    assert (c["cls56"].B, c["cls56"].C, c["cls56"].H, c["cls56"].G, c["cls56"].cpg) == (64, 96, 56, 8, 12)
+    assert (c["diff128"].B, c["diff128"].C, c["diff128"].H, c["diff128"].G) == (2, 1024, 128, 16)
+    assert c["diff128"].logit_scale == 3.0
+    assert (c["long256x1024"].H, c["long256x1024"].W) == (256, 1024)
+    assert c["train28_gc"].G == 192 and c["train28_g4"].G == 4
+    # algorithmic bytes per pixel-channel: 10 + 12/cpg (fwd, D=4), 23 + 24/cpg (bwd)
+    k = c["diff128"]
+    assert k.fwd_algorithmic_bytes() == round((10 + 12 / 64) * 2 * k.pixel_channels)
+    k = c["train28_g4"]
+    assert k.bwd_algorithmic_bytes() == round((23 + 24 / 48) * 4 * k.pixel_channels)
+    assert k.fwd_algorithmic_bytes(save_h=True) == round((14 + 12 / 48) * 4 * k.pixel_channels)
+
+
+@pytest.mark.parametrize("d", [0, 1, 2, 3])
+def test_normalised_weights_are_row_stochastic_tridiagonals(d):
+    rng = np.random.default_rng(d)
+    H, W = 5, 6
+    w = WL.normalise_logits(rng.standard_normal((2, 3, H, W)) * 3, d)
+    assert np.all(w >= 0)
+    assert np.allclose(w.sum(axis=1), 1.0, atol=1e-15)
+    if d < 2:
+        assert not w[:, 0, :, 0].any() and not w[:, 2, :, -1].any()
+    else:
+        assert not w[:, 0, 0, :].any() and not w[:, 2, -1, :].any()
+    # rows of the assembled one-step matrix sum to 1 wherever a previous line exists
+    A = O.one_step_matrix_image(w[0], d, H, W)
+    rows = A.sum(axis=1).reshape(H, W)
+    has_prev = np.ones((H, W), bool)
+    if d == 0: has_prev[0] = False
+    if d == 1: has_prev[-1] = False
+    if d == 2: has_prev[:, 0] = False
+    if d == 3: has_prev[:, -1] = False
+    assert np.allclose(rows[has_prev], 1.0, atol=1e-14) and not rows[~has_prev].any()
+
+
+def test_line_of_length_one_keeps_only_the_centre_weight():
+    w = WL.normalise_logits(np.random.default_rng(0).standard_normal((3, 4, 1)), 0)
+    assert np.array_equal(w[1], np.ones((4, 1))) and not w[0].any() and not w[2].any()
+
+
+def test_bf16_rounding_is_nearest_even_and_roundtrips():
+    v = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.1415927, 1e-3, 0.0], dtype=np.float32)
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7: goes to even (1.0); 1 + 3*2^-8 ties up to 1 + 2^-6
+    bits = WL.f32_to_bf16_bits(v)
+    back = WL.bf16_bits_to_f32(bits)
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == np.float32(1.015625)
+    assert back[3] == -2.5 and back[6] == 0.0
+    assert np.all(np.abs(back - v) <= np.abs(v) * 2.0 ** -8)
+    assert np.array_equal(WL.f32_to_bf16_bits(back), bits)
+    import torch
+    t = torch.from_numpy(v).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(t, back)
+
+
+def test_slices_reassemble_into_the_full_tensors():
+    cfg = WL.shrink(WL.CONFIGS["cls56"], B=2, C=8, H=6, W=5, G=4)
+    full = WL.make_inputs(cfg)
+    s = WL.make_slice(cfg, 1, 2)
+    assert np.array_equal(full["x"][1, 4:6], s["x"])
+    assert np.array_equal(full["w"][:, 1, 2], s["w"])
+    assert np.array_equal(full["lam"][:, 1, 4:6], s["lam"])
+    assert np.array_equal(full["gy"][1, 4:6], s["gy"])
+    again = WL.make_inputs(cfg)
+    assert all(np.array_equal(full[k], again[k]) for k in full)
+    assert full["x"].dtype == np.uint16
+    f = WL.inputs_as_f64(full, cfg.dtype)
+    assert f["w"].dtype == np.float64 and abs(f["w"][0, 0, 0, :, 2, 2].sum() - 1) < 2 ** -7
+
+
+def test_unit_config_distributions():
+    cfg = WL.CONFIGS["unit16"]
+    inp = WL.inputs_as_f64(WL.make_inputs(cfg), cfg.dtype)
+    assert inp["x"].shape == (1, 8, 16, 16) and inp["w"].shape == (4, 1, 1, 3, 16, 16)
+    assert 0 <= inp["lam"].min() and inp["lam"].max() < 1 and 0 <= inp["u"].min() and inp["u"].max() < 1
+    assert abs(inp["x"].mean()) < 0.1 and 0.9 < inp["x"].std() < 1.1

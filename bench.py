@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused 4-direction GSPN scan on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all]
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+one ``gspn_scan_fwd`` call covering all four directions (inference workloads),
+or ``gspn_scan_fwd`` (saving h) + ``gspn_scan_bwd`` (training workloads).
+Inputs are resident in HBM before the timed region; buffer sets are rotated so
+that consecutive steps do not find their inputs in the 256 MB last-level cache.
+Prints ONE JSON line (see the keys below); ``--all`` additionally writes a table
+for every workload to gpurun_out/bench_all.json.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+DEFAULT_WORKLOAD = "diff128"   # 128x128 diffusion-latent shape: first of the two target shapes
+TRAINING = ("train28_gc", "train28_g4")
+
+
+def device_inputs(cfg, seed: int):
+    """Synthetic inputs with the distributions of workloads.make_slice, drawn on the device."""
+    import torch
+    td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    B, C, H, W, G = cfg.B, cfg.C, cfg.H, cfg.W, cfg.G
+    x = torch.randn((B, C, H, W), generator=g, device="cuda").to(td)
+    w = torch.empty((4, B, G, 3, H, W), dtype=td, device="cuda")
+    lam = torch.empty((4, B, C, H, W), dtype=td, device="cuda")
+    u = torch.empty((4, B, C, H, W), dtype=td, device="cuda")
+    for d in range(4):
+        z = torch.randn((B, G, 3, H, W), generator=g, device="cuda") * cfg.logit_scale
+        if d < 2:
+            z[:, :, 0, :, 0] = float("-inf"); z[:, :, 2, :, -1] = float("-inf")
+        else:
+            z[:, :, 0, 0, :] = float("-inf"); z[:, :, 2, -1, :] = float("-inf")
+        w[d] = torch.softmax(z.double(), dim=2).to(td)
+        lam[d] = torch.rand((B, C, H, W), generator=g, device="cuda").to(td)
+        u[d] = torch.rand((B, C, H, W), generator=g, device="cuda").to(td)
+        del z
+    gy = torch.randn((B, C, H, W), generator=g, device="cuda").to(td)
+    return {"x": x, "w": w, "lam": lam, "u": u, "gy": gy}
+
+
+def make_sets(cfg, training: bool, min_total_bytes: float = 1.0e9, max_sets: int = 4):
+    import torch
+    foot = cfg.fwd_algorithmic_bytes(save_h=training) + (cfg.bwd_algorithmic_bytes() if training else 0)
+    nsets = int(min(max_sets, max(1, math.ceil(min_total_bytes / foot))))
+    sets = []
+    for i in range(nsets):
+        s = device_inputs(cfg, 1000 + i)
+        s["y"] = torch.empty_like(s["x"])
+        if training:
+            s["hs"] = torch.empty_like(s["lam"])
+            s["gx"] = torch.empty_like(s["x"])
+            s["gw"] = torch.empty_like(s["w"])
+            s["glam"] = torch.empty_like(s["lam"])
+            s["gu"] = torch.empty_like(s["lam"])
+        sets.append(s)
+    return sets
+
+
+def run_workload(cfg, steps: int, warmup: int):
+    """Times `steps` steps; returns dict with wall ms/step and per-kernel event times."""
+    import torch
+    import paper_2512_07884_amd as G
+    training = cfg.name in TRAINING
+    sets = make_sets(cfg, training)
+    stream = torch.cuda.current_stream()
+
+    def fwd(s):
+        G.gspn_scan_fwd(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), G=cfg.G, dir_mask=cfg.dir_mask)
+
+    def bwd(s):
+        G.gspn_scan_bwd(s["gy"], s["x"], s["w"], s["lam"], s["u"], s["hs"], s["gx"], s["gw"], s["glam"],
+                        s["gu"], G=cfg.G, dir_mask=cfg.dir_mask)
+
+    for i in range(warmup):
+        s = sets[i % len(sets)]
+        fwd(s)
+        if training:
+            bwd(s)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        s = sets[i % len(sets)]
+        ev[i][0].record(stream)
+        fwd(s)
+        ev[i][1].record(stream)
+        if training:
+            bwd(s)
+            ev[i][2].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    fwd_ms = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    out = {"ms_per_step": (t1 - t0) * 1e3 / steps,
+           "fwd_ms_avg": sum(fwd_ms) / steps, "fwd_ms_med": fwd_ms[steps // 2], "fwd_ms_min": fwd_ms[0],
+           "n_sets": len(sets), "training": training}
+    if training:
+        bwd_ms = sorted(e[1].elapsed_time(e[2]) for e in ev)
+        out.update({"bwd_ms_avg": sum(bwd_ms) / steps, "bwd_ms_med": bwd_ms[steps // 2], "bwd_ms_min": bwd_ms[0]})
+    del sets
+    torch.cuda.empty_cache()
+    return out
+
+
+def summarise(cfg, r):
+    import paper_2512_07884_amd as G
+    dt = 1 if cfg.dtype == "bf16" else 0
+    training = r["training"]
+    fwd_bytes = cfg.fwd_algorithmic_bytes(save_h=training)
+    d = {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "G": cfg.G,
+         "storage": cfg.dtype, "directions": cfg.n_dirs,
+         "step": "fwd+bwd" if training else "fwd",
+         "ms_per_step": r["ms_per_step"],
+         "gpixel_ch_per_s": cfg.pixel_channels / (r["ms_per_step"] * 1e-3) / 1e9,
+         "fwd_kernel": G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, cfg.dir_mask, dt, 0, training),
+         "fwd_ms_avg": r["fwd_ms_avg"], "fwd_ms_min": r["fwd_ms_min"],
+         "fwd_algorithmic_bytes": fwd_bytes,
+         "fwd_algorithmic_GBs": fwd_bytes / (r["fwd_ms_avg"] * 1e-3) / 1e9,
+         "fwd_frac_of_hbm_peak": fwd_bytes / (r["fwd_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+         "buffer_sets_rotated": r["n_sets"]}
+    if training:
+        bb = cfg.bwd_algorithmic_bytes()
+        d.update({"bwd_kernel": G.gspn_bwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, cfg.dir_mask, dt, 0),
+                  "bwd_ms_avg": r["bwd_ms_avg"], "bwd_ms_min": r["bwd_ms_min"],
+                  "bwd_algorithmic_bytes": bb,
+                  "bwd_algorithmic_GBs": bb / (r["bwd_ms_avg"] * 1e-3) / 1e9,
+                  "bwd_frac_of_hbm_peak": bb / (r["bwd_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    return d
+
+
+# ---------------------------------------------------------------- CPU baseline (the oracle, as it stands)
+def _oracle_slice(args):
+    name, b, g, training = args
+    import numpy as np
+    from oracle import gspn_oracle as O
+    from paper_2512_07884_amd import workloads as WL
+    cfg = WL.CONFIGS[name]
+    s = WL.inputs_as_f64(WL.make_slice(cfg, b, g), cfg.dtype)
+    t0 = time.perf_counter()
+    y, h = O.scan_fwd(s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None], cfg.dir_mask)
+    if training:
+        O.scan_bwd(s["gy"][None], s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None], h,
+                   cfg.dir_mask)
+    return time.perf_counter() - t0, float(np.abs(y).sum())
+
+
+def cpu_baseline(cfg, training: bool, budget_s: float = 12.0):
+    """The fp64 NumPy oracle on (batch, group) slices of the same workload, one
+    slice per worker process, timed wall-clock over the pool (input generation
+    excluded from the single-slice probe, included in the pool's wall time is
+    avoided by timing only the oracle calls and dividing by the worker count)."""
+    import multiprocessing as mp
+    cores = max(1, min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)))
+    t_probe, _ = _oracle_slice((cfg.name, 0, 0, training))
+    slice_pc = cfg.cpg * cfg.H * cfg.W
+    total_slices = cfg.B * cfg.G
+    n = int(max(cores, min(total_slices, (budget_s * cores) // max(t_probe, 1e-4))))
+    n = min(n, total_slices)
+    jobs = [(cfg.name, (i // cfg.G) % cfg.B, i % cfg.G, training) for i in range(n)]
+    ctx = mp.get_context("fork")
+    t0 = time.perf_counter()
+    with ctx.Pool(min(cores, n)) as pool:
+        res = pool.map(_oracle_slice, jobs, chunksize=1)
+    wall = time.perf_counter() - t0
+    busy = sum(r[0] for r in res)
+    used = min(cores, n)
+    # throughput of `used` workers running the oracle concurrently
+    value = n * slice_pc / (busy / used) / 1e9
+    return {"value": value, "unit": "Gpixel*ch/s", "cores": used, "kind": "oracle",
+            "sample": f"{n} of {total_slices} (batch, group) slices of {cfg.name}, "
+                      f"{'fwd+bwd' if training else 'fwd'}, fp64 NumPy, one slice per process; "
+                      f"single-process rate {slice_pc / t_probe / 1e9:.4f} Gpixel*ch/s; pool wall {wall:.1f} s"}
+
+
+def load_traffic(workload: str):
+    """Measured HBM bytes per launch of the dominant kernel, from the rocprofv3
+    counter runs summarised in profiles/traffic.json (absent -> None)."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get("fwd_hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--all", action="store_true", help="also time every other workload (table in gpurun_out/)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU; the scan shards over (batch, group) with no "
+              "exchange, and no multi-GPU figure is produced. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2512_07884_amd import workloads as WL
+    cfg = WL.CONFIGS[a.workload]
+    # the CPU legs fork worker processes: run them before this process touches the GPU
+    cpu = None if a.no_cpu else cpu_baseline(cfg, cfg.name in TRAINING)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    r = run_workload(cfg, a.steps, a.warmup)
+    s = summarise(cfg, r)
+    training = r["training"]
+    dom = "bwd" if training else "fwd"          # dominant kernel of the step
+    dom_bytes = s[f"{dom}_algorithmic_bytes"]
+    dom_ms = s[f"{dom}_ms_avg"]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    line = {
+        "metric": "GSPN 4-dir scan Gpixel*ch/s",
+        "value": s["gpixel_ch_per_s"], "unit": "Gpixel*ch/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": s["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "storage_dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} H={cfg.H} W={cfg.W} G={cfg.G} "
+                               f"{cfg.dtype} storage, {cfg.n_dirs} directions, {s['step']}",
+                   "kernel": s[f"{dom}_kernel"], "buffer_sets_rotated": s["buffer_sets_rotated"]},
+        "roofline": {"bound": "hbm", "kernel": f"gspn_scan_{dom}", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(cfg.name),
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
+        "detail": s,
+    }
+    if cpu is not None:
+        line["cpu_baseline"] = cpu
+    if a.all:
+        table = [s]
+        for name, c in WL.CONFIGS.items():
+            if name == cfg.name:
+                continue
+            k = max(20, a.steps // (8 if c.pixel_channels > 1e8 else 1))
+            table.append(summarise(c, run_workload(c, k, a.warmup)))
+            print(f"[bench] {name} done", file=sys.stderr, flush=True)
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
+            json.dump(table, f, indent=1)
+        line["all_workloads"] = [{k: t[k] for k in t if k in (
+            "workload", "step", "ms_per_step", "gpixel_ch_per_s", "fwd_ms_avg", "fwd_algorithmic_GBs",
+            "fwd_frac_of_hbm_peak", "bwd_ms_avg", "bwd_algorithmic_GBs", "bwd_frac_of_hbm_peak", "fwd_kernel",
+            "bwd_kernel")} for t in table]
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,117 @@
+/* gspn.h -- C ABI of libgspn: the GSPN line-scan propagation on AMD MI355X (gfx950).
+ *
+ * The operation (GSPN-2 paper, Sec. 3.2 Eq. 1-2; shared-weight form of Sec. 4.2):
+ *
+ *     h_i = T_i h_{i-1} + lambda_i (.) x_i ,     y_i = u_i (.) h_i
+ *
+ * swept line by line over an [H, W] feature map.  T_i is tridiagonal: position j
+ * of line i reads positions j-1, j, j+1 of line i-1 with the three weights
+ * w[0..2] stored for (i, j); a neighbour outside the line contributes 0
+ * whatever weight is stored for it; the state before the first line is 0 (first
+ * block row of Eq. 3), so the weights stored for the first line of a scan are
+ * never read.  The three weights are shared by the C/G channels of one weight
+ * group (Sec. 4.2 "compact channel propagation"; G == C is the per-channel form
+ * of Eq. 1, G == 1 the single shared matrix).  Up to four scan directions run in
+ * one call (Sec. 3.2: top->bottom, bottom->top, left->right, right->left) and
+ * their outputs are merged by a plain sum.
+ *
+ * Direction ids / mask bits:  0 top->bottom (1), 1 bottom->top (2),
+ * 2 left->right (4), 3 right->left (8).  For directions 0/1 a "line" is an image
+ * row and weight plane k addresses column j+k-1 of the previous row; for
+ * directions 2/3 a line is an image column and plane k addresses row j+k-1 of
+ * the previous column.  Planes are in image coordinates: they are not mirrored
+ * for the reversed directions.
+ *
+ * Layouts (all contiguous, row-major, element type given by `dtype`):
+ *     x, y, gy, gx            [B][C][H][W]
+ *     w, gw                   [4][B][G][3][H][W]      slot d = direction d
+ *     lam, u, h_save, glam, gu [4][B][C][H][W]        slot d = direction d
+ * Channel c belongs to group c / (C/G).  Slots of directions not in `dir_mask`
+ * are neither read nor written.  With GSPN_FLAG_SHARED_PARAMS the inputs w, lam, u
+ * have a single slot that every direction reads (outputs keep four slots).
+ *
+ * Pointers are DEVICE pointers (hipMalloc'ed or equivalent), 16-byte aligned,
+ * owned by the caller; inputs and outputs must not alias.  The library keeps no
+ * pointer after a call returns, allocates nothing and frees nothing.
+ * Arithmetic: inputs are widened to fp32, the carried state and all sums are
+ * fp32, each stored value is rounded once to nearest-even -- except the merged
+ * bf16 y / gx of feature maps too large to stage on chip, which are accumulated
+ * in storage precision direction by direction (at most one extra rounding per
+ * direction).
+ *
+ * Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
+ * default stream) and return without synchronising.  Outputs are overwritten in
+ * full; no pre-zeroing is needed.  Concurrent calls on different streams are
+ * safe as long as their output buffers differ.
+ *
+ * Errors: the return value is a gspn_status.  Argument errors are detected on
+ * the host before anything is launched and leave every output untouched.  A
+ * failed launch returns GSPN_ERR_HIP.  Nothing is printed and nothing aborts.
+ */
+#ifndef GSPN_H
+#define GSPN_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GSPN_OK = 0,
+    GSPN_ERR_NULL = 1,        /* a required pointer is NULL                              */
+    GSPN_ERR_SHAPE = 2,       /* a dimension < 1, C % G != 0, dir_mask == 0 or > 15      */
+    GSPN_ERR_DTYPE = 3,       /* dtype is not GSPN_F32 / GSPN_BF16                        */
+    GSPN_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                        */
+    GSPN_ERR_UNSUPPORTED = 5, /* a line longer than GSPN_MAX_LINE, or unknown flag bits  */
+    GSPN_ERR_HIP = 6          /* the HIP runtime refused the launch                      */
+} gspn_status;
+
+enum { GSPN_F32 = 0, GSPN_BF16 = 1 };
+enum { GSPN_DIR_TB = 1, GSPN_DIR_BT = 2, GSPN_DIR_LR = 4, GSPN_DIR_RL = 8, GSPN_DIR_ALL = 15 };
+enum { GSPN_FLAG_SHARED_PARAMS = 1 };
+enum { GSPN_MAX_LINE = 16384 };  /* largest H or W */
+
+/* Forward scan (Eq. 1, Eq. 2, sum over the directions in dir_mask).
+ *   x      in   [B,C,H,W]
+ *   w      in   [4][B,G,3,H,W] normalised tridiagonal weights
+ *   lam,u  in   [4][B,C,H,W]
+ *   y      out  [B,C,H,W]
+ *   h_save out  [4][B,C,H,W] hidden states per direction for the backward call, or NULL
+ */
+int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
+                  void* y, void* h_save,
+                  int B, int C, int H, int W, int G,
+                  unsigned dir_mask, int dtype, unsigned flags, void* stream);
+
+/* Backward scan: gradients of a scalar loss L given gy = dL/dy.  The paper gives
+ * timings but no algorithm for it (Sec. 5.1); this is the chain rule on Eq. 1-2.
+ * With e_i = dL/dh_i, per direction, swept against the scan order:
+ *     e_i   = u_i*gy_i + T_{i+1}^T e_{i+1}            (0 past the last line)
+ *     gu_i  = gy_i*h_i ,  glam_i = x_i*e_i ,  gx_i += lam_i*e_i  (summed over directions)
+ *     gw_i[k][j] = sum over the group's channels of e_i[j]*h_{i-1}[j+k-1]
+ * gw is the gradient w.r.t. the normalised weights as free variables; it is 0 on
+ * the first line of a scan and for out-of-line neighbours.
+ *   gy, x in  [B,C,H,W];  w, lam, u as in the forward call
+ *   h_save in [4][B,C,H,W] as written by gspn_scan_fwd (required)
+ *   gx out [B,C,H,W];  gw out [4][B,G,3,H,W];  glam, gu out [4][B,C,H,W]
+ */
+int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam, const void* u,
+                  const void* h_save,
+                  void* gx, void* gw, void* glam, void* gu,
+                  int B, int C, int H, int W, int G,
+                  unsigned dir_mask, int dtype, unsigned flags, void* stream);
+
+/* Name of the kernel family the forward / backward call would dispatch to for
+ * these arguments ("generic", ...); static string, never NULL.  Host only. */
+const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);
+const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
+
+/* Static, human-readable text for a gspn_status value. */
+const char* gspn_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int gspn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSPN_H */

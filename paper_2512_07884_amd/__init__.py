@@ -8,8 +8,8 @@ from . import workloads  # noqa: F401
 
 
 def __getattr__(name):
-    if name in ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_status_string", "gspn_version",
-                "load_library", "lib_path", "GspnError"):
+    if name in ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_fwd_plan", "gspn_bwd_plan", "gspn_status_string",
+                "gspn_version", "load_library", "lib_path", "GspnError"):
         from . import binding
         return getattr(binding, name)
     raise AttributeError(name)

@@ -1,0 +1,153 @@
+"""ctypes binding of libgspn.so: argument marshalling only.
+
+Same entry-point names as include/gspn.h.  PyTorch tensors are used purely as
+handles to device memory (``data_ptr()``) and for the current HIP stream; every
+step of the scan runs in the library's kernels.  There is no CPU fallback: a
+missing library raises, and so does any non-zero status from the library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+GSPN_F32, GSPN_BF16 = 0, 1
+GSPN_FLAG_SHARED_PARAMS = 1
+DIR_ALL = 15
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_fwd_plan", "gspn_bwd_plan",
+           "gspn_status_string", "gspn_version")
+
+
+class GspnError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libgspn status {status}: {text}")
+        self.status = status
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG, "libgspn.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libgspn.so (built by ``python -m paper_2512_07884_amd.build``)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    # PyTorch ships its own HIP runtime; load it first so that libgspn binds to the
+    # same runtime instance that owns the tensors and streams it will be handed.
+    import torch  # noqa: F401
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2512_07884_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = ctypes.CDLL(path)
+    vp, ci, cu = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint
+    lib.gspn_scan_fwd.argtypes = [vp] * 6 + [ci] * 5 + [cu, ci, cu, vp]
+    lib.gspn_scan_fwd.restype = ci
+    lib.gspn_scan_bwd.argtypes = [vp] * 10 + [ci] * 5 + [cu, ci, cu, vp]
+    lib.gspn_scan_bwd.restype = ci
+    lib.gspn_fwd_plan.argtypes = [ci] * 5 + [cu, ci, cu, ci]
+    lib.gspn_fwd_plan.restype = ctypes.c_char_p
+    lib.gspn_bwd_plan.argtypes = [ci] * 5 + [cu, ci, cu]
+    lib.gspn_bwd_plan.restype = ctypes.c_char_p
+    lib.gspn_status_string.argtypes = [ci]
+    lib.gspn_status_string.restype = ctypes.c_char_p
+    lib.gspn_version.argtypes = []
+    lib.gspn_version.restype = ci
+    _LIB = lib
+    return lib
+
+
+def gspn_status_string(status: int) -> str:
+    return load_library().gspn_status_string(int(status)).decode()
+
+
+def gspn_version() -> int:
+    return int(load_library().gspn_version())
+
+
+def gspn_fwd_plan(B, C, H, W, G, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0, has_h_save=False) -> str:
+    return load_library().gspn_fwd_plan(B, C, H, W, G, dir_mask, dtype, flags, int(has_h_save)).decode()
+
+
+def gspn_bwd_plan(B, C, H, W, G, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:
+    return load_library().gspn_bwd_plan(B, C, H, W, G, dir_mask, dtype, flags).decode()
+
+
+# ---------------------------------------------------------------- marshalling
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return GSPN_F32
+    if t.dtype == torch.bfloat16:
+        return GSPN_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16")
+
+
+def _ptr(t, name, shape, like):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name}: must be a device tensor")
+    if t.device != like.device or t.dtype != like.dtype:
+        raise ValueError(f"{name}: device/dtype differ from x")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)} != expected {tuple(shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(status: int):
+    if status != 0:
+        raise GspnError(status, gspn_status_string(status))
+
+
+def gspn_scan_fwd(x, w, lam, u, y, h_save=None, *, G: Optional[int] = None, dir_mask: int = DIR_ALL,
+                  flags: int = 0, stream=None) -> None:
+    """y <- sum over directions of u_d * h_d (Eq. 1-2); optionally saves h_d.
+
+    x [B,C,H,W]; w [4,B,G,3,H,W]; lam, u [4,B,C,H,W] ([1,...] with
+    GSPN_FLAG_SHARED_PARAMS); y [B,C,H,W]; h_save [4,B,C,H,W] or None.
+    All device tensors of one dtype (float32 / bfloat16), contiguous.
+    """
+    lib = load_library()
+    B, C, H, W = x.shape
+    if G is None:
+        G = w.shape[2]
+    slots = 1 if (flags & GSPN_FLAG_SHARED_PARAMS) else 4
+    px = _ptr(x, "x", (B, C, H, W), x)
+    pw = _ptr(w, "w", (slots, B, G, 3, H, W), x)
+    pl = _ptr(lam, "lam", (slots, B, C, H, W), x)
+    pu = _ptr(u, "u", (slots, B, C, H, W), x)
+    py = _ptr(y, "y", (B, C, H, W), x)
+    ph = _ptr(h_save, "h_save", (4, B, C, H, W), x)
+    _check(lib.gspn_scan_fwd(px, pw, pl, pu, py, ph, B, C, H, W, G, dir_mask, _dtype_code(x), flags,
+                             _stream(stream)))
+
+
+def gspn_scan_bwd(gy, x, w, lam, u, h_save, gx, gw, glam, gu, *, G: Optional[int] = None,
+                  dir_mask: int = DIR_ALL, flags: int = 0, stream=None) -> None:
+    """Gradients of the forward scan (see include/gspn.h); outputs overwritten."""
+    lib = load_library()
+    B, C, H, W = x.shape
+    if G is None:
+        G = w.shape[2]
+    slots = 1 if (flags & GSPN_FLAG_SHARED_PARAMS) else 4
+    args = [_ptr(gy, "gy", (B, C, H, W), x), _ptr(x, "x", (B, C, H, W), x),
+            _ptr(w, "w", (slots, B, G, 3, H, W), x), _ptr(lam, "lam", (slots, B, C, H, W), x),
+            _ptr(u, "u", (slots, B, C, H, W), x), _ptr(h_save, "h_save", (4, B, C, H, W), x),
+            _ptr(gx, "gx", (B, C, H, W), x), _ptr(gw, "gw", (4, B, G, 3, H, W), x),
+            _ptr(glam, "glam", (4, B, C, H, W), x), _ptr(gu, "gu", (4, B, C, H, W), x)]
+    _check(lib.gspn_scan_bwd(*args, B, C, H, W, G, dir_mask, _dtype_code(x), flags, _stream(stream)))

@@ -1,0 +1,98 @@
+// C ABI of libgspn: argument validation and dispatch.  See include/gspn.h.
+#include "../../include/gspn.h"
+#include "gspn_common.hpp"
+
+using namespace gspn;
+
+namespace {
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_common(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags) {
+    if (B < 1 || C < 1 || H < 1 || W < 1 || G < 1) return GSPN_ERR_SHAPE;
+    if (C % G != 0) return GSPN_ERR_SHAPE;
+    if (dir_mask == 0 || dir_mask > 15u) return GSPN_ERR_SHAPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (flags & ~(unsigned)GSPN_FLAG_SHARED_PARAMS) return GSPN_ERR_UNSUPPORTED;
+    if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
+    // plane offsets inside a (batch, channel) image are 32-bit in the kernels
+    if ((long long)H * W * 3 >= (1ll << 31)) return GSPN_ERR_UNSUPPORTED;
+    return GSPN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
+                  void* y, void* h_save,
+                  int B, int C, int H, int W, int G,
+                  unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    if (!x || !w || !lam || !u || !y) return GSPN_ERR_NULL;
+    int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
+    if (st != GSPN_OK) return st;
+    if (misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y) ||
+        (h_save && misaligned(h_save)))
+        return GSPN_ERR_ALIGN;
+    FwdParams p;
+    p.x = x; p.w = w; p.lam = lam; p.u = u; p.y = y; p.hs = h_save;
+    p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
+    p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    hipError_t e = launch_fwd(p, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam, const void* u,
+                  const void* h_save,
+                  void* gx, void* gw, void* glam, void* gu,
+                  int B, int C, int H, int W, int G,
+                  unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    if (!gy || !x || !w || !lam || !u || !h_save || !gx || !gw || !glam || !gu) return GSPN_ERR_NULL;
+    int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
+    if (st != GSPN_OK) return st;
+    if (misaligned(gy) || misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) ||
+        misaligned(h_save) || misaligned(gx) || misaligned(gw) || misaligned(glam) || misaligned(gu))
+        return GSPN_ERR_ALIGN;
+    BwdParams p;
+    p.gy = gy; p.x = x; p.w = w; p.lam = lam; p.u = u; p.hs = h_save;
+    p.gx = gx; p.gw = gw; p.glam = glam; p.gu = gu;
+    p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
+    p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    hipError_t e = launch_bwd(p, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags,
+                          int has_h_save) {
+    if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK) return "invalid";
+    FwdParams p = {};
+    p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G; p.mask = dir_mask;
+    p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    p.hs = has_h_save ? (void*)16 : nullptr;
+    return fwd_plan_name(p, dtype);
+}
+
+const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags) {
+    if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK) return "invalid";
+    BwdParams p = {};
+    p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G; p.mask = dir_mask;
+    p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    return bwd_plan_name(p, dtype);
+}
+
+const char* gspn_status_string(int status) {
+    switch (status) {
+        case GSPN_OK: return "ok";
+        case GSPN_ERR_NULL: return "a required pointer is NULL";
+        case GSPN_ERR_SHAPE: return "bad shape: dimensions must be >= 1, C divisible by G, dir_mask in 1..15";
+        case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32 or GSPN_BF16";
+        case GSPN_ERR_ALIGN: return "pointers must be 16-byte aligned";
+        case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE or unknown flag";
+        case GSPN_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int gspn_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Shared device helpers and launch parameter blocks for the GSPN scan kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gspn {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+// ---- storage <-> fp32 ------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even; NaN stays NaN (quiet)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float ldf(const float* p) { return *p; }
+__device__ __forceinline__ float ldf(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void stf(float* p, float v) { *p = v; }
+__device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ---- direction geometry ----------------------------------------------------
+// Direction d scans S lines of length L.  Element (scan step t, position j) of a
+// [H][W] plane sits at  line(t)*stride_s + j*stride_j  with line(t) = t or S-1-t.
+struct DirGeom {
+    int S, L, stride_s, stride_j, reversed;
+};
+__host__ __device__ __forceinline__ DirGeom dir_geom(int d, int H, int W) {
+    DirGeom g;
+    if (d < 2) { g.S = H; g.L = W; g.stride_s = W; g.stride_j = 1; }
+    else       { g.S = W; g.L = H; g.stride_s = 1; g.stride_j = W; }
+    g.reversed = d & 1;
+    return g;
+}
+
+struct FwdParams {
+    const void* x; const void* w; const void* lam; const void* u;
+    void* y; void* hs;
+    int B, C, H, W, G, cpg;
+    unsigned mask;
+    int shared;   // 1: w/lam/u have a single direction slot
+};
+
+struct BwdParams {
+    const void* gy; const void* x; const void* w; const void* lam; const void* u; const void* hs;
+    void* gx; void* gw; void* glam; void* gu;
+    int B, C, H, W, G, cpg;
+    unsigned mask;
+    int shared;
+};
+
+// launchers implemented by the kernel files; return hipError_t of the launch
+hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s);
+hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s);
+
+// dispatch (gspn_dispatch.hip): picks the kernel family for the arguments
+hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);
+hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s);
+const char* fwd_plan_name(const FwdParams& p, int dtype);
+const char* bwd_plan_name(const BwdParams& p, int dtype);
+
+}  // namespace gspn

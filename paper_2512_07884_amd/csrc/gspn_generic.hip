@@ -1,0 +1,176 @@
+// Generic GSPN scan kernels: any H, W up to GSPN_MAX_LINE, any group layout.
+//
+// One workgroup owns one (batch, channel) plane in the forward pass -- one
+// (batch, group) in the backward pass -- and walks every requested direction,
+// line by line, inside a single launch (the fused-loop structure of Sec. 4.1).
+// The previous line's state lives in LDS (two ping-pong lines) so a position can
+// read its three neighbours (Sec. 3.2); one barrier per line.  The merged
+// outputs (y, gx) are accumulated in place, direction after direction, by the
+// workgroup that owns the plane, so no atomics and no zero-fill are needed and
+// the summation order is fixed.
+//
+// This is the fallback for shapes the specialised kernels do not take; it makes
+// no attempt at coalescing the horizontal directions.
+#include "gspn_common.hpp"
+
+namespace gspn {
+
+template <typename T>
+__global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
+    extern __shared__ float lds[];
+    const int H = p.H, W = p.W, HW = H * W;
+    const int Lmax = H > W ? H : W;
+    const size_t plane_cnt = (size_t)p.B * p.C;
+    const T* X = (const T*)p.x;
+    const T* WT = (const T*)p.w;
+    const T* LAM = (const T*)p.lam;
+    const T* U = (const T*)p.u;
+    T* Y = (T*)p.y;
+    T* HS = (T*)p.hs;
+
+    for (size_t item = blockIdx.x; item < plane_cnt; item += gridDim.x) {
+        const int b = (int)(item / p.C), c = (int)(item % p.C), g = c / p.cpg;
+        const size_t pc = item * HW;
+        bool first = true;
+        for (int d = 0; d < 4; ++d) {
+            if (!((p.mask >> d) & 1u)) continue;
+            const DirGeom q = dir_geom(d, H, W);
+            const size_t slot_c = p.shared ? 0 : (size_t)d * plane_cnt * HW;
+            const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
+            const T* xp = X + pc;
+            const T* lp = LAM + slot_c + pc;
+            const T* up = U + slot_c + pc;
+            const T* wp = WT + slot_w + ((size_t)b * p.G + g) * 3 * HW;
+            T* yp = Y + pc;
+            T* hp = HS ? HS + (size_t)d * plane_cnt * HW + pc : nullptr;
+            float* prev = lds;
+            float* cur = lds + Lmax;
+            for (int t = 0; t < q.S; ++t) {
+                const int base = (q.reversed ? q.S - 1 - t : t) * q.stride_s;
+                for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
+                    const int off = base + j * q.stride_j;
+                    float h = ldf(lp + off) * ldf(xp + off);
+                    if (t > 0) {   // first line: state before it is zero, its weights are not read
+                        h = fmaf(ldf(wp + HW + off), prev[j], h);
+                        if (j > 0) h = fmaf(ldf(wp + off), prev[j - 1], h);
+                        if (j + 1 < q.L) h = fmaf(ldf(wp + 2 * HW + off), prev[j + 1], h);
+                    }
+                    cur[j] = h;
+                    float yv = ldf(up + off) * h;
+                    if (!first) yv += ldf(yp + off);
+                    stf(yp + off, yv);
+                    if (hp) stf(hp + off, h);
+                }
+                __syncthreads();   // line t complete (LDS) and, after the last line, y visible to the block
+                float* tmp = prev; prev = cur; cur = tmp;
+            }
+            first = false;
+        }
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
+    extern __shared__ float lds[];
+    const int H = p.H, W = p.W, HW = H * W;
+    const int Lmax = H > W ? H : W;
+    const size_t plane_cnt = (size_t)p.B * p.C;
+    const size_t group_cnt = (size_t)p.B * p.G;
+    const T* GY = (const T*)p.gy;
+    const T* X = (const T*)p.x;
+    const T* WT = (const T*)p.w;
+    const T* LAM = (const T*)p.lam;
+    const T* U = (const T*)p.u;
+    const T* HS = (const T*)p.hs;
+    T* GX = (T*)p.gx;
+    T* GW = (T*)p.gw;
+    T* GLAM = (T*)p.glam;
+    T* GU = (T*)p.gu;
+
+    for (size_t item = blockIdx.x; item < group_cnt; item += gridDim.x) {
+        const int b = (int)(item / p.G), g = (int)(item % p.G);
+        for (int ci = 0; ci < p.cpg; ++ci) {
+            const size_t pc = ((size_t)b * p.C + (size_t)g * p.cpg + ci) * HW;
+            bool first = true;
+            for (int d = 0; d < 4; ++d) {
+                if (!((p.mask >> d) & 1u)) continue;
+                const DirGeom q = dir_geom(d, H, W);
+                const size_t out_c = (size_t)d * plane_cnt * HW;
+                const size_t out_w = (size_t)d * group_cnt * 3 * HW;
+                const size_t slot_c = p.shared ? 0 : out_c;
+                const size_t slot_w = p.shared ? 0 : out_w;
+                const T* gyp = GY + pc;
+                const T* xp = X + pc;
+                const T* lp = LAM + slot_c + pc;
+                const T* up = U + slot_c + pc;
+                const T* hp = HS + out_c + pc;
+                const T* wp = WT + slot_w + item * 3 * HW;
+                T* gxp = GX + pc;
+                T* glp = GLAM + out_c + pc;
+                T* gup = GU + out_c + pc;
+                T* gwp = GW + out_w + item * 3 * HW;
+                float* enext = lds;         // e of scan step t+1
+                float* ecur = lds + Lmax;
+                for (int t = q.S - 1; t >= 0; --t) {
+                    const int base = (q.reversed ? q.S - 1 - t : t) * q.stride_s;
+                    const int step = q.reversed ? -q.stride_s : q.stride_s;   // to the next line in scan order
+                    for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
+                        const int off = base + j * q.stride_j;
+                        const float gyv = ldf(gyp + off);
+                        float e = ldf(up + off) * gyv;
+                        if (t + 1 < q.S) {   // transposed tridiagonal of the next line
+                            const int offn = off + step;
+                            e = fmaf(ldf(wp + HW + offn), enext[j], e);
+                            if (j > 0) e = fmaf(ldf(wp + 2 * HW + offn - q.stride_j), enext[j - 1], e);
+                            if (j + 1 < q.L) e = fmaf(ldf(wp + offn + q.stride_j), enext[j + 1], e);
+                        }
+                        ecur[j] = e;
+                        stf(glp + off, ldf(xp + off) * e);
+                        stf(gup + off, gyv * ldf(hp + off));
+                        float gxv = ldf(lp + off) * e;
+                        if (!first) gxv += ldf(gxp + off);
+                        stf(gxp + off, gxv);
+                        const int offp = off - step;   // same position on the previous line
+                        #pragma unroll
+                        for (int k = 0; k < 3; ++k) {
+                            const int jj = j + k - 1;
+                            float v = 0.f;
+                            if (t > 0 && jj >= 0 && jj < q.L) v = e * ldf(hp + offp + (k - 1) * q.stride_j);
+                            if (ci > 0) v += ldf(gwp + k * HW + off);
+                            stf(gwp + k * HW + off, v);
+                        }
+                    }
+                    __syncthreads();
+                    float* tmp = enext; enext = ecur; ecur = tmp;
+                }
+                first = false;
+            }
+        }
+    }
+}
+
+static int pick_block(int L) { return L <= 64 ? 64 : (L <= 128 ? 128 : 256); }
+
+hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s) {
+    const int Lmax = p.H > p.W ? p.H : p.W;
+    const size_t items = (size_t)p.B * p.C;
+    const unsigned grid = (unsigned)(items < 65536 ? items : 65536);
+    const int block = pick_block(Lmax);
+    const size_t shmem = 2 * (size_t)Lmax * sizeof(float);
+    if (dtype == 0) hipLaunchKernelGGL(fwd_generic_kernel<float>, dim3(grid), dim3(block), shmem, s, p);
+    else            hipLaunchKernelGGL(fwd_generic_kernel<bf16_t>, dim3(grid), dim3(block), shmem, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s) {
+    const int Lmax = p.H > p.W ? p.H : p.W;
+    const size_t items = (size_t)p.B * p.G;
+    const unsigned grid = (unsigned)(items < 65536 ? items : 65536);
+    const int block = pick_block(Lmax);
+    const size_t shmem = 2 * (size_t)Lmax * sizeof(float);
+    if (dtype == 0) hipLaunchKernelGGL(bwd_generic_kernel<float>, dim3(grid), dim3(block), shmem, s, p);
+    else            hipLaunchKernelGGL(bwd_generic_kernel<bf16_t>, dim3(grid), dim3(block), shmem, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace gspn

@@ -1,0 +1,84 @@
+"""The C-ABI library loads, exports what include/gspn.h declares, and rejects bad
+arguments on the host (no kernel is launched by anything in this file)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2512_07884_amd import binding
+    if not os.path.exists(binding.lib_path()):
+        from paper_2512_07884_amd import build
+        build.build(verbose=False)
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "gspn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gspn_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"gspn_scan_fwd", "gspn_scan_bwd", "gspn_status_string", "gspn_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2512_07884_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_status_strings(lib):
+    assert lib.gspn_version() >= 100
+    seen = set()
+    for s in range(0, 7):
+        t = lib.gspn_status_string(s).decode()
+        assert t and t != "unknown status"
+        seen.add(t)
+    assert len(seen) == 7
+    assert lib.gspn_status_string(99).decode() == "unknown status"
+
+
+def test_argument_errors_are_detected_before_any_launch(lib):
+    p = ctypes.c_void_p(0x1000)          # aligned, never dereferenced: every call below fails validation
+    bad = ctypes.c_void_p(0x1004)
+    f = lambda *a, **k: lib.gspn_scan_fwd(*a)
+    ok_dims = (1, 4, 8, 8, 2)
+    assert lib.gspn_scan_fwd(None, p, p, p, p, None, *ok_dims, 15, 0, 0, None) == 1
+    assert lib.gspn_scan_fwd(p, p, p, p, None, None, *ok_dims, 15, 0, 0, None) == 1
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, 1, 4, 0, 8, 2, 15, 0, 0, None) == 2
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, 1, 4, 8, 8, 3, 15, 0, 0, None) == 2      # C % G
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 0, 0, 0, None) == 2
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 16, 0, 0, None) == 2
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 15, 2, 0, None) == 3
+    assert lib.gspn_scan_fwd(p, bad, p, p, p, None, *ok_dims, 15, 0, 0, None) == 4
+    assert lib.gspn_scan_fwd(p, p, p, p, p, bad, *ok_dims, 15, 0, 0, None) == 4
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 15, 0, 8, None) == 5           # unknown flag
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, 1, 4, 8, 20000, 2, 15, 0, 0, None) == 5  # line too long
+    assert lib.gspn_scan_bwd(p, p, p, p, p, None, p, p, p, p, *ok_dims, 15, 0, 0, None) == 1  # h_save required
+    assert lib.gspn_scan_bwd(p, p, p, p, p, p, p, bad, p, p, *ok_dims, 15, 0, 0, None) == 4
+    assert lib.gspn_scan_bwd(p, p, p, p, p, p, p, p, p, p, 1, 5, 8, 8, 2, 15, 0, 0, None) == 2
+
+
+def test_plan_names(lib):
+    assert lib.gspn_fwd_plan(1, 8, 16, 16, 1, 1, 0, 0, 0).decode() != "invalid"
+    assert lib.gspn_fwd_plan(1, 8, 16, 16, 3, 1, 0, 0, 0).decode() == "invalid"
+    assert lib.gspn_bwd_plan(32, 192, 28, 28, 4, 15, 0, 0).decode() != "invalid"
+
+
+def test_binding_refuses_cpu_tensors_and_missing_library(monkeypatch):
+    import torch
+    from paper_2512_07884_amd import binding
+    x = torch.zeros(1, 2, 4, 4)
+    with pytest.raises(ValueError):
+        binding.gspn_scan_fwd(x, torch.zeros(4, 1, 1, 3, 4, 4), torch.zeros(4, 1, 2, 4, 4),
+                              torch.zeros(4, 1, 2, 4, 4), torch.zeros(1, 2, 4, 4))
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "lib_path", lambda: "/nonexistent/libgspn.so")
+    with pytest.raises(ImportError):
+        binding.load_library()

@@ -1,0 +1,100 @@
+"""GPU parity of gspn_scan_bwd against the fp64 oracle, through the C ABI.
+
+The forward call writes h_save, the backward call consumes it; every gradient
+tensor is compared separately with the tolerance of its storage dtype.
+"""
+import numpy as np
+import pytest
+
+from gpu_util import TOL, rel_inf_err, to_device, to_host_f64, empty_like_dev
+from oracle import gspn_oracle as O
+from paper_2512_07884_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+
+def run_bwd_gpu(inp, cfg, mask, flags=0):
+    import torch
+    import paper_2512_07884_amd as G
+    dev = {k: to_device(v, cfg.dtype) for k, v in inp.items()}
+    B, C, H, W = inp["x"].shape
+    nan = float("nan")
+    y = empty_like_dev((B, C, H, W), cfg.dtype, nan)
+    hs = empty_like_dev((4, B, C, H, W), cfg.dtype, nan)
+    G.gspn_scan_fwd(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, G=cfg.G, dir_mask=mask, flags=flags)
+    gx = empty_like_dev((B, C, H, W), cfg.dtype, nan)
+    gw = empty_like_dev((4, B, cfg.G, 3, H, W), cfg.dtype, nan)
+    glam = empty_like_dev((4, B, C, H, W), cfg.dtype, nan)
+    gu = empty_like_dev((4, B, C, H, W), cfg.dtype, nan)
+    G.gspn_scan_bwd(dev["gy"], dev["x"], dev["w"], dev["lam"], dev["u"], hs, gx, gw, glam, gu,
+                    G=cfg.G, dir_mask=mask, flags=flags)
+    torch.cuda.synchronize()
+    return {"h": to_host_f64(hs), "gx": to_host_f64(gx), "gw": to_host_f64(gw),
+            "glam": to_host_f64(glam), "gu": to_host_f64(gu)}
+
+
+def check_bwd(cfg, mask=None):
+    mask = cfg.dir_mask if mask is None else mask
+    inp = WL.make_inputs(cfg, with_gy=True)
+    f = WL.inputs_as_f64(inp, cfg.dtype)
+    out = run_bwd_gpu(inp, cfg, mask)
+    # the oracle's backward consumes the oracle's own hidden states, rounded to storage like h_save is
+    _, h_ref = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], mask)
+    h_used = WL.storage_to_f64(WL.to_storage(h_ref, cfg.dtype), cfg.dtype)
+    gx, gw, glam, gu = O.scan_bwd(f["gy"], f["x"], f["w"], f["lam"], f["u"], h_used, mask)
+    tol = TOL[cfg.dtype]
+    assert rel_inf_err(out["gx"], gx) <= tol, (cfg, "gx", rel_inf_err(out["gx"], gx))
+    for d in range(4):
+        for name, got, ref in (("gw", out["gw"], gw), ("glam", out["glam"], glam), ("gu", out["gu"], gu)):
+            if (mask >> d) & 1:
+                e = rel_inf_err(got[d], ref[d])
+                assert e <= tol, (cfg, name, d, e)
+            else:
+                assert np.all(np.isnan(got[d])), (name, d, "slot of an unmasked direction was written")
+    # exact zeros where a weight is never used
+    for d in range(4):
+        if not (mask >> d) & 1:
+            continue
+        g = out["gw"][d]
+        first = {0: g[:, :, :, 0, :], 1: g[:, :, :, -1, :], 2: g[:, :, :, :, 0], 3: g[:, :, :, :, -1]}[d]
+        assert not first.any()
+        if d < 2:
+            assert not g[:, :, 0, :, 0].any() and not g[:, :, 2, :, -1].any()
+        else:
+            assert not g[:, :, 0, 0, :].any() and not g[:, :, 2, -1, :].any()
+
+
+BWD_SHAPES = [(2, 6, 9, 13, 3), (1, 4, 33, 70, 2), (1, 8, 65, 31, 8), (1, 2, 1, 37, 1), (1, 2, 37, 1, 2),
+              (1, 1, 1, 1, 1), (1, 4, 130, 20, 1), (2, 8, 28, 28, 8), (2, 96, 28, 28, 2)]
+
+
+@pytest.mark.parametrize("shape", BWD_SHAPES)
+def test_backward_fp32_shapes(shape):
+    B, C, H, W, G = shape
+    check_bwd(WL.ScanConfig("bwd", B, C, H, W, G, "f32", 15, 1.0, 13))
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9])
+def test_backward_direction_masks(mask):
+    check_bwd(WL.ScanConfig("bwdmask", 2, 4, 14, 18, 2, "f32", mask, 1.0, 17))
+
+
+def test_backward_bf16_per_channel_weights():
+    # bf16 storage with one channel per group: every gradient is rounded once
+    check_bwd(WL.ScanConfig("bwdbf16", 2, 6, 24, 20, 6, "bf16", 15, 1.0, 19))
+
+
+def test_backward_adjoint_identity_on_the_gpu():
+    # <gy, scan(v)> == <gx, v> for the linear map x -> y, evaluated entirely on the GPU path
+    import torch
+    import paper_2512_07884_amd as G
+    cfg = WL.ScanConfig("adj", 2, 8, 28, 28, 2, "f32", 15, 1.0, 23)
+    inp = WL.make_inputs(cfg)
+    out = run_bwd_gpu(inp, cfg, 15)
+    v = np.random.default_rng(1).standard_normal(inp["x"].shape).astype(np.float32)
+    dev = {k: to_device(a, "f32") for k, a in inp.items()}
+    yv = torch.empty_like(dev["x"])
+    G.gspn_scan_fwd(to_device(v, "f32"), dev["w"], dev["lam"], dev["u"], yv, None, G=cfg.G)
+    lhs = float((to_host_f64(yv) * inp["gy"].astype(np.float64)).sum())
+    rhs = float((out["gx"] * v.astype(np.float64)).sum())
+    assert abs(lhs - rhs) <= 1e-4 * max(1.0, abs(lhs))

@@ -1,0 +1,146 @@
+"""GPU parity of gspn_scan_fwd against the fp64 oracle, through the C ABI.
+
+Tolerances (max|gpu - oracle| / max|oracle| per tensor): 1e-5 for fp32 storage,
+1e-2 for bf16 storage.  Both sides consume the same storage-rounded inputs.
+"""
+import numpy as np
+import pytest
+
+from gpu_util import TOL, rel_inf_err, run_fwd_gpu, to_device, to_host_f64, empty_like_dev
+from oracle import gspn_oracle as O
+from paper_2512_07884_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+
+def check_case(cfg, dir_mask=None, save_h=True, slots_nan=True):
+    mask = cfg.dir_mask if dir_mask is None else dir_mask
+    inp = WL.make_inputs(cfg, with_gy=False)
+    f = WL.inputs_as_f64(inp, cfg.dtype)
+    y_ref, h_ref = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], mask)
+    if slots_nan:   # slots of unmasked directions must never be read
+        nanv = np.float32(np.nan) if cfg.dtype == "f32" else np.uint16(0x7FC0)
+        for d in range(4):
+            if not (mask >> d) & 1:
+                for k in ("w", "lam", "u"):
+                    inp[k][d] = nanv
+    y, h, *_ = run_fwd_gpu(inp, cfg, mask, save_h=save_h)
+    tol = TOL[cfg.dtype]
+    assert np.all(np.isfinite(y)), cfg
+    err = rel_inf_err(y, y_ref)
+    assert err <= tol, (cfg, mask, "y", err)
+    if save_h:
+        for d in range(4):
+            if (mask >> d) & 1:
+                e = rel_inf_err(h[d], h_ref[d])
+                assert e <= tol, (cfg, mask, "h", d, e)
+            else:
+                assert np.all(np.isnan(h[d])), "slot of an unmasked direction was written"
+    return err
+
+
+def test_unit16_single_direction_fp32():
+    check_case(WL.CONFIGS["unit16"])
+
+
+SHAPES = [  # B, C, H, W, G
+    (2, 6, 9, 13, 3), (1, 4, 33, 70, 2), (1, 8, 65, 31, 8), (2, 4, 130, 67, 1),
+    (1, 2, 1, 37, 1), (1, 2, 37, 1, 2), (1, 1, 1, 1, 1), (1, 3, 300, 5, 3), (1, 2, 5, 300, 1),
+    (3, 5, 2, 2, 5), (1, 2, 64, 64, 1), (1, 2, 63, 65, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_ragged_shapes_all_directions(shape, dtype):
+    B, C, H, W, G = shape
+    check_case(WL.ScanConfig("ragged", B, C, H, W, G, dtype, 15, 1.0, 7))
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 5, 10, 7, 14])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_direction_masks(mask, dtype):
+    check_case(WL.ScanConfig("mask", 2, 4, 20, 24, 2, dtype, mask, 1.0, 11))
+
+
+SHRUNK = [
+    WL.shrink(WL.CONFIGS["cls56"], B=2, C=24, G=2),               # 56x56, 12 channels per group
+    WL.shrink(WL.CONFIGS["cls56"], B=2, C=24, G=2, dtype="f32"),
+    WL.shrink(WL.CONFIGS["diff128"], B=1, C=128, G=2),            # 128x128, cpg 64, peaked weights
+    WL.shrink(WL.CONFIGS["long512"], C=4, G=2),
+    WL.shrink(WL.CONFIGS["long256x1024"], C=4, G=2),
+    WL.shrink(WL.CONFIGS["long256x1024"], C=2, G=1, H=1024, W=256),
+    WL.shrink(WL.CONFIGS["train28_gc"], B=2, C=16, G=16),
+    WL.shrink(WL.CONFIGS["train28_g4"], B=2, C=96, G=2),
+    WL.shrink(WL.CONFIGS["train28_g4"], B=2, C=96, G=2, dtype="bf16"),
+]
+
+
+@pytest.mark.parametrize("cfg", SHRUNK, ids=lambda c: f"{c.name}-{c.B}x{c.C}x{c.H}x{c.W}-G{c.G}-{c.dtype}")
+def test_benchmark_shapes_with_fewer_channels(cfg):
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+
+
+def test_weights_that_are_never_read_may_hold_anything():
+    cfg = WL.ScanConfig("poison", 1, 4, 12, 10, 2, "f32", 15, 1.0, 3)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    f = WL.inputs_as_f64(inp, cfg.dtype)
+    y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
+    w = inp["w"]
+    w[0, :, :, :, 0, :] = np.nan; w[1, :, :, :, -1, :] = np.inf       # first line of each scan
+    w[2, :, :, :, :, 0] = np.nan; w[3, :, :, :, :, -1] = -np.inf
+    w[0, :, :, 0, :, 0] = np.nan; w[0, :, :, 2, :, -1] = np.inf       # out-of-line neighbours
+    w[1, :, :, 0, :, 0] = np.inf; w[1, :, :, 2, :, -1] = np.nan
+    w[2, :, :, 0, 0, :] = np.nan; w[2, :, :, 2, -1, :] = np.nan
+    w[3, :, :, 0, 0, :] = np.inf; w[3, :, :, 2, -1, :] = np.nan
+    y, *_ = run_fwd_gpu(inp, cfg, 15)
+    assert np.all(np.isfinite(y)) and rel_inf_err(y, y_ref) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_shared_parameter_flag(dtype):
+    cfg = WL.ScanConfig("shared", 2, 6, 17, 17, 3, dtype, 15, 1.0, 5)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    # one parameter set for all directions: plain (not border-renormalised) weights are fine for parity
+    one = {"x": inp["x"], "w": inp["w"][:1].copy(), "lam": inp["lam"][:1].copy(), "u": inp["u"][:1].copy()}
+    rep = {"x": inp["x"], "w": np.repeat(one["w"], 4, 0), "lam": np.repeat(one["lam"], 4, 0),
+           "u": np.repeat(one["u"], 4, 0)}
+    f = WL.inputs_as_f64(rep, dtype)
+    y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
+    y, *_ = run_fwd_gpu(one, cfg, 15, flags=1)
+    assert rel_inf_err(y, y_ref) <= TOL[dtype]
+
+
+def test_runs_on_a_side_stream_and_is_bitwise_repeatable():
+    import torch
+    import paper_2512_07884_amd as G
+    cfg = WL.ScanConfig("stream", 2, 8, 40, 36, 2, "bf16", 15, 1.0, 9)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    dev = {k: to_device(v, cfg.dtype) for k, v in inp.items()}
+    outs = []
+    s = torch.cuda.Stream()
+    for rep in range(3):
+        y = empty_like_dev(inp["x"].shape, cfg.dtype, float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s):
+            G.gspn_scan_fwd(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, G=cfg.G, stream=s)
+        s.synchronize()
+        outs.append(y.view(torch.int16).cpu().numpy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    f = WL.inputs_as_f64(inp, cfg.dtype)
+    y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
+    assert rel_inf_err(to_host_f64(y), y_ref) <= TOL["bf16"]
+
+
+def test_library_reports_shape_errors_through_the_binding():
+    import torch
+    import paper_2512_07884_amd as G
+    x = torch.zeros(1, 4, 8, 8, device="cuda")
+    w = torch.zeros(4, 1, 3, 3, 8, 8, device="cuda")      # G = 3 does not divide C = 4
+    lam = torch.zeros(4, 1, 4, 8, 8, device="cuda")
+    y = torch.full((1, 4, 8, 8), 7.0, device="cuda")
+    with pytest.raises(G.GspnError) as ei:
+        G.gspn_scan_fwd(x, w, lam, lam, y, None)
+    assert ei.value.status == 2
+    assert torch.all(y == 7.0)                               # outputs untouched on argument errors

@@ -1,16 +1,22 @@
 // Chooses the kernel family for a call.  Host code only.
 #include "gspn_common.hpp"
+#include <stdlib.h>
 
 namespace gspn {
 
-enum FwdPlan { FWD_GENERIC = 0 };
+enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1 };
 enum BwdPlan { BWD_GENERIC = 0 };
 
-static FwdPlan choose_fwd(const FwdParams&, int) { return FWD_GENERIC; }
+static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
+    const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
+    if (f && f[0] == '1') return FWD_GENERIC;
+    return fwd_tile_applicable(p, dtype) ? FWD_TILE : FWD_GENERIC;
+}
 static BwdPlan choose_bwd(const BwdParams&, int) { return BWD_GENERIC; }
 
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {
     switch (choose_fwd(p, dtype)) {
+        case FWD_TILE: return launch_fwd_tile(p, dtype, s);
         default: return launch_fwd_generic(p, dtype, s);
     }
 }
@@ -23,6 +29,7 @@ hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s) {
 
 const char* fwd_plan_name(const FwdParams& p, int dtype) {
     switch (choose_fwd(p, dtype)) {
+        case FWD_TILE: return "tile";
         default: return "generic";
     }
 }

@@ -1,0 +1,502 @@
+// Forward GSPN scan for feature maps whose fp32 output tile fits in LDS (gfx950: 160 KB per CU).
+//
+// One workgroup owns K consecutive channels of one batch image and runs all requested
+// directions over them inside one launch (Sec. 4.1 "single kernel": the loop over lines
+// is inside the kernel; here the loop over the four directions of Sec. 3.2 is too).
+//
+//  * A wave owns whole lines: each lane keeps V adjacent positions of the current line's
+//    hidden state in registers (several channels side by side when a line is shorter than
+//    the wave), so the three-neighbour read of Eq. 1 is two cross-lane DPP shifts per line
+//    plus in-lane register moves.  No LDS, no barrier on the recurrence itself.
+//  * Vertical directions: a line is an image row, the lane's V positions are contiguous in
+//    memory, one vector load per tensor per line, PF lines prefetched ahead in registers.
+//  * Horizontal directions: a line is an image column; the lane's V positions are V image
+//    rows, and each lane reads its rows in bursts of CS scan steps (16..32 B), double
+//    buffered in registers.
+//  * The merged output y = sum_d u_d*h_d (Eq. 2 + sum merge) is accumulated in an fp32 LDS
+//    tile by LDS float atomics and written once, coalesced, rounded once to the storage
+//    type.  x is the only tensor read more than once (once per direction).
+//  * Accumulation order per output element is fixed (vertical pair first -- its two
+//    contributions commute --, then the horizontal pair split at mid-scan by a barrier so
+//    that the two waves never touch the same element in the same half), so results are
+//    bitwise reproducible.
+#include "gspn_common.hpp"
+#include <stdlib.h>
+
+namespace gspn {
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- buffer addressing: a tensor is reached through a buffer resource (uniform base in SGPRs),
+// a uniform byte offset (SGPR) and a per-lane byte offset (VGPR), so that stepping from line to
+// line costs scalar adds only.  Offsets stay below 2^31 (checked on the host).
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+template <int NB> __device__ __forceinline__ void ld_buf(rsrc_t rs, uint32_t voff, int soff, uint32_t* r) {
+    soff = __builtin_amdgcn_readfirstlane(soff);   // wave-uniform by construction: keep it in an SGPR
+    if constexpr (NB == 4) { r[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, 0); }
+    else if constexpr (NB == 8) { u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, 0); r[0] = v.x; r[1] = v.y; }
+    else {
+        static_assert(NB % 16 == 0, "vector width");
+#pragma unroll
+        for (int i = 0; i < NB / 16; ++i) {
+            u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * i, soff, 0);
+            r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+        }
+    }
+}
+template <int NB> __device__ __forceinline__ void st_buf(rsrc_t rs, uint32_t voff, int soff, const uint32_t* r) {
+    soff = __builtin_amdgcn_readfirstlane(soff);
+    if constexpr (NB == 4) { __builtin_amdgcn_raw_buffer_store_b32(r[0], rs, voff, soff, 0); }
+    else if constexpr (NB == 8) { u32x2 v = {r[0], r[1]}; __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, soff, 0); }
+    else {
+#pragma unroll
+        for (int i = 0; i < NB / 16; ++i) {
+            u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff + 16 * i, soff, 0);
+        }
+    }
+}
+template <int NB> __device__ __forceinline__ void st_raw(char* p, const uint32_t* r) {
+    if constexpr (NB == 4) { *(uint32_t*)p = r[0]; }
+    else { u32x2 v = {r[0], r[1]}; *(u32x2*)p = v; }
+}
+
+// element e of a packed register vector, widened to fp32 (e is a compile-time constant after unrolling)
+template <typename T> __device__ __forceinline__ float elem(const uint32_t* r, int e) {
+    if constexpr (sizeof(T) == 4) return __uint_as_float(r[e]);
+    else return (e & 1) ? __uint_as_float(r[e >> 1] & 0xffff0000u) : __uint_as_float(r[e >> 1] << 16);
+}
+// pack V fp32 values into storage registers (round to nearest even for bf16)
+template <typename T, int V> __device__ __forceinline__ void pack(const float* v, uint32_t* r) {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) r[i] = __float_as_uint(v[i]);
+    } else {
+        static_assert(V % 2 == 0, "bf16 vectors hold an even number of elements");
+#pragma unroll
+        for (int i = 0; i < V / 2; ++i)
+            r[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    }
+}
+
+// whole-wave shift by one lane; lanes without a source read 0
+__device__ __forceinline__ float from_lane_below(float v) {   // lane i <- lane i-1
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x138, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float from_lane_above(float v) {   // lane i <- lane i+1
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
+}
+
+// One line of Eq. 1 for the lane's V positions.  `first`/`last`: the lane holds the first/last
+// positions of its line, whose outer neighbour does not exist: both the neighbour value and its
+// weight are forced to 0 so that nothing stored for it (NaN, Inf) can leak in.
+template <int V>
+__device__ __forceinline__ void line_update(float (&h)[V], const float (&a)[V], const float (&w0)[V],
+                                            const float (&w1)[V], const float (&w2)[V], bool first, bool last) {
+    float lin = from_lane_below(h[V - 1]);
+    float rin = from_lane_above(h[0]);
+    lin = first ? 0.f : lin;
+    rin = last ? 0.f : rin;
+    const float wl = first ? 0.f : w0[0];
+    const float wr = last ? 0.f : w2[V - 1];
+    float hn[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float l = v == 0 ? lin : h[v - 1];
+        const float r = v == V - 1 ? rin : h[v + 1];
+        const float c0 = v == 0 ? wl : w0[v];
+        const float c2 = v == V - 1 ? wr : w2[v];
+        hn[v] = fmaf(c0, l, fmaf(w1[v], h[v], fmaf(c2, r, a[v])));
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) h[v] = hn[v];
+}
+
+struct TileArgs {
+    FwdParams p;
+    int K;        // channels per workgroup (divides C)
+    int pitch;    // LDS tile row pitch in floats (odd)
+    int lplv, pv; // vertical phases: lanes per line, channels side by side in a wave
+    int lplh, ph; // horizontal phases
+    int nwaves;
+};
+
+// ---------------------------------------------------------------------------
+// vertical direction (d = 0 top->bottom, 1 bottom->top): lines are image rows
+// ---------------------------------------------------------------------------
+template <typename T, int V, int PF, bool SAVE>
+__device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int d, int b, int c_first, int pk,
+                                              int lane) {
+    constexpr int NB = V * (int)sizeof(T);
+    constexpr int NR = NB / 4;
+    const FwdParams& p = a.p;
+    const int H = p.H, W = p.W, HW = H * W;
+    const int pl = lane / a.lplv, i = lane - pl * a.lplv;
+    const int c_pack = c_first + pk * a.pv;                    // first channel of this wave's pack
+    const int n_here = min(a.pv, a.K - pk * a.pv);
+    const bool active = pl < n_here;
+    const int plc = active ? pl : 0, ic = active ? i : 0;
+    const int c = c_pack + plc;
+    const int g = c / p.cpg, g0 = c_pack / p.cpg;
+    const bool first = ic == 0, last = ic == a.lplv - 1;
+    const size_t planes = (size_t)p.B * p.C;
+    const size_t slot_c = p.shared ? 0 : (size_t)d * planes * HW;
+    const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
+    const size_t plane0 = ((size_t)b * p.C + c_pack) * HW;      // uniform
+    const uint32_t voff = (uint32_t)((plc * HW + ic * V) * (int)sizeof(T));
+    const uint32_t voff_w = (uint32_t)(((g - g0) * 3 * HW + ic * V) * (int)sizeof(T));
+    const rsrc_t xb = make_rsrc((const char*)p.x + plane0 * sizeof(T));
+    const rsrc_t lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * sizeof(T));
+    const rsrc_t ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
+    const rsrc_t wb = make_rsrc((const char*)p.w + (slot_w + ((size_t)b * p.G + g0) * 3 * HW) * sizeof(T));
+    const rsrc_t hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * sizeof(T) : (char*)p.y);
+    const int rev = d & 1;
+    const int row_bytes = W * (int)sizeof(T);
+    const int plane_bytes = HW * (int)sizeof(T);
+    float* trow = tile + ((pk * a.pv + plc) * H) * a.pitch + ic * V;
+
+    if (!active) return;   // the whole pass runs with unused lanes masked off (their DPP reads see 0)
+
+    struct Line { uint32_t x[NR], l[NR], u[NR], w0[NR], w1[NR], w2[NR]; };
+    Line slot[PF];
+    auto issue = [&](Line& s, int t) {
+        const int row = rev ? H - 1 - t : t;
+        const int ro = row * row_bytes;
+        ld_buf<NB>(xb, voff, ro, s.x);
+        ld_buf<NB>(lb, voff, ro, s.l);
+        ld_buf<NB>(ub, voff, ro, s.u);
+        ld_buf<NB>(wb, voff_w, ro, s.w0);
+        ld_buf<NB>(wb, voff_w, plane_bytes + ro, s.w1);
+        ld_buf<NB>(wb, voff_w, 2 * plane_bytes + ro, s.w2);
+    };
+    // unconditional (clamped) so that every path into the loop has the same loads in flight
+#pragma unroll
+    for (int k = 0; k < PF; ++k) issue(slot[k], min(k, H - 1));
+
+    float h[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) h[v] = 0.f;
+
+    // `maybe_first`: this step can be scan step 0, whose weights are never used (the stored values
+    // may be anything): they are replaced by 0 so the (zero) initial state contributes exactly 0
+    auto step = [&](const Line& cur, int t, bool maybe_first) {
+        float av[V], w0[V], w1[V], w2[V], uv[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
+            w0[v] = elem<T>(cur.w0, v); w1[v] = elem<T>(cur.w1, v); w2[v] = elem<T>(cur.w2, v);
+            uv[v] = elem<T>(cur.u, v);
+            if (maybe_first) {
+                w0[v] = t == 0 ? 0.f : w0[v]; w1[v] = t == 0 ? 0.f : w1[v]; w2[v] = t == 0 ? 0.f : w2[v];
+            }
+        }
+        line_update<V>(h, av, w0, w1, w2, first, last);
+        const int row = rev ? H - 1 - t : t;
+        float* tp = trow + row * a.pitch;
+#pragma unroll
+        for (int v = 0; v < V; ++v) atomicAdd(tp + v, uv[v] * h[v]);
+        if constexpr (SAVE) {
+            uint32_t hr[NR];
+            pack<T, V>(h, hr);
+            st_buf<NB>(hb, voff, row * row_bytes, hr);
+        }
+    };
+
+    // Full blocks of PF lines: straight-line code, slot k is consumed and at once refilled with
+    // the line PF steps ahead (clamped to the last line: redundant but in bounds near the end),
+    // so the register ring is static and the hardware load counter can be waited on by count.
+    int t0 = 0;
+    for (; t0 + PF <= H; t0 += PF) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) {
+            const int t = t0 + k;
+            step(slot[k], t, k == 0);
+            issue(slot[k], min(t + PF, H - 1));
+            __builtin_amdgcn_sched_barrier(0);   // keep the consume/refill interleaving as written
+        }
+    }
+    // tail (fewer than PF lines left): their loads are already in the ring
+#pragma unroll
+    for (int k = 0; k < PF; ++k)
+        if (t0 + k < H) step(slot[k], t0 + k, k == 0);
+}
+
+// ---------------------------------------------------------------------------
+// horizontal direction (d = 2 left->right, 3 right->left): lines are image columns;
+// the lane's V positions are V consecutive image rows.  Scan steps [c_begin*CS, c_end*CS).
+// ---------------------------------------------------------------------------
+template <typename T, int V, int CS>
+struct HBuf { uint32_t x[V][CS * sizeof(T) / 4], l[V][CS * sizeof(T) / 4], u[V][CS * sizeof(T) / 4],
+              w0[V][CS * sizeof(T) / 4], w1[V][CS * sizeof(T) / 4], w2[V][CS * sizeof(T) / 4]; };
+
+template <typename T, int V, int CS, bool REV, bool SAVE>
+struct HorizontalPass {
+    static constexpr int NB = CS * (int)sizeof(T);
+    static constexpr int NR = NB / 4;
+    rsrc_t xb, lb, ub, wb, hb;
+    uint32_t voff, voff_w;
+    int row_bytes, plane_bytes, nchunks, W;
+    float* trow;
+    int pitch;
+    bool active, first, last;
+    float h[V];
+    HBuf<T, V, CS> buf0, buf1;
+
+    __device__ __forceinline__ void init(const TileArgs& a, float* tile, int d, int b, int c_first, int pk, int lane) {
+        const FwdParams& p = a.p;
+        const int H = p.H, HW = H * p.W;
+        W = p.W;
+        const int pl = lane / a.lplh, i = lane - pl * a.lplh;
+        const int c_pack = c_first + pk * a.ph;
+        const int n_here = min(a.ph, a.K - pk * a.ph);
+        active = pl < n_here;
+        const int plc = active ? pl : 0, ic = active ? i : 0;
+        const int c = c_pack + plc;
+        const int g = c / p.cpg, g0 = c_pack / p.cpg;
+        first = ic == 0; last = ic == a.lplh - 1;
+        const size_t planes = (size_t)p.B * p.C;
+        const size_t slot_c = p.shared ? 0 : (size_t)d * planes * HW;
+        const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
+        const size_t plane0 = ((size_t)b * p.C + c_pack) * HW;
+        voff = (uint32_t)((plc * HW + ic * V * W) * (int)sizeof(T));
+        voff_w = (uint32_t)(((g - g0) * 3 * HW + ic * V * W) * (int)sizeof(T));
+        xb = make_rsrc((const char*)p.x + plane0 * sizeof(T));
+        lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * sizeof(T));
+        ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
+        wb = make_rsrc((const char*)p.w + (slot_w + ((size_t)b * p.G + g0) * 3 * HW) * sizeof(T));
+        hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * sizeof(T) : (char*)p.y);
+        row_bytes = W * (int)sizeof(T);
+        plane_bytes = HW * (int)sizeof(T);
+        nchunks = W / CS;
+        pitch = a.pitch;
+        trow = tile + ((pk * a.ph + plc) * H + ic * V) * a.pitch;
+#pragma unroll
+        for (int v = 0; v < V; ++v) h[v] = 0.f;
+    }
+
+    // byte offset of chunk c (in scan order) inside a row
+    __device__ __forceinline__ int chunk_col(int c) const { return (REV ? nchunks - 1 - c : c) * CS; }
+
+    __device__ __forceinline__ void issue(HBuf<T, V, CS>& s, int c) {
+        const int co = chunk_col(c) * (int)sizeof(T);
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int o = co + v * row_bytes;
+            ld_buf<NB>(xb, voff, o, s.x[v]);
+            ld_buf<NB>(lb, voff, o, s.l[v]);
+            ld_buf<NB>(ub, voff, o, s.u[v]);
+            ld_buf<NB>(wb, voff_w, o, s.w0[v]);
+            ld_buf<NB>(wb, voff_w, plane_bytes + o, s.w1[v]);
+            ld_buf<NB>(wb, voff_w, 2 * plane_bytes + o, s.w2[v]);
+        }
+    }
+
+    __device__ __forceinline__ void compute(const HBuf<T, V, CS>& s, int c) {
+        const int col0 = chunk_col(c);
+        float hs[V][CS];
+#pragma unroll
+        for (int k = 0; k < CS; ++k) {
+            const int e = REV ? CS - 1 - k : k;       // element inside the chunk, compile-time
+            float av[V], w0[V], w1[V], w2[V];
+            const bool start = (c == 0) && (k == 0);  // first line of the scan: its weights are never read
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                av[v] = elem<T>(s.l[v], e) * elem<T>(s.x[v], e);
+                w0[v] = elem<T>(s.w0[v], e); w1[v] = elem<T>(s.w1[v], e); w2[v] = elem<T>(s.w2[v], e);
+                if (k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
+            }
+            line_update<V>(h, av, w0, w1, w2, first, last);
+#pragma unroll
+            for (int v = 0; v < V; ++v) atomicAdd(trow + v * pitch + col0 + e, elem<T>(s.u[v], e) * h[v]);
+            if constexpr (SAVE) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) hs[v][e] = h[v];
+            }
+        }
+        if constexpr (SAVE) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                uint32_t r[NR];
+                pack<T, CS>(hs[v], r);
+                st_buf<NB>(hb, voff, col0 * (int)sizeof(T) + v * row_bytes, r);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void prologue() { if (active) issue(buf0, 0); }
+
+    // chunks [c_begin, c_end); buffer (c & 1) already holds / is loading chunk c_begin.
+    // Unused lanes are masked off for the whole loop (their DPP reads see 0).
+    __device__ __forceinline__ void run(int c_begin, int c_end) {
+        if (!active) return;
+        for (int c = c_begin; c < c_end; ++c) {
+            const int cn = c + 1 < nchunks ? c + 1 : c;      // clamped: redundant but in bounds at the end
+            if ((c & 1) == 0) {
+                issue(buf1, cn);
+                compute(buf0, c);
+            } else {
+                issue(buf0, cn);
+                compute(buf1, c);
+            }
+        }
+    }
+};
+
+template <typename T, int VV, int VH, int CS, int PF, bool SAVE, int MAXW>
+__global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
+    extern __shared__ float tile[];
+    const FwdParams& p = a.p;
+    const int H = p.H, W = p.W, HW = H * W;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int blocks_per_image = p.C / a.K;
+    const int b = blockIdx.x / blocks_per_image;
+    const int c_first = (blockIdx.x - b * blocks_per_image) * a.K;
+
+    const int tile_floats = a.K * H * a.pitch;
+    for (int i = threadIdx.x; i < tile_floats; i += blockDim.x) tile[i] = 0.f;
+    __syncthreads();
+
+    // ---- vertical pair: one wave per (pack, direction); the two contributions to an element commute
+    {
+        const int nd = ((p.mask >> 0) & 1) + ((p.mask >> 1) & 1);
+        const int packs = (a.K + a.pv - 1) / a.pv;
+        if (nd > 0 && wave < packs * nd) {
+            const int pk = wave / nd;
+            const int d = (nd == 2) ? (wave - pk * nd) : ((p.mask & 1) ? 0 : 1);
+            vertical_pass<T, VV, PF, SAVE>(a, tile, d, b, c_first, pk, lane);
+        }
+    }
+    __syncthreads();
+
+    // ---- horizontal pair, split at mid-scan so the two waves of a pack work on disjoint columns
+    {
+        const int has_lr = (p.mask >> 2) & 1, has_rl = (p.mask >> 3) & 1;
+        const int nd = has_lr + has_rl;
+        const int packs = (a.K + a.ph - 1) / a.ph;
+        const int nchunks = W / CS;
+        const int half_lr = (nchunks + 1) / 2;            // chunks the left->right wave does before the barrier
+        const int half_rl = nchunks - half_lr;            // chunks the right->left wave does before the barrier
+        const bool busy = nd > 0 && wave < packs * nd;
+        const int pk = busy ? wave / nd : 0;
+        const int d = (nd == 2) ? 2 + (wave - pk * nd) : (has_lr ? 2 : 3);
+        if (nd > 0) {
+            if (d == 2) {
+                HorizontalPass<T, VH, CS, false, SAVE> hp;
+                if (busy) { hp.init(a, tile, 2, b, c_first, pk, lane); hp.prologue(); hp.run(0, half_lr); }
+                __syncthreads();
+                if (busy) hp.run(half_lr, nchunks);
+            } else {
+                HorizontalPass<T, VH, CS, true, SAVE> hp;
+                if (busy) { hp.init(a, tile, 3, b, c_first, pk, lane); hp.prologue(); hp.run(0, half_rl); }
+                __syncthreads();
+                if (busy) hp.run(half_rl, nchunks);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- write the merged tile out once, coalesced, rounded once to the storage type
+    {
+        T* Y = (T*)p.y + ((size_t)b * p.C + c_first) * HW;
+        const int rows = a.K * H;
+        const int nw = blockDim.x >> 6;
+        for (int r = wave; r < rows; r += nw) {
+            const float* tr = tile + r * a.pitch;
+            T* yr = Y + (size_t)r * W;
+            for (int j = lane * 2; j < W; j += 128) {
+                float v[2] = {tr[j], tr[j + 1]};
+                uint32_t o[2 * sizeof(T) / 4];
+                pack<T, 2>(v, o);
+                st_raw<2 * sizeof(T)>((char*)(yr + j), o);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side: applicability, tiling choice, launch
+// ---------------------------------------------------------------------------
+static constexpr int LDS_BUDGET = 160 * 1024;
+
+struct TilePlan { bool ok; int vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwaves; size_t lds; };
+
+static TilePlan plan_tile(const FwdParams& p, int dtype) {
+    TilePlan t = {};
+    const char* force_k = getenv("GSPN_TILE_K");          // tuning aid: force the channels per workgroup
+    const int forced = force_k ? atoi(force_k) : 0;
+    const int es = dtype == 0 ? 4 : 2;
+    const int vv = 2, vh = 2;
+    int cs = 16 / es * ((dtype == 1 && p.W % 16 == 0) ? 2 : 1);     // 16 B (or 32 B) per burst
+    if (p.W % vv || p.H % vh || p.W % cs) return t;
+    if (p.W / vv > 64 || p.H / vh > 64) return t;
+    t.vv = vv; t.vh = vh; t.cs = cs;
+    t.pitch = p.W | 1;
+    t.lplv = p.W / vv; t.pv = 64 / t.lplv;
+    t.lplh = p.H / vh; t.ph = 64 / t.lplh;
+    const size_t per_channel = (size_t)p.H * t.pitch * sizeof(float);
+    // channels per workgroup: as many as fit in LDS with at most 8 waves, dividing C
+    const int dirs_v = ((p.mask >> 0) & 1) + ((p.mask >> 1) & 1), dirs_h = ((p.mask >> 2) & 1) + ((p.mask >> 3) & 1);
+    int best = 0;
+    for (int K = 1; K <= p.C && K <= 64; ++K) {
+        if (p.C % K) continue;
+        if (forced && K != forced) continue;
+        if (K * per_channel > (size_t)LDS_BUDGET) break;
+        const int wv = ((K + t.pv - 1) / t.pv) * dirs_v, wh = ((K + t.ph - 1) / t.ph) * dirs_h;
+        const int nw = wv > wh ? wv : wh;
+        if (nw > 8) continue;
+        best = K;
+        t.nwaves = nw < 1 ? 1 : nw;
+    }
+    if (!best) return t;
+    // recompute the wave count for the chosen K (the loop leaves the last accepted value)
+    t.K = best;
+    {
+        const int wv = ((best + t.pv - 1) / t.pv) * dirs_v, wh = ((best + t.ph - 1) / t.ph) * dirs_h;
+        t.nwaves = wv > wh ? wv : wh;
+        if (t.nwaves < 1) t.nwaves = 1;
+    }
+    if (t.nwaves > 4 && dtype == 1) t.cs = 8;    // the 32 B burst variant needs more than 256 registers per lane
+    t.lds = best * per_channel;
+    if ((size_t)p.B * (p.C / best) > 0x7fffffffull) return t;
+    if ((size_t)t.pv * p.H * p.W * es >= (1ull << 31) || (size_t)p.G * 3 * p.H * p.W * es >= (1ull << 31)) return t;
+    t.ok = true;
+    return t;
+}
+
+bool fwd_tile_applicable(const FwdParams& p, int dtype) { return plan_tile(p, dtype).ok; }
+
+template <typename T, int VV, int VH, int CS, int PF, bool SAVE, int MAXW>
+static hipError_t launch_one(const TileArgs& a, const TilePlan& t, hipStream_t s) {
+    const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * t.nwaves);
+    auto k = fwd_tile_kernel<T, VV, VH, CS, PF, SAVE, MAXW>;
+    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BUDGET);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
+    return hipGetLastError();
+}
+
+template <typename T, int VV, int VH, int CS, int PF>
+static hipError_t launch_cfg(const TileArgs& a, const TilePlan& t, bool save, hipStream_t s) {
+    if (t.nwaves <= 4)
+        return save ? launch_one<T, VV, VH, CS, PF, true, 4>(a, t, s) : launch_one<T, VV, VH, CS, PF, false, 4>(a, t, s);
+    return save ? launch_one<T, VV, VH, CS, PF, true, 8>(a, t, s) : launch_one<T, VV, VH, CS, PF, false, 8>(a, t, s);
+}
+
+hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s) {
+    const TilePlan t = plan_tile(p, dtype);
+    if (!t.ok) return hipErrorInvalidValue;
+    TileArgs a;
+    a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.lplh = t.lplh; a.ph = t.ph;
+    a.nwaves = t.nwaves;
+    const bool save = p.hs != nullptr;
+    if (dtype == 0) return launch_cfg<float, 2, 2, 4, 8>(a, t, save, s);
+    if (t.cs == 16) return launch_cfg<bf16_t, 2, 2, 16, 8>(a, t, save, s);
+    return launch_cfg<bf16_t, 2, 2, 8, 8>(a, t, save, s);
+}
+
+}  // namespace gspn

@@ -29,7 +29,8 @@ class GspnError(RuntimeError):
 
 
 def lib_path() -> str:
-    return os.path.join(_PKG, "libgspn.so")
+    """Path of the shared library; GSPN_LIBRARY overrides the in-tree build."""
+    return os.environ.get("GSPN_LIBRARY") or os.path.join(_PKG, "libgspn.so")
 
 
 def load_library() -> ctypes.CDLL:

@@ -91,6 +91,11 @@ __device__ __forceinline__ float from_lane_above(float v) {   // lane i <- lane 
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
 }
 
+// Workgroup barrier that orders LDS traffic only: the wave's own LDS operations are complete
+// before it arrives, and the compiler may not move memory operations across it.  Unlike
+// __syncthreads() it does not wait for the global loads in flight (the prefetch rings keep running).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // One line of Eq. 1 for the lane's V positions.  `first`/`last`: the lane holds the first/last
 // positions of its line, whose outer neighbour does not exist: both the neighbour value and its
 // weight are forced to 0 so that nothing stored for it (NaN, Inf) can leak in.
@@ -130,7 +135,7 @@ struct TileArgs {
 // ---------------------------------------------------------------------------
 template <typename T, int V, int PF, bool SAVE>
 __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int d, int b, int c_first, int pk,
-                                              int lane) {
+                                              int lane, int split) {
     constexpr int NB = V * (int)sizeof(T);
     constexpr int NR = NB / 4;
     const FwdParams& p = a.p;
@@ -198,7 +203,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
         const int row = rev ? H - 1 - t : t;
         float* tp = trow + row * a.pitch;
 #pragma unroll
-        for (int v = 0; v < V; ++v) atomicAdd(tp + v, uv[v] * h[v]);
+        for (int v = 0; v < V; ++v) tp[v] += uv[v] * h[v];   // exclusive owner of these elements in this half
         if constexpr (SAVE) {
             uint32_t hr[NR];
             pack<T, V>(h, hr);
@@ -214,6 +219,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
             const int t = t0 + k;
+            if (t == split) lds_barrier();
             step(slot[k], t, k == 0);
             issue(slot[k], min(t + PF, H - 1));
             __builtin_amdgcn_sched_barrier(0);   // keep the consume/refill interleaving as written
@@ -222,7 +228,10 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     // tail (fewer than PF lines left): their loads are already in the ring
 #pragma unroll
     for (int k = 0; k < PF; ++k)
-        if (t0 + k < H) step(slot[k], t0 + k, k == 0);
+        if (t0 + k < H) {
+            if (t0 + k == split) lds_barrier();
+            step(slot[k], t0 + k, k == 0);
+        }
 }
 
 // ---------------------------------------------------------------------------
@@ -311,7 +320,7 @@ struct HorizontalPass {
             }
             line_update<V>(h, av, w0, w1, w2, first, last);
 #pragma unroll
-            for (int v = 0; v < V; ++v) atomicAdd(trow + v * pitch + col0 + e, elem<T>(s.u[v], e) * h[v]);
+            for (int v = 0; v < V; ++v) trow[v * pitch + col0 + e] += elem<T>(s.u[v], e) * h[v];
             if constexpr (SAVE) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) hs[v][e] = h[v];
@@ -359,21 +368,26 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
 
     const int tile_floats = a.K * H * a.pitch;
     for (int i = threadIdx.x; i < tile_floats; i += blockDim.x) tile[i] = 0.f;
-    __syncthreads();
+    lds_barrier();
 
-    // ---- vertical pair: one wave per (pack, direction); the two contributions to an element commute
+    // Every element of the LDS tile has exactly one owner wave between two barriers, so plain
+    // read-modify-write is safe and the order of the four additions per element is fixed.
+    // ---- vertical pair: one wave per (pack, direction).  The top->bottom wave takes rows
+    // [0, ceil(H/2)) before the mid barrier and the rest after it; the bottom->top wave the complement.
     {
         const int nd = ((p.mask >> 0) & 1) + ((p.mask >> 1) & 1);
         const int packs = (a.K + a.pv - 1) / a.pv;
         if (nd > 0 && wave < packs * nd) {
             const int pk = wave / nd;
             const int d = (nd == 2) ? (wave - pk * nd) : ((p.mask & 1) ? 0 : 1);
-            vertical_pass<T, VV, PF, SAVE>(a, tile, d, b, c_first, pk, lane);
+            const int split = nd == 2 ? (d == 0 ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
+            vertical_pass<T, VV, PF, SAVE>(a, tile, d, b, c_first, pk, lane, split);
+        } else if (nd == 2) {
+            lds_barrier();
         }
     }
-    __syncthreads();
 
-    // ---- horizontal pair, split at mid-scan so the two waves of a pack work on disjoint columns
+    // ---- horizontal pair, split at mid-scan (chunk granularity) the same way
     {
         const int has_lr = (p.mask >> 2) & 1, has_rl = (p.mask >> 3) & 1;
         const int nd = has_lr + has_rl;
@@ -384,21 +398,29 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
         const bool busy = nd > 0 && wave < packs * nd;
         const int pk = busy ? wave / nd : 0;
         const int d = (nd == 2) ? 2 + (wave - pk * nd) : (has_lr ? 2 : 3);
-        if (nd > 0) {
-            if (d == 2) {
-                HorizontalPass<T, VH, CS, false, SAVE> hp;
-                if (busy) { hp.init(a, tile, 2, b, c_first, pk, lane); hp.prologue(); hp.run(0, half_lr); }
-                __syncthreads();
+        if (nd == 0) {
+            lds_barrier();
+        } else if (d == 2) {
+            HorizontalPass<T, VH, CS, false, SAVE> hp;
+            if (busy) { hp.init(a, tile, 2, b, c_first, pk, lane); hp.prologue(); }
+            lds_barrier();                                  // vertical phase complete (first loads already in flight)
+            if (busy) hp.run(0, nd == 2 ? half_lr : nchunks);
+            if (nd == 2) {
+                lds_barrier();
                 if (busy) hp.run(half_lr, nchunks);
-            } else {
-                HorizontalPass<T, VH, CS, true, SAVE> hp;
-                if (busy) { hp.init(a, tile, 3, b, c_first, pk, lane); hp.prologue(); hp.run(0, half_rl); }
-                __syncthreads();
+            }
+        } else {
+            HorizontalPass<T, VH, CS, true, SAVE> hp;
+            if (busy) { hp.init(a, tile, 3, b, c_first, pk, lane); hp.prologue(); }
+            lds_barrier();
+            if (busy) hp.run(0, nd == 2 ? half_rl : nchunks);
+            if (nd == 2) {
+                lds_barrier();
                 if (busy) hp.run(half_rl, nchunks);
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- write the merged tile out once, coalesced, rounded once to the storage type
     {
@@ -421,6 +443,9 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
 // ---------------------------------------------------------------------------
 // host side: applicability, tiling choice, launch
 // ---------------------------------------------------------------------------
+#ifndef EXP_PF
+#define EXP_PF 8
+#endif
 static constexpr int LDS_BUDGET = 160 * 1024;
 
 struct TilePlan { bool ok; int vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwaves; size_t lds; };
@@ -495,8 +520,8 @@ hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s) {
     a.nwaves = t.nwaves;
     const bool save = p.hs != nullptr;
     if (dtype == 0) return launch_cfg<float, 2, 2, 4, 8>(a, t, save, s);
-    if (t.cs == 16) return launch_cfg<bf16_t, 2, 2, 16, 8>(a, t, save, s);
-    return launch_cfg<bf16_t, 2, 2, 8, 8>(a, t, save, s);
+    if (t.cs == 16) return launch_cfg<bf16_t, 2, 2, 16, EXP_PF>(a, t, save, s);
+    return launch_cfg<bf16_t, 2, 2, 8, EXP_PF>(a, t, save, s);
 }
 
 }  // namespace gspn

@@ -242,7 +242,10 @@ template <typename T, int V, int CS>
 struct HBuf { uint32_t x[V][CS * sizeof(T) / 4], l[V][CS * sizeof(T) / 4], u[V][CS * sizeof(T) / 4],
               w0[V][CS * sizeof(T) / 4], w1[V][CS * sizeof(T) / 4], w2[V][CS * sizeof(T) / 4]; };
 
-template <typename T, int V, int CS, bool REV, bool SAVE>
+// DB = true: two chunk buffers, the next chunk is loaded while the current one is consumed.
+// DB = false: one buffer (for chunks too large to hold twice); the next chunk is requested as soon
+// as the current one is consumed and other waves of the CU cover the wait.
+template <typename T, int V, int CS, bool REV, bool SAVE, bool DB>
 struct HorizontalPass {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -338,10 +341,17 @@ struct HorizontalPass {
 
     __device__ __forceinline__ void prologue() { if (active) issue(buf0, 0); }
 
-    // chunks [c_begin, c_end); buffer (c & 1) already holds / is loading chunk c_begin.
+    // chunks [c_begin, c_end); the buffer for chunk c_begin already holds it or is being loaded.
     // Unused lanes are masked off for the whole loop (their DPP reads see 0).
     __device__ __forceinline__ void run(int c_begin, int c_end) {
         if (!active) return;
+        if constexpr (!DB) {
+            for (int c = c_begin; c < c_end; ++c) {
+                compute(buf0, c);
+                issue(buf0, c + 1 < nchunks ? c + 1 : c);     // clamped: redundant but in bounds at the end
+            }
+            return;
+        }
         for (int c = c_begin; c < c_end; ++c) {
             const int cn = c + 1 < nchunks ? c + 1 : c;      // clamped: redundant but in bounds at the end
             if ((c & 1) == 0) {
@@ -355,7 +365,7 @@ struct HorizontalPass {
     }
 };
 
-template <typename T, int VV, int VH, int CS, int PF, bool SAVE, int MAXW>
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW>
 __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
     extern __shared__ float tile[];
     const FwdParams& p = a.p;
@@ -401,7 +411,7 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
         if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
-            HorizontalPass<T, VH, CS, false, SAVE> hp;
+            HorizontalPass<T, VH, CS, false, SAVE, DB> hp;
             if (busy) { hp.init(a, tile, 2, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();                                  // vertical phase complete (first loads already in flight)
             if (busy) hp.run(0, nd == 2 ? half_lr : nchunks);
@@ -410,7 +420,7 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
                 if (busy) hp.run(half_lr, nchunks);
             }
         } else {
-            HorizontalPass<T, VH, CS, true, SAVE> hp;
+            HorizontalPass<T, VH, CS, true, SAVE, DB> hp;
             if (busy) { hp.init(a, tile, 3, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, nd == 2 ? half_rl : nchunks);
@@ -448,18 +458,40 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
 #endif
 static constexpr int LDS_BUDGET = 160 * 1024;
 
-struct TilePlan { bool ok; int vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwaves; size_t lds; };
+// Horizontal-phase variants: rows per lane, scan steps per burst, double buffered or not.
+//   whole-row bursts (rows of at most 128 B: 56 bf16 / 28 fp32), one row per lane, single buffer;
+//   64 B bursts (one L2 sector per row and tensor), two rows per lane, single buffer;
+//   16 B bursts, two rows per lane, double buffered: any width that is a multiple of 16 B.
+enum HVariant { H_ROW = 0, H_SECTOR = 1, H_SMALL = 2 };
+
+struct TilePlan { bool ok; int hv, vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwaves; size_t lds; };
 
 static TilePlan plan_tile(const FwdParams& p, int dtype) {
     TilePlan t = {};
     const char* force_k = getenv("GSPN_TILE_K");          // tuning aid: force the channels per workgroup
     const int forced = force_k ? atoi(force_k) : 0;
+    const char* force_h = getenv("GSPN_TILE_HV");         // tuning aid: force the horizontal variant
     const int es = dtype == 0 ? 4 : 2;
-    const int vv = 2, vh = 2;
-    int cs = 16 / es * ((dtype == 1 && p.W % 16 == 0) ? 2 : 1);     // 16 B (or 32 B) per burst
-    if (p.W % vv || p.H % vh || p.W % cs) return t;
-    if (p.W / vv > 64 || p.H / vh > 64) return t;
-    t.vv = vv; t.vh = vh; t.cs = cs;
+    const char* force_vv = getenv("GSPN_TILE_VV");        // tuning aid: columns per lane in the vertical phases
+    int vv = 2;
+    if (force_vv && atoi(force_vv) == 4 && dtype == 1 && p.W % 64 == 0) vv = 4;
+    if (force_vv && atoi(force_vv) == 8 && dtype == 1 && p.W % 64 == 0) vv = 8;
+    if (p.W % vv || p.W / vv > 64) return t;
+    const int row_bytes = p.W * es;
+    int hv;
+    if (row_bytes == 112 && p.H <= 64) hv = H_ROW;
+    else if (row_bytes % 64 == 0) hv = H_SECTOR;
+    else if (row_bytes % 16 == 0) hv = H_SMALL;
+    else return t;
+    if (force_h) {
+        const int f = atoi(force_h);
+        if (f == H_SMALL && row_bytes % 16 == 0) hv = H_SMALL;
+        if (f == H_SECTOR && row_bytes % 64 == 0) hv = H_SECTOR;
+    }
+    const int vh = hv == H_ROW ? 1 : 2;
+    const int cs = hv == H_ROW ? p.W : (hv == H_SECTOR ? 64 / es : 16 / es);
+    if (p.H % vh || p.H / vh > 64) return t;
+    t.hv = hv; t.vv = vv; t.vh = vh; t.cs = cs;
     t.pitch = p.W | 1;
     t.lplv = p.W / vv; t.pv = 64 / t.lplv;
     t.lplh = p.H / vh; t.ph = 64 / t.lplh;
@@ -475,17 +507,14 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
         const int nw = wv > wh ? wv : wh;
         if (nw > 8) continue;
         best = K;
-        t.nwaves = nw < 1 ? 1 : nw;
     }
     if (!best) return t;
-    // recompute the wave count for the chosen K (the loop leaves the last accepted value)
     t.K = best;
     {
         const int wv = ((best + t.pv - 1) / t.pv) * dirs_v, wh = ((best + t.ph - 1) / t.ph) * dirs_h;
         t.nwaves = wv > wh ? wv : wh;
         if (t.nwaves < 1) t.nwaves = 1;
     }
-    if (t.nwaves > 4 && dtype == 1) t.cs = 8;    // the 32 B burst variant needs more than 256 registers per lane
     t.lds = best * per_channel;
     if ((size_t)p.B * (p.C / best) > 0x7fffffffull) return t;
     if ((size_t)t.pv * p.H * p.W * es >= (1ull << 31) || (size_t)p.G * 3 * p.H * p.W * es >= (1ull << 31)) return t;
@@ -495,21 +524,23 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
 
 bool fwd_tile_applicable(const FwdParams& p, int dtype) { return plan_tile(p, dtype).ok; }
 
-template <typename T, int VV, int VH, int CS, int PF, bool SAVE, int MAXW>
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW>
 static hipError_t launch_one(const TileArgs& a, const TilePlan& t, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * t.nwaves);
-    auto k = fwd_tile_kernel<T, VV, VH, CS, PF, SAVE, MAXW>;
+    auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW>;
     hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BUDGET);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();
 }
 
-template <typename T, int VV, int VH, int CS, int PF>
+template <typename T, int VV, int VH, int CS, bool DB, int PF>
 static hipError_t launch_cfg(const TileArgs& a, const TilePlan& t, bool save, hipStream_t s) {
     if (t.nwaves <= 4)
-        return save ? launch_one<T, VV, VH, CS, PF, true, 4>(a, t, s) : launch_one<T, VV, VH, CS, PF, false, 4>(a, t, s);
-    return save ? launch_one<T, VV, VH, CS, PF, true, 8>(a, t, s) : launch_one<T, VV, VH, CS, PF, false, 8>(a, t, s);
+        return save ? launch_one<T, VV, VH, CS, DB, PF, true, 4>(a, t, s)
+                    : launch_one<T, VV, VH, CS, DB, PF, false, 4>(a, t, s);
+    return save ? launch_one<T, VV, VH, CS, DB, PF, true, 8>(a, t, s)
+                : launch_one<T, VV, VH, CS, DB, PF, false, 8>(a, t, s);
 }
 
 hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s) {
@@ -519,9 +550,16 @@ hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s) {
     a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.lplh = t.lplh; a.ph = t.ph;
     a.nwaves = t.nwaves;
     const bool save = p.hs != nullptr;
-    if (dtype == 0) return launch_cfg<float, 2, 2, 4, 8>(a, t, save, s);
-    if (t.cs == 16) return launch_cfg<bf16_t, 2, 2, 16, EXP_PF>(a, t, save, s);
-    return launch_cfg<bf16_t, 2, 2, 8, EXP_PF>(a, t, save, s);
+    if (dtype == 0) {
+        if (t.hv == H_ROW) return launch_cfg<float, 2, 1, 28, false, EXP_PF>(a, t, save, s);
+        if (t.hv == H_SECTOR) return launch_cfg<float, 2, 2, 16, false, EXP_PF>(a, t, save, s);
+        return launch_cfg<float, 2, 2, 4, true, EXP_PF>(a, t, save, s);
+    }
+    if (t.hv == H_ROW) return launch_cfg<bf16_t, 2, 1, 56, false, EXP_PF>(a, t, save, s);
+    if (t.hv == H_SECTOR && t.vv == 8) return launch_cfg<bf16_t, 8, 2, 32, false, 4>(a, t, save, s);
+    if (t.hv == H_SECTOR && t.vv == 4) return launch_cfg<bf16_t, 4, 2, 32, false, EXP_PF>(a, t, save, s);
+    if (t.hv == H_SECTOR) return launch_cfg<bf16_t, 2, 2, 32, false, EXP_PF>(a, t, save, s);
+    return launch_cfg<bf16_t, 2, 2, 8, true, EXP_PF>(a, t, save, s);
 }
 
 }  // namespace gspn

@@ -144,3 +144,29 @@ def test_library_reports_shape_errors_through_the_binding():
         G.gspn_scan_fwd(x, w, lam, lam, y, None)
     assert ei.value.status == 2
     assert torch.all(y == 7.0)                               # outputs untouched on argument errors
+
+
+@pytest.mark.parametrize("cfg", [SHRUNK[0], SHRUNK[2], SHRUNK[6], SHRUNK[7]],
+                         ids=lambda c: f"{c.name}-{c.dtype}")
+def test_generic_kernel_on_shapes_the_tile_kernel_normally_takes(cfg, monkeypatch):
+    import paper_2512_07884_amd as G
+    dt = int(cfg.dtype == "bf16")
+    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) == "tile"
+    monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
+    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) == "generic"
+    check_case(cfg)
+
+
+def test_both_kernel_families_agree_closely():
+    # the tile kernel (one rounding of the merged sum) and the generic kernel (one per direction)
+    # must agree to storage precision on the same inputs
+    import os
+    cfg = SHRUNK[0]
+    inp = WL.make_inputs(cfg, with_gy=False)
+    y_tile, *_ = run_fwd_gpu(inp, cfg, 15)
+    os.environ["GSPN_FORCE_GENERIC"] = "1"
+    try:
+        y_gen, *_ = run_fwd_gpu(inp, cfg, 15)
+    finally:
+        del os.environ["GSPN_FORCE_GENERIC"]
+    assert rel_inf_err(y_gen, y_tile) <= 1e-2

@@ -128,16 +128,18 @@ struct TileArgs {
     int lplv, pv; // vertical phases: lanes per line, channels side by side in a wave
     int lplh, ph; // horizontal phases
     int nwaves;
+    int parts;    // row-split horizontal phases: waves per line (each owns H/parts image rows)
 };
 
 // ---------------------------------------------------------------------------
 // vertical direction (d = 0 top->bottom, 1 bottom->top): lines are image rows
 // ---------------------------------------------------------------------------
-template <typename T, int V, int PF, bool SAVE>
-__device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int d, int b, int c_first, int pk,
+template <typename T, int V, int PF, bool REV, bool SAVE>
+__device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int b, int c_first, int pk,
                                               int lane, int split) {
     constexpr int NB = V * (int)sizeof(T);
     constexpr int NR = NB / 4;
+    constexpr int d = REV ? 1 : 0;
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
     const int pl = lane / a.lplv, i = lane - pl * a.lplv;
@@ -154,84 +156,100 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     const size_t plane0 = ((size_t)b * p.C + c_pack) * HW;      // uniform
     const uint32_t voff = (uint32_t)((plc * HW + ic * V) * (int)sizeof(T));
     const uint32_t voff_w = (uint32_t)(((g - g0) * 3 * HW + ic * V) * (int)sizeof(T));
+    const int row_bytes = W * (int)sizeof(T);
+    const size_t plane_bytes = (size_t)HW * sizeof(T);
+    const char* wbase = (const char*)p.w + (slot_w + ((size_t)b * p.G + g0) * 3 * HW) * sizeof(T);
     const rsrc_t xb = make_rsrc((const char*)p.x + plane0 * sizeof(T));
     const rsrc_t lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * sizeof(T));
     const rsrc_t ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
-    const rsrc_t wb = make_rsrc((const char*)p.w + (slot_w + ((size_t)b * p.G + g0) * 3 * HW) * sizeof(T));
+    const rsrc_t w0b = make_rsrc(wbase), w1b = make_rsrc(wbase + plane_bytes), w2b = make_rsrc(wbase + 2 * plane_bytes);
     const rsrc_t hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * sizeof(T) : (char*)p.y);
-    const int rev = d & 1;
-    const int row_bytes = W * (int)sizeof(T);
-    const int plane_bytes = HW * (int)sizeof(T);
-    float* trow = tile + ((pk * a.pv + plc) * H) * a.pitch + ic * V;
 
     if (!active) return;   // the whole pass runs with unused lanes masked off (their DPP reads see 0)
 
+    // scan step t works on image row t (top->bottom) or H-1-t (bottom->top); everything below walks
+    // byte / float offsets by a constant signed stride per step, so a step costs no address arithmetic
+    // beyond one scalar add (global) and one vector add (LDS)
+    const int sstep = REV ? -row_bytes : row_bytes;
+    const int so0 = REV ? (H - 1) * row_bytes : 0;
+    const int tstep = REV ? -a.pitch : a.pitch;
+    float* tp = tile + ((pk * a.pv + plc) * H + (REV ? H - 1 : 0)) * a.pitch + ic * V;   // row of scan step 0
+
     struct Line { uint32_t x[NR], l[NR], u[NR], w0[NR], w1[NR], w2[NR]; };
     Line slot[PF];
-    auto issue = [&](Line& s, int t) {
-        const int row = rev ? H - 1 - t : t;
-        const int ro = row * row_bytes;
-        ld_buf<NB>(xb, voff, ro, s.x);
-        ld_buf<NB>(lb, voff, ro, s.l);
-        ld_buf<NB>(ub, voff, ro, s.u);
-        ld_buf<NB>(wb, voff_w, ro, s.w0);
-        ld_buf<NB>(wb, voff_w, plane_bytes + ro, s.w1);
-        ld_buf<NB>(wb, voff_w, 2 * plane_bytes + ro, s.w2);
+    auto issue = [&](Line& s, int so) {
+        ld_buf<NB>(xb, voff, so, s.x);
+        ld_buf<NB>(lb, voff, so, s.l);
+        ld_buf<NB>(ub, voff, so, s.u);
+        ld_buf<NB>(w0b, voff_w, so, s.w0);
+        ld_buf<NB>(w1b, voff_w, so, s.w1);
+        ld_buf<NB>(w2b, voff_w, so, s.w2);
     };
-    // unconditional (clamped) so that every path into the loop has the same loads in flight
+    // the ring starts with scan steps 0..PF-1 (clamped to the last step of short scans: redundant but in
+    // bounds); issued unconditionally so that every path into the loops has the same loads in flight
 #pragma unroll
-    for (int k = 0; k < PF; ++k) issue(slot[k], min(k, H - 1));
+    for (int k = 0; k < PF; ++k) issue(slot[k], so0 + min(k, H - 1) * sstep);
 
     float h[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) h[v] = 0.f;
+    int so_cur = so0;            // byte offset of the row of the current step (for h_save)
+    int until_split = split;     // steps left before the mid-scan barrier (negative: none)
 
-    // `maybe_first`: this step can be scan step 0, whose weights are never used (the stored values
-    // may be anything): they are replaced by 0 so the (zero) initial state contributes exactly 0
-    auto step = [&](const Line& cur, int t, bool maybe_first) {
+    // `scan_start`: this is scan step 0, whose weights are never used (the stored values may be
+    // anything): they are replaced by 0 so the (zero) initial state contributes exactly 0
+    auto step = [&](const Line& cur, bool maybe_start, bool scan_start) {
+        if (until_split == 0) lds_barrier();
+        --until_split;
         float av[V], w0[V], w1[V], w2[V], uv[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
             w0[v] = elem<T>(cur.w0, v); w1[v] = elem<T>(cur.w1, v); w2[v] = elem<T>(cur.w2, v);
             uv[v] = elem<T>(cur.u, v);
-            if (maybe_first) {
-                w0[v] = t == 0 ? 0.f : w0[v]; w1[v] = t == 0 ? 0.f : w1[v]; w2[v] = t == 0 ? 0.f : w2[v];
+            if (maybe_start) {
+                w0[v] = scan_start ? 0.f : w0[v]; w1[v] = scan_start ? 0.f : w1[v]; w2[v] = scan_start ? 0.f : w2[v];
             }
         }
         line_update<V>(h, av, w0, w1, w2, first, last);
-        const int row = rev ? H - 1 - t : t;
-        float* tp = trow + row * a.pitch;
 #pragma unroll
         for (int v = 0; v < V; ++v) tp[v] += uv[v] * h[v];   // exclusive owner of these elements in this half
+        tp += tstep;
         if constexpr (SAVE) {
             uint32_t hr[NR];
             pack<T, V>(h, hr);
-            st_buf<NB>(hb, voff, row * row_bytes, hr);
+            st_buf<NB>(hb, voff, so_cur, hr);
+            so_cur += sstep;
         }
     };
 
-    // Full blocks of PF lines: straight-line code, slot k is consumed and at once refilled with
-    // the line PF steps ahead (clamped to the last line: redundant but in bounds near the end),
-    // so the register ring is static and the hardware load counter can be waited on by count.
+    // Hot loop: blocks of PF steps while the line PF steps ahead always exists.  Straight-line code:
+    // slot k is consumed and at once refilled, so the register ring is static and the hardware
+    // load counter can be waited on by count (never drained).
     int t0 = 0;
-    for (; t0 + PF <= H; t0 += PF) {
+    int so_next = so0 + PF * sstep;      // byte offset of the next line to request
+    for (; t0 + 2 * PF <= H; t0 += PF) {
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
-            const int t = t0 + k;
-            if (t == split) lds_barrier();
-            step(slot[k], t, k == 0);
-            issue(slot[k], min(t + PF, H - 1));
+            step(slot[k], k == 0, t0 == 0);
+            issue(slot[k], so_next);
+            so_next += sstep;
             __builtin_amdgcn_sched_barrier(0);   // keep the consume/refill interleaving as written
         }
     }
-    // tail (fewer than PF lines left): their loads are already in the ring
+    // Last full block: refills are clamped to the last line (redundant, in bounds), then the tail.
+    if (t0 + PF <= H) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) {
+            step(slot[k], k == 0, t0 == 0);
+            issue(slot[k], so0 + min(t0 + k + PF, H - 1) * sstep);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        t0 += PF;
+    }
 #pragma unroll
     for (int k = 0; k < PF; ++k)
-        if (t0 + k < H) {
-            if (t0 + k == split) lds_barrier();
-            step(slot[k], t0 + k, k == 0);
-        }
+        if (t0 + k < H) step(slot[k], k == 0, t0 == 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -365,6 +383,125 @@ struct HorizontalPass {
     }
 };
 
+// ---------------------------------------------------------------------------
+// horizontal direction for lines longer than a wave can hold at one row per lane: the H image
+// rows of a line are split over `parts` waves (each lane owns ONE row, so a whole 128 B memory
+// line per row and tensor fits in registers and every line is fetched exactly once).  The
+// waves of a line run in lock step, one workgroup barrier per scan step, and pass the state of
+// their edge rows to each other through a two-slot LDS mailbox (slot = parity of the step).
+// Because every step is its own barrier interval, the two directions never own the same tile
+// column at the same time and no mid-scan split is needed.
+// ---------------------------------------------------------------------------
+template <typename T, int CS, bool REV, bool SAVE>
+struct HorizontalSplitPass {
+    static constexpr int NB = CS * (int)sizeof(T);
+    static constexpr int NR = NB / 4;
+    rsrc_t xb, lb, ub, w0b, w1b, w2b, hb;
+    uint32_t voff;
+    int nchunks;
+    float* trow;        // this lane's row of the channel's tile
+    float* mb_out;      // where this lane publishes its state (edge lanes only), parity 0
+    const float* mb_up; // edge state of the part above (its last row), parity 0
+    const float* mb_dn; // edge state of the part below (its first row), parity 0
+    bool active, edge, top_lane, bot_lane, has_up, has_dn, img_first, img_last;
+    float h;
+    uint32_t bx[NR], bl[NR], bu[NR], b0[NR], b1[NR], b2[NR];
+
+    // mailbox layout: [task = channel * 2 + direction slot][part][side: 0 first row, 1 last row][parity]
+    __device__ __forceinline__ void init(const TileArgs& a, float* tile, float* mailbox, int d, int dslot, int b,
+                                         int c_first, int kc, int part, int lane) {
+        const FwdParams& p = a.p;
+        const int H = p.H, W = p.W, HW = H * W;
+        const int rp = H / a.parts;                       // rows per part (<= 64)
+        active = lane < rp;
+        const int lr = active ? lane : 0;
+        const int row = part * rp + lr;
+        const int c = c_first + kc;
+        const int g = c / p.cpg;
+        top_lane = lr == 0; bot_lane = lr == rp - 1;
+        edge = active && (top_lane || bot_lane);
+        has_up = part > 0; has_dn = part < a.parts - 1;
+        img_first = top_lane && !has_up; img_last = bot_lane && !has_dn;
+        const size_t planes = (size_t)p.B * p.C;
+        const size_t slot_c = p.shared ? 0 : (size_t)d * planes * HW;
+        const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
+        const size_t plane0 = ((size_t)b * p.C + c) * HW;
+        const size_t plane_bytes = (size_t)HW * sizeof(T);
+        const char* wbase = (const char*)p.w + (slot_w + ((size_t)b * p.G + g) * 3 * HW) * sizeof(T);
+        voff = (uint32_t)(row * W * (int)sizeof(T));
+        xb = make_rsrc((const char*)p.x + plane0 * sizeof(T));
+        lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * sizeof(T));
+        ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
+        w0b = make_rsrc(wbase); w1b = make_rsrc(wbase + plane_bytes); w2b = make_rsrc(wbase + 2 * plane_bytes);
+        hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * sizeof(T) : (char*)p.y);
+        nchunks = W / CS;
+        trow = tile + (kc * H + row) * a.pitch;
+        float* task = mailbox + ((kc * 2 + dslot) * a.parts) * 4;
+        mb_out = task + part * 4 + (bot_lane ? 2 : 0);
+        mb_up = task + (has_up ? part - 1 : part) * 4 + 2;
+        mb_dn = task + (has_dn ? part + 1 : part) * 4 + 0;
+        h = 0.f;
+    }
+
+    __device__ __forceinline__ int chunk_col(int c) const { return (REV ? nchunks - 1 - c : c) * CS; }
+
+    __device__ __forceinline__ void issue(int c) {
+        const int so = chunk_col(c) * (int)sizeof(T);
+        ld_buf<NB>(xb, voff, so, bx);
+        ld_buf<NB>(lb, voff, so, bl);
+        ld_buf<NB>(ub, voff, so, bu);
+        ld_buf<NB>(w0b, voff, so, b0);
+        ld_buf<NB>(w1b, voff, so, b1);
+        ld_buf<NB>(w2b, voff, so, b2);
+    }
+
+    // one chunk of CS scan steps; `s0` = scan step of its first column (for the mailbox parity)
+    __device__ __forceinline__ void compute(int c) {
+        const int col0 = chunk_col(c);
+        float hs[CS];
+#pragma unroll
+        for (int k = 0; k < CS; ++k) {
+            const int e = REV ? CS - 1 - k : k;
+            constexpr int dummy = 0; (void)dummy;
+            const int par = k & 1;                           // CS is even: parity of the scan step
+            // edge state the neighbouring parts published in the previous step
+            const float pu = mb_up[par ^ 1];
+            const float pd = mb_dn[par ^ 1];
+            const bool start = (c == 0) && (k == 0);
+            float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
+            if (k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
+            const float av = elem<T>(bl, e) * elem<T>(bx, e);
+            float up = from_lane_below(h), dn = from_lane_above(h);
+            up = top_lane ? (has_up ? pu : 0.f) : up;
+            dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
+            w0 = img_first ? 0.f : w0;
+            w2 = img_last ? 0.f : w2;
+            h = fmaf(w0, up, fmaf(w1, h, fmaf(w2, dn, av)));
+            trow[col0 + e] += elem<T>(bu, e) * h;
+            if (edge) mb_out[par] = h;
+            if constexpr (SAVE) hs[e] = h;
+            lds_barrier();
+        }
+        if constexpr (SAVE) {
+            uint32_t r[NR];
+            pack<T, CS>(hs, r);
+            st_buf<NB>(hb, voff, col0 * (int)sizeof(T), r);
+        }
+    }
+
+    __device__ __forceinline__ void prologue() { if (active) issue(0); }
+
+    __device__ __forceinline__ void run() {
+        // unused lanes are masked off for the whole loop; the wave still executes every barrier
+        if (active) {
+            for (int c = 0; c < nchunks; ++c) {
+                compute(c);
+                issue(c + 1 < nchunks ? c + 1 : c);     // clamped: redundant but in bounds at the end
+            }
+        }
+    }
+};
+
 template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW>
 __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
     extern __shared__ float tile[];
@@ -376,8 +513,10 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
     const int b = blockIdx.x / blocks_per_image;
     const int c_first = (blockIdx.x - b * blocks_per_image) * a.K;
 
+    // tile, followed (row-split horizontal phases only) by the mailbox: both start at zero
     const int tile_floats = a.K * H * a.pitch;
-    for (int i = threadIdx.x; i < tile_floats; i += blockDim.x) tile[i] = 0.f;
+    const int lds_floats = tile_floats + (VH == 0 ? a.K * 2 * a.parts * 4 : 0);
+    for (int i = threadIdx.x; i < lds_floats; i += blockDim.x) tile[i] = 0.f;
     lds_barrier();
 
     // Every element of the LDS tile has exactly one owner wave between two barriers, so plain
@@ -391,7 +530,8 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
             const int pk = wave / nd;
             const int d = (nd == 2) ? (wave - pk * nd) : ((p.mask & 1) ? 0 : 1);
             const int split = nd == 2 ? (d == 0 ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
-            vertical_pass<T, VV, PF, SAVE>(a, tile, d, b, c_first, pk, lane, split);
+            if (d == 0) vertical_pass<T, VV, PF, false, SAVE>(a, tile, b, c_first, pk, lane, split);
+            else vertical_pass<T, VV, PF, true, SAVE>(a, tile, b, c_first, pk, lane, split);
         } else if (nd == 2) {
             lds_barrier();
         }
@@ -408,7 +548,35 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
         const bool busy = nd > 0 && wave < packs * nd;
         const int pk = busy ? wave / nd : 0;
         const int d = (nd == 2) ? 2 + (wave - pk * nd) : (has_lr ? 2 : 3);
-        if (nd == 0) {
+        if constexpr (VH == 0) {
+            // row-split variant: wave -> (channel, direction, part); one barrier per scan step for everybody
+            const int ntask = a.K * nd * a.parts;
+            const bool work = nd > 0 && wave < ntask;
+            const int part = work ? wave % a.parts : 0;
+            const int cd = work ? wave / a.parts : 0;
+            const int kc = cd / (nd > 0 ? nd : 1);
+            const int dslot = cd - kc * (nd > 0 ? nd : 1);
+            const int dd = (nd == 2) ? 2 + dslot : (has_lr ? 2 : 3);
+            float* mailbox = tile + tile_floats;
+            if (nd == 0) {
+                lds_barrier();
+            } else if (work && dd == 2) {
+                HorizontalSplitPass<T, CS, false, SAVE> hp;
+                hp.init(a, tile, mailbox, 2, dslot, b, c_first, kc, part, lane);
+                hp.prologue();
+                lds_barrier();
+                hp.run();
+            } else if (work) {
+                HorizontalSplitPass<T, CS, true, SAVE> hp;
+                hp.init(a, tile, mailbox, 3, dslot, b, c_first, kc, part, lane);
+                hp.prologue();
+                lds_barrier();
+                hp.run();
+            } else {
+                lds_barrier();
+                for (int st = 0; st < W; ++st) lds_barrier();    // idle wave: keep the barrier count
+            }
+        } else if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
             HorizontalPass<T, VH, CS, false, SAVE, DB> hp;
@@ -462,9 +630,9 @@ static constexpr int LDS_BUDGET = 160 * 1024;
 //   whole-row bursts (rows of at most 128 B: 56 bf16 / 28 fp32), one row per lane, single buffer;
 //   64 B bursts (one L2 sector per row and tensor), two rows per lane, single buffer;
 //   16 B bursts, two rows per lane, double buffered: any width that is a multiple of 16 B.
-enum HVariant { H_ROW = 0, H_SECTOR = 1, H_SMALL = 2 };
+enum HVariant { H_ROW = 0, H_SECTOR = 1, H_SMALL = 2, H_SPLIT = 3 };
 
-struct TilePlan { bool ok; int hv, vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwaves; size_t lds; };
+struct TilePlan { bool ok; int hv, vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwaves, parts; size_t lds; };
 
 static TilePlan plan_tile(const FwdParams& p, int dtype) {
     TilePlan t = {};
@@ -472,46 +640,50 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
     const int forced = force_k ? atoi(force_k) : 0;
     const char* force_h = getenv("GSPN_TILE_HV");         // tuning aid: force the horizontal variant
     const int es = dtype == 0 ? 4 : 2;
-    const char* force_vv = getenv("GSPN_TILE_VV");        // tuning aid: columns per lane in the vertical phases
-    int vv = 2;
-    if (force_vv && atoi(force_vv) == 4 && dtype == 1 && p.W % 64 == 0) vv = 4;
-    if (force_vv && atoi(force_vv) == 8 && dtype == 1 && p.W % 64 == 0) vv = 8;
+    const int vv = 2;
     if (p.W % vv || p.W / vv > 64) return t;
     const int row_bytes = p.W * es;
     int hv;
+    const int parts = (p.H + 63) / 64;
     if (row_bytes == 112 && p.H <= 64) hv = H_ROW;
+    else if (row_bytes % 128 == 0 && p.H > 64 && p.H % parts == 0 && p.H / parts >= 2) hv = H_SPLIT;
     else if (row_bytes % 64 == 0) hv = H_SECTOR;
     else if (row_bytes % 16 == 0) hv = H_SMALL;
     else return t;
     if (force_h) {
         const int f = atoi(force_h);
+        if (f != H_SPLIT && hv == H_SPLIT) hv = H_SECTOR;
         if (f == H_SMALL && row_bytes % 16 == 0) hv = H_SMALL;
         if (f == H_SECTOR && row_bytes % 64 == 0) hv = H_SECTOR;
     }
-    const int vh = hv == H_ROW ? 1 : 2;
-    const int cs = hv == H_ROW ? p.W : (hv == H_SECTOR ? 64 / es : 16 / es);
-    if (p.H % vh || p.H / vh > 64) return t;
-    t.hv = hv; t.vv = vv; t.vh = vh; t.cs = cs;
+    const int vh = hv == H_ROW ? 1 : (hv == H_SPLIT ? 0 : 2);
+    const int cs = hv == H_ROW ? p.W : (hv == H_SPLIT ? 128 / es : (hv == H_SECTOR ? 64 / es : 16 / es));
+    if (vh > 0 && (p.H % vh || p.H / vh > 64)) return t;
+    t.hv = hv; t.vv = vv; t.vh = vh; t.cs = cs; t.parts = hv == H_SPLIT ? parts : 1;
     t.pitch = p.W | 1;
     t.lplv = p.W / vv; t.pv = 64 / t.lplv;
-    t.lplh = p.H / vh; t.ph = 64 / t.lplh;
-    const size_t per_channel = (size_t)p.H * t.pitch * sizeof(float);
-    // channels per workgroup: as many as fit in LDS with at most 8 waves, dividing C
+    t.lplh = vh > 0 ? p.H / vh : 64; t.ph = vh > 0 ? 64 / t.lplh : 1;
+    const size_t per_channel = (size_t)p.H * t.pitch * sizeof(float) + (hv == H_SPLIT ? 2 * parts * 4 * sizeof(float) : 0);
+    // channels per workgroup: the smallest count that fills the lanes of a wave in both phases
+    // (several small workgroups per CU overlap each other's barriers and load waits better than
+    // one large one), dividing C, fitting LDS, with at most 8 waves
     const int dirs_v = ((p.mask >> 0) & 1) + ((p.mask >> 1) & 1), dirs_h = ((p.mask >> 2) & 1) + ((p.mask >> 3) & 1);
+    const int want = t.pv > t.ph ? t.pv : t.ph;
     int best = 0;
     for (int K = 1; K <= p.C && K <= 64; ++K) {
         if (p.C % K) continue;
         if (forced && K != forced) continue;
         if (K * per_channel > (size_t)LDS_BUDGET) break;
-        const int wv = ((K + t.pv - 1) / t.pv) * dirs_v, wh = ((K + t.ph - 1) / t.ph) * dirs_h;
+        const int wv = ((K + t.pv - 1) / t.pv) * dirs_v, wh = ((K + t.ph - 1) / t.ph) * dirs_h * t.parts;
         const int nw = wv > wh ? wv : wh;
         if (nw > 8) continue;
         best = K;
+        if (K >= want && K % t.pv == 0 && K % t.ph == 0) break;
     }
     if (!best) return t;
     t.K = best;
     {
-        const int wv = ((best + t.pv - 1) / t.pv) * dirs_v, wh = ((best + t.ph - 1) / t.ph) * dirs_h;
+        const int wv = ((best + t.pv - 1) / t.pv) * dirs_v, wh = ((best + t.ph - 1) / t.ph) * dirs_h * t.parts;
         t.nwaves = wv > wh ? wv : wh;
         if (t.nwaves < 1) t.nwaves = 1;
     }
@@ -548,16 +720,16 @@ hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s) {
     if (!t.ok) return hipErrorInvalidValue;
     TileArgs a;
     a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.lplh = t.lplh; a.ph = t.ph;
-    a.nwaves = t.nwaves;
+    a.nwaves = t.nwaves; a.parts = t.parts;
     const bool save = p.hs != nullptr;
     if (dtype == 0) {
+        if (t.hv == H_SPLIT) return launch_cfg<float, 2, 0, 32, false, EXP_PF>(a, t, save, s);
         if (t.hv == H_ROW) return launch_cfg<float, 2, 1, 28, false, EXP_PF>(a, t, save, s);
         if (t.hv == H_SECTOR) return launch_cfg<float, 2, 2, 16, false, EXP_PF>(a, t, save, s);
         return launch_cfg<float, 2, 2, 4, true, EXP_PF>(a, t, save, s);
     }
+    if (t.hv == H_SPLIT) return launch_cfg<bf16_t, 2, 0, 64, false, EXP_PF>(a, t, save, s);
     if (t.hv == H_ROW) return launch_cfg<bf16_t, 2, 1, 56, false, EXP_PF>(a, t, save, s);
-    if (t.hv == H_SECTOR && t.vv == 8) return launch_cfg<bf16_t, 8, 2, 32, false, 4>(a, t, save, s);
-    if (t.hv == H_SECTOR && t.vv == 4) return launch_cfg<bf16_t, 4, 2, 32, false, EXP_PF>(a, t, save, s);
     if (t.hv == H_SECTOR) return launch_cfg<bf16_t, 2, 2, 32, false, EXP_PF>(a, t, save, s);
     return launch_cfg<bf16_t, 2, 2, 8, true, EXP_PF>(a, t, save, s);
 }

@@ -47,6 +47,8 @@ SHAPES = [  # B, C, H, W, G
     (2, 6, 9, 13, 3), (1, 4, 33, 70, 2), (1, 8, 65, 31, 8), (2, 4, 130, 67, 1),
     (1, 2, 1, 37, 1), (1, 2, 37, 1, 2), (1, 1, 1, 1, 1), (1, 3, 300, 5, 3), (1, 2, 5, 300, 1),
     (3, 5, 2, 2, 5), (1, 2, 64, 64, 1), (1, 2, 63, 65, 2),
+    # lines longer than one wave at one row per lane: rows split over 2, 3, 4 waves (even and ragged parts)
+    (1, 4, 128, 64, 2), (1, 2, 192, 128, 1), (1, 2, 256, 64, 2), (2, 3, 96, 64, 1), (1, 2, 130, 64, 1),
 ]
 
 

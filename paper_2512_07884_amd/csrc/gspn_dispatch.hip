@@ -5,14 +5,18 @@
 namespace gspn {
 
 enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1 };
-enum BwdPlan { BWD_GENERIC = 0 };
+enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1 };
 
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
     if (f && f[0] == '1') return FWD_GENERIC;
     return fwd_tile_applicable(p, dtype) ? FWD_TILE : FWD_GENERIC;
 }
-static BwdPlan choose_bwd(const BwdParams&, int) { return BWD_GENERIC; }
+static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
+    const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
+    if (f && f[0] == '1') return BWD_GENERIC;
+    return bwd_tile_applicable(p, dtype) ? BWD_TILE : BWD_GENERIC;
+}
 
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {
     switch (choose_fwd(p, dtype)) {
@@ -23,6 +27,7 @@ hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {
 
 hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s) {
     switch (choose_bwd(p, dtype)) {
+        case BWD_TILE: return launch_bwd_tile(p, dtype, s);
         default: return launch_bwd_generic(p, dtype, s);
     }
 }
@@ -36,6 +41,7 @@ const char* fwd_plan_name(const FwdParams& p, int dtype) {
 
 const char* bwd_plan_name(const BwdParams& p, int dtype) {
     switch (choose_bwd(p, dtype)) {
+        case BWD_TILE: return "tile";
         default: return "generic";
     }
 }

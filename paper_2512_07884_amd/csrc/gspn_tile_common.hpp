@@ -1,0 +1,80 @@
+// Device helpers shared by the register-resident ("tile") scan kernels for gfx950:
+// buffer-addressed vector loads/stores, storage <-> fp32 element access, whole-wave DPP shifts and
+// the LDS-only workgroup barrier.
+#pragma once
+#include "gspn_common.hpp"
+
+namespace gspn {
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- buffer addressing: a tensor is reached through a buffer resource (uniform base in SGPRs),
+// a uniform byte offset (SGPR) and a per-lane byte offset (VGPR), so that stepping from line to
+// line costs scalar adds only.  Offsets stay below 2^31 (checked on the host).
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+template <int NB> __device__ __forceinline__ void ld_buf(rsrc_t rs, uint32_t voff, int soff, uint32_t* r) {
+    soff = __builtin_amdgcn_readfirstlane(soff);   // wave-uniform by construction: keep it in an SGPR
+    if constexpr (NB == 4) { r[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, 0); }
+    else if constexpr (NB == 8) { u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, 0); r[0] = v.x; r[1] = v.y; }
+    else {
+        static_assert(NB % 16 == 0, "vector width");
+#pragma unroll
+        for (int i = 0; i < NB / 16; ++i) {
+            u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * i, soff, 0);
+            r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+        }
+    }
+}
+template <int NB> __device__ __forceinline__ void st_buf(rsrc_t rs, uint32_t voff, int soff, const uint32_t* r) {
+    soff = __builtin_amdgcn_readfirstlane(soff);
+    if constexpr (NB == 4) { __builtin_amdgcn_raw_buffer_store_b32(r[0], rs, voff, soff, 0); }
+    else if constexpr (NB == 8) { u32x2 v = {r[0], r[1]}; __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, soff, 0); }
+    else {
+#pragma unroll
+        for (int i = 0; i < NB / 16; ++i) {
+            u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff + 16 * i, soff, 0);
+        }
+    }
+}
+template <int NB> __device__ __forceinline__ void st_raw(char* p, const uint32_t* r) {
+    if constexpr (NB == 4) { *(uint32_t*)p = r[0]; }
+    else { u32x2 v = {r[0], r[1]}; *(u32x2*)p = v; }
+}
+
+// element e of a packed register vector, widened to fp32 (e is a compile-time constant after unrolling)
+template <typename T> __device__ __forceinline__ float elem(const uint32_t* r, int e) {
+    if constexpr (sizeof(T) == 4) return __uint_as_float(r[e]);
+    else return (e & 1) ? __uint_as_float(r[e >> 1] & 0xffff0000u) : __uint_as_float(r[e >> 1] << 16);
+}
+// pack V fp32 values into storage registers (round to nearest even for bf16)
+template <typename T, int V> __device__ __forceinline__ void pack(const float* v, uint32_t* r) {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) r[i] = __float_as_uint(v[i]);
+    } else {
+        static_assert(V % 2 == 0, "bf16 vectors hold an even number of elements");
+#pragma unroll
+        for (int i = 0; i < V / 2; ++i)
+            r[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    }
+}
+
+// whole-wave shift by one lane; lanes without a source read 0
+__device__ __forceinline__ float from_lane_below(float v) {   // lane i <- lane i-1
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x138, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float from_lane_above(float v) {   // lane i <- lane i+1
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
+}
+
+// Workgroup barrier that orders LDS traffic only: the wave's own LDS operations are complete
+// before it arrives, and the compiler may not move memory operations across it.  Unlike
+// __syncthreads() it does not wait for the global loads in flight (the prefetch rings keep running).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+}  // namespace gspn

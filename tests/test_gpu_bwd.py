@@ -67,6 +67,51 @@ def check_bwd(cfg, mask=None):
 BWD_SHAPES = [(2, 6, 9, 13, 3), (1, 4, 33, 70, 2), (1, 8, 65, 31, 8), (1, 2, 1, 37, 1), (1, 2, 37, 1, 2),
               (1, 1, 1, 1, 1), (1, 4, 130, 20, 1), (2, 8, 28, 28, 8), (2, 96, 28, 28, 2)]
 
+# shapes the register-resident backward kernel takes: per-channel weights, a whole group per
+# workgroup, a group split over two workgroups (atomic gw), several rounds, ragged lane packing
+TILE_BWD_SHAPES = [(2, 8, 28, 28, 8), (2, 96, 28, 28, 2), (1, 16, 28, 28, 4), (1, 24, 28, 28, 1), (2, 8, 56, 56, 2),
+                   (1, 4, 56, 56, 4), (1, 12, 16, 32, 3), (1, 8, 64, 128, 2), (3, 32, 2, 4, 32), (1, 24, 16, 40, 2)]
+
+
+@pytest.mark.parametrize("shape", TILE_BWD_SHAPES)
+def test_backward_tile_kernel_shapes(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 0, 0) == "tile", shape
+    check_bwd(WL.ScanConfig("bwdtile", B, C, H, W, Gr, "f32", 15, 1.0, 29))
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 5, 10, 14])
+@pytest.mark.parametrize("G_", [8, 2])
+def test_backward_tile_kernel_direction_masks(mask, G_):
+    check_bwd(WL.ScanConfig("bwdtilemask", 2, 8, 28, 28, G_, "f32", mask, 1.0, 31))
+
+
+def test_backward_generic_kernel_on_tile_shapes(monkeypatch):
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
+    assert G.gspn_bwd_plan(2, 8, 28, 28, 2, 15, 0, 0) == "generic"
+    check_bwd(WL.ScanConfig("bwdgen", 2, 8, 28, 28, 2, "f32", 15, 1.0, 37))
+
+
+def test_backward_is_bitwise_repeatable_with_split_groups():
+    import torch
+    import paper_2512_07884_amd as G
+    cfg = WL.ScanConfig("bwdrep", 2, 96, 28, 28, 2, "f32", 15, 1.0, 41)     # 48 channels per group: two workgroups per group
+    inp = WL.make_inputs(cfg)
+    dev = {k: to_device(v, "f32") for k, v in inp.items()}
+    hs = torch.empty_like(dev["lam"]); y = torch.empty_like(dev["x"])
+    G.gspn_scan_fwd(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, G=cfg.G)
+    outs = []
+    for rep in range(3):
+        gx = torch.full_like(dev["x"], float("nan")); gw = torch.full_like(dev["w"], float("nan"))
+        gl = torch.full_like(dev["lam"], float("nan")); gu = torch.full_like(dev["lam"], float("nan"))
+        G.gspn_scan_bwd(dev["gy"], dev["x"], dev["w"], dev["lam"], dev["u"], hs, gx, gw, gl, gu, G=cfg.G)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy().copy() for t in (gx, gw, gl, gu)])
+    for k in range(4):
+        assert np.array_equal(outs[0][k], outs[1][k]) and np.array_equal(outs[0][k], outs[2][k])
+
 
 @pytest.mark.parametrize("shape", BWD_SHAPES)
 def test_backward_fp32_shapes(shape):

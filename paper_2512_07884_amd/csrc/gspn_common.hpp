@@ -58,6 +58,8 @@ hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_tile_applicable(const FwdParams& p, int dtype);
+hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s);
+bool fwd_stream_applicable(const FwdParams& p, int dtype);
 hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s);
 bool bwd_tile_applicable(const BwdParams& p, int dtype);
 

@@ -4,13 +4,14 @@
 
 namespace gspn {
 
-enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1 };
+enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1, FWD_STREAM = 2 };
 enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1 };
 
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
     if (f && f[0] == '1') return FWD_GENERIC;
-    return fwd_tile_applicable(p, dtype) ? FWD_TILE : FWD_GENERIC;
+    if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
+    return fwd_stream_applicable(p, dtype) ? FWD_STREAM : FWD_GENERIC;
 }
 static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
     const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
@@ -21,6 +22,7 @@ static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {
     switch (choose_fwd(p, dtype)) {
         case FWD_TILE: return launch_fwd_tile(p, dtype, s);
+        case FWD_STREAM: return launch_fwd_stream(p, dtype, s);
         default: return launch_fwd_generic(p, dtype, s);
     }
 }
@@ -35,6 +37,7 @@ hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s) {
 const char* fwd_plan_name(const FwdParams& p, int dtype) {
     switch (choose_fwd(p, dtype)) {
         case FWD_TILE: return "tile";
+        case FWD_STREAM: return "stream";
         default: return "generic";
     }
 }

@@ -77,4 +77,29 @@ __device__ __forceinline__ float from_lane_above(float v) {   // lane i <- lane 
 // __syncthreads() it does not wait for the global loads in flight (the prefetch rings keep running).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// One line of Eq. 1 for the lane's V positions.  `first`/`last`: the lane holds the first/last
+// positions of its line, whose outer neighbour does not exist: both the neighbour value and its
+// weight are forced to 0 so that nothing stored for it (NaN, Inf) can leak in.
+template <int V>
+__device__ __forceinline__ void line_update(float (&h)[V], const float (&a)[V], const float (&w0)[V],
+                                            const float (&w1)[V], const float (&w2)[V], bool first, bool last) {
+    float lin = from_lane_below(h[V - 1]);
+    float rin = from_lane_above(h[0]);
+    lin = first ? 0.f : lin;
+    rin = last ? 0.f : rin;
+    const float wl = first ? 0.f : w0[0];
+    const float wr = last ? 0.f : w2[V - 1];
+    float hn[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float l = v == 0 ? lin : h[v - 1];
+        const float r = v == V - 1 ? rin : h[v + 1];
+        const float c0 = v == 0 ? wl : w0[v];
+        const float c2 = v == V - 1 ? wr : w2[v];
+        hn[v] = fmaf(c0, l, fmaf(w1[v], h[v], fmaf(c2, r, a[v])));
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) h[v] = hn[v];
+}
+
 }  // namespace gspn

@@ -49,6 +49,8 @@ SHAPES = [  # B, C, H, W, G
     (3, 5, 2, 2, 5), (1, 2, 64, 64, 1), (1, 2, 63, 65, 2),
     # lines longer than one wave at one row per lane: rows split over 2, 3, 4 waves (even and ragged parts)
     (1, 4, 128, 64, 2), (1, 2, 192, 128, 1), (1, 2, 256, 64, 2), (2, 3, 96, 64, 1), (1, 2, 130, 64, 1),
+    # maps too large for an on-chip output tile: output accumulated in global memory
+    (1, 2, 256, 256, 1), (1, 3, 192, 512, 3), (1, 2, 64, 1024, 1), (2, 2, 320, 256, 2),
 ]
 
 
@@ -57,6 +59,7 @@ SHAPES = [  # B, C, H, W, G
 def test_ragged_shapes_all_directions(shape, dtype):
     B, C, H, W, G = shape
     check_case(WL.ScanConfig("ragged", B, C, H, W, G, dtype, 15, 1.0, 7))
+    check_case(WL.ScanConfig("ragged", B, C, H, W, G, dtype, 15, 1.0, 8), save_h=False)
 
 
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 5, 10, 7, 14])
@@ -82,6 +85,23 @@ SHRUNK = [
 def test_benchmark_shapes_with_fewer_channels(cfg):
     check_case(cfg)
     check_case(cfg, save_h=False)
+
+
+def test_kernel_families_by_shape():
+    import paper_2512_07884_amd as G
+    assert G.gspn_fwd_plan(2, 1024, 128, 128, 16, 15, 1, 0, False) == "tile"
+    assert G.gspn_fwd_plan(64, 96, 56, 56, 8, 15, 1, 0, False) == "tile"
+    assert G.gspn_fwd_plan(1, 512, 512, 512, 16, 15, 1, 0, False) == "stream"
+    assert G.gspn_fwd_plan(1, 512, 256, 1024, 16, 15, 1, 0, False) == "stream"
+    assert G.gspn_fwd_plan(1, 2, 256, 256, 1, 15, 0, 0, False) == "stream"
+    assert G.gspn_fwd_plan(1, 2, 256, 256, 1, 15, 0, 0, True) == "generic"      # saving h is not on the stream path
+    assert G.gspn_fwd_plan(1, 2, 130, 67, 1, 15, 0, 0, False) == "generic"
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 6, 9, 14])
+def test_direction_masks_on_large_maps(mask):
+    check_case(WL.ScanConfig("maskbig", 1, 2, 256, 256, 1, "bf16", mask, 1.0, 15), save_h=False)
+    check_case(WL.ScanConfig("maskbig", 1, 2, 128, 256, 2, "f32", mask, 1.0, 16), save_h=False)
 
 
 def test_weights_that_are_never_read_may_hold_anything():

@@ -371,6 +371,7 @@ struct HorizontalSplitPass {
             // edge state the neighbouring parts published in the previous step
             const float pu = mb_up[par ^ 1];
             const float pd = mb_dn[par ^ 1];
+            const float yold = trow[col0 + e];               // read early: one LDS round trip per step, not three
             const bool start = (c == 0) && (k == 0);
             float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
             if (k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
@@ -381,8 +382,8 @@ struct HorizontalSplitPass {
             w0 = img_first ? 0.f : w0;
             w2 = img_last ? 0.f : w2;
             h = fmaf(w0, up, fmaf(w1, h, fmaf(w2, dn, av)));
-            trow[col0 + e] += elem<T>(bu, e) * h;
             if (edge) mb_out[par] = h;
+            trow[col0 + e] = fmaf(elem<T>(bu, e), h, yold);
             if constexpr (SAVE) hs[e] = h;
             lds_barrier();
         }
@@ -525,9 +526,7 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
 // ---------------------------------------------------------------------------
 // host side: applicability, tiling choice, launch
 // ---------------------------------------------------------------------------
-#ifndef EXP_PF
-#define EXP_PF 8
-#endif
+static constexpr int TILE_PF = 8;     // lines kept in flight per wave in the vertical phases
 static constexpr int LDS_BUDGET = 160 * 1024;
 
 // Horizontal-phase variants: rows per lane, scan steps per burst, double buffered or not.
@@ -627,15 +626,15 @@ hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s) {
     a.nwaves = t.nwaves; a.parts = t.parts;
     const bool save = p.hs != nullptr;
     if (dtype == 0) {
-        if (t.hv == H_SPLIT) return launch_cfg<float, 2, 0, 32, false, EXP_PF>(a, t, save, s);
-        if (t.hv == H_ROW) return launch_cfg<float, 2, 1, 28, false, EXP_PF>(a, t, save, s);
-        if (t.hv == H_SECTOR) return launch_cfg<float, 2, 2, 16, false, EXP_PF>(a, t, save, s);
-        return launch_cfg<float, 2, 2, 4, true, EXP_PF>(a, t, save, s);
+        if (t.hv == H_SPLIT) return launch_cfg<float, 2, 0, 32, false, TILE_PF>(a, t, save, s);
+        if (t.hv == H_ROW) return launch_cfg<float, 2, 1, 28, false, TILE_PF>(a, t, save, s);
+        if (t.hv == H_SECTOR) return launch_cfg<float, 2, 2, 16, false, TILE_PF>(a, t, save, s);
+        return launch_cfg<float, 2, 2, 4, true, TILE_PF>(a, t, save, s);
     }
-    if (t.hv == H_SPLIT) return launch_cfg<bf16_t, 2, 0, 64, false, EXP_PF>(a, t, save, s);
-    if (t.hv == H_ROW) return launch_cfg<bf16_t, 2, 1, 56, false, EXP_PF>(a, t, save, s);
-    if (t.hv == H_SECTOR) return launch_cfg<bf16_t, 2, 2, 32, false, EXP_PF>(a, t, save, s);
-    return launch_cfg<bf16_t, 2, 2, 8, true, EXP_PF>(a, t, save, s);
+    if (t.hv == H_SPLIT) return launch_cfg<bf16_t, 2, 0, 64, false, TILE_PF>(a, t, save, s);
+    if (t.hv == H_ROW) return launch_cfg<bf16_t, 2, 1, 56, false, TILE_PF>(a, t, save, s);
+    if (t.hv == H_SECTOR) return launch_cfg<bf16_t, 2, 2, 32, false, TILE_PF>(a, t, save, s);
+    return launch_cfg<bf16_t, 2, 2, 8, true, TILE_PF>(a, t, save, s);
 }
 
 }  // namespace gspn

@@ -197,6 +197,18 @@ def load_traffic(workload: str):
         return None
 
 
+def copy_calibration(n_bytes: int = 1 << 30, reps: int = 5):
+    """Plain copies of a known size: each must read and write exactly n_bytes, which
+    fixes the unit in which the profiler's FETCH_SIZE / WRITE_SIZE counters report."""
+    import torch
+    src = torch.ones(n_bytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration_bytes": n_bytes, "copies": reps}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -205,12 +217,17 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in gpurun_out/)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain 1 GiB device-to-device copies (known traffic, for scaling profiler counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build measures one GPU; the scan shards over (batch, group) with no "
               "exchange, and no multi-GPU figure is produced. Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    if a.copy_calibration:
+        copy_calibration()
+        return
     from paper_2512_07884_amd import workloads as WL
     cfg = WL.CONFIGS[a.workload]
     # the CPU legs fork worker processes: run them before this process touches the GPU

@@ -218,7 +218,8 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
     const int H = p.H, W = p.W;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int b = blockIdx.x / p.C, c = blockIdx.x - b * p.C;
+    const unsigned item = xcd_contiguous_item(blockIdx.x, gridDim.x);
+    const int b = item / p.C, c = item - b * p.C;
     bool wrote = false;          // does y already hold a partial sum?  (uniform over the workgroup)
 
     // ---- vertical pair (waves 0 and 1)

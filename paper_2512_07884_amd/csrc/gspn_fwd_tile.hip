@@ -415,8 +415,9 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int blocks_per_image = p.C / a.K;
-    const int b = blockIdx.x / blocks_per_image;
-    const int c_first = (blockIdx.x - b * blocks_per_image) * a.K;
+    const unsigned item = xcd_contiguous_item(blockIdx.x, gridDim.x);
+    const int b = item / blocks_per_image;
+    const int c_first = (item - b * blocks_per_image) * a.K;
 
     // tile, followed (row-split horizontal phases only) by the mailbox: both start at zero
     const int tile_floats = a.K * H * a.pitch;

@@ -72,6 +72,18 @@ __device__ __forceinline__ float from_lane_above(float v) {   // lane i <- lane 
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xf, 0xf, true));
 }
 
+// Workgroup index -> work item, for kernels whose neighbouring items read the same weight planes.
+// The dispatcher deals workgroups to the chip's 8 XCDs (each with an L2 of its own) round-robin by
+// index, so items i, i+1, ... would land in 8 different L2s and every L2 would fetch every group's
+// weights.  This bijection on [0, n) gives XCD k the contiguous range of items
+// [k*n/8 ..), so the channels of one group (Sec. 3.2: they share w) meet in one L2.
+__device__ __forceinline__ unsigned xcd_contiguous_item(unsigned wg, unsigned n) {
+    constexpr unsigned XCDS = 8;
+    const unsigned k = wg % XCDS, j = wg / XCDS;
+    const unsigned q = n / XCDS, r = n % XCDS;
+    return k * q + (k < r ? k : r) + j;
+}
+
 // Workgroup barrier that orders LDS traffic only: the wave's own LDS operations are complete
 // before it arrives, and the compiler may not move memory operations across it.  Unlike
 // __syncthreads() it does not wait for the global loads in flight (the prefetch rings keep running).

@@ -1,0 +1,337 @@
+// Backward GSPN scan for very small feature maps (fp32 storage, H, W <= 32: the 28x28 training
+// stage): every tensor crosses the memory system exactly once, as whole planes.
+//
+// The paper gives timings but no algorithm for the backward pass (Sec. 5.1); this is the chain rule
+// on Eq. 1-2 (Sec. 3.2) with the shared weights of Sec. 4.2.  Per direction, with e_s = dL/dh_s and
+// s the scan step:
+//     e_s[j]  = u_s[j]*gy_s[j] + w2_{s+1}[j-1]*e_{s+1}[j-1] + w1_{s+1}[j]*e_{s+1}[j] + w0_{s+1}[j+1]*e_{s+1}[j+1]
+//     gu_s = gy_s*h_s,  glam_s = x_s*e_s,  gx_s += lam_s*e_s (summed over directions)
+//     gw_s[k][j] = sum over the channels of the group of e_s[j] * h_{s-1}[j+k-1]      (0 for s = 0)
+//
+// A plane of at most 32x32 fp32 is 4 KB, so a wave can hold a whole directional sweep of two
+// channels in registers: lane = position on the line (lanes 0-31 one channel, 32-63 the next),
+// register index = scan step.  Planes are read from global memory as flat, fully coalesced 16 B
+// per lane copies, dropped into a per-wave LDS buffer and read back "transposed" (position per
+// lane, step per register) with an address pattern that encodes the direction; results that are
+// elementwise in the plane (gu = gy*h, glam = x*e, gx += lam*e) are formed in the flat layout, so
+// the only transposes are u*gy, w0, w1, w2 and h on the way in and e on the way out.  The sweep
+// itself is 100% register + DPP work, unrolled over the scan steps.
+//
+// gw: a wave keeps 3 x steps accumulators in registers while it walks the channel pairs it owns
+// (directions are the outer loop), the two halves of the wave and then the waves of the workgroup
+// are summed through LDS in a fixed order, and the group's gw leaves the workgroup once per
+// direction: stored when the workgroup holds the whole weight group, added atomically onto a
+// zero-filled gw when the group is split over two workgroups (two addends commute: still bitwise
+// reproducible).  With one channel per group (per-channel weights of Eq. 1) every sweep writes
+// its own gw.  gx is merged over the directions in an LDS tile owned pair-wise by single waves.
+#include "gspn_tile_common.hpp"
+#include <stdlib.h>
+
+namespace gspn {
+
+typedef float f32x4a __attribute__((ext_vector_type(4), may_alias));
+typedef float f32a __attribute__((may_alias));
+
+struct BwdPlaneArgs {
+    BwdParams p;
+    int K;             // channels per workgroup (even)
+    int shared_group;  // 1: the K channels share one weight group; 0: one weight group per channel
+    int gsplit;        // workgroups per weight group; 2: gw is accumulated atomically
+    int nwaves;
+};
+
+template <int SMAX>
+__global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
+    constexpr int NCH = (2 * SMAX * SMAX / 4 + 63) / 64;      // 16 B chunks per lane for a pair of planes
+    extern __shared__ float lds[];
+    const BwdParams& p = a.p;
+    const int H = p.H, W = p.W, HW = H * W;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int half = lane >> 5, i = lane & 31;
+    const int wgs_per_image = p.C / a.K;
+    const int b = blockIdx.x / wgs_per_image;
+    const int c_first = (blockIdx.x - b * wgs_per_image) * a.K;
+    const int pairs = a.K / 2;
+    const int n16p = HW / 4, n16 = 2 * n16p;                   // 16 B chunks per plane / per pair
+    const size_t planes = (size_t)p.B * p.C, groups = (size_t)p.B * p.G;
+    const bool shared_group = a.shared_group != 0;
+    const bool atomic = a.gsplit > 1;
+
+    float* tile = lds;                                         // [K][HW] merged gx
+    float* wave_bufs = lds + a.K * HW;                         // per wave: X (two planes), H (two planes)
+    f32a* bufX = wave_bufs + wave * 4 * HW;
+    f32a* bufH = bufX + 2 * HW;
+
+    // chunk q = k*64 + lane of a contiguous pair of planes covers floats [4q, 4q+4)
+    bool vq[NCH];        // chunk inside the pair
+    bool vq1[NCH];       // chunk inside the first plane
+    int wq[NCH];         // float offset of the chunk in a weight tensor (per-channel groups: planes 3*HW apart)
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+        const int q = k * 64 + lane;
+        vq[k] = q < n16;
+        vq1[k] = q < n16p;
+        wq[k] = (shared_group || q < n16p) ? 4 * q : 3 * HW + 4 * (q - n16p);
+    }
+    auto load_pair = [&](const float* base, f32x4a (&st)[NCH]) {
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            f32x4a v = {0.f, 0.f, 0.f, 0.f};
+            if (vq[k]) v = *(const f32x4a*)(base + 4 * (k * 64 + lane));
+            st[k] = v;
+        }
+    };
+    auto load_w = [&](const float* base, f32x4a (&st)[NCH]) {
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            f32x4a v = {0.f, 0.f, 0.f, 0.f};
+            if (shared_group ? vq1[k] : vq[k]) v = *(const f32x4a*)(base + wq[k]);
+            st[k] = v;
+        }
+    };
+    auto to_lds = [&](f32a* buf, const f32x4a (&st)[NCH], bool one_plane) {
+#pragma unroll
+        for (int k = 0; k < NCH; ++k)
+            if (one_plane ? vq1[k] : vq[k]) *(f32x4a*)(buf + 4 * (k * 64 + lane)) = st[k];
+    };
+
+    // the wave's pairs start with gx = 0
+    for (int pair = wave; pair < pairs; pair += a.nwaves) {
+        f32a* tp = tile + (size_t)2 * pair * HW;
+        const f32x4a z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < NCH; ++k)
+            if (vq[k]) *(f32x4a*)(tp + 4 * (k * 64 + lane)) = z;
+    }
+
+    for (int d = 0; d < 4; ++d) {
+        if (!((p.mask >> d) & 1u)) continue;
+        // element (position j, scan step s) of a plane sits at float offset j*ps + s0 + s*ss
+        const bool vert = d < 2, rev = (d & 1) != 0;
+        const int S = vert ? H : W, L = vert ? W : H;
+        const int ps = vert ? 1 : W;
+        const int ss = vert ? (rev ? -W : W) : (rev ? -1 : 1);
+        const int s0 = vert ? (rev ? (H - 1) * W : 0) : (rev ? W - 1 : 0);
+        const bool active = i < L;
+        const int ic = active ? i : L - 1;
+        const bool first = i == 0, last = i == L - 1;
+        const int tb = half * HW + ic * ps + s0;               // this lane's element at scan step 0
+        const int tbw = shared_group ? ic * ps + s0 : tb;      // same, in a weight plane
+        const size_t out_c = (size_t)d * planes * HW, out_w = (size_t)d * groups * 3 * HW;
+        const size_t slot_c = p.shared ? 0 : out_c, slot_w = p.shared ? 0 : out_w;
+
+        float gw0[SMAX], gw1[SMAX], gw2[SMAX];
+#pragma unroll
+        for (int s = 0; s < SMAX; ++s) { gw0[s] = 0.f; gw1[s] = 0.f; gw2[s] = 0.f; }
+
+        for (int pair = wave; pair < pairs; pair += a.nwaves) {
+            const int c0 = c_first + 2 * pair;
+            const size_t pc = ((size_t)b * p.C + c0) * HW;
+            const int g = c0 / p.cpg;
+            const size_t wg = ((size_t)b * p.G + g) * 3 * HW;
+            const float* gyp = (const float*)p.gy + pc;
+            const float* xp = (const float*)p.x + pc;
+            const float* lp = (const float*)p.lam + slot_c + pc;
+            const float* up = (const float*)p.u + slot_c + pc;
+            const float* hp = (const float*)p.hs + out_c + pc;
+            const float* wp = (const float*)p.w + slot_w + wg;
+            float* glp = (float*)p.glam + out_c + pc;
+            float* gup = (float*)p.gu + out_c + pc;
+            float* gwp = (float*)p.gw + out_w + wg;
+
+            f32x4a sa[NCH], sb[NCH], sc[NCH];
+            load_pair(gyp, sa);
+            load_pair(hp, sb);
+            load_pair(up, sc);
+            // gu = gy*h in the flat layout; h goes to LDS for the weight gradients
+#pragma unroll
+            for (int k = 0; k < NCH; ++k)
+                if (vq[k]) *(f32x4a*)(gup + 4 * (k * 64 + lane)) = sa[k] * sb[k];
+            to_lds(bufH, sb, false);
+            load_w(wp, sb);                                     // w0
+            // seed u*gy, flat -> per-lane line positions
+#pragma unroll
+            for (int k = 0; k < NCH; ++k) sc[k] = sc[k] * sa[k];
+            to_lds(bufX, sc, false);
+            load_w(wp + HW, sa);                                // w1
+            float e[SMAX];
+#pragma unroll
+            for (int s = 0; s < SMAX; ++s) e[s] = (s < S && active) ? bufX[tb + s * ss] : 0.f;
+            load_w(wp + 2 * HW, sc);                            // w2
+            float w0r[SMAX], w1r[SMAX], w2r[SMAX];
+            to_lds(bufX, sb, shared_group);
+#pragma unroll
+            for (int s = 0; s < SMAX; ++s) w0r[s] = s < S ? bufX[tbw + s * ss] : 0.f;
+            load_pair(xp, sb);
+            to_lds(bufX, sa, shared_group);
+#pragma unroll
+            for (int s = 0; s < SMAX; ++s) w1r[s] = s < S ? bufX[tbw + s * ss] : 0.f;
+            load_pair(lp, sa);
+            to_lds(bufX, sc, shared_group);
+#pragma unroll
+            for (int s = 0; s < SMAX; ++s) w2r[s] = s < S ? bufX[tbw + s * ss] : 0.f;
+
+            // the sweep, against the scan order; the weights of scan step 0 are never used
+#pragma unroll
+            for (int s = SMAX - 2; s >= 0; --s) {
+                if (s + 1 < S) {
+                    const float en = e[s + 1];
+                    const float q0 = w0r[s + 1] * en, q1 = w1r[s + 1] * en, q2 = w2r[s + 1] * en;
+                    float lin = from_lane_below(q2), rin = from_lane_above(q0);
+                    lin = first ? 0.f : lin;                    // no neighbour outside the line, whatever is stored
+                    rin = last ? 0.f : rin;
+                    const float v = e[s] + lin + q1 + rin;
+                    e[s] = active ? v : 0.f;
+                }
+            }
+            // weight gradients: e_s[j] * h_{s-1}[j-1, j, j+1]
+#pragma unroll
+            for (int s = 1; s < SMAX; ++s) {
+                if (s < S) {
+                    const float hm = bufH[tb + (s - 1) * ss];
+                    float hl = from_lane_below(hm), hr = from_lane_above(hm);
+                    hl = first ? 0.f : hl;
+                    hr = last ? 0.f : hr;
+                    gw0[s] = fmaf(e[s], hl, gw0[s]);
+                    gw1[s] = fmaf(e[s], hm, gw1[s]);
+                    gw2[s] = fmaf(e[s], hr, gw2[s]);
+                }
+            }
+            // e back to the flat layout: glam = x*e, gx += lam*e
+#pragma unroll
+            for (int s = 0; s < SMAX; ++s)
+                if (s < S && active) bufX[tb + s * ss] = e[s];
+            f32a* tp = tile + (size_t)2 * pair * HW;
+#pragma unroll
+            for (int k = 0; k < NCH; ++k) {
+                if (vq[k]) {
+                    const int o = 4 * (k * 64 + lane);
+                    const f32x4a ef = *(const f32x4a*)(bufX + o);
+                    *(f32x4a*)(glp + o) = sb[k] * ef;
+                    *(f32x4a*)(tp + o) = *(const f32x4a*)(tp + o) + sa[k] * ef;
+                }
+            }
+            if (!shared_group) {
+                // one group per channel: this sweep's gw is complete
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+#pragma unroll
+                    for (int s = 0; s < SMAX; ++s) {
+                        const float v = t == 0 ? gw0[s] : (t == 1 ? gw1[s] : gw2[s]);
+                        if (s < S && active) bufX[tb + s * ss] = v;
+                    }
+#pragma unroll
+                    for (int k = 0; k < NCH; ++k)
+                        if (vq[k]) *(f32x4a*)(gwp + t * HW + wq[k]) = *(const f32x4a*)(bufX + 4 * (k * 64 + lane));
+                }
+#pragma unroll
+                for (int s = 0; s < SMAX; ++s) { gw0[s] = 0.f; gw1[s] = 0.f; gw2[s] = 0.f; }
+            }
+        }
+
+        if (shared_group) {
+            // sum over the two halves of each wave, then over the waves (fixed order), one tap at a time
+            const int g = c_first / p.cpg;
+            float* gwp = (float*)p.gw + out_w + ((size_t)b * p.G + g) * 3 * HW;
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+#pragma unroll
+                for (int s = 0; s < SMAX; ++s) {
+                    float v = t == 0 ? gw0[s] : (t == 1 ? gw1[s] : gw2[s]);
+                    v += __int_as_float(__builtin_amdgcn_ds_bpermute(((lane ^ 32) & 63) << 2, __float_as_int(v)));
+                    if (s < S && active && half == 0) bufX[ic * ps + s0 + s * ss] = v;
+                }
+                lds_barrier();
+                for (int q = threadIdx.x; q < n16p; q += blockDim.x) {
+                    f32x4a acc = *(const f32x4a*)(wave_bufs + 4 * q);
+                    for (int wv = 1; wv < a.nwaves; ++wv) acc += *(const f32x4a*)(wave_bufs + wv * 4 * HW + 4 * q);
+                    float* dst = gwp + t * HW + 4 * q;
+                    if (atomic) {
+                        atomicAdd(dst, acc.x); atomicAdd(dst + 1, acc.y); atomicAdd(dst + 2, acc.z); atomicAdd(dst + 3, acc.w);
+                    } else {
+                        *(f32x4a*)dst = acc;
+                    }
+                }
+                lds_barrier();
+            }
+        }
+    }
+
+    // merged gx of the wave's pairs: written once, coalesced
+    for (int pair = wave; pair < pairs; pair += a.nwaves) {
+        const f32a* tp = tile + (size_t)2 * pair * HW;
+        float* gxp = (float*)p.gx + ((size_t)b * p.C + c_first + 2 * pair) * HW;
+#pragma unroll
+        for (int k = 0; k < NCH; ++k)
+            if (vq[k]) *(f32x4a*)(gxp + 4 * (k * 64 + lane)) = *(const f32x4a*)(tp + 4 * (k * 64 + lane));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static constexpr int PLANE_LDS_BUDGET = 160 * 1024;
+
+struct PlanePlan { bool ok; int K, shared_group, gsplit, nwaves, smax; size_t lds; };
+
+static size_t plane_lds(int K, int nwaves, int HW) { return (size_t)(K + 4 * nwaves) * HW * sizeof(float); }
+
+static PlanePlan plan_plane(const BwdParams& p, int dtype) {
+    PlanePlan t = {};
+    if (dtype != 0) return t;                                   // fp32 storage only
+    if (p.H < 2 || p.W < 2 || p.H > 32 || p.W > 32 || (p.H * p.W) % 4) return t;
+    const int HW = p.H * p.W;
+    if (p.cpg == 1) {
+        t.shared_group = 0; t.gsplit = 1;
+        t.K = (p.C % 8 == 0) ? 8 : ((p.C % 4 == 0) ? 4 : 2);
+        if (p.C % t.K) return t;
+    } else {
+        if (p.cpg % 2) return t;
+        t.shared_group = 1; t.gsplit = 1; t.K = p.cpg;
+        const int nw = t.K / 2 < 4 ? t.K / 2 : 4;
+        const bool few = (size_t)p.B * p.G < 256;               // fewer workgroups than compute units
+        if ((plane_lds(t.K, nw, HW) > (size_t)PLANE_LDS_BUDGET || few) && t.K % 4 == 0) { t.K /= 2; t.gsplit = 2; }
+    }
+    t.nwaves = t.K / 2 < 4 ? t.K / 2 : 4;
+    t.lds = plane_lds(t.K, t.nwaves, HW);
+    if (t.lds > (size_t)PLANE_LDS_BUDGET) return t;
+    if ((size_t)p.B * (p.C / t.K) > 0x7fffffffull) return t;
+    const int m = p.H > p.W ? p.H : p.W;
+    t.smax = m <= 16 ? 16 : (m <= 28 ? 28 : 32);
+    t.ok = true;
+    return t;
+}
+
+bool bwd_plane_applicable(const BwdParams& p, int dtype) { return plan_plane(p, dtype).ok; }
+
+template <int SMAX>
+static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
+    auto k = bwd_plane_kernel<SMAX>;
+    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, PLANE_LDS_BUDGET);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
+    hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
+    const PlanePlan t = plan_plane(p, dtype);
+    if (!t.ok) return hipErrorInvalidValue;
+    BwdPlaneArgs a;
+    a.p = p; a.K = t.K; a.shared_group = t.shared_group; a.gsplit = t.gsplit; a.nwaves = t.nwaves;
+    if (t.gsplit > 1) {
+        // gw of the requested directions is accumulated atomically: clear it first, on the same stream
+        const size_t per_dir = (size_t)p.B * p.G * 3 * p.H * p.W * sizeof(float);
+        for (int d = 0; d < 4; ++d) {
+            if (!((p.mask >> d) & 1u)) continue;
+            hipError_t e = launch_zero_fill((char*)p.gw + d * per_dir, per_dir, s);
+            if (e != hipSuccess) return e;
+        }
+    }
+    if (t.smax == 16) return launch_plane<16>(a, t, s);
+    if (t.smax == 28) return launch_plane<28>(a, t, s);
+    return launch_plane<32>(a, t, s);
+}
+
+}  // namespace gspn

@@ -481,6 +481,11 @@ __global__ void __launch_bounds__(256) zero_fill_kernel(uint32_t* p, size_t n16)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) q[i] = z;
 }
 
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s) {
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, s, (uint32_t*)p, bytes / 16);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -544,8 +549,8 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
         const size_t per_dir = (size_t)p.B * p.G * 3 * p.H * p.W * sizeof(float);
         for (int d = 0; d < 4; ++d) {
             if (!((p.mask >> d) & 1u)) continue;
-            hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, s, (uint32_t*)((char*)p.gw + d * per_dir),
-                               per_dir / 16);
+            hipError_t e = launch_zero_fill((char*)p.gw + d * per_dir, per_dir, s);
+            if (e != hipSuccess) return e;
         }
     }
     const dim3 grid((unsigned)((size_t)p.B * (p.C / t.K))), block(64 * t.nwaves);

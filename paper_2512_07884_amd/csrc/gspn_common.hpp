@@ -62,6 +62,10 @@ hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_stream_applicable(const FwdParams& p, int dtype);
 hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s);
 bool bwd_tile_applicable(const BwdParams& p, int dtype);
+hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s);
+bool bwd_plane_applicable(const BwdParams& p, int dtype);
+// clears `bytes` (a multiple of 16) of device memory with a kernel on stream s (no memset node: capturable)
+hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s);
 
 // dispatch (gspn_dispatch.hip): picks the kernel family for the arguments
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);

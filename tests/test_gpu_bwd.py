@@ -67,10 +67,24 @@ def check_bwd(cfg, mask=None):
 BWD_SHAPES = [(2, 6, 9, 13, 3), (1, 4, 33, 70, 2), (1, 8, 65, 31, 8), (1, 2, 1, 37, 1), (1, 2, 37, 1, 2),
               (1, 1, 1, 1, 1), (1, 4, 130, 20, 1), (2, 8, 28, 28, 8), (2, 96, 28, 28, 2)]
 
-# shapes the register-resident backward kernel takes: per-channel weights, a whole group per
-# workgroup, a group split over two workgroups (atomic gw), several rounds, ragged lane packing
-TILE_BWD_SHAPES = [(2, 8, 28, 28, 8), (2, 96, 28, 28, 2), (1, 16, 28, 28, 4), (1, 24, 28, 28, 1), (2, 8, 56, 56, 2),
-                   (1, 4, 56, 56, 4), (1, 12, 16, 32, 3), (1, 8, 64, 128, 2), (3, 32, 2, 4, 32), (1, 24, 16, 40, 2)]
+# shapes the whole-plane backward kernel takes (H, W <= 32): per-channel weights with 8 / 4 / 2 channels
+# per workgroup, a whole group per workgroup, a group split over two workgroups (atomic gw), several
+# pairs per wave, one wave only, H != W, the 16 / 28 / 32 step variants
+PLANE_BWD_SHAPES = [(2, 8, 28, 28, 8), (2, 96, 28, 28, 2), (1, 16, 28, 28, 4), (1, 24, 28, 28, 1), (1, 12, 16, 32, 3),
+                    (3, 32, 2, 4, 32), (2, 4, 32, 32, 2), (1, 6, 12, 20, 3), (1, 8, 6, 10, 1), (1, 12, 28, 28, 12),
+                    (1, 6, 8, 8, 6), (1, 2, 28, 28, 1), (1, 40, 28, 20, 1), (300, 16, 4, 4, 2)]
+
+# shapes the line-by-line register-resident backward kernel takes: larger maps, odd group sizes
+TILE_BWD_SHAPES = [(2, 8, 56, 56, 2), (1, 4, 56, 56, 4), (1, 8, 64, 128, 2), (1, 24, 16, 40, 2), (2, 8, 40, 32, 8),
+                   (2, 8, 40, 32, 2)]
+
+
+@pytest.mark.parametrize("shape", PLANE_BWD_SHAPES)
+def test_backward_plane_kernel_shapes(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 0, 0) == "plane", shape
+    check_bwd(WL.ScanConfig("bwdplane", B, C, H, W, Gr, "f32", 15, 1.0, 29))
 
 
 @pytest.mark.parametrize("shape", TILE_BWD_SHAPES)
@@ -81,10 +95,23 @@ def test_backward_tile_kernel_shapes(shape):
     check_bwd(WL.ScanConfig("bwdtile", B, C, H, W, Gr, "f32", 15, 1.0, 29))
 
 
+@pytest.mark.parametrize("shape", [(2, 8, 28, 28, 8), (2, 96, 28, 28, 2), (1, 16, 28, 28, 4), (1, 12, 16, 32, 3),
+                                   (3, 32, 2, 4, 32)])
+def test_backward_tile_kernel_on_shapes_the_plane_kernel_normally_takes(shape, monkeypatch):
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+    B, C, H, W, Gr = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 0, 0) == "tile", shape
+    check_bwd(WL.ScanConfig("bwdtile2", B, C, H, W, Gr, "f32", 15, 1.0, 29))
+
+
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 5, 10, 14])
 @pytest.mark.parametrize("G_", [8, 2])
-def test_backward_tile_kernel_direction_masks(mask, G_):
-    check_bwd(WL.ScanConfig("bwdtilemask", 2, 8, 28, 28, G_, "f32", mask, 1.0, 31))
+@pytest.mark.parametrize("hw", [(28, 28), (40, 32)])
+def test_backward_fast_kernels_direction_masks(mask, G_, hw):
+    import paper_2512_07884_amd as G
+    assert G.gspn_bwd_plan(2, 8, hw[0], hw[1], G_, mask, 0, 0) == ("plane" if hw[0] <= 32 else "tile")
+    check_bwd(WL.ScanConfig("bwdmask2", 2, 8, hw[0], hw[1], G_, "f32", mask, 1.0, 31))
 
 
 def test_backward_generic_kernel_on_tile_shapes(monkeypatch):
@@ -94,9 +121,13 @@ def test_backward_generic_kernel_on_tile_shapes(monkeypatch):
     check_bwd(WL.ScanConfig("bwdgen", 2, 8, 28, 28, 2, "f32", 15, 1.0, 37))
 
 
-def test_backward_is_bitwise_repeatable_with_split_groups():
+@pytest.mark.parametrize("kernel", ["plane", "tile"])
+def test_backward_is_bitwise_repeatable_with_split_groups(kernel, monkeypatch):
     import torch
     import paper_2512_07884_amd as G
+    if kernel == "tile":
+        monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+    assert G.gspn_bwd_plan(2, 96, 28, 28, 2, 15, 0, 0) == kernel
     cfg = WL.ScanConfig("bwdrep", 2, 96, 28, 28, 2, "f32", 15, 1.0, 41)     # 48 channels per group: two workgroups per group
     inp = WL.make_inputs(cfg)
     dev = {k: to_device(v, "f32") for k, v in inp.items()}

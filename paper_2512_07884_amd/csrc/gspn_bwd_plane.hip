@@ -29,6 +29,7 @@
 
 namespace gspn {
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4a __attribute__((ext_vector_type(4), may_alias));
 typedef float f32a __attribute__((may_alias));
 
@@ -40,8 +41,8 @@ struct BwdPlaneArgs {
     int nwaves;
 };
 
-template <int SMAX>
-__global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
+template <int SMAX, bool SHARED>
+__global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPlaneArgs a) {
     constexpr int NCH = (2 * SMAX * SMAX / 4 + 63) / 64;      // 16 B chunks per lane for a pair of planes
     extern __shared__ float lds[];
     const BwdParams& p = a.p;
@@ -55,7 +56,7 @@ __global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
     const int pairs = a.K / 2;
     const int n16p = HW / 4, n16 = 2 * n16p;                   // 16 B chunks per plane / per pair
     const size_t planes = (size_t)p.B * p.C, groups = (size_t)p.B * p.G;
-    const bool shared_group = a.shared_group != 0;
+    constexpr bool shared_group = SHARED;
     const bool atomic = a.gsplit > 1;
 
     float* tile = lds;                                         // [K][HW] merged gx
@@ -74,23 +75,35 @@ __global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
         vq1[k] = q < n16p;
         wq[k] = (shared_group || q < n16p) ? 4 * q : 3 * HW + 4 * (q - n16p);
     }
-    auto load_pair = [&](const float* base, f32x4a (&st)[NCH]) {
+    // global memory is reached through buffer resources: uniform base, per-lane byte offset 16*lane,
+    // uniform chunk offset k*1024 -- no per-lane 64-bit addresses to keep in registers
+    const uint32_t voff = (uint32_t)lane * 16u;
+    auto ldg = [&](rsrc_t rs, uint32_t vo, int so) -> f32x4 {
+        return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0));
+    };
+    auto stg = [&](rsrc_t rs, uint32_t vo, int so, f32x4 v) {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, vo, so, 0);
+    };
+    auto load_pair = [&](const float* base, f32x4 (&st)[NCH]) {
+        const rsrc_t rs = make_rsrc(base);
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
-            f32x4a v = {0.f, 0.f, 0.f, 0.f};
-            if (vq[k]) v = *(const f32x4a*)(base + 4 * (k * 64 + lane));
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (vq[k]) v = ldg(rs, voff, k * 1024);
             st[k] = v;
         }
     };
-    auto load_w = [&](const float* base, f32x4a (&st)[NCH]) {
+    auto load_w = [&](const float* base, f32x4 (&st)[NCH]) {
+        const rsrc_t rs = make_rsrc(base);
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
-            f32x4a v = {0.f, 0.f, 0.f, 0.f};
-            if (shared_group ? vq1[k] : vq[k]) v = *(const f32x4a*)(base + wq[k]);
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (SHARED) { if (vq1[k]) v = ldg(rs, voff, k * 1024); }
+            else { if (vq[k]) v = ldg(rs, (uint32_t)wq[k] * 4u, 0); }
             st[k] = v;
         }
     };
-    auto to_lds = [&](f32a* buf, const f32x4a (&st)[NCH], bool one_plane) {
+    auto to_lds = [&](f32a* buf, const f32x4 (&st)[NCH], bool one_plane) {
 #pragma unroll
         for (int k = 0; k < NCH; ++k)
             if (one_plane ? vq1[k] : vq[k]) *(f32x4a*)(buf + 4 * (k * 64 + lane)) = st[k];
@@ -121,6 +134,13 @@ __global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
         const size_t out_c = (size_t)d * planes * HW, out_w = (size_t)d * groups * 3 * HW;
         const size_t slot_c = p.shared ? 0 : out_c, slot_w = p.shared ? 0 : out_w;
 
+        // walking a line's scan steps in LDS: one running index, pinned in a register after every step so
+        // that the compiler keeps a single address instead of one per step; it stops at the last step
+        auto next = [&](int& idx, int s) {
+            idx += (s + 1 < S) ? ss : 0;
+            asm volatile("" : "+v"(idx));
+        };
+
         float gw0[SMAX], gw1[SMAX], gw2[SMAX];
 #pragma unroll
         for (int s = 0; s < SMAX; ++s) { gw0[s] = 0.f; gw1[s] = 0.f; gw2[s] = 0.f; }
@@ -136,18 +156,18 @@ __global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
             const float* up = (const float*)p.u + slot_c + pc;
             const float* hp = (const float*)p.hs + out_c + pc;
             const float* wp = (const float*)p.w + slot_w + wg;
-            float* glp = (float*)p.glam + out_c + pc;
-            float* gup = (float*)p.gu + out_c + pc;
+            const rsrc_t glb = make_rsrc((float*)p.glam + out_c + pc);
+            const rsrc_t gub = make_rsrc((float*)p.gu + out_c + pc);
             float* gwp = (float*)p.gw + out_w + wg;
 
-            f32x4a sa[NCH], sb[NCH], sc[NCH];
+            f32x4 sa[NCH], sb[NCH], sc[NCH];
             load_pair(gyp, sa);
             load_pair(hp, sb);
             load_pair(up, sc);
             // gu = gy*h in the flat layout; h goes to LDS for the weight gradients
 #pragma unroll
             for (int k = 0; k < NCH; ++k)
-                if (vq[k]) *(f32x4a*)(gup + 4 * (k * 64 + lane)) = sa[k] * sb[k];
+                if (vq[k]) stg(gub, voff, k * 1024, sa[k] * sb[k]);
             to_lds(bufH, sb, false);
             load_w(wp, sb);                                     // w0
             // seed u*gy, flat -> per-lane line positions
@@ -157,20 +177,22 @@ __global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
             load_w(wp + HW, sa);                                // w1
             float e[SMAX];
 #pragma unroll
-            for (int s = 0; s < SMAX; ++s) e[s] = (s < S && active) ? bufX[tb + s * ss] : 0.f;
+            for (int s = 0, idx = tb; s < SMAX; ++s) {
+                const float v = bufX[idx];                    // unconditional read of a valid address, then select
+                e[s] = active ? v : 0.f;
+                next(idx, s);
+            }
             load_w(wp + 2 * HW, sc);                            // w2
             float w0r[SMAX], w1r[SMAX], w2r[SMAX];
             to_lds(bufX, sb, shared_group);
 #pragma unroll
-            for (int s = 0; s < SMAX; ++s) w0r[s] = s < S ? bufX[tbw + s * ss] : 0.f;
-            load_pair(xp, sb);
+            for (int s = 0, idx = tbw; s < SMAX; ++s) { w0r[s] = bufX[idx]; next(idx, s); }
             to_lds(bufX, sa, shared_group);
 #pragma unroll
-            for (int s = 0; s < SMAX; ++s) w1r[s] = s < S ? bufX[tbw + s * ss] : 0.f;
-            load_pair(lp, sa);
+            for (int s = 0, idx = tbw; s < SMAX; ++s) { w1r[s] = bufX[idx]; next(idx, s); }
             to_lds(bufX, sc, shared_group);
 #pragma unroll
-            for (int s = 0; s < SMAX; ++s) w2r[s] = s < S ? bufX[tbw + s * ss] : 0.f;
+            for (int s = 0, idx = tbw; s < SMAX; ++s) { w2r[s] = bufX[idx]; next(idx, s); }
 
             // the sweep, against the scan order; the weights of scan step 0 are never used
 #pragma unroll
@@ -185,62 +207,82 @@ __global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
                     e[s] = active ? v : 0.f;
                 }
             }
+            // x and lam are requested only now: while the weights are live there are no registers to park them in
+            __builtin_amdgcn_sched_barrier(0);
+            load_pair(xp, sb);
+            load_pair(lp, sa);
             // weight gradients: e_s[j] * h_{s-1}[j-1, j, j+1]
+            if constexpr (SHARED) {
 #pragma unroll
-            for (int s = 1; s < SMAX; ++s) {
-                if (s < S) {
-                    const float hm = bufH[tb + (s - 1) * ss];
-                    float hl = from_lane_below(hm), hr = from_lane_above(hm);
-                    hl = first ? 0.f : hl;
-                    hr = last ? 0.f : hr;
-                    gw0[s] = fmaf(e[s], hl, gw0[s]);
-                    gw1[s] = fmaf(e[s], hm, gw1[s]);
-                    gw2[s] = fmaf(e[s], hr, gw2[s]);
+                for (int s = 1, idx = tb; s < SMAX; ++s) {
+                    if (s < S) {
+                        const float hm = bufH[idx];             // h of scan step s-1
+                        next(idx, s);
+                        float hl = from_lane_below(hm), hr = from_lane_above(hm);
+                        hl = first ? 0.f : hl;
+                        hr = last ? 0.f : hr;
+                        gw0[s] = fmaf(e[s], hl, gw0[s]);
+                        gw1[s] = fmaf(e[s], hm, gw1[s]);
+                        gw2[s] = fmaf(e[s], hr, gw2[s]);
+                    }
                 }
             }
             // e back to the flat layout: glam = x*e, gx += lam*e
 #pragma unroll
-            for (int s = 0; s < SMAX; ++s)
-                if (s < S && active) bufX[tb + s * ss] = e[s];
+            for (int s = 0, idx = tb; s < SMAX; ++s) {
+                if (s < S) { if (active) bufX[idx] = e[s]; }
+                next(idx, s);
+            }
             f32a* tp = tile + (size_t)2 * pair * HW;
 #pragma unroll
             for (int k = 0; k < NCH; ++k) {
                 if (vq[k]) {
                     const int o = 4 * (k * 64 + lane);
-                    const f32x4a ef = *(const f32x4a*)(bufX + o);
-                    *(f32x4a*)(glp + o) = sb[k] * ef;
+                    const f32x4 ef = *(const f32x4a*)(bufX + o);
+                    stg(glb, voff, k * 1024, sb[k] * ef);
                     *(f32x4a*)(tp + o) = *(const f32x4a*)(tp + o) + sa[k] * ef;
                 }
             }
-            if (!shared_group) {
-                // one group per channel: this sweep's gw is complete
+            if constexpr (!SHARED) {
+                // one group per channel: this sweep's gw is complete; one tap at a time through the LDS buffer
 #pragma unroll
                 for (int t = 0; t < 3; ++t) {
 #pragma unroll
-                    for (int s = 0; s < SMAX; ++s) {
-                        const float v = t == 0 ? gw0[s] : (t == 1 ? gw1[s] : gw2[s]);
-                        if (s < S && active) bufX[tb + s * ss] = v;
+                    for (int s = 0, idx = tb, idh = tb; s < SMAX; ++s) {
+                        if (s < S) {
+                            float v = 0.f;
+                            if (s > 0) {
+                                const float hm = bufH[idh];     // h of scan step s-1
+                                next(idh, s);
+                                float hn = t == 0 ? from_lane_below(hm) : (t == 2 ? from_lane_above(hm) : hm);
+                                if (t == 0) hn = first ? 0.f : hn;
+                                if (t == 2) hn = last ? 0.f : hn;
+                                v = e[s] * hn;
+                            }
+                            if (active) bufX[idx] = v;
+                        }
+                        next(idx, s);
                     }
+                    const rsrc_t gwb = make_rsrc(gwp + t * HW);
 #pragma unroll
                     for (int k = 0; k < NCH; ++k)
-                        if (vq[k]) *(f32x4a*)(gwp + t * HW + wq[k]) = *(const f32x4a*)(bufX + 4 * (k * 64 + lane));
+                        if (vq[k]) stg(gwb, (uint32_t)wq[k] * 4u, 0, *(const f32x4a*)(bufX + 4 * (k * 64 + lane)));
                 }
-#pragma unroll
-                for (int s = 0; s < SMAX; ++s) { gw0[s] = 0.f; gw1[s] = 0.f; gw2[s] = 0.f; }
             }
         }
 
-        if (shared_group) {
+        if constexpr (SHARED) {
             // sum over the two halves of each wave, then over the waves (fixed order), one tap at a time
             const int g = c_first / p.cpg;
             float* gwp = (float*)p.gw + out_w + ((size_t)b * p.G + g) * 3 * HW;
 #pragma unroll
             for (int t = 0; t < 3; ++t) {
 #pragma unroll
-                for (int s = 0; s < SMAX; ++s) {
+                for (int s = 0, idx = ic * ps + s0; s < SMAX; ++s) {
                     float v = t == 0 ? gw0[s] : (t == 1 ? gw1[s] : gw2[s]);
                     v += __int_as_float(__builtin_amdgcn_ds_bpermute(((lane ^ 32) & 63) << 2, __float_as_int(v)));
-                    if (s < S && active && half == 0) bufX[ic * ps + s0 + s * ss] = v;
+                    if (s < S) { if (active && half == 0) bufX[idx] = v; }
+                    next(idx, s);
                 }
                 lds_barrier();
                 for (int q = threadIdx.x; q < n16p; q += blockDim.x) {
@@ -261,10 +303,10 @@ __global__ void __launch_bounds__(256) bwd_plane_kernel(BwdPlaneArgs a) {
     // merged gx of the wave's pairs: written once, coalesced
     for (int pair = wave; pair < pairs; pair += a.nwaves) {
         const f32a* tp = tile + (size_t)2 * pair * HW;
-        float* gxp = (float*)p.gx + ((size_t)b * p.C + c_first + 2 * pair) * HW;
+        const rsrc_t gxb = make_rsrc((float*)p.gx + ((size_t)b * p.C + c_first + 2 * pair) * HW);
 #pragma unroll
         for (int k = 0; k < NCH; ++k)
-            if (vq[k]) *(f32x4a*)(gxp + 4 * (k * 64 + lane)) = *(const f32x4a*)(tp + 4 * (k * 64 + lane));
+            if (vq[k]) stg(gxb, voff, k * 1024, *(const f32x4a*)(tp + 4 * (k * 64 + lane)));
     }
 }
 
@@ -276,6 +318,14 @@ static constexpr int PLANE_LDS_BUDGET = 160 * 1024;
 struct PlanePlan { bool ok; int K, shared_group, gsplit, nwaves, smax; size_t lds; };
 
 static size_t plane_lds(int K, int nwaves, int HW) { return (size_t)(K + 4 * nwaves) * HW * sizeof(float); }
+
+// waves per workgroup: the most (up to `cap`) that share the channel pairs evenly and whose buffers fit
+static int plane_waves(int K, int HW, int cap) {
+    const int pairs = K / 2;
+    for (int n = cap; n > 1; --n)
+        if (pairs % n == 0 && plane_lds(K, n, HW) <= (size_t)PLANE_LDS_BUDGET) return n;
+    return 1;
+}
 
 static PlanePlan plan_plane(const BwdParams& p, int dtype) {
     PlanePlan t = {};
@@ -289,11 +339,12 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
     } else {
         if (p.cpg % 2) return t;
         t.shared_group = 1; t.gsplit = 1; t.K = p.cpg;
-        const int nw = t.K / 2 < 4 ? t.K / 2 : 4;
         const bool few = (size_t)p.B * p.G < 256;               // fewer workgroups than compute units
-        if ((plane_lds(t.K, nw, HW) > (size_t)PLANE_LDS_BUDGET || few) && t.K % 4 == 0) { t.K /= 2; t.gsplit = 2; }
+        if ((plane_lds(t.K, plane_waves(t.K, HW, 6), HW) > (size_t)PLANE_LDS_BUDGET || few) && t.K % 4 == 0) {
+            t.K /= 2; t.gsplit = 2;
+        }
     }
-    t.nwaves = t.K / 2 < 4 ? t.K / 2 : 4;
+    t.nwaves = plane_waves(t.K, HW, t.shared_group ? 6 : 4);
     t.lds = plane_lds(t.K, t.nwaves, HW);
     if (t.lds > (size_t)PLANE_LDS_BUDGET) return t;
     if ((size_t)p.B * (p.C / t.K) > 0x7fffffffull) return t;
@@ -305,9 +356,9 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
 
 bool bwd_plane_applicable(const BwdParams& p, int dtype) { return plan_plane(p, dtype).ok; }
 
-template <int SMAX>
+template <int SMAX, bool SHARED>
 static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
-    auto k = bwd_plane_kernel<SMAX>;
+    auto k = bwd_plane_kernel<SMAX, SHARED>;
     hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, PLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
@@ -329,9 +380,14 @@ hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
             if (e != hipSuccess) return e;
         }
     }
-    if (t.smax == 16) return launch_plane<16>(a, t, s);
-    if (t.smax == 28) return launch_plane<28>(a, t, s);
-    return launch_plane<32>(a, t, s);
+    if (t.shared_group) {
+        if (t.smax == 16) return launch_plane<16, true>(a, t, s);
+        if (t.smax == 28) return launch_plane<28, true>(a, t, s);
+        return launch_plane<32, true>(a, t, s);
+    }
+    if (t.smax == 16) return launch_plane<16, false>(a, t, s);
+    if (t.smax == 28) return launch_plane<28, false>(a, t, s);
+    return launch_plane<32, false>(a, t, s);
 }
 
 }  // namespace gspn

@@ -76,3 +76,43 @@ def test_full_size_constant_line_invariant(name):
     expect = cval * (uf[0] * (r + 1) + uf[1] * (H - r) + uf[2] * (q + 1) + uf[3] * (W - q))
     err = float((y.double() - expect).abs().max() / expect.abs().max())
     assert err <= TOL[cfg.dtype], (name, err)
+
+
+@pytest.mark.parametrize("name", ["train28_gc", "train28_g4"])
+def test_full_size_training_step_sampled_slices_match_the_oracle(name):
+    """Forward with h_save + backward at the benchmark's size; sampled (batch, group) slices of every
+    gradient are recomputed by the oracle from the same stored inputs (its own hidden states)."""
+    import torch
+    import paper_2512_07884_amd as G
+    cfg = WL.CONFIGS[name]
+    inp = WL.make_inputs(cfg, with_gy=True)
+    dev = {k: to_device(v, cfg.dtype) for k, v in inp.items()}
+    nan = float("nan")
+    y = empty_like_dev(inp["x"].shape, cfg.dtype, nan)
+    hs = empty_like_dev(inp["lam"].shape, cfg.dtype, nan)
+    gx = empty_like_dev(inp["x"].shape, cfg.dtype, nan)
+    gw = empty_like_dev(inp["w"].shape, cfg.dtype, nan)
+    gl = empty_like_dev(inp["lam"].shape, cfg.dtype, nan)
+    gu = empty_like_dev(inp["lam"].shape, cfg.dtype, nan)
+    G.gspn_scan_fwd(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, G=cfg.G, dir_mask=15)
+    G.gspn_scan_bwd(dev["gy"], dev["x"], dev["w"], dev["lam"], dev["u"], hs, gx, gw, gl, gu, G=cfg.G, dir_mask=15)
+    torch.cuda.synchronize()
+    for t in (y, hs, gx, gw, gl, gu):
+        assert bool(torch.isfinite(t).all())
+    rng = np.random.default_rng(7)
+    picks = {(0, 0), (cfg.B - 1, cfg.G - 1)} | {(int(rng.integers(cfg.B)), int(rng.integers(cfg.G))) for _ in range(4)}
+    tol = TOL[cfg.dtype]
+    for b, g in sorted(picks):
+        s = WL.inputs_as_f64(WL.make_slice(cfg, b, g, with_gy=True), cfg.dtype)
+        cs = slice(g * cfg.cpg, (g + 1) * cfg.cpg)
+        xs, ws, ls, us, gys = s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None], s["gy"][None]
+        y_ref, h_ref = O.scan_fwd(xs, ws, ls, us, 15)
+        h_used = WL.storage_to_f64(WL.to_storage(h_ref, cfg.dtype), cfg.dtype)
+        gx_r, gw_r, gl_r, gu_r = O.scan_bwd(gys, xs, ws, ls, us, h_used, 15)
+        assert rel_inf_err(to_host_f64(y[b, cs]), y_ref[0]) <= tol
+        assert rel_inf_err(to_host_f64(gx[b, cs]), gx_r[0]) <= tol, (name, b, g, "gx")
+        for d in range(4):
+            assert rel_inf_err(to_host_f64(hs[d, b, cs]), h_ref[d, 0]) <= tol, (name, b, g, "h", d)
+            assert rel_inf_err(to_host_f64(gl[d, b, cs]), gl_r[d, 0]) <= tol, (name, b, g, "glam", d)
+            assert rel_inf_err(to_host_f64(gu[d, b, cs]), gu_r[d, 0]) <= tol, (name, b, g, "gu", d)
+            assert rel_inf_err(to_host_f64(gw[d, b, g]), gw_r[d, 0, 0]) <= tol, (name, b, g, "gw", d)

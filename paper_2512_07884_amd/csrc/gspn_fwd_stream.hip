@@ -12,8 +12,8 @@
 //    READ-MODIFY-WRITES the other half.
 //  * Horizontal directions: a line is an image column of H positions split over H/64 waves (one
 //    image row per lane), lock-stepped with one workgroup barrier per scan step and an LDS
-//    mailbox for the edge rows; every lane reads its row in 64 B bursts (one L2 sector per tensor)
-//    and read-modify-writes its 64 B of y per burst.  The two horizontal directions run one
+//    mailbox for the edge rows; every lane reads its row in 128 B bursts (one cache line per tensor)
+//    and read-modify-writes its 128 B of y per burst.  The two horizontal directions run one
 //    after the other.
 #include "gspn_tile_common.hpp"
 #include <stdlib.h>
@@ -174,7 +174,8 @@ struct HStream {
 
     template <bool RMW>
     __device__ __forceinline__ void compute(int c) {
-        float yv[CS];
+        // the chunk's outputs replace its y words in place, element by element (no second array)
+        float ypair = 0.f;                                   // bf16: first element of the pair being assembled
 #pragma unroll
         for (int k = 0; k < CS; ++k) {
             const int e = REV ? CS - 1 - k : k;
@@ -191,14 +192,22 @@ struct HStream {
             w0 = img_first ? 0.f : w0;
             w2 = img_last ? 0.f : w2;
             h = fmaf(w0, up, fmaf(w1, h, fmaf(w2, dn, av)));
-            yv[e] = elem<T>(bu, e) * h;
-            if constexpr (RMW) yv[e] += elem<T>(by, e);
+            float yv = elem<T>(bu, e) * h;
+            if constexpr (RMW) yv += elem<T>(by, e);
+            if constexpr (sizeof(T) == 4) {
+                by[e] = __float_as_uint(yv);
+            } else {
+                // elements e and e^1 share a word; the pair is complete on every second step
+                if ((k & 1) == 0) ypair = yv;
+                else {
+                    const float lo = (e & 1) ? ypair : yv, hi = (e & 1) ? yv : ypair;
+                    by[e >> 1] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+                }
+            }
             if (edge) mb_out[par] = h;
             lds_barrier();
         }
-        uint32_t o[NR];
-        pack<T, CS>(yv, o);
-        st_buf<NB>(yb, voff, chunk_col(c) * (int)sizeof(T), o);
+        st_buf<NB>(yb, voff, chunk_col(c) * (int)sizeof(T), by);
     }
 
     template <bool RMW>
@@ -308,12 +317,12 @@ hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s) {
     StreamArgs a;
     a.p = p; a.parts = t.parts; a.nwaves = t.nwaves;
     if (dtype == 1) {
-        if (t.v == 4) return launch_stream<bf16_t, 4, 32, 4>(a, s);
-        if (t.v == 8) return launch_stream<bf16_t, 8, 32, 4>(a, s);
-        return launch_stream<bf16_t, 16, 32, 2>(a, s);
+        if (t.v == 4) return launch_stream<bf16_t, 4, 64, 4>(a, s);
+        if (t.v == 8) return launch_stream<bf16_t, 8, 64, 4>(a, s);
+        return launch_stream<bf16_t, 16, 64, 2>(a, s);
     }
-    if (t.v == 4) return launch_stream<float, 4, 16, 4>(a, s);
-    return launch_stream<float, 8, 16, 2>(a, s);
+    if (t.v == 4) return launch_stream<float, 4, 32, 4>(a, s);
+    return launch_stream<float, 8, 32, 2>(a, s);
 }
 
 }  // namespace gspn

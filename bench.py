@@ -186,13 +186,13 @@ def cpu_baseline(cfg, training: bool, budget_s: float = 12.0):
                       f"single-process rate {slice_pc / t_probe / 1e9:.4f} Gpixel*ch/s; pool wall {wall:.1f} s"}
 
 
-def load_traffic(workload: str):
-    """Measured HBM bytes per launch of the dominant kernel, from the rocprofv3
-    counter runs summarised in profiles/traffic.json (absent -> None)."""
+def load_traffic(workload: str, dom: str):
+    """Measured HBM bytes per launch of the dominant kernel (dom = "fwd" / "bwd"), from the
+    rocprofv3 counter runs summarised in profiles/traffic.json (absent -> None)."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get("fwd_hbm_bytes_per_launch")
+            return json.load(f).get(workload, {}).get(f"{dom}_hbm_bytes_per_launch")
     except (OSError, ValueError):
         return None
 
@@ -254,7 +254,7 @@ def main():
                                f"{cfg.dtype} storage, {cfg.n_dirs} directions, {s['step']}",
                    "kernel": s[f"{dom}_kernel"], "buffer_sets_rotated": s["buffer_sets_rotated"]},
         "roofline": {"bound": "hbm", "kernel": f"gspn_scan_{dom}", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(cfg.name),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(cfg.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "detail": s,
     }

@@ -374,10 +374,13 @@ hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
     if (t.gsplit > 1) {
         // gw of the requested directions is accumulated atomically: clear it first, on the same stream
         const size_t per_dir = (size_t)p.B * p.G * 3 * p.H * p.W * sizeof(float);
-        for (int d = 0; d < 4; ++d) {
-            if (!((p.mask >> d) & 1u)) continue;
-            hipError_t e = launch_zero_fill((char*)p.gw + d * per_dir, per_dir, s);
+        for (int d = 0; d < 4;) {                               // one fill per run of consecutive directions
+            if (!((p.mask >> d) & 1u)) { ++d; continue; }
+            int d1 = d;
+            while (d1 < 4 && ((p.mask >> d1) & 1u)) ++d1;
+            hipError_t e = launch_zero_fill((char*)p.gw + d * per_dir, (size_t)(d1 - d) * per_dir, s);
             if (e != hipSuccess) return e;
+            d = d1;
         }
     }
     if (t.shared_group) {

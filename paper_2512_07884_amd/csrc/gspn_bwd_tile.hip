@@ -482,7 +482,10 @@ __global__ void __launch_bounds__(256) zero_fill_kernel(uint32_t* p, size_t n16)
 }
 
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s) {
-    hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, s, (uint32_t*)p, bytes / 16);
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)((n16 + 255) / 256 < 2048 ? (n16 + 255) / 256 : 2048);
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(blocks), dim3(256), 0, s, (uint32_t*)p, n16);
     return hipGetLastError();
 }
 
@@ -547,10 +550,13 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     if (t.gsplit > 1) {
         // gw of the requested directions is accumulated atomically: clear it first, on the same stream
         const size_t per_dir = (size_t)p.B * p.G * 3 * p.H * p.W * sizeof(float);
-        for (int d = 0; d < 4; ++d) {
-            if (!((p.mask >> d) & 1u)) continue;
-            hipError_t e = launch_zero_fill((char*)p.gw + d * per_dir, per_dir, s);
+        for (int d = 0; d < 4;) {                               // one fill per run of consecutive directions
+            if (!((p.mask >> d) & 1u)) { ++d; continue; }
+            int d1 = d;
+            while (d1 < 4 && ((p.mask >> d1) & 1u)) ++d1;
+            hipError_t e = launch_zero_fill((char*)p.gw + d * per_dir, (size_t)(d1 - d) * per_dir, s);
             if (e != hipSuccess) return e;
+            d = d1;
         }
     }
     const dim3 grid((unsigned)((size_t)p.B * (p.C / t.K))), block(64 * t.nwaves);

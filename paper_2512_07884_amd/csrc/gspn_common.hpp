@@ -10,12 +10,15 @@ typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
 // ---- storage <-> fp32 ------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round-to-nearest-even; NaN stays NaN (quiet)
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// round-to-nearest-even, NaN stays NaN: gfx950 converts in hardware (v_cvt_pk_bf16_f32, two values per
+// instruction), which is what these casts compile to
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values into one 32-bit word: `lo` in bits 0-15, `hi` in bits 16-31
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const f32x2_hw v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw));
 }
 
 __device__ __forceinline__ float ldf(const float* p) { return *p; }
@@ -58,6 +61,8 @@ hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_tile_applicable(const FwdParams& p, int dtype);
+hipError_t launch_fwd_plane(const FwdParams& p, int dtype, hipStream_t s);
+bool fwd_plane_applicable(const FwdParams& p, int dtype);
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_stream_applicable(const FwdParams& p, int dtype);
 hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s);

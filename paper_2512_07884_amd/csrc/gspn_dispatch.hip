@@ -4,12 +4,14 @@
 
 namespace gspn {
 
-enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1, FWD_STREAM = 2 };
+enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1, FWD_STREAM = 2, FWD_PLANE = 3 };
 enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1, BWD_PLANE = 2 };
 
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
     if (f && f[0] == '1') return FWD_GENERIC;
+    const char* np = getenv("GSPN_FWD_NO_PLANE");     // testing aid: keep the tile kernel reachable on small maps
+    if (!(np && np[0] == '1') && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
     if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
     return fwd_stream_applicable(p, dtype) ? FWD_STREAM : FWD_GENERIC;
 }
@@ -25,6 +27,7 @@ hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {
     switch (choose_fwd(p, dtype)) {
         case FWD_TILE: return launch_fwd_tile(p, dtype, s);
         case FWD_STREAM: return launch_fwd_stream(p, dtype, s);
+        case FWD_PLANE: return launch_fwd_plane(p, dtype, s);
         default: return launch_fwd_generic(p, dtype, s);
     }
 }
@@ -41,6 +44,7 @@ const char* fwd_plan_name(const FwdParams& p, int dtype) {
     switch (choose_fwd(p, dtype)) {
         case FWD_TILE: return "tile";
         case FWD_STREAM: return "stream";
+        case FWD_PLANE: return "plane";
         default: return "generic";
     }
 }

@@ -1,0 +1,377 @@
+// Forward GSPN scan for small feature maps (lines of at most 64 positions, planes of at most 8 KB in
+// storage precision: 56x56 bf16, 28x28 fp32, ...): every tensor is read from global memory exactly
+// once per use as flat, fully coalesced 16 B-per-lane plane copies, and the scans run out of LDS.
+//
+// Per (channel, direction) the recurrence of Eq. 1 (Sec. 3.2)
+//     h_s[j] = w0_s[j] h_{s-1}[j-1] + w1_s[j] h_{s-1}[j] + w2_s[j] h_{s-1}[j+1] + lam_s[j] x_s[j]
+// is walked by one wave: lane = position j on the line (two channels side by side when a line fits
+// in 32 lanes), the previous line's neighbours come from DPP whole-wave shifts, and the per-step
+// operands a = lam*x, w0, w1, w2 are read from fp32 planes in LDS through an address walk whose stride
+// encodes the direction (+-pitch for the vertical scans, +-1 for the horizontal ones), so that one
+// code path serves all four directions.  h overwrites a in place; afterwards the plane is read back
+// in the flat layout for y += u*h (Eq. 2 and the sum merge of the four passes, accumulated in
+// registers and rounded once) and, when asked for, h_save.
+//
+// What this saves over line-by-line loading: x is loaded once for all directions and stays in
+// registers; with channel-shared weights (Sec. 4.2) the three weight planes of a direction are
+// loaded ONCE per workgroup into LDS and read by all its channels; every request is a complete
+// cache line.  Rows in LDS have an odd pitch so that both access orientations are conflict-free.
+#include "gspn_tile_common.hpp"
+#include <stdlib.h>
+
+namespace gspn {
+
+namespace {
+
+typedef float pf32a __attribute__((may_alias));
+typedef __attribute__((address_space(3))) pf32a plds_f32;
+extern __shared__ float plane_lds[];
+
+__device__ __forceinline__ uint32_t plds_base() {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)plane_lds;
+}
+__device__ __forceinline__ float plds_ld(uint32_t a) { return *(const plds_f32*)(uintptr_t)a; }
+__device__ __forceinline__ void plds_st(uint32_t a, float v) { *(plds_f32*)(uintptr_t)a = v; }
+typedef float pf32x4a __attribute__((ext_vector_type(4), may_alias));
+typedef __attribute__((address_space(3))) pf32x4a plds_f32x4;
+__device__ __forceinline__ pf32x4a plds_ld4(uint32_t a) { return *(const plds_f32x4*)(uintptr_t)a; }
+
+// element e of a 16 B chunk of storage, widened to fp32
+template <typename T> __device__ __forceinline__ float chunk_elem(const u32x4& c, int e) {
+    if constexpr (sizeof(T) == 4) return __uint_as_float(c[e]);
+    else return (e & 1) ? __uint_as_float(c[e >> 1] & 0xffff0000u) : __uint_as_float(c[e >> 1] << 16);
+}
+template <typename T> __device__ __forceinline__ u32x4 chunk_pack(const float* v) {
+    u32x4 c;
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = __float_as_uint(v[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+    }
+    return c;
+}
+
+}  // namespace
+
+struct FwdPlaneArgs {
+    FwdParams p;
+    int K;        // channels per workgroup
+    int cpw;      // channels per wave: 2 when a line fits in 32 lanes, else 1
+    int nwaves;
+    int pitch;    // LDS row pitch in floats (odd)
+};
+
+template <typename T, bool SAVE, bool SHARED>
+__global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneArgs a) {
+    constexpr int E = 16 / (int)sizeof(T);        // elements per 16 B chunk
+    constexpr int NCH = 8;                        // chunks per lane: the wave's channels hold at most 8 KB
+    constexpr int WSH = 4;                        // weight chunks per thread (shared weights)
+    const FwdParams& p = a.p;
+    const int H = p.H, W = p.W, HW = H * W, P = a.pitch;
+    const int HP = (H * P + 3) & ~3;                   // floats per plane region in LDS (16 B granules)
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int cpw = a.cpw;
+    const int half = cpw == 2 ? lane >> 5 : 0;
+    const int i = cpw == 2 ? lane & 31 : lane;
+    const int wgs_per_image = p.C / a.K;
+    const unsigned item = xcd_contiguous_item(blockIdx.x, gridDim.x);
+    const int b = item / wgs_per_image;
+    const int c_first = (item - b * wgs_per_image) * a.K;
+    const int c0 = c_first + wave * cpw;                               // first channel of this wave
+    const size_t planes = (size_t)p.B * p.C, groups = (size_t)p.B * p.G;
+    const size_t pc = ((size_t)b * p.C + c0) * HW;
+    const int n16 = cpw * HW / E;                                      // 16 B chunks of the wave's channels
+    const int n16p = HW / E;                                           // ... of one plane
+
+    // LDS (floats).  Weights are kept interleaved, [H][P][4] = (w0, w1, w2, unused) per position, so that a scan
+    // step fetches its three taps with one 16 B read.  Shared weights: one such region for the direction,
+    // then per wave [cpw][H][P] a/h.  Per-channel weights: per wave [cpw] weight regions, then [cpw][H][P] a/h.
+    const uint32_t base = plds_base();
+    const uint32_t wreg = SHARED ? base : base + 4u * (uint32_t)(wave * cpw * 5 * HP);
+    const uint32_t ahreg = SHARED ? base + 4u * (uint32_t)(4 * HP + wave * cpw * HP)
+                                  : wreg + 4u * (uint32_t)(cpw * 4 * HP);
+
+    // flat layout: chunk q = k*64 + lane covers elements [q*E, q*E + E) of the wave's channels
+    bool vq[NCH];
+    int rc[NCH];          // row*P + col of the chunk's first element
+    int ch[NCH];          // channel of the wave (0 / 1) the chunk belongs to
+    int row0[NCH], col0[NCH];
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+        const int q = k * 64 + lane;
+        vq[k] = q < n16;
+        const int idx0 = vq[k] ? q * E : 0;
+        ch[k] = idx0 >= HW ? 1 : 0;
+        const int rem = idx0 - ch[k] * HW;
+        const int row = rem / W;
+        rc[k] = row * P + (rem - row * W);
+        row0[k] = row; col0[k] = rem - row * W;
+    }
+    const uint32_t flat = (uint32_t)lane * 16u;
+    auto ldg = [&](rsrc_t rs, uint32_t vo, int so) -> u32x4 { return __builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0); };
+    auto load_planes = [&](const T* basep, u32x4 (&st)[NCH]) {
+        const rsrc_t rs = make_rsrc(basep);
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            u32x4 v = {0, 0, 0, 0};
+            if (vq[k]) v = ldg(rs, flat, k * 1024);
+            st[k] = v;
+        }
+    };
+
+    // shared weights: the three planes of a direction are 3*n16p chunks, dealt round-robin to the threads
+    const int nthreads = blockDim.x;
+    bool wv[WSH];
+    int wl[WSH];          // LDS float offset of the chunk's first element in the weight region (tap included)
+    int wrow[WSH], wcol[WSH], wtap[WSH];
+    uint32_t wgo[WSH];    // byte offset of the chunk from the group's first weight plane
+    if constexpr (SHARED) {
+#pragma unroll
+        for (int j = 0; j < WSH; ++j) {
+            const int c = (int)threadIdx.x + j * nthreads;
+            wv[j] = c < 3 * n16p;
+            const int cc = wv[j] ? c : 0;
+            const int tap = cc / n16p;
+            const int idx0 = (cc - tap * n16p) * E;
+            const int row = idx0 / W;
+            wl[j] = 4 * (row * P + (idx0 - row * W)) + tap;
+            wrow[j] = row; wcol[j] = idx0 - row * W; wtap[j] = tap;
+            wgo[j] = (uint32_t)((tap * HW + idx0) * (int)sizeof(T));
+        }
+    }
+    auto load_wshare = [&](const T* wbase, u32x4 (&st)[WSH]) {
+        const rsrc_t rs = make_rsrc(wbase);
+#pragma unroll
+        for (int j = 0; j < WSH; ++j) {
+            u32x4 v = {0, 0, 0, 0};
+            if (wv[j]) v = ldg(rs, wgo[j], 0);
+            st[j] = v;
+        }
+    };
+
+    u32x4 xs[NCH];
+    load_planes((const T*)p.x + pc, xs);
+    float y[NCH][E];
+#pragma unroll
+    for (int k = 0; k < NCH; ++k)
+#pragma unroll
+        for (int e = 0; e < E; ++e) y[k][e] = 0.f;
+
+    // directions in scan order; operands of the first one are requested here, later ones a direction ahead
+    int d = 0;
+    while (d < 4 && !((p.mask >> d) & 1u)) ++d;
+    const int g = c_first / p.cpg;                                     // shared weights: the workgroup's group
+    auto slot_c = [&](int dd) { return p.shared ? (size_t)0 : (size_t)dd * planes * HW; };
+    auto wptr = [&](int dd, int grp) {
+        return (const T*)p.w + (p.shared ? (size_t)0 : (size_t)dd * groups * 3 * HW) + ((size_t)b * p.G + grp) * 3 * HW;
+    };
+    u32x4 ls[NCH], us[NCH], wsh[WSH];
+    if (d < 4) {
+        load_planes((const T*)p.lam + slot_c(d) + pc, ls);
+        if constexpr (SHARED) load_wshare(wptr(d, g), wsh);
+    }
+
+    while (d < 4) {
+        int dn = d + 1;
+        while (dn < 4 && !((p.mask >> dn) & 1u)) ++dn;
+        // element (position j, scan step s) of a plane sits at float offset j*ps + s0 + s*ss
+        const bool vert = d < 2, rev = (d & 1) != 0;
+        const int S = vert ? H : W, L = vert ? W : H;
+        const int ps = vert ? 1 : P;
+        const int ss4 = 4 * (vert ? (rev ? -P : P) : (rev ? -1 : 1));
+        const int s0 = vert ? (rev ? (H - 1) * P : 0) : (rev ? W - 1 : 0);
+        const bool active = i < L;
+        const int ic = active ? i : L - 1;
+        const bool first = i == 0, last = i == L - 1;
+        const int tpos = ic * ps + s0;
+
+        // ---- operands into LDS
+        if constexpr (SHARED) {
+            lds_barrier();                                 // every wave is done with the previous direction's weights
+#pragma unroll
+            for (int j = 0; j < WSH; ++j) {
+                if (wv[j]) {
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        // a tap that points outside the line is stored as 0, whatever the tensor holds there
+                        const int pos = vert ? wcol[j] + e : wrow[j];
+                        const bool outside = (wtap[j] == 0 && pos == 0) || (wtap[j] == 2 && pos == L - 1);
+                        plds_st(wreg + 4u * (uint32_t)(wl[j] + 4 * e), outside ? 0.f : chunk_elem<T>(wsh[j], e));
+                    }
+                }
+            }
+        } else {
+            // the wave's own channels: three planes each, 3*HW elements apart per channel
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                const rsrc_t rs = make_rsrc(wptr(d, c0) + (size_t)t * HW);
+                u32x4 wt[NCH];
+#pragma unroll
+                for (int k = 0; k < NCH; ++k) {
+                    u32x4 v = {0, 0, 0, 0};
+                    if (vq[k]) v = ldg(rs, (uint32_t)(((ch[k] * 2 * HW) + (k * 64 + lane) * E) * (int)sizeof(T)), 0);
+                    wt[k] = v;
+                }
+#pragma unroll
+                for (int k = 0; k < NCH; ++k) {
+                    if (vq[k]) {
+                        const uint32_t o = wreg + 4u * (uint32_t)(ch[k] * 4 * HP + 4 * rc[k] + t);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            const int pos = vert ? col0[k] + e : row0[k];
+                            const bool outside = (t == 0 && pos == 0) || (t == 2 && pos == L - 1);
+                            plds_st(o + 16u * e, outside ? 0.f : chunk_elem<T>(wt[k], e));
+                        }
+                    }
+                }
+            }
+        }
+        // a = lam * x
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            if (vq[k]) {
+                const uint32_t o = ahreg + 4u * (uint32_t)(ch[k] * HP + rc[k]);
+#pragma unroll
+                for (int e = 0; e < E; ++e) plds_st(o + 4u * e, chunk_elem<T>(ls[k], e) * chunk_elem<T>(xs[k], e));
+            }
+        }
+        // requests for after the sweep (u) and for the next direction (lam, shared weights)
+        load_planes((const T*)p.u + slot_c(d) + pc, us);
+        if (dn < 4) {
+            load_planes((const T*)p.lam + slot_c(dn) + pc, ls);
+            if constexpr (SHARED) load_wshare(wptr(dn, g), wsh);
+        }
+        if constexpr (SHARED) lds_barrier();               // weights of this direction are in place (LDS only: the
+                                                           // requests above stay in flight across the barrier)
+
+        // ---- the scan: h overwrites a
+        {
+            uint32_t aad = ahreg + 4u * (uint32_t)(half * HP + tpos);
+            uint32_t wad = wreg + 16u * (uint32_t)((SHARED ? 0 : half * HP) + tpos);
+            float h = plds_ld(aad);                        // scan step 0: no previous line, its weights are never read
+            // lanes past the end of the line walk the last position's operands; what they compute is never
+            // stored, and the selects below keep it out of the line
+            auto step = [&]() {
+                aad += (uint32_t)ss4; wad += (uint32_t)(4 * ss4);
+                const float av = plds_ld(aad);
+                const pf32x4a w = plds_ld4(wad);
+                float hl = from_lane_below(h), hr = from_lane_above(h);
+                hl = first ? 0.f : hl;                     // no neighbour outside the line (its weight is stored as 0)
+                hr = last ? 0.f : hr;
+                h = fmaf(w.x, hl, fmaf(w.y, h, fmaf(w.z, hr, av)));
+                if (active) plds_st(aad, h);
+            };
+            // four steps per trip: their operand reads do not depend on h and are issued together
+            int s = 1;
+            for (; s + 3 < S; s += 4) { step(); step(); step(); step(); }
+            for (; s < S; ++s) step();
+        }
+
+        // ---- back in the flat layout: y += u*h, optional h_save
+        {
+            const rsrc_t hb = make_rsrc(SAVE ? (T*)p.hs + (size_t)d * planes * HW + pc : (T*)p.y);
+#pragma unroll
+            for (int k = 0; k < NCH; ++k) {
+                if (vq[k]) {
+                    const uint32_t o = ahreg + 4u * (uint32_t)(ch[k] * HP + rc[k]);
+                    float hv[E];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        hv[e] = plds_ld(o + 4u * e);
+                        y[k][e] = fmaf(chunk_elem<T>(us[k], e), hv[e], y[k][e]);
+                    }
+                    if constexpr (SAVE) __builtin_amdgcn_raw_buffer_store_b128(chunk_pack<T>(hv), hb, flat, k * 1024, 0);
+                }
+            }
+        }
+        d = dn;
+    }
+
+    // merged output, rounded once
+    {
+        const rsrc_t yb = make_rsrc((T*)p.y + pc);
+#pragma unroll
+        for (int k = 0; k < NCH; ++k)
+            if (vq[k]) __builtin_amdgcn_raw_buffer_store_b128(chunk_pack<T>(y[k]), yb, flat, k * 1024, 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static constexpr int FPLANE_LDS_BUDGET = 160 * 1024;
+
+struct FwdPlanePlan { bool ok; int K, cpw, nwaves, pitch, shared_group; size_t lds; };
+
+static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
+    FwdPlanePlan t = {};
+    const int es = dtype == 0 ? 4 : 2, E = 16 / es;
+    if (p.H < 2 || p.W < 2 || p.H > 64 || p.W > 64 || p.W % E) return t;
+    const int HW = p.H * p.W;
+    const int m = p.H > p.W ? p.H : p.W;
+    t.cpw = m <= 32 ? 2 : 1;
+    if ((size_t)t.cpw * HW * es > 8192) {
+        if (t.cpw == 2 && (size_t)HW * es <= 8192) t.cpw = 1; else return t;
+    }
+    t.pitch = p.W | 1;
+    const size_t hp = (((size_t)p.H * t.pitch + 3) & ~(size_t)3) * sizeof(float);   // one plane region in LDS
+    if (p.cpg == 1) {
+        t.shared_group = 0;
+        if (p.C % t.cpw) { if (t.cpw == 2) t.cpw = 1; }
+        // per wave: cpw * 4 planes; aim at 4 waves per workgroup
+        int nw = 4;
+        while (nw > 1 && (p.C % (nw * t.cpw) || (size_t)nw * t.cpw * 5 * hp > (size_t)FPLANE_LDS_BUDGET)) --nw;
+        if (p.C % (nw * t.cpw) || (size_t)nw * t.cpw * 5 * hp > (size_t)FPLANE_LDS_BUDGET) return t;
+        t.nwaves = nw; t.K = nw * t.cpw;
+        t.lds = (size_t)nw * t.cpw * 5 * hp;
+    } else {
+        t.shared_group = 1;
+        if (p.cpg % t.cpw) t.cpw = 1;
+        // the most waves (up to 8) whose channels divide the group and whose planes fit beside the weights
+        int nw = 8;
+        if (const char* e = getenv("GSPN_FPLANE_NW")) { const int v = atoi(e); if (v >= 1 && v <= 8) nw = v; }   // tuning aid
+        for (; nw >= 1; --nw) {
+            if ((p.cpg / t.cpw) % nw) continue;
+            if ((4 + (size_t)nw * t.cpw) * hp > (size_t)FPLANE_LDS_BUDGET) continue;
+            if (3 * (HW / E) > 4 * 64 * nw) continue;             // weight chunks per thread
+            break;
+        }
+        if (nw < 1) return t;
+        t.nwaves = nw; t.K = nw * t.cpw;
+        t.lds = (4 + (size_t)nw * t.cpw) * hp;
+    }
+    if ((size_t)p.B * (p.C / t.K) > 0x7fffffffull) return t;
+    t.ok = true;
+    return t;
+}
+
+bool fwd_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane(p, dtype).ok; }
+
+template <typename T, bool SAVE, bool SHARED>
+static hipError_t launch_fplane(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    auto k = fwd_plane_kernel<T, SAVE, SHARED>;
+    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, FPLANE_LDS_BUDGET);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
+    hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
+    return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_fplane_t(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    if (a.p.hs) return t.shared_group ? launch_fplane<T, true, true>(a, t, s) : launch_fplane<T, true, false>(a, t, s);
+    return t.shared_group ? launch_fplane<T, false, true>(a, t, s) : launch_fplane<T, false, false>(a, t, s);
+}
+
+hipError_t launch_fwd_plane(const FwdParams& p, int dtype, hipStream_t s) {
+    const FwdPlanePlan t = plan_fwd_plane(p, dtype);
+    if (!t.ok) return hipErrorInvalidValue;
+    FwdPlaneArgs a;
+    a.p = p; a.K = t.K; a.cpw = t.cpw; a.nwaves = t.nwaves; a.pitch = t.pitch;
+    return dtype == 0 ? launch_fplane_t<float>(a, t, s) : launch_fplane_t<bf16_t>(a, t, s);
+}
+
+}  // namespace gspn

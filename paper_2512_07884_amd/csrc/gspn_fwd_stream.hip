@@ -201,7 +201,7 @@ struct HStream {
                 if ((k & 1) == 0) ypair = yv;
                 else {
                     const float lo = (e & 1) ? ypair : yv, hi = (e & 1) ? yv : ypair;
-                    by[e >> 1] = (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+                    by[e >> 1] = pack_bf16x2(lo, hi);
                 }
             }
             if (edge) mb_out[par] = h;

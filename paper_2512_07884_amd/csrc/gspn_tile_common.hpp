@@ -60,7 +60,7 @@ template <typename T, int V> __device__ __forceinline__ void pack(const float* v
         static_assert(V % 2 == 0, "bf16 vectors hold an even number of elements");
 #pragma unroll
         for (int i = 0; i < V / 2; ++i)
-            r[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+            r[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
     }
 }
 

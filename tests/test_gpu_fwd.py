@@ -90,7 +90,10 @@ def test_benchmark_shapes_with_fewer_channels(cfg):
 def test_kernel_families_by_shape():
     import paper_2512_07884_amd as G
     assert G.gspn_fwd_plan(2, 1024, 128, 128, 16, 15, 1, 0, False) == "tile"
-    assert G.gspn_fwd_plan(64, 96, 56, 56, 8, 15, 1, 0, False) == "tile"
+    assert G.gspn_fwd_plan(64, 96, 56, 56, 8, 15, 1, 0, False) == "plane"
+    assert G.gspn_fwd_plan(32, 192, 28, 28, 4, 15, 0, 0, True) == "plane"
+    assert G.gspn_fwd_plan(32, 192, 28, 28, 192, 15, 0, 0, True) == "plane"
+    assert G.gspn_fwd_plan(2, 8, 56, 56, 2, 15, 0, 0, False) == "tile"          # fp32 56x56 planes exceed the plane kernel's 8 KB
     assert G.gspn_fwd_plan(1, 512, 512, 512, 16, 15, 1, 0, False) == "stream"
     assert G.gspn_fwd_plan(1, 512, 256, 1024, 16, 15, 1, 0, False) == "stream"
     assert G.gspn_fwd_plan(1, 2, 256, 256, 1, 15, 0, 0, False) == "stream"
@@ -170,10 +173,10 @@ def test_library_reports_shape_errors_through_the_binding():
 
 @pytest.mark.parametrize("cfg", [SHRUNK[0], SHRUNK[2], SHRUNK[6], SHRUNK[7]],
                          ids=lambda c: f"{c.name}-{c.dtype}")
-def test_generic_kernel_on_shapes_the_tile_kernel_normally_takes(cfg, monkeypatch):
+def test_generic_kernel_on_shapes_the_fast_kernels_normally_take(cfg, monkeypatch):
     import paper_2512_07884_amd as G
     dt = int(cfg.dtype == "bf16")
-    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) == "tile"
+    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) in ("tile", "plane")
     monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
     assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) == "generic"
     check_case(cfg)
@@ -192,3 +195,39 @@ def test_both_kernel_families_agree_closely():
     finally:
         del os.environ["GSPN_FORCE_GENERIC"]
     assert rel_inf_err(y_gen, y_tile) <= 1e-2
+
+
+# shapes the whole-plane forward kernel takes (lines <= 64, planes <= 8 KB): shared weights with 1 / 2
+# channels per wave, per-channel weights, several waves, H != W, ragged last chunk, a single wave
+PLANE_FWD_SHAPES = [(2, 24, 56, 56, 2, "bf16"), (2, 16, 28, 28, 2, "f32"), (2, 8, 28, 28, 8, "f32"), (1, 12, 16, 32, 3, "f32"),
+                    (1, 6, 40, 24, 3, "bf16"), (3, 32, 2, 4, 32, "f32"), (1, 8, 64, 64, 8, "bf16"), (1, 4, 12, 20, 2, "f32"),
+                    (1, 3, 28, 28, 3, "f32"), (2, 10, 8, 16, 5, "bf16"), (1, 2, 33, 40, 1, "bf16"), (5, 7, 20, 8, 1, "f32")]
+
+
+@pytest.mark.parametrize("shape", PLANE_FWD_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_forward_plane_kernel_shapes(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    dt = int(dtype == "bf16")
+    assert G.gspn_fwd_plan(B, C, H, W, Gr, 15, dt, 0, True) == "plane", shape
+    cfg = WL.ScanConfig("fwdplane", B, C, H, W, Gr, dtype, 15, 1.0, 43)
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 6, 9, 14])
+@pytest.mark.parametrize("G_", [8, 2])
+def test_forward_plane_kernel_direction_masks(mask, G_):
+    check_case(WL.ScanConfig("fwdplanemask", 2, 8, 28, 24, G_, "bf16", mask, 1.0, 47))
+
+
+@pytest.mark.parametrize("shape", [(2, 24, 56, 56, 2, "bf16"), (2, 16, 28, 28, 2, "f32"), (2, 8, 28, 28, 8, "f32"),
+                                   (1, 12, 16, 32, 3, "f32")], ids=lambda s: "x".join(map(str, s)))
+def test_tile_kernel_on_shapes_the_plane_kernel_normally_takes(shape, monkeypatch):
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FWD_NO_PLANE", "1")
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_fwd_plan(B, C, H, W, Gr, 15, int(dtype == "bf16"), 0, True) == "tile", shape
+    cfg = WL.ScanConfig("fwdtile2", B, C, H, W, Gr, dtype, 15, 1.0, 43)
+    check_case(cfg)
+    check_case(cfg, save_h=False)

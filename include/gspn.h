@@ -101,7 +101,16 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
                   unsigned dir_mask, int dtype, unsigned flags, void* stream);
 
 /* Name of the kernel family the forward / backward call would dispatch to for
- * these arguments ("generic", ...); static string, never NULL.  Host only. */
+ * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
+ * merged output fits in LDS), "stream" (larger maps, forward only), "generic" (any
+ * shape); static string, never NULL.  Host only.
+ *
+ * Environment variables read at every call, for tests and tuning (results are the
+ * same whichever kernel runs, up to the rounding of the storage type):
+ *   GSPN_FORCE_GENERIC=1   always the generic kernels
+ *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
+ *   GSPN_TILE_K=<n>, GSPN_TILE_HV=<0..3>   forward tile kernel: channels per
+ *       workgroup / horizontal-phase variant (ignored when they do not fit) */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);
 const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
 

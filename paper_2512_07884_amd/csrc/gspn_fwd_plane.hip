@@ -203,6 +203,22 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                     }
                 }
             }
+            // small workgroups: the chunks beyond WSH per thread are fetched here, without the head start
+            if (3 * n16p > WSH * nthreads) {
+                const rsrc_t rs = make_rsrc(wptr(d, g));
+                for (int c = (int)threadIdx.x + WSH * nthreads; c < 3 * n16p; c += nthreads) {
+                    const int tap = c / n16p;
+                    const int idx0 = (c - tap * n16p) * E;
+                    const int row = idx0 / W, col = idx0 - row * W;
+                    const u32x4 v = ldg(rs, (uint32_t)((tap * HW + idx0) * (int)sizeof(T)), 0);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const int pos = vert ? col + e : row;
+                        const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1);
+                        plds_st(wreg + 4u * (uint32_t)(4 * (row * P + col + e) + tap), outside ? 0.f : chunk_elem<T>(v, e));
+                    }
+                }
+            }
         } else {
             // the wave's own channels: three planes each, 3*HW elements apart per channel
 #pragma unroll
@@ -332,11 +348,9 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
         if (p.cpg % t.cpw) t.cpw = 1;
         // the most waves (up to 8) whose channels divide the group and whose planes fit beside the weights
         int nw = 8;
-        if (const char* e = getenv("GSPN_FPLANE_NW")) { const int v = atoi(e); if (v >= 1 && v <= 8) nw = v; }   // tuning aid
         for (; nw >= 1; --nw) {
             if ((p.cpg / t.cpw) % nw) continue;
             if ((4 + (size_t)nw * t.cpw) * hp > (size_t)FPLANE_LDS_BUDGET) continue;
-            if (3 * (HW / E) > 4 * 64 * nw) continue;             // weight chunks per thread
             break;
         }
         if (nw < 1) return t;

@@ -201,7 +201,9 @@ def test_both_kernel_families_agree_closely():
 # channels per wave, per-channel weights, several waves, H != W, ragged last chunk, a single wave
 PLANE_FWD_SHAPES = [(2, 24, 56, 56, 2, "bf16"), (2, 16, 28, 28, 2, "f32"), (2, 8, 28, 28, 8, "f32"), (1, 12, 16, 32, 3, "f32"),
                     (1, 6, 40, 24, 3, "bf16"), (3, 32, 2, 4, 32, "f32"), (1, 8, 64, 64, 8, "bf16"), (1, 4, 12, 20, 2, "f32"),
-                    (1, 3, 28, 28, 3, "f32"), (2, 10, 8, 16, 5, "bf16"), (1, 2, 33, 40, 1, "bf16"), (5, 7, 20, 8, 1, "f32")]
+                    (1, 3, 28, 28, 3, "f32"), (2, 10, 8, 16, 5, "bf16"), (1, 2, 33, 40, 1, "bf16"), (5, 7, 20, 8, 1, "f32"),
+                    # small groups: more weight chunks than the threads prefetch
+                    (2, 8, 28, 28, 2, "f32"), (1, 2, 64, 64, 1, "bf16"), (1, 4, 56, 56, 2, "bf16"), (1, 1, 32, 32, 1, "f32")]
 
 
 @pytest.mark.parametrize("shape", PLANE_FWD_SHAPES, ids=lambda s: "x".join(map(str, s)))

@@ -1,5 +1,5 @@
-// Backward GSPN scan for very small feature maps (fp32 storage, H, W <= 32: the 28x28 training
-// stage): every tensor crosses the memory system exactly once, as whole planes.
+// Backward GSPN scan for very small feature maps (fp32 or bf16 storage, H, W <= 32: the 28x28
+// training stage): every tensor crosses the memory system exactly once, as whole planes.
 //
 // The paper gives timings but no algorithm for the backward pass (Sec. 5.1); this is the chain rule
 // on Eq. 1-2 (Sec. 3.2) with the shared weights of Sec. 4.2.  Per direction, with e_s = dL/dh_s and
@@ -41,9 +41,33 @@ struct BwdPlaneArgs {
     int nwaves;
 };
 
-template <int SMAX, bool SHARED>
-__global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPlaneArgs a) {
-    constexpr int NCH = (2 * SMAX * SMAX / 4 + 63) / 64;      // 16 B chunks per lane for a pair of planes
+// widening / narrowing of one 16 B chunk of storage (E = 4 fp32 or 8 bf16 elements)
+template <typename T, int E> __device__ __forceinline__ void chunk_unpack(const u32x4& c, float (&v)[E]) {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(c[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[2 * e] = __uint_as_float(c[e] << 16); v[2 * e + 1] = __uint_as_float(c[e] & 0xffff0000u); }
+    }
+}
+template <typename T, int E> __device__ __forceinline__ u32x4 chunk_pack(const float (&v)[E]) {
+    u32x4 c;
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = __float_as_uint(v[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+    }
+    return c;
+}
+
+template <typename T, int SMAX, bool SHARED>
+__global__ void __launch_bounds__((SHARED && SMAX < 32) ? 384 : 256, (SHARED && SMAX == 32) ? 1 : 2)
+bwd_plane_kernel(BwdPlaneArgs a) {
+    constexpr int E = 16 / (int)sizeof(T);                    // elements per 16 B chunk of storage
+    constexpr int NCH = (2 * SMAX * SMAX / E + 63) / 64;      // chunks per lane for a pair of planes
     extern __shared__ float lds[];
     const BwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
@@ -54,68 +78,87 @@ __global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPla
     const int b = blockIdx.x / wgs_per_image;
     const int c_first = (blockIdx.x - b * wgs_per_image) * a.K;
     const int pairs = a.K / 2;
-    const int n16p = HW / 4, n16 = 2 * n16p;                   // 16 B chunks per plane / per pair
+    const int n16p = HW / E, n16 = 2 * n16p;                   // chunks per plane / per pair
     const size_t planes = (size_t)p.B * p.C, groups = (size_t)p.B * p.G;
     constexpr bool shared_group = SHARED;
-    const bool atomic = a.gsplit > 1;
+    const bool atomic = a.gsplit > 1;                          // fp32 storage only (checked on the host)
 
-    float* tile = lds;                                         // [K][HW] merged gx
-    float* wave_bufs = lds + a.K * HW;                         // per wave: X (two planes), H (two planes)
+    float* tile = lds;                                         // [K][HW] merged gx (fp32)
+    float* wave_bufs = lds + a.K * HW;                         // per wave: X (two planes), H (two planes), fp32
     f32a* bufX = wave_bufs + wave * 4 * HW;
     f32a* bufH = bufX + 2 * HW;
+    const int xoff = 4 * (a.K * HW + wave * 4 * HW), hoff = xoff + 8 * HW;   // the same, as byte offsets in LDS
 
-    // chunk q = k*64 + lane of a contiguous pair of planes covers floats [4q, 4q+4)
+    // chunk q = k*64 + lane of a contiguous pair of planes covers elements [E*q, E*q + E)
     bool vq[NCH];        // chunk inside the pair
     bool vq1[NCH];       // chunk inside the first plane
-    int wq[NCH];         // float offset of the chunk in a weight tensor (per-channel groups: planes 3*HW apart)
+    uint32_t wq[NCH];    // byte offset of the chunk in a weight tensor (per-channel groups: planes 3*HW apart)
 #pragma unroll
     for (int k = 0; k < NCH; ++k) {
         const int q = k * 64 + lane;
         vq[k] = q < n16;
         vq1[k] = q < n16p;
-        wq[k] = (shared_group || q < n16p) ? 4 * q : 3 * HW + 4 * (q - n16p);
+        wq[k] = (uint32_t)((shared_group || q < n16p) ? 16 * q : 3 * HW * (int)sizeof(T) + 16 * (q - n16p));
     }
     // global memory is reached through buffer resources: uniform base, per-lane byte offset 16*lane,
     // uniform chunk offset k*1024 -- no per-lane 64-bit addresses to keep in registers
     const uint32_t voff = (uint32_t)lane * 16u;
-    auto ldg = [&](rsrc_t rs, uint32_t vo, int so) -> f32x4 {
-        return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0));
+    auto ldg = [&](rsrc_t rs, uint32_t vo, int so, float (&v)[E]) {
+        chunk_unpack<T, E>(__builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0), v);
     };
-    auto stg = [&](rsrc_t rs, uint32_t vo, int so, f32x4 v) {
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, vo, so, 0);
+    auto stg = [&](rsrc_t rs, uint32_t vo, int so, const float (&v)[E]) {
+        __builtin_amdgcn_raw_buffer_store_b128(chunk_pack<T, E>(v), rs, vo, so, 0);
     };
-    auto load_pair = [&](const float* base, f32x4 (&st)[NCH]) {
+    auto zero = [&](float (&v)[E]) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) v[e] = 0.f;
+    };
+    auto load_pair = [&](const T* base, float (&st)[NCH][E]) {
         const rsrc_t rs = make_rsrc(base);
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (vq[k]) v = ldg(rs, voff, k * 1024);
-            st[k] = v;
+            zero(st[k]);
+            if (vq[k]) ldg(rs, voff, k * 1024, st[k]);
         }
     };
-    auto load_w = [&](const float* base, f32x4 (&st)[NCH]) {
+    auto load_w = [&](const T* base, float (&st)[NCH][E]) {
         const rsrc_t rs = make_rsrc(base);
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if constexpr (SHARED) { if (vq1[k]) v = ldg(rs, voff, k * 1024); }
-            else { if (vq[k]) v = ldg(rs, (uint32_t)wq[k] * 4u, 0); }
-            st[k] = v;
+            zero(st[k]);
+            if constexpr (SHARED) { if (vq1[k]) ldg(rs, voff, k * 1024, st[k]); }
+            else { if (vq[k]) ldg(rs, wq[k], 0, st[k]); }
         }
     };
-    auto to_lds = [&](f32a* buf, const f32x4 (&st)[NCH], bool one_plane) {
+    // flat fp32 planes in LDS: chunk q sits at floats [E*q, E*q + E)
+    auto lds_put = [&](f32a* buf, int q, const float (&v)[E]) {
+#pragma unroll
+        for (int j = 0; j < E / 4; ++j) {
+            const f32x4 t = {v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
+            *(f32x4a*)(buf + E * q + 4 * j) = t;
+        }
+    };
+    auto lds_get = [&](const f32a* buf, int q, float (&v)[E]) {
+#pragma unroll
+        for (int j = 0; j < E / 4; ++j) {
+            const f32x4 t = *(const f32x4a*)(buf + E * q + 4 * j);
+            v[4 * j] = t.x; v[4 * j + 1] = t.y; v[4 * j + 2] = t.z; v[4 * j + 3] = t.w;
+        }
+    };
+    auto to_lds = [&](f32a* buf, const float (&st)[NCH][E], bool one_plane) {
 #pragma unroll
         for (int k = 0; k < NCH; ++k)
-            if (one_plane ? vq1[k] : vq[k]) *(f32x4a*)(buf + 4 * (k * 64 + lane)) = st[k];
+            if (one_plane ? vq1[k] : vq[k]) lds_put(buf, k * 64 + lane, st[k]);
     };
 
     // the wave's pairs start with gx = 0
     for (int pair = wave; pair < pairs; pair += a.nwaves) {
         f32a* tp = tile + (size_t)2 * pair * HW;
-        const f32x4a z = {0.f, 0.f, 0.f, 0.f};
+        float z[E];
+        zero(z);
 #pragma unroll
         for (int k = 0; k < NCH; ++k)
-            if (vq[k]) *(f32x4a*)(tp + 4 * (k * 64 + lane)) = z;
+            if (vq[k]) lds_put(tp, k * 64 + lane, z);
     }
 
     for (int d = 0; d < 4; ++d) {
@@ -150,29 +193,37 @@ __global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPla
             const size_t pc = ((size_t)b * p.C + c0) * HW;
             const int g = c0 / p.cpg;
             const size_t wg = ((size_t)b * p.G + g) * 3 * HW;
-            const float* gyp = (const float*)p.gy + pc;
-            const float* xp = (const float*)p.x + pc;
-            const float* lp = (const float*)p.lam + slot_c + pc;
-            const float* up = (const float*)p.u + slot_c + pc;
-            const float* hp = (const float*)p.hs + out_c + pc;
-            const float* wp = (const float*)p.w + slot_w + wg;
-            const rsrc_t glb = make_rsrc((float*)p.glam + out_c + pc);
-            const rsrc_t gub = make_rsrc((float*)p.gu + out_c + pc);
-            float* gwp = (float*)p.gw + out_w + wg;
+            const T* gyp = (const T*)p.gy + pc;
+            const T* xp = (const T*)p.x + pc;
+            const T* lp = (const T*)p.lam + slot_c + pc;
+            const T* up = (const T*)p.u + slot_c + pc;
+            const T* hp = (const T*)p.hs + out_c + pc;
+            const T* wp = (const T*)p.w + slot_w + wg;
+            const rsrc_t glb = make_rsrc((T*)p.glam + out_c + pc);
+            const rsrc_t gub = make_rsrc((T*)p.gu + out_c + pc);
+            T* gwp = (T*)p.gw + out_w + wg;
 
-            f32x4 sa[NCH], sb[NCH], sc[NCH];
+            float sa[NCH][E], sb[NCH][E], sc[NCH][E];
             load_pair(gyp, sa);
             load_pair(hp, sb);
             load_pair(up, sc);
             // gu = gy*h in the flat layout; h goes to LDS for the weight gradients
 #pragma unroll
-            for (int k = 0; k < NCH; ++k)
-                if (vq[k]) stg(gub, voff, k * 1024, sa[k] * sb[k]);
+            for (int k = 0; k < NCH; ++k) {
+                if (vq[k]) {
+                    float t[E];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) t[e] = sa[k][e] * sb[k][e];
+                    stg(gub, voff, k * 1024, t);
+                }
+            }
             to_lds(bufH, sb, false);
             load_w(wp, sb);                                     // w0
             // seed u*gy, flat -> per-lane line positions
 #pragma unroll
-            for (int k = 0; k < NCH; ++k) sc[k] = sc[k] * sa[k];
+            for (int k = 0; k < NCH; ++k)
+#pragma unroll
+                for (int e = 0; e < E; ++e) sc[k][e] *= sa[k][e];
             to_lds(bufX, sc, false);
             load_w(wp + HW, sa);                                // w1
             float e[SMAX];
@@ -237,10 +288,14 @@ __global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPla
 #pragma unroll
             for (int k = 0; k < NCH; ++k) {
                 if (vq[k]) {
-                    const int o = 4 * (k * 64 + lane);
-                    const f32x4 ef = *(const f32x4a*)(bufX + o);
-                    stg(glb, voff, k * 1024, sb[k] * ef);
-                    *(f32x4a*)(tp + o) = *(const f32x4a*)(tp + o) + sa[k] * ef;
+                    const int q = k * 64 + lane;
+                    float ef[E], acc[E], gl[E];
+                    lds_get(bufX, q, ef);
+                    lds_get(tp, q, acc);
+#pragma unroll
+                    for (int j = 0; j < E; ++j) { gl[j] = sb[k][j] * ef[j]; acc[j] = fmaf(sa[k][j], ef[j], acc[j]); }
+                    stg(glb, voff, k * 1024, gl);
+                    lds_put(tp, q, acc);
                 }
             }
             if constexpr (!SHARED) {
@@ -265,8 +320,13 @@ __global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPla
                     }
                     const rsrc_t gwb = make_rsrc(gwp + t * HW);
 #pragma unroll
-                    for (int k = 0; k < NCH; ++k)
-                        if (vq[k]) stg(gwb, (uint32_t)wq[k] * 4u, 0, *(const f32x4a*)(bufX + 4 * (k * 64 + lane)));
+                    for (int k = 0; k < NCH; ++k) {
+                        if (vq[k]) {
+                            float v[E];
+                            lds_get(bufX, k * 64 + lane, v);
+                            stg(gwb, wq[k], 0, v);
+                        }
+                    }
                 }
             }
         }
@@ -274,7 +334,7 @@ __global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPla
         if constexpr (SHARED) {
             // sum over the two halves of each wave, then over the waves (fixed order), one tap at a time
             const int g = c_first / p.cpg;
-            float* gwp = (float*)p.gw + out_w + ((size_t)b * p.G + g) * 3 * HW;
+            T* gwp = (T*)p.gw + out_w + ((size_t)b * p.G + g) * 3 * HW;
 #pragma unroll
             for (int t = 0; t < 3; ++t) {
 #pragma unroll
@@ -286,13 +346,24 @@ __global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPla
                 }
                 lds_barrier();
                 for (int q = threadIdx.x; q < n16p; q += blockDim.x) {
-                    f32x4a acc = *(const f32x4a*)(wave_bufs + 4 * q);
-                    for (int wv = 1; wv < a.nwaves; ++wv) acc += *(const f32x4a*)(wave_bufs + wv * 4 * HW + 4 * q);
-                    float* dst = gwp + t * HW + 4 * q;
-                    if (atomic) {
-                        atomicAdd(dst, acc.x); atomicAdd(dst + 1, acc.y); atomicAdd(dst + 2, acc.z); atomicAdd(dst + 3, acc.w);
+                    float acc[E];
+                    lds_get(wave_bufs, q, acc);
+                    for (int wv = 1; wv < a.nwaves; ++wv) {
+                        float o[E];
+                        lds_get(wave_bufs + wv * 4 * HW, q, o);
+#pragma unroll
+                        for (int j = 0; j < E; ++j) acc[j] += o[j];
+                    }
+                    T* dst = gwp + t * HW + E * q;
+                    if constexpr (sizeof(T) == 4) {
+                        if (atomic) {
+#pragma unroll
+                            for (int j = 0; j < E; ++j) atomicAdd((float*)dst + j, acc[j]);
+                        } else {
+                            *(u32x4*)dst = chunk_pack<T, E>(acc);
+                        }
                     } else {
-                        *(f32x4a*)dst = acc;
+                        *(u32x4*)dst = chunk_pack<T, E>(acc);
                     }
                 }
                 lds_barrier();
@@ -303,10 +374,15 @@ __global__ void __launch_bounds__(SHARED ? 384 : 256, 2) bwd_plane_kernel(BwdPla
     // merged gx of the wave's pairs: written once, coalesced
     for (int pair = wave; pair < pairs; pair += a.nwaves) {
         const f32a* tp = tile + (size_t)2 * pair * HW;
-        const rsrc_t gxb = make_rsrc((float*)p.gx + ((size_t)b * p.C + c_first + 2 * pair) * HW);
+        const rsrc_t gxb = make_rsrc((T*)p.gx + ((size_t)b * p.C + c_first + 2 * pair) * HW);
 #pragma unroll
-        for (int k = 0; k < NCH; ++k)
-            if (vq[k]) stg(gxb, voff, k * 1024, *(const f32x4a*)(tp + 4 * (k * 64 + lane)));
+        for (int k = 0; k < NCH; ++k) {
+            if (vq[k]) {
+                float v[E];
+                lds_get(tp, k * 64 + lane, v);
+                stg(gxb, voff, k * 1024, v);
+            }
+        }
     }
 }
 
@@ -329,9 +405,12 @@ static int plane_waves(int K, int HW, int cap) {
 
 static PlanePlan plan_plane(const BwdParams& p, int dtype) {
     PlanePlan t = {};
-    if (dtype != 0) return t;                                   // fp32 storage only
-    if (p.H < 2 || p.W < 2 || p.H > 32 || p.W > 32 || (p.H * p.W) % 4) return t;
+    const int E = dtype == 0 ? 4 : 8;                           // elements per 16 B of storage
+    if (p.H < 2 || p.W < 2 || p.H > 32 || p.W > 32 || (p.H * p.W) % E) return t;
     const int HW = p.H * p.W;
+    const int m = p.H > p.W ? p.H : p.W;
+    t.smax = m <= 16 ? 16 : (m <= 28 ? 28 : 32);
+    const int cap_shared = t.smax < 32 ? 6 : 4;                 // the 32-step variant needs more registers per wave
     if (p.cpg == 1) {
         t.shared_group = 0; t.gsplit = 1;
         t.K = (p.C % 8 == 0) ? 8 : ((p.C % 4 == 0) ? 4 : 2);
@@ -340,30 +419,41 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
         if (p.cpg % 2) return t;
         t.shared_group = 1; t.gsplit = 1; t.K = p.cpg;
         const bool few = (size_t)p.B * p.G < 256;               // fewer workgroups than compute units
-        if ((plane_lds(t.K, plane_waves(t.K, HW, 6), HW) > (size_t)PLANE_LDS_BUDGET || few) && t.K % 4 == 0) {
+        // a split group adds into gw atomically, which needs fp32 storage
+        if (dtype == 0 && (plane_lds(t.K, plane_waves(t.K, HW, cap_shared), HW) > (size_t)PLANE_LDS_BUDGET || few) && t.K % 4 == 0) {
             t.K /= 2; t.gsplit = 2;
         }
     }
-    t.nwaves = plane_waves(t.K, HW, t.shared_group ? 6 : 4);
+    t.nwaves = plane_waves(t.K, HW, t.shared_group ? cap_shared : 4);
     t.lds = plane_lds(t.K, t.nwaves, HW);
     if (t.lds > (size_t)PLANE_LDS_BUDGET) return t;
     if ((size_t)p.B * (p.C / t.K) > 0x7fffffffull) return t;
-    const int m = p.H > p.W ? p.H : p.W;
-    t.smax = m <= 16 ? 16 : (m <= 28 ? 28 : 32);
     t.ok = true;
     return t;
 }
 
 bool bwd_plane_applicable(const BwdParams& p, int dtype) { return plan_plane(p, dtype).ok; }
 
-template <int SMAX, bool SHARED>
+template <typename T, int SMAX, bool SHARED>
 static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
-    auto k = bwd_plane_kernel<SMAX, SHARED>;
+    auto k = bwd_plane_kernel<T, SMAX, SHARED>;
     hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, PLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_plane_t(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
+    if (t.shared_group) {
+        if (t.smax == 16) return launch_plane<T, 16, true>(a, t, s);
+        if (t.smax == 28) return launch_plane<T, 28, true>(a, t, s);
+        return launch_plane<T, 32, true>(a, t, s);
+    }
+    if (t.smax == 16) return launch_plane<T, 16, false>(a, t, s);
+    if (t.smax == 28) return launch_plane<T, 28, false>(a, t, s);
+    return launch_plane<T, 32, false>(a, t, s);
 }
 
 hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
@@ -383,14 +473,7 @@ hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
             d = d1;
         }
     }
-    if (t.shared_group) {
-        if (t.smax == 16) return launch_plane<16, true>(a, t, s);
-        if (t.smax == 28) return launch_plane<28, true>(a, t, s);
-        return launch_plane<32, true>(a, t, s);
-    }
-    if (t.smax == 16) return launch_plane<16, false>(a, t, s);
-    if (t.smax == 28) return launch_plane<28, false>(a, t, s);
-    return launch_plane<32, false>(a, t, s);
+    return dtype == 0 ? launch_plane_t<float>(a, t, s) : launch_plane_t<bf16_t>(a, t, s);
 }
 
 }  // namespace gspn

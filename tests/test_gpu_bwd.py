@@ -87,6 +87,24 @@ def test_backward_plane_kernel_shapes(shape):
     check_bwd(WL.ScanConfig("bwdplane", B, C, H, W, Gr, "f32", 15, 1.0, 29))
 
 
+# the same kernel in bf16 storage (H*W a multiple of 8; a group is never split: no atomics in bf16)
+PLANE_BWD_BF16_SHAPES = [(2, 8, 28, 28, 8), (2, 16, 28, 28, 2), (1, 12, 16, 32, 3), (3, 32, 2, 4, 32), (2, 4, 32, 32, 2),
+                         (1, 6, 12, 20, 3), (1, 24, 28, 28, 1), (1, 12, 28, 28, 12), (300, 16, 4, 4, 2)]
+
+
+@pytest.mark.parametrize("shape", PLANE_BWD_BF16_SHAPES)
+def test_backward_plane_kernel_shapes_bf16(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 1, 0) == "plane", shape
+    check_bwd(WL.ScanConfig("bwdplane16", B, C, H, W, Gr, "bf16", 15, 1.0, 53))
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 6, 9, 14])
+def test_backward_plane_kernel_direction_masks_bf16(mask):
+    check_bwd(WL.ScanConfig("bwdplane16mask", 2, 8, 28, 28, 2, "bf16", mask, 1.0, 59))
+
+
 @pytest.mark.parametrize("shape", TILE_BWD_SHAPES)
 def test_backward_tile_kernel_shapes(shape):
     import paper_2512_07884_amd as G
@@ -153,6 +171,13 @@ def test_backward_fp32_shapes(shape):
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9])
 def test_backward_direction_masks(mask):
     check_bwd(WL.ScanConfig("bwdmask", 2, 4, 14, 18, 2, "f32", mask, 1.0, 17))
+
+
+def test_backward_generic_kernel_bf16(monkeypatch):
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
+    assert G.gspn_bwd_plan(2, 6, 24, 20, 6, 15, 1, 0) == "generic"
+    check_bwd(WL.ScanConfig("bwdgenbf16", 2, 6, 24, 20, 6, "bf16", 15, 1.0, 19))
 
 
 def test_backward_bf16_per_channel_weights():

@@ -107,7 +107,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
         chunk_unpack<T, E>(__builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0), v);
     };
     auto stg = [&](rsrc_t rs, uint32_t vo, int so, const float (&v)[E]) {
-        __builtin_amdgcn_raw_buffer_store_b128(chunk_pack<T, E>(v), rs, vo, so, 0);
+        st_b128(rs, vo + (uint32_t)so, chunk_pack<T, E>(v));     // whole offset in the vector offset (see st_b128)
     };
     auto zero = [&](float (&v)[E]) {
 #pragma unroll

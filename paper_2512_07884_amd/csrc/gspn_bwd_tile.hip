@@ -1,4 +1,4 @@
-// Backward GSPN scan for small feature maps (fp32 storage, H <= 64, W <= 128): all directions in
+// Backward GSPN scan for small feature maps (fp32 or bf16 storage, H <= 64, W <= 128): all directions in
 // one launch, wave-owned lines in registers, the merged gradient gx accumulated in an fp32 LDS tile.
 //
 // The paper gives timings but no algorithm for the backward pass (Sec. 5.1); this is the chain rule
@@ -34,6 +34,8 @@ struct BwdTileArgs {
     int ph;           // horizontal phases: channels side by side (one image row per lane, H lanes per line)
     int shared_group; // 1: the K channels share one weight group; 0: one weight group per channel
     int gsplit;       // workgroups per weight group (shared_group only); > 1: gw is accumulated atomically
+    int seq_parts;    // > 1: a group is covered by this many launches, one slice of K channels each (bf16 storage)
+    int seq_index;    // which slice this launch covers; slices after the first add onto the stored gw
     int nwaves;
     int est_floats;   // LDS floats per wave for the carried state of its rounds
 };
@@ -52,6 +54,23 @@ __device__ __forceinline__ float slot_sum(float v, int slots, int stride, int la
 __device__ __forceinline__ void gw_out(rsrc_t rs, char* base, uint32_t voff, int so, float v, bool atomic) {
     if (atomic) atomicAdd((float*)(base + so + voff), v);
     else __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, voff, __builtin_amdgcn_readfirstlane(so), 0);
+}
+
+// gw of one line leaves the wave: plain store, or (later launches over the same group) stored value + v
+template <typename T, int V>
+__device__ __forceinline__ void gw_store(rsrc_t rs, uint32_t voff, int so, const float (&v)[V], bool add) {
+    constexpr int NB = V * (int)sizeof(T);
+    uint32_t o[NB / 4];
+    float t[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) t[k] = v[k];
+    if (add) {
+        ld_buf<NB>(rs, voff, so, o);
+#pragma unroll
+        for (int k = 0; k < V; ++k) t[k] += elem<T>(o, k);
+    }
+    pack<T, V>(t, o);
+    st_buf<NB>(rs, voff, so, o);
 }
 
 // ---------------------------------------------------------------------------
@@ -190,11 +209,18 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
                         }
                     }
                     if (!a.shared_group || pl == 0) {
+                        if (sizeof(T) == 4 && atomic) {
 #pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            gw_out(g0b, gwbase, voff_w + 4 * v, sow, gw0[v], atomic);
-                            gw_out(g1b, gwbase + plane_bytes, voff_w + 4 * v, sow, gw1[v], atomic);
-                            gw_out(g2b, gwbase + 2 * plane_bytes, voff_w + 4 * v, sow, gw2[v], atomic);
+                            for (int v = 0; v < V; ++v) {
+                                gw_out(g0b, gwbase, voff_w + 4 * v, sow, gw0[v], true);
+                                gw_out(g1b, gwbase + plane_bytes, voff_w + 4 * v, sow, gw1[v], true);
+                                gw_out(g2b, gwbase + 2 * plane_bytes, voff_w + 4 * v, sow, gw2[v], true);
+                            }
+                        } else {
+                            const bool add = a.seq_index > 0;
+                            gw_store<T, V>(g0b, voff_w, sow, gw0, add);
+                            gw_store<T, V>(g1b, voff_w, sow, gw1, add);
+                            gw_store<T, V>(g2b, voff_w, sow, gw2, add);
                         }
                     }
 #pragma unroll
@@ -226,7 +252,7 @@ struct BwdHorizontal {
     int W, nchunks, rounds, pk0, round_bytes, wround_bytes, tile_round, pitch, ph, H, lane, pl;
     float* trow;
     float* es;
-    bool active, first, last, shared_group, atomic;
+    bool active, first, last, shared_group, atomic, gw_add;
     int in, ir;                    // (chunk, round) of the next item to request
     int m, r;                      // (chunk, round) of the next item to consume
     float wc0, wc1, wc2;           // weights at the previous sweep position (last element of the previous chunk)
@@ -244,7 +270,7 @@ struct BwdHorizontal {
         active = pl < a.ph;
         const int plc = active ? pl : 0, ic = active ? i : 0;
         first = ic == 0; last = ic == H - 1;
-        shared_group = a.shared_group != 0; atomic = a.gsplit > 1;
+        shared_group = a.shared_group != 0; atomic = a.gsplit > 1; gw_add = a.seq_index > 0;
         ph = a.ph; pk0 = pk0_; rounds = rounds_; pitch = a.pitch;
         const size_t planes = (size_t)p.B * p.C, groups = (size_t)p.B * p.G;
         const size_t out_c = (size_t)d * planes * HW, out_w = (size_t)d * groups * 3 * HW;
@@ -294,7 +320,11 @@ struct BwdHorizontal {
         ld_buf<NB>(lb, voff, so, s.l);
         ld_buf<NB>(ub, voff, so, s.u);
         ld_buf<NB>(hb, voff, so, s.h);
-        ld_buf<4>(hb, voff, cn * (int)sizeof(T) + (pk0 + ir) * round_bytes, &s.hm);
+        {
+            const int soh = __builtin_amdgcn_readfirstlane(cn * (int)sizeof(T) + (pk0 + ir) * round_bytes);
+            if constexpr (sizeof(T) == 4) s.hm = __builtin_amdgcn_raw_buffer_load_b32(hb, voff, soh, 0);
+            else s.hm = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(hb, voff, soh, 0) << 16;   // widened: fp32 bits
+        }
         ld_buf<NB>(w0b, voff_w, sow, s.w0);
         ld_buf<NB>(w1b, voff_w, sow, s.w1);
         ld_buf<NB>(w2b, voff_w, sow, s.w2);
@@ -356,10 +386,9 @@ struct BwdHorizontal {
                         atomicAdd((float*)(gwbase + 2 * plane_bytes + sow + voff_w + 4 * ix), gw2[ix]);
                     }
                 } else {
-                    uint32_t o[NR];
-                    pack<T, CS>(gw0, o); st_buf<NB>(g0b, voff_w, sow, o);
-                    pack<T, CS>(gw1, o); st_buf<NB>(g1b, voff_w, sow, o);
-                    pack<T, CS>(gw2, o); st_buf<NB>(g2b, voff_w, sow, o);
+                    gw_store<T, CS>(g0b, voff_w, sow, gw0, gw_add);
+                    gw_store<T, CS>(g1b, voff_w, sow, gw1, gw_add);
+                    gw_store<T, CS>(g2b, voff_w, sow, gw2, gw_add);
                 }
             }
 #pragma unroll
@@ -392,9 +421,10 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
     const int H = p.H, W = p.W, HW = H * W;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int blocks_per_image = p.C / a.K;
+    // one workgroup per K channels; when a group is covered by several launches, this one takes slice seq_index
+    const int blocks_per_image = p.C / (a.K * a.seq_parts);
     const int b = blockIdx.x / blocks_per_image;
-    const int c_first = (blockIdx.x - b * blocks_per_image) * a.K;
+    const int c_first = ((blockIdx.x - b * blocks_per_image) * a.seq_parts + a.seq_index) * a.K;
     float* tile = lds;
     const int tile_floats = a.K * H * a.pitch;
     float* est = lds + tile_floats + wave * a.est_floats;
@@ -494,11 +524,10 @@ hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s) {
 // ---------------------------------------------------------------------------
 static constexpr int BWD_LDS_BUDGET = 160 * 1024;
 
-struct BwdPlan { bool ok; int K, pitch, lplv, pv, ph, shared_group, gsplit, nwaves, est_floats; size_t lds; };
+struct BwdPlan { bool ok; int K, pitch, lplv, pv, ph, shared_group, gsplit, seq_parts, nwaves, est_floats; size_t lds; };
 
 static BwdPlan plan_bwd(const BwdParams& p, int dtype) {
     BwdPlan t = {};
-    if (dtype != 0) return t;                                  // fp32 storage only
     if (p.W % 4 || p.W / 2 > 64 || p.H > 64 || p.H < 2) return t;
     t.pitch = p.W | 1;
     t.lplv = p.W / 2; t.pv = 64 / t.lplv;
@@ -509,7 +538,7 @@ static BwdPlan plan_bwd(const BwdParams& p, int dtype) {
     const size_t hw4 = (size_t)p.H * p.W * 4;
     if (p.cpg == 1) {
         // one weight group per channel: the smallest workgroup that fills the lanes in both phases
-        t.shared_group = 0; t.gsplit = 1;
+        t.shared_group = 0; t.gsplit = 1; t.seq_parts = 1;
         const int K = lcm;
         if (p.C % K) return t;
         const int wv = (K / t.pv) * dirs_v, wh = (K / t.ph) * dirs_h;
@@ -523,9 +552,13 @@ static BwdPlan plan_bwd(const BwdParams& p, int dtype) {
         t.shared_group = 1;
         int K = p.cpg, gs = 1;
         const size_t wgs = (size_t)p.B * p.G;
-        if ((K * per_channel > (size_t)BWD_LDS_BUDGET - 16384 || wgs < 384) && K % (2 * lcm) == 0) { K /= 2; gs = 2; }
+        // a split group adds into gw atomically, which needs fp32 storage
+        if (dtype == 0 && (K * per_channel > (size_t)BWD_LDS_BUDGET - 16384 || wgs < 384) && K % (2 * lcm) == 0) { K /= 2; gs = 2; }
+        // bf16 storage: a group too large for LDS is covered by two launches, the second adding onto gw
+        int seq = 1;
+        if (dtype != 0 && K * per_channel > (size_t)BWD_LDS_BUDGET - 16384 && K % (2 * lcm) == 0) { K /= 2; seq = 2; }
         if (K % lcm || K * per_channel > (size_t)BWD_LDS_BUDGET - 16384) return t;
-        t.K = K; t.gsplit = gs;
+        t.K = K; t.gsplit = gs; t.seq_parts = seq;
         t.nwaves = dirs_v > dirs_h ? dirs_v : dirs_h;
         if (t.nwaves < 1) t.nwaves = 1;
         const int rv = K / t.pv, rh = K / t.ph;
@@ -547,6 +580,7 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     BwdTileArgs a;
     a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.ph = t.ph;
     a.shared_group = t.shared_group; a.gsplit = t.gsplit; a.nwaves = t.nwaves; a.est_floats = t.est_floats;
+    a.seq_parts = t.seq_parts; a.seq_index = 0;
     if (t.gsplit > 1) {
         // gw of the requested directions is accumulated atomically: clear it first, on the same stream
         const size_t per_dir = (size_t)p.B * p.G * 3 * p.H * p.W * sizeof(float);
@@ -559,12 +593,17 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
             d = d1;
         }
     }
-    const dim3 grid((unsigned)((size_t)p.B * (p.C / t.K))), block(64 * t.nwaves);
-    auto k = bwd_tile_kernel<float, 4, 8>;
+    const dim3 grid((unsigned)((size_t)p.B * (p.C / (t.K * t.seq_parts)))), block(64 * t.nwaves);
+    auto k = dtype == 0 ? bwd_tile_kernel<float, 4, 8> : bwd_tile_kernel<bf16_t, 4, 8>;
     hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, BWD_LDS_BUDGET);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
-    return hipGetLastError();
+    for (int part = 0; part < t.seq_parts; ++part) {          // same stream: the launches run one after the other
+        a.seq_index = part;
+        hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace gspn

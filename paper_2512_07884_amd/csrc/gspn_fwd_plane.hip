@@ -63,7 +63,9 @@ struct FwdPlaneArgs {
     int pitch;    // LDS row pitch in floats (odd)
 };
 
-template <typename T, bool SAVE, bool SHARED>
+// WPRE (shared weights): the workgroup has enough threads to hold a direction's weights in registers
+// (WSH chunks per thread), so they are requested a direction ahead; otherwise they are fetched in place.
+template <typename T, bool SAVE, bool SHARED, bool WPRE>
 __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneArgs a) {
     constexpr int E = 16 / (int)sizeof(T);        // elements per 16 B chunk
     constexpr int NCH = 8;                        // chunks per lane: the wave's channels hold at most 8 KB
@@ -128,7 +130,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
     int wl[WSH];          // LDS float offset of the chunk's first element in the weight region (tap included)
     int wrow[WSH], wcol[WSH], wtap[WSH];
     uint32_t wgo[WSH];    // byte offset of the chunk from the group's first weight plane
-    if constexpr (SHARED) {
+    if constexpr (SHARED && WPRE) {
 #pragma unroll
         for (int j = 0; j < WSH; ++j) {
             const int c = (int)threadIdx.x + j * nthreads;
@@ -171,7 +173,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
     u32x4 ls[NCH], us[NCH], wsh[WSH];
     if (d < 4) {
         load_planes((const T*)p.lam + slot_c(d) + pc, ls);
-        if constexpr (SHARED) load_wshare(wptr(d, g), wsh);
+        if constexpr (SHARED && WPRE) load_wshare(wptr(d, g), wsh);
     }
 
     while (d < 4) {
@@ -191,22 +193,23 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         // ---- operands into LDS
         if constexpr (SHARED) {
             lds_barrier();                                 // every wave is done with the previous direction's weights
+            if constexpr (WPRE) {
 #pragma unroll
-            for (int j = 0; j < WSH; ++j) {
-                if (wv[j]) {
+                for (int j = 0; j < WSH; ++j) {
+                    if (wv[j]) {
 #pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        // a tap that points outside the line is stored as 0, whatever the tensor holds there
-                        const int pos = vert ? wcol[j] + e : wrow[j];
-                        const bool outside = (wtap[j] == 0 && pos == 0) || (wtap[j] == 2 && pos == L - 1);
-                        plds_st(wreg + 4u * (uint32_t)(wl[j] + 4 * e), outside ? 0.f : chunk_elem<T>(wsh[j], e));
+                        for (int e = 0; e < E; ++e) {
+                            // a tap that points outside the line is stored as 0, whatever the tensor holds there
+                            const int pos = vert ? wcol[j] + e : wrow[j];
+                            const bool outside = (wtap[j] == 0 && pos == 0) || (wtap[j] == 2 && pos == L - 1);
+                            plds_st(wreg + 4u * (uint32_t)(wl[j] + 4 * e), outside ? 0.f : chunk_elem<T>(wsh[j], e));
+                        }
                     }
                 }
-            }
-            // small workgroups: the chunks beyond WSH per thread are fetched here, without the head start
-            if (3 * n16p > WSH * nthreads) {
+            } else {
+                // small workgroups: fetched here, without the head start
                 const rsrc_t rs = make_rsrc(wptr(d, g));
-                for (int c = (int)threadIdx.x + WSH * nthreads; c < 3 * n16p; c += nthreads) {
+                for (int c = (int)threadIdx.x; c < 3 * n16p; c += nthreads) {
                     const int tap = c / n16p;
                     const int idx0 = (c - tap * n16p) * E;
                     const int row = idx0 / W, col = idx0 - row * W;
@@ -258,7 +261,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         load_planes((const T*)p.u + slot_c(d) + pc, us);
         if (dn < 4) {
             load_planes((const T*)p.lam + slot_c(dn) + pc, ls);
-            if constexpr (SHARED) load_wshare(wptr(dn, g), wsh);
+            if constexpr (SHARED && WPRE) load_wshare(wptr(dn, g), wsh);
         }
         if constexpr (SHARED) lds_barrier();               // weights of this direction are in place (LDS only: the
                                                            // requests above stay in flight across the barrier)
@@ -299,7 +302,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                         hv[e] = plds_ld(o + 4u * e);
                         y[k][e] = fmaf(chunk_elem<T>(us[k], e), hv[e], y[k][e]);
                     }
-                    if constexpr (SAVE) __builtin_amdgcn_raw_buffer_store_b128(chunk_pack<T>(hv), hb, flat, k * 1024, 0);
+                    if constexpr (SAVE) st_b128(hb, flat + k * 1024, chunk_pack<T>(hv));
                 }
             }
         }
@@ -311,7 +314,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         const rsrc_t yb = make_rsrc((T*)p.y + pc);
 #pragma unroll
         for (int k = 0; k < NCH; ++k)
-            if (vq[k]) __builtin_amdgcn_raw_buffer_store_b128(chunk_pack<T>(y[k]), yb, flat, k * 1024, 0);
+            if (vq[k]) st_b128(yb, flat + k * 1024, chunk_pack<T>(y[k]));
     }
 }
 
@@ -364,14 +367,25 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
 
 bool fwd_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane(p, dtype).ok; }
 
-template <typename T, bool SAVE, bool SHARED>
-static hipError_t launch_fplane(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
-    auto k = fwd_plane_kernel<T, SAVE, SHARED>;
+template <typename T, bool SAVE, bool SHARED, bool WPRE>
+static hipError_t launch_fplane_k(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE>;
     hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, FPLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();
+}
+
+template <typename T, bool SAVE, bool SHARED>
+static hipError_t launch_fplane(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    if constexpr (SHARED) {
+        const int E = 16 / (int)sizeof(T);
+        const bool wpre = 3 * (a.p.H * a.p.W / E) <= 4 * 64 * a.nwaves;   // WSH chunks per thread
+        return wpre ? launch_fplane_k<T, SAVE, true, true>(a, t, s) : launch_fplane_k<T, SAVE, true, false>(a, t, s);
+    } else {
+        return launch_fplane_k<T, SAVE, false, false>(a, t, s);
+    }
 }
 
 template <typename T>

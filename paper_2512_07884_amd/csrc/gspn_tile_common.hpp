@@ -29,15 +29,25 @@ template <int NB> __device__ __forceinline__ void ld_buf(rsrc_t rs, uint32_t vof
         }
     }
 }
+// A store of more than 8 bytes must not be followed directly by a VALU write of its data registers.
+// The compiler inserts the wait state only when the store's scalar offset is not a register (measured
+// on gfx950: with an SGPR offset and the data registers rewritten by the next instruction, the upper
+// half of the stored 16 B was corrupted now and then).  16 B stores therefore carry their whole
+// offset in the vector offset and pass 0 as the scalar one.
+__device__ __forceinline__ void st_b128(rsrc_t rs, uint32_t voff, u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff, 0, 0);
+}
 template <int NB> __device__ __forceinline__ void st_buf(rsrc_t rs, uint32_t voff, int soff, const uint32_t* r) {
-    soff = __builtin_amdgcn_readfirstlane(soff);
-    if constexpr (NB == 4) { __builtin_amdgcn_raw_buffer_store_b32(r[0], rs, voff, soff, 0); }
-    else if constexpr (NB == 8) { u32x2 v = {r[0], r[1]}; __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, soff, 0); }
-    else {
+    if constexpr (NB == 4) { __builtin_amdgcn_raw_buffer_store_b32(r[0], rs, voff, __builtin_amdgcn_readfirstlane(soff), 0); }
+    else if constexpr (NB == 8) {
+        u32x2 v = {r[0], r[1]};
+        __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, __builtin_amdgcn_readfirstlane(soff), 0);
+    } else {
+        const uint32_t vo = voff + (uint32_t)soff;
 #pragma unroll
         for (int i = 0; i < NB / 16; ++i) {
             u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
-            __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff + 16 * i, soff, 0);
+            st_b128(rs, vo + 16 * i, v);
         }
     }
 }

@@ -105,6 +105,20 @@ def test_backward_plane_kernel_direction_masks_bf16(mask):
     check_bwd(WL.ScanConfig("bwdplane16mask", 2, 8, 28, 28, 2, "bf16", mask, 1.0, 59))
 
 
+@pytest.mark.parametrize("shape", [(2, 8, 56, 56, 2), (1, 4, 56, 56, 4), (1, 8, 64, 128, 2), (1, 24, 16, 40, 2), (2, 8, 40, 32, 8),
+                                   (2, 12, 56, 56, 1)])
+def test_backward_tile_kernel_shapes_bf16(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 1, 0) == "tile", shape
+    check_bwd(WL.ScanConfig("bwdtile16", B, C, H, W, Gr, "bf16", 15, 1.0, 61))
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 6, 9])
+def test_backward_tile_kernel_direction_masks_bf16(mask):
+    check_bwd(WL.ScanConfig("bwdtile16mask", 1, 8, 40, 32, 2, "bf16", mask, 1.0, 67))
+
+
 @pytest.mark.parametrize("shape", TILE_BWD_SHAPES)
 def test_backward_tile_kernel_shapes(shape):
     import paper_2512_07884_amd as G

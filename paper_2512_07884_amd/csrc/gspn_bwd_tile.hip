@@ -237,11 +237,10 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
 
 // ---------------------------------------------------------------------------
 // horizontal directions: lines are image columns, one image row per lane, the sweep is read in
-// chunks of 4 columns (16 B of fp32 per row and tensor)
+// chunks of CS columns (16 B per row and tensor: 4 of fp32, 8 of bf16; 4 of bf16 for odd widths)
 // ---------------------------------------------------------------------------
-template <typename T, bool REV>
+template <typename T, bool REV, int CS>
 struct BwdHorizontal {
-    static constexpr int CS = 4;
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
     struct Item { uint32_t gy[NR], x[NR], l[NR], u[NR], h[NR], w0[NR], w1[NR], w2[NR], hm; };
@@ -414,7 +413,7 @@ struct BwdHorizontal {
     }
 };
 
-template <typename T, int PF, int MAXW>
+template <typename T, int PF, int MAXW, int HCS>
 __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
     extern __shared__ float lds[];
     const BwdParams& p = a.p;
@@ -460,12 +459,12 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
         const int dsel = a.shared_group ? wave : wave - slot * nd;
         const int d = (nd == 2) ? 2 + dsel : (has_lr ? 2 : 3);
         const int rounds = a.shared_group ? packs_h : 1;
-        const int nchunks = W / 4;
+        const int nchunks = W / HCS;
         const int half_lr = (nchunks + 1) / 2, half_rl = nchunks - half_lr;
         if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
-            BwdHorizontal<T, false> hp;
+            BwdHorizontal<T, false, HCS> hp;
             if (busy) { hp.init(a, tile, est, 2, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_lr : nchunks) * rounds);
@@ -474,7 +473,7 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
                 if (busy) hp.run(half_lr * rounds, nchunks * rounds);
             }
         } else {
-            BwdHorizontal<T, true> hp;
+            BwdHorizontal<T, true, HCS> hp;
             if (busy) { hp.init(a, tile, est, 3, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_rl : nchunks) * rounds);
@@ -594,7 +593,10 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
         }
     }
     const dim3 grid((unsigned)((size_t)p.B * (p.C / (t.K * t.seq_parts)))), block(64 * t.nwaves);
-    auto k = dtype == 0 ? bwd_tile_kernel<float, 4, 8> : bwd_tile_kernel<bf16_t, 4, 8>;
+    // horizontal phases read 16 B per row and request: 4 columns of fp32, 8 of bf16 when the width allows
+    const bool wide = dtype != 0 && p.W % 8 == 0;
+    auto k = dtype == 0 ? bwd_tile_kernel<float, 4, 8, 4>
+                        : (wide ? bwd_tile_kernel<bf16_t, 4, 8, 8> : bwd_tile_kernel<bf16_t, 4, 8, 4>);
     hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, BWD_LDS_BUDGET);
     if (e != hipSuccess) return e;
     for (int part = 0; part < t.seq_parts; ++part) {          // same stream: the launches run one after the other

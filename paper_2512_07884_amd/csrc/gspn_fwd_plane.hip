@@ -285,6 +285,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
             };
             // four steps per trip: their operand reads do not depend on h and are issued together
             int s = 1;
+            for (; s + 7 < S; s += 8) { step(); step(); step(); step(); step(); step(); step(); step(); }
             for (; s + 3 < S; s += 4) { step(); step(); step(); step(); }
             for (; s < S; ++s) step();
         }

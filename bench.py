@@ -9,7 +9,7 @@ or ``gspn_scan_fwd`` (saving h) + ``gspn_scan_bwd`` (training workloads).
 Inputs are resident in HBM before the timed region; buffer sets are rotated so
 that consecutive steps do not find their inputs in the 256 MB last-level cache.
 Prints ONE JSON line (see the keys below); ``--all`` additionally writes a table
-for every workload to gpurun_out/bench_all.json.
+for every workload to <out>/bench_all.json (see --out).
 """
 from __future__ import annotations
 
@@ -227,7 +227,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
-    ap.add_argument("--all", action="store_true", help="also time every other workload (table in gpurun_out/)")
+    ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
+    ap.add_argument("--out", default="gpurun_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain 1 GiB device-to-device copies (known traffic, for scaling profiler counters)")
@@ -280,8 +281,8 @@ def main():
             k = max(20, a.steps // (8 if c.pixel_channels > 1e8 else 1))
             table.append(summarise(c, run_workload(c, k, a.warmup)))
             print(f"[bench] {name} done", file=sys.stderr, flush=True)
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
+        os.makedirs(os.path.join(ROOT, a.out), exist_ok=True)
+        with open(os.path.join(ROOT, a.out, "bench_all.json"), "w") as f:
             json.dump(table, f, indent=1)
         line["all_workloads"] = [{k: t[k] for k in t if k in (
             "workload", "step", "ms_per_step", "gpixel_ch_per_s", "fwd_ms_avg", "fwd_algorithmic_GBs",

@@ -593,10 +593,12 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
         }
     }
     const dim3 grid((unsigned)((size_t)p.B * (p.C / (t.K * t.seq_parts)))), block(64 * t.nwaves);
-    // horizontal phases read 16 B per row and request: 4 columns of fp32, 8 of bf16 when the width allows
-    const bool wide = dtype != 0 && p.W % 8 == 0;
-    auto k = dtype == 0 ? bwd_tile_kernel<float, 4, 8, 4>
-                        : (wide ? bwd_tile_kernel<bf16_t, 4, 8, 8> : bwd_tile_kernel<bf16_t, 4, 8, 4>);
+    // horizontal phases read 8 columns per row and request when the width allows (bf16: 16 B; fp32: 32 B, which
+    // needs more registers than 8 waves per workgroup leave, so only workgroups of up to 4 waves take it)
+    const bool wide = p.W % 8 == 0;
+    void (*k)(BwdTileArgs);
+    if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8> : bwd_tile_kernel<float, 4, 8, 4>;
+    else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8> : bwd_tile_kernel<bf16_t, 4, 8, 4>;
     hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, BWD_LDS_BUDGET);
     if (e != hipSuccess) return e;
     for (int part = 0; part < t.seq_parts; ++part) {          // same stream: the launches run one after the other

@@ -71,6 +71,26 @@ def test_plan_names(lib):
     assert lib.gspn_bwd_plan(32, 192, 28, 28, 4, 15, 0, 0).decode() != "invalid"
 
 
+def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
+    """Host-side dispatch only: which kernel family each workload of the benchmark runs on."""
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_TILE_K", "GSPN_TILE_HV"):
+        monkeypatch.delenv(v, raising=False)
+    fwd = lambda *a: lib.gspn_fwd_plan(*a).decode()
+    bwd = lambda *a: lib.gspn_bwd_plan(*a).decode()
+    assert fwd(1, 8, 16, 16, 1, 1, 0, 0, 0) == "plane"                       # unit16
+    assert fwd(64, 96, 56, 56, 8, 15, 1, 0, 0) == "plane"                    # cls56
+    assert fwd(2, 1024, 128, 128, 16, 15, 1, 0, 0) == "tile"                 # diff128
+    assert fwd(1, 512, 512, 512, 16, 15, 1, 0, 0) == "stream"                # long512
+    assert fwd(1, 512, 256, 1024, 16, 15, 1, 0, 0) == "stream"               # long256x1024
+    for G in (192, 4):                                                        # train28_gc / train28_g4
+        assert fwd(32, 192, 28, 28, G, 15, 0, 0, 1) == "plane"
+        assert bwd(32, 192, 28, 28, G, 15, 0, 0) == "plane"
+    assert bwd(64, 96, 56, 56, 8, 15, 1, 0) == "tile" and bwd(64, 96, 56, 56, 8, 15, 0, 0) == "tile"
+    assert bwd(2, 1024, 128, 128, 16, 15, 1, 0) == "generic"                 # no fast backward beyond 64 lines
+    monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
+    assert fwd(64, 96, 56, 56, 8, 15, 1, 0, 0) == "generic" and bwd(32, 192, 28, 28, 4, 15, 0, 0) == "generic"
+
+
 def test_binding_refuses_cpu_tensors_and_missing_library(monkeypatch):
     import torch
     from paper_2512_07884_amd import binding

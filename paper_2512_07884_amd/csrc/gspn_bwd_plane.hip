@@ -87,7 +87,6 @@ bwd_plane_kernel(BwdPlaneArgs a) {
     float* wave_bufs = lds + a.K * HW;                         // per wave: X (two planes), H (two planes), fp32
     f32a* bufX = wave_bufs + wave * 4 * HW;
     f32a* bufH = bufX + 2 * HW;
-    const int xoff = 4 * (a.K * HW + wave * 4 * HW), hoff = xoff + 8 * HW;   // the same, as byte offsets in LDS
 
     // chunk q = k*64 + lane of a contiguous pair of planes covers elements [E*q, E*q + E)
     bool vq[NCH];        // chunk inside the pair
@@ -437,7 +436,7 @@ bool bwd_plane_applicable(const BwdParams& p, int dtype) { return plan_plane(p, 
 template <typename T, int SMAX, bool SHARED>
 static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
     auto k = bwd_plane_kernel<T, SMAX, SHARED>;
-    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, PLANE_LDS_BUDGET);
+    hipError_t e = allow_dynamic_lds((const void*)k, PLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);

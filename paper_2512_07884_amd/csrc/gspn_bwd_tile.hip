@@ -599,7 +599,7 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     void (*k)(BwdTileArgs);
     if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8> : bwd_tile_kernel<float, 4, 8, 4>;
     else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8> : bwd_tile_kernel<bf16_t, 4, 8, 4>;
-    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, BWD_LDS_BUDGET);
+    hipError_t e = allow_dynamic_lds((const void*)k, BWD_LDS_BUDGET);
     if (e != hipSuccess) return e;
     for (int part = 0; part < t.seq_parts; ++part) {          // same stream: the launches run one after the other
         a.seq_index = part;

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <mutex>
 
 namespace gspn {
 
@@ -55,6 +56,26 @@ struct BwdParams {
     unsigned mask;
     int shared;
 };
+
+// Raises a kernel's dynamic-LDS limit (up to the 160 KB of a gfx950 CU) once per (kernel, device).
+// Later calls are a table lookup, so that a launch made while the stream is being captured issues
+// no attribute call.  Host only.
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes) {
+    struct Seen { const void* kernel; int device; };
+    static Seen seen[512];
+    static int n = 0;
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> guard(mu);
+    for (int i = 0; i < n; ++i)
+        if (seen[i].kernel == kernel && seen[i].device == dev) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    if (n < 512) seen[n++] = Seen{kernel, dev};
+    return hipSuccess;
+}
 
 // launchers implemented by the kernel files; return hipError_t of the launch
 hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s);

@@ -371,7 +371,7 @@ bool fwd_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane
 template <typename T, bool SAVE, bool SHARED, bool WPRE>
 static hipError_t launch_fplane_k(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
     auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE>;
-    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, FPLANE_LDS_BUDGET);
+    hipError_t e = allow_dynamic_lds((const void*)k, FPLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);

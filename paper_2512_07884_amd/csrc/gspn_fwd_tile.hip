@@ -604,7 +604,7 @@ template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MA
 static hipError_t launch_one(const TileArgs& a, const TilePlan& t, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * t.nwaves);
     auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW>;
-    hipError_t e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BUDGET);
+    hipError_t e = allow_dynamic_lds((const void*)k, LDS_BUDGET);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();

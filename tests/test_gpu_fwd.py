@@ -233,3 +233,23 @@ def test_tile_kernel_on_shapes_the_plane_kernel_normally_takes(shape, monkeypatc
     cfg = WL.ScanConfig("fwdtile2", B, C, H, W, Gr, dtype, 15, 1.0, 43)
     check_case(cfg)
     check_case(cfg, save_h=False)
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 2, 16384), (1, 2, 16384, 2)], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_longest_supported_line(shape, dtype):
+    """GSPN_MAX_LINE positions per line / lines per scan (generic kernel).  In fp32 storage the bound on the
+    error of S sequential fp32 steps with non-expanding weights is S * 2^-24 (1e-3 here), which replaces the
+    1e-5 of the short scans.  In bf16 storage this kernel rounds the running sum of the directions once per
+    direction (2^-9 each), relative to partial sums that may exceed the final maximum: 2e-2 here."""
+    import paper_2512_07884_amd as G
+    B, C, H, W = shape
+    assert G.gspn_fwd_plan(B, C, H, W, 1, 15, int(dtype == "bf16"), 0, False) == "generic"
+    cfg = WL.ScanConfig("maxline", B, C, H, W, 1, dtype, 15, 1.0, 73)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    f = WL.inputs_as_f64(inp, dtype)
+    y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
+    y, *_ = run_fwd_gpu(inp, cfg, 15)
+    tol = 2e-2 if dtype == "bf16" else max(TOL["f32"], 16384 * 2.0 ** -24)
+    assert np.all(np.isfinite(y))
+    assert rel_inf_err(y, y_ref) <= tol

@@ -16,6 +16,12 @@
 // registers; with channel-shared weights (Sec. 4.2) the three weight planes of a direction are
 // loaded ONCE per workgroup into LDS and read by all its channels; every request is a complete
 // cache line.  Rows in LDS have an odd pitch so that both access orientations are conflict-free.
+//
+// Maps whose rows are not whole 16 B chunks (7x7, 14x14, 28x28 bf16: the later stages of a classifier) take
+// the FLAT variant: LDS planes without padding, so that a chunk's place in LDS is its place in memory and
+// chunks may run over row and channel ends; 2, 4 or 8 channels side by side in a wave (32, 16 or 8 lanes
+// each) so that the wave's channels together are whole chunks; weights fetched in the widest pieces their
+// alignment allows.
 #include "gspn_tile_common.hpp"
 #include <stdlib.h>
 
@@ -58,26 +64,30 @@ template <typename T> __device__ __forceinline__ u32x4 chunk_pack(const float* v
 struct FwdPlaneArgs {
     FwdParams p;
     int K;        // channels per workgroup
-    int cpw;      // channels per wave: 2 when a line fits in 32 lanes, else 1
+    int cpw;      // channels per wave (1, 2, 4 or 8): each takes 64 / cpw lanes
+    int lsh;      // log2 of the lanes per channel
     int nwaves;
-    int pitch;    // LDS row pitch in floats (odd)
+    int pitch;    // LDS row pitch in floats (odd; W in the flat variant)
+    int wlw;      // flat variant, shared weights: bytes per weight request (16, 8, 4 or 2)
 };
 
 // WPRE (shared weights): the workgroup has enough threads to hold a direction's weights in registers
 // (WSH chunks per thread), so they are requested a direction ahead; otherwise they are fetched in place.
-template <typename T, bool SAVE, bool SHARED, bool WPRE>
+// FLAT: planes in LDS are unpadded and the wave's channels contiguous (see the head of the file).
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT>
 __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneArgs a) {
+    static_assert(!(FLAT && WPRE), "the flat variant fetches its weights in place");
     constexpr int E = 16 / (int)sizeof(T);        // elements per 16 B chunk
     constexpr int NCH = 8;                        // chunks per lane: the wave's channels hold at most 8 KB
     constexpr int WSH = 4;                        // weight chunks per thread (shared weights)
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W, P = a.pitch;
-    const int HP = (H * P + 3) & ~3;                   // floats per plane region in LDS (16 B granules)
+    const int HP = FLAT ? HW : (H * P + 3) & ~3;       // floats per plane region in LDS (16 B granules when padded)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cpw = a.cpw;
-    const int half = cpw == 2 ? lane >> 5 : 0;
-    const int i = cpw == 2 ? lane & 31 : lane;
+    const int half = lane >> a.lsh;                    // which of the wave's channels this lane works on
+    const int i = lane & ((1 << a.lsh) - 1);           // position on the line
     const int wgs_per_image = p.C / a.K;
     const unsigned item = xcd_contiguous_item(blockIdx.x, gridDim.x);
     const int b = item / wgs_per_image;
@@ -106,11 +116,15 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         const int q = k * 64 + lane;
         vq[k] = q < n16;
         const int idx0 = vq[k] ? q * E : 0;
-        ch[k] = idx0 >= HW ? 1 : 0;
-        const int rem = idx0 - ch[k] * HW;
-        const int row = rem / W;
-        rc[k] = row * P + (rem - row * W);
-        row0[k] = row; col0[k] = rem - row * W;
+        if constexpr (FLAT) {
+            ch[k] = 0; rc[k] = idx0; row0[k] = 0; col0[k] = 0;     // LDS offset = offset in memory
+        } else {
+            ch[k] = idx0 >= HW ? 1 : 0;
+            const int rem = idx0 - ch[k] * HW;
+            const int row = rem / W;
+            rc[k] = row * P + (rem - row * W);
+            row0[k] = row; col0[k] = rem - row * W;
+        }
     }
     const uint32_t flat = (uint32_t)lane * 16u;
     auto ldg = [&](rsrc_t rs, uint32_t vo, int so) -> u32x4 { return __builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0); };
@@ -191,7 +205,42 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         const int tpos = ic * ps + s0;
 
         // ---- operands into LDS
-        if constexpr (SHARED) {
+        if constexpr (FLAT) {
+            if constexpr (SHARED) lds_barrier();           // every wave is done with the previous direction's weights
+            // The block to bring in: the group's three planes (the threads of the workgroup share the work) or
+            // the three planes of each of the wave's channels, which are contiguous in memory.  A request may run
+            // over the end of a row, a plane or a channel: the place of every element is tracked on its own.
+            const int nel = SHARED ? 3 * HW : cpw * 3 * HW;
+            const int lw = SHARED ? a.wlw : 16;
+            const int ew = lw / (int)sizeof(T);            // elements per request; divides nel (host)
+            const int t0 = SHARED ? (int)threadIdx.x : lane, tn = SHARED ? nthreads : 64;
+            const rsrc_t rs = make_rsrc(wptr(d, SHARED ? g : c0));
+            for (int c = t0; c * ew < nel; c += tn) {
+                const int idx0 = c * ew;
+                const uint32_t bo = (uint32_t)(idx0 * (int)sizeof(T));
+                u32x4 v = {0, 0, 0, 0};
+                if (lw == 16) v = ldg(rs, bo, 0);
+                else if (lw == 8) { const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, bo, 0, 0); v[0] = t.x; v[1] = t.y; }
+                else if (lw == 4) v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, bo, 0, 0);
+                else v[0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, bo, 0, 0);
+                int chn = idx0 / (3 * HW);
+                int r = idx0 - chn * 3 * HW;
+                int tap = r / HW;
+                r -= tap * HW;
+                int row = r / W, col = r - row * W;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    if (e < ew) {
+                        // a tap that points outside the line is stored as 0, whatever the tensor holds there
+                        const int pos = vert ? col : row;
+                        const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1);
+                        plds_st(wreg + 4u * (uint32_t)(chn * 4 * HP + 4 * (row * W + col) + tap),
+                                outside ? 0.f : chunk_elem<T>(v, e));
+                        if (++col == W) { col = 0; if (++row == H) { row = 0; if (++tap == 3) { tap = 0; ++chn; } } }
+                    }
+                }
+            }
+        } else if constexpr (SHARED) {
             lds_barrier();                                 // every wave is done with the previous direction's weights
             if constexpr (WPRE) {
 #pragma unroll
@@ -324,32 +373,20 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
 // ---------------------------------------------------------------------------
 static constexpr int FPLANE_LDS_BUDGET = 160 * 1024;
 
-struct FwdPlanePlan { bool ok; int K, cpw, nwaves, pitch, shared_group; size_t lds; };
+struct FwdPlanePlan { bool ok, flat; int K, cpw, lsh, nwaves, pitch, shared_group, wlw; size_t lds; };
 
-static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
-    FwdPlanePlan t = {};
-    const int es = dtype == 0 ? 4 : 2, E = 16 / es;
-    if (p.H < 2 || p.W < 2 || p.H > 64 || p.W > 64 || p.W % E) return t;
-    const int HW = p.H * p.W;
-    const int m = p.H > p.W ? p.H : p.W;
-    t.cpw = m <= 32 ? 2 : 1;
-    if ((size_t)t.cpw * HW * es > 8192) {
-        if (t.cpw == 2 && (size_t)HW * es <= 8192) t.cpw = 1; else return t;
-    }
-    t.pitch = p.W | 1;
-    const size_t hp = (((size_t)p.H * t.pitch + 3) & ~(size_t)3) * sizeof(float);   // one plane region in LDS
+// waves per workgroup and LDS bytes, given the channels per wave and the bytes of one fp32 plane region
+static bool plan_fwd_plane_waves(const FwdParams& p, FwdPlanePlan& t, size_t hp) {
     if (p.cpg == 1) {
         t.shared_group = 0;
-        if (p.C % t.cpw) { if (t.cpw == 2) t.cpw = 1; }
-        // per wave: cpw * 4 planes; aim at 4 waves per workgroup
+        // per wave: cpw * (4 weight + 1 a/h) planes; aim at 4 waves per workgroup
         int nw = 4;
         while (nw > 1 && (p.C % (nw * t.cpw) || (size_t)nw * t.cpw * 5 * hp > (size_t)FPLANE_LDS_BUDGET)) --nw;
-        if (p.C % (nw * t.cpw) || (size_t)nw * t.cpw * 5 * hp > (size_t)FPLANE_LDS_BUDGET) return t;
+        if (p.C % (nw * t.cpw) || (size_t)nw * t.cpw * 5 * hp > (size_t)FPLANE_LDS_BUDGET) return false;
         t.nwaves = nw; t.K = nw * t.cpw;
         t.lds = (size_t)nw * t.cpw * 5 * hp;
     } else {
         t.shared_group = 1;
-        if (p.cpg % t.cpw) t.cpw = 1;
         // the most waves (up to 8) whose channels divide the group and whose planes fit beside the weights
         int nw = 8;
         for (; nw >= 1; --nw) {
@@ -357,20 +394,57 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
             if ((4 + (size_t)nw * t.cpw) * hp > (size_t)FPLANE_LDS_BUDGET) continue;
             break;
         }
-        if (nw < 1) return t;
+        if (nw < 1) return false;
         t.nwaves = nw; t.K = nw * t.cpw;
         t.lds = (4 + (size_t)nw * t.cpw) * hp;
     }
-    if ((size_t)p.B * (p.C / t.K) > 0x7fffffffull) return t;
-    t.ok = true;
+    return (size_t)p.B * (p.C / t.K) <= 0x7fffffffull;
+}
+
+static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
+    FwdPlanePlan t = {};
+    const int es = dtype == 0 ? 4 : 2, E = 16 / es;
+    if (p.H < 2 || p.W < 2 || p.H > 64 || p.W > 64) return t;
+    const int HW = p.H * p.W;
+    const int m = p.H > p.W ? p.H : p.W;
+    if (p.W % E == 0) {
+        // padded planes, one or two channels per wave
+        t.cpw = m <= 32 ? 2 : 1;
+        if ((size_t)t.cpw * HW * es > 8192) {
+            if (t.cpw == 2 && (size_t)HW * es <= 8192) t.cpw = 1; else return t;
+        }
+        if (p.cpg == 1 ? p.C % t.cpw : p.cpg % t.cpw) t.cpw = 1;
+        t.lsh = t.cpw == 2 ? 5 : 6;
+        t.pitch = p.W | 1;
+        const size_t hp = (((size_t)p.H * t.pitch + 3) & ~(size_t)3) * sizeof(float);   // one plane region in LDS
+        t.ok = plan_fwd_plane_waves(p, t, hp);
+        return t;
+    }
+    // flat planes: the most channels per wave (each on 64 / cpw lanes) that are whole 16 B chunks together
+    t.flat = true;
+    int lsh = 3;
+    while ((1 << lsh) < m) ++lsh;
+    for (; lsh <= 6; ++lsh) {
+        const int cpw = 64 >> lsh;
+        if ((size_t)cpw * HW * es % 16 || (size_t)cpw * HW * es > 8192) continue;
+        if (p.cpg == 1 ? p.C % cpw : p.cpg % cpw) continue;
+        t.cpw = cpw; t.lsh = lsh;
+        break;
+    }
+    if (!t.cpw) return t;
+    t.pitch = p.W;
+    // shared weights: the widest request that divides a group's block (its start is a multiple of its size)
+    const size_t wblock = (size_t)3 * HW * es;
+    t.wlw = wblock % 16 == 0 ? 16 : wblock % 8 == 0 ? 8 : wblock % 4 == 0 ? 4 : 2;
+    t.ok = plan_fwd_plane_waves(p, t, (size_t)HW * sizeof(float));
     return t;
 }
 
 bool fwd_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane(p, dtype).ok; }
 
-template <typename T, bool SAVE, bool SHARED, bool WPRE>
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT>
 static hipError_t launch_fplane_k(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
-    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE>;
+    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE, FLAT>;
     hipError_t e = allow_dynamic_lds((const void*)k, FPLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
@@ -380,12 +454,14 @@ static hipError_t launch_fplane_k(const FwdPlaneArgs& a, const FwdPlanePlan& t, 
 
 template <typename T, bool SAVE, bool SHARED>
 static hipError_t launch_fplane(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    if (t.flat) return launch_fplane_k<T, SAVE, SHARED, false, true>(a, t, s);
     if constexpr (SHARED) {
         const int E = 16 / (int)sizeof(T);
         const bool wpre = 3 * (a.p.H * a.p.W / E) <= 4 * 64 * a.nwaves;   // WSH chunks per thread
-        return wpre ? launch_fplane_k<T, SAVE, true, true>(a, t, s) : launch_fplane_k<T, SAVE, true, false>(a, t, s);
+        return wpre ? launch_fplane_k<T, SAVE, true, true, false>(a, t, s)
+                    : launch_fplane_k<T, SAVE, true, false, false>(a, t, s);
     } else {
-        return launch_fplane_k<T, SAVE, false, false>(a, t, s);
+        return launch_fplane_k<T, SAVE, false, false, false>(a, t, s);
     }
 }
 
@@ -399,7 +475,7 @@ hipError_t launch_fwd_plane(const FwdParams& p, int dtype, hipStream_t s) {
     const FwdPlanePlan t = plan_fwd_plane(p, dtype);
     if (!t.ok) return hipErrorInvalidValue;
     FwdPlaneArgs a;
-    a.p = p; a.K = t.K; a.cpw = t.cpw; a.nwaves = t.nwaves; a.pitch = t.pitch;
+    a.p = p; a.K = t.K; a.cpw = t.cpw; a.lsh = t.lsh; a.nwaves = t.nwaves; a.pitch = t.pitch; a.wlw = t.wlw;
     return dtype == 0 ? launch_fplane_t<float>(a, t, s) : launch_fplane_t<bf16_t>(a, t, s);
 }
 

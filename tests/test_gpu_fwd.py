@@ -107,20 +107,28 @@ def test_direction_masks_on_large_maps(mask):
     check_case(WL.ScanConfig("maskbig", 1, 2, 128, 256, 2, "f32", mask, 1.0, 16), save_h=False)
 
 
-def test_weights_that_are_never_read_may_hold_anything():
-    cfg = WL.ScanConfig("poison", 1, 4, 12, 10, 2, "f32", 15, 1.0, 3)
+@pytest.mark.parametrize("shape", [(1, 4, 12, 10, 2, "f32"), (1, 16, 7, 7, 2, "bf16"), (1, 8, 14, 14, 8, "f32"),
+                                   (1, 4, 28, 24, 2, "bf16"), (1, 2, 40, 40, 1, "f32"), (1, 3, 9, 11, 3, "bf16")],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_weights_that_are_never_read_may_hold_anything(shape):
+    """The first line of a scan has no predecessor and the end positions of a line have no neighbour outside
+    it (Eq. 1 with a zero initial state, Sec. 3.2): what w holds there must not reach the output."""
+    B, C, H, W, Gr, dtype = shape
+    cfg = WL.ScanConfig("poison", B, C, H, W, Gr, dtype, 15, 1.0, 3)
     inp = WL.make_inputs(cfg, with_gy=False)
     f = WL.inputs_as_f64(inp, cfg.dtype)
     y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
     w = inp["w"]
-    w[0, :, :, :, 0, :] = np.nan; w[1, :, :, :, -1, :] = np.inf       # first line of each scan
-    w[2, :, :, :, :, 0] = np.nan; w[3, :, :, :, :, -1] = -np.inf
-    w[0, :, :, 0, :, 0] = np.nan; w[0, :, :, 2, :, -1] = np.inf       # out-of-line neighbours
-    w[1, :, :, 0, :, 0] = np.inf; w[1, :, :, 2, :, -1] = np.nan
-    w[2, :, :, 0, 0, :] = np.nan; w[2, :, :, 2, -1, :] = np.nan
-    w[3, :, :, 0, 0, :] = np.inf; w[3, :, :, 2, -1, :] = np.nan
+    nan, inf, ninf = ((np.nan, np.inf, -np.inf) if dtype == "f32" else
+                      (np.uint16(0x7FC0), np.uint16(0x7F80), np.uint16(0xFF80)))
+    w[0, :, :, :, 0, :] = nan; w[1, :, :, :, -1, :] = inf             # first line of each scan
+    w[2, :, :, :, :, 0] = nan; w[3, :, :, :, :, -1] = ninf
+    w[0, :, :, 0, :, 0] = nan; w[0, :, :, 2, :, -1] = inf             # out-of-line neighbours
+    w[1, :, :, 0, :, 0] = inf; w[1, :, :, 2, :, -1] = nan
+    w[2, :, :, 0, 0, :] = nan; w[2, :, :, 2, -1, :] = nan
+    w[3, :, :, 0, 0, :] = inf; w[3, :, :, 2, -1, :] = nan
     y, *_ = run_fwd_gpu(inp, cfg, 15)
-    assert np.all(np.isfinite(y)) and rel_inf_err(y, y_ref) <= TOL["f32"]
+    assert np.all(np.isfinite(y)) and rel_inf_err(y, y_ref) <= TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -215,6 +223,34 @@ def test_forward_plane_kernel_shapes(shape):
     cfg = WL.ScanConfig("fwdplane", B, C, H, W, Gr, dtype, 15, 1.0, 43)
     check_case(cfg)
     check_case(cfg, save_h=False)
+
+
+# maps whose rows are not whole 16 B chunks (unpadded planes in LDS, 2 / 4 / 8 channels per wave): shared
+# weights fetched in 16, 8, 4 and 2 B pieces, per-channel weights, H != W, one to six waves, and the later
+# stages of the paper's classifier (Sec. 5.2: 28x28, 14x14, 7x7) with fewer images
+FLAT_FWD_SHAPES = [(2, 16, 28, 28, 2, "bf16"), (2, 8, 14, 14, 2, "f32"), (2, 16, 14, 14, 2, "bf16"), (2, 16, 7, 7, 2, "bf16"),
+                   (2, 16, 7, 7, 2, "f32"), (1, 8, 7, 7, 8, "f32"), (2, 16, 7, 7, 16, "bf16"), (1, 8, 14, 14, 8, "bf16"),
+                   (3, 8, 5, 6, 1, "bf16"), (1, 4, 9, 9, 1, "f32"), (1, 24, 14, 14, 2, "bf16"), (2, 2, 28, 28, 1, "bf16"),
+                   (1, 8, 6, 14, 2, "bf16"), (1, 4, 12, 10, 2, "f32"), (1, 2, 30, 30, 2, "f32"), (1, 4, 28, 28, 4, "bf16"),
+                   (2, 192, 28, 28, 8, "bf16"), (2, 384, 14, 14, 8, "bf16"), (2, 384, 14, 14, 8, "f32"),
+                   (2, 768, 7, 7, 8, "bf16"), (2, 768, 7, 7, 8, "f32")]
+
+
+@pytest.mark.parametrize("shape", FLAT_FWD_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_forward_plane_kernel_on_maps_with_ragged_rows(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_fwd_plan(B, C, H, W, Gr, 15, int(dtype == "bf16"), 0, True) == "plane", shape
+    cfg = WL.ScanConfig("fwdflat", B, C, H, W, Gr, dtype, 15, 1.0, 53)
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 5, 10, 7])
+@pytest.mark.parametrize("shape", [(2, 8, 14, 14, 2, "bf16"), (1, 8, 7, 7, 8, "f32")], ids=lambda s: "x".join(map(str, s)))
+def test_forward_plane_kernel_direction_masks_on_ragged_rows(mask, shape):
+    B, C, H, W, Gr, dtype = shape
+    check_case(WL.ScanConfig("fwdflatmask", B, C, H, W, Gr, dtype, mask, 1.0, 59))
 
 
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 6, 9, 14])

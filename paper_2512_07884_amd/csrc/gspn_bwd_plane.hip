@@ -24,6 +24,11 @@
 // zero-filled gw when the group is split over two workgroups (two addends commute: still bitwise
 // reproducible).  With one channel per group (per-channel weights of Eq. 1) every sweep writes
 // its own gw.  gx is merged over the directions in an LDS tile owned pair-wise by single waves.
+//
+// Lines of at most 16 / 8 positions (14x14, 7x7: the last stages of a classifier) put four / eight
+// channels side by side in a wave instead of two.  There a plane need not be a whole number of 16 B
+// chunks: only the wave's channels together are, and the group's three weight planes (and their
+// gradients) move as one block in the widest pieces its alignment allows.
 #include "gspn_tile_common.hpp"
 #include <stdlib.h>
 
@@ -35,11 +40,26 @@ typedef float f32a __attribute__((may_alias));
 
 struct BwdPlaneArgs {
     BwdParams p;
-    int K;             // channels per workgroup (even)
+    int K;             // channels per workgroup (a multiple of the channels per wave)
     int shared_group;  // 1: the K channels share one weight group; 0: one weight group per channel
     int gsplit;        // workgroups per weight group; 2: gw is accumulated atomically
     int nwaves;
+    int wlw;           // four / eight channels per wave: bytes per request of the group's weight block (16, 8, 4, 2)
 };
+
+// one piece of `ew` elements (a power of two, at most E) to storage
+template <typename T, int E> __device__ __forceinline__ void store_piece(T* dst, const float (&v)[E], int ew) {
+    if constexpr (sizeof(T) == 4) {
+        if (ew == 4) { const u32x4 c = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])}; *(u32x4*)dst = c; }
+        else if (ew == 2) { const u32x2 c = {__float_as_uint(v[0]), __float_as_uint(v[1])}; *(u32x2*)dst = c; }
+        else *(float*)dst = v[0];
+    } else {
+        if (ew == 8) { const u32x4 c = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])}; *(u32x4*)dst = c; }
+        else if (ew == 4) { const u32x2 c = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; *(u32x2*)dst = c; }
+        else if (ew == 2) *(uint32_t*)dst = pack_bf16x2(v[0], v[1]);
+        else *(bf16_t*)dst = f32_to_bf16(v[0]);
+    }
+}
 
 // widening / narrowing of one 16 B chunk of storage (E = 4 fp32 or 8 bf16 elements)
 template <typename T, int E> __device__ __forceinline__ void chunk_unpack(const u32x4& c, float (&v)[E]) {
@@ -63,30 +83,34 @@ template <typename T, int E> __device__ __forceinline__ u32x4 chunk_pack(const f
     return c;
 }
 
-template <typename T, int SMAX, bool SHARED>
+// SMAX: scan steps held in registers; CPW: channels per wave, on 64 / CPW lanes each
+template <typename T, int SMAX, int CPW, bool SHARED>
 __global__ void __launch_bounds__((SHARED && SMAX < 32) ? 384 : 256, (SHARED && SMAX == 32) ? 1 : 2)
 bwd_plane_kernel(BwdPlaneArgs a) {
+    static_assert(CPW == 2 || SHARED, "more than two channels per wave: shared weights only");
+    static_assert(SMAX * CPW <= 64, "a line per channel");
     constexpr int E = 16 / (int)sizeof(T);                    // elements per 16 B chunk of storage
-    constexpr int NCH = (2 * SMAX * SMAX / E + 63) / 64;      // chunks per lane for a pair of planes
+    constexpr int LPC = 64 / CPW;                             // lanes per channel
+    constexpr int NCH = (CPW * SMAX * SMAX / E + 63) / 64;    // chunks per lane for the planes of the wave's channels
     extern __shared__ float lds[];
     const BwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int half = lane >> 5, i = lane & 31;
+    const int half = lane / LPC, i = lane % LPC;               // channel of the wave, position on the line
     const int wgs_per_image = p.C / a.K;
     const int b = blockIdx.x / wgs_per_image;
     const int c_first = (blockIdx.x - b * wgs_per_image) * a.K;
-    const int pairs = a.K / 2;
-    const int n16p = HW / E, n16 = 2 * n16p;                   // chunks per plane / per pair
+    const int pairs = a.K / CPW;                               // sets of CPW channels ("pairs" when CPW = 2)
+    const int n16p = HW / E, n16 = CPW * HW / E;               // chunks per plane (CPW = 2 only) / per set
     const size_t planes = (size_t)p.B * p.C, groups = (size_t)p.B * p.G;
     constexpr bool shared_group = SHARED;
     const bool atomic = a.gsplit > 1;                          // fp32 storage only (checked on the host)
 
     float* tile = lds;                                         // [K][HW] merged gx (fp32)
-    float* wave_bufs = lds + a.K * HW;                         // per wave: X (two planes), H (two planes), fp32
-    f32a* bufX = wave_bufs + wave * 4 * HW;
-    f32a* bufH = bufX + 2 * HW;
+    float* wave_bufs = lds + a.K * HW;                         // per wave: X (CPW planes), H (CPW planes), fp32
+    f32a* bufX = wave_bufs + wave * 2 * CPW * HW;
+    f32a* bufH = bufX + CPW * HW;
 
     // chunk q = k*64 + lane of a contiguous pair of planes covers elements [E*q, E*q + E)
     bool vq[NCH];        // chunk inside the pair
@@ -152,7 +176,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
 
     // the wave's pairs start with gx = 0
     for (int pair = wave; pair < pairs; pair += a.nwaves) {
-        f32a* tp = tile + (size_t)2 * pair * HW;
+        f32a* tp = tile + (size_t)CPW * pair * HW;
         float z[E];
         zero(z);
 #pragma unroll
@@ -188,7 +212,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
         for (int s = 0; s < SMAX; ++s) { gw0[s] = 0.f; gw1[s] = 0.f; gw2[s] = 0.f; }
 
         for (int pair = wave; pair < pairs; pair += a.nwaves) {
-            const int c0 = c_first + 2 * pair;
+            const int c0 = c_first + CPW * pair;
             const size_t pc = ((size_t)b * p.C + c0) * HW;
             const int g = c0 / p.cpg;
             const size_t wg = ((size_t)b * p.G + g) * 3 * HW;
@@ -217,14 +241,14 @@ bwd_plane_kernel(BwdPlaneArgs a) {
                 }
             }
             to_lds(bufH, sb, false);
-            load_w(wp, sb);                                     // w0
+            if constexpr (CPW == 2) load_w(wp, sb);             // w0
             // seed u*gy, flat -> per-lane line positions
 #pragma unroll
             for (int k = 0; k < NCH; ++k)
 #pragma unroll
                 for (int e = 0; e < E; ++e) sc[k][e] *= sa[k][e];
             to_lds(bufX, sc, false);
-            load_w(wp + HW, sa);                                // w1
+            if constexpr (CPW == 2) load_w(wp + HW, sa);        // w1
             float e[SMAX];
 #pragma unroll
             for (int s = 0, idx = tb; s < SMAX; ++s) {
@@ -232,17 +256,42 @@ bwd_plane_kernel(BwdPlaneArgs a) {
                 e[s] = active ? v : 0.f;
                 next(idx, s);
             }
-            load_w(wp + 2 * HW, sc);                            // w2
             float w0r[SMAX], w1r[SMAX], w2r[SMAX];
-            to_lds(bufX, sb, shared_group);
+            if constexpr (CPW == 2) {
+                load_w(wp + 2 * HW, sc);                        // w2
+                to_lds(bufX, sb, shared_group);
 #pragma unroll
-            for (int s = 0, idx = tbw; s < SMAX; ++s) { w0r[s] = bufX[idx]; next(idx, s); }
-            to_lds(bufX, sa, shared_group);
+                for (int s = 0, idx = tbw; s < SMAX; ++s) { w0r[s] = bufX[idx]; next(idx, s); }
+                to_lds(bufX, sa, shared_group);
 #pragma unroll
-            for (int s = 0, idx = tbw; s < SMAX; ++s) { w1r[s] = bufX[idx]; next(idx, s); }
-            to_lds(bufX, sc, shared_group);
+                for (int s = 0, idx = tbw; s < SMAX; ++s) { w1r[s] = bufX[idx]; next(idx, s); }
+                to_lds(bufX, sc, shared_group);
 #pragma unroll
-            for (int s = 0, idx = tbw; s < SMAX; ++s) { w2r[s] = bufX[idx]; next(idx, s); }
+                for (int s = 0, idx = tbw; s < SMAX; ++s) { w2r[s] = bufX[idx]; next(idx, s); }
+            } else {
+                // the group's three planes as one block of 3*HW elements, in pieces of a.wlw bytes (the block's
+                // start is a multiple of its size, so a piece that divides the size is aligned)
+                const int ew = a.wlw / (int)sizeof(T);
+                const rsrc_t rs = make_rsrc(wp);
+                for (int c = lane; c * ew < 3 * HW; c += 64) {
+                    const uint32_t bo = (uint32_t)(c * ew * (int)sizeof(T));
+                    u32x4 v = {0, 0, 0, 0};
+                    if (a.wlw == 16) v = __builtin_amdgcn_raw_buffer_load_b128(rs, bo, 0, 0);
+                    else if (a.wlw == 8) { const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, bo, 0, 0); v[0] = t.x; v[1] = t.y; }
+                    else if (a.wlw == 4) v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, bo, 0, 0);
+                    else v[0] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, bo, 0, 0);
+                    float f[E];
+                    chunk_unpack<T, E>(v, f);
+#pragma unroll
+                    for (int j = 0; j < E; ++j)
+                        if (j < ew) bufX[c * ew + j] = f[j];
+                }
+#pragma unroll
+                for (int s = 0, idx = tbw; s < SMAX; ++s) {
+                    w0r[s] = bufX[idx]; w1r[s] = bufX[idx + HW]; w2r[s] = bufX[idx + 2 * HW];
+                    next(idx, s);
+                }
+            }
 
             // the sweep, against the scan order; the weights of scan step 0 are never used
 #pragma unroll
@@ -283,7 +332,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
                 if (s < S) { if (active) bufX[idx] = e[s]; }
                 next(idx, s);
             }
-            f32a* tp = tile + (size_t)2 * pair * HW;
+            f32a* tp = tile + (size_t)CPW * pair * HW;
 #pragma unroll
             for (int k = 0; k < NCH; ++k) {
                 if (vq[k]) {
@@ -330,7 +379,49 @@ bwd_plane_kernel(BwdPlaneArgs a) {
             }
         }
 
-        if constexpr (SHARED) {
+        if constexpr (SHARED && CPW > 2) {
+            // sum over the channels of each wave, then over the waves (fixed order); the three taps are one block
+            const int g = c_first / p.cpg;
+            T* gwp = (T*)p.gw + out_w + ((size_t)b * p.G + g) * 3 * HW;
+#pragma unroll
+            for (int s = 0, idx = ic * ps + s0; s < SMAX; ++s) {
+                float v0 = gw0[s], v1 = gw1[s], v2 = gw2[s];
+#pragma unroll
+                for (int m = 32; m >= LPC; m >>= 1) {
+                    const int src = ((lane ^ m) & 63) << 2;
+                    v0 += __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(v0)));
+                    v1 += __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(v1)));
+                    v2 += __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(v2)));
+                }
+                if (s < S) { if (active && half == 0) { bufX[idx] = v0; bufX[idx + HW] = v1; bufX[idx + 2 * HW] = v2; } }
+                next(idx, s);
+            }
+            lds_barrier();
+            const int ew = a.wlw / (int)sizeof(T);
+            for (int el = (int)threadIdx.x * ew; el < 3 * HW; el += (int)blockDim.x * ew) {
+                float acc[E];
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    acc[j] = 0.f;
+                    if (j < ew) {
+                        acc[j] = wave_bufs[el + j];
+                        for (int wv = 1; wv < a.nwaves; ++wv) acc[j] += wave_bufs[wv * 2 * CPW * HW + el + j];
+                    }
+                }
+                if constexpr (sizeof(T) == 4) {
+                    if (atomic) {
+#pragma unroll
+                        for (int j = 0; j < E; ++j)
+                            if (j < ew) atomicAdd((float*)gwp + el + j, acc[j]);
+                    } else {
+                        store_piece<T, E>(gwp + el, acc, ew);
+                    }
+                } else {
+                    store_piece<T, E>(gwp + el, acc, ew);
+                }
+            }
+            lds_barrier();
+        } else if constexpr (SHARED) {
             // sum over the two halves of each wave, then over the waves (fixed order), one tap at a time
             const int g = c_first / p.cpg;
             T* gwp = (T*)p.gw + out_w + ((size_t)b * p.G + g) * 3 * HW;
@@ -372,8 +463,8 @@ bwd_plane_kernel(BwdPlaneArgs a) {
 
     // merged gx of the wave's pairs: written once, coalesced
     for (int pair = wave; pair < pairs; pair += a.nwaves) {
-        const f32a* tp = tile + (size_t)2 * pair * HW;
-        const rsrc_t gxb = make_rsrc((T*)p.gx + ((size_t)b * p.C + c_first + 2 * pair) * HW);
+        const f32a* tp = tile + (size_t)CPW * pair * HW;
+        const rsrc_t gxb = make_rsrc((T*)p.gx + ((size_t)b * p.C + c_first + CPW * pair) * HW);
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
             if (vq[k]) {
@@ -390,25 +481,37 @@ bwd_plane_kernel(BwdPlaneArgs a) {
 // ---------------------------------------------------------------------------
 static constexpr int PLANE_LDS_BUDGET = 160 * 1024;
 
-struct PlanePlan { bool ok; int K, shared_group, gsplit, nwaves, smax; size_t lds; };
+struct PlanePlan { bool ok; int K, shared_group, gsplit, nwaves, smax, cpw, wlw; size_t lds; };
 
-static size_t plane_lds(int K, int nwaves, int HW) { return (size_t)(K + 4 * nwaves) * HW * sizeof(float); }
+static size_t plane_lds(int K, int nwaves, int HW, int cpw) {
+    return (size_t)(K + 2 * cpw * nwaves) * HW * sizeof(float);
+}
 
-// waves per workgroup: the most (up to `cap`) that share the channel pairs evenly and whose buffers fit
-static int plane_waves(int K, int HW, int cap) {
-    const int pairs = K / 2;
+// waves per workgroup: the most (up to `cap`) that share the channel sets evenly and whose buffers fit
+static int plane_waves(int K, int HW, int cap, int cpw) {
+    const int sets = K / cpw;
     for (int n = cap; n > 1; --n)
-        if (pairs % n == 0 && plane_lds(K, n, HW) <= (size_t)PLANE_LDS_BUDGET) return n;
+        if (sets % n == 0 && plane_lds(K, n, HW, cpw) <= (size_t)PLANE_LDS_BUDGET) return n;
     return 1;
 }
 
 static PlanePlan plan_plane(const BwdParams& p, int dtype) {
     PlanePlan t = {};
-    const int E = dtype == 0 ? 4 : 8;                           // elements per 16 B of storage
-    if (p.H < 2 || p.W < 2 || p.H > 32 || p.W > 32 || (p.H * p.W) % E) return t;
+    const int es = dtype == 0 ? 4 : 2, E = 16 / es;             // elements per 16 B of storage
+    if (p.H < 2 || p.W < 2 || p.H > 32 || p.W > 32) return t;
     const int HW = p.H * p.W;
     const int m = p.H > p.W ? p.H : p.W;
-    t.smax = m <= 16 ? 16 : (m <= 28 ? 28 : 32);
+    // channels per wave: eight / four when the lines are short enough, the group divides evenly and the
+    // channels together are whole 16 B chunks; else two, which needs whole chunks per plane
+    auto fits = [&](int cpw) { return (64 / cpw) >= m && p.cpg % cpw == 0 && ((size_t)cpw * HW * es) % 16 == 0; };
+    if (p.cpg > 1 && fits(8)) { t.cpw = 8; t.smax = 8; }
+    else if (p.cpg > 1 && fits(4)) { t.cpw = 4; t.smax = 16; }
+    else {
+        if (HW % E) return t;
+        t.cpw = 2; t.smax = m <= 16 ? 16 : (m <= 28 ? 28 : 32);
+    }
+    const size_t wblock = (size_t)3 * HW * es;
+    t.wlw = wblock % 16 == 0 ? 16 : wblock % 8 == 0 ? 8 : wblock % 4 == 0 ? 4 : 2;
     const int cap_shared = t.smax < 32 ? 6 : 4;                 // the 32-step variant needs more registers per wave
     if (p.cpg == 1) {
         t.shared_group = 0; t.gsplit = 1;
@@ -419,12 +522,13 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
         t.shared_group = 1; t.gsplit = 1; t.K = p.cpg;
         const bool few = (size_t)p.B * p.G < 256;               // fewer workgroups than compute units
         // a split group adds into gw atomically, which needs fp32 storage
-        if (dtype == 0 && (plane_lds(t.K, plane_waves(t.K, HW, cap_shared), HW) > (size_t)PLANE_LDS_BUDGET || few) && t.K % 4 == 0) {
+        if (dtype == 0 && (plane_lds(t.K, plane_waves(t.K, HW, cap_shared, t.cpw), HW, t.cpw) > (size_t)PLANE_LDS_BUDGET || few) &&
+            t.K % (2 * t.cpw) == 0) {
             t.K /= 2; t.gsplit = 2;
         }
     }
-    t.nwaves = plane_waves(t.K, HW, t.shared_group ? cap_shared : 4);
-    t.lds = plane_lds(t.K, t.nwaves, HW);
+    t.nwaves = plane_waves(t.K, HW, t.shared_group ? cap_shared : 4, t.cpw);
+    t.lds = plane_lds(t.K, t.nwaves, HW, t.cpw);
     if (t.lds > (size_t)PLANE_LDS_BUDGET) return t;
     if ((size_t)p.B * (p.C / t.K) > 0x7fffffffull) return t;
     t.ok = true;
@@ -433,9 +537,9 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
 
 bool bwd_plane_applicable(const BwdParams& p, int dtype) { return plan_plane(p, dtype).ok; }
 
-template <typename T, int SMAX, bool SHARED>
+template <typename T, int SMAX, int CPW, bool SHARED>
 static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
-    auto k = bwd_plane_kernel<T, SMAX, SHARED>;
+    auto k = bwd_plane_kernel<T, SMAX, CPW, SHARED>;
     hipError_t e = allow_dynamic_lds((const void*)k, PLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
@@ -445,21 +549,23 @@ static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStr
 
 template <typename T>
 static hipError_t launch_plane_t(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
+    if (t.cpw == 8) return launch_plane<T, 8, 8, true>(a, t, s);
+    if (t.cpw == 4) return launch_plane<T, 16, 4, true>(a, t, s);
     if (t.shared_group) {
-        if (t.smax == 16) return launch_plane<T, 16, true>(a, t, s);
-        if (t.smax == 28) return launch_plane<T, 28, true>(a, t, s);
-        return launch_plane<T, 32, true>(a, t, s);
+        if (t.smax == 16) return launch_plane<T, 16, 2, true>(a, t, s);
+        if (t.smax == 28) return launch_plane<T, 28, 2, true>(a, t, s);
+        return launch_plane<T, 32, 2, true>(a, t, s);
     }
-    if (t.smax == 16) return launch_plane<T, 16, false>(a, t, s);
-    if (t.smax == 28) return launch_plane<T, 28, false>(a, t, s);
-    return launch_plane<T, 32, false>(a, t, s);
+    if (t.smax == 16) return launch_plane<T, 16, 2, false>(a, t, s);
+    if (t.smax == 28) return launch_plane<T, 28, 2, false>(a, t, s);
+    return launch_plane<T, 32, 2, false>(a, t, s);
 }
 
 hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
     const PlanePlan t = plan_plane(p, dtype);
     if (!t.ok) return hipErrorInvalidValue;
     BwdPlaneArgs a;
-    a.p = p; a.K = t.K; a.shared_group = t.shared_group; a.gsplit = t.gsplit; a.nwaves = t.nwaves;
+    a.p = p; a.K = t.K; a.shared_group = t.shared_group; a.gsplit = t.gsplit; a.nwaves = t.nwaves; a.wlw = t.wlw;
     if (t.gsplit > 1) {
         // gw of the requested directions is accumulated atomically: clear it first, on the same stream
         const size_t per_dir = (size_t)p.B * p.G * 3 * p.H * p.W * sizeof(float);

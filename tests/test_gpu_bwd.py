@@ -100,6 +100,31 @@ def test_backward_plane_kernel_shapes_bf16(shape):
     check_bwd(WL.ScanConfig("bwdplane16", B, C, H, W, Gr, "bf16", 15, 1.0, 53))
 
 
+# lines of at most 16 / 8 positions with shared weights: four / eight channels per wave; planes that are not
+# whole 16 B chunks, weight blocks moved in 16, 8, 4 and 2 B pieces, a group split over two workgroups
+# (fp32, few groups), one to six waves, and the last stages of the paper's classifier (Sec. 5.2) with fewer images
+PLANE_BWD_SMALL_SHAPES = [(2, 16, 14, 14, 2, "f32"), (2, 16, 7, 7, 2, "f32"), (1, 48, 7, 7, 1, "f32"), (1, 12, 14, 14, 1, "f32"),
+                          (1, 8, 5, 6, 1, "f32"), (1, 4, 9, 9, 1, "f32"), (2, 8, 14, 10, 2, "f32"), (300, 16, 7, 7, 2, "f32"),
+                          (2, 16, 14, 14, 2, "bf16"), (2, 16, 7, 7, 2, "bf16"), (3, 8, 5, 6, 1, "bf16"), (1, 24, 14, 14, 2, "bf16"),
+                          (1, 8, 6, 14, 2, "bf16"), (1, 16, 8, 8, 2, "bf16"), (1, 48, 7, 7, 1, "bf16"),
+                          (2, 384, 14, 14, 8, "f32"), (2, 768, 7, 7, 8, "f32"), (2, 384, 14, 14, 8, "bf16"), (2, 768, 7, 7, 8, "bf16")]
+
+
+@pytest.mark.parametrize("shape", PLANE_BWD_SMALL_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_backward_plane_kernel_on_short_lines(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, int(dtype == "bf16"), 0) == "plane", shape
+    check_bwd(WL.ScanConfig("bwdsmall", B, C, H, W, Gr, dtype, 15, 1.0, 61))
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 5, 10, 14])
+@pytest.mark.parametrize("shape", [(2, 16, 7, 7, 2, "bf16"), (2, 8, 14, 14, 2, "f32")], ids=lambda s: "x".join(map(str, s)))
+def test_backward_plane_kernel_direction_masks_on_short_lines(mask, shape):
+    B, C, H, W, Gr, dtype = shape
+    check_bwd(WL.ScanConfig("bwdsmallmask", B, C, H, W, Gr, dtype, mask, 1.0, 67))
+
+
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 6, 9, 14])
 def test_backward_plane_kernel_direction_masks_bf16(mask):
     check_bwd(WL.ScanConfig("bwdplane16mask", 2, 8, 28, 28, 2, "bf16", mask, 1.0, 59))

@@ -42,6 +42,11 @@ lower-triangular product form of Eq. 3, the width-1 scalar recurrence closed
 form, identity weights -> cumulative sum, the row-stochastic constant
 invariant, group replication, linearity, central finite differences, the
 adjoint identity and the dense transposed operator for the backward.
+GSPN-local (scan_fwd_local / scan_bwd_local, tests/test_oracle_local.py): the
+dense solve with the links between stretches removed, kchunk = 1 (no
+propagation: y = sum_d u_d lam_d x) and kchunk >= scan length (the global
+scan), confinement of a perturbation to its stretch, central finite
+differences and the adjoint identity for the backward.
 """
 from __future__ import annotations
 
@@ -226,6 +231,67 @@ def scan_bwd(gy, x, w, lam, u, h_all, dir_mask=15):
 
 
 # --------------------------------------------------------------------------
+# GSPN-local (Sec. 3.2): propagation confined to stretches of `kchunk` lines
+# --------------------------------------------------------------------------
+def _stretches(S: int, kchunk: int):
+    """The scan axis [0, S) cut into stretches of kchunk lines, the last one shorter when kchunk does
+    not divide S.  The cut is made in image coordinates, so it is the same for a direction and its
+    reverse (reading: the paper only says that each row or column is split into fixed-length segments)."""
+    if kchunk < 1:
+        raise ValueError("kchunk must be >= 1")
+    return [(a, min(a + kchunk, S)) for a in range(0, S, kchunk)]
+
+
+def _cut(a, d, lo, hi):
+    """Lines lo..hi-1 of the scan axis of direction d (rows for the vertical scans, columns otherwise)."""
+    return a[..., lo:hi, :] if d < 2 else a[..., :, lo:hi]
+
+
+def scan_fwd_local(x, w, lam, u, kchunk, dir_mask=15):
+    """GSPN-local forward: every stretch of kchunk lines along the scan axis is a scan of its own (Eq. 1-2
+    on the sub-image, state zero before the stretch's first line in scan order), written out as exactly
+    that: one call of the global scan per (direction, stretch).  Shapes as in scan_fwd."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    lam = np.asarray(lam, dtype=np.float64)
+    u = np.asarray(u, dtype=np.float64)
+    H, W = x.shape[-2:]
+    y = np.zeros_like(x)
+    h_all = np.zeros((4,) + x.shape)
+    for d in _dirs_of(dir_mask):
+        for lo, hi in _stretches(H if d < 2 else W, kchunk):
+            ys, hs = scan_fwd(_cut(x, d, lo, hi), _cut(w, d, lo, hi), _cut(lam, d, lo, hi), _cut(u, d, lo, hi), 1 << d)
+            _cut(y, d, lo, hi)[...] += ys
+            _cut(h_all[d], d, lo, hi)[...] = hs[d]
+    return y, h_all
+
+
+def scan_bwd_local(gy, x, w, lam, u, h_all, kchunk, dir_mask=15):
+    """GSPN-local backward: the gradients of every (direction, stretch) scan on its own sub-image; gx is
+    summed over the directions, gw of a stretch's first line in scan order is zero.  Shapes as in scan_bwd."""
+    gy = np.asarray(gy, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    lam = np.asarray(lam, dtype=np.float64)
+    u = np.asarray(u, dtype=np.float64)
+    h_all = np.asarray(h_all, dtype=np.float64)
+    H, W = x.shape[-2:]
+    gx = np.zeros_like(x)
+    gw = np.zeros_like(w)
+    glam = np.zeros_like(lam)
+    gu = np.zeros_like(u)
+    for d in _dirs_of(dir_mask):
+        for lo, hi in _stretches(H if d < 2 else W, kchunk):
+            c = lambda a: _cut(a, d, lo, hi)
+            gxs, gws, gls, gus = scan_bwd(c(gy), c(x), c(w), c(lam), c(u), c(h_all), 1 << d)
+            c(gx)[...] += gxs
+            c(gw[d])[...] = gws[d]
+            c(glam[d])[...] = gls[d]
+            c(gu[d])[...] = gus[d]
+    return gx, gw, glam, gu
+
+
+# --------------------------------------------------------------------------
 # dense forms used only to pin the scans on tiny inputs
 # --------------------------------------------------------------------------
 def tridiagonal(w_line):
@@ -263,10 +329,11 @@ def eq3_block_matrix(w_bg, lam_bc):
     return M
 
 
-def one_step_matrix_image(w_dbg, d, H, W):
+def one_step_matrix_image(w_dbg, d, H, W, kchunk=None):
     """A [H*W, H*W] with A[p, q] = weight with which pixel q (on the previous
     line of direction d) feeds pixel p, written directly in image coordinates
-    (row-major pixel index r*W + c) without any view transform.
+    (row-major pixel index r*W + c) without any view transform.  With kchunk
+    (GSPN-local) a pixel is fed only from its own stretch of kchunk lines.
 
     w_dbg : [3, H, W] weights of direction d for one (batch, group)
     """
@@ -283,15 +350,18 @@ def one_step_matrix_image(w_dbg, d, H, W):
                     rr, cc = r + k - 1, c - 1
                 else:
                     rr, cc = r + k - 1, c + 1
+                if kchunk is not None and (r // kchunk != rr // kchunk if d < 2 else c // kchunk != cc // kchunk):
+                    continue
                 if 0 <= rr < H and 0 <= cc < W:
                     A[r * W + c, rr * W + cc] = w_dbg[k, r, c]
     return A
 
 
-def dense_fwd(x, w, lam, u, dir_mask=15):
+def dense_fwd(x, w, lam, u, dir_mask=15, kchunk=None):
     """y and h by solving (I - A_d) h_d = lam_d * x per (direction, batch,
     channel): the recurrence h = A h + lam*x with A strictly "previous line"
-    (nilpotent), which is Eq. 3 written without choosing a line order."""
+    (nilpotent), which is Eq. 3 written without choosing a line order.  With
+    kchunk the links that leave a stretch of kchunk lines are absent."""
     x = np.asarray(x, dtype=np.float64)
     B, C, H, W = x.shape
     G = w.shape[2]
@@ -302,7 +372,7 @@ def dense_fwd(x, w, lam, u, dir_mask=15):
     for d in _dirs_of(dir_mask):
         for b in range(B):
             for c in range(C):
-                A = one_step_matrix_image(w[d, b, c // cpg], d, H, W)
+                A = one_step_matrix_image(w[d, b, c // cpg], d, H, W, kchunk)
                 rhs = (np.asarray(lam[d, b, c], dtype=np.float64) * x[b, c]).reshape(-1)
                 h = np.linalg.solve(eye - A, rhs).reshape(H, W)
                 h_all[d, b, c] = h

@@ -86,6 +86,11 @@ def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
         assert fwd(32, 192, 28, 28, G, 15, 0, 0, 1) == "plane"
         assert bwd(32, 192, 28, 28, G, 15, 0, 0) == "plane"
     assert bwd(64, 96, 56, 56, 8, 15, 1, 0) == "tile" and bwd(64, 96, 56, 56, 8, 15, 0, 0) == "tile"
+    # the later stages of the paper's classifier (Sec. 5.2), forward with h_save and backward, both storage types
+    for C, HW in ((192, 28), (384, 14), (768, 7)):
+        for dt in (0, 1):
+            assert fwd(64, C, HW, HW, 8, 15, dt, 0, 1) == "plane", (C, HW, dt)
+            assert bwd(64, C, HW, HW, 8, 15, dt, 0) == "plane", (C, HW, dt)
     assert bwd(2, 1024, 128, 128, 16, 15, 1, 0) == "generic"                 # no fast backward beyond 64 lines
     monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
     assert fwd(64, 96, 56, 56, 8, 15, 1, 0, 0) == "generic" and bwd(32, 192, 28, 28, 4, 15, 0, 0) == "generic"

@@ -58,7 +58,7 @@ extern "C" {
 typedef enum {
     GSPN_OK = 0,
     GSPN_ERR_NULL = 1,        /* a required pointer is NULL                              */
-    GSPN_ERR_SHAPE = 2,       /* a dimension < 1, C % G != 0, dir_mask == 0 or > 15      */
+    GSPN_ERR_SHAPE = 2,       /* a dimension or kchunk < 1, C % G != 0, dir_mask == 0 or > 15 */
     GSPN_ERR_DTYPE = 3,       /* dtype is not GSPN_F32 / GSPN_BF16                        */
     GSPN_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                        */
     GSPN_ERR_UNSUPPORTED = 5, /* a line longer than GSPN_MAX_LINE, or unknown flag bits  */
@@ -100,6 +100,27 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
                   int B, int C, int H, int W, int G,
                   unsigned dir_mask, int dtype, unsigned flags, void* stream);
 
+/* GSPN-local (Sec. 3.2): the same two calls with propagation confined to stretches of `kchunk` lines
+ * along the scan axis.  The scan axis of every direction (rows for top<->bottom, columns for
+ * left<->right) is cut at image lines 0, kchunk, 2*kchunk, ... -- the same cut for a direction and its
+ * reverse, the last stretch shorter when kchunk does not divide the axis -- and each stretch is a scan
+ * of its own: the state before its first line in scan order is 0, so that line's weights are never
+ * read and its gw is 0.  kchunk >= max(H, W) is the global scan; kchunk == 1 leaves no propagation
+ * (y = sum over directions of u*lam*x).  kchunk < 1 is GSPN_ERR_SHAPE.  Everything else (layouts,
+ * ownership, stream semantics, errors) is as for gspn_scan_fwd / gspn_scan_bwd, and h_save written by
+ * the local forward call is what the local backward call with the same kchunk expects.
+ * Maps with H, W <= 64 (forward) / <= 32 (backward) run on the "plane" kernels at the speed of the
+ * global scan; other shapes take the "generic" kernels. */
+int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const void* u,
+                        void* y, void* h_save,
+                        int B, int C, int H, int W, int G, int kchunk,
+                        unsigned dir_mask, int dtype, unsigned flags, void* stream);
+int gspn_scan_bwd_local(const void* gy, const void* x, const void* w, const void* lam, const void* u,
+                        const void* h_save,
+                        void* gx, void* gw, void* glam, void* gu,
+                        int B, int C, int H, int W, int G, int kchunk,
+                        unsigned dir_mask, int dtype, unsigned flags, void* stream);
+
 /* Name of the kernel family the forward / backward call would dispatch to for
  * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
  * merged output fits in LDS), "stream" (larger maps, forward only), "generic" (any
@@ -113,6 +134,11 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
  *       workgroup / horizontal-phase variant (ignored when they do not fit) */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);
 const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
+/* the same for the GSPN-local calls */
+const char* gspn_fwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                unsigned flags, int has_h_save);
+const char* gspn_bwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                unsigned flags);
 
 /* Static, human-readable text for a gspn_status value. */
 const char* gspn_status_string(int status);

@@ -18,7 +18,8 @@ DIR_ALL = 15
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_fwd_plan", "gspn_bwd_plan",
+EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_bwd_local",
+           "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
            "gspn_status_string", "gspn_version")
 
 
@@ -51,6 +52,14 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_scan_fwd.restype = ci
     lib.gspn_scan_bwd.argtypes = [vp] * 10 + [ci] * 5 + [cu, ci, cu, vp]
     lib.gspn_scan_bwd.restype = ci
+    lib.gspn_scan_fwd_local.argtypes = [vp] * 6 + [ci] * 6 + [cu, ci, cu, vp]
+    lib.gspn_scan_fwd_local.restype = ci
+    lib.gspn_scan_bwd_local.argtypes = [vp] * 10 + [ci] * 6 + [cu, ci, cu, vp]
+    lib.gspn_scan_bwd_local.restype = ci
+    lib.gspn_fwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu, ci]
+    lib.gspn_fwd_local_plan.restype = ctypes.c_char_p
+    lib.gspn_bwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu]
+    lib.gspn_bwd_local_plan.restype = ctypes.c_char_p
     lib.gspn_fwd_plan.argtypes = [ci] * 5 + [cu, ci, cu, ci]
     lib.gspn_fwd_plan.restype = ctypes.c_char_p
     lib.gspn_bwd_plan.argtypes = [ci] * 5 + [cu, ci, cu]
@@ -77,6 +86,14 @@ def gspn_fwd_plan(B, C, H, W, G, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0, has_
 
 def gspn_bwd_plan(B, C, H, W, G, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:
     return load_library().gspn_bwd_plan(B, C, H, W, G, dir_mask, dtype, flags).decode()
+
+
+def gspn_fwd_local_plan(B, C, H, W, G, kchunk, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0, has_h_save=False) -> str:
+    return load_library().gspn_fwd_local_plan(B, C, H, W, G, kchunk, dir_mask, dtype, flags, int(has_h_save)).decode()
+
+
+def gspn_bwd_local_plan(B, C, H, W, G, kchunk, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:
+    return load_library().gspn_bwd_local_plan(B, C, H, W, G, kchunk, dir_mask, dtype, flags).decode()
 
 
 # ---------------------------------------------------------------- marshalling
@@ -115,15 +132,7 @@ def _check(status: int):
         raise GspnError(status, gspn_status_string(status))
 
 
-def gspn_scan_fwd(x, w, lam, u, y, h_save=None, *, G: Optional[int] = None, dir_mask: int = DIR_ALL,
-                  flags: int = 0, stream=None) -> None:
-    """y <- sum over directions of u_d * h_d (Eq. 1-2); optionally saves h_d.
-
-    x [B,C,H,W]; w [4,B,G,3,H,W]; lam, u [4,B,C,H,W] ([1,...] with
-    GSPN_FLAG_SHARED_PARAMS); y [B,C,H,W]; h_save [4,B,C,H,W] or None.
-    All device tensors of one dtype (float32 / bfloat16), contiguous.
-    """
-    lib = load_library()
+def _fwd_args(x, w, lam, u, y, h_save, G, flags):
     B, C, H, W = x.shape
     if G is None:
         G = w.shape[2]
@@ -134,14 +143,30 @@ def gspn_scan_fwd(x, w, lam, u, y, h_save=None, *, G: Optional[int] = None, dir_
     pu = _ptr(u, "u", (slots, B, C, H, W), x)
     py = _ptr(y, "y", (B, C, H, W), x)
     ph = _ptr(h_save, "h_save", (4, B, C, H, W), x)
-    _check(lib.gspn_scan_fwd(px, pw, pl, pu, py, ph, B, C, H, W, G, dir_mask, _dtype_code(x), flags,
-                             _stream(stream)))
+    return [px, pw, pl, pu, py, ph], (B, C, H, W, G)
 
 
-def gspn_scan_bwd(gy, x, w, lam, u, h_save, gx, gw, glam, gu, *, G: Optional[int] = None,
-                  dir_mask: int = DIR_ALL, flags: int = 0, stream=None) -> None:
-    """Gradients of the forward scan (see include/gspn.h); outputs overwritten."""
-    lib = load_library()
+def gspn_scan_fwd(x, w, lam, u, y, h_save=None, *, G: Optional[int] = None, dir_mask: int = DIR_ALL,
+                  flags: int = 0, stream=None) -> None:
+    """y <- sum over directions of u_d * h_d (Eq. 1-2); optionally saves h_d.
+
+    x [B,C,H,W]; w [4,B,G,3,H,W]; lam, u [4,B,C,H,W] ([1,...] with
+    GSPN_FLAG_SHARED_PARAMS); y [B,C,H,W]; h_save [4,B,C,H,W] or None.
+    All device tensors of one dtype (float32 / bfloat16), contiguous.
+    """
+    ptrs, dims = _fwd_args(x, w, lam, u, y, h_save, G, flags)
+    _check(load_library().gspn_scan_fwd(*ptrs, *dims, dir_mask, _dtype_code(x), flags, _stream(stream)))
+
+
+def gspn_scan_fwd_local(x, w, lam, u, y, h_save=None, *, kchunk: int, G: Optional[int] = None,
+                        dir_mask: int = DIR_ALL, flags: int = 0, stream=None) -> None:
+    """GSPN-local forward (Sec. 3.2): as gspn_scan_fwd, propagation confined to stretches of kchunk lines."""
+    ptrs, dims = _fwd_args(x, w, lam, u, y, h_save, G, flags)
+    _check(load_library().gspn_scan_fwd_local(*ptrs, *dims, int(kchunk), dir_mask, _dtype_code(x), flags,
+                                              _stream(stream)))
+
+
+def _bwd_args(gy, x, w, lam, u, h_save, gx, gw, glam, gu, G, flags):
     B, C, H, W = x.shape
     if G is None:
         G = w.shape[2]
@@ -151,4 +176,19 @@ def gspn_scan_bwd(gy, x, w, lam, u, h_save, gx, gw, glam, gu, *, G: Optional[int
             _ptr(u, "u", (slots, B, C, H, W), x), _ptr(h_save, "h_save", (4, B, C, H, W), x),
             _ptr(gx, "gx", (B, C, H, W), x), _ptr(gw, "gw", (4, B, G, 3, H, W), x),
             _ptr(glam, "glam", (4, B, C, H, W), x), _ptr(gu, "gu", (4, B, C, H, W), x)]
-    _check(lib.gspn_scan_bwd(*args, B, C, H, W, G, dir_mask, _dtype_code(x), flags, _stream(stream)))
+    return args, (B, C, H, W, G)
+
+
+def gspn_scan_bwd(gy, x, w, lam, u, h_save, gx, gw, glam, gu, *, G: Optional[int] = None,
+                  dir_mask: int = DIR_ALL, flags: int = 0, stream=None) -> None:
+    """Gradients of the forward scan (see include/gspn.h); outputs overwritten."""
+    args, dims = _bwd_args(gy, x, w, lam, u, h_save, gx, gw, glam, gu, G, flags)
+    _check(load_library().gspn_scan_bwd(*args, *dims, dir_mask, _dtype_code(x), flags, _stream(stream)))
+
+
+def gspn_scan_bwd_local(gy, x, w, lam, u, h_save, gx, gw, glam, gu, *, kchunk: int, G: Optional[int] = None,
+                        dir_mask: int = DIR_ALL, flags: int = 0, stream=None) -> None:
+    """Gradients of the GSPN-local forward scan with the same kchunk; outputs overwritten."""
+    args, dims = _bwd_args(gy, x, w, lam, u, h_save, gx, gw, glam, gu, G, flags)
+    _check(load_library().gspn_scan_bwd_local(*args, *dims, int(kchunk), dir_mask, _dtype_code(x), flags,
+                                              _stream(stream)))

@@ -18,18 +18,39 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-fno-gpu-rdc", "-Wall", "-Wno-unused-function"]
 
 
-def build(verbose: bool = True) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [HIPCC] + FLAGS + srcs + ["-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
+def _run(cmd):
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
     if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + r.stdout + "\n" + err)
-    if verbose and err.strip():
-        print(err, file=sys.stderr)
+        raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + r.stdout + "\n" + err)
+    return err
+
+
+def build(verbose: bool = True) -> str:
+    """Compiles every source to an object (in parallel, at most 8 at a time) and links the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+    import shutil
+    tmp = os.path.join(PKG, "_build")          # objects only; removed again below
+    os.makedirs(tmp, exist_ok=True)
+    try:
+        jobs = []
+        for src in SOURCES:
+            obj = os.path.join(tmp, src.replace(".hip", ".o"))
+            jobs.append(([HIPCC] + [f for f in FLAGS if f != "-shared"] + ["-c", os.path.join(CSRC, src), "-o", obj], obj))
+        if verbose:
+            for cmd, _ in jobs:
+                print(" ".join(cmd), flush=True)
+        with ThreadPoolExecutor(max_workers=min(8, len(jobs))) as pool:
+            errs = list(pool.map(_run, [cmd for cmd, _ in jobs]))
+        link = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950"] + [obj for _, obj in jobs] + ["-o", LIB]
+        if verbose:
+            print(" ".join(link), flush=True)
+        errs.append(_run(link))
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
+    if verbose and any(e.strip() for e in errs):
+        print("\n".join(e for e in errs if e.strip()), file=sys.stderr)
     return LIB
 
 

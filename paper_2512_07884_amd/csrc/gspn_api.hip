@@ -20,17 +20,21 @@ int check_common(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype
     return GSPN_OK;
 }
 
+// a stretch at least as long as both axes is the global scan: 0 for the kernels
+int effective_kchunk(int kchunk, int H, int W) { return (kchunk >= H && kchunk >= W) ? 0 : kchunk; }
+
 }  // namespace
 
 extern "C" {
 
-int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
-                  void* y, void* h_save,
-                  int B, int C, int H, int W, int G,
-                  unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const void* u,
+                        void* y, void* h_save,
+                        int B, int C, int H, int W, int G, int kchunk,
+                        unsigned dir_mask, int dtype, unsigned flags, void* stream) {
     if (!x || !w || !lam || !u || !y) return GSPN_ERR_NULL;
     int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
     if (st != GSPN_OK) return st;
+    if (kchunk < 1) return GSPN_ERR_SHAPE;
     if (misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y) ||
         (h_save && misaligned(h_save)))
         return GSPN_ERR_ALIGN;
@@ -38,18 +42,27 @@ int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
     p.x = x; p.w = w; p.lam = lam; p.u = u; p.y = y; p.hs = h_save;
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
     p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    p.kchunk = effective_kchunk(kchunk, H, W);
     hipError_t e = launch_fwd(p, dtype, (hipStream_t)stream);
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
 }
 
-int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam, const void* u,
-                  const void* h_save,
-                  void* gx, void* gw, void* glam, void* gu,
+int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
+                  void* y, void* h_save,
                   int B, int C, int H, int W, int G,
                   unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    return gspn_scan_fwd_local(x, w, lam, u, y, h_save, B, C, H, W, G, GSPN_MAX_LINE, dir_mask, dtype, flags, stream);
+}
+
+int gspn_scan_bwd_local(const void* gy, const void* x, const void* w, const void* lam, const void* u,
+                        const void* h_save,
+                        void* gx, void* gw, void* glam, void* gu,
+                        int B, int C, int H, int W, int G, int kchunk,
+                        unsigned dir_mask, int dtype, unsigned flags, void* stream) {
     if (!gy || !x || !w || !lam || !u || !h_save || !gx || !gw || !glam || !gu) return GSPN_ERR_NULL;
     int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
     if (st != GSPN_OK) return st;
+    if (kchunk < 1) return GSPN_ERR_SHAPE;
     if (misaligned(gy) || misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) ||
         misaligned(h_save) || misaligned(gx) || misaligned(gw) || misaligned(glam) || misaligned(gu))
         return GSPN_ERR_ALIGN;
@@ -58,33 +71,55 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
     p.gx = gx; p.gw = gw; p.glam = glam; p.gu = gu;
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
     p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    p.kchunk = effective_kchunk(kchunk, H, W);
     hipError_t e = launch_bwd(p, dtype, (hipStream_t)stream);
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
 }
 
-const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags,
-                          int has_h_save) {
-    if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK) return "invalid";
+int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam, const void* u,
+                  const void* h_save,
+                  void* gx, void* gw, void* glam, void* gu,
+                  int B, int C, int H, int W, int G,
+                  unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    return gspn_scan_bwd_local(gy, x, w, lam, u, h_save, gx, gw, glam, gu, B, C, H, W, G, GSPN_MAX_LINE,
+                               dir_mask, dtype, flags, stream);
+}
+
+const char* gspn_fwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                unsigned flags, int has_h_save) {
+    if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK || kchunk < 1) return "invalid";
     FwdParams p = {};
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G; p.mask = dir_mask;
     p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    p.kchunk = effective_kchunk(kchunk, H, W);
     p.hs = has_h_save ? (void*)16 : nullptr;
     return fwd_plan_name(p, dtype);
 }
 
-const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags) {
-    if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK) return "invalid";
+const char* gspn_bwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                unsigned flags) {
+    if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK || kchunk < 1) return "invalid";
     BwdParams p = {};
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G; p.mask = dir_mask;
     p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    p.kchunk = effective_kchunk(kchunk, H, W);
     return bwd_plan_name(p, dtype);
+}
+
+const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags,
+                          int has_h_save) {
+    return gspn_fwd_local_plan(B, C, H, W, G, GSPN_MAX_LINE, dir_mask, dtype, flags, has_h_save);
+}
+
+const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags) {
+    return gspn_bwd_local_plan(B, C, H, W, G, GSPN_MAX_LINE, dir_mask, dtype, flags);
 }
 
 const char* gspn_status_string(int status) {
     switch (status) {
         case GSPN_OK: return "ok";
         case GSPN_ERR_NULL: return "a required pointer is NULL";
-        case GSPN_ERR_SHAPE: return "bad shape: dimensions must be >= 1, C divisible by G, dir_mask in 1..15";
+        case GSPN_ERR_SHAPE: return "bad shape: dimensions and kchunk must be >= 1, C divisible by G, dir_mask in 1..15";
         case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32 or GSPN_BF16";
         case GSPN_ERR_ALIGN: return "pointers must be 16-byte aligned";
         case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE or unknown flag";

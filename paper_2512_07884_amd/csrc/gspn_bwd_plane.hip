@@ -45,6 +45,7 @@ struct BwdPlaneArgs {
     int gsplit;        // workgroups per weight group; 2: gw is accumulated atomically
     int nwaves;
     int wlw;           // four / eight channels per wave: bytes per request of the group's weight block (16, 8, 4, 2)
+    uint32_t seg[4];   // per direction: bit s set <=> scan step s starts a stretch (bit 0 always)
 };
 
 // one piece of `ew` elements (a power of two, at most E) to storage
@@ -83,8 +84,8 @@ template <typename T, int E> __device__ __forceinline__ u32x4 chunk_pack(const f
     return c;
 }
 
-// SMAX: scan steps held in registers; CPW: channels per wave, on 64 / CPW lanes each
-template <typename T, int SMAX, int CPW, bool SHARED>
+// SMAX: scan steps held in registers; CPW: channels per wave, on 64 / CPW lanes each; LOCAL: GSPN-local
+template <typename T, int SMAX, int CPW, bool SHARED, bool LOCAL>
 __global__ void __launch_bounds__((SHARED && SMAX < 32) ? 384 : 256, (SHARED && SMAX == 32) ? 1 : 2)
 bwd_plane_kernel(BwdPlaneArgs a) {
     static_assert(CPW == 2 || SHARED, "more than two channels per wave: shared weights only");
@@ -199,6 +200,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
         const int tbw = shared_group ? ic * ps + s0 : tb;      // same, in a weight plane
         const size_t out_c = (size_t)d * planes * HW, out_w = (size_t)d * groups * 3 * HW;
         const size_t slot_c = p.shared ? 0 : out_c, slot_w = p.shared ? 0 : out_w;
+        const uint32_t starts = LOCAL ? a.seg[d] : 1u;         // scan steps without a predecessor
 
         // walking a line's scan steps in LDS: one running index, pinned in a register after every step so
         // that the compiler keeps a single address instead of one per step; it stops at the last step
@@ -293,6 +295,17 @@ bwd_plane_kernel(BwdPlaneArgs a) {
                 }
             }
 
+            if constexpr (LOCAL) {
+                // GSPN-local: nothing flows into the first line of a stretch -- its weights count as 0, and so
+                // does the line before it where the weight gradients read it (h in LDS serves nothing else)
+#pragma unroll
+                for (int s = 1, idx = tb; s < SMAX; ++s) {
+                    const bool z = (starts >> s) & 1u;
+                    w0r[s] = z ? 0.f : w0r[s]; w1r[s] = z ? 0.f : w1r[s]; w2r[s] = z ? 0.f : w2r[s];
+                    if (s < S) { if (z && active) bufH[idx] = 0.f; }     // h of scan step s-1
+                    next(idx, s);
+                }
+            }
             // the sweep, against the scan order; the weights of scan step 0 are never used
 #pragma unroll
             for (int s = SMAX - 2; s >= 0; --s) {
@@ -537,14 +550,21 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
 
 bool bwd_plane_applicable(const BwdParams& p, int dtype) { return plan_plane(p, dtype).ok; }
 
-template <typename T, int SMAX, int CPW, bool SHARED>
-static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
-    auto k = bwd_plane_kernel<T, SMAX, CPW, SHARED>;
+template <typename T, int SMAX, int CPW, bool SHARED, bool LOCAL>
+static hipError_t launch_plane_k(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
+    auto k = bwd_plane_kernel<T, SMAX, CPW, SHARED, LOCAL>;
     hipError_t e = allow_dynamic_lds((const void*)k, PLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();
+}
+
+// GSPN-local (Sec. 3.2) runs on instantiations of its own, so that the global scan carries none of it
+template <typename T, int SMAX, int CPW, bool SHARED>
+static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
+    return a.p.kchunk > 0 ? launch_plane_k<T, SMAX, CPW, SHARED, true>(a, t, s)
+                          : launch_plane_k<T, SMAX, CPW, SHARED, false>(a, t, s);
 }
 
 template <typename T>
@@ -566,6 +586,7 @@ hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
     if (!t.ok) return hipErrorInvalidValue;
     BwdPlaneArgs a;
     a.p = p; a.K = t.K; a.shared_group = t.shared_group; a.gsplit = t.gsplit; a.nwaves = t.nwaves; a.wlw = t.wlw;
+    for (int d = 0; d < 4; ++d) a.seg[d] = (uint32_t)stretch_start_bits(d < 2 ? p.H : p.W, d & 1, p.kchunk, true);
     if (t.gsplit > 1) {
         // gw of the requested directions is accumulated atomically: clear it first, on the same stream
         const size_t per_dir = (size_t)p.B * p.G * 3 * p.H * p.W * sizeof(float);

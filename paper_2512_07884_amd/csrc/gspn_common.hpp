@@ -41,12 +41,32 @@ __host__ __device__ __forceinline__ DirGeom dir_geom(int d, int H, int W) {
     return g;
 }
 
+// ---- GSPN-local (Sec. 3.2): propagation confined to stretches of kchunk lines ------------------
+// The scan axis is cut at image lines 0, kchunk, 2*kchunk, ... (the same cut for a direction and its
+// reverse).  A line that starts a stretch in scan order has no predecessor: its state is lambda*x and
+// its weights are never read.  kchunk <= 0 means one stretch (the global scan).
+// t = scan step (0 = first line visited), S = lines along the scan axis.
+__host__ __device__ __forceinline__ bool starts_stretch(int t, int S, int reversed, int kchunk) {
+    if (t == 0) return true;
+    if (kchunk <= 0) return false;
+    const int r = reversed ? S - 1 - t : t;               // image line
+    return reversed ? (r + 1) % kchunk == 0 : r % kchunk == 0;
+}
+// bit i set <=> line i starts a stretch in scan order; i is the scan step (by_step) or the image line.  S <= 64.
+inline uint64_t stretch_start_bits(int S, int reversed, int kchunk, bool by_step) {
+    uint64_t m = 0;
+    for (int t = 0; t < S && t < 64; ++t)
+        if (starts_stretch(t, S, reversed, kchunk)) m |= 1ull << (by_step ? t : (reversed ? S - 1 - t : t));
+    return m;
+}
+
 struct FwdParams {
     const void* x; const void* w; const void* lam; const void* u;
     void* y; void* hs;
     int B, C, H, W, G, cpg;
     unsigned mask;
     int shared;   // 1: w/lam/u have a single direction slot
+    int kchunk;   // GSPN-local stretch length; 0: global scan
 };
 
 struct BwdParams {
@@ -55,6 +75,7 @@ struct BwdParams {
     int B, C, H, W, G, cpg;
     unsigned mask;
     int shared;
+    int kchunk;   // GSPN-local stretch length; 0: global scan
 };
 
 // Raises a kernel's dynamic-LDS limit (up to the 160 KB of a gfx950 CU) once per (kernel, device).

@@ -69,12 +69,14 @@ struct FwdPlaneArgs {
     int nwaves;
     int pitch;    // LDS row pitch in floats (odd; W in the flat variant)
     int wlw;      // flat variant, shared weights: bytes per weight request (16, 8, 4 or 2)
+    uint64_t seg[4];   // per direction: bit r set <=> image line r of the scan axis starts a stretch in scan order
 };
 
 // WPRE (shared weights): the workgroup has enough threads to hold a direction's weights in registers
 // (WSH chunks per thread), so they are requested a direction ahead; otherwise they are fetched in place.
 // FLAT: planes in LDS are unpadded and the wave's channels contiguous (see the head of the file).
-template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT>
+// LOCAL: GSPN-local (Sec. 3.2), on instantiations of its own so that the global scan carries none of it.
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL>
 __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneArgs a) {
     static_assert(!(FLAT && WPRE), "the flat variant fetches its weights in place");
     constexpr int E = 16 / (int)sizeof(T);        // elements per 16 B chunk
@@ -314,6 +316,22 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         }
         if constexpr (SHARED) lds_barrier();               // weights of this direction are in place (LDS only: the
                                                            // requests above stay in flight across the barrier)
+        if constexpr (LOCAL) {
+            // GSPN-local: a line that starts a stretch has no predecessor, so its three taps become 0 and
+            // the sweep below restarts from lam*x there without knowing about stretches
+            const uint64_t starts = a.seg[d];
+            const int nch = SHARED ? 1 : cpw;              // weight regions to patch: the group's, or the wave's own
+            const int t0 = SHARED ? (int)threadIdx.x : lane, tn = SHARED ? nthreads : 64;
+            for (int r = 0; r < S; ++r) {
+                if (!((starts >> r) & 1ull)) continue;
+                for (int j = t0; j < nch * L; j += tn) {
+                    const int chn = j / L, jj = j - chn * L;
+                    const uint32_t o = wreg + 16u * (uint32_t)(chn * HP + (vert ? r * P + jj : jj * P + r));
+                    plds_st(o, 0.f); plds_st(o + 4u, 0.f); plds_st(o + 8u, 0.f);
+                }
+            }
+            if constexpr (SHARED) lds_barrier();
+        }
 
         // ---- the scan: h overwrites a
         {
@@ -442,14 +460,20 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
 
 bool fwd_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane(p, dtype).ok; }
 
-template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT>
-static hipError_t launch_fplane_k(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
-    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE, FLAT>;
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL>
+static hipError_t launch_fplane_kl(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE, FLAT, LOCAL>;
     hipError_t e = allow_dynamic_lds((const void*)k, FPLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();
+}
+
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT>
+static hipError_t launch_fplane_k(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    return a.p.kchunk > 0 ? launch_fplane_kl<T, SAVE, SHARED, WPRE, FLAT, true>(a, t, s)
+                          : launch_fplane_kl<T, SAVE, SHARED, WPRE, FLAT, false>(a, t, s);
 }
 
 template <typename T, bool SAVE, bool SHARED>
@@ -476,6 +500,7 @@ hipError_t launch_fwd_plane(const FwdParams& p, int dtype, hipStream_t s) {
     if (!t.ok) return hipErrorInvalidValue;
     FwdPlaneArgs a;
     a.p = p; a.K = t.K; a.cpw = t.cpw; a.lsh = t.lsh; a.nwaves = t.nwaves; a.pitch = t.pitch; a.wlw = t.wlw;
+    for (int d = 0; d < 4; ++d) a.seg[d] = stretch_start_bits(d < 2 ? p.H : p.W, d & 1, p.kchunk, false);
     return dtype == 0 ? launch_fplane_t<float>(a, t, s) : launch_fplane_t<bf16_t>(a, t, s);
 }
 

@@ -47,10 +47,11 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
             float* cur = lds + Lmax;
             for (int t = 0; t < q.S; ++t) {
                 const int base = (q.reversed ? q.S - 1 - t : t) * q.stride_s;
+                const bool starts = starts_stretch(t, q.S, q.reversed, p.kchunk);
                 for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
                     const int off = base + j * q.stride_j;
                     float h = ldf(lp + off) * ldf(xp + off);
-                    if (t > 0) {   // first line: state before it is zero, its weights are not read
+                    if (!starts) {   // first line (of the scan, of a stretch): state before it is zero, its weights are not read
                         h = fmaf(ldf(wp + HW + off), prev[j], h);
                         if (j > 0) h = fmaf(ldf(wp + off), prev[j - 1], h);
                         if (j + 1 < q.L) h = fmaf(ldf(wp + 2 * HW + off), prev[j + 1], h);
@@ -114,11 +115,13 @@ __global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
                 for (int t = q.S - 1; t >= 0; --t) {
                     const int base = (q.reversed ? q.S - 1 - t : t) * q.stride_s;
                     const int step = q.reversed ? -q.stride_s : q.stride_s;   // to the next line in scan order
+                    const bool starts = starts_stretch(t, q.S, q.reversed, p.kchunk);
+                    const bool next_starts = t + 1 < q.S && starts_stretch(t + 1, q.S, q.reversed, p.kchunk);
                     for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
                         const int off = base + j * q.stride_j;
                         const float gyv = ldf(gyp + off);
                         float e = ldf(up + off) * gyv;
-                        if (t + 1 < q.S) {   // transposed tridiagonal of the next line
+                        if (t + 1 < q.S && !next_starts) {   // transposed tridiagonal of the next line (of the same stretch)
                             const int offn = off + step;
                             e = fmaf(ldf(wp + HW + offn), enext[j], e);
                             if (j > 0) e = fmaf(ldf(wp + 2 * HW + offn - q.stride_j), enext[j - 1], e);
@@ -135,7 +138,7 @@ __global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
                         for (int k = 0; k < 3; ++k) {
                             const int jj = j + k - 1;
                             float v = 0.f;
-                            if (t > 0 && jj >= 0 && jj < q.L) v = e * ldf(hp + offp + (k - 1) * q.stride_j);
+                            if (!starts && jj >= 0 && jj < q.L) v = e * ldf(hp + offp + (k - 1) * q.stride_j);
                             if (ci > 0) v += ldf(gwp + k * HW + off);
                             stf(gwp + k * HW + off, v);
                         }

@@ -63,12 +63,33 @@ def test_argument_errors_are_detected_before_any_launch(lib):
     assert lib.gspn_scan_bwd(p, p, p, p, p, None, p, p, p, p, *ok_dims, 15, 0, 0, None) == 1  # h_save required
     assert lib.gspn_scan_bwd(p, p, p, p, p, p, p, bad, p, p, *ok_dims, 15, 0, 0, None) == 4
     assert lib.gspn_scan_bwd(p, p, p, p, p, p, p, p, p, p, 1, 5, 8, 8, 2, 15, 0, 0, None) == 2
+    # GSPN-local: the same checks, and a stretch of less than one line is a shape error
+    assert lib.gspn_scan_fwd_local(p, p, p, p, p, None, *ok_dims, 0, 15, 0, 0, None) == 2
+    assert lib.gspn_scan_fwd_local(p, p, p, p, p, None, *ok_dims, -3, 15, 0, 0, None) == 2
+    assert lib.gspn_scan_fwd_local(None, p, p, p, p, None, *ok_dims, 4, 15, 0, 0, None) == 1
+    assert lib.gspn_scan_fwd_local(p, p, p, p, p, bad, *ok_dims, 4, 15, 0, 0, None) == 4
+    assert lib.gspn_scan_bwd_local(p, p, p, p, p, p, p, p, p, p, *ok_dims, 0, 15, 0, 0, None) == 2
+    assert lib.gspn_scan_bwd_local(p, p, p, p, p, None, p, p, p, p, *ok_dims, 4, 15, 0, 0, None) == 1
+    assert lib.gspn_scan_bwd_local(p, p, p, p, p, p, p, p, p, bad, *ok_dims, 4, 15, 0, 0, None) == 4
 
 
 def test_plan_names(lib):
     assert lib.gspn_fwd_plan(1, 8, 16, 16, 1, 1, 0, 0, 0).decode() != "invalid"
     assert lib.gspn_fwd_plan(1, 8, 16, 16, 3, 1, 0, 0, 0).decode() == "invalid"
     assert lib.gspn_bwd_plan(32, 192, 28, 28, 4, 15, 0, 0).decode() != "invalid"
+
+
+def test_kernel_family_chosen_for_local_scans(lib, monkeypatch):
+    """GSPN-local: small maps keep the plane kernels, larger ones take the generic kernels (the tile and stream
+    kernels scan whole lines only); a stretch that covers both axes is the global scan and dispatches like it."""
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE"):
+        monkeypatch.delenv(v, raising=False)
+    fwd = lambda *a: lib.gspn_fwd_local_plan(*a).decode()
+    bwd = lambda *a: lib.gspn_bwd_local_plan(*a).decode()
+    assert fwd(64, 96, 56, 56, 8, 14, 15, 1, 0, 0) == "plane" and bwd(32, 192, 28, 28, 4, 7, 15, 0, 0) == "plane"
+    assert fwd(2, 1024, 128, 128, 16, 32, 15, 1, 0, 0) == "generic" and bwd(64, 96, 56, 56, 8, 14, 15, 1, 0) == "generic"
+    assert fwd(2, 1024, 128, 128, 16, 128, 15, 1, 0, 0) == "tile" and fwd(1, 512, 512, 512, 16, 4096, 15, 1, 0, 0) == "stream"
+    assert fwd(1, 8, 16, 16, 1, 0, 15, 0, 0, 0) == "invalid" and bwd(1, 8, 16, 16, 1, 0, 15, 0, 0) == "invalid"
 
 
 def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):

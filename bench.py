@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused 4-direction GSPN scan on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kchunk K] [--all]
 
 A step is one pass of the whole hot path over one batch of synthetic input:
 one ``gspn_scan_fwd`` call covering all four directions (inference workloads),
@@ -9,7 +9,8 @@ or ``gspn_scan_fwd`` (saving h) + ``gspn_scan_bwd`` (training workloads).
 Inputs are resident in HBM before the timed region; buffer sets are rotated so
 that consecutive steps do not find their inputs in the 256 MB last-level cache.
 Prints ONE JSON line (see the keys below); ``--all`` additionally writes a table
-for every workload to <out>/bench_all.json (see --out).
+for every workload to <out>/bench_all.json (see --out).  ``--kchunk K`` times the
+GSPN-local calls (propagation confined to stretches of K lines) on the same workload.
 """
 from __future__ import annotations
 
@@ -71,7 +72,7 @@ def make_sets(cfg, training: bool, min_total_bytes: float = 1.0e9, max_sets: int
     return sets
 
 
-def run_workload(cfg, steps: int, warmup: int):
+def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0):
     """Times `steps` steps; returns dict with wall ms/step and per-kernel event times."""
     import torch
     import paper_2512_07884_amd as G
@@ -80,11 +81,19 @@ def run_workload(cfg, steps: int, warmup: int):
     stream = torch.cuda.current_stream()
 
     def fwd(s):
-        G.gspn_scan_fwd(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), G=cfg.G, dir_mask=cfg.dir_mask)
+        if kchunk:
+            G.gspn_scan_fwd_local(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), kchunk=kchunk, G=cfg.G,
+                                  dir_mask=cfg.dir_mask)
+        else:
+            G.gspn_scan_fwd(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), G=cfg.G, dir_mask=cfg.dir_mask)
 
     def bwd(s):
-        G.gspn_scan_bwd(s["gy"], s["x"], s["w"], s["lam"], s["u"], s["hs"], s["gx"], s["gw"], s["glam"],
-                        s["gu"], G=cfg.G, dir_mask=cfg.dir_mask)
+        if kchunk:
+            G.gspn_scan_bwd_local(s["gy"], s["x"], s["w"], s["lam"], s["u"], s["hs"], s["gx"], s["gw"], s["glam"],
+                                  s["gu"], kchunk=kchunk, G=cfg.G, dir_mask=cfg.dir_mask)
+        else:
+            G.gspn_scan_bwd(s["gy"], s["x"], s["w"], s["lam"], s["u"], s["hs"], s["gx"], s["gw"], s["glam"],
+                            s["gu"], G=cfg.G, dir_mask=cfg.dir_mask)
 
     for i in range(warmup):
         s = sets[i % len(sets)]
@@ -119,7 +128,7 @@ def run_workload(cfg, steps: int, warmup: int):
     fwd_ms = sorted(e[0].elapsed_time(e[1]) for e in ev)
     out = {"ms_per_step": (t1 - t0) * 1e3 / steps,
            "fwd_ms_avg": sum(fwd_ms) / steps, "fwd_ms_med": fwd_ms[steps // 2], "fwd_ms_min": fwd_ms[0],
-           "n_sets": len(sets), "training": training, "warm_ms_per_step": warm_ms}
+           "n_sets": len(sets), "training": training, "warm_ms_per_step": warm_ms, "kchunk": kchunk}
     if training:
         bwd_ms = sorted(e[1].elapsed_time(e[2]) for e in ev)
         out.update({"bwd_ms_avg": sum(bwd_ms) / steps, "bwd_ms_med": bwd_ms[steps // 2], "bwd_ms_min": bwd_ms[0]})
@@ -132,21 +141,25 @@ def summarise(cfg, r):
     import paper_2512_07884_amd as G
     dt = 1 if cfg.dtype == "bf16" else 0
     training = r["training"]
+    kchunk = r.get("kchunk", 0)
+    big = 1 << 14                      # a stretch longer than any line: the global scan
     fwd_bytes = cfg.fwd_algorithmic_bytes(save_h=training)
     d = {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "G": cfg.G,
          "storage": cfg.dtype, "directions": cfg.n_dirs,
          "step": "fwd+bwd" if training else "fwd",
          "ms_per_step": r["ms_per_step"], "warm_single_set_ms_per_step": r["warm_ms_per_step"],
          "gpixel_ch_per_s": cfg.pixel_channels / (r["ms_per_step"] * 1e-3) / 1e9,
-         "fwd_kernel": G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, cfg.dir_mask, dt, 0, training),
+         "fwd_kernel": G.gspn_fwd_local_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0, training),
          "fwd_ms_avg": r["fwd_ms_avg"], "fwd_ms_min": r["fwd_ms_min"],
          "fwd_algorithmic_bytes": fwd_bytes,
          "fwd_algorithmic_GBs": fwd_bytes / (r["fwd_ms_avg"] * 1e-3) / 1e9,
          "fwd_frac_of_hbm_peak": fwd_bytes / (r["fwd_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
          "buffer_sets_rotated": r["n_sets"]}
+    if kchunk:
+        d["kchunk"] = kchunk
     if training:
         bb = cfg.bwd_algorithmic_bytes()
-        d.update({"bwd_kernel": G.gspn_bwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, cfg.dir_mask, dt, 0),
+        d.update({"bwd_kernel": G.gspn_bwd_local_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0),
                   "bwd_ms_avg": r["bwd_ms_avg"], "bwd_ms_min": r["bwd_ms_min"],
                   "bwd_algorithmic_bytes": bb,
                   "bwd_algorithmic_GBs": bb / (r["bwd_ms_avg"] * 1e-3) / 1e9,
@@ -156,33 +169,38 @@ def summarise(cfg, r):
 
 # ---------------------------------------------------------------- CPU baseline (the oracle, as it stands)
 def _oracle_slice(args):
-    name, b, g, training = args
+    name, b, g, training, kchunk = args
     import numpy as np
     from oracle import gspn_oracle as O
     from paper_2512_07884_amd import workloads as WL
     cfg = WL.CONFIGS[name]
     s = WL.inputs_as_f64(WL.make_slice(cfg, b, g), cfg.dtype)
     t0 = time.perf_counter()
-    y, h = O.scan_fwd(s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None], cfg.dir_mask)
-    if training:
-        O.scan_bwd(s["gy"][None], s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None], h,
-                   cfg.dir_mask)
+    a = (s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None])
+    if kchunk:
+        y, h = O.scan_fwd_local(*a, kchunk, cfg.dir_mask)
+        if training:
+            O.scan_bwd_local(s["gy"][None], *a, h, kchunk, cfg.dir_mask)
+    else:
+        y, h = O.scan_fwd(*a, cfg.dir_mask)
+        if training:
+            O.scan_bwd(s["gy"][None], *a, h, cfg.dir_mask)
     return time.perf_counter() - t0, float(np.abs(y).sum())
 
 
-def cpu_baseline(cfg, training: bool, budget_s: float = 12.0):
+def cpu_baseline(cfg, training: bool, budget_s: float = 12.0, kchunk: int = 0):
     """The fp64 NumPy oracle on (batch, group) slices of the same workload, one
     slice per worker process, timed wall-clock over the pool (input generation
     excluded from the single-slice probe, included in the pool's wall time is
     avoided by timing only the oracle calls and dividing by the worker count)."""
     import multiprocessing as mp
     cores = max(1, min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)))
-    t_probe, _ = _oracle_slice((cfg.name, 0, 0, training))
+    t_probe, _ = _oracle_slice((cfg.name, 0, 0, training, kchunk))
     slice_pc = cfg.cpg * cfg.H * cfg.W
     total_slices = cfg.B * cfg.G
     n = int(max(cores, min(total_slices, (budget_s * cores) // max(t_probe, 1e-4))))
     n = min(n, total_slices)
-    jobs = [(cfg.name, (i // cfg.G) % cfg.B, i % cfg.G, training) for i in range(n)]
+    jobs = [(cfg.name, (i // cfg.G) % cfg.B, i % cfg.G, training, kchunk) for i in range(n)]
     ctx = mp.get_context("fork")
     t0 = time.perf_counter()
     with ctx.Pool(min(cores, n)) as pool:
@@ -227,6 +245,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--kchunk", type=int, default=0,
+                    help="GSPN-local: confine propagation to stretches of this many lines (0: the global scan)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
     ap.add_argument("--out", default="gpurun_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -244,13 +264,16 @@ def main():
     from paper_2512_07884_amd import workloads as WL
     cfg = WL.CONFIGS[a.workload]
     # the CPU legs fork worker processes: run them before this process touches the GPU
-    cpu = None if a.no_cpu else cpu_baseline(cfg, cfg.name in TRAINING)
+    if a.kchunk < 0:
+        print("bench.py: --kchunk must be >= 0", file=sys.stderr)
+        sys.exit(2)
+    cpu = None if a.no_cpu else cpu_baseline(cfg, cfg.name in TRAINING, kchunk=a.kchunk)
     import torch
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    r = run_workload(cfg, a.steps, a.warmup)
+    r = run_workload(cfg, a.steps, a.warmup, a.kchunk)
     s = summarise(cfg, r)
     training = r["training"]
     dom = "bwd" if training else "fwd"          # dominant kernel of the step
@@ -264,10 +287,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "storage_dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} H={cfg.H} W={cfg.W} G={cfg.G} "
-                               f"{cfg.dtype} storage, {cfg.n_dirs} directions, {s['step']}",
+                               f"{cfg.dtype} storage, {cfg.n_dirs} directions, {s['step']}"
+                               + (f", GSPN-local kchunk={a.kchunk}" if a.kchunk else ""),
                    "kernel": s[f"{dom}_kernel"], "buffer_sets_rotated": s["buffer_sets_rotated"]},
         "roofline": {"bound": "hbm", "kernel": f"gspn_scan_{dom}", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(cfg.name, dom),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None if a.kchunk else load_traffic(cfg.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "detail": s,
     }
@@ -279,7 +304,7 @@ def main():
             if name == cfg.name:
                 continue
             k = max(20, a.steps // (8 if c.pixel_channels > 1e8 else 1))
-            table.append(summarise(c, run_workload(c, k, a.warmup)))
+            table.append(summarise(c, run_workload(c, k, a.warmup, a.kchunk)))
             print(f"[bench] {name} done", file=sys.stderr, flush=True)
         os.makedirs(os.path.join(ROOT, a.out), exist_ok=True)
         with open(os.path.join(ROOT, a.out, "bench_all.json"), "w") as f:

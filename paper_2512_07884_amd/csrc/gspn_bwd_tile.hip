@@ -76,7 +76,8 @@ __device__ __forceinline__ void gw_store(rsrc_t rs, uint32_t voff, int so, const
 // ---------------------------------------------------------------------------
 // vertical directions: lines are image rows, 2 adjacent columns per lane
 // ---------------------------------------------------------------------------
-template <typename T, int PF, bool REV>
+// LOCAL: GSPN-local (Sec. 3.2), on instantiations of its own so that the global scan carries none of it
+template <typename T, int PF, bool REV, bool LOCAL>
 __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, float* est, int b, int c_first,
                                              int pk0, int rounds, int lane, int split) {
     constexpr int V = 2;
@@ -154,6 +155,9 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
     float gw0[V] = {0.f, 0.f}, gw1[V] = {0.f, 0.f}, gw2[V] = {0.f, 0.f};
     int n = 0, r = 0;
     int until_split = split;
+    StretchWalkBack walk;
+    if constexpr (LOCAL) walk.init(H, REV, p.kchunk);
+    bool no_prev = false;                     // this scan step has no line before it: its gw is 0, nothing flows into it
     for (int it0 = 0; it0 < nitems; it0 += PF) {
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
@@ -162,8 +166,10 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
                 if (r == 0) {
                     if (until_split == 0) lds_barrier();
                     --until_split;
+                    // scan step 0 (GSPN-local: the first line of a stretch)
+                    if constexpr (LOCAL) no_prev = walk.start(n == H - 1);
+                    else no_prev = n == H - 1;
                 }
-                const bool no_prev = n == H - 1;      // scan step 0: there is no line before it, its gw is 0
                 const float en0 = es[r * 128], en1 = es[r * 128 + 1];
                 const float q00 = wp0[0] * en0, q01 = wp0[1] * en1;
                 const float q10 = wp1[0] * en0, q11 = wp1[1] * en1;
@@ -196,6 +202,10 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
                 gw2[0] = fmaf(e0, hm1, gw2[0]); gw2[1] = fmaf(e1, hr, gw2[1]);
 #pragma unroll
                 for (int v = 0; v < V; ++v) { wn0[v] = elem<T>(cur.w0, v); wn1[v] = elem<T>(cur.w1, v); wn2[v] = elem<T>(cur.w2, v); }
+                if constexpr (LOCAL) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) { wn0[v] = no_prev ? 0.f : wn0[v]; wn1[v] = no_prev ? 0.f : wn1[v]; wn2[v] = no_prev ? 0.f : wn2[v]; }
+                }
                 issue(slot[k]);
                 if (++r == rounds) {
                     // end of the line: gw leaves the wave, this line's weights become the previous line's
@@ -239,7 +249,7 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
 // horizontal directions: lines are image columns, one image row per lane, the sweep is read in
 // chunks of CS columns (16 B per row and tensor: 4 of fp32, 8 of bf16; 4 of bf16 for odd widths)
 // ---------------------------------------------------------------------------
-template <typename T, bool REV, int CS>
+template <typename T, bool REV, int CS, bool LOCAL>
 struct BwdHorizontal {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -256,6 +266,8 @@ struct BwdHorizontal {
     int m, r;                      // (chunk, round) of the next item to consume
     float wc0, wc1, wc2;           // weights at the previous sweep position (last element of the previous chunk)
     float gw0[CS], gw1[CS], gw2[CS];
+    StretchWalkBack walk;          // GSPN-local only
+    unsigned starts;               // GSPN-local: bit k set <=> the element of the current chunk visited k-th starts a stretch
     Item buf0, buf1;
 
     __device__ __forceinline__ void init(const BwdTileArgs& a, float* tile, float* est, int d, int b, int c_first,
@@ -301,6 +313,8 @@ struct BwdHorizontal {
         wc0 = 0.f; wc1 = 0.f; wc2 = 0.f;
 #pragma unroll
         for (int e = 0; e < CS; ++e) { gw0[e] = 0.f; gw1[e] = 0.f; gw2[e] = 0.f; }
+        starts = 0;
+        if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
     }
 
     // Sweep chunk c covers the columns the backward pass visits c-th: the scan left->right is swept
@@ -333,6 +347,13 @@ struct BwdHorizontal {
     __device__ __forceinline__ void compute(const Item& s) {
         const int c0 = chunk_col(m);
         const bool last_chunk = m == nchunks - 1;
+        if constexpr (LOCAL) {
+            if (r == 0) {                                         // once per chunk, the same for all its rounds
+                starts = 0;
+#pragma unroll
+                for (int k = 0; k < CS; ++k) starts |= (walk.start(last_chunk && k == CS - 1) ? 1u : 0u) << k;
+            }
+        }
         float e = es[r * 64];
         float gl[CS], gu[CS];
         float w0p = wc0, w1p = wc1, w2p = wc2;
@@ -351,6 +372,7 @@ struct BwdHorizontal {
             trow[r * tile_round + c0 + ix] += elem<T>(s.l, ix) * e;
             float hm = (k == CS - 1) ? __uint_as_float(s.hm) : elem<T>(s.h, ixn);
             if (k == CS - 1) hm = last_chunk ? 0.f : hm;          // scan step 0 has no predecessor: gw = 0
+            if constexpr (LOCAL) hm = ((starts >> k) & 1u) ? 0.f : hm;   // nor has the first line of a stretch
             float hl = from_lane_below(hm), hr = from_lane_above(hm);
             hl = first ? 0.f : hl;
             hr = last ? 0.f : hr;
@@ -358,6 +380,10 @@ struct BwdHorizontal {
             gw1[ix] = fmaf(e, hm, gw1[ix]);
             gw2[ix] = fmaf(e, hr, gw2[ix]);
             w0p = elem<T>(s.w0, ix); w1p = elem<T>(s.w1, ix); w2p = elem<T>(s.w2, ix);
+            if constexpr (LOCAL) {
+                const bool z = (starts >> k) & 1u;                // nothing flows into the first line of a stretch
+                w0p = z ? 0.f : w0p; w1p = z ? 0.f : w1p; w2p = z ? 0.f : w2p;
+            }
         }
         es[r * 64] = e;
         {
@@ -413,7 +439,7 @@ struct BwdHorizontal {
     }
 };
 
-template <typename T, int PF, int MAXW, int HCS>
+template <typename T, int PF, int MAXW, int HCS, bool LOCAL>
 __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
     extern __shared__ float lds[];
     const BwdParams& p = a.p;
@@ -444,8 +470,8 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
             const int rounds = a.shared_group ? packs_v : 1;
             // the wave sweeping the top->bottom scan starts at the bottom rows, the other at the top rows
             const int split = nd == 2 ? (d == 0 ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
-            if (d == 0) bwd_vertical<T, PF, false>(a, tile, est, b, c_first, slot, rounds, lane, split);
-            else bwd_vertical<T, PF, true>(a, tile, est, b, c_first, slot, rounds, lane, split);
+            if (d == 0) bwd_vertical<T, PF, false, LOCAL>(a, tile, est, b, c_first, slot, rounds, lane, split);
+            else bwd_vertical<T, PF, true, LOCAL>(a, tile, est, b, c_first, slot, rounds, lane, split);
         } else if (nd == 2) {
             lds_barrier();
         }
@@ -464,7 +490,7 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
         if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
-            BwdHorizontal<T, false, HCS> hp;
+            BwdHorizontal<T, false, HCS, LOCAL> hp;
             if (busy) { hp.init(a, tile, est, 2, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_lr : nchunks) * rounds);
@@ -473,7 +499,7 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
                 if (busy) hp.run(half_lr * rounds, nchunks * rounds);
             }
         } else {
-            BwdHorizontal<T, true, HCS> hp;
+            BwdHorizontal<T, true, HCS, LOCAL> hp;
             if (busy) { hp.init(a, tile, est, 3, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_rl : nchunks) * rounds);
@@ -597,8 +623,13 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     // needs more registers than 8 waves per workgroup leave, so only workgroups of up to 4 waves take it)
     const bool wide = p.W % 8 == 0;
     void (*k)(BwdTileArgs);
-    if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8> : bwd_tile_kernel<float, 4, 8, 4>;
-    else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8> : bwd_tile_kernel<bf16_t, 4, 8, 4>;
+    if (p.kchunk > 0) {
+        if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, true> : bwd_tile_kernel<float, 4, 8, 4, true>;
+        else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, true> : bwd_tile_kernel<bf16_t, 4, 8, 4, true>;
+    } else {
+        if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, false> : bwd_tile_kernel<float, 4, 8, 4, false>;
+        else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, false> : bwd_tile_kernel<bf16_t, 4, 8, 4, false>;
+    }
     hipError_t e = allow_dynamic_lds((const void*)k, BWD_LDS_BUDGET);
     if (e != hipSuccess) return e;
     for (int part = 0; part < t.seq_parts; ++part) {          // same stream: the launches run one after the other

@@ -60,6 +60,41 @@ inline uint64_t stretch_start_bits(int S, int reversed, int kchunk, bool by_step
     return m;
 }
 
+// The same predicate as a running counter for kernels that walk the scan steps in order: `start()` is
+// called once per scan step and tells whether that step starts a stretch (uniform scalar work only).
+struct StretchWalk {
+    int until, gap, k;
+    // S lines along the scan axis; kchunk >= 1
+    __device__ __forceinline__ void init(int S, int reversed, int kchunk) {
+        k = kchunk;
+        until = 0;                                        // scan step 0 starts a stretch
+        gap = (reversed && S % kchunk) ? S % kchunk : kchunk;   // a reversed scan begins with the short last stretch
+    }
+    __device__ __forceinline__ bool start() {
+        const bool s = until == 0;
+        if (s) { until = gap; gap = k; }
+        --until;
+        return s;
+    }
+};
+
+// ... and for kernels that walk the scan steps against the scan order (backward sweeps): `start(at_step0)`
+// is called once per scan step, from the last one down to step 0.
+struct StretchWalkBack {
+    int phase, k, rev;
+    __device__ __forceinline__ void init(int S, int reversed, int kchunk) {
+        k = kchunk; rev = reversed;
+        // position of the last scan step inside its stretch, counted so that 0 = "starts a stretch"
+        phase = reversed ? 1 % kchunk : (S - 1) % kchunk;
+    }
+    __device__ __forceinline__ bool start(bool at_step0) {
+        const bool s = phase == 0 || at_step0;
+        if (rev) phase = (phase + 1 == k) ? 0 : phase + 1;
+        else phase = (phase == 0) ? k - 1 : phase - 1;
+        return s;
+    }
+};
+
 struct FwdParams {
     const void* x; const void* w; const void* lam; const void* u;
     void* y; void* hs;

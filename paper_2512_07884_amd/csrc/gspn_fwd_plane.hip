@@ -205,6 +205,13 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         const int ic = active ? i : L - 1;
         const bool first = i == 0, last = i == L - 1;
         const int tpos = ic * ps + s0;
+        // GSPN-local (Sec. 3.2): a line that starts a stretch has no predecessor, so its three taps are stored as 0
+        // like the out-of-line ones, and the sweep restarts from lam*x there without knowing about stretches.
+        // The prefetching variant has no registers to spare for the test where the weights are written: it clears
+        // those lines in a pass of its own afterwards.
+        constexpr bool LOCAL_PASS = LOCAL && WPRE;
+        const uint64_t starts = LOCAL ? a.seg[d] : 0ull;
+        auto no_pred = [&](int row, int col) { return LOCAL && !LOCAL_PASS && ((starts >> (vert ? row : col)) & 1ull) != 0; };
 
         // ---- operands into LDS
         if constexpr (FLAT) {
@@ -235,7 +242,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                     if (e < ew) {
                         // a tap that points outside the line is stored as 0, whatever the tensor holds there
                         const int pos = vert ? col : row;
-                        const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1);
+                        const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1) || no_pred(row, col);
                         plds_st(wreg + 4u * (uint32_t)(chn * 4 * HP + 4 * (row * W + col) + tap),
                                 outside ? 0.f : chunk_elem<T>(v, e));
                         if (++col == W) { col = 0; if (++row == H) { row = 0; if (++tap == 3) { tap = 0; ++chn; } } }
@@ -252,7 +259,8 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                         for (int e = 0; e < E; ++e) {
                             // a tap that points outside the line is stored as 0, whatever the tensor holds there
                             const int pos = vert ? wcol[j] + e : wrow[j];
-                            const bool outside = (wtap[j] == 0 && pos == 0) || (wtap[j] == 2 && pos == L - 1);
+                            const bool outside = (wtap[j] == 0 && pos == 0) || (wtap[j] == 2 && pos == L - 1) ||
+                                                 no_pred(wrow[j], wcol[j] + e);
                             plds_st(wreg + 4u * (uint32_t)(wl[j] + 4 * e), outside ? 0.f : chunk_elem<T>(wsh[j], e));
                         }
                     }
@@ -268,7 +276,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
                         const int pos = vert ? col + e : row;
-                        const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1);
+                        const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1) || no_pred(row, col + e);
                         plds_st(wreg + 4u * (uint32_t)(4 * (row * P + col + e) + tap), outside ? 0.f : chunk_elem<T>(v, e));
                     }
                 }
@@ -292,7 +300,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
                             const int pos = vert ? col0[k] + e : row0[k];
-                            const bool outside = (t == 0 && pos == 0) || (t == 2 && pos == L - 1);
+                            const bool outside = (t == 0 && pos == 0) || (t == 2 && pos == L - 1) || no_pred(row0[k], col0[k] + e);
                             plds_st(o + 16u * e, outside ? 0.f : chunk_elem<T>(wt[k], e));
                         }
                     }
@@ -316,21 +324,16 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         }
         if constexpr (SHARED) lds_barrier();               // weights of this direction are in place (LDS only: the
                                                            // requests above stay in flight across the barrier)
-        if constexpr (LOCAL) {
-            // GSPN-local: a line that starts a stretch has no predecessor, so its three taps become 0 and
-            // the sweep below restarts from lam*x there without knowing about stretches
-            const uint64_t starts = a.seg[d];
-            const int nch = SHARED ? 1 : cpw;              // weight regions to patch: the group's, or the wave's own
-            const int t0 = SHARED ? (int)threadIdx.x : lane, tn = SHARED ? nthreads : 64;
+
+        if constexpr (LOCAL_PASS) {
             for (int r = 0; r < S; ++r) {
                 if (!((starts >> r) & 1ull)) continue;
-                for (int j = t0; j < nch * L; j += tn) {
-                    const int chn = j / L, jj = j - chn * L;
-                    const uint32_t o = wreg + 16u * (uint32_t)(chn * HP + (vert ? r * P + jj : jj * P + r));
+                for (int j = (int)threadIdx.x; j < L; j += nthreads) {
+                    const uint32_t o = wreg + 16u * (uint32_t)(vert ? r * P + j : j * P + r);
                     plds_st(o, 0.f); plds_st(o + 4u, 0.f); plds_st(o + 8u, 0.f);
                 }
             }
-            if constexpr (SHARED) lds_barrier();
+            lds_barrier();
         }
 
         // ---- the scan: h overwrites a

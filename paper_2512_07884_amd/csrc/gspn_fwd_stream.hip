@@ -29,7 +29,8 @@ struct StreamArgs {
 // ---------------------------------------------------------------------------
 // vertical direction, one wave per line
 // ---------------------------------------------------------------------------
-template <typename T, int V, int PF, bool REV>
+// LOCAL: GSPN-local (Sec. 3.2), on instantiations of its own so that the global scan carries none of it
+template <typename T, int V, int PF, bool REV, bool LOCAL>
 struct VStream {
     static constexpr int NB = V * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -39,10 +40,12 @@ struct VStream {
     int H, row_bytes;
     bool first, last;
     float h[V];
+    StretchWalk walk;   // GSPN-local only
 
     __device__ __forceinline__ void init(const FwdParams& p, int b, int c, int lane) {
         constexpr int d = REV ? 1 : 0;
         H = p.H;
+        if constexpr (LOCAL) walk.init(p.H, REV, p.kchunk);
         const int W = p.W, HW = H * W;
         const int g = c / p.cpg;
         const size_t planes = (size_t)p.B * p.C;
@@ -89,12 +92,16 @@ struct VStream {
                 if (t < t_end) {
                     const Line& cur = slot[k];
                     float av[V], w0[V], w1[V], w2[V], yv[V];
+                    // scan step 0 (only ever in ring slot 0): its weights are never used (the stored values may be
+                    // anything); GSPN-local: the same for the first line of every stretch, any slot
+                    bool start = t == 0;
+                    if constexpr (LOCAL) start = walk.start();
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
                         av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
                         w0[v] = elem<T>(cur.w0, v); w1[v] = elem<T>(cur.w1, v); w2[v] = elem<T>(cur.w2, v);
-                        // scan step 0 (only ever in ring slot 0): its weights are never used (the stored values may be anything)
-                        if (k == 0) { w0[v] = t == 0 ? 0.f : w0[v]; w1[v] = t == 0 ? 0.f : w1[v]; w2[v] = t == 0 ? 0.f : w2[v]; }
+                        if (LOCAL || k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
+                        if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
                     }
                     line_update<V>(h, av, w0, w1, w2, first, last);
 #pragma unroll
@@ -115,7 +122,7 @@ struct VStream {
 // ---------------------------------------------------------------------------
 // horizontal direction, the rows of the image split over `parts` waves, one row per lane
 // ---------------------------------------------------------------------------
-template <typename T, int CS, bool REV>
+template <typename T, int CS, bool REV, bool LOCAL>
 struct HStream {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -127,6 +134,7 @@ struct HStream {
     const float* mb_dn;
     bool edge, top_lane, bot_lane, has_up, has_dn, img_first, img_last;
     float h;
+    StretchWalk walk;   // GSPN-local only
     uint32_t bx[NR], bl[NR], bu[NR], b0[NR], b1[NR], b2[NR], by[NR];
 
     __device__ __forceinline__ void init(const FwdParams& p, float* mailbox, int parts, int b, int c, int part, int lane) {
@@ -156,6 +164,7 @@ struct HStream {
         mb_up = mailbox + (has_up ? part - 1 : part) * 4 + 2;
         mb_dn = mailbox + (has_dn ? part + 1 : part) * 4 + 0;
         h = 0.f;
+        if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
     }
 
     __device__ __forceinline__ int chunk_col(int c) const { return (REV ? nchunks - 1 - c : c) * CS; }
@@ -182,9 +191,10 @@ struct HStream {
             const int par = k & 1;                           // CS is even: parity of the scan step
             const float pu = mb_up[par ^ 1];
             const float pd = mb_dn[par ^ 1];
-            const bool start = (c == 0) && (k == 0);         // scan step 0: its weights are never used
+            bool start = (c == 0) && (k == 0);               // scan step 0: its weights are never used
+            if constexpr (LOCAL) start = walk.start();       // ... nor those of a stretch's first line
             float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
-            if (k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
+            if (LOCAL || k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
             const float av = elem<T>(bl, e) * elem<T>(bx, e);
             float up = from_lane_below(h), dn = from_lane_above(h);
             up = top_lane ? (has_up ? pu : 0.f) : up;
@@ -220,7 +230,7 @@ struct HStream {
     }
 };
 
-template <typename T, int V, int CS, int PF>
+template <typename T, int V, int CS, int PF, bool LOCAL>
 __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
     __shared__ float mailbox[8 * 4];
     const FwdParams& p = a.p;
@@ -238,12 +248,12 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
         if (nd == 2) {
             const int split = (H + 1) / 2;          // top->bottom wave: rows [0, split) first; bottom->top: rows [split, H)
             if (wave == 0) {
-                VStream<T, V, PF, false> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, false, LOCAL> v; v.init(p, b, c, lane);
                 v.template run<false>(0, split);
                 __syncthreads();
                 v.template run<true>(split, H);
             } else if (wave == 1) {
-                VStream<T, V, PF, true> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, true, LOCAL> v; v.init(p, b, c, lane);
                 v.template run<false>(0, H - split);
                 __syncthreads();
                 v.template run<true>(H - split, H);
@@ -253,8 +263,8 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
             wrote = true;
         } else if (nd == 1) {
             if (wave == 0) {
-                if (has_tb) { VStream<T, V, PF, false> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
-                else        { VStream<T, V, PF, true> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
+                if (has_tb) { VStream<T, V, PF, false, LOCAL> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
+                else        { VStream<T, V, PF, true, LOCAL> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
             }
             wrote = true;
         }
@@ -267,10 +277,10 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
         __syncthreads();                        // y of the previous phase visible, mailbox cleared
         if (wave < a.parts) {
             if (dsel == 0) {
-                HStream<T, CS, false> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, false, LOCAL> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             } else {
-                HStream<T, CS, true> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, true, LOCAL> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             }
         } else {
@@ -307,7 +317,8 @@ bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p
 template <typename T, int V, int CS, int PF>
 static hipError_t launch_stream(const StreamArgs& a, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * a.p.C)), block(64 * a.nwaves);
-    hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF>), grid, block, 0, s, a);
+    if (a.p.kchunk > 0) hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 

@@ -38,7 +38,7 @@ struct TileArgs {
 // ---------------------------------------------------------------------------
 // vertical direction (d = 0 top->bottom, 1 bottom->top): lines are image rows
 // ---------------------------------------------------------------------------
-template <typename T, int V, int PF, bool REV, bool SAVE>
+template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL>
 __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int b, int c_first, int pk,
                                               int lane, int split) {
     constexpr int NB = V * (int)sizeof(T);
@@ -101,10 +101,21 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     int until_split = split;     // steps left before the mid-scan barrier (negative: none)
 
     // `scan_start`: this is scan step 0, whose weights are never used (the stored values may be
-    // anything): they are replaced by 0 so the (zero) initial state contributes exactly 0
+    // anything): they are replaced by 0 so the (zero) initial state contributes exactly 0.  GSPN-local
+    // (Sec. 3.2): the same at the first line of every stretch, where the carried state counts as 0 too.
+    StretchWalk walk;
+    if constexpr (LOCAL) walk.init(H, REV, p.kchunk);
     auto step = [&](const Line& cur, bool maybe_start, bool scan_start) {
         if (until_split == 0) lds_barrier();
         --until_split;
+        if constexpr (LOCAL) {
+            maybe_start = true;
+            scan_start = walk.start();
+            if (scan_start) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) h[v] = 0.f;
+            }
+        }
         float av[V], w0[V], w1[V], w2[V], uv[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
@@ -167,7 +178,7 @@ struct HBuf { uint32_t x[V][CS * sizeof(T) / 4], l[V][CS * sizeof(T) / 4], u[V][
 // DB = true: two chunk buffers, the next chunk is loaded while the current one is consumed.
 // DB = false: one buffer (for chunks too large to hold twice); the next chunk is requested as soon
 // as the current one is consumed and other waves of the CU cover the wait.
-template <typename T, int V, int CS, bool REV, bool SAVE, bool DB>
+template <typename T, int V, int CS, bool REV, bool SAVE, bool DB, bool LOCAL>
 struct HorizontalPass {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -178,6 +189,7 @@ struct HorizontalPass {
     int pitch;
     bool active, first, last;
     float h[V];
+    StretchWalk walk;   // GSPN-local only
     HBuf<T, V, CS> buf0, buf1;
 
     __device__ __forceinline__ void init(const TileArgs& a, float* tile, int d, int b, int c_first, int pk, int lane) {
@@ -210,6 +222,7 @@ struct HorizontalPass {
         trow = tile + ((pk * a.ph + plc) * H + ic * V) * a.pitch;
 #pragma unroll
         for (int v = 0; v < V; ++v) h[v] = 0.f;
+        if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
     }
 
     // byte offset of chunk c (in scan order) inside a row
@@ -236,12 +249,15 @@ struct HorizontalPass {
         for (int k = 0; k < CS; ++k) {
             const int e = REV ? CS - 1 - k : k;       // element inside the chunk, compile-time
             float av[V], w0[V], w1[V], w2[V];
-            const bool start = (c == 0) && (k == 0);  // first line of the scan: its weights are never read
+            // first line of the scan (GSPN-local: of a stretch): its weights are never read, the state before it is 0
+            bool start = (c == 0) && (k == 0);
+            if constexpr (LOCAL) start = walk.start();
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 av[v] = elem<T>(s.l[v], e) * elem<T>(s.x[v], e);
                 w0[v] = elem<T>(s.w0[v], e); w1[v] = elem<T>(s.w1[v], e); w2[v] = elem<T>(s.w2[v], e);
-                if (k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
+                if (LOCAL || k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
+                if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
             }
             line_update<V>(h, av, w0, w1, w2, first, last);
 #pragma unroll
@@ -296,7 +312,7 @@ struct HorizontalPass {
 // Because every step is its own barrier interval, the two directions never own the same tile
 // column at the same time and no mid-scan split is needed.
 // ---------------------------------------------------------------------------
-template <typename T, int CS, bool REV, bool SAVE>
+template <typename T, int CS, bool REV, bool SAVE, bool LOCAL>
 struct HorizontalSplitPass {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -309,6 +325,7 @@ struct HorizontalSplitPass {
     const float* mb_dn; // edge state of the part below (its first row), parity 0
     bool active, edge, top_lane, bot_lane, has_up, has_dn, img_first, img_last;
     float h;
+    StretchWalk walk;   // GSPN-local only
     uint32_t bx[NR], bl[NR], bu[NR], b0[NR], b1[NR], b2[NR];
 
     // mailbox layout: [task = channel * 2 + direction slot][part][side: 0 first row, 1 last row][parity]
@@ -345,6 +362,7 @@ struct HorizontalSplitPass {
         mb_up = task + (has_up ? part - 1 : part) * 4 + 2;
         mb_dn = task + (has_dn ? part + 1 : part) * 4 + 0;
         h = 0.f;
+        if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
     }
 
     __device__ __forceinline__ int chunk_col(int c) const { return (REV ? nchunks - 1 - c : c) * CS; }
@@ -372,9 +390,10 @@ struct HorizontalSplitPass {
             const float pu = mb_up[par ^ 1];
             const float pd = mb_dn[par ^ 1];
             const float yold = trow[col0 + e];               // read early: one LDS round trip per step, not three
-            const bool start = (c == 0) && (k == 0);
+            bool start = (c == 0) && (k == 0);
+            if constexpr (LOCAL) start = walk.start();
             float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
-            if (k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
+            if (LOCAL || k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
             const float av = elem<T>(bl, e) * elem<T>(bx, e);
             float up = from_lane_below(h), dn = from_lane_above(h);
             up = top_lane ? (has_up ? pu : 0.f) : up;
@@ -407,7 +426,7 @@ struct HorizontalSplitPass {
     }
 };
 
-template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW>
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL>
 __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
     extern __shared__ float tile[];
     const FwdParams& p = a.p;
@@ -436,8 +455,8 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
             const int pk = wave / nd;
             const int d = (nd == 2) ? (wave - pk * nd) : ((p.mask & 1) ? 0 : 1);
             const int split = nd == 2 ? (d == 0 ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
-            if (d == 0) vertical_pass<T, VV, PF, false, SAVE>(a, tile, b, c_first, pk, lane, split);
-            else vertical_pass<T, VV, PF, true, SAVE>(a, tile, b, c_first, pk, lane, split);
+            if (d == 0) vertical_pass<T, VV, PF, false, SAVE, LOCAL>(a, tile, b, c_first, pk, lane, split);
+            else vertical_pass<T, VV, PF, true, SAVE, LOCAL>(a, tile, b, c_first, pk, lane, split);
         } else if (nd == 2) {
             lds_barrier();
         }
@@ -467,13 +486,13 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
             if (nd == 0) {
                 lds_barrier();
             } else if (work && dd == 2) {
-                HorizontalSplitPass<T, CS, false, SAVE> hp;
+                HorizontalSplitPass<T, CS, false, SAVE, LOCAL> hp;
                 hp.init(a, tile, mailbox, 2, dslot, b, c_first, kc, part, lane);
                 hp.prologue();
                 lds_barrier();
                 hp.run();
             } else if (work) {
-                HorizontalSplitPass<T, CS, true, SAVE> hp;
+                HorizontalSplitPass<T, CS, true, SAVE, LOCAL> hp;
                 hp.init(a, tile, mailbox, 3, dslot, b, c_first, kc, part, lane);
                 hp.prologue();
                 lds_barrier();
@@ -485,7 +504,7 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
         } else if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
-            HorizontalPass<T, VH, CS, false, SAVE, DB> hp;
+            HorizontalPass<T, VH, CS, false, SAVE, DB, LOCAL> hp;
             if (busy) { hp.init(a, tile, 2, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();                                  // vertical phase complete (first loads already in flight)
             if (busy) hp.run(0, nd == 2 ? half_lr : nchunks);
@@ -494,7 +513,7 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
                 if (busy) hp.run(half_lr, nchunks);
             }
         } else {
-            HorizontalPass<T, VH, CS, true, SAVE, DB> hp;
+            HorizontalPass<T, VH, CS, true, SAVE, DB, LOCAL> hp;
             if (busy) { hp.init(a, tile, 3, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, nd == 2 ? half_rl : nchunks);
@@ -600,14 +619,21 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
 
 bool fwd_tile_applicable(const FwdParams& p, int dtype) { return plan_tile(p, dtype).ok; }
 
-template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW>
-static hipError_t launch_one(const TileArgs& a, const TilePlan& t, hipStream_t s) {
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL>
+static hipError_t launch_one_l(const TileArgs& a, const TilePlan& t, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * t.nwaves);
-    auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW>;
+    auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW, LOCAL>;
     hipError_t e = allow_dynamic_lds((const void*)k, LDS_BUDGET);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();
+}
+
+// GSPN-local (Sec. 3.2) runs on instantiations of its own, so that the global scan carries none of it
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW>
+static hipError_t launch_one(const TileArgs& a, const TilePlan& t, hipStream_t s) {
+    return a.p.kchunk > 0 ? launch_one_l<T, VV, VH, CS, DB, PF, SAVE, MAXW, true>(a, t, s)
+                          : launch_one_l<T, VV, VH, CS, DB, PF, SAVE, MAXW, false>(a, t, s);
 }
 
 template <typename T, int VV, int VH, int CS, bool DB, int PF>

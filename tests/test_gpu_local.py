@@ -1,6 +1,5 @@
 """GPU parity of the GSPN-local calls (Sec. 3.2: propagation confined to stretches of kchunk lines)
-against the fp64 oracle, through the C ABI, forward and backward, on the kernels that take them
-(plane kernels for small maps, generic kernels otherwise)."""
+against the fp64 oracle, through the C ABI, forward and backward, on every kernel family."""
 import numpy as np
 import pytest
 
@@ -100,11 +99,16 @@ def test_local_scans_on_the_plane_kernels(shape, kchunk):
     check_local(shape, kchunk)
 
 
-# forward-only plane shapes (lines of 33..64 positions) and shapes on the generic kernels (whose bf16 gw is summed
-# in storage precision channel by channel: small groups here)
+# larger maps: forward plane kernel with the backward tile kernel (lines of 33..64 positions), the tile kernels'
+# horizontal variants (whole rows, 64 B and 16 B bursts, rows split over waves), the stream kernel, per-channel
+# and shared weights, and ragged shapes on the generic kernels (whose bf16 gw is summed in storage precision
+# channel by channel: small groups there)
 @pytest.mark.parametrize("shape,kchunk,plans", [
-    ((2, 8, 56, 56, 2, "bf16"), 14, ("plane", "generic")), ((1, 8, 64, 64, 8, "bf16"), 10, ("plane", "generic")),
-    ((1, 6, 40, 24, 3, "bf16"), 16, ("plane", "generic")), ((1, 4, 128, 128, 2, "bf16"), 32, ("generic", "generic")),
+    ((2, 8, 56, 56, 2, "bf16"), 14, ("plane", "tile")), ((1, 8, 64, 64, 8, "bf16"), 10, ("plane", "tile")),
+    ((1, 6, 40, 24, 3, "bf16"), 16, ("plane", "generic")), ((2, 8, 56, 56, 2, "f32"), 9, ("tile", "tile")),
+    ((1, 4, 128, 128, 2, "bf16"), 32, ("tile", "generic")), ((1, 4, 128, 128, 4, "bf16"), 5, ("tile", "generic")),
+    ((1, 8, 64, 128, 2, "f32"), 48, ("tile", "tile")), ((1, 24, 16, 40, 2, "f32"), 3, ("plane", "tile")),
+    ((2, 8, 40, 32, 8, "f32"), 7, ("plane", "tile")), ((1, 4, 96, 72, 2, "bf16"), 20, ("tile", "generic")),
     ((1, 4, 33, 70, 2, "f32"), 9, ("generic", "generic")), ((2, 6, 9, 13, 3, "f32"), 4, ("generic", "generic")),
     ((1, 2, 1, 37, 1, "f32"), 5, ("generic", "generic")), ((1, 2, 64, 256, 1, "bf16"), 100, ("generic", "generic"))],
     ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
@@ -117,6 +121,40 @@ def test_local_scans_on_larger_and_ragged_maps(shape, kchunk, plans):
     check_local(shape, kchunk)
 
 
+@pytest.mark.parametrize("shape,kchunk", [((2, 8, 56, 56, 2, "bf16"), 9), ((2, 16, 28, 28, 2, "f32"), 5),
+                                          ((1, 12, 16, 32, 3, "f32"), 6), ((2, 8, 28, 28, 8, "f32"), 14)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_local_scans_on_the_tile_kernels_for_small_maps(shape, kchunk, monkeypatch):
+    """Shapes the plane kernels normally take, on the tile kernels (whole-row bursts among them)."""
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FWD_NO_PLANE", "1")
+    monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+    B, C, H, W, Gr, dtype = shape
+    dt = int(dtype == "bf16")
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, True) == "tile"
+    assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0) == "tile"
+    check_local(shape, kchunk)
+
+
+@pytest.mark.parametrize("shape,kchunk", [((1, 2, 256, 256, 1, "bf16"), 37), ((1, 2, 512, 512, 2, "bf16"), 64),
+                                          ((1, 2, 128, 256, 2, "f32"), 100), ((1, 2, 256, 1024, 1, "bf16"), 300)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_local_scans_on_the_stream_kernel(shape, kchunk):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, int(dtype == "bf16"), 0, False) == "stream"
+    cfg = WL.ScanConfig("localstream", B, C, H, W, Gr, dtype, 15, 1.0, 87)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    f = WL.inputs_as_f64(inp, dtype)
+    y_ref, _ = O.scan_fwd_local(f["x"], f["w"], f["lam"], f["u"], kchunk, 15)
+    import torch
+    dev = {k: to_device(v, dtype) for k, v in inp.items()}
+    y = empty_like_dev((B, C, H, W), dtype, float("nan"))
+    G.gspn_scan_fwd_local(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, kchunk=kchunk, G=Gr)
+    torch.cuda.synchronize()
+    assert rel_inf_err(to_host_f64(y), y_ref) <= TOL[dtype]
+
+
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9, 13])
 @pytest.mark.parametrize("shape,kchunk", [((2, 8, 28, 28, 2, "f32"), 6), ((1, 4, 20, 36, 2, "bf16"), 8)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
@@ -125,7 +163,8 @@ def test_local_scans_direction_masks(shape, kchunk, mask):
 
 
 @pytest.mark.parametrize("shape,kchunk", [((1, 8, 28, 28, 2, "f32"), 7), ((1, 8, 14, 14, 2, "bf16"), 5),
-                                          ((1, 4, 12, 10, 4, "f32"), 4), ((1, 2, 40, 70, 1, "f32"), 16)],
+                                          ((1, 4, 12, 10, 4, "f32"), 4), ((1, 2, 40, 70, 1, "f32"), 16),
+                                          ((1, 4, 56, 56, 2, "f32"), 8), ((1, 2, 128, 128, 1, "bf16"), 24)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_weights_on_the_first_line_of_a_stretch_are_never_read(shape, kchunk):
     check_local(shape, kchunk, poison_starts=True)

@@ -47,6 +47,10 @@ dense solve with the links between stretches removed, kchunk = 1 (no
 propagation: y = sum_d u_d lam_d x) and kchunk >= scan length (the global
 scan), confinement of a perturbation to its stretch, central finite
 differences and the adjoint identity for the backward.
+Weights as logits (weights_from_logits, scan_*_logits, tests/test_oracle_logits.py):
+scipy's softmax on the taps that exist, rows of the assembled T_i summing to
+1, shift invariance, indifference to what a masked logit holds, central finite
+differences through the logits.
 """
 from __future__ import annotations
 
@@ -289,6 +293,69 @@ def scan_bwd_local(gy, x, w, lam, u, h_all, kchunk, dir_mask=15):
             c(glam[d])[...] = gls[d]
             c(gu[d])[...] = gus[d]
     return gx, gw, glam, gu
+
+
+# --------------------------------------------------------------------------
+# weights given as raw logits (the normalisation of Sec. 3.2 done on the way in)
+# --------------------------------------------------------------------------
+def _outside_taps(d, H, W):
+    """[3, H, W] bool: tap k at (r, c) addresses a neighbour outside the line (column c+k-1 for the vertical
+    scans, row r+k-1 for the horizontal ones, image coordinates)."""
+    out = np.zeros((3, H, W), dtype=bool)
+    if d < 2:
+        out[0, :, 0] = True
+        out[2, :, W - 1] = True
+    else:
+        out[0, 0, :] = True
+        out[2, H - 1, :] = True
+    return out
+
+
+def weights_from_logits(z):
+    """Row-stochastic tridiagonal weights from raw logits (Sec. 3.2: the weights are "learned and normalized"
+    so that every row of T_i sums to 1; the normaliser taken here is the softmax over the three taps).
+    A tap whose neighbour lies outside the line gets weight 0 and takes no part in the normalisation, whatever
+    its logit holds -- so the rows at the ends of a line are stochastic over the two neighbours that exist.
+
+    z : [4, B, G, 3, H, W] -> w of the same shape
+    """
+    z = np.asarray(z, dtype=np.float64)
+    H, W = z.shape[-2:]
+    w = np.zeros_like(z)
+    for d in ALL_DIRS:
+        out = _outside_taps(d, H, W)
+        zd = np.where(out, -np.inf, z[d])                 # what a masked logit holds (NaN included) is never used
+        m = zd.max(axis=-3, keepdims=True)
+        e = np.exp(zd - m)
+        w[d] = e / e.sum(axis=-3, keepdims=True)
+    return w
+
+
+def logits_grad_from_weights_grad(gw, w):
+    """Gradient w.r.t. the logits given the gradient w.r.t. the normalised weights (softmax over the taps,
+    per position): gz_k = w_k (gw_k - sum_j w_j gw_j).  Taps outside the line have w = 0, hence gz = 0."""
+    gw = np.asarray(gw, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    return w * (gw - (w * gw).sum(axis=-3, keepdims=True))
+
+
+def scan_fwd_logits(x, z, lam, u, dir_mask=15, kchunk=None):
+    """Forward scan with the weights given as logits z [4, B, G, 3, H, W]; otherwise as scan_fwd
+    (scan_fwd_local with kchunk)."""
+    w = weights_from_logits(z)
+    if kchunk is None:
+        return scan_fwd(x, w, lam, u, dir_mask)
+    return scan_fwd_local(x, w, lam, u, kchunk, dir_mask)
+
+
+def scan_bwd_logits(gy, x, z, lam, u, h_all, dir_mask=15, kchunk=None):
+    """Backward scan with the weights given as logits: returns gx, gz, glam, gu (gz in place of gw)."""
+    w = weights_from_logits(z)
+    if kchunk is None:
+        gx, gw, glam, gu = scan_bwd(gy, x, w, lam, u, h_all, dir_mask)
+    else:
+        gx, gw, glam, gu = scan_bwd_local(gy, x, w, lam, u, h_all, kchunk, dir_mask)
+    return gx, logits_grad_from_weights_grad(gw, w), glam, gu
 
 
 # --------------------------------------------------------------------------

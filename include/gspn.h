@@ -61,7 +61,7 @@ typedef enum {
     GSPN_ERR_SHAPE = 2,       /* a dimension or kchunk < 1, C % G != 0, dir_mask == 0 or > 15 */
     GSPN_ERR_DTYPE = 3,       /* dtype is not GSPN_F32 / GSPN_BF16                        */
     GSPN_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                        */
-    GSPN_ERR_UNSUPPORTED = 5, /* a line longer than GSPN_MAX_LINE, or unknown flag bits  */
+    GSPN_ERR_UNSUPPORTED = 5, /* a line longer than GSPN_MAX_LINE (GSPN_MAX_LINE_LOGITS), unknown flag bits */
     GSPN_ERR_HIP = 6          /* the HIP runtime refused the launch                      */
 } gspn_status;
 
@@ -121,6 +121,30 @@ int gspn_scan_bwd_local(const void* gy, const void* x, const void* w, const void
                         int B, int C, int H, int W, int G, int kchunk,
                         unsigned dir_mask, int dtype, unsigned flags, void* stream);
 
+/* Weights given as raw logits: the normalisation of Sec. 3.2 ("learned and normalized to be row-stochastic")
+ * done inside the call instead of by a pass of its own over w beforehand.  z has the layout of w,
+ * [4][B,G,3,H,W]; the weights used are the softmax of the three logits stored for a position, taken over the
+ * taps whose neighbour exists: at the two ends of a line the tap that points outside gets weight 0 and takes no
+ * part in the normalisation, whatever its logit holds (it is never read), so every row of T_i sums to 1.  The
+ * logits of a line without predecessor (first line of the scan, of a stretch) are never read either.  The
+ * softmax is computed in fp32 from the stored logits and is not rounded to the storage type.
+ * The backward call returns gz, the gradient w.r.t. the logits, where gspn_scan_bwd returns gw:
+ *     gz_k = w_k * (gw_k - sum_j w_j gw_j)      per position, with gw as defined above;
+ * it is 0 for taps that point outside the line and on lines without predecessor.
+ * kchunk as in the GSPN-local calls; pass GSPN_MAX_LINE for the global scan.  H, W <= GSPN_MAX_LINE_LOGITS,
+ * else GSPN_ERR_UNSUPPORTED.  A learned per-direction (per-channel) merge weight needs no entry point of its
+ * own: y = sum_d m_d u_d h_d is this call with u_d scaled by m_d. */
+enum { GSPN_MAX_LINE_LOGITS = 4096 };
+int gspn_scan_fwd_logits(const void* x, const void* z, const void* lam, const void* u,
+                         void* y, void* h_save,
+                         int B, int C, int H, int W, int G, int kchunk,
+                         unsigned dir_mask, int dtype, unsigned flags, void* stream);
+int gspn_scan_bwd_logits(const void* gy, const void* x, const void* z, const void* lam, const void* u,
+                         const void* h_save,
+                         void* gx, void* gz, void* glam, void* gu,
+                         int B, int C, int H, int W, int G, int kchunk,
+                         unsigned dir_mask, int dtype, unsigned flags, void* stream);
+
 /* Name of the kernel family the forward / backward call would dispatch to for
  * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
  * merged output fits in LDS), "stream" (larger maps, forward only), "generic" (any
@@ -139,6 +163,11 @@ const char* gspn_fwd_local_plan(int B, int C, int H, int W, int G, int kchunk, u
                                 unsigned flags, int has_h_save);
 const char* gspn_bwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
                                 unsigned flags);
+/* ... and for the calls that take logits */
+const char* gspn_fwd_logits_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                 unsigned flags, int has_h_save);
+const char* gspn_bwd_logits_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                 unsigned flags);
 
 /* Static, human-readable text for a gspn_status value. */
 const char* gspn_status_string(int status);

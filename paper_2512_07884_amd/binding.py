@@ -19,7 +19,9 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_bwd_local",
+           "gspn_scan_fwd_logits", "gspn_scan_bwd_logits",
            "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
+           "gspn_fwd_logits_plan", "gspn_bwd_logits_plan",
            "gspn_status_string", "gspn_version")
 
 
@@ -56,6 +58,14 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_scan_fwd_local.restype = ci
     lib.gspn_scan_bwd_local.argtypes = [vp] * 10 + [ci] * 6 + [cu, ci, cu, vp]
     lib.gspn_scan_bwd_local.restype = ci
+    lib.gspn_scan_fwd_logits.argtypes = [vp] * 6 + [ci] * 6 + [cu, ci, cu, vp]
+    lib.gspn_scan_fwd_logits.restype = ci
+    lib.gspn_scan_bwd_logits.argtypes = [vp] * 10 + [ci] * 6 + [cu, ci, cu, vp]
+    lib.gspn_scan_bwd_logits.restype = ci
+    lib.gspn_fwd_logits_plan.argtypes = [ci] * 6 + [cu, ci, cu, ci]
+    lib.gspn_fwd_logits_plan.restype = ctypes.c_char_p
+    lib.gspn_bwd_logits_plan.argtypes = [ci] * 6 + [cu, ci, cu]
+    lib.gspn_bwd_logits_plan.restype = ctypes.c_char_p
     lib.gspn_fwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu, ci]
     lib.gspn_fwd_local_plan.restype = ctypes.c_char_p
     lib.gspn_bwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu]
@@ -94,6 +104,17 @@ def gspn_fwd_local_plan(B, C, H, W, G, kchunk, dir_mask=DIR_ALL, dtype=GSPN_F32,
 
 def gspn_bwd_local_plan(B, C, H, W, G, kchunk, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:
     return load_library().gspn_bwd_local_plan(B, C, H, W, G, kchunk, dir_mask, dtype, flags).decode()
+
+
+GLOBAL_SCAN = 1 << 14      # a kchunk no line reaches (GSPN_MAX_LINE): the global scan
+
+
+def gspn_fwd_logits_plan(B, C, H, W, G, kchunk=GLOBAL_SCAN, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0, has_h_save=False) -> str:
+    return load_library().gspn_fwd_logits_plan(B, C, H, W, G, kchunk, dir_mask, dtype, flags, int(has_h_save)).decode()
+
+
+def gspn_bwd_logits_plan(B, C, H, W, G, kchunk=GLOBAL_SCAN, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:
+    return load_library().gspn_bwd_logits_plan(B, C, H, W, G, kchunk, dir_mask, dtype, flags).decode()
 
 
 # ---------------------------------------------------------------- marshalling
@@ -166,6 +187,14 @@ def gspn_scan_fwd_local(x, w, lam, u, y, h_save=None, *, kchunk: int, G: Optiona
                                               _stream(stream)))
 
 
+def gspn_scan_fwd_logits(x, z, lam, u, y, h_save=None, *, kchunk: int = GLOBAL_SCAN, G: Optional[int] = None,
+                         dir_mask: int = DIR_ALL, flags: int = 0, stream=None) -> None:
+    """As gspn_scan_fwd with the weights given as raw logits z (softmax over the taps that exist, inside the call)."""
+    ptrs, dims = _fwd_args(x, z, lam, u, y, h_save, G, flags)
+    _check(load_library().gspn_scan_fwd_logits(*ptrs, *dims, int(kchunk), dir_mask, _dtype_code(x), flags,
+                                               _stream(stream)))
+
+
 def _bwd_args(gy, x, w, lam, u, h_save, gx, gw, glam, gu, G, flags):
     B, C, H, W = x.shape
     if G is None:
@@ -192,3 +221,12 @@ def gspn_scan_bwd_local(gy, x, w, lam, u, h_save, gx, gw, glam, gu, *, kchunk: i
     args, dims = _bwd_args(gy, x, w, lam, u, h_save, gx, gw, glam, gu, G, flags)
     _check(load_library().gspn_scan_bwd_local(*args, *dims, int(kchunk), dir_mask, _dtype_code(x), flags,
                                               _stream(stream)))
+
+
+
+def gspn_scan_bwd_logits(gy, x, z, lam, u, h_save, gx, gz, glam, gu, *, kchunk: int = GLOBAL_SCAN,
+                         G: Optional[int] = None, dir_mask: int = DIR_ALL, flags: int = 0, stream=None) -> None:
+    """Gradients of gspn_scan_fwd_logits; gz (shape of z) is the gradient w.r.t. the logits; outputs overwritten."""
+    args, dims = _bwd_args(gy, x, z, lam, u, h_save, gx, gz, glam, gu, G, flags)
+    _check(load_library().gspn_scan_bwd_logits(*args, *dims, int(kchunk), dir_mask, _dtype_code(x), flags,
+                                               _stream(stream)))

@@ -27,14 +27,15 @@ int effective_kchunk(int kchunk, int H, int W) { return (kchunk >= H && kchunk >
 
 extern "C" {
 
-int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const void* u,
+static int scan_fwd_any(const void* x, const void* w, const void* lam, const void* u,
                         void* y, void* h_save,
-                        int B, int C, int H, int W, int G, int kchunk,
+                        int B, int C, int H, int W, int G, int kchunk, int logits,
                         unsigned dir_mask, int dtype, unsigned flags, void* stream) {
     if (!x || !w || !lam || !u || !y) return GSPN_ERR_NULL;
     int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
     if (st != GSPN_OK) return st;
     if (kchunk < 1) return GSPN_ERR_SHAPE;
+    if (logits && (H > GSPN_MAX_LINE_LOGITS || W > GSPN_MAX_LINE_LOGITS)) return GSPN_ERR_UNSUPPORTED;
     if (misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y) ||
         (h_save && misaligned(h_save)))
         return GSPN_ERR_ALIGN;
@@ -43,8 +44,23 @@ int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const voi
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
     p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
     p.kchunk = effective_kchunk(kchunk, H, W);
+    p.logits = logits;
     hipError_t e = launch_fwd(p, dtype, (hipStream_t)stream);
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const void* u,
+                        void* y, void* h_save,
+                        int B, int C, int H, int W, int G, int kchunk,
+                        unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    return scan_fwd_any(x, w, lam, u, y, h_save, B, C, H, W, G, kchunk, 0, dir_mask, dtype, flags, stream);
+}
+
+int gspn_scan_fwd_logits(const void* x, const void* z, const void* lam, const void* u,
+                         void* y, void* h_save,
+                         int B, int C, int H, int W, int G, int kchunk,
+                         unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    return scan_fwd_any(x, z, lam, u, y, h_save, B, C, H, W, G, kchunk, 1, dir_mask, dtype, flags, stream);
 }
 
 int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
@@ -54,15 +70,16 @@ int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
     return gspn_scan_fwd_local(x, w, lam, u, y, h_save, B, C, H, W, G, GSPN_MAX_LINE, dir_mask, dtype, flags, stream);
 }
 
-int gspn_scan_bwd_local(const void* gy, const void* x, const void* w, const void* lam, const void* u,
+static int scan_bwd_any(const void* gy, const void* x, const void* w, const void* lam, const void* u,
                         const void* h_save,
                         void* gx, void* gw, void* glam, void* gu,
-                        int B, int C, int H, int W, int G, int kchunk,
+                        int B, int C, int H, int W, int G, int kchunk, int logits,
                         unsigned dir_mask, int dtype, unsigned flags, void* stream) {
     if (!gy || !x || !w || !lam || !u || !h_save || !gx || !gw || !glam || !gu) return GSPN_ERR_NULL;
     int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
     if (st != GSPN_OK) return st;
     if (kchunk < 1) return GSPN_ERR_SHAPE;
+    if (logits && (H > GSPN_MAX_LINE_LOGITS || W > GSPN_MAX_LINE_LOGITS)) return GSPN_ERR_UNSUPPORTED;
     if (misaligned(gy) || misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) ||
         misaligned(h_save) || misaligned(gx) || misaligned(gw) || misaligned(glam) || misaligned(gu))
         return GSPN_ERR_ALIGN;
@@ -72,8 +89,25 @@ int gspn_scan_bwd_local(const void* gy, const void* x, const void* w, const void
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
     p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
     p.kchunk = effective_kchunk(kchunk, H, W);
+    p.logits = logits;
     hipError_t e = launch_bwd(p, dtype, (hipStream_t)stream);
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+int gspn_scan_bwd_local(const void* gy, const void* x, const void* w, const void* lam, const void* u,
+                        const void* h_save,
+                        void* gx, void* gw, void* glam, void* gu,
+                        int B, int C, int H, int W, int G, int kchunk,
+                        unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    return scan_bwd_any(gy, x, w, lam, u, h_save, gx, gw, glam, gu, B, C, H, W, G, kchunk, 0, dir_mask, dtype, flags, stream);
+}
+
+int gspn_scan_bwd_logits(const void* gy, const void* x, const void* z, const void* lam, const void* u,
+                         const void* h_save,
+                         void* gx, void* gz, void* glam, void* gu,
+                         int B, int C, int H, int W, int G, int kchunk,
+                         unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    return scan_bwd_any(gy, x, z, lam, u, h_save, gx, gz, glam, gu, B, C, H, W, G, kchunk, 1, dir_mask, dtype, flags, stream);
 }
 
 int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam, const void* u,
@@ -85,10 +119,12 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
                                dir_mask, dtype, flags, stream);
 }
 
-const char* gspn_fwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+static const char* fwd_plan_any(int B, int C, int H, int W, int G, int kchunk, int logits, unsigned dir_mask, int dtype,
                                 unsigned flags, int has_h_save) {
     if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK || kchunk < 1) return "invalid";
+    if (logits && (H > GSPN_MAX_LINE_LOGITS || W > GSPN_MAX_LINE_LOGITS)) return "invalid";
     FwdParams p = {};
+    p.logits = logits;
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G; p.mask = dir_mask;
     p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
     p.kchunk = effective_kchunk(kchunk, H, W);
@@ -96,14 +132,34 @@ const char* gspn_fwd_local_plan(int B, int C, int H, int W, int G, int kchunk, u
     return fwd_plan_name(p, dtype);
 }
 
-const char* gspn_bwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+const char* gspn_fwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                unsigned flags, int has_h_save) {
+    return fwd_plan_any(B, C, H, W, G, kchunk, 0, dir_mask, dtype, flags, has_h_save);
+}
+const char* gspn_fwd_logits_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                 unsigned flags, int has_h_save) {
+    return fwd_plan_any(B, C, H, W, G, kchunk, 1, dir_mask, dtype, flags, has_h_save);
+}
+
+static const char* bwd_plan_any(int B, int C, int H, int W, int G, int kchunk, int logits, unsigned dir_mask, int dtype,
                                 unsigned flags) {
     if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK || kchunk < 1) return "invalid";
+    if (logits && (H > GSPN_MAX_LINE_LOGITS || W > GSPN_MAX_LINE_LOGITS)) return "invalid";
     BwdParams p = {};
+    p.logits = logits;
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G; p.mask = dir_mask;
     p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
     p.kchunk = effective_kchunk(kchunk, H, W);
     return bwd_plan_name(p, dtype);
+}
+
+const char* gspn_bwd_local_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                unsigned flags) {
+    return bwd_plan_any(B, C, H, W, G, kchunk, 0, dir_mask, dtype, flags);
+}
+const char* gspn_bwd_logits_plan(int B, int C, int H, int W, int G, int kchunk, unsigned dir_mask, int dtype,
+                                 unsigned flags) {
+    return bwd_plan_any(B, C, H, W, G, kchunk, 1, dir_mask, dtype, flags);
 }
 
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags,
@@ -122,7 +178,7 @@ const char* gspn_status_string(int status) {
         case GSPN_ERR_SHAPE: return "bad shape: dimensions and kchunk must be >= 1, C divisible by G, dir_mask in 1..15";
         case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32 or GSPN_BF16";
         case GSPN_ERR_ALIGN: return "pointers must be 16-byte aligned";
-        case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE or unknown flag";
+        case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE (GSPN_MAX_LINE_LOGITS with logits) or unknown flag";
         case GSPN_ERR_HIP: return "HIP launch failed";
         default: return "unknown status";
     }

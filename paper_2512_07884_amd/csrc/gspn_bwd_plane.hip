@@ -512,6 +512,7 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
     PlanePlan t = {};
     const int es = dtype == 0 ? 4 : 2, E = 16 / es;             // elements per 16 B of storage
     if (p.H < 2 || p.W < 2 || p.H > 32 || p.W > 32) return t;
+    if (p.logits) return t;
     const int HW = p.H * p.W;
     const int m = p.H > p.W ? p.H : p.W;
     // channels per wave: eight / four when the lines are short enough, the group divides evenly and the

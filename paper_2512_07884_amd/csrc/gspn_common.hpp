@@ -27,6 +27,25 @@ __device__ __forceinline__ float ldf(const bf16_t* p) { return bf16_to_f32(*p); 
 __device__ __forceinline__ void stf(float* p, float v) { *p = v; }
 __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 
+// ---- weights from raw logits (Sec. 3.2: the weights are normalised so that every row of T_i sums to 1) ----
+// Softmax over the three taps of one position, in place.  A tap whose neighbour lies outside the line
+// (out0: tap 0, out2: tap 2) takes no part and gets weight 0, whatever its logit holds.
+__device__ __forceinline__ void softmax3(float& z0, float& z1, float& z2, bool out0, bool out2) {
+    const float ninf = -__builtin_huge_valf();
+    z0 = out0 ? ninf : z0;
+    z2 = out2 ? ninf : z2;
+    const float m = fmaxf(z1, fmaxf(z0, z2));
+    const float e0 = expf(z0 - m), e1 = expf(z1 - m), e2 = expf(z2 - m);   // exp(-inf) = 0
+    const float r = 1.0f / (e0 + e1 + e2);
+    z0 = e0 * r; z1 = e1 * r; z2 = e2 * r;
+}
+// Gradient w.r.t. the logits from the gradient w.r.t. the normalised weights, in place: linear in g, so it
+// may be applied to partial sums over channels.  w = 0 (masked tap, line without predecessor) gives 0.
+__device__ __forceinline__ void softmax3_grad(float& g0, float& g1, float& g2, float w0, float w1, float w2) {
+    const float dot = fmaf(w0, g0, fmaf(w1, g1, w2 * g2));
+    g0 = w0 * (g0 - dot); g1 = w1 * (g1 - dot); g2 = w2 * (g2 - dot);
+}
+
 // ---- direction geometry ----------------------------------------------------
 // Direction d scans S lines of length L.  Element (scan step t, position j) of a
 // [H][W] plane sits at  line(t)*stride_s + j*stride_j  with line(t) = t or S-1-t.
@@ -102,6 +121,7 @@ struct FwdParams {
     unsigned mask;
     int shared;   // 1: w/lam/u have a single direction slot
     int kchunk;   // GSPN-local stretch length; 0: global scan
+    int logits;   // 1: w holds raw logits, normalised on the way in (softmax3)
 };
 
 struct BwdParams {
@@ -111,6 +131,7 @@ struct BwdParams {
     unsigned mask;
     int shared;
     int kchunk;   // GSPN-local stretch length; 0: global scan
+    int logits;   // 1: w holds raw logits and gw receives the gradient w.r.t. them
 };
 
 // Raises a kernel's dynamic-LDS limit (up to the 160 KB of a gfx950 CU) once per (kernel, device).

@@ -52,9 +52,12 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
                     const int off = base + j * q.stride_j;
                     float h = ldf(lp + off) * ldf(xp + off);
                     if (!starts) {   // first line (of the scan, of a stretch): state before it is zero, its weights are not read
-                        h = fmaf(ldf(wp + HW + off), prev[j], h);
-                        if (j > 0) h = fmaf(ldf(wp + off), prev[j - 1], h);
-                        if (j + 1 < q.L) h = fmaf(ldf(wp + 2 * HW + off), prev[j + 1], h);
+                        const bool out0 = j == 0, out2 = j + 1 == q.L;     // no neighbour there: that tap is never read
+                        float w0 = out0 ? 0.f : ldf(wp + off), w1 = ldf(wp + HW + off), w2 = out2 ? 0.f : ldf(wp + 2 * HW + off);
+                        if (p.logits) softmax3(w0, w1, w2, out0, out2);
+                        h = fmaf(w1, prev[j], h);
+                        if (!out0) h = fmaf(w0, prev[j - 1], h);
+                        if (!out2) h = fmaf(w2, prev[j + 1], h);
                     }
                     cur[j] = h;
                     float yv = ldf(up + off) * h;
@@ -112,20 +115,44 @@ __global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
                 T* gwp = GW + out_w + item * 3 * HW;
                 float* enext = lds;         // e of scan step t+1
                 float* ecur = lds + Lmax;
+                // weights as logits: the normalised taps of the current line and of the next one (scan order)
+                float* wcur = lds + 2 * Lmax;
+                float* wnext = lds + 5 * Lmax;
+                const bool last_channel = ci == p.cpg - 1;
                 for (int t = q.S - 1; t >= 0; --t) {
                     const int base = (q.reversed ? q.S - 1 - t : t) * q.stride_s;
                     const int step = q.reversed ? -q.stride_s : q.stride_s;   // to the next line in scan order
                     const bool starts = starts_stretch(t, q.S, q.reversed, p.kchunk);
                     const bool next_starts = t + 1 < q.S && starts_stretch(t + 1, q.S, q.reversed, p.kchunk);
+                    if (p.logits) {
+                        // this line's taps, normalised (0 where nothing is read: the line has no predecessor)
+                        for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
+                            const int off = base + j * q.stride_j;
+                            const bool out0 = j == 0, out2 = j + 1 == q.L;
+                            float w0 = 0.f, w1 = 0.f, w2 = 0.f;
+                            if (!starts) {
+                                w0 = out0 ? 0.f : ldf(wp + off); w1 = ldf(wp + HW + off); w2 = out2 ? 0.f : ldf(wp + 2 * HW + off);
+                                softmax3(w0, w1, w2, out0, out2);
+                            }
+                            wcur[j] = w0; wcur[Lmax + j] = w1; wcur[2 * Lmax + j] = w2;
+                        }
+                        __syncthreads();
+                    }
                     for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
                         const int off = base + j * q.stride_j;
                         const float gyv = ldf(gyp + off);
                         float e = ldf(up + off) * gyv;
                         if (t + 1 < q.S && !next_starts) {   // transposed tridiagonal of the next line (of the same stretch)
                             const int offn = off + step;
-                            e = fmaf(ldf(wp + HW + offn), enext[j], e);
-                            if (j > 0) e = fmaf(ldf(wp + 2 * HW + offn - q.stride_j), enext[j - 1], e);
-                            if (j + 1 < q.L) e = fmaf(ldf(wp + offn + q.stride_j), enext[j + 1], e);
+                            if (p.logits) {
+                                e = fmaf(wnext[Lmax + j], enext[j], e);
+                                if (j > 0) e = fmaf(wnext[2 * Lmax + j - 1], enext[j - 1], e);
+                                if (j + 1 < q.L) e = fmaf(wnext[j + 1], enext[j + 1], e);
+                            } else {
+                                e = fmaf(ldf(wp + HW + offn), enext[j], e);
+                                if (j > 0) e = fmaf(ldf(wp + 2 * HW + offn - q.stride_j), enext[j - 1], e);
+                                if (j + 1 < q.L) e = fmaf(ldf(wp + offn + q.stride_j), enext[j + 1], e);
+                            }
                         }
                         ecur[j] = e;
                         stf(glp + off, ldf(xp + off) * e);
@@ -134,17 +161,22 @@ __global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
                         if (!first) gxv += ldf(gxp + off);
                         stf(gxp + off, gxv);
                         const int offp = off - step;   // same position on the previous line
+                        float v[3];
                         #pragma unroll
                         for (int k = 0; k < 3; ++k) {
                             const int jj = j + k - 1;
-                            float v = 0.f;
-                            if (!starts && jj >= 0 && jj < q.L) v = e * ldf(hp + offp + (k - 1) * q.stride_j);
-                            if (ci > 0) v += ldf(gwp + k * HW + off);
-                            stf(gwp + k * HW + off, v);
+                            v[k] = 0.f;
+                            if (!starts && jj >= 0 && jj < q.L) v[k] = e * ldf(hp + offp + (k - 1) * q.stride_j);
+                            if (ci > 0) v[k] += ldf(gwp + k * HW + off);
                         }
+                        // weights as logits: the sum over the group's channels goes through the softmax once, at the end
+                        if (p.logits && last_channel) softmax3_grad(v[0], v[1], v[2], wcur[j], wcur[Lmax + j], wcur[2 * Lmax + j]);
+                        #pragma unroll
+                        for (int k = 0; k < 3; ++k) stf(gwp + k * HW + off, v[k]);
                     }
                     __syncthreads();
                     float* tmp = enext; enext = ecur; ecur = tmp;
+                    tmp = wnext; wnext = wcur; wcur = tmp;
                 }
                 first = false;
             }
@@ -170,7 +202,8 @@ hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s) {
     const size_t items = (size_t)p.B * p.G;
     const unsigned grid = (unsigned)(items < 65536 ? items : 65536);
     const int block = pick_block(Lmax);
-    const size_t shmem = 2 * (size_t)Lmax * sizeof(float);
+    const size_t shmem = (p.logits ? 8 : 2) * (size_t)Lmax * sizeof(float);
+    if (shmem > 128 * 1024) return hipErrorInvalidValue;      // checked by the caller (GSPN_MAX_LINE_LOGITS)
     if (dtype == 0) hipLaunchKernelGGL(bwd_generic_kernel<float>, dim3(grid), dim3(block), shmem, s, p);
     else            hipLaunchKernelGGL(bwd_generic_kernel<bf16_t>, dim3(grid), dim3(block), shmem, s, p);
     return hipGetLastError();

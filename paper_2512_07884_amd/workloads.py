@@ -185,5 +185,14 @@ def make_inputs(cfg: ScanConfig, with_gy: bool = True) -> dict:
     return out
 
 
+def make_logits(cfg: ScanConfig) -> np.ndarray:
+    """Raw weight logits [4, B, G, 3, H, W] ~ N(0, 1) * logit_scale in the storage dtype, for the calls that
+    normalise inside (seeded by the config; nothing is masked: the taps that point outside a line are
+    never read)."""
+    rng = np.random.default_rng([cfg.seed, 977])
+    z = rng.standard_normal((4, cfg.B, cfg.G, 3, cfg.H, cfg.W)) * cfg.logit_scale
+    return to_storage(z, cfg.dtype)
+
+
 def inputs_as_f64(inp: dict, dtype: str) -> dict:
     return {k: storage_to_f64(v, dtype) for k, v in inp.items()}

@@ -1,0 +1,89 @@
+"""GPU parity of the calls that take the weights as raw logits (normalisation of Sec. 3.2 inside the call)
+against the fp64 oracle, through the C ABI, forward and backward."""
+import numpy as np
+import pytest
+
+from gpu_util import TOL, rel_inf_err, to_device, to_host_f64, empty_like_dev
+from oracle import gspn_oracle as O
+from paper_2512_07884_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+
+def check_logits(shape, kchunk=None, mask=15, seed=101, scale=1.5, poison=False, fwd_plan=None, bwd_plan=None):
+    import torch
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    cfg = WL.ScanConfig("logits", B, C, H, W, Gr, dtype, mask, scale, seed)
+    inp = WL.make_inputs(cfg, with_gy=True)
+    inp["w"] = WL.make_logits(cfg)
+    f = WL.inputs_as_f64(inp, dtype)
+    y_ref, h_ref = O.scan_fwd_logits(f["x"], f["w"], f["lam"], f["u"], mask, kchunk)
+    if poison:
+        # logits that are never read: taps that point outside the line, first line of each scan
+        nan = np.nan if dtype == "f32" else np.uint16(0x7FC0)
+        z = inp["w"]
+        z[0, :, :, 0, :, 0] = nan; z[1, :, :, 2, :, -1] = nan; z[2, :, :, 0, 0, :] = nan; z[3, :, :, 2, -1, :] = nan
+        z[0, :, :, :, 0, :] = nan; z[1, :, :, :, -1, :] = nan; z[2, :, :, :, :, 0] = nan; z[3, :, :, :, :, -1] = nan
+    k = kchunk if kchunk else 1 << 14
+    dt = int(dtype == "bf16")
+    if fwd_plan:
+        assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, k, mask, dt, 0, True) == fwd_plan
+    if bwd_plan:
+        assert G.gspn_bwd_logits_plan(B, C, H, W, Gr, k, mask, dt, 0) == bwd_plan
+    dev = {n: to_device(v, dtype) for n, v in inp.items()}
+    nanf = float("nan")
+    y = empty_like_dev((B, C, H, W), dtype, nanf)
+    y2 = empty_like_dev((B, C, H, W), dtype, nanf)
+    hs = empty_like_dev((4, B, C, H, W), dtype, nanf)
+    gx = empty_like_dev((B, C, H, W), dtype, nanf)
+    gz = empty_like_dev((4, B, Gr, 3, H, W), dtype, nanf)
+    glam = empty_like_dev((4, B, C, H, W), dtype, nanf)
+    gu = empty_like_dev((4, B, C, H, W), dtype, nanf)
+    G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, kchunk=k, G=Gr, dir_mask=mask)
+    G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y2, None, kchunk=k, G=Gr, dir_mask=mask)
+    G.gspn_scan_bwd_logits(dev["gy"], dev["x"], dev["w"], dev["lam"], dev["u"], hs, gx, gz, glam, gu, kchunk=k, G=Gr,
+                           dir_mask=mask)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_inf_err(to_host_f64(y), y_ref) <= tol, ("y", rel_inf_err(to_host_f64(y), y_ref))
+    assert rel_inf_err(to_host_f64(y2), y_ref) <= tol
+    h_used = WL.storage_to_f64(WL.to_storage(h_ref, dtype), dtype)
+    gx_r, gz_r, glam_r, gu_r = O.scan_bwd_logits(f["gy"], f["x"], f["w"], f["lam"], f["u"], h_used, mask, kchunk)
+    assert rel_inf_err(to_host_f64(gx), gx_r) <= tol, ("gx", rel_inf_err(to_host_f64(gx), gx_r))
+    got = {"gz": to_host_f64(gz), "glam": to_host_f64(glam), "gu": to_host_f64(gu), "h": to_host_f64(hs)}
+    ref = {"gz": gz_r, "glam": glam_r, "gu": gu_r, "h": h_ref}
+    for d in range(4):
+        for n in got:
+            if (mask >> d) & 1:
+                e = rel_inf_err(got[n][d], ref[n][d])
+                assert e <= tol, (n, d, e)
+            else:
+                assert np.all(np.isnan(got[n][d])), (n, d)
+    # exact zeros of gz: taps that point outside the line, first line of each scan
+    g = got["gz"]
+    for d in range(4):
+        if not (mask >> d) & 1:
+            continue
+        if d < 2:
+            assert not g[d][:, :, 0, :, 0].any() and not g[d][:, :, 2, :, -1].any()
+        else:
+            assert not g[d][:, :, 0, 0, :].any() and not g[d][:, :, 2, -1, :].any()
+        if kchunk is None:
+            first = {0: g[d][:, :, :, 0, :], 1: g[d][:, :, :, -1, :], 2: g[d][:, :, :, :, 0], 3: g[d][:, :, :, :, -1]}[d]
+            assert not first.any()
+
+
+GENERIC_SHAPES = [(2, 6, 9, 13, 3, "f32"), (1, 4, 33, 70, 2, "f32"), (1, 2, 1, 37, 1, "f32"), (1, 2, 37, 1, 2, "f32"),
+                  (1, 4, 40, 72, 2, "bf16"), (1, 2, 128, 128, 2, "bf16"), (1, 1, 1, 1, 1, "f32")]
+
+
+@pytest.mark.parametrize("shape", GENERIC_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_logits_on_the_generic_kernels(shape):
+    check_logits(shape, fwd_plan="generic", bwd_plan="generic")
+
+
+@pytest.mark.parametrize("shape,kchunk", [((2, 6, 9, 13, 3, "f32"), 4), ((1, 4, 40, 72, 2, "bf16"), 16)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_logits_with_local_stretches_on_the_generic_kernels(shape, kchunk):
+    check_logits(shape, kchunk=kchunk, fwd_plan="generic", bwd_plan="generic")

@@ -41,6 +41,7 @@ __device__ __forceinline__ void plds_st(uint32_t a, float v) { *(plds_f32*)(uint
 typedef float pf32x4a __attribute__((ext_vector_type(4), may_alias));
 typedef __attribute__((address_space(3))) pf32x4a plds_f32x4;
 __device__ __forceinline__ pf32x4a plds_ld4(uint32_t a) { return *(const plds_f32x4*)(uintptr_t)a; }
+__device__ __forceinline__ void plds_st4(uint32_t a, pf32x4a v) { *(plds_f32x4*)(uintptr_t)a = v; }
 
 // element e of a 16 B chunk of storage, widened to fp32
 template <typename T> __device__ __forceinline__ float chunk_elem(const u32x4& c, int e) {
@@ -210,6 +211,8 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         // The prefetching variant has no registers to spare for the test where the weights are written: it clears
         // those lines in a pass of its own afterwards.
         constexpr bool LOCAL_PASS = LOCAL && WPRE;
+        // weights given as logits: a tap that takes no part is stored as -inf and the three are normalised in LDS
+        const float masked = p.logits ? -__builtin_huge_valf() : 0.f;
         const uint64_t starts = LOCAL ? a.seg[d] : 0ull;
         auto no_pred = [&](int row, int col) { return LOCAL && !LOCAL_PASS && ((starts >> (vert ? row : col)) & 1ull) != 0; };
 
@@ -244,7 +247,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                         const int pos = vert ? col : row;
                         const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1) || no_pred(row, col);
                         plds_st(wreg + 4u * (uint32_t)(chn * 4 * HP + 4 * (row * W + col) + tap),
-                                outside ? 0.f : chunk_elem<T>(v, e));
+                                outside ? masked : chunk_elem<T>(v, e));
                         if (++col == W) { col = 0; if (++row == H) { row = 0; if (++tap == 3) { tap = 0; ++chn; } } }
                     }
                 }
@@ -261,7 +264,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                             const int pos = vert ? wcol[j] + e : wrow[j];
                             const bool outside = (wtap[j] == 0 && pos == 0) || (wtap[j] == 2 && pos == L - 1) ||
                                                  no_pred(wrow[j], wcol[j] + e);
-                            plds_st(wreg + 4u * (uint32_t)(wl[j] + 4 * e), outside ? 0.f : chunk_elem<T>(wsh[j], e));
+                            plds_st(wreg + 4u * (uint32_t)(wl[j] + 4 * e), outside ? masked : chunk_elem<T>(wsh[j], e));
                         }
                     }
                 }
@@ -277,7 +280,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                     for (int e = 0; e < E; ++e) {
                         const int pos = vert ? col + e : row;
                         const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1) || no_pred(row, col + e);
-                        plds_st(wreg + 4u * (uint32_t)(4 * (row * P + col + e) + tap), outside ? 0.f : chunk_elem<T>(v, e));
+                        plds_st(wreg + 4u * (uint32_t)(4 * (row * P + col + e) + tap), outside ? masked : chunk_elem<T>(v, e));
                     }
                 }
             }
@@ -301,7 +304,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                         for (int e = 0; e < E; ++e) {
                             const int pos = vert ? col0[k] + e : row0[k];
                             const bool outside = (t == 0 && pos == 0) || (t == 2 && pos == L - 1) || no_pred(row0[k], col0[k] + e);
-                            plds_st(o + 16u * e, outside ? 0.f : chunk_elem<T>(wt[k], e));
+                            plds_st(o + 16u * e, outside ? masked : chunk_elem<T>(wt[k], e));
                         }
                     }
                 }
@@ -325,7 +328,26 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         if constexpr (SHARED) lds_barrier();               // weights of this direction are in place (LDS only: the
                                                            // requests above stay in flight across the barrier)
 
-        if constexpr (LOCAL_PASS) {
+        if (p.logits) {
+            // Sec. 3.2 normalisation: softmax over the taps of a position that take part (the others hold -inf);
+            // a line without predecessor (GSPN-local: first line of a stretch) gets three zeros
+            const int nreg = SHARED ? 1 : cpw;             // weight regions: the group's, or the wave's own
+            const int t0 = SHARED ? (int)threadIdx.x : lane, tn = SHARED ? nthreads : 64;
+            for (int idx = t0; idx < nreg * HP; idx += tn) {
+                const int chn = idx / HP, pos = idx - chn * HP;
+                const int row = pos / P, col = pos - row * P;
+                if (row >= H || col >= W) continue;        // padding
+                const uint32_t o = wreg + 16u * (uint32_t)idx;
+                pf32x4a z = plds_ld4(o);
+                const float m = fmaxf(z.y, fmaxf(z.x, z.z));
+                const bool none = m == -__builtin_huge_valf() || (LOCAL && ((starts >> (vert ? row : col)) & 1ull) != 0);
+                const float e0 = expf(z.x - m), e1 = expf(z.y - m), e2 = expf(z.z - m);
+                const float r = 1.0f / (e0 + e1 + e2);
+                z.x = none ? 0.f : e0 * r; z.y = none ? 0.f : e1 * r; z.z = none ? 0.f : e2 * r; z.w = 0.f;
+                plds_st4(o, z);
+            }
+            if constexpr (SHARED) lds_barrier();
+        } else if constexpr (LOCAL_PASS) {
             for (int r = 0; r < S; ++r) {
                 if (!((starts >> r) & 1ull)) continue;
                 for (int j = (int)threadIdx.x; j < L; j += nthreads) {
@@ -426,7 +448,6 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
     FwdPlanePlan t = {};
     const int es = dtype == 0 ? 4 : 2, E = 16 / es;
     if (p.H < 2 || p.W < 2 || p.H > 64 || p.W > 64) return t;
-    if (p.logits) return t;
     const int HW = p.H * p.W;
     const int m = p.H > p.W ? p.H : p.W;
     if (p.W % E == 0) {

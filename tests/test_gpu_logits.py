@@ -87,3 +87,34 @@ def test_logits_on_the_generic_kernels(shape):
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_logits_with_local_stretches_on_the_generic_kernels(shape, kchunk):
     check_logits(shape, kchunk=kchunk, fwd_plan="generic", bwd_plan="generic")
+
+
+# shapes of the plane kernels: padded and unpadded LDS planes, shared and per-channel weights, 1 to 8 channels
+# per wave, small groups (weights not prefetched), bf16 and fp32
+PLANE_SHAPES = [(2, 16, 28, 28, 2, "f32"), (2, 8, 28, 28, 8, "f32"), (2, 24, 56, 56, 2, "bf16"), (2, 16, 28, 28, 2, "bf16"),
+                (2, 16, 14, 14, 2, "bf16"), (2, 16, 7, 7, 2, "f32"), (1, 8, 14, 14, 8, "f32"), (1, 12, 16, 32, 3, "f32"),
+                (2, 8, 28, 28, 2, "f32"), (1, 4, 12, 10, 2, "f32"), (1, 8, 64, 64, 8, "bf16"), (300, 16, 4, 4, 2, "bf16")]
+
+
+@pytest.mark.parametrize("shape", PLANE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_logits_on_the_plane_kernels(shape):
+    check_logits(shape, fwd_plan="plane")
+
+
+@pytest.mark.parametrize("shape,kchunk", [((2, 16, 28, 28, 2, "f32"), 7), ((2, 8, 28, 28, 8, "f32"), 5),
+                                          ((2, 24, 56, 56, 2, "bf16"), 14), ((2, 16, 7, 7, 2, "f32"), 3),
+                                          ((2, 8, 28, 28, 2, "f32"), 6)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_logits_with_local_stretches_on_the_plane_kernels(shape, kchunk):
+    check_logits(shape, kchunk=kchunk, fwd_plan="plane")
+
+
+@pytest.mark.parametrize("shape", [(1, 8, 28, 28, 2, "f32"), (1, 4, 12, 10, 4, "f32"), (1, 4, 40, 70, 2, "f32"),
+                                   (1, 8, 14, 14, 2, "bf16")], ids=lambda s: "x".join(map(str, s)))
+def test_logits_that_are_never_read_may_hold_anything(shape):
+    check_logits(shape, poison=True)
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9])
+def test_logits_direction_masks(mask):
+    check_logits((2, 8, 28, 28, 2, "f32"), mask=mask)

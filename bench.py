@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused 4-direction GSPN scan on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kchunk K] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kchunk K] [--logits] [--all]
 
 A step is one pass of the whole hot path over one batch of synthetic input:
 one ``gspn_scan_fwd`` call covering all four directions (inference workloads),
@@ -10,7 +10,8 @@ Inputs are resident in HBM before the timed region; buffer sets are rotated so
 that consecutive steps do not find their inputs in the 256 MB last-level cache.
 Prints ONE JSON line (see the keys below); ``--all`` additionally writes a table
 for every workload to <out>/bench_all.json (see --out).  ``--kchunk K`` times the
-GSPN-local calls (propagation confined to stretches of K lines) on the same workload.
+GSPN-local calls (propagation confined to stretches of K lines) on the same workload; ``--logits``
+the calls that take the weights as raw logits and normalise them inside.
 """
 from __future__ import annotations
 
@@ -29,7 +30,7 @@ DEFAULT_WORKLOAD = "diff128"   # 128x128 diffusion-latent shape: first of the tw
 TRAINING = ("train28_gc", "train28_g4")
 
 
-def device_inputs(cfg, seed: int):
+def device_inputs(cfg, seed: int, logits: bool = False):
     """Synthetic inputs with the distributions of workloads.make_slice, drawn on the device."""
     import torch
     td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -46,7 +47,7 @@ def device_inputs(cfg, seed: int):
             z[:, :, 0, :, 0] = float("-inf"); z[:, :, 2, :, -1] = float("-inf")
         else:
             z[:, :, 0, 0, :] = float("-inf"); z[:, :, 2, -1, :] = float("-inf")
-        w[d] = torch.softmax(z.double(), dim=2).to(td)
+        w[d] = z.nan_to_num(neginf=0.0).to(td) if logits else torch.softmax(z.double(), dim=2).to(td)
         lam[d] = torch.rand((B, C, H, W), generator=g, device="cuda").to(td)
         u[d] = torch.rand((B, C, H, W), generator=g, device="cuda").to(td)
         del z
@@ -54,13 +55,13 @@ def device_inputs(cfg, seed: int):
     return {"x": x, "w": w, "lam": lam, "u": u, "gy": gy}
 
 
-def make_sets(cfg, training: bool, min_total_bytes: float = 1.0e9, max_sets: int = 4):
+def make_sets(cfg, training: bool, min_total_bytes: float = 1.0e9, max_sets: int = 4, logits: bool = False):
     import torch
     foot = cfg.fwd_algorithmic_bytes(save_h=training) + (cfg.bwd_algorithmic_bytes() if training else 0)
     nsets = int(min(max_sets, max(1, math.ceil(min_total_bytes / foot))))
     sets = []
     for i in range(nsets):
-        s = device_inputs(cfg, 1000 + i)
+        s = device_inputs(cfg, 1000 + i, logits)
         s["y"] = torch.empty_like(s["x"])
         if training:
             s["hs"] = torch.empty_like(s["lam"])
@@ -72,23 +73,30 @@ def make_sets(cfg, training: bool, min_total_bytes: float = 1.0e9, max_sets: int
     return sets
 
 
-def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0):
+def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0, logits: bool = False):
     """Times `steps` steps; returns dict with wall ms/step and per-kernel event times."""
     import torch
     import paper_2512_07884_amd as G
     training = cfg.name in TRAINING
-    sets = make_sets(cfg, training)
+    sets = make_sets(cfg, training, logits=logits)
     stream = torch.cuda.current_stream()
+    big = 1 << 14
 
     def fwd(s):
-        if kchunk:
+        if logits:
+            G.gspn_scan_fwd_logits(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), kchunk=kchunk or big, G=cfg.G,
+                                   dir_mask=cfg.dir_mask)
+        elif kchunk:
             G.gspn_scan_fwd_local(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), kchunk=kchunk, G=cfg.G,
                                   dir_mask=cfg.dir_mask)
         else:
             G.gspn_scan_fwd(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), G=cfg.G, dir_mask=cfg.dir_mask)
 
     def bwd(s):
-        if kchunk:
+        if logits:
+            G.gspn_scan_bwd_logits(s["gy"], s["x"], s["w"], s["lam"], s["u"], s["hs"], s["gx"], s["gw"], s["glam"],
+                                   s["gu"], kchunk=kchunk or big, G=cfg.G, dir_mask=cfg.dir_mask)
+        elif kchunk:
             G.gspn_scan_bwd_local(s["gy"], s["x"], s["w"], s["lam"], s["u"], s["hs"], s["gx"], s["gw"], s["glam"],
                                   s["gu"], kchunk=kchunk, G=cfg.G, dir_mask=cfg.dir_mask)
         else:
@@ -128,7 +136,7 @@ def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0):
     fwd_ms = sorted(e[0].elapsed_time(e[1]) for e in ev)
     out = {"ms_per_step": (t1 - t0) * 1e3 / steps,
            "fwd_ms_avg": sum(fwd_ms) / steps, "fwd_ms_med": fwd_ms[steps // 2], "fwd_ms_min": fwd_ms[0],
-           "n_sets": len(sets), "training": training, "warm_ms_per_step": warm_ms, "kchunk": kchunk}
+           "n_sets": len(sets), "training": training, "warm_ms_per_step": warm_ms, "kchunk": kchunk, "logits": logits}
     if training:
         bwd_ms = sorted(e[1].elapsed_time(e[2]) for e in ev)
         out.update({"bwd_ms_avg": sum(bwd_ms) / steps, "bwd_ms_med": bwd_ms[steps // 2], "bwd_ms_min": bwd_ms[0]})
@@ -143,13 +151,15 @@ def summarise(cfg, r):
     training = r["training"]
     kchunk = r.get("kchunk", 0)
     big = 1 << 14                      # a stretch longer than any line: the global scan
+    fplan, bplan = (G.gspn_fwd_logits_plan, G.gspn_bwd_logits_plan) if r.get("logits") else \
+                   (G.gspn_fwd_local_plan, G.gspn_bwd_local_plan)
     fwd_bytes = cfg.fwd_algorithmic_bytes(save_h=training)
     d = {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "G": cfg.G,
          "storage": cfg.dtype, "directions": cfg.n_dirs,
          "step": "fwd+bwd" if training else "fwd",
          "ms_per_step": r["ms_per_step"], "warm_single_set_ms_per_step": r["warm_ms_per_step"],
          "gpixel_ch_per_s": cfg.pixel_channels / (r["ms_per_step"] * 1e-3) / 1e9,
-         "fwd_kernel": G.gspn_fwd_local_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0, training),
+         "fwd_kernel": fplan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0, training),
          "fwd_ms_avg": r["fwd_ms_avg"], "fwd_ms_min": r["fwd_ms_min"],
          "fwd_algorithmic_bytes": fwd_bytes,
          "fwd_algorithmic_GBs": fwd_bytes / (r["fwd_ms_avg"] * 1e-3) / 1e9,
@@ -157,9 +167,11 @@ def summarise(cfg, r):
          "buffer_sets_rotated": r["n_sets"]}
     if kchunk:
         d["kchunk"] = kchunk
+    if r.get("logits"):
+        d["weights"] = "logits"
     if training:
         bb = cfg.bwd_algorithmic_bytes()
-        d.update({"bwd_kernel": G.gspn_bwd_local_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0),
+        d.update({"bwd_kernel": bplan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0),
                   "bwd_ms_avg": r["bwd_ms_avg"], "bwd_ms_min": r["bwd_ms_min"],
                   "bwd_algorithmic_bytes": bb,
                   "bwd_algorithmic_GBs": bb / (r["bwd_ms_avg"] * 1e-3) / 1e9,
@@ -169,7 +181,7 @@ def summarise(cfg, r):
 
 # ---------------------------------------------------------------- CPU baseline (the oracle, as it stands)
 def _oracle_slice(args):
-    name, b, g, training, kchunk = args
+    name, b, g, training, kchunk, logits = args
     import numpy as np
     from oracle import gspn_oracle as O
     from paper_2512_07884_amd import workloads as WL
@@ -177,7 +189,11 @@ def _oracle_slice(args):
     s = WL.inputs_as_f64(WL.make_slice(cfg, b, g), cfg.dtype)
     t0 = time.perf_counter()
     a = (s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None])
-    if kchunk:
+    if logits:      # the generated weights serve as logit values: same shapes, same cost
+        y, h = O.scan_fwd_logits(*a, cfg.dir_mask, kchunk or None)
+        if training:
+            O.scan_bwd_logits(s["gy"][None], *a, h, cfg.dir_mask, kchunk or None)
+    elif kchunk:
         y, h = O.scan_fwd_local(*a, kchunk, cfg.dir_mask)
         if training:
             O.scan_bwd_local(s["gy"][None], *a, h, kchunk, cfg.dir_mask)
@@ -188,19 +204,19 @@ def _oracle_slice(args):
     return time.perf_counter() - t0, float(np.abs(y).sum())
 
 
-def cpu_baseline(cfg, training: bool, budget_s: float = 12.0, kchunk: int = 0):
+def cpu_baseline(cfg, training: bool, budget_s: float = 12.0, kchunk: int = 0, logits: bool = False):
     """The fp64 NumPy oracle on (batch, group) slices of the same workload, one
     slice per worker process, timed wall-clock over the pool (input generation
     excluded from the single-slice probe, included in the pool's wall time is
     avoided by timing only the oracle calls and dividing by the worker count)."""
     import multiprocessing as mp
     cores = max(1, min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)))
-    t_probe, _ = _oracle_slice((cfg.name, 0, 0, training, kchunk))
+    t_probe, _ = _oracle_slice((cfg.name, 0, 0, training, kchunk, logits))
     slice_pc = cfg.cpg * cfg.H * cfg.W
     total_slices = cfg.B * cfg.G
     n = int(max(cores, min(total_slices, (budget_s * cores) // max(t_probe, 1e-4))))
     n = min(n, total_slices)
-    jobs = [(cfg.name, (i // cfg.G) % cfg.B, i % cfg.G, training, kchunk) for i in range(n)]
+    jobs = [(cfg.name, (i // cfg.G) % cfg.B, i % cfg.G, training, kchunk, logits) for i in range(n)]
     ctx = mp.get_context("fork")
     t0 = time.perf_counter()
     with ctx.Pool(min(cores, n)) as pool:
@@ -247,6 +263,8 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--kchunk", type=int, default=0,
                     help="GSPN-local: confine propagation to stretches of this many lines (0: the global scan)")
+    ap.add_argument("--logits", action="store_true",
+                    help="weights given as raw logits, normalised inside the call (gspn_scan_*_logits)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
     ap.add_argument("--out", default="gpurun_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -267,13 +285,13 @@ def main():
     if a.kchunk < 0:
         print("bench.py: --kchunk must be >= 0", file=sys.stderr)
         sys.exit(2)
-    cpu = None if a.no_cpu else cpu_baseline(cfg, cfg.name in TRAINING, kchunk=a.kchunk)
+    cpu = None if a.no_cpu else cpu_baseline(cfg, cfg.name in TRAINING, kchunk=a.kchunk, logits=a.logits)
     import torch
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    r = run_workload(cfg, a.steps, a.warmup, a.kchunk)
+    r = run_workload(cfg, a.steps, a.warmup, a.kchunk, a.logits)
     s = summarise(cfg, r)
     training = r["training"]
     dom = "bwd" if training else "fwd"          # dominant kernel of the step
@@ -288,11 +306,12 @@ def main():
         "dtype": "f32", "storage_dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} H={cfg.H} W={cfg.W} G={cfg.G} "
                                f"{cfg.dtype} storage, {cfg.n_dirs} directions, {s['step']}"
-                               + (f", GSPN-local kchunk={a.kchunk}" if a.kchunk else ""),
+                               + (f", GSPN-local kchunk={a.kchunk}" if a.kchunk else "")
+                               + (", weights as logits" if a.logits else ""),
                    "kernel": s[f"{dom}_kernel"], "buffer_sets_rotated": s["buffer_sets_rotated"]},
         "roofline": {"bound": "hbm", "kernel": f"gspn_scan_{dom}", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if a.kchunk else load_traffic(cfg.name, dom),
+                     "traffic": None if (a.kchunk or a.logits) else load_traffic(cfg.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "detail": s,
     }
@@ -304,7 +323,7 @@ def main():
             if name == cfg.name:
                 continue
             k = max(20, a.steps // (8 if c.pixel_channels > 1e8 else 1))
-            table.append(summarise(c, run_workload(c, k, a.warmup, a.kchunk)))
+            table.append(summarise(c, run_workload(c, k, a.warmup, a.kchunk, a.logits)))
             print(f"[bench] {name} done", file=sys.stderr, flush=True)
         os.makedirs(os.path.join(ROOT, a.out), exist_ok=True)
         with open(os.path.join(ROOT, a.out, "bench_all.json"), "w") as f:

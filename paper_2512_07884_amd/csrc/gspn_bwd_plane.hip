@@ -84,8 +84,9 @@ template <typename T, int E> __device__ __forceinline__ u32x4 chunk_pack(const f
     return c;
 }
 
-// SMAX: scan steps held in registers; CPW: channels per wave, on 64 / CPW lanes each; LOCAL: GSPN-local
-template <typename T, int SMAX, int CPW, bool SHARED, bool LOCAL>
+// SMAX: scan steps held in registers; CPW: channels per wave, on 64 / CPW lanes each; LOCAL: GSPN-local;
+// LOGITS: w holds raw logits (normalised here, Sec. 3.2) and gw receives the gradient w.r.t. them
+template <typename T, int SMAX, int CPW, bool SHARED, bool LOCAL, bool LOGITS>
 __global__ void __launch_bounds__((SHARED && SMAX < 32) ? 384 : 256, (SHARED && SMAX == 32) ? 1 : 2)
 bwd_plane_kernel(BwdPlaneArgs a) {
     static_assert(CPW == 2 || SHARED, "more than two channels per wave: shared weights only");
@@ -213,6 +214,12 @@ bwd_plane_kernel(BwdPlaneArgs a) {
 #pragma unroll
         for (int s = 0; s < SMAX; ++s) { gw0[s] = 0.f; gw1[s] = 0.f; gw2[s] = 0.f; }
 
+        // LOGITS: softmax over the taps whose neighbour exists, per scan step; step 0 has no predecessor: no weight
+        auto normalise = [&](float (&w0r)[SMAX], float (&w1r)[SMAX], float (&w2r)[SMAX]) {
+#pragma unroll
+            for (int s = 1; s < SMAX; ++s) softmax3(w0r[s], w1r[s], w2r[s], first, last);
+            w0r[0] = 0.f; w1r[0] = 0.f; w2r[0] = 0.f;
+        };
         for (int pair = wave; pair < pairs; pair += a.nwaves) {
             const int c0 = c_first + CPW * pair;
             const size_t pc = ((size_t)b * p.C + c0) * HW;
@@ -295,6 +302,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
                 }
             }
 
+            if constexpr (LOGITS) normalise(w0r, w1r, w2r);     // what was loaded are logits
             if constexpr (LOCAL) {
                 // GSPN-local: nothing flows into the first line of a stretch -- its weights count as 0, and so
                 // does the line before it where the weight gradients read it (h in LDS serves nothing else)
@@ -361,6 +369,19 @@ bwd_plane_kernel(BwdPlaneArgs a) {
             }
             if constexpr (!SHARED) {
                 // one group per channel: this sweep's gw is complete; one tap at a time through the LDS buffer
+                float dot[LOGITS ? SMAX : 1];                   // LOGITS: sum over the taps of w * gw, per scan step
+                if constexpr (LOGITS) {
+                    dot[0] = 0.f;
+#pragma unroll
+                    for (int s = 1, idh = tb; s < SMAX; ++s) {
+                        const float hm = bufH[idh];             // h of scan step s-1
+                        next(idh, s);
+                        float hl = from_lane_below(hm), hr = from_lane_above(hm);
+                        hl = first ? 0.f : hl;
+                        hr = last ? 0.f : hr;
+                        dot[s] = e[s] * fmaf(w0r[s], hl, fmaf(w1r[s], hm, w2r[s] * hr));
+                    }
+                }
 #pragma unroll
                 for (int t = 0; t < 3; ++t) {
 #pragma unroll
@@ -374,6 +395,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
                                 if (t == 0) hn = first ? 0.f : hn;
                                 if (t == 2) hn = last ? 0.f : hn;
                                 v = e[s] * hn;
+                                if constexpr (LOGITS) v = (t == 0 ? w0r[s] : (t == 1 ? w1r[s] : w2r[s])) * (v - dot[s]);
                             }
                             if (active) bufX[idx] = v;
                         }
@@ -392,6 +414,56 @@ bwd_plane_kernel(BwdPlaneArgs a) {
             }
         }
 
+        if constexpr (SHARED && LOGITS) {
+            // The softmax gradient is linear in gw: it is applied to this lane's partial sums before they are
+            // added up.  The group's weights are fetched once more for it (keeping them in registers across
+            // the loop above would cost more than this one fetch per direction).
+            const int g = c_first / p.cpg;
+            const T* wp = (const T*)p.w + slot_w + ((size_t)b * p.G + g) * 3 * HW;
+            float w0r[SMAX], w1r[SMAX], w2r[SMAX];
+            if constexpr (CPW == 2) {
+                float st[NCH][E];
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    load_w(wp + t * HW, st);
+                    to_lds(bufX, st, true);
+#pragma unroll
+                    for (int s = 0, idx = ic * ps + s0; s < SMAX; ++s) {
+                        const float v = bufX[idx];
+                        if (t == 0) w0r[s] = v; else if (t == 1) w1r[s] = v; else w2r[s] = v;
+                        next(idx, s);
+                    }
+                }
+            } else {
+                const int ew = a.wlw / (int)sizeof(T);
+                const rsrc_t rs = make_rsrc(wp);
+                for (int c = lane; c * ew < 3 * HW; c += 64) {
+                    const uint32_t bo = (uint32_t)(c * ew * (int)sizeof(T));
+                    u32x4 v = {0, 0, 0, 0};
+                    if (a.wlw == 16) v = __builtin_amdgcn_raw_buffer_load_b128(rs, bo, 0, 0);
+                    else if (a.wlw == 8) { const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, bo, 0, 0); v[0] = t.x; v[1] = t.y; }
+                    else if (a.wlw == 4) v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, bo, 0, 0);
+                    else v[0] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, bo, 0, 0);
+                    float f[E];
+                    chunk_unpack<T, E>(v, f);
+#pragma unroll
+                    for (int j = 0; j < E; ++j)
+                        if (j < ew) bufX[c * ew + j] = f[j];
+                }
+#pragma unroll
+                for (int s = 0, idx = ic * ps + s0; s < SMAX; ++s) {
+                    w0r[s] = bufX[idx]; w1r[s] = bufX[idx + HW]; w2r[s] = bufX[idx + 2 * HW];
+                    next(idx, s);
+                }
+            }
+            normalise(w0r, w1r, w2r);
+#pragma unroll
+            for (int s = 0; s < SMAX; ++s) {
+                // a step that starts a stretch has gw = 0 already; its weights count as 0 as well
+                const bool z = LOCAL && ((starts >> s) & 1u);
+                softmax3_grad(gw0[s], gw1[s], gw2[s], z ? 0.f : w0r[s], z ? 0.f : w1r[s], z ? 0.f : w2r[s]);
+            }
+        }
         if constexpr (SHARED && CPW > 2) {
             // sum over the channels of each wave, then over the waves (fixed order); the three taps are one block
             const int g = c_first / p.cpg;
@@ -512,7 +584,6 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
     PlanePlan t = {};
     const int es = dtype == 0 ? 4 : 2, E = 16 / es;             // elements per 16 B of storage
     if (p.H < 2 || p.W < 2 || p.H > 32 || p.W > 32) return t;
-    if (p.logits) return t;
     const int HW = p.H * p.W;
     const int m = p.H > p.W ? p.H : p.W;
     // channels per wave: eight / four when the lines are short enough, the group divides evenly and the
@@ -551,9 +622,9 @@ static PlanePlan plan_plane(const BwdParams& p, int dtype) {
 
 bool bwd_plane_applicable(const BwdParams& p, int dtype) { return plan_plane(p, dtype).ok; }
 
-template <typename T, int SMAX, int CPW, bool SHARED, bool LOCAL>
+template <typename T, int SMAX, int CPW, bool SHARED, bool LOCAL, bool LOGITS>
 static hipError_t launch_plane_k(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
-    auto k = bwd_plane_kernel<T, SMAX, CPW, SHARED, LOCAL>;
+    auto k = bwd_plane_kernel<T, SMAX, CPW, SHARED, LOCAL, LOGITS>;
     hipError_t e = allow_dynamic_lds((const void*)k, PLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
@@ -564,8 +635,10 @@ static hipError_t launch_plane_k(const BwdPlaneArgs& a, const PlanePlan& t, hipS
 // GSPN-local (Sec. 3.2) runs on instantiations of its own, so that the global scan carries none of it
 template <typename T, int SMAX, int CPW, bool SHARED>
 static hipError_t launch_plane(const BwdPlaneArgs& a, const PlanePlan& t, hipStream_t s) {
-    return a.p.kchunk > 0 ? launch_plane_k<T, SMAX, CPW, SHARED, true>(a, t, s)
-                          : launch_plane_k<T, SMAX, CPW, SHARED, false>(a, t, s);
+    // weights as logits always run the local instantiation (a global scan is one stretch: only step 0 starts one)
+    if (a.p.logits) return launch_plane_k<T, SMAX, CPW, SHARED, true, true>(a, t, s);
+    return a.p.kchunk > 0 ? launch_plane_k<T, SMAX, CPW, SHARED, true, false>(a, t, s)
+                          : launch_plane_k<T, SMAX, CPW, SHARED, false, false>(a, t, s);
 }
 
 template <typename T>

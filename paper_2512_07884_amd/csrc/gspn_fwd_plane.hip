@@ -333,15 +333,20 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
             // a line without predecessor (GSPN-local: first line of a stretch) gets three zeros
             const int nreg = SHARED ? 1 : cpw;             // weight regions: the group's, or the wave's own
             const int t0 = SHARED ? (int)threadIdx.x : lane, tn = SHARED ? nthreads : 64;
+            // (padding positions are normalised like the rest: what they hold is never read)
+            const float inv_hp = 1.0f / (float)HP, inv_p = 1.0f / (float)P;
             for (int idx = t0; idx < nreg * HP; idx += tn) {
-                const int chn = idx / HP, pos = idx - chn * HP;
-                const int row = pos / P, col = pos - row * P;
-                if (row >= H || col >= W) continue;        // padding
                 const uint32_t o = wreg + 16u * (uint32_t)idx;
                 pf32x4a z = plds_ld4(o);
                 const float m = fmaxf(z.y, fmaxf(z.x, z.z));
-                const bool none = m == -__builtin_huge_valf() || (LOCAL && ((starts >> (vert ? row : col)) & 1ull) != 0);
-                const float e0 = expf(z.x - m), e1 = expf(z.y - m), e2 = expf(z.z - m);
+                bool none = m == -__builtin_huge_valf();
+                if constexpr (LOCAL) {
+                    // (row, column) of the position; the float quotients are exact at these sizes (idx < 2^16, P <= 65)
+                    const int chn = (int)(((float)idx + 0.5f) * inv_hp), pos = idx - chn * HP;
+                    const int row = (int)(((float)pos + 0.5f) * inv_p), col = pos - row * P;
+                    none = none || ((starts >> ((vert ? row : col) & 63)) & 1ull) != 0;
+                }
+                const float e0 = __expf(z.x - m), e1 = __expf(z.y - m), e2 = __expf(z.z - m);
                 const float r = 1.0f / (e0 + e1 + e2);
                 z.x = none ? 0.f : e0 * r; z.y = none ? 0.f : e1 * r; z.z = none ? 0.f : e2 * r; z.w = 0.f;
                 plds_st4(o, z);

@@ -98,7 +98,20 @@ PLANE_SHAPES = [(2, 16, 28, 28, 2, "f32"), (2, 8, 28, 28, 8, "f32"), (2, 24, 56,
 
 @pytest.mark.parametrize("shape", PLANE_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_logits_on_the_plane_kernels(shape):
-    check_logits(shape, fwd_plan="plane")
+    B, C, H, W, Gr, dtype = shape
+    small = max(H, W) <= 32 and (C // Gr) % 2 == 0 or C == Gr and (H * W) % (4 if dtype == "f32" else 8) == 0 and max(H, W) <= 32
+    check_logits(shape, fwd_plan="plane", bwd_plan="plane" if small else None)
+
+
+# the backward plane kernel's own variants: 16 / 28 / 32 steps, two / four / eight channels per wave, a group
+# split over two workgroups (fp32, few groups), per-channel weights with 8 / 4 / 2 channels per workgroup
+@pytest.mark.parametrize("shape", [(2, 96, 28, 28, 2, "f32"), (1, 16, 28, 28, 4, "f32"), (2, 4, 32, 32, 2, "f32"),
+                                   (1, 6, 12, 20, 3, "f32"), (1, 12, 28, 28, 12, "f32"), (1, 2, 28, 28, 1, "f32"),
+                                   (1, 48, 7, 7, 1, "f32"), (2, 16, 14, 14, 2, "f32"), (2, 16, 7, 7, 2, "bf16"),
+                                   (1, 24, 28, 28, 1, "bf16"), (3, 32, 2, 4, 32, "bf16"), (2, 4, 32, 32, 4, "f32")],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_logits_on_the_backward_plane_kernel_variants(shape):
+    check_logits(shape, bwd_plan="plane")
 
 
 @pytest.mark.parametrize("shape,kchunk", [((2, 16, 28, 28, 2, "f32"), 7), ((2, 8, 28, 28, 8, "f32"), 5),
@@ -106,7 +119,7 @@ def test_logits_on_the_plane_kernels(shape):
                                           ((2, 8, 28, 28, 2, "f32"), 6)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_logits_with_local_stretches_on_the_plane_kernels(shape, kchunk):
-    check_logits(shape, kchunk=kchunk, fwd_plan="plane")
+    check_logits(shape, kchunk=kchunk, fwd_plan="plane", bwd_plan="plane" if max(shape[2], shape[3]) <= 32 else None)
 
 
 @pytest.mark.parametrize("shape", [(1, 8, 28, 28, 2, "f32"), (1, 4, 12, 10, 4, "f32"), (1, 4, 40, 70, 2, "f32"),

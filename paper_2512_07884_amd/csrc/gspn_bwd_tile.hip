@@ -77,7 +77,8 @@ __device__ __forceinline__ void gw_store(rsrc_t rs, uint32_t voff, int so, const
 // vertical directions: lines are image rows, 2 adjacent columns per lane
 // ---------------------------------------------------------------------------
 // LOCAL: GSPN-local (Sec. 3.2), on instantiations of its own so that the global scan carries none of it
-template <typename T, int PF, bool REV, bool LOCAL>
+// LOGITS (with LOCAL): w holds raw logits (normalised as they are consumed) and gw receives the gradient w.r.t. them
+template <typename T, int PF, bool REV, bool LOCAL, bool LOGITS>
 __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, float* est, int b, int c_first,
                                              int pk0, int rounds, int lane, int split) {
     constexpr int V = 2;
@@ -202,6 +203,10 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
                 gw2[0] = fmaf(e0, hm1, gw2[0]); gw2[1] = fmaf(e1, hr, gw2[1]);
 #pragma unroll
                 for (int v = 0; v < V; ++v) { wn0[v] = elem<T>(cur.w0, v); wn1[v] = elem<T>(cur.w1, v); wn2[v] = elem<T>(cur.w2, v); }
+                if constexpr (LOGITS) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) softmax3(wn0[v], wn1[v], wn2[v], first && v == 0, last && v == V - 1);
+                }
                 if constexpr (LOCAL) {
 #pragma unroll
                     for (int v = 0; v < V; ++v) { wn0[v] = no_prev ? 0.f : wn0[v]; wn1[v] = no_prev ? 0.f : wn1[v]; wn2[v] = no_prev ? 0.f : wn2[v]; }
@@ -210,6 +215,11 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
                 if (++r == rounds) {
                     // end of the line: gw leaves the wave, this line's weights become the previous line's
                     const int sow = so0 + n * sstep + pk0 * wround_bytes;
+                    if constexpr (LOGITS) {
+                        // gradient w.r.t. the logits: linear in gw, applied to the partial sums of this lane
+#pragma unroll
+                        for (int v = 0; v < V; ++v) softmax3_grad(gw0[v], gw1[v], gw2[v], wn0[v], wn1[v], wn2[v]);
+                    }
                     if (a.shared_group) {
 #pragma unroll
                         for (int v = 0; v < V; ++v) {
@@ -249,7 +259,7 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
 // horizontal directions: lines are image columns, one image row per lane, the sweep is read in
 // chunks of CS columns (16 B per row and tensor: 4 of fp32, 8 of bf16; 4 of bf16 for odd widths)
 // ---------------------------------------------------------------------------
-template <typename T, bool REV, int CS, bool LOCAL>
+template <typename T, bool REV, int CS, bool LOCAL, bool LOGITS>
 struct BwdHorizontal {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -357,6 +367,7 @@ struct BwdHorizontal {
         float e = es[r * 64];
         float gl[CS], gu[CS];
         float w0p = wc0, w1p = wc1, w2p = wc2;
+        float wk0[LOGITS ? CS : 1], wk1[LOGITS ? CS : 1], wk2[LOGITS ? CS : 1];   // LOGITS: this chunk's normalised weights
 #pragma unroll
         for (int k = 0; k < CS; ++k) {
             const int ix = REV ? k : CS - 1 - k;                  // element of the chunk visited k-th
@@ -380,10 +391,12 @@ struct BwdHorizontal {
             gw1[ix] = fmaf(e, hm, gw1[ix]);
             gw2[ix] = fmaf(e, hr, gw2[ix]);
             w0p = elem<T>(s.w0, ix); w1p = elem<T>(s.w1, ix); w2p = elem<T>(s.w2, ix);
+            if constexpr (LOGITS) softmax3(w0p, w1p, w2p, first, last);
             if constexpr (LOCAL) {
                 const bool z = (starts >> k) & 1u;                // nothing flows into the first line of a stretch
                 w0p = z ? 0.f : w0p; w1p = z ? 0.f : w1p; w2p = z ? 0.f : w2p;
             }
+            if constexpr (LOGITS) { wk0[ix] = w0p; wk1[ix] = w1p; wk2[ix] = w2p; }
         }
         es[r * 64] = e;
         {
@@ -394,6 +407,11 @@ struct BwdHorizontal {
         }
         if (++r == rounds) {
             const int sow = c0 * (int)sizeof(T) + pk0 * wround_bytes;
+            if constexpr (LOGITS) {
+                // gradient w.r.t. the logits: linear in gw, applied to the partial sums of this lane
+#pragma unroll
+                for (int ix = 0; ix < CS; ++ix) softmax3_grad(gw0[ix], gw1[ix], gw2[ix], wk0[ix], wk1[ix], wk2[ix]);
+            }
             if (shared_group) {
 #pragma unroll
                 for (int ix = 0; ix < CS; ++ix) {
@@ -439,8 +457,9 @@ struct BwdHorizontal {
     }
 };
 
-template <typename T, int PF, int MAXW, int HCS, bool LOCAL>
+template <typename T, int PF, int MAXW, int HCS, bool LOCAL, bool LOGITS>
 __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
+    static_assert(LOCAL || !LOGITS, "logits run on the local instantiations (a global scan is one stretch)");
     extern __shared__ float lds[];
     const BwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
@@ -470,8 +489,8 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
             const int rounds = a.shared_group ? packs_v : 1;
             // the wave sweeping the top->bottom scan starts at the bottom rows, the other at the top rows
             const int split = nd == 2 ? (d == 0 ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
-            if (d == 0) bwd_vertical<T, PF, false, LOCAL>(a, tile, est, b, c_first, slot, rounds, lane, split);
-            else bwd_vertical<T, PF, true, LOCAL>(a, tile, est, b, c_first, slot, rounds, lane, split);
+            if (d == 0) bwd_vertical<T, PF, false, LOCAL, LOGITS>(a, tile, est, b, c_first, slot, rounds, lane, split);
+            else bwd_vertical<T, PF, true, LOCAL, LOGITS>(a, tile, est, b, c_first, slot, rounds, lane, split);
         } else if (nd == 2) {
             lds_barrier();
         }
@@ -490,7 +509,7 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
         if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
-            BwdHorizontal<T, false, HCS, LOCAL> hp;
+            BwdHorizontal<T, false, HCS, LOCAL, LOGITS> hp;
             if (busy) { hp.init(a, tile, est, 2, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_lr : nchunks) * rounds);
@@ -499,7 +518,7 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
                 if (busy) hp.run(half_lr * rounds, nchunks * rounds);
             }
         } else {
-            BwdHorizontal<T, true, HCS, LOCAL> hp;
+            BwdHorizontal<T, true, HCS, LOCAL, LOGITS> hp;
             if (busy) { hp.init(a, tile, est, 3, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_rl : nchunks) * rounds);
@@ -623,12 +642,15 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     // needs more registers than 8 waves per workgroup leave, so only workgroups of up to 4 waves take it)
     const bool wide = p.W % 8 == 0;
     void (*k)(BwdTileArgs);
-    if (p.kchunk > 0) {
-        if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, true> : bwd_tile_kernel<float, 4, 8, 4, true>;
-        else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, true> : bwd_tile_kernel<bf16_t, 4, 8, 4, true>;
+    if (p.logits) {
+        if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, true, true> : bwd_tile_kernel<float, 4, 8, 4, true, true>;
+        else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, true, true> : bwd_tile_kernel<bf16_t, 4, 8, 4, true, true>;
+    } else if (p.kchunk > 0) {
+        if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, true, false> : bwd_tile_kernel<float, 4, 8, 4, true, false>;
+        else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, true, false> : bwd_tile_kernel<bf16_t, 4, 8, 4, true, false>;
     } else {
-        if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, false> : bwd_tile_kernel<float, 4, 8, 4, false>;
-        else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, false> : bwd_tile_kernel<bf16_t, 4, 8, 4, false>;
+        if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, false, false> : bwd_tile_kernel<float, 4, 8, 4, false, false>;
+        else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, false, false> : bwd_tile_kernel<bf16_t, 4, 8, 4, false, false>;
     }
     hipError_t e = allow_dynamic_lds((const void*)k, BWD_LDS_BUDGET);
     if (e != hipSuccess) return e;

@@ -87,6 +87,7 @@ struct StretchWalk {
     int until, gap, k;
     // S lines along the scan axis; kchunk >= 1
     __device__ __forceinline__ void init(int S, int reversed, int kchunk) {
+        if (kchunk <= 0) kchunk = 1 << 30;                // the global scan is one stretch
         k = kchunk;
         until = 0;                                        // scan step 0 starts a stretch
         gap = (reversed && S % kchunk) ? S % kchunk : kchunk;   // a reversed scan begins with the short last stretch
@@ -104,6 +105,7 @@ struct StretchWalk {
 struct StretchWalkBack {
     int phase, k, rev;
     __device__ __forceinline__ void init(int S, int reversed, int kchunk) {
+        if (kchunk <= 0) kchunk = 1 << 30;                // the global scan is one stretch
         k = kchunk; rev = reversed;
         // position of the last scan step inside its stretch, counted so that 0 = "starts a stretch"
         phase = reversed ? 1 % kchunk : (S - 1) % kchunk;

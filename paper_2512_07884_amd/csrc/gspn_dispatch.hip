@@ -12,7 +12,6 @@ static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     if (f && f[0] == '1') return FWD_GENERIC;
     const char* np = getenv("GSPN_FWD_NO_PLANE");     // testing aid: keep the tile kernel reachable on small maps
     if (!(np && np[0] == '1') && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
-    if (p.logits) return FWD_GENERIC;                 // weights as logits: plane and generic kernels only
     if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
     return fwd_stream_applicable(p, dtype) ? FWD_STREAM : FWD_GENERIC;
 }
@@ -21,7 +20,6 @@ static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
     if (f && f[0] == '1') return BWD_GENERIC;
     const char* np = getenv("GSPN_BWD_NO_PLANE");     // testing aid: keep the tile kernel reachable on tiny maps
     if (!(np && np[0] == '1') && bwd_plane_applicable(p, dtype)) return BWD_PLANE;
-    if (p.logits) return BWD_GENERIC;                 // weights as logits: plane and generic kernels only
     return bwd_tile_applicable(p, dtype) ? BWD_TILE : BWD_GENERIC;
 }
 

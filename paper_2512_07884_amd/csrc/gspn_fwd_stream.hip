@@ -30,7 +30,8 @@ struct StreamArgs {
 // vertical direction, one wave per line
 // ---------------------------------------------------------------------------
 // LOCAL: GSPN-local (Sec. 3.2), on instantiations of its own so that the global scan carries none of it
-template <typename T, int V, int PF, bool REV, bool LOCAL>
+// LOGITS (with LOCAL): w holds raw logits, normalised as they are consumed (softmax3)
+template <typename T, int V, int PF, bool REV, bool LOCAL, bool LOGITS>
 struct VStream {
     static constexpr int NB = V * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -100,6 +101,7 @@ struct VStream {
                     for (int v = 0; v < V; ++v) {
                         av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
                         w0[v] = elem<T>(cur.w0, v); w1[v] = elem<T>(cur.w1, v); w2[v] = elem<T>(cur.w2, v);
+                        if constexpr (LOGITS) softmax3(w0[v], w1[v], w2[v], first && v == 0, last && v == V - 1);
                         if (LOCAL || k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
                         if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
                     }
@@ -122,7 +124,7 @@ struct VStream {
 // ---------------------------------------------------------------------------
 // horizontal direction, the rows of the image split over `parts` waves, one row per lane
 // ---------------------------------------------------------------------------
-template <typename T, int CS, bool REV, bool LOCAL>
+template <typename T, int CS, bool REV, bool LOCAL, bool LOGITS>
 struct HStream {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -194,6 +196,7 @@ struct HStream {
             bool start = (c == 0) && (k == 0);               // scan step 0: its weights are never used
             if constexpr (LOCAL) start = walk.start();       // ... nor those of a stretch's first line
             float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
+            if constexpr (LOGITS) softmax3(w0, w1, w2, img_first, img_last);
             if (LOCAL || k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
             const float av = elem<T>(bl, e) * elem<T>(bx, e);
             float up = from_lane_below(h), dn = from_lane_above(h);
@@ -230,8 +233,9 @@ struct HStream {
     }
 };
 
-template <typename T, int V, int CS, int PF, bool LOCAL>
+template <typename T, int V, int CS, int PF, bool LOCAL, bool LOGITS>
 __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
+    static_assert(LOCAL || !LOGITS, "logits run on the local instantiations (a global scan is one stretch)");
     __shared__ float mailbox[8 * 4];
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W;
@@ -248,12 +252,12 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
         if (nd == 2) {
             const int split = (H + 1) / 2;          // top->bottom wave: rows [0, split) first; bottom->top: rows [split, H)
             if (wave == 0) {
-                VStream<T, V, PF, false, LOCAL> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, false, LOCAL, LOGITS> v; v.init(p, b, c, lane);
                 v.template run<false>(0, split);
                 __syncthreads();
                 v.template run<true>(split, H);
             } else if (wave == 1) {
-                VStream<T, V, PF, true, LOCAL> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, true, LOCAL, LOGITS> v; v.init(p, b, c, lane);
                 v.template run<false>(0, H - split);
                 __syncthreads();
                 v.template run<true>(H - split, H);
@@ -263,8 +267,8 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
             wrote = true;
         } else if (nd == 1) {
             if (wave == 0) {
-                if (has_tb) { VStream<T, V, PF, false, LOCAL> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
-                else        { VStream<T, V, PF, true, LOCAL> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
+                if (has_tb) { VStream<T, V, PF, false, LOCAL, LOGITS> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
+                else        { VStream<T, V, PF, true, LOCAL, LOGITS> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
             }
             wrote = true;
         }
@@ -277,10 +281,10 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
         __syncthreads();                        // y of the previous phase visible, mailbox cleared
         if (wave < a.parts) {
             if (dsel == 0) {
-                HStream<T, CS, false, LOCAL> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, false, LOCAL, LOGITS> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             } else {
-                HStream<T, CS, true, LOCAL> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, true, LOCAL, LOGITS> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             }
         } else {
@@ -317,8 +321,9 @@ bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p
 template <typename T, int V, int CS, int PF>
 static hipError_t launch_stream(const StreamArgs& a, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * a.p.C)), block(64 * a.nwaves);
-    if (a.p.kchunk > 0) hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, false>), grid, block, 0, s, a);
+    if (a.p.logits) hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, true, true>), grid, block, 0, s, a);
+    else if (a.p.kchunk > 0) hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, true, false>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, false, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 

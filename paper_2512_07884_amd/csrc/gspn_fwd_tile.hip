@@ -38,7 +38,8 @@ struct TileArgs {
 // ---------------------------------------------------------------------------
 // vertical direction (d = 0 top->bottom, 1 bottom->top): lines are image rows
 // ---------------------------------------------------------------------------
-template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL>
+// LOGITS (with LOCAL): w holds raw logits, normalised as they are consumed (softmax3)
+template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL, bool LOGITS>
 __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int b, int c_first, int pk,
                                               int lane, int split) {
     constexpr int NB = V * (int)sizeof(T);
@@ -122,6 +123,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
             av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
             w0[v] = elem<T>(cur.w0, v); w1[v] = elem<T>(cur.w1, v); w2[v] = elem<T>(cur.w2, v);
             uv[v] = elem<T>(cur.u, v);
+            if constexpr (LOGITS) softmax3(w0[v], w1[v], w2[v], first && v == 0, last && v == V - 1);
             if (maybe_start) {
                 w0[v] = scan_start ? 0.f : w0[v]; w1[v] = scan_start ? 0.f : w1[v]; w2[v] = scan_start ? 0.f : w2[v];
             }
@@ -178,7 +180,7 @@ struct HBuf { uint32_t x[V][CS * sizeof(T) / 4], l[V][CS * sizeof(T) / 4], u[V][
 // DB = true: two chunk buffers, the next chunk is loaded while the current one is consumed.
 // DB = false: one buffer (for chunks too large to hold twice); the next chunk is requested as soon
 // as the current one is consumed and other waves of the CU cover the wait.
-template <typename T, int V, int CS, bool REV, bool SAVE, bool DB, bool LOCAL>
+template <typename T, int V, int CS, bool REV, bool SAVE, bool DB, bool LOCAL, bool LOGITS>
 struct HorizontalPass {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -256,6 +258,7 @@ struct HorizontalPass {
             for (int v = 0; v < V; ++v) {
                 av[v] = elem<T>(s.l[v], e) * elem<T>(s.x[v], e);
                 w0[v] = elem<T>(s.w0[v], e); w1[v] = elem<T>(s.w1[v], e); w2[v] = elem<T>(s.w2[v], e);
+                if constexpr (LOGITS) softmax3(w0[v], w1[v], w2[v], first && v == 0, last && v == V - 1);
                 if (LOCAL || k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
                 if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
             }
@@ -312,7 +315,7 @@ struct HorizontalPass {
 // Because every step is its own barrier interval, the two directions never own the same tile
 // column at the same time and no mid-scan split is needed.
 // ---------------------------------------------------------------------------
-template <typename T, int CS, bool REV, bool SAVE, bool LOCAL>
+template <typename T, int CS, bool REV, bool SAVE, bool LOCAL, bool LOGITS>
 struct HorizontalSplitPass {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -393,6 +396,7 @@ struct HorizontalSplitPass {
             bool start = (c == 0) && (k == 0);
             if constexpr (LOCAL) start = walk.start();
             float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
+            if constexpr (LOGITS) softmax3(w0, w1, w2, img_first, img_last);
             if (LOCAL || k == 0) { w0 = start ? 0.f : w0; w1 = start ? 0.f : w1; w2 = start ? 0.f : w2; }
             const float av = elem<T>(bl, e) * elem<T>(bx, e);
             float up = from_lane_below(h), dn = from_lane_above(h);
@@ -426,8 +430,9 @@ struct HorizontalSplitPass {
     }
 };
 
-template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL>
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL, bool LOGITS>
 __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
+    static_assert(LOCAL || !LOGITS, "logits run on the local instantiations (a global scan is one stretch)");
     extern __shared__ float tile[];
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
@@ -455,8 +460,8 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
             const int pk = wave / nd;
             const int d = (nd == 2) ? (wave - pk * nd) : ((p.mask & 1) ? 0 : 1);
             const int split = nd == 2 ? (d == 0 ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
-            if (d == 0) vertical_pass<T, VV, PF, false, SAVE, LOCAL>(a, tile, b, c_first, pk, lane, split);
-            else vertical_pass<T, VV, PF, true, SAVE, LOCAL>(a, tile, b, c_first, pk, lane, split);
+            if (d == 0) vertical_pass<T, VV, PF, false, SAVE, LOCAL, LOGITS>(a, tile, b, c_first, pk, lane, split);
+            else vertical_pass<T, VV, PF, true, SAVE, LOCAL, LOGITS>(a, tile, b, c_first, pk, lane, split);
         } else if (nd == 2) {
             lds_barrier();
         }
@@ -486,13 +491,13 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
             if (nd == 0) {
                 lds_barrier();
             } else if (work && dd == 2) {
-                HorizontalSplitPass<T, CS, false, SAVE, LOCAL> hp;
+                HorizontalSplitPass<T, CS, false, SAVE, LOCAL, LOGITS> hp;
                 hp.init(a, tile, mailbox, 2, dslot, b, c_first, kc, part, lane);
                 hp.prologue();
                 lds_barrier();
                 hp.run();
             } else if (work) {
-                HorizontalSplitPass<T, CS, true, SAVE, LOCAL> hp;
+                HorizontalSplitPass<T, CS, true, SAVE, LOCAL, LOGITS> hp;
                 hp.init(a, tile, mailbox, 3, dslot, b, c_first, kc, part, lane);
                 hp.prologue();
                 lds_barrier();
@@ -504,7 +509,7 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
         } else if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
-            HorizontalPass<T, VH, CS, false, SAVE, DB, LOCAL> hp;
+            HorizontalPass<T, VH, CS, false, SAVE, DB, LOCAL, LOGITS> hp;
             if (busy) { hp.init(a, tile, 2, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();                                  // vertical phase complete (first loads already in flight)
             if (busy) hp.run(0, nd == 2 ? half_lr : nchunks);
@@ -513,7 +518,7 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
                 if (busy) hp.run(half_lr, nchunks);
             }
         } else {
-            HorizontalPass<T, VH, CS, true, SAVE, DB, LOCAL> hp;
+            HorizontalPass<T, VH, CS, true, SAVE, DB, LOCAL, LOGITS> hp;
             if (busy) { hp.init(a, tile, 3, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, nd == 2 ? half_rl : nchunks);
@@ -619,10 +624,10 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
 
 bool fwd_tile_applicable(const FwdParams& p, int dtype) { return plan_tile(p, dtype).ok; }
 
-template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL>
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL, bool LOGITS>
 static hipError_t launch_one_l(const TileArgs& a, const TilePlan& t, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * t.nwaves);
-    auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW, LOCAL>;
+    auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW, LOCAL, LOGITS>;
     hipError_t e = allow_dynamic_lds((const void*)k, LDS_BUDGET);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
@@ -632,8 +637,9 @@ static hipError_t launch_one_l(const TileArgs& a, const TilePlan& t, hipStream_t
 // GSPN-local (Sec. 3.2) runs on instantiations of its own, so that the global scan carries none of it
 template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW>
 static hipError_t launch_one(const TileArgs& a, const TilePlan& t, hipStream_t s) {
-    return a.p.kchunk > 0 ? launch_one_l<T, VV, VH, CS, DB, PF, SAVE, MAXW, true>(a, t, s)
-                          : launch_one_l<T, VV, VH, CS, DB, PF, SAVE, MAXW, false>(a, t, s);
+    if (a.p.logits) return launch_one_l<T, VV, VH, CS, DB, PF, SAVE, MAXW, true, true>(a, t, s);
+    return a.p.kchunk > 0 ? launch_one_l<T, VV, VH, CS, DB, PF, SAVE, MAXW, true, false>(a, t, s)
+                          : launch_one_l<T, VV, VH, CS, DB, PF, SAVE, MAXW, false, false>(a, t, s);
 }
 
 template <typename T, int VV, int VH, int CS, bool DB, int PF>

@@ -73,6 +73,30 @@ def test_argument_errors_are_detected_before_any_launch(lib):
     assert lib.gspn_scan_bwd_local(p, p, p, p, p, p, p, p, p, bad, *ok_dims, 4, 15, 0, 0, None) == 4
 
 
+def test_logits_calls_check_their_arguments_and_dispatch_on_the_host(lib, monkeypatch):
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE"):
+        monkeypatch.delenv(v, raising=False)
+    p = ctypes.c_void_p(0x1000)
+    bad = ctypes.c_void_p(0x1008)
+    dims = (1, 4, 8, 8, 2)
+    big = 1 << 14
+    assert lib.gspn_scan_fwd_logits(p, None, p, p, p, None, *dims, big, 15, 0, 0, None) == 1
+    assert lib.gspn_scan_fwd_logits(p, p, p, p, p, None, *dims, 0, 15, 0, 0, None) == 2            # kchunk < 1
+    assert lib.gspn_scan_fwd_logits(p, bad, p, p, p, None, *dims, big, 15, 0, 0, None) == 4
+    assert lib.gspn_scan_fwd_logits(p, p, p, p, p, None, 1, 4, 8, 5000, 2, big, 15, 0, 0, None) == 5  # line too long here
+    assert lib.gspn_scan_bwd_logits(p, p, p, p, p, None, p, p, p, p, *dims, big, 15, 0, 0, None) == 1
+    assert lib.gspn_scan_bwd_logits(p, p, p, p, p, p, p, bad, p, p, *dims, big, 15, 0, 0, None) == 4
+    assert lib.gspn_scan_bwd_logits(p, p, p, p, p, p, p, p, p, p, 1, 4, 5000, 8, 2, big, 15, 0, 0, None) == 5
+    fwd = lambda *a: lib.gspn_fwd_logits_plan(*a).decode()
+    bwd = lambda *a: lib.gspn_bwd_logits_plan(*a).decode()
+    # dispatch as for the normalised weights (the training stage with per-channel weights is what the fusion is for)
+    assert fwd(32, 192, 28, 28, 192, big, 15, 0, 0, 1) == "plane" and bwd(32, 192, 28, 28, 192, big, 15, 0, 0) == "plane"
+    assert fwd(32, 192, 28, 28, 4, 7, 15, 0, 0, 1) == "plane" and bwd(32, 192, 28, 28, 4, 7, 15, 0, 0) == "plane"
+    assert fwd(64, 96, 56, 56, 8, big, 15, 1, 0, 0) == "plane" and bwd(64, 96, 56, 56, 8, big, 15, 1, 0) == "tile"
+    assert fwd(2, 1024, 128, 128, 16, big, 15, 1, 0, 0) == "tile" and fwd(1, 512, 512, 512, 16, big, 15, 1, 0, 0) == "stream"
+    assert fwd(1, 2, 8, 5000, 1, big, 15, 0, 0, 0) == "invalid" and bwd(1, 2, 8, 8, 1, 0, 15, 0, 0) == "invalid"
+
+
 def test_plan_names(lib):
     assert lib.gspn_fwd_plan(1, 8, 16, 16, 1, 1, 0, 0, 0).decode() != "invalid"
     assert lib.gspn_fwd_plan(1, 8, 16, 16, 3, 1, 0, 0, 0).decode() == "invalid"

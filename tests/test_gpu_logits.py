@@ -75,7 +75,7 @@ def check_logits(shape, kchunk=None, mask=15, seed=101, scale=1.5, poison=False,
 
 
 GENERIC_SHAPES = [(2, 6, 9, 13, 3, "f32"), (1, 4, 33, 70, 2, "f32"), (1, 2, 1, 37, 1, "f32"), (1, 2, 37, 1, 2, "f32"),
-                  (1, 4, 40, 72, 2, "bf16"), (1, 2, 128, 128, 2, "bf16"), (1, 1, 1, 1, 1, "f32")]
+                  (1, 4, 41, 73, 2, "bf16"), (1, 2, 130, 67, 2, "bf16"), (1, 1, 1, 1, 1, "f32")]
 
 
 @pytest.mark.parametrize("shape", GENERIC_SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -83,7 +83,7 @@ def test_logits_on_the_generic_kernels(shape):
     check_logits(shape, fwd_plan="generic", bwd_plan="generic")
 
 
-@pytest.mark.parametrize("shape,kchunk", [((2, 6, 9, 13, 3, "f32"), 4), ((1, 4, 40, 72, 2, "bf16"), 16)],
+@pytest.mark.parametrize("shape,kchunk", [((2, 6, 9, 13, 3, "f32"), 4), ((1, 4, 41, 73, 2, "bf16"), 16)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_logits_with_local_stretches_on_the_generic_kernels(shape, kchunk):
     check_logits(shape, kchunk=kchunk, fwd_plan="generic", bwd_plan="generic")
@@ -131,3 +131,51 @@ def test_logits_that_are_never_read_may_hold_anything(shape):
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9])
 def test_logits_direction_masks(mask):
     check_logits((2, 8, 28, 28, 2, "f32"), mask=mask)
+
+
+# the tile kernels (forward: rows split over waves, 64 B and 16 B bursts; backward: 4 and 8 columns per request,
+# shared and per-channel weights) and the stream kernel (forward without h_save)
+@pytest.mark.parametrize("shape,plans", [
+    ((1, 4, 128, 128, 2, "bf16"), ("tile", "generic")), ((2, 8, 56, 56, 2, "f32"), ("tile", "tile")),
+    ((1, 8, 64, 128, 2, "f32"), ("tile", "tile")), ((1, 4, 96, 72, 2, "bf16"), ("tile", "generic")),
+    ((2, 8, 56, 56, 2, "bf16"), ("plane", "tile")), ((1, 4, 56, 56, 4, "f32"), ("tile", "tile")),
+    ((1, 24, 16, 40, 2, "f32"), ("plane", "tile")), ((2, 8, 40, 32, 8, "f32"), ("plane", "tile")),
+    ((2, 8, 40, 32, 2, "bf16"), ("plane", "tile"))],
+    ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_logits_on_the_tile_kernels(shape, plans):
+    check_logits(shape, fwd_plan=plans[0], bwd_plan=plans[1])
+
+
+@pytest.mark.parametrize("shape,kchunk", [((2, 8, 56, 56, 2, "f32"), 9), ((1, 4, 128, 128, 2, "bf16"), 32),
+                                          ((2, 8, 40, 32, 8, "f32"), 7)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_logits_with_local_stretches_on_the_tile_kernels(shape, kchunk):
+    check_logits(shape, kchunk=kchunk)
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 56, 56, 2, "bf16"), (2, 16, 28, 28, 2, "f32"), (2, 8, 28, 28, 8, "f32")],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_logits_on_the_tile_kernels_for_small_maps(shape, monkeypatch):
+    monkeypatch.setenv("GSPN_FWD_NO_PLANE", "1")
+    monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+    check_logits(shape, fwd_plan="tile", bwd_plan="tile")
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 256, 256, 1, "bf16"), (1, 2, 128, 256, 2, "f32"), (1, 2, 256, 1024, 1, "bf16")],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_logits_on_the_stream_kernel(shape):
+    import torch
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    big = 1 << 14
+    assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, big, 15, int(dtype == "bf16"), 0, False) == "stream"
+    cfg = WL.ScanConfig("logitsstream", B, C, H, W, Gr, dtype, 15, 1.5, 103)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    inp["w"] = WL.make_logits(cfg)
+    f = WL.inputs_as_f64(inp, dtype)
+    y_ref, _ = O.scan_fwd_logits(f["x"], f["w"], f["lam"], f["u"], 15)
+    dev = {k: to_device(v, dtype) for k, v in inp.items()}
+    y = empty_like_dev((B, C, H, W), dtype, float("nan"))
+    G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, G=Gr)
+    torch.cuda.synchronize()
+    assert rel_inf_err(to_host_f64(y), y_ref) <= TOL[dtype]

@@ -184,6 +184,6 @@ const char* gspn_status_string(int status) {
     }
 }
 
-int gspn_version(void) { return 100; }
+int gspn_version(void) { return 200; }   // 0.2.0: GSPN-local and logits entry points
 
 }  // extern "C"

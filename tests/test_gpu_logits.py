@@ -179,3 +179,40 @@ def test_logits_on_the_stream_kernel(shape):
     G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, G=Gr)
     torch.cuda.synchronize()
     assert rel_inf_err(to_host_f64(y), y_ref) <= TOL[dtype]
+
+
+def test_logits_training_stage_at_full_size_on_sampled_slices():
+    """The 28x28 training shape of the benchmark with per-channel weights (B=32, C=192, G=192, fp32) -- the case the
+    fused normalisation is for -- in the launch shape the benchmark times; the oracle computes a few (b, g) slices."""
+    import torch
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr = 32, 192, 28, 28, 192
+    cfg = WL.ScanConfig("logitsfull", B, C, H, W, Gr, "f32", 15, 1.5, 107)
+    inp = WL.make_inputs(cfg, with_gy=True)
+    inp["w"] = WL.make_logits(cfg)
+    dev = {n: to_device(v, "f32") for n, v in inp.items()}
+    nanf = float("nan")
+    y = empty_like_dev((B, C, H, W), "f32", nanf)
+    hs = empty_like_dev((4, B, C, H, W), "f32", nanf)
+    gx = empty_like_dev((B, C, H, W), "f32", nanf)
+    gz = empty_like_dev((4, B, Gr, 3, H, W), "f32", nanf)
+    glam = empty_like_dev((4, B, C, H, W), "f32", nanf)
+    gu = empty_like_dev((4, B, C, H, W), "f32", nanf)
+    assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, 1 << 14, 15, 0, 0, True) == "plane"
+    assert G.gspn_bwd_logits_plan(B, C, H, W, Gr, 1 << 14, 15, 0, 0) == "plane"
+    G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, G=Gr)
+    G.gspn_scan_bwd_logits(dev["gy"], dev["x"], dev["w"], dev["lam"], dev["u"], hs, gx, gz, glam, gu, G=Gr)
+    torch.cuda.synchronize()
+    got = {"y": to_host_f64(y), "gx": to_host_f64(gx), "gz": to_host_f64(gz), "glam": to_host_f64(glam), "gu": to_host_f64(gu)}
+    for b, c0 in ((0, 0), (13, 77), (31, 184)):
+        cs = slice(c0, c0 + 8)                       # eight channels = eight weight groups
+        f = {n: np.asarray(inp[n][:, b:b + 1, cs] if n in ("lam", "u", "w") else inp[n][b:b + 1, cs], dtype=np.float64)
+             for n in ("x", "w", "lam", "u", "gy")}
+        y_ref, h_ref = O.scan_fwd_logits(f["x"], f["w"], f["lam"], f["u"], 15)
+        assert rel_inf_err(got["y"][b:b + 1, cs], y_ref) <= TOL["f32"]
+        h_used = h_ref.astype(np.float32).astype(np.float64)
+        gx_r, gz_r, glam_r, gu_r = O.scan_bwd_logits(f["gy"], f["x"], f["w"], f["lam"], f["u"], h_used, 15)
+        assert rel_inf_err(got["gx"][b:b + 1, cs], gx_r) <= TOL["f32"]
+        assert rel_inf_err(got["gz"][:, b:b + 1, cs], gz_r) <= TOL["f32"]
+        assert rel_inf_err(got["glam"][:, b:b + 1, cs], glam_r) <= TOL["f32"]
+        assert rel_inf_err(got["gu"][:, b:b + 1, cs], gu_r) <= TOL["f32"]

@@ -214,6 +214,31 @@ bwd_plane_kernel(BwdPlaneArgs a) {
 #pragma unroll
         for (int s = 0; s < SMAX; ++s) { gw0[s] = 0.f; gw1[s] = 0.f; gw2[s] = 0.f; }
 
+        // Four / eight channels per wave: the group's three weight planes as one block of 3*HW elements, fetched in
+        // pieces of a.wlw bytes (the block's start is a multiple of its size, so a piece that divides the size is
+        // aligned), through the wave's LDS buffer into registers by scan step; `at` = this lane's element at step 0
+        auto weight_block = [&](const T* wp, int at, float (&w0r)[SMAX], float (&w1r)[SMAX], float (&w2r)[SMAX]) {
+            const int ew = a.wlw / (int)sizeof(T);
+            const rsrc_t rs = make_rsrc(wp);
+            for (int c = lane; c * ew < 3 * HW; c += 64) {
+                const uint32_t bo = (uint32_t)(c * ew * (int)sizeof(T));
+                u32x4 v = {0, 0, 0, 0};
+                if (a.wlw == 16) v = __builtin_amdgcn_raw_buffer_load_b128(rs, bo, 0, 0);
+                else if (a.wlw == 8) { const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, bo, 0, 0); v[0] = t.x; v[1] = t.y; }
+                else if (a.wlw == 4) v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, bo, 0, 0);
+                else v[0] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, bo, 0, 0);
+                float f[E];
+                chunk_unpack<T, E>(v, f);
+#pragma unroll
+                for (int j = 0; j < E; ++j)
+                    if (j < ew) bufX[c * ew + j] = f[j];
+            }
+#pragma unroll
+            for (int s = 0, idx = at; s < SMAX; ++s) {
+                w0r[s] = bufX[idx]; w1r[s] = bufX[idx + HW]; w2r[s] = bufX[idx + 2 * HW];
+                next(idx, s);
+            }
+        };
         // LOGITS: softmax over the taps whose neighbour exists, per scan step; step 0 has no predecessor: no weight
         auto normalise = [&](float (&w0r)[SMAX], float (&w1r)[SMAX], float (&w2r)[SMAX]) {
 #pragma unroll
@@ -278,28 +303,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
 #pragma unroll
                 for (int s = 0, idx = tbw; s < SMAX; ++s) { w2r[s] = bufX[idx]; next(idx, s); }
             } else {
-                // the group's three planes as one block of 3*HW elements, in pieces of a.wlw bytes (the block's
-                // start is a multiple of its size, so a piece that divides the size is aligned)
-                const int ew = a.wlw / (int)sizeof(T);
-                const rsrc_t rs = make_rsrc(wp);
-                for (int c = lane; c * ew < 3 * HW; c += 64) {
-                    const uint32_t bo = (uint32_t)(c * ew * (int)sizeof(T));
-                    u32x4 v = {0, 0, 0, 0};
-                    if (a.wlw == 16) v = __builtin_amdgcn_raw_buffer_load_b128(rs, bo, 0, 0);
-                    else if (a.wlw == 8) { const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, bo, 0, 0); v[0] = t.x; v[1] = t.y; }
-                    else if (a.wlw == 4) v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, bo, 0, 0);
-                    else v[0] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, bo, 0, 0);
-                    float f[E];
-                    chunk_unpack<T, E>(v, f);
-#pragma unroll
-                    for (int j = 0; j < E; ++j)
-                        if (j < ew) bufX[c * ew + j] = f[j];
-                }
-#pragma unroll
-                for (int s = 0, idx = tbw; s < SMAX; ++s) {
-                    w0r[s] = bufX[idx]; w1r[s] = bufX[idx + HW]; w2r[s] = bufX[idx + 2 * HW];
-                    next(idx, s);
-                }
+                weight_block(wp, tbw, w0r, w1r, w2r);
             }
 
             if constexpr (LOGITS) normalise(w0r, w1r, w2r);     // what was loaded are logits
@@ -435,26 +439,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
                     }
                 }
             } else {
-                const int ew = a.wlw / (int)sizeof(T);
-                const rsrc_t rs = make_rsrc(wp);
-                for (int c = lane; c * ew < 3 * HW; c += 64) {
-                    const uint32_t bo = (uint32_t)(c * ew * (int)sizeof(T));
-                    u32x4 v = {0, 0, 0, 0};
-                    if (a.wlw == 16) v = __builtin_amdgcn_raw_buffer_load_b128(rs, bo, 0, 0);
-                    else if (a.wlw == 8) { const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, bo, 0, 0); v[0] = t.x; v[1] = t.y; }
-                    else if (a.wlw == 4) v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, bo, 0, 0);
-                    else v[0] = (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, bo, 0, 0);
-                    float f[E];
-                    chunk_unpack<T, E>(v, f);
-#pragma unroll
-                    for (int j = 0; j < E; ++j)
-                        if (j < ew) bufX[c * ew + j] = f[j];
-                }
-#pragma unroll
-                for (int s = 0, idx = ic * ps + s0; s < SMAX; ++s) {
-                    w0r[s] = bufX[idx]; w1r[s] = bufX[idx + HW]; w2r[s] = bufX[idx + 2 * HW];
-                    next(idx, s);
-                }
+                weight_block(wp, ic * ps + s0, w0r, w1r, w2r);
             }
             normalise(w0r, w1r, w2r);
 #pragma unroll

@@ -155,6 +155,16 @@ def test_local_scans_on_the_stream_kernel(shape, kchunk):
     assert rel_inf_err(to_host_f64(y), y_ref) <= TOL[dtype]
 
 
+# the two limits on every kernel family: kchunk = 1 (every line starts a stretch: no propagation at all) and a
+# stretch longer than one axis only
+@pytest.mark.parametrize("shape,kchunk", [((1, 4, 56, 56, 2, "f32"), 1), ((1, 2, 128, 128, 2, "bf16"), 1),
+                                          ((2, 8, 28, 28, 2, "f32"), 1), ((1, 2, 40, 70, 1, "f32"), 1),
+                                          ((1, 8, 40, 32, 2, "f32"), 36), ((1, 2, 64, 128, 2, "f32"), 64)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_local_scans_at_the_limits_of_kchunk(shape, kchunk):
+    check_local(shape, kchunk)
+
+
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9, 13])
 @pytest.mark.parametrize("shape,kchunk", [((2, 8, 28, 28, 2, "f32"), 6), ((1, 4, 20, 36, 2, "bf16"), 8)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))

@@ -243,6 +243,41 @@ def load_traffic(workload: str, dom: str):
         return None
 
 
+PROXY_SHAPES = (("classifier stage, C 96 -> 8", 64, 96, 8, 56, 56), ("classifier stage, back up 8 -> 96", 64, 8, 96, 56, 56),
+                ("diffusion study, C 1152 -> 144", 2, 1152, 144, 128, 128), ("diffusion study, back up 144 -> 1152", 2, 144, 1152, 128, 128))
+
+
+def proxy_table(steps: int = 50):
+    """Compressive proxy projections (Sec. 4.2) on bf16 tensors: time per call and bytes moved (input read once,
+    output written once, P negligible) against the HBM peak; buffer pairs rotated as in the scan benchmark."""
+    import torch
+    import paper_2512_07884_amd as G
+    rows = []
+    for name, B, K, M, H, W in PROXY_SHAPES:
+        nbytes = 2 * B * (K + M) * H * W
+        nsets = int(min(32, max(1, math.ceil(1.0e9 / nbytes))))     # >= 1 GB in rotation: past the last-level cache
+        sets = [(torch.randn(B, K, H, W, device="cuda").to(torch.bfloat16),
+                 (torch.randn(M, K, device="cuda") / K ** 0.5).to(torch.bfloat16),
+                 torch.empty(B, M, H, W, device="cuda", dtype=torch.bfloat16)) for _ in range(nsets)]
+        for i in range(5):
+            G.gspn_proxy_project(*sets[i % nsets])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            G.gspn_proxy_project(*sets[i % nsets])
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        rows.append({"projection": name, "B": B, "K": K, "M": M, "H": H, "W": W, "kernel": G.gspn_proxy_plan(B, K, M, H, W, 1),
+                     "ms": ms, "bytes": nbytes, "GBs": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "TFLOPs": 2.0 * B * K * M * H * W / (ms * 1e-3) / 1e12})
+        del sets
+        torch.cuda.empty_cache()
+    return rows
+
+
 def copy_calibration(n_bytes: int = 1 << 30, reps: int = 5):
     """Plain copies of a known size: each must read and write exactly n_bytes, which
     fixes the unit in which the profiler's FETCH_SIZE / WRITE_SIZE counters report."""
@@ -265,6 +300,8 @@ def main():
                     help="GSPN-local: confine propagation to stretches of this many lines (0: the global scan)")
     ap.add_argument("--logits", action="store_true",
                     help="weights given as raw logits, normalised inside the call (gspn_scan_*_logits)")
+    ap.add_argument("--proxy", action="store_true",
+                    help="also time the compressive proxy projections (table under detail.proxy_projections)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
     ap.add_argument("--out", default="gpurun_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -317,6 +354,8 @@ def main():
     }
     if cpu is not None:
         line["cpu_baseline"] = cpu
+    if a.proxy:
+        line["detail"]["proxy_projections"] = proxy_table()
     if a.all:
         table = [s]
         for name, c in WL.CONFIGS.items():

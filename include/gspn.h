@@ -145,6 +145,18 @@ int gspn_scan_bwd_logits(const void* gy, const void* x, const void* z, const voi
                          int B, int C, int H, int W, int G, int kchunk,
                          unsigned dir_mask, int dtype, unsigned flags, void* stream);
 
+/* Compressive proxy projection (Sec. 4.2, "Compressive Proxy Dimension"): the 1x1 convolution over the channel
+ * axis that takes x from C channels to C_proxy before the scan, and the learned 1x1 projection back to C after it:
+ *     out[b][m][h][w] = sum_k P[m][k] * in[b][k][h][w]
+ *   in  [B,K,H,W]   P [M,K] row-major   out [B,M,H,W]   (down: K = C, M = C_proxy; up: K = C_proxy, M = C)
+ * The scan in the proxy space is an ordinary gspn_scan_fwd on [B,C_proxy,H,W].  bf16 storage with K and H*W
+ * multiples of 8 runs on the matrix cores (fp32 accumulation, one rounding per output); other shapes and fp32
+ * storage run a plain FMA kernel.  Forward only.  Pointers, stream and errors as for the scan calls. */
+int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int H, int W, int dtype,
+                       void* stream);
+/* "mfma" or "fma": which kernel gspn_proxy_project runs for these arguments ("invalid" for bad ones). */
+const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
+
 /* Name of the kernel family the forward / backward call would dispatch to for
  * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
  * merged output fits in LDS), "stream" (larger maps, forward only), "generic" (any

@@ -51,6 +51,8 @@ Weights as logits (weights_from_logits, scan_*_logits, tests/test_oracle_logits.
 scipy's softmax on the taps that exist, rows of the assembled T_i summing to
 1, shift invariance, indifference to what a masked logit holds, central finite
 differences through the logits.
+Proxy projections (proxy_project, tests/test_oracle_proxy.py): explicit loops,
+identity and selection matrices, composition of two projections.
 """
 from __future__ import annotations
 
@@ -356,6 +358,26 @@ def scan_bwd_logits(gy, x, z, lam, u, h_all, dir_mask=15, kchunk=None):
     else:
         gx, gw, glam, gu = scan_bwd_local(gy, x, w, lam, u, h_all, kchunk, dir_mask)
     return gx, logits_grad_from_weights_grad(gw, w), glam, gu
+
+
+# --------------------------------------------------------------------------
+# compressive proxy projections (Sec. 4.2): 1x1 convolutions over the channel axis
+# --------------------------------------------------------------------------
+def proxy_project(inp, P):
+    """out[b, m, h, w] = sum_k P[m, k] * inp[b, k, h, w]: the projection of Sec. 4.2 that takes x from C
+    channels to C_proxy before the scan (P: [C_proxy, C]) and the learned 1x1 projection back (P: [C, C_proxy])."""
+    inp = np.asarray(inp, dtype=np.float64)
+    P = np.asarray(P, dtype=np.float64)
+    if P.ndim != 2 or inp.ndim != 4 or P.shape[1] != inp.shape[1]:
+        raise ValueError("shape mismatch")
+    return np.einsum("mk,bkhw->bmhw", P, inp)
+
+
+def proxy_scan_fwd(x, Pd, w, lam, u, Pu, dir_mask=15):
+    """The scan wrapped in the compressive proxy (Sec. 4.2): project down, propagate in the proxy space with the
+    shared weights, project back.  x [B,C,H,W]; Pd [Cp,C]; w [4,B,G,3,H,W]; lam, u [4,B,Cp,H,W]; Pu [C,Cp]."""
+    yp, _ = scan_fwd(proxy_project(x, Pd), w, lam, u, dir_mask)
+    return proxy_project(yp, Pu)
 
 
 # --------------------------------------------------------------------------

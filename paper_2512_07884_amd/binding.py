@@ -21,7 +21,7 @@ _LIB = None
 EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_bwd_local",
            "gspn_scan_fwd_logits", "gspn_scan_bwd_logits",
            "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
-           "gspn_fwd_logits_plan", "gspn_bwd_logits_plan",
+           "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_plan",
            "gspn_status_string", "gspn_version")
 
 
@@ -66,6 +66,10 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_fwd_logits_plan.restype = ctypes.c_char_p
     lib.gspn_bwd_logits_plan.argtypes = [ci] * 6 + [cu, ci, cu]
     lib.gspn_bwd_logits_plan.restype = ctypes.c_char_p
+    lib.gspn_proxy_project.argtypes = [vp] * 3 + [ci] * 6 + [vp]
+    lib.gspn_proxy_project.restype = ci
+    lib.gspn_proxy_plan.argtypes = [ci] * 6
+    lib.gspn_proxy_plan.restype = ctypes.c_char_p
     lib.gspn_fwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu, ci]
     lib.gspn_fwd_local_plan.restype = ctypes.c_char_p
     lib.gspn_bwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu]
@@ -230,3 +234,16 @@ def gspn_scan_bwd_logits(gy, x, z, lam, u, h_save, gx, gz, glam, gu, *, kchunk: 
     args, dims = _bwd_args(gy, x, z, lam, u, h_save, gx, gz, glam, gu, G, flags)
     _check(load_library().gspn_scan_bwd_logits(*args, *dims, int(kchunk), dir_mask, _dtype_code(x), flags,
                                                _stream(stream)))
+
+
+def gspn_proxy_plan(B, K, M, H, W, dtype=GSPN_BF16) -> str:
+    return load_library().gspn_proxy_plan(B, K, M, H, W, dtype).decode()
+
+
+def gspn_proxy_project(inp, P, out, *, stream=None) -> None:
+    """out[b, m] = sum_k P[m, k] * inp[b, k] per pixel (compressive proxy projection, Sec. 4.2).
+    inp [B,K,H,W]; P [M,K]; out [B,M,H,W]; device tensors of one dtype, contiguous."""
+    B, K, H, W = inp.shape
+    M = P.shape[0]
+    args = [_ptr(inp, "inp", (B, K, H, W), inp), _ptr(P, "P", (M, K), inp), _ptr(out, "out", (B, M, H, W), inp)]
+    _check(load_library().gspn_proxy_project(*args, B, K, M, H, W, _dtype_code(inp), _stream(stream)))

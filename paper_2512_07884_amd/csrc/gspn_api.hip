@@ -171,6 +171,24 @@ const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, 
     return gspn_bwd_local_plan(B, C, H, W, G, GSPN_MAX_LINE, dir_mask, dtype, flags);
 }
 
+int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int H, int W, int dtype,
+                       void* stream) {
+    if (!in || !P || !out) return GSPN_ERR_NULL;
+    if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1) return GSPN_ERR_SHAPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
+    if ((long long)H * W >= (1ll << 31)) return GSPN_ERR_UNSUPPORTED;
+    if (misaligned(in) || misaligned(P) || misaligned(out)) return GSPN_ERR_ALIGN;
+    hipError_t e = launch_proxy_project(in, P, out, B, K, M, H * W, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype) {
+    if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1 || (dtype != GSPN_F32 && dtype != GSPN_BF16)) return "invalid";
+    if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE || (long long)H * W >= (1ll << 31)) return "invalid";
+    return proxy_mfma_applicable(B, K, M, H * W, dtype) ? "mfma" : "fma";
+}
+
 const char* gspn_status_string(int status) {
     switch (status) {
         case GSPN_OK: return "ok";

@@ -174,6 +174,10 @@ bool bwd_plane_applicable(const BwdParams& p, int dtype);
 // clears `bytes` (a multiple of 16) of device memory with a kernel on stream s (no memset node: capturable)
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s);
 
+// compressive proxy projection (gspn_proxy.hip): out[b][m][n] = sum_k P[m][k] in[b][k][n]
+hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int N, int dtype, hipStream_t s);
+bool proxy_mfma_applicable(int B, int K, int M, int N, int dtype);
+
 // dispatch (gspn_dispatch.hip): picks the kernel family for the arguments
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s);

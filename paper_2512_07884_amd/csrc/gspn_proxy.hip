@@ -1,0 +1,154 @@
+// Compressive proxy projections (Sec. 4.2, "Compressive Proxy Dimension"): the 1x1 convolutions over the channel
+// axis that take x from C channels down to C_proxy before the scan and back up to C after it,
+//
+//     out[b][m][n] = sum_k P[m][k] * in[b][k][n]        n = pixel (h*W + w), contiguous
+//
+// i.e. per image a dense [M x K] by [K x N] product with N = H*W: down-projection M = C_proxy, K = C; back up
+// M = C, K = C_proxy.  This is the one dense contraction around the scan, so it runs on the matrix cores in bf16
+// (v_mfma_f32_32x32x8_bf16_1k, fp32 accumulation); with C_proxy << C it moves far more bytes than it computes and
+// is bound by reading `in` (down) or writing `out` (up) once.
+//
+// Mapping: one wave owns a tile of 32 output channels x 256 pixels.  The MFMA wants both operands packed along
+// k, while `in` is contiguous along n: each lane loads, for its four k-rows (lanes 0-31: k0..k0+3, lanes 32-63:
+// k0+4..k0+7), 16 B = 8 consecutive pixels (a wave reads whole 512 B row segments), and regroups them in registers
+// with byte permutes into eight k-packed B operands, one per pixel of its eight.  Eight MFMAs per k-step then give
+// each lane, per output row it holds, eight consecutive pixels: the result leaves as 16 B stores of whole segments.
+// Shapes the MFMA path does not take (fp32 storage, K or N not multiples of 8) run a plain FMA kernel.
+#include "gspn_tile_common.hpp"
+
+namespace gspn {
+
+namespace {
+
+typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+__global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ P,
+                                                         bf16_t* __restrict__ out, int B, int K, int M, int N,
+                                                         int ntiles, int mtiles) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // work item -> (image, row tile, pixel tile); the four waves of a workgroup take neighbouring pixel tiles
+    const long item = (long)blockIdx.x * 4 + wave;
+    const long per_image = (long)ntiles * mtiles;
+    if (item >= (long)B * per_image) return;
+    const int b = (int)(item / per_image);
+    const int rem = (int)(item - (long)b * per_image);
+    const int mt = rem / ntiles, nt = rem - mt * ntiles;
+    const int jl = lane & 31, kh = lane >> 5;                  // pixel group of the lane, which half of the k-step
+    const int n_lane = nt * 256 + jl * 8;                      // first of the lane's eight pixels
+    const bool n_ok = n_lane < N;                              // N is a multiple of 8: all eight or none
+    const int m_lane = mt * 32 + jl;                           // row of P this lane feeds as the A operand
+    const bool m_ok = m_lane < M;
+
+    const rsrc_t inb = make_rsrc(in + (size_t)b * K * N);
+    const rsrc_t pb = make_rsrc(P);
+    f32x16_t acc[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[v][r] = 0.f;
+
+    // operands of one k-step: the lane's four k-rows of `in` (kr .. kr+3 with kr = k0 + 4*kh) and P[m_lane][kr .. kr+3]
+    auto fetch = [&](int k0, u32x4 (&q)[4], u32x2& pa) {
+        const int kr = k0 + 4 * kh;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            q[kk] = u32x4{0, 0, 0, 0};
+            if (n_ok) q[kk] = __builtin_amdgcn_raw_buffer_load_b128(inb, (uint32_t)(((size_t)(kr + kk) * N + n_lane) * 2), 0, 0);
+        }
+        pa = u32x2{0, 0};
+        if (m_ok) pa = __builtin_amdgcn_raw_buffer_load_b64(pb, (uint32_t)(((size_t)m_lane * K + kr) * 2), 0, 0);
+    };
+    auto multiply = [&](const u32x4 (&q)[4], const u32x2& pa) {
+        const bf16x4_t a = __builtin_bit_cast(bf16x4_t, pa);
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            // pixel v of the lane's eight, its four k values packed: element v sits in word v/2, half v%2
+            const uint32_t sel = (v & 1) ? 0x07060302u : 0x05040100u;
+            const u32x2 bb = {__builtin_amdgcn_perm(q[1][v >> 1], q[0][v >> 1], sel),
+                              __builtin_amdgcn_perm(q[3][v >> 1], q[2][v >> 1], sel)};
+            acc[v] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, __builtin_bit_cast(bf16x4_t, bb), acc[v], 0, 0, 0);
+        }
+    };
+    // two k-steps per trip, the operands of the next two requested before the current two are multiplied
+    // (past the end the last step is requested again: redundant, in bounds, never multiplied)
+    u32x4 q0[4], q1[4], r0[4], r1[4];
+    u32x2 p0, p1, s0, s1;
+    const int last = K - 8;
+    fetch(0, q0, p0);
+    fetch(min(8, last), q1, p1);
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        fetch(min(k0 + 16, last), r0, s0);
+        fetch(min(k0 + 24, last), r1, s1);
+        multiply(q0, p0);
+        if (k0 + 8 < K) multiply(q1, p1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) { q0[kk] = r0[kk]; q1[kk] = r1[kk]; }
+        p0 = s0; p1 = s1;
+    }
+
+    // accumulator register r of a lane: output row 8*(r/4) + 4*(lane/32) + r%4 of the tile, column = the lane's pixel
+    if (!n_ok) return;
+    const rsrc_t ob = make_rsrc(out + (size_t)b * M * N);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = mt * 32 + 8 * (r >> 2) + 4 * kh + (r & 3);
+        if (m < M) {
+            const u32x4 o = {pack_bf16x2(acc[0][r], acc[1][r]), pack_bf16x2(acc[2][r], acc[3][r]),
+                             pack_bf16x2(acc[4][r], acc[5][r]), pack_bf16x2(acc[6][r], acc[7][r])};
+            st_b128(ob, (uint32_t)(((size_t)m * N + n_lane) * 2), o);
+        }
+    }
+}
+
+// any shape, either storage type: one thread per pixel, eight output channels at a time
+template <typename T>
+__global__ void __launch_bounds__(256) proxy_fma_kernel(const T* __restrict__ in, const T* __restrict__ P, T* __restrict__ out,
+                                                        int B, int K, int M, int N) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)B * N) return;
+    const int b = (int)(idx / N), n = (int)(idx - (long)b * N);
+    const T* x = in + (size_t)b * K * N + n;
+    T* y = out + (size_t)b * M * N + n;
+    for (int m0 = 0; m0 < M; m0 += 8) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < K; ++k) {
+            const float xv = ldf(x + (size_t)k * N);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (m0 + j < M) acc[j] = fmaf(ldf(P + (size_t)(m0 + j) * K + k), xv, acc[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (m0 + j < M) stf(y + (size_t)(m0 + j) * N, acc[j]);
+    }
+}
+
+}  // namespace
+
+bool proxy_mfma_applicable(int B, int K, int M, int N, int dtype) {
+    if (dtype != 1 || K % 8 || N % 8) return false;
+    // 32-bit byte offsets inside one image of `in` / `out` and inside P
+    return (size_t)K * N * 2 < (1ull << 31) && (size_t)M * N * 2 < (1ull << 31) && (size_t)M * K * 2 < (1ull << 31);
+}
+
+hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int N, int dtype,
+                                hipStream_t s) {
+    if (proxy_mfma_applicable(B, K, M, N, dtype)) {
+        const int ntiles = (N + 255) / 256, mtiles = (M + 31) / 32;
+        const long items = (long)B * ntiles * mtiles;
+        if ((items + 3) / 4 > 0x7fffffffl) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(proxy_mfma_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, (const bf16_t*)in,
+                           (const bf16_t*)P, (bf16_t*)out, B, K, M, N, ntiles, mtiles);
+        return hipGetLastError();
+    }
+    const long threads = (long)B * N;
+    if ((threads + 255) / 256 > 0x7fffffffl) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    if (dtype == 0) hipLaunchKernelGGL(proxy_fma_kernel<float>, grid, block, 0, s, (const float*)in, (const float*)P, (float*)out, B, K, M, N);
+    else hipLaunchKernelGGL(proxy_fma_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)in, (const bf16_t*)P, (bf16_t*)out, B, K, M, N);
+    return hipGetLastError();
+}
+
+}  // namespace gspn

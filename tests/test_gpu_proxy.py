@@ -1,0 +1,81 @@
+"""GPU parity of the compressive proxy projection (Sec. 4.2) against the fp64 oracle, through the C ABI:
+matrix-core kernel (bf16) and the plain FMA kernel (fp32, ragged shapes), and the whole wrapper
+project down -> scan -> project up."""
+import numpy as np
+import pytest
+
+from gpu_util import TOL, rel_inf_err, to_device, to_host_f64, empty_like_dev
+from oracle import gspn_oracle as O
+from paper_2512_07884_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+
+def run_project(x_st, P_st, dtype):
+    import torch
+    import paper_2512_07884_amd as G
+    B, K, H, W = x_st.shape
+    M = P_st.shape[0]
+    out = empty_like_dev((B, M, H, W), dtype, float("nan"))
+    G.gspn_proxy_project(to_device(x_st, dtype), to_device(P_st, dtype), out)
+    torch.cuda.synchronize()
+    return to_host_f64(out)
+
+
+# (B, K, M, H, W, dtype): down- and up-projections of the paper's shapes (C_proxy = 2 and 8 at classifier widths,
+# 1152 -> 144 of the diffusion study, Sec. 4.2 / App. "low rank"), several row tiles, ragged pixel and row tiles
+SHAPES = [(2, 96, 8, 56, 56, "bf16"), (2, 8, 96, 56, 56, "bf16"), (1, 96, 2, 28, 28, "bf16"), (1, 1152, 144, 16, 16, "bf16"),
+          (1, 144, 1152, 16, 16, "bf16"), (3, 40, 33, 12, 10, "bf16"), (1, 8, 1, 2, 4, "bf16"), (1, 64, 70, 24, 40, "bf16"),
+          (2, 96, 8, 28, 28, "f32"), (1, 7, 5, 9, 13, "f32"), (1, 12, 3, 5, 7, "bf16"), (1, 10, 4, 8, 8, "bf16")]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_projection_matches_the_oracle(shape):
+    import paper_2512_07884_amd as G
+    B, K, M, H, W, dtype = shape
+    rng = np.random.default_rng([11, K, M, H])
+    x = WL.to_storage(rng.standard_normal((B, K, H, W)), dtype)
+    P = WL.to_storage(rng.standard_normal((M, K)) / np.sqrt(K), dtype)
+    want = "mfma" if dtype == "bf16" and K % 8 == 0 and (H * W) % 8 == 0 else "fma"
+    assert G.gspn_proxy_plan(B, K, M, H, W, int(dtype == "bf16")) == want
+    ref = O.proxy_project(WL.storage_to_f64(x, dtype), WL.storage_to_f64(P, dtype))
+    got = run_project(x, P, dtype)
+    assert rel_inf_err(got, ref) <= TOL[dtype], rel_inf_err(got, ref)
+
+
+def test_every_output_element_comes_from_its_own_row_and_pixel():
+    """P with a single 1 per row copies input channels: the output must equal them bit for bit, which pins the
+    operand and accumulator layout of the matrix-core kernel element by element."""
+    rng = np.random.default_rng(5)
+    B, K, M, H, W = 2, 64, 40, 16, 24
+    x = WL.to_storage(rng.standard_normal((B, K, H, W)), "bf16")
+    pick = rng.integers(0, K, size=M)
+    P = np.zeros((M, K))
+    P[np.arange(M), pick] = 1.0
+    got = run_project(x, WL.to_storage(P, "bf16"), "bf16")
+    assert np.array_equal(got, WL.storage_to_f64(x, "bf16")[:, pick])
+
+
+def test_scan_wrapped_in_the_proxy():
+    import torch
+    import paper_2512_07884_amd as G
+    B, C, Cp, H, W, dtype = 2, 96, 8, 56, 56, "bf16"
+    cfg = WL.ScanConfig("proxy", B, Cp, H, W, 1, dtype, 15, 1.0, 21)        # the scan runs on the proxy channels
+    inp = WL.make_inputs(cfg, with_gy=False)
+    rng = np.random.default_rng(22)
+    x = WL.to_storage(rng.standard_normal((B, C, H, W)), dtype)
+    Pd = WL.to_storage(rng.standard_normal((Cp, C)) / np.sqrt(C), dtype)
+    Pu = WL.to_storage(rng.standard_normal((C, Cp)) / np.sqrt(Cp), dtype)
+    dev = {k: to_device(v, dtype) for k, v in inp.items()}
+    xp = empty_like_dev((B, Cp, H, W), dtype)
+    yp = empty_like_dev((B, Cp, H, W), dtype)
+    y = empty_like_dev((B, C, H, W), dtype, float("nan"))
+    G.gspn_proxy_project(to_device(x, dtype), to_device(Pd, dtype), xp)
+    G.gspn_scan_fwd(xp, dev["w"], dev["lam"], dev["u"], yp, None, G=1)
+    G.gspn_proxy_project(yp, to_device(Pu, dtype), y)
+    torch.cuda.synchronize()
+    f = WL.inputs_as_f64(inp, dtype)
+    ref = O.proxy_scan_fwd(WL.storage_to_f64(x, dtype), WL.storage_to_f64(Pd, dtype), f["w"], f["lam"], f["u"],
+                           WL.storage_to_f64(Pu, dtype))
+    # three roundings to bf16 on the way (x_proxy, y_proxy, y): 3 * 2^-9 relative to intermediate maxima
+    assert rel_inf_err(to_host_f64(y), ref) <= 2e-2

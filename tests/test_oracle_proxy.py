@@ -1,0 +1,47 @@
+"""Pins for the oracle's compressive proxy projection (Sec. 4.2), CPU only: the einsum is held against the
+definition written as loops, against matrices whose effect is known, and against composition."""
+import numpy as np
+
+from oracle import gspn_oracle as O
+
+
+def test_projection_equals_the_sum_written_out():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((2, 5, 3, 4))
+    P = rng.standard_normal((3, 5))
+    got = O.proxy_project(x, P)
+    ref = np.zeros((2, 3, 3, 4))
+    for b in range(2):
+        for m in range(3):
+            for k in range(5):
+                for h in range(3):
+                    for w in range(4):
+                        ref[b, m, h, w] += P[m, k] * x[b, k, h, w]
+    assert np.allclose(got, ref, rtol=0, atol=1e-14)
+
+
+def test_identity_selection_and_summing_matrices():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((2, 6, 4, 5))
+    assert np.array_equal(O.proxy_project(x, np.eye(6)), x)
+    sel = np.zeros((2, 6)); sel[0, 4] = 1.0; sel[1, 1] = -2.0
+    out = O.proxy_project(x, sel)
+    assert np.array_equal(out[:, 0], x[:, 4]) and np.array_equal(out[:, 1], -2.0 * x[:, 1])
+    assert np.allclose(O.proxy_project(x, np.ones((1, 6)))[:, 0], x.sum(axis=1), rtol=0, atol=1e-14)
+
+
+def test_two_projections_compose_like_their_matrix_product_and_the_wrapper_is_linear_in_x():
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((1, 8, 3, 3))
+    Pd = rng.standard_normal((2, 8)); Pu = rng.standard_normal((8, 2))
+    assert np.allclose(O.proxy_project(O.proxy_project(x, Pd), Pu), O.proxy_project(x, Pu @ Pd), rtol=0, atol=1e-13)
+    from test_oracle_forward import rand_problem
+    _, w, lam, u = rand_problem(rng, 1, 2, 3, 3, 1)
+    x2 = rng.standard_normal(x.shape)
+    y = O.proxy_scan_fwd(x, Pd, w, lam, u, Pu)
+    y2 = O.proxy_scan_fwd(x2, Pd, w, lam, u, Pu)
+    y12 = O.proxy_scan_fwd(0.5 * x - 2.0 * x2, Pd, w, lam, u, Pu)
+    assert np.allclose(y12, 0.5 * y - 2.0 * y2, rtol=0, atol=1e-12)
+    # with identity projections the wrapper is the scan itself
+    xs = rng.standard_normal((1, 2, 3, 3))
+    assert np.array_equal(O.proxy_scan_fwd(xs, np.eye(2), w, lam, u, np.eye(2)), O.scan_fwd(xs, w, lam, u)[0])

@@ -5,12 +5,12 @@
 //
 // i.e. per image a dense [M x K] by [K x N] product with N = H*W: down-projection M = C_proxy, K = C; back up
 // M = C, K = C_proxy.  This is the one dense contraction around the scan, so it runs on the matrix cores in bf16
-// (v_mfma_f32_32x32x8_bf16_1k, fp32 accumulation); with C_proxy << C it moves far more bytes than it computes and
+// (v_mfma_f32_32x32x16_bf16, or 32x32x8 when K is not a multiple of 16; fp32 accumulation); with C_proxy << C it moves far more bytes than it computes and
 // is bound by reading `in` (down) or writing `out` (up) once.
 //
 // Mapping: one wave owns a tile of 32 output channels x 256 pixels.  The MFMA wants both operands packed along
-// k, while `in` is contiguous along n: each lane loads, for its four k-rows (lanes 0-31: k0..k0+3, lanes 32-63:
-// k0+4..k0+7), 16 B = 8 consecutive pixels (a wave reads whole 512 B row segments), and regroups them in registers
+// k, while `in` is contiguous along n: each lane loads, for its k-rows (lanes 0-31 the first half of the k-step,
+// lanes 32-63 the second), 16 B = 8 consecutive pixels (a wave reads whole 512 B row segments), and regroups them in registers
 // with byte permutes into eight k-packed B operands, one per pixel of its eight.  Eight MFMAs per k-step then give
 // each lane, per output row it holds, eight consecutive pixels: the result leaves as 16 B stores of whole segments.
 // Shapes the MFMA path does not take (fp32 storage, K or N not multiples of 8) run a plain FMA kernel.
@@ -21,20 +21,27 @@ namespace gspn {
 namespace {
 
 typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
+// KS = k values per MFMA: 8 (v_mfma_f32_32x32x8_bf16_1k) or 16 (v_mfma_f32_32x32x16_bf16, K a multiple of 16).
+// A lane feeds KS/2 consecutive k: lanes 0-31 the first half of the k-step, lanes 32-63 the second.
+template <int KS>
 __global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ P,
                                                          bf16_t* __restrict__ out, int B, int K, int M, int N,
                                                          int ntiles, int mtiles) {
+    constexpr int KL = KS / 2;                                 // k-rows per lane and k-step
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    // work item -> (image, row tile, pixel tile); the four waves of a workgroup take neighbouring pixel tiles
+    // work item -> (image, pixel tile, row tile), row tile fastest: the waves of a workgroup take the row tiles of
+    // one pixel tile (they read the same `in`, which then comes out of L1) or, with a single row tile,
+    // neighbouring pixel tiles
     const long item = (long)blockIdx.x * 4 + wave;
     const long per_image = (long)ntiles * mtiles;
     if (item >= (long)B * per_image) return;
     const int b = (int)(item / per_image);
     const int rem = (int)(item - (long)b * per_image);
-    const int mt = rem / ntiles, nt = rem - mt * ntiles;
+    const int nt = rem / mtiles, mt = rem - nt * mtiles;
     const int jl = lane & 31, kh = lane >> 5;                  // pixel group of the lane, which half of the k-step
     const int n_lane = nt * 256 + jl * 8;                      // first of the lane's eight pixels
     const bool n_ok = n_lane < N;                              // N is a multiple of 8: all eight or none
@@ -49,43 +56,50 @@ __global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restric
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[v][r] = 0.f;
 
-    // operands of one k-step: the lane's four k-rows of `in` (kr .. kr+3 with kr = k0 + 4*kh) and P[m_lane][kr .. kr+3]
-    auto fetch = [&](int k0, u32x4 (&q)[4], u32x2& pa) {
-        const int kr = k0 + 4 * kh;
+    struct Step { u32x4 q[KL]; uint32_t pa[KL / 2]; };         // the lane's k-rows of `in`; P[m_lane][its k values]
+    auto fetch = [&](int k0, Step& t) {
+        const int kr = k0 + KL * kh;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            q[kk] = u32x4{0, 0, 0, 0};
-            if (n_ok) q[kk] = __builtin_amdgcn_raw_buffer_load_b128(inb, (uint32_t)(((size_t)(kr + kk) * N + n_lane) * 2), 0, 0);
+        for (int kk = 0; kk < KL; ++kk) {
+            t.q[kk] = u32x4{0, 0, 0, 0};
+            if (n_ok) t.q[kk] = __builtin_amdgcn_raw_buffer_load_b128(inb, (uint32_t)(((size_t)(kr + kk) * N + n_lane) * 2), 0, 0);
         }
-        pa = u32x2{0, 0};
-        if (m_ok) pa = __builtin_amdgcn_raw_buffer_load_b64(pb, (uint32_t)(((size_t)m_lane * K + kr) * 2), 0, 0);
+#pragma unroll
+        for (int i = 0; i < KL / 2; ++i) t.pa[i] = 0;
+        if (m_ok) {
+            const uint32_t po = (uint32_t)(((size_t)m_lane * K + kr) * 2);
+            if constexpr (KS == 8) { const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(pb, po, 0, 0); t.pa[0] = v.x; t.pa[1] = v.y; }
+            else { const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(pb, po, 0, 0); t.pa[0] = v.x; t.pa[1] = v.y; t.pa[2] = v.z; t.pa[3] = v.w; }
+        }
     };
-    auto multiply = [&](const u32x4 (&q)[4], const u32x2& pa) {
-        const bf16x4_t a = __builtin_bit_cast(bf16x4_t, pa);
+    auto multiply = [&](const Step& t) {
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-            // pixel v of the lane's eight, its four k values packed: element v sits in word v/2, half v%2
+            // pixel v of the lane's eight, its k values packed in pairs: element v sits in word v/2, half v%2
             const uint32_t sel = (v & 1) ? 0x07060302u : 0x05040100u;
-            const u32x2 bb = {__builtin_amdgcn_perm(q[1][v >> 1], q[0][v >> 1], sel),
-                              __builtin_amdgcn_perm(q[3][v >> 1], q[2][v >> 1], sel)};
-            acc[v] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, __builtin_bit_cast(bf16x4_t, bb), acc[v], 0, 0, 0);
+            uint32_t bb[KL / 2];
+#pragma unroll
+            for (int i = 0; i < KL / 2; ++i) bb[i] = __builtin_amdgcn_perm(t.q[2 * i + 1][v >> 1], t.q[2 * i][v >> 1], sel);
+            if constexpr (KS == 8) {
+                const u32x2 av = {t.pa[0], t.pa[1]}, bv = {bb[0], bb[1]};
+                acc[v] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(bf16x4_t, av), __builtin_bit_cast(bf16x4_t, bv),
+                                                                  acc[v], 0, 0, 0);
+            } else {
+                const u32x4 av = {t.pa[0], t.pa[1], t.pa[2], t.pa[3]}, bv = {bb[0], bb[1], bb[2], bb[3]};
+                acc[v] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv),
+                                                                 acc[v], 0, 0, 0);
+            }
         }
     };
-    // two k-steps per trip, the operands of the next two requested before the current two are multiplied
-    // (past the end the last step is requested again: redundant, in bounds, never multiplied)
-    u32x4 q0[4], q1[4], r0[4], r1[4];
-    u32x2 p0, p1, s0, s1;
-    const int last = K - 8;
-    fetch(0, q0, p0);
-    fetch(min(8, last), q1, p1);
-    for (int k0 = 0; k0 < K; k0 += 16) {
-        fetch(min(k0 + 16, last), r0, s0);
-        fetch(min(k0 + 24, last), r1, s1);
-        multiply(q0, p0);
-        if (k0 + 8 < K) multiply(q1, p1);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) { q0[kk] = r0[kk]; q1[kk] = r1[kk]; }
-        p0 = s0; p1 = s1;
+    // the operands of the next k-step are requested before the current one is multiplied (past the end the last
+    // step is requested again: redundant, in bounds, never multiplied)
+    Step cur, nxt;
+    const int last = K - KS;
+    fetch(0, cur);
+    for (int k0 = 0; k0 < K; k0 += KS) {
+        fetch(min(k0 + KS, last), nxt);
+        multiply(cur);
+        cur = nxt;
     }
 
     // accumulator register r of a lane: output row 8*(r/4) + 4*(lane/32) + r%4 of the tile, column = the lane's pixel
@@ -139,8 +153,13 @@ hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B,
         const int ntiles = (N + 255) / 256, mtiles = (M + 31) / 32;
         const long items = (long)B * ntiles * mtiles;
         if ((items + 3) / 4 > 0x7fffffffl) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(proxy_mfma_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, (const bf16_t*)in,
-                           (const bf16_t*)P, (bf16_t*)out, B, K, M, N, ntiles, mtiles);
+        const dim3 grid((unsigned)((items + 3) / 4)), block(256);
+        if (K % 16 == 0)
+            hipLaunchKernelGGL(proxy_mfma_kernel<16>, grid, block, 0, s, (const bf16_t*)in, (const bf16_t*)P, (bf16_t*)out,
+                               B, K, M, N, ntiles, mtiles);
+        else
+            hipLaunchKernelGGL(proxy_mfma_kernel<8>, grid, block, 0, s, (const bf16_t*)in, (const bf16_t*)P, (bf16_t*)out,
+                               B, K, M, N, ntiles, mtiles);
         return hipGetLastError();
     }
     const long threads = (long)B * N;

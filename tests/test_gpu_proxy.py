@@ -43,11 +43,12 @@ def test_projection_matches_the_oracle(shape):
     assert rel_inf_err(got, ref) <= TOL[dtype], rel_inf_err(got, ref)
 
 
-def test_every_output_element_comes_from_its_own_row_and_pixel():
+@pytest.mark.parametrize("K", [64, 40], ids=["k16_steps", "k8_steps"])
+def test_every_output_element_comes_from_its_own_row_and_pixel(K):
     """P with a single 1 per row copies input channels: the output must equal them bit for bit, which pins the
-    operand and accumulator layout of the matrix-core kernel element by element."""
+    operand and accumulator layout of the matrix-core kernel (both instruction shapes) element by element."""
     rng = np.random.default_rng(5)
-    B, K, M, H, W = 2, 64, 40, 16, 24
+    B, M, H, W = 2, 40, 16, 24
     x = WL.to_storage(rng.standard_normal((B, K, H, W)), "bf16")
     pick = rng.integers(0, K, size=M)
     P = np.zeros((M, K))

@@ -192,8 +192,12 @@ hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s) {
     const unsigned grid = (unsigned)(items < 65536 ? items : 65536);
     const int block = pick_block(Lmax);
     const size_t shmem = 2 * (size_t)Lmax * sizeof(float);
-    if (dtype == 0) hipLaunchKernelGGL(fwd_generic_kernel<float>, dim3(grid), dim3(block), shmem, s, p);
-    else            hipLaunchKernelGGL(fwd_generic_kernel<bf16_t>, dim3(grid), dim3(block), shmem, s, p);
+    void (*k)(FwdParams) = dtype == 0 ? fwd_generic_kernel<float> : fwd_generic_kernel<bf16_t>;
+    if (shmem > 48 * 1024) {                                 // long lines: ask for the LDS explicitly
+        const hipError_t e = allow_dynamic_lds((const void*)k, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k, dim3(grid), dim3(block), shmem, s, p);
     return hipGetLastError();
 }
 
@@ -204,8 +208,12 @@ hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s) {
     const int block = pick_block(Lmax);
     const size_t shmem = (p.logits ? 8 : 2) * (size_t)Lmax * sizeof(float);
     if (shmem > 128 * 1024) return hipErrorInvalidValue;      // checked by the caller (GSPN_MAX_LINE_LOGITS)
-    if (dtype == 0) hipLaunchKernelGGL(bwd_generic_kernel<float>, dim3(grid), dim3(block), shmem, s, p);
-    else            hipLaunchKernelGGL(bwd_generic_kernel<bf16_t>, dim3(grid), dim3(block), shmem, s, p);
+    void (*k)(BwdParams) = dtype == 0 ? bwd_generic_kernel<float> : bwd_generic_kernel<bf16_t>;
+    if (shmem > 48 * 1024) {                                 // long lines: ask for the LDS explicitly
+        const hipError_t e = allow_dynamic_lds((const void*)k, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k, dim3(grid), dim3(block), shmem, s, p);
     return hipGetLastError();
 }
 

@@ -216,3 +216,38 @@ def test_logits_training_stage_at_full_size_on_sampled_slices():
         assert rel_inf_err(got["gz"][:, b:b + 1, cs], gz_r) <= TOL["f32"]
         assert rel_inf_err(got["glam"][:, b:b + 1, cs], glam_r) <= TOL["f32"]
         assert rel_inf_err(got["gu"][:, b:b + 1, cs], gu_r) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 2, 4096, 1, "f32"), (1, 2, 4096, 2, 2, "f32")], ids=lambda s: "x".join(map(str, s)))
+def test_logits_at_the_longest_supported_line(shape):
+    """GSPN_MAX_LINE_LOGITS positions per line / lines per scan (generic kernels, 128 KB of LDS in the backward).
+    The bound on the error of S sequential fp32 steps with non-expanding weights is S * 2^-24 (2.4e-4 here), which
+    replaces the 1e-5 of the short scans."""
+    import torch
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    big = 1 << 14
+    assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, big, 15, 0, 0, True) == "generic"
+    assert G.gspn_bwd_logits_plan(B, C, H, W, Gr, big, 15, 0, 0) == "generic"
+    cfg = WL.ScanConfig("logitsmax", B, C, H, W, Gr, dtype, 15, 1.0, 109)
+    inp = WL.make_inputs(cfg, with_gy=True)
+    inp["w"] = WL.make_logits(cfg)
+    f = WL.inputs_as_f64(inp, dtype)
+    dev = {n: to_device(v, dtype) for n, v in inp.items()}
+    y = empty_like_dev((B, C, H, W), dtype, float("nan"))
+    hs = empty_like_dev((4, B, C, H, W), dtype, float("nan"))
+    gx = empty_like_dev((B, C, H, W), dtype, float("nan"))
+    gz = empty_like_dev((4, B, Gr, 3, H, W), dtype, float("nan"))
+    glam = empty_like_dev((4, B, C, H, W), dtype, float("nan"))
+    gu = empty_like_dev((4, B, C, H, W), dtype, float("nan"))
+    G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, G=Gr)
+    G.gspn_scan_bwd_logits(dev["gy"], dev["x"], dev["w"], dev["lam"], dev["u"], hs, gx, gz, glam, gu, G=Gr)
+    torch.cuda.synchronize()
+    tol = 4096 * 2.0 ** -24
+    y_ref, h_ref = O.scan_fwd_logits(f["x"], f["w"], f["lam"], f["u"], 15)
+    assert rel_inf_err(to_host_f64(y), y_ref) <= tol
+    h_used = h_ref.astype(np.float32).astype(np.float64)
+    gx_r, gz_r, glam_r, gu_r = O.scan_bwd_logits(f["gy"], f["x"], f["w"], f["lam"], f["u"], h_used, 15)
+    assert rel_inf_err(to_host_f64(gx), gx_r) <= tol
+    assert rel_inf_err(to_host_f64(gz), gz_r) <= tol
+    assert rel_inf_err(to_host_f64(glam), glam_r) <= tol and rel_inf_err(to_host_f64(gu), gu_r) <= tol

@@ -73,7 +73,7 @@ def make_sets(cfg, training: bool, min_total_bytes: float = 1.0e9, max_sets: int
     return sets
 
 
-def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0, logits: bool = False):
+def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0, logits: bool = False, transposed: bool = False):
     """Times `steps` steps; returns dict with wall ms/step and per-kernel event times."""
     import torch
     import paper_2512_07884_amd as G
@@ -81,9 +81,14 @@ def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0, logits: bool = F
     sets = make_sets(cfg, training, logits=logits)
     stream = torch.cuda.current_stream()
     big = 1 << 14
+    if transposed:      # x in both layouts; the parameter slots of directions 2, 3 are read as [.., W, H] (random data)
+        for s_ in sets:
+            s_["xt"] = s_["x"].transpose(-1, -2).contiguous()
 
     def fwd(s):
-        if logits:
+        if transposed:
+            G.gspn_scan_fwd_transposed(s["x"], s["xt"], s["w"], s["lam"], s["u"], s["y"], G=cfg.G, dir_mask=cfg.dir_mask)
+        elif logits:
             G.gspn_scan_fwd_logits(s["x"], s["w"], s["lam"], s["u"], s["y"], s.get("hs"), kchunk=kchunk or big, G=cfg.G,
                                    dir_mask=cfg.dir_mask)
         elif kchunk:
@@ -136,7 +141,7 @@ def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0, logits: bool = F
     fwd_ms = sorted(e[0].elapsed_time(e[1]) for e in ev)
     out = {"ms_per_step": (t1 - t0) * 1e3 / steps,
            "fwd_ms_avg": sum(fwd_ms) / steps, "fwd_ms_med": fwd_ms[steps // 2], "fwd_ms_min": fwd_ms[0],
-           "n_sets": len(sets), "training": training, "warm_ms_per_step": warm_ms, "kchunk": kchunk, "logits": logits}
+           "n_sets": len(sets), "training": training, "warm_ms_per_step": warm_ms, "kchunk": kchunk, "logits": logits, "transposed": transposed}
     if training:
         bwd_ms = sorted(e[1].elapsed_time(e[2]) for e in ev)
         out.update({"bwd_ms_avg": sum(bwd_ms) / steps, "bwd_ms_med": bwd_ms[steps // 2], "bwd_ms_min": bwd_ms[0]})
@@ -153,6 +158,8 @@ def summarise(cfg, r):
     big = 1 << 14                      # a stretch longer than any line: the global scan
     fplan, bplan = (G.gspn_fwd_logits_plan, G.gspn_bwd_logits_plan) if r.get("logits") else \
                    (G.gspn_fwd_local_plan, G.gspn_bwd_local_plan)
+    if r.get("transposed"):
+        fplan = lambda B, C, H, W, G_, k, mask, dt, flags, save: G.gspn_fwd_transposed_plan(B, C, H, W, G_, mask, dt, flags)
     fwd_bytes = cfg.fwd_algorithmic_bytes(save_h=training)
     d = {"workload": cfg.name, "B": cfg.B, "C": cfg.C, "H": cfg.H, "W": cfg.W, "G": cfg.G,
          "storage": cfg.dtype, "directions": cfg.n_dirs,
@@ -169,6 +176,12 @@ def summarise(cfg, r):
         d["kchunk"] = kchunk
     if r.get("logits"):
         d["weights"] = "logits"
+    if r.get("transposed"):
+        d["layout"] = "horizontal directions stored transposed (x read in both layouts: one more plane per pixel*channel)"
+        fwd_bytes += cfg.pixel_channels * (2 if cfg.dtype == "bf16" else 4)
+        d["fwd_algorithmic_bytes"] = fwd_bytes
+        d["fwd_algorithmic_GBs"] = fwd_bytes / (r["fwd_ms_avg"] * 1e-3) / 1e9
+        d["fwd_frac_of_hbm_peak"] = d["fwd_algorithmic_GBs"] / HBM_PEAK_GBS
     if training:
         bb = cfg.bwd_algorithmic_bytes()
         d.update({"bwd_kernel": bplan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0),
@@ -300,6 +313,8 @@ def main():
                     help="GSPN-local: confine propagation to stretches of this many lines (0: the global scan)")
     ap.add_argument("--logits", action="store_true",
                     help="weights given as raw logits, normalised inside the call (gspn_scan_*_logits)")
+    ap.add_argument("--transposed", action="store_true",
+                    help="forward workloads: horizontal directions stored transposed (gspn_scan_fwd_transposed)")
     ap.add_argument("--proxy", action="store_true",
                     help="also time the compressive proxy projections (table under detail.proxy_projections)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
@@ -328,7 +343,10 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    r = run_workload(cfg, a.steps, a.warmup, a.kchunk, a.logits)
+    if a.transposed and (cfg.name in TRAINING or a.kchunk or a.logits):
+        print("bench.py: --transposed is a forward-only layout of the plain scan", file=sys.stderr)
+        sys.exit(2)
+    r = run_workload(cfg, a.steps, a.warmup, a.kchunk, a.logits, a.transposed)
     s = summarise(cfg, r)
     training = r["training"]
     dom = "bwd" if training else "fwd"          # dominant kernel of the step
@@ -344,11 +362,12 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B} C={cfg.C} H={cfg.H} W={cfg.W} G={cfg.G} "
                                f"{cfg.dtype} storage, {cfg.n_dirs} directions, {s['step']}"
                                + (f", GSPN-local kchunk={a.kchunk}" if a.kchunk else "")
-                               + (", weights as logits" if a.logits else ""),
+                               + (", weights as logits" if a.logits else "")
+                               + (", horizontal directions stored transposed" if a.transposed else ""),
                    "kernel": s[f"{dom}_kernel"], "buffer_sets_rotated": s["buffer_sets_rotated"]},
         "roofline": {"bound": "hbm", "kernel": f"gspn_scan_{dom}", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if (a.kchunk or a.logits) else load_traffic(cfg.name, dom),
+                     "traffic": None if (a.kchunk or a.logits or a.transposed) else load_traffic(cfg.name, dom),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "detail": s,
     }

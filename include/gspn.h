@@ -145,6 +145,21 @@ int gspn_scan_bwd_logits(const void* gy, const void* x, const void* z, const voi
                          int B, int C, int H, int W, int G, int kchunk,
                          unsigned dir_mask, int dtype, unsigned flags, void* stream);
 
+/* Forward scan with the horizontal directions stored transposed (Sec. 4.3 reaches coalesced access by laying the
+ * data out along the orthogonal axis; this is that layout offered to a caller who can produce it, e.g. by
+ * computing the parameters of the two horizontal directions from a transposed feature map).  Slots 0 and 1 of
+ * w, lam, u are as in gspn_scan_fwd; slots 2 and 3 hold the tensors of the left->right / right->left directions
+ * transposed, [B,G,3,W,H] and [B,C,W,H], and xt is x transposed, [B,C,W,H].  Weight plane k of a horizontal
+ * direction still addresses row j+k-1 of the previous column.  y is [B,C,H,W] as always: the transposition back
+ * happens on chip.  Inference only (no h_save).  Every scan then reads whole contiguous lines: on maps the tile
+ * kernel takes (H, W even, at most 128) the horizontal directions run at the speed of the vertical ones.
+ * With GSPN_FLAG_SHARED_PARAMS the single slot is read untransposed by directions 0/1 and transposed by 2/3,
+ * which is only meaningful for square maps with symmetric parameters: not recommended. */
+int gspn_scan_fwd_transposed(const void* x, const void* xt, const void* w, const void* lam, const void* u, void* y,
+                             int B, int C, int H, int W, int G,
+                             unsigned dir_mask, int dtype, unsigned flags, void* stream);
+const char* gspn_fwd_transposed_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
+
 /* Compressive proxy projection (Sec. 4.2, "Compressive Proxy Dimension"): the 1x1 convolution over the channel
  * axis that takes x from C channels to C_proxy before the scan, and the learned 1x1 projection back to C after it:
  *     out[b][m][h][w] = sum_k P[m][k] * in[b][k][h][w]

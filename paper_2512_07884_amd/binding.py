@@ -22,6 +22,7 @@ EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_b
            "gspn_scan_fwd_logits", "gspn_scan_bwd_logits",
            "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
            "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_plan",
+           "gspn_scan_fwd_transposed", "gspn_fwd_transposed_plan",
            "gspn_status_string", "gspn_version")
 
 
@@ -66,6 +67,10 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_fwd_logits_plan.restype = ctypes.c_char_p
     lib.gspn_bwd_logits_plan.argtypes = [ci] * 6 + [cu, ci, cu]
     lib.gspn_bwd_logits_plan.restype = ctypes.c_char_p
+    lib.gspn_scan_fwd_transposed.argtypes = [vp] * 6 + [ci] * 5 + [cu, ci, cu, vp]
+    lib.gspn_scan_fwd_transposed.restype = ci
+    lib.gspn_fwd_transposed_plan.argtypes = [ci] * 5 + [cu, ci, cu]
+    lib.gspn_fwd_transposed_plan.restype = ctypes.c_char_p
     lib.gspn_proxy_project.argtypes = [vp] * 3 + [ci] * 6 + [vp]
     lib.gspn_proxy_project.restype = ci
     lib.gspn_proxy_plan.argtypes = [ci] * 6
@@ -247,3 +252,21 @@ def gspn_proxy_project(inp, P, out, *, stream=None) -> None:
     M = P.shape[0]
     args = [_ptr(inp, "inp", (B, K, H, W), inp), _ptr(P, "P", (M, K), inp), _ptr(out, "out", (B, M, H, W), inp)]
     _check(load_library().gspn_proxy_project(*args, B, K, M, H, W, _dtype_code(inp), _stream(stream)))
+
+
+def gspn_fwd_transposed_plan(B, C, H, W, G, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:
+    return load_library().gspn_fwd_transposed_plan(B, C, H, W, G, dir_mask, dtype, flags).decode()
+
+
+def gspn_scan_fwd_transposed(x, xt, w, lam, u, y, *, G: Optional[int] = None, dir_mask: int = DIR_ALL, flags: int = 0,
+                             stream=None) -> None:
+    """Forward scan with the horizontal directions stored transposed: xt [B,C,W,H]; slots 2 and 3 of w, lam, u hold
+    [B,G,3,W,H] / [B,C,W,H] in the same memory footprint as the untransposed slots (pass tensors of the usual shapes
+    whose slots 2, 3 were filled through a transposed view).  y [B,C,H,W]."""
+    B, C, H, W = x.shape
+    if G is None:
+        G = w.shape[2]
+    slots = 1 if (flags & GSPN_FLAG_SHARED_PARAMS) else 4
+    args = [_ptr(x, "x", (B, C, H, W), x), _ptr(xt, "xt", (B, C, W, H), x), _ptr(w, "w", (slots, B, G, 3, H, W), x),
+            _ptr(lam, "lam", (slots, B, C, H, W), x), _ptr(u, "u", (slots, B, C, H, W), x), _ptr(y, "y", (B, C, H, W), x)]
+    _check(load_library().gspn_scan_fwd_transposed(*args, B, C, H, W, G, dir_mask, _dtype_code(x), flags, _stream(stream)))

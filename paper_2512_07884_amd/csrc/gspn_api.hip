@@ -39,7 +39,7 @@ static int scan_fwd_any(const void* x, const void* w, const void* lam, const voi
     if (misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y) ||
         (h_save && misaligned(h_save)))
         return GSPN_ERR_ALIGN;
-    FwdParams p;
+    FwdParams p = {};
     p.x = x; p.w = w; p.lam = lam; p.u = u; p.y = y; p.hs = h_save;
     p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
     p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
@@ -47,6 +47,31 @@ static int scan_fwd_any(const void* x, const void* w, const void* lam, const voi
     p.logits = logits;
     hipError_t e = launch_fwd(p, dtype, (hipStream_t)stream);
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+int gspn_scan_fwd_transposed(const void* x, const void* xt, const void* w, const void* lam, const void* u, void* y,
+                             int B, int C, int H, int W, int G,
+                             unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    if (!x || !xt || !w || !lam || !u || !y) return GSPN_ERR_NULL;
+    int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
+    if (st != GSPN_OK) return st;
+    if (misaligned(x) || misaligned(xt) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y))
+        return GSPN_ERR_ALIGN;
+    FwdParams p = {};
+    p.x = x; p.xt = xt; p.w = w; p.lam = lam; p.u = u; p.y = y; p.hs = nullptr;
+    p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
+    p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    hipError_t e = launch_fwd(p, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+const char* gspn_fwd_transposed_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags) {
+    if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK) return "invalid";
+    FwdParams p = {};
+    p.xt = (const void*)16;
+    p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G; p.mask = dir_mask;
+    p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    return fwd_plan_name(p, dtype);
 }
 
 int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const void* u,

@@ -126,6 +126,8 @@ struct FwdParams {
     int shared;   // 1: w/lam/u have a single direction slot
     int kchunk;   // GSPN-local stretch length; 0: global scan
     int logits;   // 1: w holds raw logits, normalised on the way in (softmax3)
+    const void* xt;   // transposed-horizontal layout: x stored [B][C][W][H]; NULL otherwise.  Slots 2 and 3 of
+                      // w, lam, u are then stored transposed as well ([..][W][H])
 };
 
 struct BwdParams {

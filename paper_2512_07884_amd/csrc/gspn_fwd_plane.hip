@@ -453,6 +453,7 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
     FwdPlanePlan t = {};
     const int es = dtype == 0 ? 4 : 2, E = 16 / es;
     if (p.H < 2 || p.W < 2 || p.H > 64 || p.W > 64) return t;
+    if (p.xt) return t;                                    // transposed-horizontal layout: tile and generic kernels
     const int HW = p.H * p.W;
     const int m = p.H > p.W ? p.H : p.W;
     if (p.W % E == 0) {

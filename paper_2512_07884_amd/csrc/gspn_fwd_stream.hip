@@ -302,6 +302,7 @@ struct StreamPlan { bool ok; int v, parts, nwaves; };
 static StreamPlan plan_stream(const FwdParams& p, int dtype) {
     StreamPlan t = {};
     if (p.hs) return t;                                    // hidden states are not saved on this path
+    if (p.xt) return t;                                    // transposed-horizontal layout: tile and generic kernels
     if (p.W % 64 || p.H % 64) return t;
     const int v = p.W / 64;
     if (dtype == 1 && !(v == 4 || v == 8 || v == 16)) return t;

@@ -39,32 +39,37 @@ struct TileArgs {
 // vertical direction (d = 0 top->bottom, 1 bottom->top): lines are image rows
 // ---------------------------------------------------------------------------
 // LOGITS (with LOCAL): w holds raw logits, normalised as they are consumed (softmax3)
-template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL, bool LOGITS>
+// HT: the same pass for a horizontal direction (2 left->right, 3 right->left) whose w, lam, u (and h_save) slots
+// and x are stored transposed, [..][W][H]: lines are image columns, contiguous in memory, and the pass differs
+// from the vertical one only in the roles of H and W and in how it walks the (row-major) output tile
+template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL, bool LOGITS, bool HT = false>
 __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int b, int c_first, int pk,
                                               int lane, int split) {
     constexpr int NB = V * (int)sizeof(T);
     constexpr int NR = NB / 4;
-    constexpr int d = REV ? 1 : 0;
+    constexpr int d = HT ? (REV ? 3 : 2) : (REV ? 1 : 0);
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
-    const int pl = lane / a.lplv, i = lane - pl * a.lplv;
-    const int c_pack = c_first + pk * a.pv;                    // first channel of this wave's pack
-    const int n_here = min(a.pv, a.K - pk * a.pv);
+    const int S = HT ? W : H, LL = HT ? H : W;                 // scan steps, positions per line
+    const int lpl = HT ? a.lplh : a.lplv, pp = HT ? a.ph : a.pv;
+    const int pl = lane / lpl, i = lane - pl * lpl;
+    const int c_pack = c_first + pk * pp;                      // first channel of this wave's pack
+    const int n_here = min(pp, a.K - pk * pp);
     const bool active = pl < n_here;
     const int plc = active ? pl : 0, ic = active ? i : 0;
     const int c = c_pack + plc;
     const int g = c / p.cpg, g0 = c_pack / p.cpg;
-    const bool first = ic == 0, last = ic == a.lplv - 1;
+    const bool first = ic == 0, last = ic == lpl - 1;
     const size_t planes = (size_t)p.B * p.C;
     const size_t slot_c = p.shared ? 0 : (size_t)d * planes * HW;
     const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
     const size_t plane0 = ((size_t)b * p.C + c_pack) * HW;      // uniform
     const uint32_t voff = (uint32_t)((plc * HW + ic * V) * (int)sizeof(T));
     const uint32_t voff_w = (uint32_t)(((g - g0) * 3 * HW + ic * V) * (int)sizeof(T));
-    const int row_bytes = W * (int)sizeof(T);
+    const int row_bytes = LL * (int)sizeof(T);
     const size_t plane_bytes = (size_t)HW * sizeof(T);
     const char* wbase = (const char*)p.w + (slot_w + ((size_t)b * p.G + g0) * 3 * HW) * sizeof(T);
-    const rsrc_t xb = make_rsrc((const char*)p.x + plane0 * sizeof(T));
+    const rsrc_t xb = make_rsrc((const char*)(HT ? p.xt : p.x) + plane0 * sizeof(T));
     const rsrc_t lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * sizeof(T));
     const rsrc_t ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
     const rsrc_t w0b = make_rsrc(wbase), w1b = make_rsrc(wbase + plane_bytes), w2b = make_rsrc(wbase + 2 * plane_bytes);
@@ -76,9 +81,12 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     // byte / float offsets by a constant signed stride per step, so a step costs no address arithmetic
     // beyond one scalar add (global) and one vector add (LDS)
     const int sstep = REV ? -row_bytes : row_bytes;
-    const int so0 = REV ? (H - 1) * row_bytes : 0;
-    const int tstep = REV ? -a.pitch : a.pitch;
-    float* tp = tile + ((pk * a.pv + plc) * H + (REV ? H - 1 : 0)) * a.pitch + ic * V;   // row of scan step 0
+    const int so0 = REV ? (S - 1) * row_bytes : 0;
+    // tile element of (scan step s, position j of the line): row s, column j -- transposed passes: row j, column s
+    const int tstep = HT ? (REV ? -1 : 1) : (REV ? -a.pitch : a.pitch);
+    const int tvs = HT ? a.pitch : 1;                          // from one of the lane's positions to the next
+    float* tp = HT ? tile + ((pk * pp + plc) * H + ic * V) * a.pitch + (REV ? W - 1 : 0)
+                   : tile + ((pk * pp + plc) * H + (REV ? H - 1 : 0)) * a.pitch + ic * V;   // scan step 0
 
     struct Line { uint32_t x[NR], l[NR], u[NR], w0[NR], w1[NR], w2[NR]; };
     Line slot[PF];
@@ -93,7 +101,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     // the ring starts with scan steps 0..PF-1 (clamped to the last step of short scans: redundant but in
     // bounds); issued unconditionally so that every path into the loops has the same loads in flight
 #pragma unroll
-    for (int k = 0; k < PF; ++k) issue(slot[k], so0 + min(k, H - 1) * sstep);
+    for (int k = 0; k < PF; ++k) issue(slot[k], so0 + min(k, S - 1) * sstep);
 
     float h[V];
 #pragma unroll
@@ -105,7 +113,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     // anything): they are replaced by 0 so the (zero) initial state contributes exactly 0.  GSPN-local
     // (Sec. 3.2): the same at the first line of every stretch, where the carried state counts as 0 too.
     StretchWalk walk;
-    if constexpr (LOCAL) walk.init(H, REV, p.kchunk);
+    if constexpr (LOCAL) walk.init(S, REV, p.kchunk);
     auto step = [&](const Line& cur, bool maybe_start, bool scan_start) {
         if (until_split == 0) lds_barrier();
         --until_split;
@@ -130,7 +138,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
         }
         line_update<V>(h, av, w0, w1, w2, first, last);
 #pragma unroll
-        for (int v = 0; v < V; ++v) tp[v] += uv[v] * h[v];   // exclusive owner of these elements in this half
+        for (int v = 0; v < V; ++v) tp[v * tvs] += uv[v] * h[v];   // exclusive owner of these elements in this half
         tp += tstep;
         if constexpr (SAVE) {
             uint32_t hr[NR];
@@ -145,7 +153,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     // load counter can be waited on by count (never drained).
     int t0 = 0;
     int so_next = so0 + PF * sstep;      // byte offset of the next line to request
-    for (; t0 + 2 * PF <= H; t0 += PF) {
+    for (; t0 + 2 * PF <= S; t0 += PF) {
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
             step(slot[k], k == 0, t0 == 0);
@@ -155,18 +163,18 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
         }
     }
     // Last full block: refills are clamped to the last line (redundant, in bounds), then the tail.
-    if (t0 + PF <= H) {
+    if (t0 + PF <= S) {
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
             step(slot[k], k == 0, t0 == 0);
-            issue(slot[k], so0 + min(t0 + k + PF, H - 1) * sstep);
+            issue(slot[k], so0 + min(t0 + k + PF, S - 1) * sstep);
             __builtin_amdgcn_sched_barrier(0);
         }
         t0 += PF;
     }
 #pragma unroll
     for (int k = 0; k < PF; ++k)
-        if (t0 + k < H) step(slot[k], k == 0, t0 == 0);
+        if (t0 + k < S) step(slot[k], k == 0, t0 == 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -478,7 +486,18 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
         const bool busy = nd > 0 && wave < packs * nd;
         const int pk = busy ? wave / nd : 0;
         const int d = (nd == 2) ? 2 + (wave - pk * nd) : (has_lr ? 2 : 3);
-        if constexpr (VH == 0) {
+        if constexpr (VH == 3) {
+            // transposed storage of the horizontal directions: the vertical pass with the roles of H and W swapped;
+            // the left->right wave takes columns [0, ceil(W/2)) before the mid barrier, the other wave the complement
+            lds_barrier();                                  // vertical phase complete
+            if (busy) {
+                const int split = nd == 2 ? (d == 2 ? (W + 1) / 2 : W - (W + 1) / 2) : -1;
+                if (d == 2) vertical_pass<T, VV, PF, false, SAVE, LOCAL, LOGITS, true>(a, tile, b, c_first, pk, lane, split);
+                else vertical_pass<T, VV, PF, true, SAVE, LOCAL, LOGITS, true>(a, tile, b, c_first, pk, lane, split);
+            } else if (nd == 2) {
+                lds_barrier();
+            }
+        } else if constexpr (VH == 0) {
             // row-split variant: wave -> (channel, direction, part); one barrier per scan step for everybody
             const int ntask = a.K * nd * a.parts;
             const bool work = nd > 0 && wave < ntask;
@@ -558,7 +577,7 @@ static constexpr int LDS_BUDGET = 160 * 1024;
 //   whole-row bursts (rows of at most 128 B: 56 bf16 / 28 fp32), one row per lane, single buffer;
 //   64 B bursts (one L2 sector per row and tensor), two rows per lane, single buffer;
 //   16 B bursts, two rows per lane, double buffered: any width that is a multiple of 16 B.
-enum HVariant { H_ROW = 0, H_SECTOR = 1, H_SMALL = 2, H_SPLIT = 3 };
+enum HVariant { H_ROW = 0, H_SECTOR = 1, H_SMALL = 2, H_SPLIT = 3, H_TRANSPOSED = 4 };
 
 struct TilePlan { bool ok; int hv, vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwaves, parts; size_t lds; };
 
@@ -573,18 +592,23 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
     const int row_bytes = p.W * es;
     int hv;
     const int parts = (p.H + 63) / 64;
-    if (row_bytes == 112 && p.H <= 64) hv = H_ROW;
+    if (p.xt) {
+        // horizontal directions stored transposed: they run the vertical machinery, two image rows per lane
+        if (p.hs || p.H % vv || p.H / vv > 64) return t;
+        hv = H_TRANSPOSED;
+    }
+    else if (row_bytes == 112 && p.H <= 64) hv = H_ROW;
     else if (row_bytes % 128 == 0 && p.H > 64 && p.H % parts == 0 && p.H / parts >= 2) hv = H_SPLIT;
     else if (row_bytes % 64 == 0) hv = H_SECTOR;
     else if (row_bytes % 16 == 0) hv = H_SMALL;
     else return t;
-    if (force_h) {
+    if (force_h && hv != H_TRANSPOSED) {
         const int f = atoi(force_h);
         if (f != H_SPLIT && hv == H_SPLIT) hv = H_SECTOR;
         if (f == H_SMALL && row_bytes % 16 == 0) hv = H_SMALL;
         if (f == H_SECTOR && row_bytes % 64 == 0) hv = H_SECTOR;
     }
-    const int vh = hv == H_ROW ? 1 : (hv == H_SPLIT ? 0 : 2);
+    const int vh = hv == H_ROW ? 1 : (hv == H_SPLIT ? 0 : 2);      // image rows per lane (0: one row, rows split over waves)
     const int cs = hv == H_ROW ? p.W : (hv == H_SPLIT ? 128 / es : (hv == H_SECTOR ? 64 / es : 16 / es));
     if (vh > 0 && (p.H % vh || p.H / vh > 64)) return t;
     t.hv = hv; t.vv = vv; t.vh = vh; t.cs = cs; t.parts = hv == H_SPLIT ? parts : 1;
@@ -659,11 +683,13 @@ hipError_t launch_fwd_tile(const FwdParams& p, int dtype, hipStream_t s) {
     a.nwaves = t.nwaves; a.parts = t.parts;
     const bool save = p.hs != nullptr;
     if (dtype == 0) {
+        if (t.hv == H_TRANSPOSED) return launch_cfg<float, 2, 3, 2, false, TILE_PF>(a, t, save, s);
         if (t.hv == H_SPLIT) return launch_cfg<float, 2, 0, 32, false, TILE_PF>(a, t, save, s);
         if (t.hv == H_ROW) return launch_cfg<float, 2, 1, 28, false, TILE_PF>(a, t, save, s);
         if (t.hv == H_SECTOR) return launch_cfg<float, 2, 2, 16, false, TILE_PF>(a, t, save, s);
         return launch_cfg<float, 2, 2, 4, true, TILE_PF>(a, t, save, s);
     }
+    if (t.hv == H_TRANSPOSED) return launch_cfg<bf16_t, 2, 3, 2, false, TILE_PF>(a, t, save, s);
     if (t.hv == H_SPLIT) return launch_cfg<bf16_t, 2, 0, 64, false, TILE_PF>(a, t, save, s);
     if (t.hv == H_ROW) return launch_cfg<bf16_t, 2, 1, 56, false, TILE_PF>(a, t, save, s);
     if (t.hv == H_SECTOR) return launch_cfg<bf16_t, 2, 2, 32, false, TILE_PF>(a, t, save, s);

@@ -37,7 +37,9 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
             const DirGeom q = dir_geom(d, H, W);
             const size_t slot_c = p.shared ? 0 : (size_t)d * plane_cnt * HW;
             const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
-            const T* xp = X + pc;
+            // transposed-horizontal layout: x, w, lam, u of directions 2 and 3 are stored [..][W][H]
+            const bool tr = p.xt != nullptr && d >= 2;
+            const T* xp = (tr ? (const T*)p.xt : X) + pc;
             const T* lp = LAM + slot_c + pc;
             const T* up = U + slot_c + pc;
             const T* wp = WT + slot_w + ((size_t)b * p.G + g) * 3 * HW;
@@ -46,10 +48,12 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
             float* prev = lds;
             float* cur = lds + Lmax;
             for (int t = 0; t < q.S; ++t) {
-                const int base = (q.reversed ? q.S - 1 - t : t) * q.stride_s;
+                const int line = q.reversed ? q.S - 1 - t : t;
+                const int base = line * q.stride_s;
                 const bool starts = starts_stretch(t, q.S, q.reversed, p.kchunk);
                 for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
-                    const int off = base + j * q.stride_j;
+                    const int offy = base + j * q.stride_j;               // in the image (y)
+                    const int off = tr ? line * q.L + j : offy;          // in the inputs
                     float h = ldf(lp + off) * ldf(xp + off);
                     if (!starts) {   // first line (of the scan, of a stretch): state before it is zero, its weights are not read
                         const bool out0 = j == 0, out2 = j + 1 == q.L;     // no neighbour there: that tap is never read
@@ -61,8 +65,8 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
                     }
                     cur[j] = h;
                     float yv = ldf(up + off) * h;
-                    if (!first) yv += ldf(yp + off);
-                    stf(yp + off, yv);
+                    if (!first) yv += ldf(yp + offy);
+                    stf(yp + offy, yv);
                     if (hp) stf(hp + off, h);
                 }
                 __syncthreads();   // line t complete (LDS) and, after the last line, y visible to the block

@@ -116,3 +116,49 @@ def test_full_size_training_step_sampled_slices_match_the_oracle(name):
             assert rel_inf_err(to_host_f64(gl[d, b, cs]), gl_r[d, 0]) <= tol, (name, b, g, "glam", d)
             assert rel_inf_err(to_host_f64(gu[d, b, cs]), gu_r[d, 0]) <= tol, (name, b, g, "gu", d)
             assert rel_inf_err(to_host_f64(gw[d, b, g]), gw_r[d, 0, 0]) <= tol, (name, b, g, "gw", d)
+
+
+@pytest.mark.parametrize("mode", ["local", "logits", "transposed"])
+def test_full_size_diffusion_shape_in_the_other_call_forms(mode):
+    """diff128 (B=2, C=1024, 128x128, G=16, bf16) through the GSPN-local call (kchunk = 32), the logits call and the
+    call with the horizontal directions stored transposed, in the launch shape bench.py times for them; sampled
+    (b, g) slices against the oracle."""
+    import torch
+    import paper_2512_07884_amd as G
+    cfg = WL.CONFIGS["diff128"]
+    B, C, H, W, Gr, dtype = cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, cfg.dtype
+    inp = WL.make_inputs(cfg, with_gy=False)
+    if mode == "logits":
+        inp["w"] = WL.make_logits(cfg)
+    host = inp
+    if mode == "transposed":
+        host = {k: v.copy() for k, v in inp.items()}
+        for n in ("w", "lam", "u"):
+            for d in (2, 3):
+                host[n][d] = np.ascontiguousarray(np.swapaxes(inp[n][d], -1, -2)).reshape(inp[n][d].shape)
+        host["xt"] = np.ascontiguousarray(np.swapaxes(inp["x"], -1, -2))
+    dev = {k: to_device(v, dtype) for k, v in host.items()}
+    y = empty_like_dev((B, C, H, W), dtype, float("nan"))
+    if mode == "local":
+        assert G.gspn_fwd_local_plan(B, C, H, W, Gr, 32, 15, 1, 0, False) == "tile"
+        G.gspn_scan_fwd_local(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, kchunk=32, G=Gr)
+    elif mode == "logits":
+        assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, 1 << 14, 15, 1, 0, False) == "tile"
+        G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, G=Gr)
+    else:
+        assert G.gspn_fwd_transposed_plan(B, C, H, W, Gr, 15, 1, 0) == "tile"
+        G.gspn_scan_fwd_transposed(dev["x"], dev["xt"], dev["w"], dev["lam"], dev["u"], y, G=Gr)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y.float()).all())
+    f = {k: WL.storage_to_f64(v, dtype) for k, v in inp.items()}
+    for b, g in ((0, 0), (1, 15), (1, 7)):
+        cs = slice(g * cfg.cpg, (g + 1) * cfg.cpg)
+        a = (f["x"][b:b + 1, cs], f["w"][:, b:b + 1, g:g + 1], f["lam"][:, b:b + 1, cs], f["u"][:, b:b + 1, cs])
+        if mode == "local":
+            y_ref, _ = O.scan_fwd_local(*a, 32, 15)
+        elif mode == "logits":
+            y_ref, _ = O.scan_fwd_logits(*a, 15)
+        else:
+            y_ref, _ = O.scan_fwd(*a, 15)
+        err = rel_inf_err(to_host_f64(y[b, cs]), y_ref[0])
+        assert err <= TOL[dtype], (mode, b, g, err)

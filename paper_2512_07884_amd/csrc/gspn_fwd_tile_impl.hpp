@@ -575,7 +575,8 @@ static constexpr int TILE_PF = 8;     // lines kept in flight per wave in the ve
 static constexpr int LDS_BUDGET = 160 * 1024;
 
 // Horizontal-phase variants: rows per lane, scan steps per burst, double buffered or not.
-//   whole-row bursts (rows of at most 128 B: 56 bf16 / 28 fp32), one row per lane, single buffer;
+//   bursts of 112 B (a whole row of 56 bf16 / 28 fp32, half a row of 56 fp32 / 112 bf16), one row per lane,
+//   single buffer;
 //   64 B bursts (one L2 sector per row and tensor), two rows per lane, single buffer;
 //   16 B bursts, two rows per lane, double buffered: any width that is a multiple of 16 B.
 enum HVariant { H_ROW = 0, H_SECTOR = 1, H_SMALL = 2, H_SPLIT = 3, H_TRANSPOSED = 4 };
@@ -601,7 +602,7 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
         if (p.hs || p.H % vv || p.H / vv > 64) return t;
         hv = H_TRANSPOSED;
     }
-    else if (row_bytes == 112 && p.H <= 64) hv = H_ROW;
+    else if (row_bytes % 112 == 0 && row_bytes <= 224 && p.H <= 64) hv = H_ROW;
     else if (row_bytes % 128 == 0 && p.H > 64 && p.H % parts == 0 && p.H / parts >= 2) hv = H_SPLIT;
     else if (row_bytes % 64 == 0) hv = H_SECTOR;
     else if (row_bytes % 16 == 0) hv = H_SMALL;
@@ -613,7 +614,7 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
         if (f == H_SECTOR && row_bytes % 64 == 0) hv = H_SECTOR;
     }
     const int vh = hv == H_ROW ? 1 : (hv == H_SPLIT ? 0 : 2);      // image rows per lane (0: one row, rows split over waves)
-    const int cs = hv == H_ROW ? p.W : (hv == H_SPLIT ? 128 / es : (hv == H_SECTOR ? 64 / es : 16 / es));
+    const int cs = hv == H_ROW ? 112 / es : (hv == H_SPLIT ? 128 / es : (hv == H_SECTOR ? 64 / es : 16 / es));
     if (vh > 0 && (p.H % vh || p.H / vh > 64)) return t;
     t.hv = hv; t.vv = vv; t.vh = vh; t.cs = cs; t.parts = hv == H_SPLIT ? parts : 1;
     t.pitch = p.W | 1;

@@ -49,6 +49,8 @@ SHAPES = [  # B, C, H, W, G
     (3, 5, 2, 2, 5), (1, 2, 64, 64, 1), (1, 2, 63, 65, 2),
     # lines longer than one wave at one row per lane: rows split over 2, 3, 4 waves (even and ragged parts)
     (1, 4, 128, 64, 2), (1, 2, 192, 128, 1), (1, 2, 256, 64, 2), (2, 3, 96, 64, 1), (1, 2, 130, 64, 1),
+    # rows of 224 B in bf16: two bursts of 112 B per row
+    (1, 4, 40, 112, 2),
     # maps too large for an on-chip output tile: output accumulated in global memory
     (1, 2, 256, 256, 1), (1, 3, 192, 512, 3), (1, 2, 64, 1024, 1), (2, 2, 320, 256, 2),
 ]

@@ -34,7 +34,7 @@ struct BwdTileArgs {
     int ph;           // horizontal phases: channels side by side (one image row per lane, H lanes per line)
     int shared_group; // 1: the K channels share one weight group; 0: one weight group per channel
     int gsplit;       // workgroups per weight group (shared_group only); > 1: gw is accumulated atomically
-    int seq_parts;    // > 1: a group is covered by this many launches, one slice of K channels each (bf16 storage)
+    int seq_parts;    // > 1: a group is covered by this many launches, one slice of K channels each
     int seq_index;    // which slice this launch covers; slices after the first add onto the stored gw
     int nwaves;
     int est_floats;   // LDS floats per wave for the carried state of its rounds
@@ -257,9 +257,12 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
 
 // ---------------------------------------------------------------------------
 // horizontal directions: lines are image columns, one image row per lane, the sweep is read in
-// chunks of CS columns (16 B per row and tensor: 4 of fp32, 8 of bf16; 4 of bf16 for odd widths)
+// chunks of CS columns (16 B per row and tensor: 4 of fp32, 8 of bf16; 4 of bf16 for odd widths; 56 B / 112 B --
+// 28 columns of bf16 / fp32 -- for rows that are multiples of 112 B in workgroups of at most four waves)
 // ---------------------------------------------------------------------------
-template <typename T, bool REV, int CS, bool LOCAL, bool LOGITS>
+// DB = false: one item buffer (for bursts too large to hold twice); the next item is requested when the current one
+// has been consumed
+template <typename T, bool REV, int CS, bool LOCAL, bool LOGITS, bool DB = true>
 struct BwdHorizontal {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -450,6 +453,10 @@ struct BwdHorizontal {
     // items [begin, end) of the flattened (chunk, round) sequence; buffer (item & 1) holds item `begin`
     __device__ __forceinline__ void run(int begin, int end) {
         if (!active) return;
+        if constexpr (!DB) {
+            for (int it = begin; it < end; ++it) { compute(buf0); issue(buf0); }   // (past the end: the last item again)
+            return;
+        }
         for (int it = begin; it < end; ++it) {
             if ((it & 1) == 0) { issue(buf1); compute(buf0); }
             else               { issue(buf0); compute(buf1); }
@@ -509,7 +516,7 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
         if (nd == 0) {
             lds_barrier();
         } else if (d == 2) {
-            BwdHorizontal<T, false, HCS, LOCAL, LOGITS> hp;
+            BwdHorizontal<T, false, HCS, LOCAL, LOGITS, (HCS * sizeof(T) < 56)> hp;
             if (busy) { hp.init(a, tile, est, 2, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_lr : nchunks) * rounds);
@@ -518,7 +525,7 @@ __global__ void __launch_bounds__(64 * MAXW) bwd_tile_kernel(BwdTileArgs a) {
                 if (busy) hp.run(half_lr * rounds, nchunks * rounds);
             }
         } else {
-            BwdHorizontal<T, true, HCS, LOCAL, LOGITS> hp;
+            BwdHorizontal<T, true, HCS, LOCAL, LOGITS, (HCS * sizeof(T) < 56)> hp;
             if (busy) { hp.init(a, tile, est, 3, b, c_first, slot, rounds, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, (nd == 2 ? half_rl : nchunks) * rounds);
@@ -596,11 +603,14 @@ static BwdPlan plan_bwd(const BwdParams& p, int dtype) {
         t.shared_group = 1;
         int K = p.cpg, gs = 1;
         const size_t wgs = (size_t)p.B * p.G;
-        // a split group adds into gw atomically, which needs fp32 storage
-        if (dtype == 0 && (K * per_channel > (size_t)BWD_LDS_BUDGET - 16384 || wgs < 384) && K % (2 * lcm) == 0) { K /= 2; gs = 2; }
-        // bf16 storage: a group too large for LDS is covered by two launches, the second adding onto gw
+        // a group too large for LDS is covered by two launches, the second adding onto the stored gw (in the horizontal
+        // phases a lane's gw elements are a row pitch apart: atomics there were measured at four times the cost of this
+        // read-add-write, 1210 against 300 us for the horizontal pair of 56x56x96 fp32); a group that fits, fp32
+        // storage, too few groups to fill the chip: split over two workgroups that add into gw atomically
         int seq = 1;
-        if (dtype != 0 && K * per_channel > (size_t)BWD_LDS_BUDGET - 16384 && K % (2 * lcm) == 0) { K /= 2; seq = 2; }
+        if (K * per_channel > (size_t)BWD_LDS_BUDGET - 16384) {
+            if (K % (2 * lcm) == 0) { K /= 2; seq = 2; }
+        } else if (dtype == 0 && wgs < 384 && K % (2 * lcm) == 0) { K /= 2; gs = 2; }
         if (K % lcm || K * per_channel > (size_t)BWD_LDS_BUDGET - 16384) return t;
         t.K = K; t.gsplit = gs; t.seq_parts = seq;
         t.nwaves = dirs_v > dirs_h ? dirs_v : dirs_h;
@@ -641,8 +651,14 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     // horizontal phases read 8 columns per row and request when the width allows (bf16: 16 B; fp32: 32 B, which
     // needs more registers than 8 waves per workgroup leave, so only workgroups of up to 4 waves take it)
     const bool wide = p.W % 8 == 0;
+    // rows of 112 B and their multiples (56 columns of bf16, 28 / 56 of fp32), workgroups of up to 4 waves: 56 B per
+    // row and request -- the whole register file of a SIMD goes to the one wave it runs
+    const bool burst56 = (p.W * (dtype == 0 ? 4 : 2)) % 112 == 0 && t.nwaves <= 4 && !p.logits && !getenv("GSPN_BWD_NO_BURST56");
     void (*k)(BwdTileArgs);
-    if (p.logits) {
+    if (burst56) {
+        if (p.kchunk > 0) k = dtype == 0 ? bwd_tile_kernel<float, 8, 4, 28, true, false> : bwd_tile_kernel<bf16_t, 8, 4, 28, true, false>;
+        else k = dtype == 0 ? bwd_tile_kernel<float, 8, 4, 28, false, false> : bwd_tile_kernel<bf16_t, 8, 4, 28, false, false>;
+    } else if (p.logits) {
         if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, true, true> : bwd_tile_kernel<float, 4, 8, 4, true, true>;
         else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, true, true> : bwd_tile_kernel<bf16_t, 4, 8, 4, true, true>;
     } else if (p.kchunk > 0) {

@@ -21,11 +21,15 @@ template <int NB> __device__ __forceinline__ void ld_buf(rsrc_t rs, uint32_t vof
     if constexpr (NB == 4) { r[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, 0); }
     else if constexpr (NB == 8) { u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, 0); r[0] = v.x; r[1] = v.y; }
     else {
-        static_assert(NB % 16 == 0, "vector width");
+        static_assert(NB % 8 == 0, "vector width");
 #pragma unroll
         for (int i = 0; i < NB / 16; ++i) {
             u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * i, soff, 0);
             r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+        }
+        if constexpr (NB % 16 != 0) {                  // bursts of 8 (mod 16) bytes: the rest as one 8 B request
+            u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff + (NB / 16) * 16, soff, 0);
+            r[NB / 4 - 2] = v.x; r[NB / 4 - 1] = v.y;
         }
     }
 }
@@ -43,11 +47,16 @@ template <int NB> __device__ __forceinline__ void st_buf(rsrc_t rs, uint32_t vof
         u32x2 v = {r[0], r[1]};
         __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, __builtin_amdgcn_readfirstlane(soff), 0);
     } else {
+        static_assert(NB % 8 == 0, "vector width");
         const uint32_t vo = voff + (uint32_t)soff;
 #pragma unroll
         for (int i = 0; i < NB / 16; ++i) {
             u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
             st_b128(rs, vo + 16 * i, v);
+        }
+        if constexpr (NB % 16 != 0) {
+            u32x2 v = {r[NB / 4 - 2], r[NB / 4 - 1]};
+            __builtin_amdgcn_raw_buffer_store_b64(v, rs, vo + (NB / 16) * 16, 0, 0);
         }
     }
 }

@@ -75,8 +75,10 @@ PLANE_BWD_SHAPES = [(2, 8, 28, 28, 8), (2, 96, 28, 28, 2), (1, 16, 28, 28, 4), (
                     (1, 6, 8, 8, 6), (1, 2, 28, 28, 1), (1, 40, 28, 20, 1), (300, 16, 4, 4, 2)]
 
 # shapes the line-by-line register-resident backward kernel takes: larger maps, odd group sizes
+# (56- and 112-wide maps read 56 / 112 B per row and request in the horizontal phases; twelve 56x56 channels in a
+# group do not fit in LDS: two launches, the second adding onto the stored gw)
 TILE_BWD_SHAPES = [(2, 8, 56, 56, 2), (1, 4, 56, 56, 4), (1, 8, 64, 128, 2), (1, 24, 16, 40, 2), (2, 8, 40, 32, 8),
-                   (2, 8, 40, 32, 2)]
+                   (2, 8, 40, 32, 2), (2, 12, 56, 56, 1), (1, 4, 40, 112, 2)]
 
 
 @pytest.mark.parametrize("shape", PLANE_BWD_SHAPES)
@@ -131,7 +133,7 @@ def test_backward_plane_kernel_direction_masks_bf16(mask):
 
 
 @pytest.mark.parametrize("shape", [(2, 8, 56, 56, 2), (1, 4, 56, 56, 4), (1, 8, 64, 128, 2), (1, 24, 16, 40, 2), (2, 8, 40, 32, 8),
-                                   (2, 12, 56, 56, 1)])
+                                   (2, 12, 56, 56, 1), (1, 4, 40, 112, 2)])
 def test_backward_tile_kernel_shapes_bf16(shape):
     import paper_2512_07884_amd as G
     B, C, H, W, Gr = shape

@@ -651,13 +651,18 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     // horizontal phases read 8 columns per row and request when the width allows (bf16: 16 B; fp32: 32 B, which
     // needs more registers than 8 waves per workgroup leave, so only workgroups of up to 4 waves take it)
     const bool wide = p.W % 8 == 0;
-    // rows of 112 B and their multiples (56 columns of bf16, 28 / 56 of fp32), workgroups of up to 4 waves: 56 B per
-    // row and request -- the whole register file of a SIMD goes to the one wave it runs
-    const bool burst56 = (p.W * (dtype == 0 ? 4 : 2)) % 112 == 0 && t.nwaves <= 4 && !p.logits && !getenv("GSPN_BWD_NO_BURST56");
+    // rows that are multiples of 112 B (56 columns of bf16; 28, 56 of fp32) or of 64 / 128 B (32 columns), workgroups
+    // of up to 4 waves: 56 / 64 B (bf16) or 112 / 128 B (fp32) per row and request -- the whole register file of a SIMD
+    // goes to the one wave it runs
+    const bool big = t.nwaves <= 4 && !p.logits && !getenv("GSPN_BWD_NO_BIG_BURSTS");
+    const bool burst28 = big && (p.W * (dtype == 0 ? 4 : 2)) % 112 == 0, burst32 = big && !burst28 && p.W % 32 == 0;
     void (*k)(BwdTileArgs);
-    if (burst56) {
+    if (burst28) {
         if (p.kchunk > 0) k = dtype == 0 ? bwd_tile_kernel<float, 8, 4, 28, true, false> : bwd_tile_kernel<bf16_t, 8, 4, 28, true, false>;
         else k = dtype == 0 ? bwd_tile_kernel<float, 8, 4, 28, false, false> : bwd_tile_kernel<bf16_t, 8, 4, 28, false, false>;
+    } else if (burst32) {
+        if (p.kchunk > 0) k = dtype == 0 ? bwd_tile_kernel<float, 8, 4, 32, true, false> : bwd_tile_kernel<bf16_t, 8, 4, 32, true, false>;
+        else k = dtype == 0 ? bwd_tile_kernel<float, 8, 4, 32, false, false> : bwd_tile_kernel<bf16_t, 8, 4, 32, false, false>;
     } else if (p.logits) {
         if (dtype == 0) k = (wide && t.nwaves <= 4) ? bwd_tile_kernel<float, 4, 4, 8, true, true> : bwd_tile_kernel<float, 4, 8, 4, true, true>;
         else k = wide ? bwd_tile_kernel<bf16_t, 4, 8, 8, true, true> : bwd_tile_kernel<bf16_t, 4, 8, 4, true, true>;

@@ -156,6 +156,18 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
     float gw0[V] = {0.f, 0.f}, gw1[V] = {0.f, 0.f}, gw2[V] = {0.f, 0.f};
     int n = 0, r = 0;
     int until_split = split;
+    // launches after the first over a group: sums of the line whose stored gw is on its way, and where they go
+    float pend0[V] = {0.f, 0.f}, pend1[V] = {0.f, 0.f}, pend2[V] = {0.f, 0.f};
+    uint32_t old0[NR], old1[NR], old2[NR];
+    int pend_so = -1;
+    auto flush_pending = [&]() {
+        uint32_t o[NR];
+#pragma unroll
+        for (int v = 0; v < V; ++v) { pend0[v] += elem<T>(old0, v); pend1[v] += elem<T>(old1, v); pend2[v] += elem<T>(old2, v); }
+        pack<T, V>(pend0, o); st_buf<NB>(g0b, voff_w, pend_so, o);
+        pack<T, V>(pend1, o); st_buf<NB>(g1b, voff_w, pend_so, o);
+        pack<T, V>(pend2, o); st_buf<NB>(g2b, voff_w, pend_so, o);
+    };
     StretchWalkBack walk;
     if constexpr (LOCAL) walk.init(H, REV, p.kchunk);
     bool no_prev = false;                     // this scan step has no line before it: its gw is 0, nothing flows into it
@@ -236,11 +248,20 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
                                 gw_out(g1b, gwbase + plane_bytes, voff_w + 4 * v, sow, gw1[v], true);
                                 gw_out(g2b, gwbase + 2 * plane_bytes, voff_w + 4 * v, sow, gw2[v], true);
                             }
+                        } else if (a.seq_index > 0) {
+                            // a later launch over the same group adds onto the stored gw: the stored values of this line
+                            // are requested here and added a line later, when they have arrived behind that line's work
+                            if (pend_so >= 0) flush_pending();
+#pragma unroll
+                            for (int v = 0; v < V; ++v) { pend0[v] = gw0[v]; pend1[v] = gw1[v]; pend2[v] = gw2[v]; }
+                            ld_buf<NB>(g0b, voff_w, sow, old0);
+                            ld_buf<NB>(g1b, voff_w, sow, old1);
+                            ld_buf<NB>(g2b, voff_w, sow, old2);
+                            pend_so = sow;
                         } else {
-                            const bool add = a.seq_index > 0;
-                            gw_store<T, V>(g0b, voff_w, sow, gw0, add);
-                            gw_store<T, V>(g1b, voff_w, sow, gw1, add);
-                            gw_store<T, V>(g2b, voff_w, sow, gw2, add);
+                            gw_store<T, V>(g0b, voff_w, sow, gw0, false);
+                            gw_store<T, V>(g1b, voff_w, sow, gw1, false);
+                            gw_store<T, V>(g2b, voff_w, sow, gw2, false);
                         }
                     }
 #pragma unroll
@@ -253,6 +274,7 @@ __device__ __forceinline__ void bwd_vertical(const BwdTileArgs& a, float* tile, 
             }
         }
     }
+    if (pend_so >= 0 && (!a.shared_group || pl == 0)) flush_pending();
 }
 
 // ---------------------------------------------------------------------------

@@ -1,0 +1,198 @@
+// Backward GSPN scan in two passes, for maps beyond the reach of the single-launch backward kernels (more than 64
+// lines per scan, weight groups that do not fit one workgroup: the 128x128 diffusion shape with 64 channels per group).
+//
+// The paper gives no algorithm for the backward pass (Sec. 5.1 has timings only); this is the chain rule on Eq. 1-2
+// (Sec. 3.2) with the shared weights of Sec. 4.2, split where the sum over the channels of a group comes in:
+//
+//   pass 1, per channel: e_t = u_t*gy_t + T_{t+1}^T e_{t+1} is the forward recurrence run against the scan order with the
+//           tridiagonal transposed, and gx = sum_d lam_d*e_d is its merged output -- so it runs on the forward tile kernels
+//           (reverse-sweep instantiations: gy as x, u as lam, lam as u, gx as y), which also save e per direction, into
+//           the buffer of glam;
+//   pass 2, per (direction, image, group) and pixel: gw[k] = sum over the group's channels of e[j] * h_{t-1}[j+k-1] has no
+//           recurrence left: one thread per few adjacent pixels walks the channels, accumulates the three taps in fp32
+//           registers, and on the way turns the saved e into glam = x*e in place and writes gu = gy*h.
+//
+// No scratch memory and no atomics: every output element has one writer, the channel sum has a fixed order.  In bf16
+// storage e passes through storage precision between the passes (one rounding more on glam and on the terms of gw,
+// whose sum is still accumulated in fp32).
+#include "gspn_tile_common.hpp"
+
+namespace gspn {
+
+hipError_t launch_reverse_sweep_f32(const FwdParams& p, hipStream_t s);
+hipError_t launch_reverse_sweep_bf16(const FwdParams& p, hipStream_t s);
+
+namespace {
+
+// VEC adjacent elements of storage, widened to fp32 (p aligned to VEC elements)
+template <typename T, int VEC> __device__ __forceinline__ void ldv(const T* p, float (&out)[VEC]) {
+    constexpr int NB = VEC * (int)sizeof(T);
+    uint32_t r[NB / 4];
+    if constexpr (NB == 4) r[0] = *(const uint32_t*)p;
+    else if constexpr (NB == 8) { const u32x2 v = *(const u32x2*)p; r[0] = v.x; r[1] = v.y; }
+    else {
+#pragma unroll
+        for (int i = 0; i < NB / 16; ++i) {
+            const u32x4 v = ((const u32x4*)p)[i];
+            r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) out[v] = elem<T>(r, v);
+}
+template <typename T, int VEC> __device__ __forceinline__ void stv(T* p, const float (&in)[VEC]) {
+    constexpr int NB = VEC * (int)sizeof(T);
+    uint32_t r[NB / 4];
+    pack<T, VEC>(in, r);
+    if constexpr (NB == 4) *(uint32_t*)p = r[0];
+    else if constexpr (NB == 8) { const u32x2 v = {r[0], r[1]}; *(u32x2*)p = v; }
+    else {
+#pragma unroll
+        for (int i = 0; i < NB / 16; ++i) {
+            const u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
+            ((u32x4*)p)[i] = v;
+        }
+    }
+}
+
+// h of the previous scan line as the three taps of VEC adjacent pixels see it.  `row` = the image row to read (NULL: it
+// does not exist), j0 = first column of the pixels, `shift` = column offset of the tap (-1, 0, +1); 0 outside the image.
+template <typename T, int VEC>
+__device__ __forceinline__ void tap_window(const T* row, int j0, int W, int shift, const float (&centre)[VEC], float (&out)[VEC]) {
+    if (shift == 0) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) out[v] = centre[v];
+    } else if (shift < 0) {
+        const float edge = (row && j0 > 0) ? ldf(row + j0 - 1) : 0.f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) out[v] = v > 0 ? centre[v - 1] : edge;
+    } else {
+        const float edge = (row && j0 + VEC < W) ? ldf(row + j0 + VEC) : 0.f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) out[v] = v < VEC - 1 ? centre[v + 1] : edge;
+    }
+}
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs) {
+    const int H = p.H, W = p.W, HW = H * W;
+    const int npb = HW / VEC;
+    const size_t per_dir = (size_t)p.B * p.G * npb;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_dir * ndirs) return;
+    int dsel = (int)(idx / per_dir);
+    const size_t rem = idx - (size_t)dsel * per_dir;
+    const int bg = (int)(rem / npb);
+    const int pix0 = (int)(rem - (size_t)bg * npb) * VEC;
+    int d = 0;
+    for (;; ++d)                                               // the dsel-th direction of the mask
+        if ((p.mask >> d) & 1u) { if (dsel == 0) break; --dsel; }
+    const int b = bg / p.G, g = bg - b * p.G;
+    const int i = pix0 / W, j0 = pix0 - i * W;                 // VEC divides W: the pixels share a row
+    const size_t planes = (size_t)p.B * p.C, groups = (size_t)p.B * p.G;
+    const T* X = (const T*)p.x;
+    const T* GY = (const T*)p.gy;
+    const T* HS = (const T*)p.hs + (size_t)d * planes * HW;
+    T* GL = (T*)p.glam + (size_t)d * planes * HW;              // holds e on entry
+    T* GU = (T*)p.gu + (size_t)d * planes * HW;
+    T* GW = (T*)p.gw + ((size_t)d * groups + bg) * 3 * HW;
+    // where the previous scan line is: a row up / down (vertical scans, taps along the columns) or a column left / right
+    // (horizontal scans, taps along the rows)
+    const bool vert = d < 2;
+    const int drow = vert ? ((d & 1) ? 1 : -1) : 0;
+    const int dcol = vert ? 0 : ((d & 1) ? 1 : -1);
+
+    float a0[VEC], a1[VEC], a2[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) { a0[v] = 0.f; a1[v] = 0.f; a2[v] = 0.f; }
+
+    for (int ci = 0; ci < p.cpg; ++ci) {
+        const size_t plane = ((size_t)b * p.C + (size_t)g * p.cpg + ci) * HW;
+        float e[VEC], xv[VEC], gyv[VEC], hc[VEC];
+        ldv<T, VEC>(GL + plane + pix0, e);
+        ldv<T, VEC>(X + plane + pix0, xv);
+        ldv<T, VEC>(GY + plane + pix0, gyv);
+        ldv<T, VEC>(HS + plane + pix0, hc);
+        float t0[VEC], t1[VEC], t2[VEC];
+        if (vert) {
+            const int ip = i + drow;
+            const T* row = (ip >= 0 && ip < H) ? HS + plane + (size_t)ip * W : nullptr;
+            float hv[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) hv[v] = 0.f;
+            if (row) ldv<T, VEC>(row + j0, hv);
+            tap_window<T, VEC>(row, j0, W, -1, hv, t0);
+            tap_window<T, VEC>(row, j0, W, 0, hv, t1);
+            tap_window<T, VEC>(row, j0, W, 1, hv, t2);
+        } else {
+            float hv[VEC];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const int ir = i + k - 1;
+                const T* row = (ir >= 0 && ir < H) ? HS + plane + (size_t)ir * W : nullptr;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) hv[v] = 0.f;
+                if (row) ldv<T, VEC>(row + j0, hv);
+                tap_window<T, VEC>(row, j0, W, dcol, hv, k == 0 ? t0 : (k == 1 ? t1 : t2));
+            }
+        }
+        float gl[VEC], gu[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            a0[v] = fmaf(e[v], t0[v], a0[v]);
+            a1[v] = fmaf(e[v], t1[v], a1[v]);
+            a2[v] = fmaf(e[v], t2[v], a2[v]);
+            gl[v] = xv[v] * e[v];
+            gu[v] = gyv[v] * hc[v];
+        }
+        stv<T, VEC>(GL + plane + pix0, gl);
+        stv<T, VEC>(GU + plane + pix0, gu);
+    }
+    stv<T, VEC>(GW + pix0, a0);
+    stv<T, VEC>(GW + HW + pix0, a1);
+    stv<T, VEC>(GW + 2 * (size_t)HW + pix0, a2);
+}
+
+FwdParams reverse_sweep_params(const BwdParams& p) {
+    FwdParams f = {};
+    f.x = p.gy; f.w = p.w; f.lam = p.u; f.u = p.lam; f.y = p.gx; f.hs = p.glam;
+    f.B = p.B; f.C = p.C; f.H = p.H; f.W = p.W; f.G = p.G; f.cpg = p.cpg;
+    f.mask = p.mask; f.shared = p.shared; f.kchunk = 0; f.logits = 0; f.xt = nullptr;
+    return f;
+}
+
+template <typename T, int VEC>
+hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
+    const size_t threads = (size_t)ndirs * p.B * p.G * (p.H * p.W / VEC);
+    const size_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_finish_kernel<T, VEC>), dim3((unsigned)blocks), dim3(256), 0, s, p, ndirs);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool bwd_twopass_applicable(const BwdParams& p, int dtype) {
+    if (p.kchunk > 0 || p.logits || p.W % 2) return false;
+    if ((size_t)p.B * p.G * ((size_t)p.H * p.W / 2) * 4 / 256 > 0x7fffffffull) return false;
+    return fwd_tile_applicable(reverse_sweep_params(p), dtype);
+}
+
+hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
+    if (!bwd_twopass_applicable(p, dtype)) return hipErrorInvalidValue;
+    const FwdParams f = reverse_sweep_params(p);
+    hipError_t e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);
+    if (e != hipSuccess) return e;
+    int ndirs = 0;
+    for (int d = 0; d < 4; ++d) ndirs += (p.mask >> d) & 1u;
+    if (dtype == 0) {
+        if (p.W % 8 == 0) return launch_finish<float, 8>(p, ndirs, s);
+        if (p.W % 4 == 0) return launch_finish<float, 4>(p, ndirs, s);
+        return launch_finish<float, 2>(p, ndirs, s);
+    }
+    if (p.W % 8 == 0) return launch_finish<bf16_t, 8>(p, ndirs, s);
+    if (p.W % 4 == 0) return launch_finish<bf16_t, 4>(p, ndirs, s);
+    return launch_finish<bf16_t, 2>(p, ndirs, s);
+}
+
+}  // namespace gspn

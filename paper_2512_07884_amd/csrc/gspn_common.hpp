@@ -173,6 +173,8 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s);
 bool bwd_tile_applicable(const BwdParams& p, int dtype);
 hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s);
 bool bwd_plane_applicable(const BwdParams& p, int dtype);
+hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s);
+bool bwd_twopass_applicable(const BwdParams& p, int dtype);
 // clears `bytes` (a multiple of 16) of device memory with a kernel on stream s (no memset node: capturable)
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s);
 

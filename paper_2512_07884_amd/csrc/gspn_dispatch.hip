@@ -5,7 +5,7 @@
 namespace gspn {
 
 enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1, FWD_STREAM = 2, FWD_PLANE = 3 };
-enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1, BWD_PLANE = 2 };
+enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1, BWD_PLANE = 2, BWD_TWOPASS = 3 };
 
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
@@ -20,7 +20,10 @@ static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
     if (f && f[0] == '1') return BWD_GENERIC;
     const char* np = getenv("GSPN_BWD_NO_PLANE");     // testing aid: keep the tile kernel reachable on tiny maps
     if (!(np && np[0] == '1') && bwd_plane_applicable(p, dtype)) return BWD_PLANE;
-    return bwd_tile_applicable(p, dtype) ? BWD_TILE : BWD_GENERIC;
+    if (bwd_tile_applicable(p, dtype)) return BWD_TILE;
+    const char* nt = getenv("GSPN_BWD_NO_TWOPASS");   // testing aid: keep the generic kernel reachable on large maps
+    if (!(nt && nt[0] == '1') && bwd_twopass_applicable(p, dtype)) return BWD_TWOPASS;
+    return BWD_GENERIC;
 }
 
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {
@@ -36,6 +39,7 @@ hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s) {
     switch (choose_bwd(p, dtype)) {
         case BWD_TILE: return launch_bwd_tile(p, dtype, s);
         case BWD_PLANE: return launch_bwd_plane(p, dtype, s);
+        case BWD_TWOPASS: return launch_bwd_twopass(p, dtype, s);
         default: return launch_bwd_generic(p, dtype, s);
     }
 }
@@ -53,6 +57,7 @@ const char* bwd_plan_name(const BwdParams& p, int dtype) {
     switch (choose_bwd(p, dtype)) {
         case BWD_TILE: return "tile";
         case BWD_PLANE: return "plane";
+        case BWD_TWOPASS: return "twopass";
         default: return "generic";
     }
 }

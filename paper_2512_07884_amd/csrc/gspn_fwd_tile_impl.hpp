@@ -43,12 +43,17 @@ struct TileArgs {
 // HT: the same pass for a horizontal direction (2 left->right, 3 right->left) whose w, lam, u (and h_save) slots
 // and x are stored transposed, [..][W][H]: lines are image columns, contiguous in memory, and the pass differs
 // from the vertical one only in the roles of H and W and in how it walks the (row-major) output tile
-template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL, bool LOGITS, bool HT = false>
+// BWD: the reverse sweep of the backward pass over the same machinery (see line_update_transposed): the caller passes gy
+// as x, u as lam, lam as u, gx as y and the buffer that receives e as h_save; the wave that walks the rows downwards
+// (REV = false) then works on the parameters of the bottom->top scan and the other way round, and the taps it applies
+// are those of the line it swept before.
+template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL, bool LOGITS, bool HT = false, bool BWD = false>
 __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int b, int c_first, int pk,
                                               int lane, int split) {
+    static_assert(!BWD || (SAVE && !LOCAL && !LOGITS && !HT), "the reverse sweep: global scan, normalised weights, e saved");
     constexpr int NB = V * (int)sizeof(T);
     constexpr int NR = NB / 4;
-    constexpr int d = HT ? (REV ? 3 : 2) : (REV ? 1 : 0);
+    constexpr int d = HT ? (REV ? 3 : 2) : ((REV != BWD) ? 1 : 0);
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
     const int S = HT ? W : H, LL = HT ? H : W;                 // scan steps, positions per line
@@ -115,9 +120,32 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     // (Sec. 3.2): the same at the first line of every stretch, where the carried state counts as 0 too.
     StretchWalk walk;
     if constexpr (LOCAL) walk.init(S, REV, p.kchunk);
+    float wp0[V], wp1[V], wp2[V];            // BWD: taps of the line swept before (none before the first: 0)
+#pragma unroll
+    for (int v = 0; v < V; ++v) { wp0[v] = 0.f; wp1[v] = 0.f; wp2[v] = 0.f; }
     auto step = [&](const Line& cur, bool maybe_start, bool scan_start) {
         if (until_split == 0) lds_barrier();
         --until_split;
+        if constexpr (BWD) {
+            float av[V], uv[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) { av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v); uv[v] = elem<T>(cur.u, v); }
+            line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                // a tap that points outside the line takes nothing, whatever the tensor holds there
+                wp0[v] = (first && v == 0) ? 0.f : elem<T>(cur.w0, v);
+                wp1[v] = elem<T>(cur.w1, v);
+                wp2[v] = (last && v == V - 1) ? 0.f : elem<T>(cur.w2, v);
+                tp[v * tvs] += uv[v] * h[v];
+            }
+            tp += tstep;
+            uint32_t hr[NR];
+            pack<T, V>(h, hr);
+            st_buf<NB>(hb, voff, so_cur, hr);
+            so_cur += sstep;
+            return;
+        }
         if constexpr (LOCAL) {
             maybe_start = true;
             scan_start = walk.start();
@@ -189,7 +217,7 @@ struct HBuf { uint32_t x[V][CS * sizeof(T) / 4], l[V][CS * sizeof(T) / 4], u[V][
 // DB = true: two chunk buffers, the next chunk is loaded while the current one is consumed.
 // DB = false: one buffer (for chunks too large to hold twice); the next chunk is requested as soon
 // as the current one is consumed and other waves of the CU cover the wait.
-template <typename T, int V, int CS, bool REV, bool SAVE, bool DB, bool LOCAL, bool LOGITS>
+template <typename T, int V, int CS, bool REV, bool SAVE, bool DB, bool LOCAL, bool LOGITS, bool BWD = false>
 struct HorizontalPass {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -200,6 +228,7 @@ struct HorizontalPass {
     int pitch;
     bool active, first, last;
     float h[V];
+    float wp0[V], wp1[V], wp2[V];   // BWD: taps of the column swept before
     StretchWalk walk;   // GSPN-local only
     HBuf<T, V, CS> buf0, buf1;
 
@@ -232,7 +261,7 @@ struct HorizontalPass {
         pitch = a.pitch;
         trow = tile + ((pk * a.ph + plc) * H + ic * V) * a.pitch;
 #pragma unroll
-        for (int v = 0; v < V; ++v) h[v] = 0.f;
+        for (int v = 0; v < V; ++v) { h[v] = 0.f; wp0[v] = 0.f; wp1[v] = 0.f; wp2[v] = 0.f; }
         if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
     }
 
@@ -260,6 +289,20 @@ struct HorizontalPass {
         for (int k = 0; k < CS; ++k) {
             const int e = REV ? CS - 1 - k : k;       // element inside the chunk, compile-time
             float av[V], w0[V], w1[V], w2[V];
+            if constexpr (BWD) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) av[v] = elem<T>(s.l[v], e) * elem<T>(s.x[v], e);
+                line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    wp0[v] = (first && v == 0) ? 0.f : elem<T>(s.w0[v], e);
+                    wp1[v] = elem<T>(s.w1[v], e);
+                    wp2[v] = (last && v == V - 1) ? 0.f : elem<T>(s.w2[v], e);
+                    trow[v * pitch + col0 + e] += elem<T>(s.u[v], e) * h[v];
+                    hs[v][e] = h[v];
+                }
+                continue;
+            }
             // first line of the scan (GSPN-local: of a stretch): its weights are never read, the state before it is 0
             bool start = (c == 0) && (k == 0);
             if constexpr (LOCAL) start = walk.start();
@@ -324,7 +367,7 @@ struct HorizontalPass {
 // Because every step is its own barrier interval, the two directions never own the same tile
 // column at the same time and no mid-scan split is needed.
 // ---------------------------------------------------------------------------
-template <typename T, int CS, bool REV, bool SAVE, bool LOCAL, bool LOGITS>
+template <typename T, int CS, bool REV, bool SAVE, bool LOCAL, bool LOGITS, bool BWD = false>
 struct HorizontalSplitPass {
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
@@ -337,6 +380,7 @@ struct HorizontalSplitPass {
     const float* mb_dn; // edge state of the part below (its first row), parity 0
     bool active, edge, top_lane, bot_lane, has_up, has_dn, img_first, img_last;
     float h;
+    float wp0, wp1, wp2;   // BWD: taps of the column swept before
     StretchWalk walk;   // GSPN-local only
     uint32_t bx[NR], bl[NR], bu[NR], b0[NR], b1[NR], b2[NR];
 
@@ -373,7 +417,7 @@ struct HorizontalSplitPass {
         mb_out = task + part * 4 + (bot_lane ? 2 : 0);
         mb_up = task + (has_up ? part - 1 : part) * 4 + 2;
         mb_dn = task + (has_dn ? part + 1 : part) * 4 + 0;
-        h = 0.f;
+        h = 0.f; wp0 = 0.f; wp1 = 0.f; wp2 = 0.f;
         if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
     }
 
@@ -402,6 +446,23 @@ struct HorizontalSplitPass {
             const float pu = mb_up[par ^ 1];
             const float pd = mb_dn[par ^ 1];
             const float yold = trow[col0 + e];               // read early: one LDS round trip per step, not three
+            if constexpr (BWD) {
+                // the edge rows publish the products that cross into the neighbouring part: tap 0 of a part's first row
+                // reads the row above it, tap 2 of its last row the row below
+                const float q0 = wp0 * h, q2 = wp2 * h;
+                float up = from_lane_below(q2), dn = from_lane_above(q0);
+                up = top_lane ? (has_up ? pu : 0.f) : up;
+                dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
+                h = fmaf(wp1, h, elem<T>(bl, e) * elem<T>(bx, e)) + (up + dn);
+                wp0 = img_first ? 0.f : elem<T>(b0, e);
+                wp1 = elem<T>(b1, e);
+                wp2 = img_last ? 0.f : elem<T>(b2, e);
+                if (edge) mb_out[par] = bot_lane ? wp2 * h : wp0 * h;
+                trow[col0 + e] = fmaf(elem<T>(bu, e), h, yold);
+                hs[e] = h;
+                lds_barrier();
+                continue;
+            }
             bool start = (c == 0) && (k == 0);
             if constexpr (LOCAL) start = walk.start();
             float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
@@ -439,9 +500,12 @@ struct HorizontalSplitPass {
     }
 };
 
-template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL, bool LOGITS>
+// BWD: the first pass of the backward scan for maps beyond the backward kernels' reach (see vertical_pass): the wave
+// that sweeps in the orientation of scan direction d works on the parameters of the opposite direction d ^ 1
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL, bool LOGITS, bool BWD = false>
 __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
     static_assert(LOCAL || !LOGITS, "logits run on the local instantiations (a global scan is one stretch)");
+    static_assert(!BWD || VH != 3, "the reverse sweep takes the standard layout");
     extern __shared__ float tile[];
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W;
@@ -468,9 +532,10 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
         if (nd > 0 && wave < packs * nd) {
             const int pk = wave / nd;
             const int d = (nd == 2) ? (wave - pk * nd) : ((p.mask & 1) ? 0 : 1);
-            const int split = nd == 2 ? (d == 0 ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
-            if (d == 0) vertical_pass<T, VV, PF, false, SAVE, LOCAL, LOGITS>(a, tile, b, c_first, pk, lane, split);
-            else vertical_pass<T, VV, PF, true, SAVE, LOCAL, LOGITS>(a, tile, b, c_first, pk, lane, split);
+            const bool down = (d == 0) != BWD;                 // this wave walks the rows from the top
+            const int split = nd == 2 ? (down ? (H + 1) / 2 : H - (H + 1) / 2) : -1;
+            if (down) vertical_pass<T, VV, PF, false, SAVE, LOCAL, LOGITS, false, BWD>(a, tile, b, c_first, pk, lane, split);
+            else vertical_pass<T, VV, PF, true, SAVE, LOCAL, LOGITS, false, BWD>(a, tile, b, c_first, pk, lane, split);
         } else if (nd == 2) {
             lds_barrier();
         }
@@ -510,15 +575,15 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
             float* mailbox = tile + tile_floats;
             if (nd == 0) {
                 lds_barrier();
-            } else if (work && dd == 2) {
-                HorizontalSplitPass<T, CS, false, SAVE, LOCAL, LOGITS> hp;
-                hp.init(a, tile, mailbox, 2, dslot, b, c_first, kc, part, lane);
+            } else if (work && (dd == 2) != BWD) {             // this wave walks the columns from the left
+                HorizontalSplitPass<T, CS, false, SAVE, LOCAL, LOGITS, BWD> hp;
+                hp.init(a, tile, mailbox, dd, dslot, b, c_first, kc, part, lane);
                 hp.prologue();
                 lds_barrier();
                 hp.run();
             } else if (work) {
-                HorizontalSplitPass<T, CS, true, SAVE, LOCAL, LOGITS> hp;
-                hp.init(a, tile, mailbox, 3, dslot, b, c_first, kc, part, lane);
+                HorizontalSplitPass<T, CS, true, SAVE, LOCAL, LOGITS, BWD> hp;
+                hp.init(a, tile, mailbox, dd, dslot, b, c_first, kc, part, lane);
                 hp.prologue();
                 lds_barrier();
                 hp.run();
@@ -528,9 +593,9 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
             }
         } else if (nd == 0) {
             lds_barrier();
-        } else if (d == 2) {
-            HorizontalPass<T, VH, CS, false, SAVE, DB, LOCAL, LOGITS> hp;
-            if (busy) { hp.init(a, tile, 2, b, c_first, pk, lane); hp.prologue(); }
+        } else if ((d == 2) != BWD) {                       // this wave walks the columns from the left
+            HorizontalPass<T, VH, CS, false, SAVE, DB, LOCAL, LOGITS, BWD> hp;
+            if (busy) { hp.init(a, tile, d, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();                                  // vertical phase complete (first loads already in flight)
             if (busy) hp.run(0, nd == 2 ? half_lr : nchunks);
             if (nd == 2) {
@@ -538,8 +603,8 @@ __global__ void __launch_bounds__(64 * MAXW) fwd_tile_kernel(TileArgs a) {
                 if (busy) hp.run(half_lr, nchunks);
             }
         } else {
-            HorizontalPass<T, VH, CS, true, SAVE, DB, LOCAL, LOGITS> hp;
-            if (busy) { hp.init(a, tile, 3, b, c_first, pk, lane); hp.prologue(); }
+            HorizontalPass<T, VH, CS, true, SAVE, DB, LOCAL, LOGITS, BWD> hp;
+            if (busy) { hp.init(a, tile, d, b, c_first, pk, lane); hp.prologue(); }
             lds_barrier();
             if (busy) hp.run(0, nd == 2 ? half_rl : nchunks);
             if (nd == 2) {
@@ -652,10 +717,10 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
 }
 
 
-template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL, bool LOGITS>
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool SAVE, int MAXW, bool LOCAL, bool LOGITS, bool BWD = false>
 static hipError_t launch_one_l(const TileArgs& a, const TilePlan& t, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * t.nwaves);
-    auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW, LOCAL, LOGITS>;
+    auto k = fwd_tile_kernel<T, VV, VH, CS, DB, PF, SAVE, MAXW, LOCAL, LOGITS, BWD>;
     hipError_t e = allow_dynamic_lds((const void*)k, LDS_BUDGET);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
@@ -700,6 +765,28 @@ static hipError_t launch_fwd_tile_part(const FwdParams& p, hipStream_t s) {
     if (t.hv == H_ROW) return launch_cfg<T, 2, 1, 112 / ES, false, TILE_PF, LOC>(a, t, save, s);
     if (t.hv == H_SECTOR) return launch_cfg<T, 2, 2, 64 / ES, false, TILE_PF, LOC>(a, t, save, s);
     return launch_cfg<T, 2, 2, 16 / ES, true, TILE_PF, LOC>(a, t, save, s);
+}
+
+// First pass of the two-pass backward scan (gspn_bwd_twopass.hip): p holds gy as x, u as lam, lam as u, gx as y and
+// the buffer that receives e as hs.  One translation unit per storage type.
+template <typename T, int VV, int VH, int CS, bool DB, int PF>
+static hipError_t launch_cfg_reverse(const TileArgs& a, const TilePlan& t, hipStream_t s) {
+    if (t.nwaves <= 4) return launch_one_l<T, VV, VH, CS, DB, PF, true, 4, false, false, true>(a, t, s);
+    return launch_one_l<T, VV, VH, CS, DB, PF, true, 8, false, false, true>(a, t, s);
+}
+
+template <typename T>
+static hipError_t launch_reverse_sweep_part(const FwdParams& p, hipStream_t s) {
+    constexpr int ES = (int)sizeof(T);
+    const TilePlan t = plan_tile(p, ES == 4 ? 0 : 1);
+    if (!t.ok || t.hv == H_TRANSPOSED || !p.hs || p.kchunk > 0 || p.logits) return hipErrorInvalidValue;
+    TileArgs a;
+    a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.lplh = t.lplh; a.ph = t.ph;
+    a.nwaves = t.nwaves; a.parts = t.parts;
+    if (t.hv == H_SPLIT) return launch_cfg_reverse<T, 2, 0, 128 / ES, false, TILE_PF>(a, t, s);
+    if (t.hv == H_ROW) return launch_cfg_reverse<T, 2, 1, 112 / ES, false, TILE_PF>(a, t, s);
+    if (t.hv == H_SECTOR) return launch_cfg_reverse<T, 2, 2, 64 / ES, false, TILE_PF>(a, t, s);
+    return launch_cfg_reverse<T, 2, 2, 16 / ES, true, TILE_PF>(a, t, s);
 }
 
 }  // namespace gspn

@@ -133,4 +133,28 @@ __device__ __forceinline__ void line_update(float (&h)[V], const float (&a)[V], 
     for (int v = 0; v < V; ++v) h[v] = hn[v];
 }
 
+// The same for the reverse sweep of the backward pass, e_t = a_t + T_{t+1}^T e_{t+1} (chain rule on Eq. 1): every position
+// multiplies its own state by the three taps of the line swept before (`wp*`, the line after it in scan order) and hands
+// the products to the positions those taps read from.  h holds e of that line on entry and of this line on exit.
+template <int V>
+__device__ __forceinline__ void line_update_transposed(float (&h)[V], const float (&a)[V], const float (&wp0)[V],
+                                                       const float (&wp1)[V], const float (&wp2)[V], bool first, bool last) {
+    float q0[V], q2[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) { q0[v] = wp0[v] * h[v]; q2[v] = wp2[v] * h[v]; }
+    float lin = from_lane_below(q2[V - 1]);      // tap 2 of position j-1 reads position j
+    float rin = from_lane_above(q0[0]);          // tap 0 of position j+1 reads position j
+    lin = first ? 0.f : lin;
+    rin = last ? 0.f : rin;
+    float hn[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float l = v == 0 ? lin : q2[v - 1];
+        const float r = v == V - 1 ? rin : q0[v + 1];
+        hn[v] = fmaf(wp1[v], h[v], a[v]) + (l + r);
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) h[v] = hn[v];
+}
+
 }  // namespace gspn

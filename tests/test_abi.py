@@ -135,7 +135,7 @@ def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
         for dt in (0, 1):
             assert fwd(64, C, HW, HW, 8, 15, dt, 0, 1) == "plane", (C, HW, dt)
             assert bwd(64, C, HW, HW, 8, 15, dt, 0) == "plane", (C, HW, dt)
-    assert bwd(2, 1024, 128, 128, 16, 15, 1, 0) == "generic"                 # no fast backward beyond 64 lines
+    assert bwd(2, 1024, 128, 128, 16, 15, 1, 0) == "twopass"                 # beyond 64 lines: reverse sweep on the forward tile kernels + channel sum
     monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
     assert fwd(64, 96, 56, 56, 8, 15, 1, 0, 0) == "generic" and bwd(32, 192, 28, 28, 4, 15, 0, 0) == "generic"
 

@@ -1,0 +1,54 @@
+"""GPU parity of the two-pass backward scan (maps beyond the single-launch backward kernels) against the fp64 oracle.
+
+Pass 1 runs the reverse sweep on the forward tile kernels (all four of their horizontal variants are covered here),
+pass 2 sums gw over the channels of a group; the shapes below are ones the backward plane and tile kernels refuse."""
+import numpy as np
+import pytest
+
+from gpu_util import to_device
+from paper_2512_07884_amd import workloads as WL
+from test_gpu_bwd import check_bwd
+
+pytestmark = pytest.mark.gpu
+
+# B, C, H, W, G, dtype: rows split over waves (2 and 3 parts), 64 B bursts, 16 B bursts, 112 B bursts with a group too
+# large for one workgroup; per-channel and shared weights; several images
+SHAPES = [(1, 4, 128, 128, 2, "bf16"), (2, 4, 128, 128, 4, "bf16"), (1, 2, 128, 64, 1, "f32"), (1, 3, 192, 128, 3, "bf16"),
+          (1, 4, 96, 96, 2, "bf16"), (1, 2, 100, 48, 1, "f32"), (1, 4, 96, 72, 2, "bf16"), (1, 4, 70, 36, 2, "f32"),
+          (1, 32, 56, 56, 1, "bf16"), (1, 32, 56, 56, 1, "f32"), (2, 6, 66, 40, 3, "f32")]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_two_pass_backward_shapes(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, int(dtype == "bf16"), 0) == "twopass", shape
+    check_bwd(WL.ScanConfig("twopass", B, C, H, W, Gr, dtype, 15, 1.0, 71))
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 5, 10, 7, 12])
+@pytest.mark.parametrize("shape", [(1, 4, 128, 64, 2, "f32"), (1, 4, 96, 72, 2, "bf16")], ids=lambda s: "x".join(map(str, s)))
+def test_two_pass_backward_direction_masks(mask, shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, mask, int(dtype == "bf16"), 0) == "twopass"
+    check_bwd(WL.ScanConfig("twopassmask", B, C, H, W, Gr, dtype, mask, 1.0, 73))
+
+
+def test_two_pass_backward_is_bitwise_repeatable():
+    import torch
+    import paper_2512_07884_amd as G
+    cfg = WL.ScanConfig("twopassrep", 1, 8, 128, 128, 2, "bf16", 15, 1.0, 79)
+    inp = WL.make_inputs(cfg)
+    dev = {k: to_device(v, "bf16") for k, v in inp.items()}
+    hs = torch.empty_like(dev["lam"]); y = torch.empty_like(dev["x"])
+    G.gspn_scan_fwd(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, G=cfg.G)
+    outs = []
+    for rep in range(3):
+        gx = torch.full_like(dev["x"], float("nan")); gw = torch.full_like(dev["w"], float("nan"))
+        gl = torch.full_like(dev["lam"], float("nan")); gu = torch.full_like(dev["lam"], float("nan"))
+        G.gspn_scan_bwd(dev["gy"], dev["x"], dev["w"], dev["lam"], dev["u"], hs, gx, gw, gl, gu, G=cfg.G)
+        torch.cuda.synchronize()
+        outs.append([t.view(torch.int16).cpu().numpy().copy() for t in (gx, gw, gl, gu)])
+    for k in range(4):
+        assert np.array_equal(outs[0][k], outs[1][k]) and np.array_equal(outs[0][k], outs[2][k])

@@ -93,6 +93,8 @@ int gspn_scan_fwd(const void* x, const void* w, const void* lam, const void* u,
  *   gy, x in  [B,C,H,W];  w, lam, u as in the forward call
  *   h_save in [4][B,C,H,W] as written by gspn_scan_fwd (required)
  *   gx out [B,C,H,W];  gw out [4][B,G,3,H,W];  glam, gu out [4][B,C,H,W]
+ * The outputs must not alias each other or an input: on large maps glam holds e
+ * between the two passes of the call.
  */
 int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam, const void* u,
                   const void* h_save,
@@ -174,13 +176,17 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 
 /* Name of the kernel family the forward / backward call would dispatch to for
  * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
- * merged output fits in LDS), "stream" (larger maps, forward only), "generic" (any
- * shape); static string, never NULL.  Host only.
+ * merged output fits in LDS), "stream" (larger maps, forward only), "twopass" (backward of
+ * the global scan on maps the forward tile kernels take and the single-launch backward kernels
+ * do not: the reverse sweep per channel, then the sum over each group's channels; in bf16
+ * storage e passes through storage precision between the two), "generic" (any shape);
+ * static string, never NULL.  Host only.
  *
  * Environment variables read at every call, for tests and tuning (results are the
  * same whichever kernel runs, up to the rounding of the storage type):
  *   GSPN_FORCE_GENERIC=1   always the generic kernels
  *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
+ *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward
  *   GSPN_TILE_K=<n>, GSPN_TILE_HV=<0..3>   forward tile kernel: channels per
  *       workgroup / horizontal-phase variant (ignored when they do not fit) */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);

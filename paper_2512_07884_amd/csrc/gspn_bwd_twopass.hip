@@ -5,9 +5,9 @@
 // (Sec. 3.2) with the shared weights of Sec. 4.2, split where the sum over the channels of a group comes in:
 //
 //   pass 1, per channel: e_t = u_t*gy_t + T_{t+1}^T e_{t+1} is the forward recurrence run against the scan order with the
-//           tridiagonal transposed, and gx = sum_d lam_d*e_d is its merged output -- so it runs on the forward tile kernels
-//           (reverse-sweep instantiations: gy as x, u as lam, lam as u, gx as y), which also save e per direction, into
-//           the buffer of glam;
+//           tridiagonal transposed, and gx = sum_d lam_d*e_d is its merged output -- so it runs on the forward tile kernels,
+//           or on the forward stream kernel for maps beyond the LDS tile (reverse-sweep instantiations: gy as x, u as lam,
+//           lam as u, gx as y), which also save e per direction, into the buffer of glam;
 //   pass 2, per (direction, image, group) and pixel: gw[k] = sum over the group's channels of e[j] * h_{t-1}[j+k-1] has no
 //           recurrence left: one thread per few adjacent pixels walks the channels, accumulates the three taps in fp32
 //           registers, and on the way turns the saved e into glam = x*e in place and writes gu = gy*h.
@@ -21,6 +21,8 @@ namespace gspn {
 
 hipError_t launch_reverse_sweep_f32(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_bf16(const FwdParams& p, hipStream_t s);
+hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s);    // maps beyond the LDS tile
+bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype);
 
 namespace {
 
@@ -175,13 +177,16 @@ hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
 bool bwd_twopass_applicable(const BwdParams& p, int dtype) {
     if (p.kchunk > 0 || p.logits || p.W % 2) return false;
     if ((size_t)p.B * p.G * ((size_t)p.H * p.W / 2) * 4 / 256 > 0x7fffffffull) return false;
-    return fwd_tile_applicable(reverse_sweep_params(p), dtype);
+    const FwdParams f = reverse_sweep_params(p);
+    return fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype);
 }
 
 hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     if (!bwd_twopass_applicable(p, dtype)) return hipErrorInvalidValue;
     const FwdParams f = reverse_sweep_params(p);
-    hipError_t e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);
+    hipError_t e;
+    if (fwd_tile_applicable(f, dtype)) e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);
+    else e = launch_reverse_sweep_stream(f, dtype, s);
     if (e != hipSuccess) return e;
     int ndirs = 0;
     for (int d = 0; d < 4; ++d) ndirs += (p.mask >> d) & 1u;

@@ -31,20 +31,27 @@ struct StreamArgs {
 // ---------------------------------------------------------------------------
 // LOCAL: GSPN-local (Sec. 3.2), on instantiations of its own so that the global scan carries none of it
 // LOGITS (with LOCAL): w holds raw logits, normalised as they are consumed (softmax3)
-template <typename T, int V, int PF, bool REV, bool LOCAL, bool LOGITS>
+// BWD: the reverse sweep of the backward pass (first pass of the two-pass backward scan): the caller passes gy as x, u as
+// lam, lam as u, gx as y and the buffer that receives e as hs; the wave that walks the rows downwards then works on the
+// parameters of the bottom->top scan and the other way round, applies the taps of the line it swept before
+// (line_update_transposed) and stores its state per line
+// SAVE: the state of every line is stored per direction (h_save of the forward call; e of the reverse sweep)
+template <typename T, int V, int PF, bool REV, bool LOCAL, bool LOGITS, bool BWD = false, bool SAVE = BWD>
 struct VStream {
+    static_assert(!BWD || (!LOCAL && !LOGITS && SAVE), "the reverse sweep: global scan, normalised weights, state saved");
     static constexpr int NB = V * (int)sizeof(T);
     static constexpr int NR = NB / 4;
     struct Line { uint32_t x[NR], l[NR], u[NR], w0[NR], w1[NR], w2[NR], y[NR]; };
-    rsrc_t xb, lb, ub, w0b, w1b, w2b, yb;
+    rsrc_t xb, lb, ub, w0b, w1b, w2b, yb, hb;
     uint32_t voff;
     int H, row_bytes;
     bool first, last;
     float h[V];
+    float wp0[BWD ? V : 1], wp1[BWD ? V : 1], wp2[BWD ? V : 1];   // BWD: taps of the line swept before
     StretchWalk walk;   // GSPN-local only
 
     __device__ __forceinline__ void init(const FwdParams& p, int b, int c, int lane) {
-        constexpr int d = REV ? 1 : 0;
+        constexpr int d = (REV != BWD) ? 1 : 0;
         H = p.H;
         if constexpr (LOCAL) walk.init(p.H, REV, p.kchunk);
         const int W = p.W, HW = H * W;
@@ -63,8 +70,13 @@ struct VStream {
         ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
         w0b = make_rsrc(wbase); w1b = make_rsrc(wbase + plane_bytes); w2b = make_rsrc(wbase + 2 * plane_bytes);
         yb = make_rsrc((char*)p.y + plane0 * sizeof(T));
+        hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * sizeof(T) : (char*)p.y);
 #pragma unroll
         for (int v = 0; v < V; ++v) h[v] = 0.f;
+        if constexpr (BWD) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) { wp0[v] = 0.f; wp1[v] = 0.f; wp2[v] = 0.f; }
+        }
     }
 
     __device__ __forceinline__ int row_off(int t) const { return (REV ? H - 1 - t : t) * row_bytes; }
@@ -93,6 +105,27 @@ struct VStream {
                 if (t < t_end) {
                     const Line& cur = slot[k];
                     float av[V], w0[V], w1[V], w2[V], yv[V];
+                    if constexpr (BWD) {
+#pragma unroll
+                        for (int v = 0; v < V; ++v) av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
+                        line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
+#pragma unroll
+                        for (int v = 0; v < V; ++v) {
+                            // a tap that points outside the line takes nothing, whatever the tensor holds there
+                            wp0[v] = (first && v == 0) ? 0.f : elem<T>(cur.w0, v);
+                            wp1[v] = elem<T>(cur.w1, v);
+                            wp2[v] = (last && v == V - 1) ? 0.f : elem<T>(cur.w2, v);
+                            yv[v] = elem<T>(cur.u, v) * h[v];
+                            if constexpr (RMW) yv[v] += elem<T>(cur.y, v);
+                        }
+                        uint32_t o[NR];
+                        pack<T, V>(yv, o);
+                        st_buf<NB>(yb, voff, row_off(t), o);
+                        pack<T, V>(h, o);
+                        st_buf<NB>(hb, voff, row_off(t), o);
+                        issue(slot[k], t + PF);
+                        continue;
+                    }
                     // scan step 0 (only ever in ring slot 0): its weights are never used (the stored values may be
                     // anything); GSPN-local: the same for the first line of every stretch, any slot
                     bool start = t == 0;
@@ -114,6 +147,10 @@ struct VStream {
                     uint32_t o[NR];
                     pack<T, V>(yv, o);
                     st_buf<NB>(yb, voff, row_off(t), o);
+                    if constexpr (SAVE) {
+                        pack<T, V>(h, o);
+                        st_buf<NB>(hb, voff, row_off(t), o);
+                    }
                     issue(slot[k], t + PF);
                 }
             }
@@ -124,11 +161,13 @@ struct VStream {
 // ---------------------------------------------------------------------------
 // horizontal direction, the rows of the image split over `parts` waves, one row per lane
 // ---------------------------------------------------------------------------
-template <typename T, int CS, bool REV, bool LOCAL, bool LOGITS>
+template <typename T, int CS, bool REV, bool LOCAL, bool LOGITS, bool BWD = false, bool SAVE = BWD>
 struct HStream {
+    static_assert(!BWD || (!LOCAL && !LOGITS && SAVE), "the reverse sweep: global scan, normalised weights, state saved");
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
-    rsrc_t xb, lb, ub, w0b, w1b, w2b, yb;
+    rsrc_t xb, lb, ub, w0b, w1b, w2b, yb, hb;
+    float wp0, wp1, wp2;   // BWD: taps of the column swept before
     uint32_t voff;
     int nchunks;
     float* mb_out;
@@ -140,7 +179,7 @@ struct HStream {
     uint32_t bx[NR], bl[NR], bu[NR], b0[NR], b1[NR], b2[NR], by[NR];
 
     __device__ __forceinline__ void init(const FwdParams& p, float* mailbox, int parts, int b, int c, int part, int lane) {
-        constexpr int d = REV ? 3 : 2;
+        constexpr int d = (REV != BWD) ? 3 : 2;
         const int H = p.H, W = p.W, HW = H * W;
         const int row = part * 64 + lane;
         const int g = c / p.cpg;
@@ -160,6 +199,8 @@ struct HStream {
         ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
         w0b = make_rsrc(wbase); w1b = make_rsrc(wbase + plane_bytes); w2b = make_rsrc(wbase + 2 * plane_bytes);
         yb = make_rsrc((char*)p.y + plane0 * sizeof(T));
+        hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * sizeof(T) : (char*)p.y);
+        wp0 = 0.f; wp1 = 0.f; wp2 = 0.f;
         nchunks = W / CS;
         // mailbox: [part][side: 0 first row, 1 last row][parity]
         mb_out = mailbox + part * 4 + (bot_lane ? 2 : 0);
@@ -187,12 +228,41 @@ struct HStream {
     __device__ __forceinline__ void compute(int c) {
         // the chunk's outputs replace its y words in place, element by element (no second array)
         float ypair = 0.f;                                   // bf16: first element of the pair being assembled
+        float epair = 0.f;                                   // SAVE: the same for the saved state
 #pragma unroll
         for (int k = 0; k < CS; ++k) {
             const int e = REV ? CS - 1 - k : k;
             const int par = k & 1;                           // CS is even: parity of the scan step
             const float pu = mb_up[par ^ 1];
             const float pd = mb_dn[par ^ 1];
+            if constexpr (BWD) {
+                // the edge rows publish the products that cross into the neighbouring part: tap 0 of a part's first row
+                // reads the row above it, tap 2 of its last row the row below
+                const float q0 = wp0 * h, q2 = wp2 * h;
+                float up = from_lane_below(q2), dn = from_lane_above(q0);
+                up = top_lane ? (has_up ? pu : 0.f) : up;
+                dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
+                h = fmaf(wp1, h, elem<T>(bl, e) * elem<T>(bx, e)) + (up + dn);
+                wp0 = img_first ? 0.f : elem<T>(b0, e);
+                wp1 = elem<T>(b1, e);
+                wp2 = img_last ? 0.f : elem<T>(b2, e);
+                float yv = elem<T>(bu, e) * h;
+                if constexpr (RMW) yv += elem<T>(by, e);
+                // y replaces the chunk's y words and e its x words (= gy, consumed), element by element
+                if constexpr (sizeof(T) == 4) {
+                    by[e] = __float_as_uint(yv);
+                    bx[e] = __float_as_uint(h);
+                } else {
+                    if ((k & 1) == 0) { ypair = yv; epair = h; }
+                    else {
+                        by[e >> 1] = pack_bf16x2((e & 1) ? ypair : yv, (e & 1) ? yv : ypair);
+                        bx[e >> 1] = pack_bf16x2((e & 1) ? epair : h, (e & 1) ? h : epair);
+                    }
+                }
+                if (edge) mb_out[par] = bot_lane ? wp2 * h : wp0 * h;
+                lds_barrier();
+                continue;
+            }
             bool start = (c == 0) && (k == 0);               // scan step 0: its weights are never used
             if constexpr (LOCAL) start = walk.start();       // ... nor those of a stretch's first line
             float w0 = elem<T>(b0, e), w1 = elem<T>(b1, e), w2 = elem<T>(b2, e);
@@ -209,18 +279,21 @@ struct HStream {
             if constexpr (RMW) yv += elem<T>(by, e);
             if constexpr (sizeof(T) == 4) {
                 by[e] = __float_as_uint(yv);
+                if constexpr (SAVE) bx[e] = __float_as_uint(h);      // x of this element is consumed: its word takes h
             } else {
                 // elements e and e^1 share a word; the pair is complete on every second step
-                if ((k & 1) == 0) ypair = yv;
+                if ((k & 1) == 0) { ypair = yv; epair = h; }
                 else {
                     const float lo = (e & 1) ? ypair : yv, hi = (e & 1) ? yv : ypair;
                     by[e >> 1] = pack_bf16x2(lo, hi);
+                    if constexpr (SAVE) bx[e >> 1] = pack_bf16x2((e & 1) ? epair : h, (e & 1) ? h : epair);
                 }
             }
             if (edge) mb_out[par] = h;
             lds_barrier();
         }
         st_buf<NB>(yb, voff, chunk_col(c) * (int)sizeof(T), by);
+        if constexpr (SAVE) st_buf<NB>(hb, voff, chunk_col(c) * (int)sizeof(T), bx);
     }
 
     template <bool RMW>
@@ -233,7 +306,9 @@ struct HStream {
     }
 };
 
-template <typename T, int V, int CS, int PF, bool LOCAL, bool LOGITS>
+// BWD: first pass of the two-pass backward scan (see VStream); the wave that sweeps in the orientation of scan direction d
+// works on the parameters of the opposite direction d ^ 1
+template <typename T, int V, int CS, int PF, bool LOCAL, bool LOGITS, bool BWD = false, bool SAVE = BWD>
 __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
     static_assert(LOCAL || !LOGITS, "logits run on the local instantiations (a global scan is one stretch)");
     __shared__ float mailbox[8 * 4];
@@ -252,12 +327,12 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
         if (nd == 2) {
             const int split = (H + 1) / 2;          // top->bottom wave: rows [0, split) first; bottom->top: rows [split, H)
             if (wave == 0) {
-                VStream<T, V, PF, false, LOCAL, LOGITS> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, false, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, c, lane);
                 v.template run<false>(0, split);
                 __syncthreads();
                 v.template run<true>(split, H);
             } else if (wave == 1) {
-                VStream<T, V, PF, true, LOCAL, LOGITS> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, true, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, c, lane);
                 v.template run<false>(0, H - split);
                 __syncthreads();
                 v.template run<true>(H - split, H);
@@ -267,8 +342,8 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
             wrote = true;
         } else if (nd == 1) {
             if (wave == 0) {
-                if (has_tb) { VStream<T, V, PF, false, LOCAL, LOGITS> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
-                else        { VStream<T, V, PF, true, LOCAL, LOGITS> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
+                if ((has_tb != 0) != BWD) { VStream<T, V, PF, false, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
+                else                      { VStream<T, V, PF, true, LOCAL, LOGITS, BWD, SAVE> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
             }
             wrote = true;
         }
@@ -280,11 +355,11 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
         if (threadIdx.x < 32) mailbox[threadIdx.x] = 0.f;
         __syncthreads();                        // y of the previous phase visible, mailbox cleared
         if (wave < a.parts) {
-            if (dsel == 0) {
-                HStream<T, CS, false, LOCAL, LOGITS> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+            if ((dsel == 0) != BWD) {                    // columns walked from the left
+                HStream<T, CS, false, LOCAL, LOGITS, BWD, SAVE> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             } else {
-                HStream<T, CS, true, LOCAL, LOGITS> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, true, LOCAL, LOGITS, BWD, SAVE> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             }
         } else {
@@ -299,9 +374,10 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
 // ---------------------------------------------------------------------------
 struct StreamPlan { bool ok; int v, parts, nwaves; };
 
-static StreamPlan plan_stream(const FwdParams& p, int dtype) {
+static StreamPlan plan_stream(const FwdParams& p, int dtype, bool reverse = false) {
     StreamPlan t = {};
-    if (p.hs) return t;                                    // hidden states are not saved on this path
+    if (p.hs && (p.kchunk > 0 || p.logits)) return t;      // hidden states are saved by the global scan only
+    if (reverse && (p.kchunk > 0 || p.logits)) return t;
     if (p.xt) return t;                                    // transposed-horizontal layout: tile and generic kernels
     if (p.W % 64 || p.H % 64) return t;
     const int v = p.W / 64;
@@ -318,14 +394,39 @@ static StreamPlan plan_stream(const FwdParams& p, int dtype) {
 }
 
 bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok; }
+bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype, true).ok; }
 
 template <typename T, int V, int CS, int PF>
 static hipError_t launch_stream(const StreamArgs& a, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * a.p.C)), block(64 * a.nwaves);
     if (a.p.logits) hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, true, true>), grid, block, 0, s, a);
     else if (a.p.kchunk > 0) hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, true, false>), grid, block, 0, s, a);
+    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, false, false, false, true>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, false, false>), grid, block, 0, s, a);
     return hipGetLastError();
+}
+
+template <typename T, int V, int CS, int PF>
+static hipError_t launch_stream_reverse(const StreamArgs& a, hipStream_t s) {
+    const dim3 grid((unsigned)((size_t)a.p.B * a.p.C)), block(64 * a.nwaves);
+    hipLaunchKernelGGL((fwd_stream_kernel<T, V, CS, PF, false, false, true>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+// first pass of the two-pass backward scan on maps beyond the tile kernels: p holds gy as x, u as lam, lam as u, gx as y
+// and the buffer that receives e as hs
+hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s) {
+    const StreamPlan t = plan_stream(p, dtype, true);
+    if (!t.ok || !p.hs) return hipErrorInvalidValue;
+    StreamArgs a;
+    a.p = p; a.parts = t.parts; a.nwaves = t.nwaves;
+    if (dtype == 1) {
+        if (t.v == 4) return launch_stream_reverse<bf16_t, 4, 64, 4>(a, s);
+        if (t.v == 8) return launch_stream_reverse<bf16_t, 8, 64, 4>(a, s);
+        return launch_stream_reverse<bf16_t, 16, 64, 2>(a, s);
+    }
+    if (t.v == 4) return launch_stream_reverse<float, 4, 32, 4>(a, s);
+    return launch_stream_reverse<float, 8, 32, 2>(a, s);
 }
 
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s) {

@@ -1,7 +1,8 @@
 """GPU parity of the two-pass backward scan (maps beyond the single-launch backward kernels) against the fp64 oracle.
 
-Pass 1 runs the reverse sweep on the forward tile kernels (all four of their horizontal variants are covered here),
-pass 2 sums gw over the channels of a group; the shapes below are ones the backward plane and tile kernels refuse."""
+Pass 1 runs the reverse sweep on the forward tile kernels (all four of their horizontal variants are covered here) or,
+for maps beyond the LDS tile, on the forward stream kernel; pass 2 sums gw over the channels of a group; the shapes
+below are ones the backward plane and tile kernels refuse."""
 import numpy as np
 import pytest
 
@@ -15,7 +16,10 @@ pytestmark = pytest.mark.gpu
 # large for one workgroup; per-channel and shared weights; several images
 SHAPES = [(1, 4, 128, 128, 2, "bf16"), (2, 4, 128, 128, 4, "bf16"), (1, 2, 128, 64, 1, "f32"), (1, 3, 192, 128, 3, "bf16"),
           (1, 4, 96, 96, 2, "bf16"), (1, 2, 100, 48, 1, "f32"), (1, 4, 96, 72, 2, "bf16"), (1, 4, 70, 36, 2, "f32"),
-          (1, 32, 56, 56, 1, "bf16"), (1, 32, 56, 56, 1, "f32"), (2, 6, 66, 40, 3, "f32")]
+          (1, 32, 56, 56, 1, "bf16"), (1, 32, 56, 56, 1, "f32"), (2, 6, 66, 40, 3, "f32"),
+          # maps beyond the LDS tile: 4 / 8 / 16 positions per lane in the vertical passes, 1 to 5 waves per column
+          (1, 2, 256, 256, 1, "bf16"), (1, 2, 128, 256, 2, "f32"), (1, 2, 64, 1024, 1, "bf16"), (2, 2, 320, 256, 2, "bf16"),
+          (1, 2, 192, 512, 1, "f32"), (1, 4, 128, 512, 2, "bf16")]
 
 
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -27,7 +31,8 @@ def test_two_pass_backward_shapes(shape):
 
 
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 5, 10, 7, 12])
-@pytest.mark.parametrize("shape", [(1, 4, 128, 64, 2, "f32"), (1, 4, 96, 72, 2, "bf16")], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("shape", [(1, 4, 128, 64, 2, "f32"), (1, 4, 96, 72, 2, "bf16"), (1, 2, 128, 256, 1, "bf16")],
+                         ids=lambda s: "x".join(map(str, s)))
 def test_two_pass_backward_direction_masks(mask, shape):
     import paper_2512_07884_amd as G
     B, C, H, W, Gr, dtype = shape
@@ -52,3 +57,13 @@ def test_two_pass_backward_is_bitwise_repeatable():
         outs.append([t.view(torch.int16).cpu().numpy().copy() for t in (gx, gw, gl, gu)])
     for k in range(4):
         assert np.array_equal(outs[0][k], outs[1][k]) and np.array_equal(outs[0][k], outs[2][k])
+
+
+def test_two_pass_backward_on_512x512_planes():
+    """The high-resolution shape (512x512, 32 channels per group, bf16) with fewer channels: the same kernels and the same
+    work per workgroup as bench.py's train512 workload."""
+    import paper_2512_07884_amd as G
+    cfg = WL.shrink(WL.CONFIGS["train512"], C=64, G=2)
+    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, 1, 0, True) == "stream"
+    assert G.gspn_bwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, 1, 0) == "twopass"
+    check_bwd(cfg)

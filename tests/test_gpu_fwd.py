@@ -99,7 +99,7 @@ def test_kernel_families_by_shape():
     assert G.gspn_fwd_plan(1, 512, 512, 512, 16, 15, 1, 0, False) == "stream"
     assert G.gspn_fwd_plan(1, 512, 256, 1024, 16, 15, 1, 0, False) == "stream"
     assert G.gspn_fwd_plan(1, 2, 256, 256, 1, 15, 0, 0, False) == "stream"
-    assert G.gspn_fwd_plan(1, 2, 256, 256, 1, 15, 0, 0, True) == "generic"      # saving h is not on the stream path
+    assert G.gspn_fwd_plan(1, 2, 256, 256, 1, 15, 0, 0, True) == "stream"       # ... with h_save too (global scan)
     assert G.gspn_fwd_plan(1, 2, 130, 67, 1, 15, 0, 0, False) == "generic"
 
 

@@ -4,7 +4,8 @@
 // neighbour exchange, and the merged output y = sum_d u_d*h_d (Eq. 2 + sum merge of the four
 // passes of Sec. 3.2) accumulated in place in global memory, direction after direction, by the
 // workgroup that owns the plane (fixed order, no atomics, no zero fill).  In bf16 storage the
-// running sum is rounded once per direction.
+// running sum is rounded once per direction.  The global scan can save its hidden states (h_save), and
+// the same kernel runs the reverse sweep of the two-pass backward scan (template flags SAVE, BWD).
 //
 //  * Vertical directions: a line is an image row of W = 64*V positions held by ONE wave (V
 //    contiguous positions per lane, 16..32 B vector loads), PF lines prefetched in registers.  The

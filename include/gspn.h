@@ -176,8 +176,8 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 
 /* Name of the kernel family the forward / backward call would dispatch to for
  * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
- * merged output fits in LDS), "stream" (larger maps, forward only), "twopass" (backward of
- * the global scan on maps the forward tile or stream kernels take and the single-launch backward
+ * merged output fits in LDS), "stream" (larger maps, forward only), "twopass" (backward
+ * on maps the forward tile or stream kernels take and the single-launch backward
  * kernels do not: the reverse sweep per channel, then the sum over each group's channels; in bf16
  * storage e passes through storage precision between the two), "generic" (any shape);
  * static string, never NULL.  Host only.

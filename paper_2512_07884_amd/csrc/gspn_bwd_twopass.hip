@@ -12,6 +12,9 @@
 //           recurrence left: one thread per few adjacent pixels walks the channels, accumulates the three taps in fp32
 //           registers, and on the way turns the saved e into glam = x*e in place and writes gu = gy*h.
 //
+// GSPN-local (Sec. 3.2) cuts both passes at the stretch boundaries; with the weights given as logits pass 1 normalises
+// them as it reads them and pass 2 sends the channel sum through the softmax of its pixel.
+//
 // No scratch memory and no atomics: every output element has one writer, the channel sum has a fixed order.  In bf16
 // storage e passes through storage precision between the passes (one rounding more on glam and on the terms of gw,
 // whose sum is still accumulated in fp32).
@@ -21,6 +24,8 @@ namespace gspn {
 
 hipError_t launch_reverse_sweep_f32(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_bf16(const FwdParams& p, hipStream_t s);
+hipError_t launch_reverse_sweep_f32_local(const FwdParams& p, hipStream_t s);     // GSPN-local and logits calls
+hipError_t launch_reverse_sweep_bf16_local(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s);    // maps beyond the LDS tile
 bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype);
 
@@ -107,6 +112,13 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
     float a0[VEC], a1[VEC], a2[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) { a0[v] = 0.f; a1[v] = 0.f; a2[v] = 0.f; }
+    // GSPN-local (Sec. 3.2): a pixel on a line that starts a stretch has no previous line (its taps were never read)
+    bool starts[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        const int r = vert ? i : j0 + v, S = vert ? H : W;        // image line along the scan axis
+        starts[v] = p.kchunk > 0 && starts_stretch((d & 1) ? S - 1 - r : r, S, d & 1, p.kchunk);
+    }
 
     for (int ci = 0; ci < p.cpg; ++ci) {
         const size_t plane = ((size_t)b * p.C + (size_t)g * p.cpg + ci) * HW;
@@ -141,14 +153,29 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
         float gl[VEC], gu[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-            a0[v] = fmaf(e[v], t0[v], a0[v]);
-            a1[v] = fmaf(e[v], t1[v], a1[v]);
-            a2[v] = fmaf(e[v], t2[v], a2[v]);
+            const float ev = starts[v] ? 0.f : e[v];
+            a0[v] = fmaf(ev, t0[v], a0[v]);
+            a1[v] = fmaf(ev, t1[v], a1[v]);
+            a2[v] = fmaf(ev, t2[v], a2[v]);
             gl[v] = xv[v] * e[v];
             gu[v] = gyv[v] * hc[v];
         }
         stv<T, VEC>(GL + plane + pix0, gl);
         stv<T, VEC>(GU + plane + pix0, gu);
+    }
+    if (p.logits) {
+        // the weights were given as logits: the sum over the group's channels goes through the softmax of its pixel once
+        const T* Z = (const T*)p.w + ((p.shared ? (size_t)0 : (size_t)d * groups) + bg) * 3 * HW;
+        float z0[VEC], z1[VEC], z2[VEC];
+        ldv<T, VEC>(Z + pix0, z0);
+        ldv<T, VEC>(Z + HW + pix0, z1);
+        ldv<T, VEC>(Z + 2 * (size_t)HW + pix0, z2);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const int pos = vert ? j0 + v : i, L = vert ? W : H;      // position on the line
+            softmax3(z0[v], z1[v], z2[v], pos == 0, pos == L - 1);
+            softmax3_grad(a0[v], a1[v], a2[v], z0[v], z1[v], z2[v]);
+        }
     }
     stv<T, VEC>(GW + pix0, a0);
     stv<T, VEC>(GW + HW + pix0, a1);
@@ -159,7 +186,7 @@ FwdParams reverse_sweep_params(const BwdParams& p) {
     FwdParams f = {};
     f.x = p.gy; f.w = p.w; f.lam = p.u; f.u = p.lam; f.y = p.gx; f.hs = p.glam;
     f.B = p.B; f.C = p.C; f.H = p.H; f.W = p.W; f.G = p.G; f.cpg = p.cpg;
-    f.mask = p.mask; f.shared = p.shared; f.kchunk = 0; f.logits = 0; f.xt = nullptr;
+    f.mask = p.mask; f.shared = p.shared; f.kchunk = p.kchunk; f.logits = p.logits; f.xt = nullptr;
     return f;
 }
 
@@ -175,7 +202,7 @@ hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
 }  // namespace
 
 bool bwd_twopass_applicable(const BwdParams& p, int dtype) {
-    if (p.kchunk > 0 || p.logits || p.W % 2) return false;
+    if (p.W % 2) return false;
     if ((size_t)p.B * p.G * ((size_t)p.H * p.W / 2) * 4 / 256 > 0x7fffffffull) return false;
     const FwdParams f = reverse_sweep_params(p);
     return fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype);
@@ -185,8 +212,12 @@ hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     if (!bwd_twopass_applicable(p, dtype)) return hipErrorInvalidValue;
     const FwdParams f = reverse_sweep_params(p);
     hipError_t e;
-    if (fwd_tile_applicable(f, dtype)) e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);
-    else e = launch_reverse_sweep_stream(f, dtype, s);
+    if (fwd_tile_applicable(f, dtype)) {
+        if (p.kchunk > 0 || p.logits) e = dtype == 0 ? launch_reverse_sweep_f32_local(f, s) : launch_reverse_sweep_bf16_local(f, s);
+        else e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);
+    } else {
+        e = launch_reverse_sweep_stream(f, dtype, s);
+    }
     if (e != hipSuccess) return e;
     int ndirs = 0;
     for (int d = 0; d < 4; ++d) ndirs += (p.mask >> d) & 1u;

@@ -1,8 +1,9 @@
-// Reverse sweep of the two-pass backward scan on the forward tile machinery, f32 storage (see gspn_bwd_twopass.hip).
+// Reverse sweep of the two-pass backward scan on the forward tile machinery, f32 storage, global scan
+// (see gspn_bwd_twopass.hip).
 #include "gspn_fwd_tile_impl.hpp"
 
 namespace gspn {
 
-hipError_t launch_reverse_sweep_f32(const FwdParams& p, hipStream_t s) { return launch_reverse_sweep_part<float>(p, s); }
+hipError_t launch_reverse_sweep_f32(const FwdParams& p, hipStream_t s) { return launch_reverse_sweep_part<float, false>(p, s); }
 
 }  // namespace gspn

@@ -50,7 +50,7 @@ struct TileArgs {
 template <typename T, int V, int PF, bool REV, bool SAVE, bool LOCAL, bool LOGITS, bool HT = false, bool BWD = false>
 __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, int b, int c_first, int pk,
                                               int lane, int split) {
-    static_assert(!BWD || (SAVE && !LOCAL && !LOGITS && !HT), "the reverse sweep: global scan, normalised weights, e saved");
+    static_assert(!BWD || (SAVE && !HT), "the reverse sweep saves e and takes the standard layout");
     constexpr int NB = V * (int)sizeof(T);
     constexpr int NR = NB / 4;
     constexpr int d = HT ? (REV ? 3 : 2) : ((REV != BWD) ? 1 : 0);
@@ -123,20 +123,30 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
     float wp0[V], wp1[V], wp2[V];            // BWD: taps of the line swept before (none before the first: 0)
 #pragma unroll
     for (int v = 0; v < V; ++v) { wp0[v] = 0.f; wp1[v] = 0.f; wp2[v] = 0.f; }
+    StretchWalkBack bwalk;                   // BWD, GSPN-local: the scan steps from the last one down
+    if constexpr (BWD && LOCAL) bwalk.init(S, d & 1, p.kchunk);
+    int sweep_t = 0;
     auto step = [&](const Line& cur, bool maybe_start, bool scan_start) {
         if (until_split == 0) lds_barrier();
         --until_split;
         if constexpr (BWD) {
+            // GSPN-local: a line that starts a stretch takes nothing from the line before it in scan order, so its
+            // taps hand nothing on to the line swept next
+            bool starts = false;
+            if constexpr (LOCAL) starts = bwalk.start(sweep_t == S - 1);
+            ++sweep_t;
             float av[V], uv[V];
 #pragma unroll
             for (int v = 0; v < V; ++v) { av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v); uv[v] = elem<T>(cur.u, v); }
             line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
 #pragma unroll
             for (int v = 0; v < V; ++v) {
+                float c0 = elem<T>(cur.w0, v), c1 = elem<T>(cur.w1, v), c2 = elem<T>(cur.w2, v);
+                if constexpr (LOGITS) softmax3(c0, c1, c2, first && v == 0, last && v == V - 1);
                 // a tap that points outside the line takes nothing, whatever the tensor holds there
-                wp0[v] = (first && v == 0) ? 0.f : elem<T>(cur.w0, v);
-                wp1[v] = elem<T>(cur.w1, v);
-                wp2[v] = (last && v == V - 1) ? 0.f : elem<T>(cur.w2, v);
+                wp0[v] = ((first && v == 0) || starts) ? 0.f : c0;
+                wp1[v] = starts ? 0.f : c1;
+                wp2[v] = ((last && v == V - 1) || starts) ? 0.f : c2;
                 tp[v * tvs] += uv[v] * h[v];
             }
             tp += tstep;
@@ -230,6 +240,7 @@ struct HorizontalPass {
     float h[V];
     float wp0[V], wp1[V], wp2[V];   // BWD: taps of the column swept before
     StretchWalk walk;   // GSPN-local only
+    StretchWalkBack bwalk;   // ... in the reverse sweep
     HBuf<T, V, CS> buf0, buf1;
 
     __device__ __forceinline__ void init(const TileArgs& a, float* tile, int d, int b, int c_first, int pk, int lane) {
@@ -262,7 +273,8 @@ struct HorizontalPass {
         trow = tile + ((pk * a.ph + plc) * H + ic * V) * a.pitch;
 #pragma unroll
         for (int v = 0; v < V; ++v) { h[v] = 0.f; wp0[v] = 0.f; wp1[v] = 0.f; wp2[v] = 0.f; }
-        if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
+        if constexpr (LOCAL && !BWD) walk.init(W, REV, p.kchunk);
+        if constexpr (LOCAL && BWD) bwalk.init(W, d & 1, p.kchunk);
     }
 
     // byte offset of chunk c (in scan order) inside a row
@@ -290,14 +302,18 @@ struct HorizontalPass {
             const int e = REV ? CS - 1 - k : k;       // element inside the chunk, compile-time
             float av[V], w0[V], w1[V], w2[V];
             if constexpr (BWD) {
+                bool starts = false;                  // GSPN-local: this column starts a stretch in scan order
+                if constexpr (LOCAL) starts = bwalk.start(c == nchunks - 1 && k == CS - 1);
 #pragma unroll
                 for (int v = 0; v < V; ++v) av[v] = elem<T>(s.l[v], e) * elem<T>(s.x[v], e);
                 line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
-                    wp0[v] = (first && v == 0) ? 0.f : elem<T>(s.w0[v], e);
-                    wp1[v] = elem<T>(s.w1[v], e);
-                    wp2[v] = (last && v == V - 1) ? 0.f : elem<T>(s.w2[v], e);
+                    float c0 = elem<T>(s.w0[v], e), c1 = elem<T>(s.w1[v], e), c2 = elem<T>(s.w2[v], e);
+                    if constexpr (LOGITS) softmax3(c0, c1, c2, first && v == 0, last && v == V - 1);
+                    wp0[v] = ((first && v == 0) || starts) ? 0.f : c0;
+                    wp1[v] = starts ? 0.f : c1;
+                    wp2[v] = ((last && v == V - 1) || starts) ? 0.f : c2;
                     trow[v * pitch + col0 + e] += elem<T>(s.u[v], e) * h[v];
                     hs[v][e] = h[v];
                 }
@@ -382,6 +398,7 @@ struct HorizontalSplitPass {
     float h;
     float wp0, wp1, wp2;   // BWD: taps of the column swept before
     StretchWalk walk;   // GSPN-local only
+    StretchWalkBack bwalk;   // ... in the reverse sweep
     uint32_t bx[NR], bl[NR], bu[NR], b0[NR], b1[NR], b2[NR];
 
     // mailbox layout: [task = channel * 2 + direction slot][part][side: 0 first row, 1 last row][parity]
@@ -418,7 +435,8 @@ struct HorizontalSplitPass {
         mb_up = task + (has_up ? part - 1 : part) * 4 + 2;
         mb_dn = task + (has_dn ? part + 1 : part) * 4 + 0;
         h = 0.f; wp0 = 0.f; wp1 = 0.f; wp2 = 0.f;
-        if constexpr (LOCAL) walk.init(W, REV, p.kchunk);
+        if constexpr (LOCAL && !BWD) walk.init(W, REV, p.kchunk);
+        if constexpr (LOCAL && BWD) bwalk.init(W, d & 1, p.kchunk);
     }
 
     __device__ __forceinline__ int chunk_col(int c) const { return (REV ? nchunks - 1 - c : c) * CS; }
@@ -454,9 +472,13 @@ struct HorizontalSplitPass {
                 up = top_lane ? (has_up ? pu : 0.f) : up;
                 dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
                 h = fmaf(wp1, h, elem<T>(bl, e) * elem<T>(bx, e)) + (up + dn);
-                wp0 = img_first ? 0.f : elem<T>(b0, e);
-                wp1 = elem<T>(b1, e);
-                wp2 = img_last ? 0.f : elem<T>(b2, e);
+                bool starts = false;                      // GSPN-local: this column starts a stretch in scan order
+                if constexpr (LOCAL) starts = bwalk.start(c == nchunks - 1 && k == CS - 1);
+                float c0 = elem<T>(b0, e), c1 = elem<T>(b1, e), c2 = elem<T>(b2, e);
+                if constexpr (LOGITS) softmax3(c0, c1, c2, img_first, img_last);
+                wp0 = (img_first || starts) ? 0.f : c0;
+                wp1 = starts ? 0.f : c1;
+                wp2 = (img_last || starts) ? 0.f : c2;
                 if (edge) mb_out[par] = bot_lane ? wp2 * h : wp0 * h;
                 trow[col0 + e] = fmaf(elem<T>(bu, e), h, yold);
                 hs[e] = h;
@@ -769,24 +791,35 @@ static hipError_t launch_fwd_tile_part(const FwdParams& p, hipStream_t s) {
 
 // First pass of the two-pass backward scan (gspn_bwd_twopass.hip): p holds gy as x, u as lam, lam as u, gx as y and
 // the buffer that receives e as hs.  One translation unit per storage type.
-template <typename T, int VV, int VH, int CS, bool DB, int PF>
-static hipError_t launch_cfg_reverse(const TileArgs& a, const TilePlan& t, hipStream_t s) {
-    if (t.nwaves <= 4) return launch_one_l<T, VV, VH, CS, DB, PF, true, 4, false, false, true>(a, t, s);
-    return launch_one_l<T, VV, VH, CS, DB, PF, true, 8, false, false, true>(a, t, s);
+template <typename T, int VV, int VH, int CS, bool DB, int PF, int MAXW, bool LOC>
+static hipError_t launch_one_reverse(const TileArgs& a, const TilePlan& t, hipStream_t s) {
+    if constexpr (LOC) {
+        if (a.p.logits) return launch_one_l<T, VV, VH, CS, DB, PF, true, MAXW, true, true, true>(a, t, s);
+        return launch_one_l<T, VV, VH, CS, DB, PF, true, MAXW, true, false, true>(a, t, s);
+    } else {
+        return launch_one_l<T, VV, VH, CS, DB, PF, true, MAXW, false, false, true>(a, t, s);
+    }
 }
 
-template <typename T>
+template <typename T, int VV, int VH, int CS, bool DB, int PF, bool LOC>
+static hipError_t launch_cfg_reverse(const TileArgs& a, const TilePlan& t, hipStream_t s) {
+    if (t.nwaves <= 4) return launch_one_reverse<T, VV, VH, CS, DB, PF, 4, LOC>(a, t, s);
+    return launch_one_reverse<T, VV, VH, CS, DB, PF, 8, LOC>(a, t, s);
+}
+
+// LOC as in launch_one: the GSPN-local and logits calls on instantiations (and in translation units) of their own
+template <typename T, bool LOC>
 static hipError_t launch_reverse_sweep_part(const FwdParams& p, hipStream_t s) {
     constexpr int ES = (int)sizeof(T);
     const TilePlan t = plan_tile(p, ES == 4 ? 0 : 1);
-    if (!t.ok || t.hv == H_TRANSPOSED || !p.hs || p.kchunk > 0 || p.logits) return hipErrorInvalidValue;
+    if (!t.ok || t.hv == H_TRANSPOSED || !p.hs || LOC != (p.kchunk > 0 || p.logits)) return hipErrorInvalidValue;
     TileArgs a;
     a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.lplh = t.lplh; a.ph = t.ph;
     a.nwaves = t.nwaves; a.parts = t.parts;
-    if (t.hv == H_SPLIT) return launch_cfg_reverse<T, 2, 0, 128 / ES, false, TILE_PF>(a, t, s);
-    if (t.hv == H_ROW) return launch_cfg_reverse<T, 2, 1, 112 / ES, false, TILE_PF>(a, t, s);
-    if (t.hv == H_SECTOR) return launch_cfg_reverse<T, 2, 2, 64 / ES, false, TILE_PF>(a, t, s);
-    return launch_cfg_reverse<T, 2, 2, 16 / ES, true, TILE_PF>(a, t, s);
+    if (t.hv == H_SPLIT) return launch_cfg_reverse<T, 2, 0, 128 / ES, false, TILE_PF, LOC>(a, t, s);
+    if (t.hv == H_ROW) return launch_cfg_reverse<T, 2, 1, 112 / ES, false, TILE_PF, LOC>(a, t, s);
+    if (t.hv == H_SECTOR) return launch_cfg_reverse<T, 2, 2, 64 / ES, false, TILE_PF, LOC>(a, t, s);
+    return launch_cfg_reverse<T, 2, 2, 16 / ES, true, TILE_PF, LOC>(a, t, s);
 }
 
 }  // namespace gspn

@@ -67,3 +67,31 @@ def test_two_pass_backward_on_512x512_planes():
     assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, 1, 0, True) == "stream"
     assert G.gspn_bwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, 1, 0) == "twopass"
     check_bwd(cfg)
+
+
+# GSPN-local and logits calls on the same maps: stretch lengths that divide the map, that do not, of one line, longer
+# than a chunk of the horizontal phases; all four horizontal variants of the reverse sweep
+@pytest.mark.parametrize("shape,kchunk", [((1, 4, 128, 128, 2, "bf16"), 32), ((1, 4, 128, 64, 2, "f32"), 48), ((1, 4, 96, 96, 2, "bf16"), 7),
+                                          ((1, 4, 96, 72, 2, "bf16"), 20), ((1, 4, 70, 36, 2, "f32"), 1), ((1, 32, 56, 56, 1, "f32"), 9),
+                                          ((2, 3, 192, 128, 3, "bf16"), 100)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_two_pass_backward_with_local_stretches(shape, kchunk):
+    import paper_2512_07884_amd as G
+    from test_gpu_local import check_local
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, int(dtype == "bf16"), 0) == "twopass"
+    check_local(shape, kchunk)
+
+
+@pytest.mark.parametrize("shape,kchunk", [((1, 4, 128, 128, 2, "bf16"), None), ((1, 4, 128, 64, 2, "f32"), None), ((1, 4, 96, 96, 2, "f32"), None),
+                                          ((1, 4, 96, 72, 2, "bf16"), 20), ((1, 4, 70, 36, 2, "f32"), 16), ((1, 32, 56, 56, 1, "f32"), None)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_two_pass_backward_with_logits(shape, kchunk):
+    from test_gpu_logits import check_logits
+    check_logits(shape, kchunk=kchunk, bwd_plan="twopass")
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9])
+def test_two_pass_backward_with_logits_and_local_stretches_direction_masks(mask):
+    from test_gpu_logits import check_logits
+    check_logits((1, 4, 128, 64, 2, "f32"), kchunk=24, mask=mask, bwd_plan="twopass")

@@ -105,10 +105,10 @@ def test_local_scans_on_the_plane_kernels(shape, kchunk):
 # channel by channel: small groups there)
 @pytest.mark.parametrize("shape,kchunk,plans", [
     ((2, 8, 56, 56, 2, "bf16"), 14, ("plane", "tile")), ((1, 8, 64, 64, 8, "bf16"), 10, ("plane", "tile")),
-    ((1, 6, 40, 24, 3, "bf16"), 16, ("plane", "generic")), ((2, 8, 56, 56, 2, "f32"), 9, ("tile", "tile")),
-    ((1, 4, 128, 128, 2, "bf16"), 32, ("tile", "generic")), ((1, 4, 128, 128, 4, "bf16"), 5, ("tile", "generic")),
+    ((1, 6, 40, 24, 3, "bf16"), 16, ("plane", "twopass")), ((2, 8, 56, 56, 2, "f32"), 9, ("tile", "tile")),
+    ((1, 4, 128, 128, 2, "bf16"), 32, ("tile", "twopass")), ((1, 4, 128, 128, 4, "bf16"), 5, ("tile", "twopass")),
     ((1, 8, 64, 128, 2, "f32"), 48, ("tile", "tile")), ((1, 24, 16, 40, 2, "f32"), 3, ("plane", "tile")),
-    ((2, 8, 40, 32, 8, "f32"), 7, ("plane", "tile")), ((1, 4, 96, 72, 2, "bf16"), 20, ("tile", "generic")),
+    ((2, 8, 40, 32, 8, "f32"), 7, ("plane", "tile")), ((1, 4, 96, 72, 2, "bf16"), 20, ("tile", "twopass")),
     ((1, 4, 33, 70, 2, "f32"), 9, ("generic", "generic")), ((2, 6, 9, 13, 3, "f32"), 4, ("generic", "generic")),
     ((1, 2, 1, 37, 1, "f32"), 5, ("generic", "generic")), ((1, 2, 64, 256, 1, "bf16"), 100, ("generic", "generic")),
     ((1, 4, 40, 112, 2, "bf16"), 30, ("tile", "tile"))],

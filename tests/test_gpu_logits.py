@@ -136,8 +136,8 @@ def test_logits_direction_masks(mask):
 # the tile kernels (forward: rows split over waves, 64 B and 16 B bursts; backward: 4 and 8 columns per request,
 # shared and per-channel weights) and the stream kernel (forward without h_save)
 @pytest.mark.parametrize("shape,plans", [
-    ((1, 4, 128, 128, 2, "bf16"), ("tile", "generic")), ((2, 8, 56, 56, 2, "f32"), ("tile", "tile")),
-    ((1, 8, 64, 128, 2, "f32"), ("tile", "tile")), ((1, 4, 96, 72, 2, "bf16"), ("tile", "generic")),
+    ((1, 4, 128, 128, 2, "bf16"), ("tile", "twopass")), ((2, 8, 56, 56, 2, "f32"), ("tile", "tile")),
+    ((1, 8, 64, 128, 2, "f32"), ("tile", "tile")), ((1, 4, 96, 72, 2, "bf16"), ("tile", "twopass")),
     ((2, 8, 56, 56, 2, "bf16"), ("plane", "tile")), ((1, 4, 56, 56, 4, "f32"), ("tile", "tile")),
     ((1, 24, 16, 40, 2, "f32"), ("plane", "tile")), ((2, 8, 40, 32, 8, "f32"), ("plane", "tile")),
     ((2, 8, 40, 32, 2, "bf16"), ("plane", "tile"))],

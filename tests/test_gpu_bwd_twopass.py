@@ -73,7 +73,9 @@ def test_two_pass_backward_on_512x512_planes():
 # than a chunk of the horizontal phases; all four horizontal variants of the reverse sweep
 @pytest.mark.parametrize("shape,kchunk", [((1, 4, 128, 128, 2, "bf16"), 32), ((1, 4, 128, 64, 2, "f32"), 48), ((1, 4, 96, 96, 2, "bf16"), 7),
                                           ((1, 4, 96, 72, 2, "bf16"), 20), ((1, 4, 70, 36, 2, "f32"), 1), ((1, 32, 56, 56, 1, "f32"), 9),
-                                          ((2, 3, 192, 128, 3, "bf16"), 100)],
+                                          ((2, 3, 192, 128, 3, "bf16"), 100),
+                                          # maps beyond the LDS tile
+                                          ((1, 2, 256, 256, 1, "bf16"), 37), ((1, 2, 128, 256, 2, "f32"), 100), ((1, 2, 64, 1024, 1, "bf16"), 300)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_two_pass_backward_with_local_stretches(shape, kchunk):
     import paper_2512_07884_amd as G
@@ -84,7 +86,8 @@ def test_two_pass_backward_with_local_stretches(shape, kchunk):
 
 
 @pytest.mark.parametrize("shape,kchunk", [((1, 4, 128, 128, 2, "bf16"), None), ((1, 4, 128, 64, 2, "f32"), None), ((1, 4, 96, 96, 2, "f32"), None),
-                                          ((1, 4, 96, 72, 2, "bf16"), 20), ((1, 4, 70, 36, 2, "f32"), 16), ((1, 32, 56, 56, 1, "f32"), None)],
+                                          ((1, 4, 96, 72, 2, "bf16"), 20), ((1, 4, 70, 36, 2, "f32"), 16), ((1, 32, 56, 56, 1, "f32"), None),
+                                          ((1, 2, 256, 256, 1, "bf16"), None), ((1, 2, 128, 256, 2, "f32"), 50), ((2, 2, 320, 256, 2, "bf16"), 64)],
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_two_pass_backward_with_logits(shape, kchunk):
     from test_gpu_logits import check_logits

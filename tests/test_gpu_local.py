@@ -110,7 +110,7 @@ def test_local_scans_on_the_plane_kernels(shape, kchunk):
     ((1, 8, 64, 128, 2, "f32"), 48, ("tile", "tile")), ((1, 24, 16, 40, 2, "f32"), 3, ("plane", "tile")),
     ((2, 8, 40, 32, 8, "f32"), 7, ("plane", "tile")), ((1, 4, 96, 72, 2, "bf16"), 20, ("tile", "twopass")),
     ((1, 4, 33, 70, 2, "f32"), 9, ("generic", "generic")), ((2, 6, 9, 13, 3, "f32"), 4, ("generic", "generic")),
-    ((1, 2, 1, 37, 1, "f32"), 5, ("generic", "generic")), ((1, 2, 64, 256, 1, "bf16"), 100, ("generic", "generic")),
+    ((1, 2, 1, 37, 1, "f32"), 5, ("generic", "generic")), ((1, 2, 64, 256, 1, "bf16"), 100, ("stream", "twopass")),
     ((1, 4, 40, 112, 2, "bf16"), 30, ("tile", "tile"))],
     ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_local_scans_on_larger_and_ragged_maps(shape, kchunk, plans):

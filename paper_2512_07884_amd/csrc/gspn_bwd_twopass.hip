@@ -85,10 +85,14 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
     const int H = p.H, W = p.W, HW = H * W;
     const int npb = HW / VEC;
     const size_t per_dir = (size_t)p.B * p.G * npb;
-    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= per_dir * ndirs) return;
-    int dsel = (int)(idx / per_dir);
-    const size_t rem = idx - (size_t)dsel * per_dir;
+    // workgroup -> (direction, block of pixels): the workgroups that work on the same pixels in the different
+    // directions read the same x and gy; they get indices 8 apart, which the dispatcher hands to the same XCD one
+    // after the other, so that those re-reads meet in one L2
+    const unsigned wg = blockIdx.x;
+    int dsel = (int)((wg / 8) % (unsigned)ndirs);
+    const unsigned blk = (wg / (8 * (unsigned)ndirs)) * 8 + (wg % 8);
+    const size_t rem = (size_t)blk * blockDim.x + threadIdx.x;
+    if (rem >= per_dir) return;
     const int bg = (int)(rem / npb);
     const int pix0 = (int)(rem - (size_t)bg * npb) * VEC;
     int d = 0;
@@ -192,8 +196,8 @@ FwdParams reverse_sweep_params(const BwdParams& p) {
 
 template <typename T, int VEC>
 hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
-    const size_t threads = (size_t)ndirs * p.B * p.G * (p.H * p.W / VEC);
-    const size_t blocks = (threads + 255) / 256;
+    const size_t per_dir = (size_t)p.B * p.G * (p.H * p.W / VEC);
+    const size_t blocks = ((per_dir + 255) / 256 + 7) / 8 * 8 * ndirs;      // per direction: a multiple of 8 workgroups
     if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
     hipLaunchKernelGGL((bwd_finish_kernel<T, VEC>), dim3((unsigned)blocks), dim3(256), 0, s, p, ndirs);
     return hipGetLastError();

@@ -186,7 +186,7 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  * same whichever kernel runs, up to the rounding of the storage type):
  *   GSPN_FORCE_GENERIC=1   always the generic kernels
  *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
- *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward
+ *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps)
  *   GSPN_TILE_K=<n>, GSPN_TILE_HV=<0..3>   forward tile kernel: channels per
  *       workgroup / horizontal-phase variant (ignored when they do not fit) */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);

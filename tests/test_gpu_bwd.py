@@ -74,7 +74,8 @@ PLANE_BWD_SHAPES = [(2, 8, 28, 28, 8), (2, 96, 28, 28, 2), (1, 16, 28, 28, 4), (
                     (3, 32, 2, 4, 32), (2, 4, 32, 32, 2), (1, 6, 12, 20, 3), (1, 8, 6, 10, 1), (1, 12, 28, 28, 12),
                     (1, 6, 8, 8, 6), (1, 2, 28, 28, 1), (1, 40, 28, 20, 1), (300, 16, 4, 4, 2)]
 
-# shapes the line-by-line register-resident backward kernel takes: larger maps, odd group sizes
+# shapes the line-by-line register-resident backward kernel takes (when the two-pass backward, which comes first in the
+# dispatch, is switched off): larger maps, odd group sizes
 # (56- and 112-wide maps read 56 / 112 B per row and request in the horizontal phases; twelve 56x56 channels in a
 # group do not fit in LDS: two launches, the second adding onto the stored gw)
 TILE_BWD_SHAPES = [(2, 8, 56, 56, 2), (1, 4, 56, 56, 4), (1, 8, 64, 128, 2), (1, 24, 16, 40, 2), (2, 8, 40, 32, 8),
@@ -134,8 +135,9 @@ def test_backward_plane_kernel_direction_masks_bf16(mask):
 
 @pytest.mark.parametrize("shape", [(2, 8, 56, 56, 2), (1, 4, 56, 56, 4), (1, 8, 64, 128, 2), (1, 24, 16, 40, 2), (2, 8, 40, 32, 8),
                                    (2, 12, 56, 56, 1), (1, 4, 40, 112, 2)])
-def test_backward_tile_kernel_shapes_bf16(shape):
+def test_backward_tile_kernel_shapes_bf16(shape, monkeypatch):
     import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")     # (the two-pass backward takes these maps first)
     B, C, H, W, Gr = shape
     assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 1, 0) == "tile", shape
     check_bwd(WL.ScanConfig("bwdtile16", B, C, H, W, Gr, "bf16", 15, 1.0, 61))
@@ -147,8 +149,9 @@ def test_backward_tile_kernel_direction_masks_bf16(mask):
 
 
 @pytest.mark.parametrize("shape", TILE_BWD_SHAPES)
-def test_backward_tile_kernel_shapes(shape):
+def test_backward_tile_kernel_shapes(shape, monkeypatch):
     import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
     B, C, H, W, Gr = shape
     assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 0, 0) == "tile", shape
     check_bwd(WL.ScanConfig("bwdtile", B, C, H, W, Gr, "f32", 15, 1.0, 29))
@@ -159,6 +162,7 @@ def test_backward_tile_kernel_shapes(shape):
 def test_backward_tile_kernel_on_shapes_the_plane_kernel_normally_takes(shape, monkeypatch):
     import paper_2512_07884_amd as G
     monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
     B, C, H, W, Gr = shape
     assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 0, 0) == "tile", shape
     check_bwd(WL.ScanConfig("bwdtile2", B, C, H, W, Gr, "f32", 15, 1.0, 29))
@@ -167,8 +171,9 @@ def test_backward_tile_kernel_on_shapes_the_plane_kernel_normally_takes(shape, m
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 5, 10, 14])
 @pytest.mark.parametrize("G_", [8, 2])
 @pytest.mark.parametrize("hw", [(28, 28), (40, 32)])
-def test_backward_fast_kernels_direction_masks(mask, G_, hw):
+def test_backward_fast_kernels_direction_masks(mask, G_, hw, monkeypatch):
     import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
     assert G.gspn_bwd_plan(2, 8, hw[0], hw[1], G_, mask, 0, 0) == ("plane" if hw[0] <= 32 else "tile")
     check_bwd(WL.ScanConfig("bwdmask2", 2, 8, hw[0], hw[1], G_, "f32", mask, 1.0, 31))
 
@@ -186,6 +191,7 @@ def test_backward_is_bitwise_repeatable_with_split_groups(kernel, monkeypatch):
     import paper_2512_07884_amd as G
     if kernel == "tile":
         monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+        monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
     assert G.gspn_bwd_plan(2, 96, 28, 28, 2, 15, 0, 0) == kernel
     cfg = WL.ScanConfig("bwdrep", 2, 96, 28, 28, 2, "f32", 15, 1.0, 41)     # 48 channels per group: two workgroups per group
     inp = WL.make_inputs(cfg)

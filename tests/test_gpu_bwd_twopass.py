@@ -17,6 +17,9 @@ pytestmark = pytest.mark.gpu
 SHAPES = [(1, 4, 128, 128, 2, "bf16"), (2, 4, 128, 128, 4, "bf16"), (1, 2, 128, 64, 1, "f32"), (1, 3, 192, 128, 3, "bf16"),
           (1, 4, 96, 96, 2, "bf16"), (1, 2, 100, 48, 1, "f32"), (1, 4, 96, 72, 2, "bf16"), (1, 4, 70, 36, 2, "f32"),
           (1, 32, 56, 56, 1, "bf16"), (1, 32, 56, 56, 1, "f32"), (2, 6, 66, 40, 3, "f32"),
+          # maps the single-launch tile kernel would take too (the two-pass backward comes first)
+          (2, 8, 56, 56, 2, "bf16"), (2, 24, 56, 56, 2, "f32"), (1, 8, 64, 128, 2, "f32"), (2, 8, 40, 32, 8, "f32"),
+          (1, 24, 16, 40, 2, "f32"), (1, 8, 64, 64, 8, "bf16"),
           # maps beyond the LDS tile: 4 / 8 / 16 positions per lane in the vertical passes, 1 to 5 waves per column
           (1, 2, 256, 256, 1, "bf16"), (1, 2, 128, 256, 2, "f32"), (1, 2, 64, 1024, 1, "bf16"), (2, 2, 320, 256, 2, "bf16"),
           (1, 2, 192, 512, 1, "f32"), (1, 4, 128, 512, 2, "bf16")]

@@ -113,8 +113,10 @@ def test_local_scans_on_the_plane_kernels(shape, kchunk):
     ((1, 2, 1, 37, 1, "f32"), 5, ("generic", "generic")), ((1, 2, 64, 256, 1, "bf16"), 100, ("stream", "twopass")),
     ((1, 4, 40, 112, 2, "bf16"), 30, ("tile", "tile"))],
     ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
-def test_local_scans_on_larger_and_ragged_maps(shape, kchunk, plans):
+def test_local_scans_on_larger_and_ragged_maps(shape, kchunk, plans, monkeypatch):
     import paper_2512_07884_amd as G
+    if plans[1] == "tile":
+        monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")     # (the two-pass backward takes these maps first)
     B, C, H, W, Gr, dtype = shape
     dt = int(dtype == "bf16")
     assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, True) == plans[0]
@@ -130,6 +132,7 @@ def test_local_scans_on_the_tile_kernels_for_small_maps(shape, kchunk, monkeypat
     import paper_2512_07884_amd as G
     monkeypatch.setenv("GSPN_FWD_NO_PLANE", "1")
     monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
     B, C, H, W, Gr, dtype = shape
     dt = int(dtype == "bf16")
     assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, True) == "tile"

@@ -142,7 +142,9 @@ def test_logits_direction_masks(mask):
     ((1, 24, 16, 40, 2, "f32"), ("plane", "tile")), ((2, 8, 40, 32, 8, "f32"), ("plane", "tile")),
     ((2, 8, 40, 32, 2, "bf16"), ("plane", "tile"))],
     ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
-def test_logits_on_the_tile_kernels(shape, plans):
+def test_logits_on_the_tile_kernels(shape, plans, monkeypatch):
+    if plans[1] == "tile":
+        monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")     # (the two-pass backward takes these maps first)
     check_logits(shape, fwd_plan=plans[0], bwd_plan=plans[1])
 
 
@@ -158,6 +160,7 @@ def test_logits_with_local_stretches_on_the_tile_kernels(shape, kchunk):
 def test_logits_on_the_tile_kernels_for_small_maps(shape, monkeypatch):
     monkeypatch.setenv("GSPN_FWD_NO_PLANE", "1")
     monkeypatch.setenv("GSPN_BWD_NO_PLANE", "1")
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
     check_logits(shape, fwd_plan="tile", bwd_plan="tile")
 
 

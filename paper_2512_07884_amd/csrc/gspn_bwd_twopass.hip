@@ -5,9 +5,9 @@
 // (Sec. 3.2) with the shared weights of Sec. 4.2, split where the sum over the channels of a group comes in:
 //
 //   pass 1, per channel: e_t = u_t*gy_t + T_{t+1}^T e_{t+1} is the forward recurrence run against the scan order with the
-//           tridiagonal transposed, and gx = sum_d lam_d*e_d is its merged output -- so it runs on the forward tile kernels,
-//           or on the forward stream kernel for maps beyond the LDS tile (reverse-sweep instantiations: gy as x, u as lam,
-//           lam as u, gx as y), which also save e per direction, into the buffer of glam;
+//           tridiagonal transposed, and gx = sum_d lam_d*e_d is its merged output -- so it runs on the forward kernels: the
+//           plane kernel on small maps, the tile kernels, the stream kernel beyond the LDS tile (reverse-sweep
+//           instantiations: gy as x, u as lam, lam as u, gx as y), which also save e per direction, into the buffer of glam;
 //   pass 2, per (direction, image, group) and pixel: gw[k] = sum over the group's channels of e[j] * h_{t-1}[j+k-1] has no
 //           recurrence left: one thread per few adjacent pixels walks the channels, accumulates the three taps in fp32
 //           registers, and on the way turns the saved e into glam = x*e in place and writes gu = gy*h.
@@ -26,6 +26,8 @@ hipError_t launch_reverse_sweep_f32(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_bf16(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_f32_local(const FwdParams& p, hipStream_t s);     // GSPN-local and logits calls
 hipError_t launch_reverse_sweep_bf16_local(const FwdParams& p, hipStream_t s);
+hipError_t launch_reverse_sweep_plane(const FwdParams& p, int dtype, hipStream_t s);     // small maps: whole planes through LDS
+bool reverse_sweep_plane_applicable(const FwdParams& p, int dtype);
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s);    // maps beyond the LDS tile
 bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype);
 
@@ -33,31 +35,39 @@ namespace {
 
 // VEC adjacent elements of storage, widened to fp32 (p aligned to VEC elements)
 template <typename T, int VEC> __device__ __forceinline__ void ldv(const T* p, float (&out)[VEC]) {
-    constexpr int NB = VEC * (int)sizeof(T);
-    uint32_t r[NB / 4];
-    if constexpr (NB == 4) r[0] = *(const uint32_t*)p;
-    else if constexpr (NB == 8) { const u32x2 v = *(const u32x2*)p; r[0] = v.x; r[1] = v.y; }
-    else {
+    if constexpr (VEC == 1) {
+        out[0] = ldf(p);
+    } else {
+        constexpr int NB = VEC * (int)sizeof(T);
+        uint32_t r[NB / 4];
+        if constexpr (NB == 4) r[0] = *(const uint32_t*)p;
+        else if constexpr (NB == 8) { const u32x2 v = *(const u32x2*)p; r[0] = v.x; r[1] = v.y; }
+        else {
 #pragma unroll
-        for (int i = 0; i < NB / 16; ++i) {
-            const u32x4 v = ((const u32x4*)p)[i];
-            r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+            for (int i = 0; i < NB / 16; ++i) {
+                const u32x4 v = ((const u32x4*)p)[i];
+                r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+            }
         }
-    }
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) out[v] = elem<T>(r, v);
+        for (int v = 0; v < VEC; ++v) out[v] = elem<T>(r, v);
+    }
 }
 template <typename T, int VEC> __device__ __forceinline__ void stv(T* p, const float (&in)[VEC]) {
-    constexpr int NB = VEC * (int)sizeof(T);
-    uint32_t r[NB / 4];
-    pack<T, VEC>(in, r);
-    if constexpr (NB == 4) *(uint32_t*)p = r[0];
-    else if constexpr (NB == 8) { const u32x2 v = {r[0], r[1]}; *(u32x2*)p = v; }
-    else {
+    if constexpr (VEC == 1) {
+        stf(p, in[0]);
+    } else {
+        constexpr int NB = VEC * (int)sizeof(T);
+        uint32_t r[NB / 4];
+        pack<T, VEC>(in, r);
+        if constexpr (NB == 4) *(uint32_t*)p = r[0];
+        else if constexpr (NB == 8) { const u32x2 v = {r[0], r[1]}; *(u32x2*)p = v; }
+        else {
 #pragma unroll
-        for (int i = 0; i < NB / 16; ++i) {
-            const u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
-            ((u32x4*)p)[i] = v;
+            for (int i = 0; i < NB / 16; ++i) {
+                const u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
+                ((u32x4*)p)[i] = v;
+            }
         }
     }
 }
@@ -206,17 +216,18 @@ hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
 }  // namespace
 
 bool bwd_twopass_applicable(const BwdParams& p, int dtype) {
-    if (p.W % 2) return false;
-    if ((size_t)p.B * p.G * ((size_t)p.H * p.W / 2) * 4 / 256 > 0x7fffffffull) return false;
+    if ((size_t)p.B * p.G * ((size_t)p.H * p.W) * 4 / 256 > 0x7fffffffull) return false;
     const FwdParams f = reverse_sweep_params(p);
-    return fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype);
+    return reverse_sweep_plane_applicable(f, dtype) || fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype);
 }
 
 hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     if (!bwd_twopass_applicable(p, dtype)) return hipErrorInvalidValue;
     const FwdParams f = reverse_sweep_params(p);
     hipError_t e;
-    if (fwd_tile_applicable(f, dtype)) {
+    if (reverse_sweep_plane_applicable(f, dtype)) {
+        e = launch_reverse_sweep_plane(f, dtype, s);
+    } else if (fwd_tile_applicable(f, dtype)) {
         if (p.kchunk > 0 || p.logits) e = dtype == 0 ? launch_reverse_sweep_f32_local(f, s) : launch_reverse_sweep_bf16_local(f, s);
         else e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);
     } else {
@@ -228,11 +239,13 @@ hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     if (dtype == 0) {
         if (p.W % 8 == 0) return launch_finish<float, 8>(p, ndirs, s);
         if (p.W % 4 == 0) return launch_finish<float, 4>(p, ndirs, s);
-        return launch_finish<float, 2>(p, ndirs, s);
+        if (p.W % 2 == 0) return launch_finish<float, 2>(p, ndirs, s);
+        return launch_finish<float, 1>(p, ndirs, s);
     }
     if (p.W % 8 == 0) return launch_finish<bf16_t, 8>(p, ndirs, s);
     if (p.W % 4 == 0) return launch_finish<bf16_t, 4>(p, ndirs, s);
-    return launch_finish<bf16_t, 2>(p, ndirs, s);
+    if (p.W % 2 == 0) return launch_finish<bf16_t, 2>(p, ndirs, s);
+    return launch_finish<bf16_t, 1>(p, ndirs, s);
 }
 
 }  // namespace gspn

@@ -18,12 +18,20 @@ static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
 static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
     const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
     if (f && f[0] == '1') return BWD_GENERIC;
-    const char* np = getenv("GSPN_BWD_NO_PLANE");     // testing aid: keep the tile kernel reachable on tiny maps
-    if (!(np && np[0] == '1') && bwd_plane_applicable(p, dtype)) return BWD_PLANE;
+    const char* nt = getenv("GSPN_BWD_NO_TWOPASS");   // testing aid: keep the plane, tile and generic kernels reachable
+    const bool twopass = !(nt && nt[0] == '1') && bwd_twopass_applicable(p, dtype);
+    const char* np = getenv("GSPN_BWD_NO_PLANE");     // testing aid: keep the other kernels reachable on tiny maps
+    if (!(np && np[0] == '1') && bwd_plane_applicable(p, dtype)) {
+        // the single-launch plane kernel, except where the two passes were measured faster: bf16 storage, shared
+        // weights, lines of more than 16 positions (28x28x192, B = 64, G = 8: 382 -> 270 us; the other stages of that
+        // classifier and the fp32 maps run as fast or faster on the plane kernel)
+        const int m = p.H > p.W ? p.H : p.W;
+        if (twopass && dtype == 1 && p.cpg > 1 && m > 16) return BWD_TWOPASS;
+        return BWD_PLANE;
+    }
     // the two-pass backward before the single-launch tile kernel: measured faster on every map both take (56x56x96
-    // 506 -> 422 us bf16, 64x64x256 457 -> 186 us, 64x128x256 438 -> 193 us)
-    const char* nt = getenv("GSPN_BWD_NO_TWOPASS");   // testing aid: keep the tile and generic kernels reachable
-    if (!(nt && nt[0] == '1') && bwd_twopass_applicable(p, dtype)) return BWD_TWOPASS;
+    // 506 -> 365 us bf16, 64x64x256 457 -> 186 us, 64x128x256 438 -> 193 us)
+    if (twopass) return BWD_TWOPASS;
     return bwd_tile_applicable(p, dtype) ? BWD_TILE : BWD_GENERIC;
 }
 

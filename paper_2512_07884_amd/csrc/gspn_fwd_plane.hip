@@ -77,9 +77,15 @@ struct FwdPlaneArgs {
 // (WSH chunks per thread), so they are requested a direction ahead; otherwise they are fetched in place.
 // FLAT: planes in LDS are unpadded and the wave's channels contiguous (see the head of the file).
 // LOCAL: GSPN-local (Sec. 3.2), on instantiations of its own so that the global scan carries none of it.
-template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL>
+// BWD: the reverse sweep of the backward pass (first pass of the two-pass backward scan) on the same machinery: the
+// caller passes gy as x, u as lam, lam as u, gx as y and the buffer that receives e as hs; every direction is walked
+// against its scan order, and a position multiplies its state by the taps of the line swept before and hands the
+// products to the positions those taps read from (e_t = u_t*gy_t + T_{t+1}^T e_{t+1}).  The taps that are stored as 0
+// (out-of-line neighbours, GSPN-local: lines that start a stretch) are the ones that must pass nothing on here too.
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL, bool BWD = false>
 __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneArgs a) {
     static_assert(!(FLAT && WPRE), "the flat variant fetches its weights in place");
+    static_assert(!BWD || SAVE, "the reverse sweep saves its state");
     constexpr int E = 16 / (int)sizeof(T);        // elements per 16 B chunk
     constexpr int NCH = 8;                        // chunks per lane: the wave's channels hold at most 8 KB
     constexpr int WSH = 4;                        // weight chunks per thread (shared weights)
@@ -197,7 +203,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         int dn = d + 1;
         while (dn < 4 && !((p.mask >> dn) & 1u)) ++dn;
         // element (position j, scan step s) of a plane sits at float offset j*ps + s0 + s*ss
-        const bool vert = d < 2, rev = (d & 1) != 0;
+        const bool vert = d < 2, rev = ((d & 1) != 0) != BWD;       // (the reverse sweep walks against the scan order)
         const int S = vert ? H : W, L = vert ? W : H;
         const int ps = vert ? 1 : P;
         const int ss4 = 4 * (vert ? (rev ? -P : P) : (rev ? -1 : 1));
@@ -368,16 +374,25 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
             uint32_t aad = ahreg + 4u * (uint32_t)(half * HP + tpos);
             uint32_t wad = wreg + 16u * (uint32_t)((SHARED ? 0 : half * HP) + tpos);
             float h = plds_ld(aad);                        // scan step 0: no previous line, its weights are never read
+            pf32x4a wp = plds_ld4(wad);                    // BWD: taps of the line swept before
             // lanes past the end of the line walk the last position's operands; what they compute is never
             // stored, and the selects below keep it out of the line
             auto step = [&]() {
                 aad += (uint32_t)ss4; wad += (uint32_t)(4 * ss4);
                 const float av = plds_ld(aad);
                 const pf32x4a w = plds_ld4(wad);
-                float hl = from_lane_below(h), hr = from_lane_above(h);
-                hl = first ? 0.f : hl;                     // no neighbour outside the line (its weight is stored as 0)
-                hr = last ? 0.f : hr;
-                h = fmaf(w.x, hl, fmaf(w.y, h, fmaf(w.z, hr, av)));
+                if constexpr (BWD) {
+                    float lin = from_lane_below(wp.z * h), rin = from_lane_above(wp.x * h);
+                    lin = first ? 0.f : lin;
+                    rin = last ? 0.f : rin;
+                    h = fmaf(wp.y, h, av) + (lin + rin);
+                    wp = w;
+                } else {
+                    float hl = from_lane_below(h), hr = from_lane_above(h);
+                    hl = first ? 0.f : hl;                 // no neighbour outside the line (its weight is stored as 0)
+                    hr = last ? 0.f : hr;
+                    h = fmaf(w.x, hl, fmaf(w.y, h, fmaf(w.z, hr, av)));
+                }
                 if (active) plds_st(aad, h);
             };
             // four steps per trip: their operand reads do not depend on h and are issued together
@@ -491,9 +506,9 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
 
 bool fwd_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane(p, dtype).ok; }
 
-template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL>
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL, bool BWD = false>
 static hipError_t launch_fplane_kl(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
-    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE, FLAT, LOCAL>;
+    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE, FLAT, LOCAL, BWD>;
     hipError_t e = allow_dynamic_lds((const void*)k, FPLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
@@ -524,6 +539,37 @@ template <typename T>
 static hipError_t launch_fplane_t(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
     if (a.p.hs) return t.shared_group ? launch_fplane<T, true, true>(a, t, s) : launch_fplane<T, true, false>(a, t, s);
     return t.shared_group ? launch_fplane<T, false, true>(a, t, s) : launch_fplane<T, false, false>(a, t, s);
+}
+
+// reverse sweep (first pass of the two-pass backward scan): the same choice of variant, state always saved
+template <typename T, bool SHARED, bool WPRE, bool FLAT>
+static hipError_t launch_fplane_rev_k(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    return a.p.kchunk > 0 ? launch_fplane_kl<T, true, SHARED, WPRE, FLAT, true, true>(a, t, s)
+                          : launch_fplane_kl<T, true, SHARED, WPRE, FLAT, false, true>(a, t, s);
+}
+template <typename T, bool SHARED>
+static hipError_t launch_fplane_rev(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    if (t.flat) return launch_fplane_rev_k<T, SHARED, false, true>(a, t, s);
+    if constexpr (SHARED) {
+        const int E = 16 / (int)sizeof(T);
+        const bool wpre = 3 * (a.p.H * a.p.W / E) <= 4 * 64 * a.nwaves;   // WSH chunks per thread
+        return wpre ? launch_fplane_rev_k<T, true, true, false>(a, t, s) : launch_fplane_rev_k<T, true, false, false>(a, t, s);
+    } else {
+        return launch_fplane_rev_k<T, false, false, false>(a, t, s);
+    }
+}
+
+bool reverse_sweep_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane(p, dtype).ok; }
+
+// p holds gy as x, u as lam, lam as u, gx as y and the buffer that receives e as hs
+hipError_t launch_reverse_sweep_plane(const FwdParams& p, int dtype, hipStream_t s) {
+    const FwdPlanePlan t = plan_fwd_plane(p, dtype);
+    if (!t.ok || !p.hs) return hipErrorInvalidValue;
+    FwdPlaneArgs a;
+    a.p = p; a.K = t.K; a.cpw = t.cpw; a.lsh = t.lsh; a.nwaves = t.nwaves; a.pitch = t.pitch; a.wlw = t.wlw;
+    for (int d = 0; d < 4; ++d) a.seg[d] = stretch_start_bits(d < 2 ? p.H : p.W, d & 1, p.kchunk, false);
+    if (dtype == 0) return t.shared_group ? launch_fplane_rev<float, true>(a, t, s) : launch_fplane_rev<float, false>(a, t, s);
+    return t.shared_group ? launch_fplane_rev<bf16_t, true>(a, t, s) : launch_fplane_rev<bf16_t, false>(a, t, s);
 }
 
 hipError_t launch_fwd_plane(const FwdParams& p, int dtype, hipStream_t s) {

@@ -134,7 +134,7 @@ def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
     for C, HW in ((192, 28), (384, 14), (768, 7)):
         for dt in (0, 1):
             assert fwd(64, C, HW, HW, 8, 15, dt, 0, 1) == "plane", (C, HW, dt)
-            assert bwd(64, C, HW, HW, 8, 15, dt, 0) == "plane", (C, HW, dt)
+            assert bwd(64, C, HW, HW, 8, 15, dt, 0) == ("twopass" if (HW, dt) == (28, 1) else "plane"), (C, HW, dt)   # (28x28 bf16: two passes measured faster)
     assert bwd(2, 1024, 128, 128, 16, 15, 1, 0) == "twopass"                 # beyond 64 lines: reverse sweep on the forward tile kernels + channel sum
     monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
     assert fwd(64, 96, 56, 56, 8, 15, 1, 0, 0) == "generic" and bwd(32, 192, 28, 28, 4, 15, 0, 0) == "generic"

@@ -96,8 +96,9 @@ PLANE_BWD_BF16_SHAPES = [(2, 8, 28, 28, 8), (2, 16, 28, 28, 2), (1, 12, 16, 32, 
 
 
 @pytest.mark.parametrize("shape", PLANE_BWD_BF16_SHAPES)
-def test_backward_plane_kernel_shapes_bf16(shape):
+def test_backward_plane_kernel_shapes_bf16(shape, monkeypatch):
     import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")     # (the two-pass backward takes the larger of these maps first)
     B, C, H, W, Gr = shape
     assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 1, 0) == "plane", shape
     check_bwd(WL.ScanConfig("bwdplane16", B, C, H, W, Gr, "bf16", 15, 1.0, 53))
@@ -129,7 +130,8 @@ def test_backward_plane_kernel_direction_masks_on_short_lines(mask, shape):
 
 
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 3, 12, 6, 9, 14])
-def test_backward_plane_kernel_direction_masks_bf16(mask):
+def test_backward_plane_kernel_direction_masks_bf16(mask, monkeypatch):
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
     check_bwd(WL.ScanConfig("bwdplane16mask", 2, 8, 28, 28, 2, "bf16", mask, 1.0, 59))
 
 

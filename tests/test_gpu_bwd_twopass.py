@@ -101,3 +101,39 @@ def test_two_pass_backward_with_logits(shape, kchunk):
 def test_two_pass_backward_with_logits_and_local_stretches_direction_masks(mask):
     from test_gpu_logits import check_logits
     check_logits((1, 4, 128, 64, 2, "f32"), kchunk=24, mask=mask, bwd_plan="twopass")
+
+
+# small maps whose forward runs on the plane kernel and whose backward the plane kernel refuses: the reverse sweep runs on
+# the plane kernel too (padded and unpadded LDS planes, 1 to 8 channels per wave, shared and per-channel weights --
+# 7x7 and 14x14 with one weight map per channel are the original GSPN on the last stages of a classifier, Sec. 5.2)
+PLANE_SWEEP_SHAPES = [(2, 16, 28, 28, 2, "bf16"), (1, 12, 16, 32, 3, "bf16"), (2, 24, 56, 56, 2, "bf16"), (1, 8, 64, 64, 8, "bf16"), (1, 6, 40, 24, 3, "bf16"), (2, 16, 14, 14, 16, "bf16"),
+                      (2, 16, 7, 7, 16, "f32"), (2, 16, 7, 7, 16, "bf16"), (3, 8, 56, 56, 8, "bf16"), (1, 4, 64, 64, 1, "bf16")]
+
+
+@pytest.mark.parametrize("shape", PLANE_SWEEP_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_two_pass_backward_with_the_reverse_sweep_on_the_plane_kernel(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    dt = int(dtype == "bf16")
+    assert G.gspn_fwd_plan(B, C, H, W, Gr, 15, dt, 0, True) == "plane"
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, dt, 0) == "twopass"
+    check_bwd(WL.ScanConfig("planesweep", B, C, H, W, Gr, dtype, 15, 1.0, 89))
+
+
+@pytest.mark.parametrize("shape,kchunk", [((2, 24, 56, 56, 2, "bf16"), 14), ((1, 8, 64, 64, 8, "bf16"), 10), ((2, 16, 14, 14, 16, "bf16"), 5),
+                                          ((2, 16, 7, 7, 16, "f32"), 3)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_two_pass_backward_on_the_plane_kernel_with_local_stretches_and_logits(shape, kchunk):
+    import paper_2512_07884_amd as G
+    from test_gpu_local import check_local
+    from test_gpu_logits import check_logits
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, int(dtype == "bf16"), 0) == "twopass"
+    check_local(shape, kchunk)
+    check_logits(shape, kchunk=kchunk, fwd_plan="plane", bwd_plan="twopass")
+    check_logits(shape, fwd_plan="plane", bwd_plan="twopass")
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9, 11])
+def test_two_pass_backward_on_the_plane_kernel_direction_masks(mask):
+    check_bwd(WL.ScanConfig("planesweepmask", 2, 8, 56, 56, 2, "bf16", mask, 1.0, 97))

@@ -8,7 +8,9 @@ import pytest
 
 from gpu_util import to_device
 from paper_2512_07884_amd import workloads as WL
-from test_gpu_bwd import check_bwd
+from test_gpu_bwd import check_bwd, run_bwd_gpu
+from gpu_util import TOL, rel_inf_err
+from oracle import gspn_oracle as O
 
 pytestmark = pytest.mark.gpu
 
@@ -137,3 +139,27 @@ def test_two_pass_backward_on_the_plane_kernel_with_local_stretches_and_logits(s
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9, 11])
 def test_two_pass_backward_on_the_plane_kernel_direction_masks(mask):
     check_bwd(WL.ScanConfig("planesweepmask", 2, 8, 56, 56, 2, "bf16", mask, 1.0, 97))
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 28, 28, 2, "f32"), (1, 4, 128, 64, 2, "f32"), (2, 24, 56, 56, 2, "bf16"), (1, 2, 256, 256, 1, "bf16"),
+                                   (2, 6, 17, 17, 3, "f32")], ids=lambda s: "x".join(map(str, s)))
+def test_backward_with_one_parameter_set_for_all_directions(shape):
+    """GSPN_FLAG_SHARED_PARAMS: w, lam, u have a single slot that every direction reads; the gradients keep four slots
+    (plane, two-pass on the tile / plane / stream sweeps, generic kernels)."""
+    B, C, H, W, Gr, dtype = shape
+    cfg = WL.ScanConfig("sharedbwd", B, C, H, W, Gr, dtype, 15, 1.0, 101)
+    inp = WL.make_inputs(cfg, with_gy=True)
+    one = {"x": inp["x"], "gy": inp["gy"], "w": inp["w"][:1].copy(), "lam": inp["lam"][:1].copy(), "u": inp["u"][:1].copy()}
+    rep = {"x": inp["x"], "gy": inp["gy"], "w": np.repeat(one["w"], 4, 0), "lam": np.repeat(one["lam"], 4, 0),
+           "u": np.repeat(one["u"], 4, 0)}
+    f = WL.inputs_as_f64(rep, dtype)
+    _, h_ref = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
+    h_used = WL.storage_to_f64(WL.to_storage(h_ref, dtype), dtype)
+    gx, gw, glam, gu = O.scan_bwd(f["gy"], f["x"], f["w"], f["lam"], f["u"], h_used, 15)
+    out = run_bwd_gpu(one, cfg, 15, flags=1)
+    tol = TOL[dtype]
+    assert rel_inf_err(out["gx"], gx) <= tol
+    for d in range(4):
+        for name, got, ref in (("gw", out["gw"], gw), ("glam", out["glam"], glam), ("gu", out["gu"], gu)):
+            e = rel_inf_err(got[d], ref[d])
+            assert e <= tol, (shape, name, d, e)

@@ -371,6 +371,13 @@ def main():
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "detail": s,
     }
+    if cfg.name == "diff128" and not (a.kchunk or a.logits or a.transposed):
+        # the same shape as a training step (forward with h_save + backward), beside the forward-only headline
+        ct = WL.CONFIGS["train128"]
+        t = summarise(ct, run_workload(ct, max(20, a.steps // 4), a.warmup))
+        line["detail"]["training_step_on_this_shape"] = {k: t[k] for k in (
+            "workload", "step", "ms_per_step", "gpixel_ch_per_s", "fwd_kernel", "fwd_ms_avg", "fwd_algorithmic_GBs",
+            "fwd_frac_of_hbm_peak", "bwd_kernel", "bwd_ms_avg", "bwd_algorithmic_GBs", "bwd_frac_of_hbm_peak")}
     if cpu is not None:
         line["cpu_baseline"] = cpu
     if a.proxy:

@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "diff128"   # 128x128 diffusion-latent shape: first of the two target shapes
-TRAINING = ("train28_gc", "train28_g4", "train128", "train512")
+TRAINING = ("train28_gc", "train28_g4", "train56", "train128", "train512")
 
 
 def device_inputs(cfg, seed: int, logits: bool = False):

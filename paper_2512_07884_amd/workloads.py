@@ -82,8 +82,9 @@ CONFIGS = {
     "long256x1024": ScanConfig("long256x1024", 1, 512, 256, 1024, 16, "bf16", 15, 1.0, 3),
     "train28_gc":  ScanConfig("train28_gc", 32, 192, 28, 28, 192, "f32", 15, 1.0, 4),
     "train28_g4":  ScanConfig("train28_g4", 32, 192, 28, 28, 4, "f32", 15, 1.0, 4),
-    # not in the benchmark definition: the diffusion-latent and high-resolution shapes as training steps (forward with
+    # not in the benchmark definition: the classification, diffusion-latent and high-resolution shapes as training steps (forward with
     # h_save + backward)
+    "train56":     ScanConfig("train56", 64, 96, 56, 56, 8, "bf16", 15, 1.0, 7),
     "train128":    ScanConfig("train128", 2, 1024, 128, 128, 16, "bf16", 15, 3.0, 5),
     "train512":    ScanConfig("train512", 1, 512, 512, 512, 16, "bf16", 15, 1.0, 6),
 }

@@ -78,7 +78,7 @@ def test_full_size_constant_line_invariant(name):
     assert err <= TOL[cfg.dtype], (name, err)
 
 
-@pytest.mark.parametrize("name", ["train28_gc", "train28_g4", "train128"])
+@pytest.mark.parametrize("name", ["train28_gc", "train28_g4", "train56", "train128"])
 def test_full_size_training_step_sampled_slices_match_the_oracle(name):
     """Forward with h_save + backward at the benchmark's size; sampled (batch, group) slices of every
     gradient are recomputed by the oracle from the same stored inputs (its own hidden states)."""

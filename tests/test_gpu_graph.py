@@ -1,5 +1,5 @@
 """The library under HIP graph capture: forward + backward calls (including the zero-fill kernel of the
-split-group backward) recorded once and replayed several times with changed inputs; every replay must
+split-group backward and the two launches of the two-pass backward) recorded once and replayed several times with changed inputs; every replay must
 equal the eager result bit for bit."""
 import numpy as np
 import pytest
@@ -10,7 +10,8 @@ from paper_2512_07884_amd import workloads as WL
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("shape", [(2, 96, 28, 28, 2, "f32"), (2, 8, 56, 56, 2, "bf16"), (1, 4, 128, 128, 2, "bf16")],
+@pytest.mark.parametrize("shape", [(2, 96, 28, 28, 2, "f32"), (2, 8, 56, 56, 2, "bf16"), (1, 4, 128, 128, 2, "bf16"),
+                                   (1, 2, 256, 256, 1, "bf16")],
                          ids=lambda s: "x".join(map(str, s)))
 def test_captured_training_step_replays_like_eager(shape):
     import torch

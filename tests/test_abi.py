@@ -117,7 +117,7 @@ def test_kernel_family_chosen_for_local_scans(lib, monkeypatch):
 
 def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
     """Host-side dispatch only: which kernel family each workload of the benchmark runs on."""
-    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_TILE_K", "GSPN_TILE_HV"):
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_BWD_NO_TWOPASS", "GSPN_TILE_K", "GSPN_TILE_HV"):
         monkeypatch.delenv(v, raising=False)
     fwd = lambda *a: lib.gspn_fwd_plan(*a).decode()
     bwd = lambda *a: lib.gspn_bwd_plan(*a).decode()
@@ -136,6 +136,14 @@ def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
             assert fwd(64, C, HW, HW, 8, 15, dt, 0, 1) == "plane", (C, HW, dt)
             assert bwd(64, C, HW, HW, 8, 15, dt, 0) == ("twopass" if (HW, dt) == (28, 1) else "plane"), (C, HW, dt)   # (28x28 bf16: two passes measured faster)
     assert bwd(2, 1024, 128, 128, 16, 15, 1, 0) == "twopass"                 # beyond 64 lines: reverse sweep on the forward tile kernels + channel sum
+    # training steps on the larger shapes: h_save on the stream kernel, two-pass backward (reverse sweep on the stream
+    # kernel); small maps with one weight map per channel in bf16: two-pass with the reverse sweep on the plane kernel
+    assert fwd(1, 512, 512, 512, 16, 15, 1, 0, 1) == "stream" and bwd(1, 512, 512, 512, 16, 15, 1, 0) == "twopass"
+    assert bwd(64, 768, 7, 7, 768, 15, 1, 0) == "twopass" and bwd(64, 384, 14, 14, 384, 15, 1, 0) == "twopass"
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")                           # the kernels behind it stay reachable
+    assert bwd(64, 96, 56, 56, 8, 15, 1, 0) == "tile" and bwd(2, 1024, 128, 128, 16, 15, 1, 0) == "generic"
+    assert bwd(64, 192, 28, 28, 8, 15, 1, 0) == "plane"
+    monkeypatch.delenv("GSPN_BWD_NO_TWOPASS")
     monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
     assert fwd(64, 96, 56, 56, 8, 15, 1, 0, 0) == "generic" and bwd(32, 192, 28, 28, 4, 15, 0, 0) == "generic"
 

@@ -373,6 +373,23 @@ def proxy_project(inp, P):
     return np.einsum("mk,bkhw->bmhw", P, inp)
 
 
+def proxy_project_bwd(gout, inp, P):
+    """Gradients of out = proxy_project(inp, P) for a loss L with gout = dL/dout (chain rule on the sum above):
+        gin[b, k, h, w] = sum_m P[m, k] * gout[b, m, h, w]
+        gP[m, k]        = sum over b, h, w of gout[b, m, h, w] * inp[b, k, h, w]
+    Returns (gin, gP)."""
+    gout = np.asarray(gout, dtype=np.float64)
+    inp = np.asarray(inp, dtype=np.float64)
+    P = np.asarray(P, dtype=np.float64)
+    if P.ndim != 2 or inp.ndim != 4 or gout.ndim != 4 or P.shape[1] != inp.shape[1] or P.shape[0] != gout.shape[1]:
+        raise ValueError("shape mismatch")
+    if gout.shape[0] != inp.shape[0] or gout.shape[2:] != inp.shape[2:]:
+        raise ValueError("shape mismatch")
+    gin = np.einsum("mk,bmhw->bkhw", P, gout)
+    gP = np.einsum("bmhw,bkhw->mk", gout, inp)
+    return gin, gP
+
+
 def proxy_scan_fwd(x, Pd, w, lam, u, Pu, dir_mask=15):
     """The scan wrapped in the compressive proxy (Sec. 4.2): project down, propagate in the proxy space with the
     shared weights, project back.  x [B,C,H,W]; Pd [Cp,C]; w [4,B,G,3,H,W]; lam, u [4,B,Cp,H,W]; Pu [C,Cp]."""

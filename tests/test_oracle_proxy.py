@@ -45,3 +45,47 @@ def test_two_projections_compose_like_their_matrix_product_and_the_wrapper_is_li
     # with identity projections the wrapper is the scan itself
     xs = rng.standard_normal((1, 2, 3, 3))
     assert np.array_equal(O.proxy_scan_fwd(xs, np.eye(2), w, lam, u, np.eye(2)), O.scan_fwd(xs, w, lam, u)[0])
+
+
+def test_projection_gradients_equal_the_sums_written_out():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((2, 5, 3, 4)); P = rng.standard_normal((3, 5)); g = rng.standard_normal((2, 3, 3, 4))
+    gin, gP = O.proxy_project_bwd(g, x, P)
+    rin = np.zeros_like(x); rP = np.zeros_like(P)
+    for b in range(2):
+        for m in range(3):
+            for k in range(5):
+                for h in range(3):
+                    for w in range(4):
+                        rin[b, k, h, w] += P[m, k] * g[b, m, h, w]
+                        rP[m, k] += g[b, m, h, w] * x[b, k, h, w]
+    assert np.allclose(gin, rin, rtol=0, atol=1e-14) and np.allclose(gP, rP, rtol=0, atol=1e-13)
+
+
+def test_projection_gradients_against_finite_differences_and_the_adjoint_identity():
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((2, 4, 2, 3)); P = rng.standard_normal((3, 4)); g = rng.standard_normal((2, 3, 2, 3))
+    gin, gP = O.proxy_project_bwd(g, x, P)
+    loss = lambda xx, PP: float(np.sum(g * O.proxy_project(xx, PP)))
+    eps = 1e-6
+    for idx in [(0, 0, 0, 0), (1, 3, 1, 2), (0, 2, 1, 1)]:
+        d = np.zeros_like(x); d[idx] = eps
+        assert abs((loss(x + d, P) - loss(x - d, P)) / (2 * eps) - gin[idx]) < 1e-8
+    for idx in [(0, 0), (2, 3), (1, 2)]:
+        d = np.zeros_like(P); d[idx] = eps
+        assert abs((loss(x, P + d) - loss(x, P - d)) / (2 * eps) - gP[idx]) < 1e-8
+    # <g, P x> = <P^T g, x> and = <gP, P>: the loss is bilinear
+    assert np.isclose(np.sum(g * O.proxy_project(x, P)), np.sum(gin * x), rtol=1e-13)
+    assert np.isclose(np.sum(g * O.proxy_project(x, P)), np.sum(gP * P), rtol=1e-13)
+    # the input gradient is the projection with the transposed matrix
+    assert np.allclose(gin, O.proxy_project(g, P.T), rtol=0, atol=1e-14)
+
+
+def test_projection_gradient_of_a_selection_matrix():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((1, 6, 2, 2)); g = rng.standard_normal((1, 2, 2, 2))
+    sel = np.zeros((2, 6)); sel[0, 4] = 1.0; sel[1, 1] = -2.0
+    gin, gP = O.proxy_project_bwd(g, x, sel)
+    assert np.array_equal(gin[:, 4], g[:, 0]) and np.array_equal(gin[:, 1], -2.0 * g[:, 1])
+    assert not gin[:, [0, 2, 3, 5]].any()
+    assert np.isclose(gP[0, 4], np.sum(g[:, 0] * x[:, 4])) and np.isclose(gP[1, 0], np.sum(g[:, 1] * x[:, 0]))

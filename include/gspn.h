@@ -168,9 +168,21 @@ const char* gspn_fwd_transposed_plan(int B, int C, int H, int W, int G, unsigned
  *   in  [B,K,H,W]   P [M,K] row-major   out [B,M,H,W]   (down: K = C, M = C_proxy; up: K = C_proxy, M = C)
  * The scan in the proxy space is an ordinary gspn_scan_fwd on [B,C_proxy,H,W].  bf16 storage with K and H*W
  * multiples of 8 runs on the matrix cores (fp32 accumulation, one rounding per output); other shapes and fp32
- * storage run a plain FMA kernel.  Forward only.  Pointers, stream and errors as for the scan calls. */
+ * storage run a plain FMA kernel.  Pointers, stream and errors as for the scan calls. */
 int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int H, int W, int dtype,
                        void* stream);
+/* Gradients of gspn_proxy_project for a scalar loss L, given gout = dL/dout (chain rule on the sum above):
+ *     gin[b][k][h][w] = sum_m P[m][k] * gout[b][m][h][w]                  the projection with P transposed
+ *     gP[m][k]        = sum over b, h, w of gout[b][m][h][w] * in[b][k][h][w]
+ *   gout in [B,M,H,W]; in [B,K,H,W] and P [M,K] as in the forward call
+ *   gin     out [B,K,H,W] in the storage type, or NULL (not computed)
+ *   gP      out [M,K] in fp32 whatever the storage type, or NULL (not computed; at least one of gin, gP is required)
+ *   partial workspace of the caller's, B*M*K floats, required with gP (NULL otherwise): it receives the per-image
+ *           sums, which a second small kernel adds in image order -- no atomics, the result is bitwise repeatable.
+ * The library still allocates nothing.  bf16 storage runs on the matrix cores when M (for gin) and H*W (both; for gP
+ * a multiple of 16) allow, as in the forward call; other shapes and fp32 storage run plain FMA kernels. */
+int gspn_proxy_project_bwd(const void* gout, const void* in, const void* P, void* gin, float* gP, float* partial,
+                           int B, int K, int M, int H, int W, int dtype, void* stream);
 /* "mfma" or "fma": which kernel gspn_proxy_project runs for these arguments ("invalid" for bad ones). */
 const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 

@@ -21,7 +21,7 @@ _LIB = None
 EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_bwd_local",
            "gspn_scan_fwd_logits", "gspn_scan_bwd_logits",
            "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
-           "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_plan",
+           "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_project_bwd", "gspn_proxy_plan",
            "gspn_scan_fwd_transposed", "gspn_fwd_transposed_plan",
            "gspn_status_string", "gspn_version")
 
@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_fwd_transposed_plan.restype = ctypes.c_char_p
     lib.gspn_proxy_project.argtypes = [vp] * 3 + [ci] * 6 + [vp]
     lib.gspn_proxy_project.restype = ci
+    lib.gspn_proxy_project_bwd.argtypes = [vp] * 6 + [ci] * 6 + [vp]
+    lib.gspn_proxy_project_bwd.restype = ci
     lib.gspn_proxy_plan.argtypes = [ci] * 6
     lib.gspn_proxy_plan.restype = ctypes.c_char_p
     lib.gspn_fwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu, ci]
@@ -252,6 +254,25 @@ def gspn_proxy_project(inp, P, out, *, stream=None) -> None:
     M = P.shape[0]
     args = [_ptr(inp, "inp", (B, K, H, W), inp), _ptr(P, "P", (M, K), inp), _ptr(out, "out", (B, M, H, W), inp)]
     _check(load_library().gspn_proxy_project(*args, B, K, M, H, W, _dtype_code(inp), _stream(stream)))
+
+
+def gspn_proxy_project_bwd(gout, inp, P, gin, gP, partial, *, stream=None) -> None:
+    """Gradients of gspn_proxy_project: gin[b, k] = sum_m P[m, k] * gout[b, m] per pixel (storage dtype, or None) and
+    gP[m, k] = sum over images and pixels of gout[b, m] * inp[b, k] (float32 [M,K], or None); partial: float32 [B,M,K]
+    workspace, required with gP.  gout [B,M,H,W]; inp [B,K,H,W]; P [M,K]; device tensors, contiguous."""
+    import torch
+    B, K, H, W = inp.shape
+    M = P.shape[0]
+    args = [_ptr(gout, "gout", (B, M, H, W), inp), _ptr(inp, "inp", (B, K, H, W), inp), _ptr(P, "P", (M, K), inp),
+            _ptr(gin, "gin", (B, K, H, W), inp)]
+    for t, name, shape in ((gP, "gP", (M, K)), (partial, "partial", (B, M, K))):
+        if t is None:
+            args.append(None)
+            continue
+        if not t.is_cuda or t.device != inp.device or t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError(f"{name}: must be a contiguous float32 device tensor of shape {shape}")
+        args.append(ctypes.c_void_p(t.data_ptr()))
+    _check(load_library().gspn_proxy_project_bwd(*args, B, K, M, H, W, _dtype_code(inp), _stream(stream)))
 
 
 def gspn_fwd_transposed_plan(B, C, H, W, G, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:

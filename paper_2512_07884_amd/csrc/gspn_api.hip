@@ -208,6 +208,19 @@ int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, i
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
 }
 
+int gspn_proxy_project_bwd(const void* gout, const void* in, const void* P, void* gin, float* gP, float* partial,
+                           int B, int K, int M, int H, int W, int dtype, void* stream) {
+    if (!gout || !in || !P || (!gin && !gP) || (gP && !partial)) return GSPN_ERR_NULL;
+    if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1) return GSPN_ERR_SHAPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
+    if ((long long)H * W >= (1ll << 31) || (long long)M * K >= (1ll << 31)) return GSPN_ERR_UNSUPPORTED;
+    if (misaligned(gout) || misaligned(in) || misaligned(P) || misaligned(gin) || misaligned(gP) || misaligned(partial))
+        return GSPN_ERR_ALIGN;
+    hipError_t e = launch_proxy_project_bwd(gout, in, P, gin, gP, partial, B, K, M, H * W, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
 const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype) {
     if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1 || (dtype != GSPN_F32 && dtype != GSPN_BF16)) return "invalid";
     if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE || (long long)H * W >= (1ll << 31)) return "invalid";

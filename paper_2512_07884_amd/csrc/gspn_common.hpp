@@ -181,6 +181,10 @@ hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s);
 // compressive proxy projection (gspn_proxy.hip): out[b][m][n] = sum_k P[m][k] in[b][k][n]
 hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int N, int dtype, hipStream_t s);
 bool proxy_mfma_applicable(int B, int K, int M, int N, int dtype);
+// ... and its gradients: gin[b][k][n] = sum_m P[m][k] gout[b][m][n] (NULL: skipped); gP[m][k] = sum_{b,n} gout[b][m][n] in[b][k][n]
+// (fp32, NULL: skipped; partial = B*M*K floats of the caller's)
+hipError_t launch_proxy_project_bwd(const void* gout, const void* in, const void* P, void* gin, float* gP, float* partial,
+                                    int B, int K, int M, int N, int dtype, hipStream_t s);
 
 // dispatch (gspn_dispatch.hip): picks the kernel family for the arguments
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);

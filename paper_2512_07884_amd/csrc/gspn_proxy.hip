@@ -26,7 +26,10 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 // KS = k values per MFMA: 8 (v_mfma_f32_32x32x8_bf16_1k) or 16 (v_mfma_f32_32x32x16_bf16, K a multiple of 16).
 // A lane feeds KS/2 consecutive k: lanes 0-31 the first half of the k-step, lanes 32-63 the second.
-template <int KS>
+// PT: the matrix is applied transposed, out[b][m][n] = sum_k P[k][m] * in[b][k][n] with P stored [K][M] (the gradient of
+// the projection w.r.t. its input): a lane then gathers its KS/2 values of P with 2-byte loads a row apart (P is small
+// and stays in cache).
+template <int KS, bool PT = false>
 __global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ P,
                                                          bf16_t* __restrict__ out, int B, int K, int M, int N,
                                                          int ntiles, int mtiles) {
@@ -66,7 +69,14 @@ __global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restric
         }
 #pragma unroll
         for (int i = 0; i < KL / 2; ++i) t.pa[i] = 0;
-        if (m_ok) {
+        if (m_ok && PT) {
+#pragma unroll
+            for (int i = 0; i < KL / 2; ++i) {
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(pb, (uint32_t)(((size_t)(kr + 2 * i) * M + m_lane) * 2), 0, 0);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(pb, (uint32_t)(((size_t)(kr + 2 * i + 1) * M + m_lane) * 2), 0, 0);
+                t.pa[i] = (lo & 0xffffu) | (hi << 16);
+            }
+        } else if (m_ok) {
             const uint32_t po = (uint32_t)(((size_t)m_lane * K + kr) * 2);
             if constexpr (KS == 8) { const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(pb, po, 0, 0); t.pa[0] = v.x; t.pa[1] = v.y; }
             else { const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(pb, po, 0, 0); t.pa[0] = v.x; t.pa[1] = v.y; t.pa[2] = v.z; t.pa[3] = v.w; }
@@ -117,7 +127,7 @@ __global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restric
 }
 
 // any shape, either storage type: one thread per pixel, eight output channels at a time
-template <typename T>
+template <typename T, bool PT = false>
 __global__ void __launch_bounds__(256) proxy_fma_kernel(const T* __restrict__ in, const T* __restrict__ P, T* __restrict__ out,
                                                         int B, int K, int M, int N) {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -131,12 +141,99 @@ __global__ void __launch_bounds__(256) proxy_fma_kernel(const T* __restrict__ in
             const float xv = ldf(x + (size_t)k * N);
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                if (m0 + j < M) acc[j] = fmaf(ldf(P + (size_t)(m0 + j) * K + k), xv, acc[j]);
+                if (m0 + j < M) acc[j] = fmaf(ldf(PT ? P + (size_t)k * M + (m0 + j) : P + (size_t)(m0 + j) * K + k), xv, acc[j]);
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             if (m0 + j < M) stf(y + (size_t)(m0 + j) * N, acc[j]);
     }
+}
+
+// ---- gradient w.r.t. the matrix: gP[m][k] = sum over b, n of gout[b][m][n] * in[b][k][n] ----------------------------
+// Both operands are contiguous along the contraction axis n, which is what the matrix cores want.  One workgroup per
+// (image, 32 x 32 tile of gP); its four waves take interleaved 16-pixel steps of n and add their accumulators through
+// LDS in wave order; the per-image sums go to the caller's workspace and a small kernel adds the images in order, so the
+// result does not depend on scheduling.
+__global__ void __launch_bounds__(256) proxy_gradw_mfma_kernel(const bf16_t* __restrict__ gout, const bf16_t* __restrict__ in,
+                                                               float* __restrict__ partial, int K, int M, int N,
+                                                               int mtiles, int ktiles) {
+    __shared__ float red[4][16][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int per_image = mtiles * ktiles;
+    const int b = blockIdx.x / per_image;
+    const int rem = blockIdx.x - b * per_image;
+    const int mt = rem / ktiles, kt = rem - mt * ktiles;
+    const int jl = lane & 31, nh = lane >> 5;                  // row of the operand this lane feeds; which 8 of the 16 pixels
+    const int m_lane = mt * 32 + jl, k_lane = kt * 32 + jl;
+    const bool m_ok = m_lane < M, k_ok = k_lane < K;
+    const rsrc_t gb = make_rsrc(gout + ((size_t)b * M + mt * 32) * N);      // the tile's 32 rows of gout / of in
+    const rsrc_t ib = make_rsrc(in + ((size_t)b * K + kt * 32) * N);
+    const uint32_t row_off = (uint32_t)((size_t)jl * N * 2);
+    f32x16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int n0 = wave * 16; n0 < N; n0 += 64) {               // N is a multiple of 16
+        const uint32_t off = row_off + (uint32_t)((n0 + 8 * nh) * 2);
+        u32x4 av = {0, 0, 0, 0}, bv = {0, 0, 0, 0};
+        if (m_ok) av = __builtin_amdgcn_raw_buffer_load_b128(gb, off, 0, 0);
+        if (k_ok) bv = __builtin_amdgcn_raw_buffer_load_b128(ib, off, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
+    __syncthreads();
+    // accumulator register r of a lane: row 8*(r/4) + 4*(lane/32) + r%4 of the tile (m), column lane%32 (k)
+    for (int idx = threadIdx.x; idx < 16 * 64; idx += 256) {
+        const int r = idx >> 6, l = idx & 63;
+        const float v = ((red[0][r][l] + red[1][r][l]) + red[2][r][l]) + red[3][r][l];
+        const int m = mt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), k = kt * 32 + (l & 31);
+        if (m < M && k < K) partial[((size_t)b * M + m) * K + k] = v;
+    }
+}
+
+// any shape, either storage type: a workgroup owns 8 rows x 32 columns of gP for one image and walks n in chunks of 64
+// staged through LDS (coalesced loads along n; pitch 65 keeps the per-thread walks conflict-free)
+template <typename T>
+__global__ void __launch_bounds__(256) proxy_gradw_fma_kernel(const T* __restrict__ gout, const T* __restrict__ in,
+                                                              float* __restrict__ partial, int K, int M, int N,
+                                                              int mtiles, int ktiles) {
+    __shared__ float gs[8][65], xs[32][65];
+    const int per_image = mtiles * ktiles;
+    const int b = blockIdx.x / per_image;
+    const int rem = blockIdx.x - b * per_image;
+    const int mt = rem / ktiles, kt = rem - mt * ktiles;
+    const int tm = threadIdx.x >> 5, tk = threadIdx.x & 31;    // this thread's element of the tile
+    const int col = threadIdx.x & 63, row4 = threadIdx.x >> 6; // loader: pixel inside the chunk, row group
+    float acc = 0.f;
+    for (int n0 = 0; n0 < N; n0 += 64) {
+        const int n = n0 + col;
+#pragma unroll
+        for (int r = row4; r < 8; r += 4) {
+            const int m = mt * 8 + r;
+            gs[r][col] = (m < M && n < N) ? ldf(gout + ((size_t)b * M + m) * N + n) : 0.f;
+        }
+#pragma unroll
+        for (int r = row4; r < 32; r += 4) {
+            const int k = kt * 32 + r;
+            xs[r][col] = (k < K && n < N) ? ldf(in + ((size_t)b * K + k) * N + n) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int j = 0; j < 64; ++j) acc = fmaf(gs[tm][j], xs[tk][j], acc);
+        __syncthreads();
+    }
+    const int m = mt * 8 + tm, k = kt * 32 + tk;
+    if (m < M && k < K) partial[((size_t)b * M + m) * K + k] = acc;
+}
+
+// gP = the per-image sums added in image order
+__global__ void __launch_bounds__(256) proxy_gradw_sum_kernel(const float* __restrict__ partial, float* __restrict__ gP, int B, int MK) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= MK) return;
+    float v = 0.f;
+    for (int b = 0; b < B; ++b) v += partial[(size_t)b * MK + i];
+    gP[i] = v;
 }
 
 }  // namespace
@@ -168,6 +265,58 @@ hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B,
     if (dtype == 0) hipLaunchKernelGGL(proxy_fma_kernel<float>, grid, block, 0, s, (const float*)in, (const float*)P, (float*)out, B, K, M, N);
     else hipLaunchKernelGGL(proxy_fma_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)in, (const bf16_t*)P, (bf16_t*)out, B, K, M, N);
     return hipGetLastError();
+}
+
+// Gradients of the projection (chain rule on the sum above): gin = P^T gout per pixel (storage type, may be NULL) and
+// gP = sum over images and pixels of gout in^T (fp32 [M, K], may be NULL; `partial` = B*M*K floats of the caller's).
+hipError_t launch_proxy_project_bwd(const void* gout, const void* in, const void* P, void* gin, float* gP, float* partial,
+                                    int B, int K, int M, int N, int dtype, hipStream_t s) {
+    if (gin) {
+        // the forward kernels with the matrix read transposed: K output channels, contraction over the M channels of gout
+        if (proxy_mfma_applicable(B, M, K, N, dtype)) {
+            const int ntiles = (N + 255) / 256, mtiles = (K + 31) / 32;
+            const long items = (long)B * ntiles * mtiles;
+            if ((items + 3) / 4 > 0x7fffffffl) return hipErrorInvalidValue;
+            const dim3 grid((unsigned)((items + 3) / 4)), block(256);
+            if (M % 16 == 0)
+                hipLaunchKernelGGL((proxy_mfma_kernel<16, true>), grid, block, 0, s, (const bf16_t*)gout, (const bf16_t*)P,
+                                   (bf16_t*)gin, B, M, K, N, ntiles, mtiles);
+            else
+                hipLaunchKernelGGL((proxy_mfma_kernel<8, true>), grid, block, 0, s, (const bf16_t*)gout, (const bf16_t*)P,
+                                   (bf16_t*)gin, B, M, K, N, ntiles, mtiles);
+        } else {
+            const long threads = (long)B * N;
+            if ((threads + 255) / 256 > 0x7fffffffl) return hipErrorInvalidValue;
+            const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+            if (dtype == 0) hipLaunchKernelGGL((proxy_fma_kernel<float, true>), grid, block, 0, s, (const float*)gout, (const float*)P, (float*)gin, B, M, K, N);
+            else hipLaunchKernelGGL((proxy_fma_kernel<bf16_t, true>), grid, block, 0, s, (const bf16_t*)gout, (const bf16_t*)P, (bf16_t*)gin, B, M, K, N);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (gP) {
+        if (!partial) return hipErrorInvalidValue;
+        const bool mfma = dtype == 1 && N % 16 == 0 && (size_t)N * 2 * 32 < (1ull << 31);
+        const int ktiles = (K + 31) / 32, mtiles = mfma ? (M + 31) / 32 : (M + 7) / 8;
+        const long blocks = (long)B * mtiles * ktiles;
+        if (blocks > 0x7fffffffl) return hipErrorInvalidValue;
+        if (mfma)
+            hipLaunchKernelGGL(proxy_gradw_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
+                               partial, K, M, N, mtiles, ktiles);
+        else if (dtype == 0)
+            hipLaunchKernelGGL(proxy_gradw_fma_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)gout, (const float*)in,
+                               partial, K, M, N, mtiles, ktiles);
+        else
+            hipLaunchKernelGGL(proxy_gradw_fma_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
+                               partial, K, M, N, mtiles, ktiles);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const int MK = M * K;
+        hipLaunchKernelGGL(proxy_gradw_sum_kernel, dim3((unsigned)((MK + 255) / 256)), dim3(256), 0, s, partial, gP, B, MK);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace gspn

@@ -80,3 +80,70 @@ def test_scan_wrapped_in_the_proxy():
                            WL.storage_to_f64(Pu, dtype))
     # three roundings to bf16 on the way (x_proxy, y_proxy, y): 3 * 2^-9 relative to intermediate maxima
     assert rel_inf_err(to_host_f64(y), ref) <= 2e-2
+
+
+# ---- gradients of the projection ------------------------------------------------------------------------------------
+def run_project_bwd(g_st, x_st, P_st, dtype, want_gin=True, want_gp=True):
+    import torch
+    import paper_2512_07884_amd as G
+    B, K, H, W = x_st.shape
+    M = P_st.shape[0]
+    gin = empty_like_dev((B, K, H, W), dtype, float("nan")) if want_gin else None
+    gP = torch.full((M, K), float("nan"), device="cuda", dtype=torch.float32) if want_gp else None
+    partial = torch.full((B, M, K), float("nan"), device="cuda", dtype=torch.float32) if want_gp else None
+    G.gspn_proxy_project_bwd(to_device(g_st, dtype), to_device(x_st, dtype), to_device(P_st, dtype), gin, gP, partial)
+    torch.cuda.synchronize()
+    return (to_host_f64(gin) if want_gin else None), (gP.double().cpu().numpy() if want_gp else None)
+
+
+# (B, K, M, H, W, dtype) as above: matrix-core kernels (M a multiple of 16 / of 8 for gin, H*W a multiple of 16 for gP),
+# plain kernels (fp32, C_proxy = 2, ragged pixel counts), several tiles of gP with ragged edges
+BWD_SHAPES = [(2, 96, 8, 56, 56, "bf16"), (2, 8, 96, 56, 56, "bf16"), (1, 96, 2, 28, 28, "bf16"), (1, 1152, 144, 16, 16, "bf16"),
+              (1, 144, 1152, 16, 16, "bf16"), (3, 40, 33, 12, 10, "bf16"), (1, 64, 70, 24, 40, "bf16"), (2, 96, 8, 28, 28, "f32"),
+              (1, 7, 5, 9, 13, "f32"), (1, 12, 3, 5, 7, "bf16"), (2, 40, 16, 12, 12, "bf16"), (2, 70, 24, 8, 6, "f32")]
+
+
+@pytest.mark.parametrize("shape", BWD_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_projection_gradients_match_the_oracle(shape):
+    B, K, M, H, W, dtype = shape
+    rng = np.random.default_rng([13, K, M, H])
+    x = WL.to_storage(rng.standard_normal((B, K, H, W)), dtype)
+    P = WL.to_storage(rng.standard_normal((M, K)) / np.sqrt(K), dtype)
+    g = WL.to_storage(rng.standard_normal((B, M, H, W)), dtype)
+    gin_ref, gP_ref = O.proxy_project_bwd(WL.storage_to_f64(g, dtype), WL.storage_to_f64(x, dtype), WL.storage_to_f64(P, dtype))
+    gin, gP = run_project_bwd(g, x, P, dtype)
+    assert rel_inf_err(gin, gin_ref) <= TOL[dtype], ("gin", rel_inf_err(gin, gin_ref))
+    # gP is accumulated and returned in fp32 whatever the storage type
+    assert rel_inf_err(gP, gP_ref) <= 1e-5, ("gP", rel_inf_err(gP, gP_ref))
+
+
+def test_projection_gradients_one_at_a_time_and_bitwise_repeatable():
+    rng = np.random.default_rng(17)
+    B, K, M, H, W = 3, 96, 8, 28, 28
+    x = WL.to_storage(rng.standard_normal((B, K, H, W)), "bf16")
+    P = WL.to_storage(rng.standard_normal((M, K)) / np.sqrt(K), "bf16")
+    g = WL.to_storage(rng.standard_normal((B, M, H, W)), "bf16")
+    gin, gP = run_project_bwd(g, x, P, "bf16")
+    gin_only, none = run_project_bwd(g, x, P, "bf16", want_gp=False)
+    none2, gP_only = run_project_bwd(g, x, P, "bf16", want_gin=False)
+    assert none is None and none2 is None
+    assert np.array_equal(gin, gin_only) and np.array_equal(gP, gP_only)
+    for _ in range(2):
+        gin2, gP2 = run_project_bwd(g, x, P, "bf16")
+        assert np.array_equal(gin, gin2) and np.array_equal(gP, gP2)
+
+
+def test_input_gradient_of_a_selection_matrix_is_a_copy():
+    """P with a single 1 per row: gin of the picked channels equals gout bit for bit, the other channels get 0 -- pins the
+    transposed read of P in the matrix-core kernel."""
+    rng = np.random.default_rng(19)
+    B, K, M, H, W = 2, 64, 16, 16, 24
+    g = WL.to_storage(rng.standard_normal((B, M, H, W)), "bf16")
+    x = WL.to_storage(rng.standard_normal((B, K, H, W)), "bf16")
+    pick = rng.permutation(K)[:M]
+    P = np.zeros((M, K))
+    P[np.arange(M), pick] = 1.0
+    gin, _ = run_project_bwd(g, x, WL.to_storage(P, "bf16"), "bf16", want_gp=False)
+    assert np.array_equal(gin[:, pick], WL.storage_to_f64(g, "bf16"))
+    rest = np.setdiff1d(np.arange(K), pick)
+    assert not gin[:, rest].any()

@@ -282,11 +282,30 @@ def proxy_table(steps: int = 50):
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
+        # its gradients: gin (reads gout, writes gin) and gP (reads gout and in; fp32 [M,K] through a [B,M,K] workspace)
+        gin = torch.empty(B, K, H, W, device="cuda", dtype=torch.bfloat16)
+        gP = torch.empty(M, K, device="cuda", dtype=torch.float32)
+        part = torch.empty(B, M, K, device="cuda", dtype=torch.float32)
+        bwd_ms = []
+        for want in ((gin, None, None), (None, gP, part)):
+            for i in range(5):
+                x_, P_, o_ = sets[i % nsets]
+                G.gspn_proxy_project_bwd(o_, x_, P_, *want)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(steps):
+                x_, P_, o_ = sets[i % nsets]
+                G.gspn_proxy_project_bwd(o_, x_, P_, *want)        # (the forward's output buffers serve as gout)
+            e1.record()
+            torch.cuda.synchronize()
+            bwd_ms.append(e0.elapsed_time(e1) / steps)
         rows.append({"projection": name, "B": B, "K": K, "M": M, "H": H, "W": W, "kernel": G.gspn_proxy_plan(B, K, M, H, W, 1),
                      "ms": ms, "bytes": nbytes, "GBs": nbytes / (ms * 1e-3) / 1e9,
                      "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "TFLOPs": 2.0 * B * K * M * H * W / (ms * 1e-3) / 1e12})
-        del sets
+                     "TFLOPs": 2.0 * B * K * M * H * W / (ms * 1e-3) / 1e12,
+                     "grad_input_ms": bwd_ms[0], "grad_input_GBs": nbytes / (bwd_ms[0] * 1e-3) / 1e9,
+                     "grad_weight_ms": bwd_ms[1], "grad_weight_GBs": nbytes / (bwd_ms[1] * 1e-3) / 1e9})
+        del sets, gin, gP, part
         torch.cuda.empty_cache()
     return rows
 

@@ -173,12 +173,21 @@ __global__ void __launch_bounds__(256) proxy_gradw_mfma_kernel(const bf16_t* __r
     f32x16_t acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    for (int n0 = wave * 16; n0 < N; n0 += 64) {               // N is a multiple of 16
-        const uint32_t off = row_off + (uint32_t)((n0 + 8 * nh) * 2);
-        u32x4 av = {0, 0, 0, 0}, bv = {0, 0, 0, 0};
-        if (m_ok) av = __builtin_amdgcn_raw_buffer_load_b128(gb, off, 0, 0);
-        if (k_ok) bv = __builtin_amdgcn_raw_buffer_load_b128(ib, off, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
+    // four 16-pixel steps per trip: their eight loads are requested together (N is a multiple of 16; steps past the end
+    // load nothing and multiply zeros)
+    for (int n0 = wave * 16; n0 < N; n0 += 256) {
+        u32x4 av[4], bv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int n = n0 + 64 * q;
+            const uint32_t off = row_off + (uint32_t)((n + 8 * nh) * 2);
+            av[q] = u32x4{0, 0, 0, 0}; bv[q] = u32x4{0, 0, 0, 0};
+            if (m_ok && n < N) av[q] = __builtin_amdgcn_raw_buffer_load_b128(gb, off, 0, 0);
+            if (k_ok && n < N) bv[q] = __builtin_amdgcn_raw_buffer_load_b128(ib, off, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[q]), __builtin_bit_cast(bf16x8_t, bv[q]), acc, 0, 0, 0);
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];

@@ -397,6 +397,17 @@ def proxy_scan_fwd(x, Pd, w, lam, u, Pu, dir_mask=15):
     return proxy_project(yp, Pu)
 
 
+def proxy_scan_bwd(gy, x, Pd, w, lam, u, Pu, dir_mask=15):
+    """Gradients through the wrapped scan (chain rule over its three stages, each with its own definition above):
+    returns (gx, gPd, gw, glam, gu, gPu) for y = proxy_scan_fwd(x, Pd, w, lam, u, Pu) and gy = dL/dy."""
+    xp = proxy_project(x, Pd)
+    yp, h = scan_fwd(xp, w, lam, u, dir_mask)
+    gyp, gPu = proxy_project_bwd(gy, yp, Pu)
+    gxp, gw, glam, gu = scan_bwd(gyp, xp, w, lam, u, h, dir_mask)
+    gx, gPd = proxy_project_bwd(gxp, x, Pd)
+    return gx, gPd, gw, glam, gu, gPu
+
+
 # --------------------------------------------------------------------------
 # dense forms used only to pin the scans on tiny inputs
 # --------------------------------------------------------------------------

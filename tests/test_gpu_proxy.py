@@ -147,3 +147,39 @@ def test_input_gradient_of_a_selection_matrix_is_a_copy():
     assert np.array_equal(gin[:, pick], WL.storage_to_f64(g, "bf16"))
     rest = np.setdiff1d(np.arange(K), pick)
     assert not gin[:, rest].any()
+
+
+def test_training_step_through_the_wrapped_scan():
+    """project down -> scan -> project up, and the gradients back through the three stages, all on the GPU path, against
+    the oracle's chain (fp32 storage: the intermediate tensors are rounded nowhere)."""
+    import torch
+    import paper_2512_07884_amd as G
+    B, C, Cp, H, W, dtype = 2, 24, 8, 28, 28, "f32"
+    cfg = WL.ScanConfig("proxytrain", B, Cp, H, W, 2, dtype, 15, 1.0, 23)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    rng = np.random.default_rng(24)
+    x = WL.to_storage(rng.standard_normal((B, C, H, W)), dtype)
+    Pd = WL.to_storage(rng.standard_normal((Cp, C)) / np.sqrt(C), dtype)
+    Pu = WL.to_storage(rng.standard_normal((C, Cp)) / np.sqrt(Cp), dtype)
+    gy = WL.to_storage(rng.standard_normal((B, C, H, W)), dtype)
+    d = {k: to_device(v, dtype) for k, v in inp.items()}
+    dx, dPd, dPu, dgy = (to_device(a, dtype) for a in (x, Pd, Pu, gy))
+    new = lambda *shape: torch.full(shape, float("nan"), device="cuda", dtype=torch.float32)
+    xp, yp, y, hs = new(B, Cp, H, W), new(B, Cp, H, W), new(B, C, H, W), new(4, B, Cp, H, W)
+    G.gspn_proxy_project(dx, dPd, xp)
+    G.gspn_scan_fwd(xp, d["w"], d["lam"], d["u"], yp, hs, G=cfg.G)
+    G.gspn_proxy_project(yp, dPu, y)
+    gyp, gPu, part_u = new(B, Cp, H, W), new(C, Cp), new(B, C, Cp)
+    G.gspn_proxy_project_bwd(dgy, yp, dPu, gyp, gPu, part_u)
+    gxp, gw, glam, gu = new(B, Cp, H, W), torch.full_like(d["w"], float("nan")), new(4, B, Cp, H, W), new(4, B, Cp, H, W)
+    G.gspn_scan_bwd(gyp, xp, d["w"], d["lam"], d["u"], hs, gxp, gw, glam, gu, G=cfg.G)
+    gx, gPd, part_d = new(B, C, H, W), new(Cp, C), new(B, Cp, C)
+    G.gspn_proxy_project_bwd(gxp, dx, dPd, gx, gPd, part_d)
+    torch.cuda.synchronize()
+    f = WL.inputs_as_f64(inp, dtype)
+    ref = O.proxy_scan_bwd(gy.astype(np.float64), x.astype(np.float64), Pd.astype(np.float64), f["w"], f["lam"], f["u"],
+                           Pu.astype(np.float64))
+    got = (gx, gPd, gw, glam, gu, gPu)
+    for name, a, r in zip(("gx", "gPd", "gw", "glam", "gu", "gPu"), got, ref):
+        e = rel_inf_err(a.double().cpu().numpy(), r)
+        assert e <= 2e-5, (name, e)

@@ -89,3 +89,23 @@ def test_projection_gradient_of_a_selection_matrix():
     assert np.array_equal(gin[:, 4], g[:, 0]) and np.array_equal(gin[:, 1], -2.0 * g[:, 1])
     assert not gin[:, [0, 2, 3, 5]].any()
     assert np.isclose(gP[0, 4], np.sum(g[:, 0] * x[:, 4])) and np.isclose(gP[1, 0], np.sum(g[:, 1] * x[:, 0]))
+
+
+def test_gradients_through_the_wrapped_scan_against_finite_differences():
+    from test_oracle_forward import rand_problem
+    rng = np.random.default_rng(6)
+    B, C, Cp, H, W = 1, 5, 2, 3, 4
+    x = rng.standard_normal((B, C, H, W))
+    Pd = rng.standard_normal((Cp, C)); Pu = rng.standard_normal((C, Cp))
+    _, w, lam, u = rand_problem(rng, B, Cp, H, W, 1)
+    gy = rng.standard_normal((B, C, H, W))
+    gx, gPd, gw, glam, gu, gPu = O.proxy_scan_bwd(gy, x, Pd, w, lam, u, Pu)
+    loss = lambda **kw: float(np.sum(gy * O.proxy_scan_fwd(kw.get("x", x), kw.get("Pd", Pd), kw.get("w", w), kw.get("lam", lam),
+                                                           kw.get("u", u), kw.get("Pu", Pu))))
+    eps = 1e-6
+    for name, base, grad in (("x", x, gx), ("Pd", Pd, gPd), ("Pu", Pu, gPu), ("lam", lam, glam), ("u", u, gu)):
+        for _ in range(4):
+            idx = tuple(int(rng.integers(n)) for n in base.shape)
+            d = np.zeros_like(base); d[idx] = eps
+            fd = (loss(**{name: base + d}) - loss(**{name: base - d})) / (2 * eps)
+            assert abs(fd - grad[idx]) < 1e-7 * max(1.0, abs(fd)), (name, idx, fd, grad[idx])

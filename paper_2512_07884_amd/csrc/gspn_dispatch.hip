@@ -23,8 +23,9 @@ static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
     const char* np = getenv("GSPN_BWD_NO_PLANE");     // testing aid: keep the other kernels reachable on tiny maps
     if (!(np && np[0] == '1') && bwd_plane_applicable(p, dtype)) {
         // the single-launch plane kernel, except where the two passes were measured faster: bf16 storage, shared
-        // weights, lines of more than 16 positions (28x28x192, B = 64, G = 8: 382 -> 270 us; the other stages of that
-        // classifier and the fp32 maps run as fast or faster on the plane kernel)
+        // weights, lines of more than 16 positions (28x28x192, B = 64, G = 8: 382 -> 270 us; B = 32, G = 4, where a bf16
+        // group cannot be split over workgroups: 1401 -> 177 us; 32x32x256 G = 16: 250 -> 73 us; the shorter lines of
+        // the later classifier stages and the fp32 maps run as fast or faster on the plane kernel)
         const int m = p.H > p.W ? p.H : p.W;
         if (twopass && dtype == 1 && p.cpg > 1 && m > 16) return BWD_TWOPASS;
         return BWD_PLANE;

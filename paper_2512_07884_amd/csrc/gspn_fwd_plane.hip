@@ -82,16 +82,21 @@ struct FwdPlaneArgs {
 // against its scan order, and a position multiplies its state by the taps of the line swept before and hands the
 // products to the positions those taps read from (e_t = u_t*gy_t + T_{t+1}^T e_{t+1}).  The taps that are stored as 0
 // (out-of-line neighbours, GSPN-local: lines that start a stretch) are the ones that must pass nothing on here too.
-template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL, bool BWD = false>
+// NCHT: 16 B chunks per lane the register arrays are sized for (8: the wave's channels hold at most 8 KB; 4: small maps
+// of the flat variant, which then has the registers to give its LDS planes an odd pitch too -- every element's place is
+// tracked through two bit masks per chunk)
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL, bool BWD = false, int NCHT = 8>
 __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneArgs a) {
     static_assert(!(FLAT && WPRE), "the flat variant fetches its weights in place");
+    static_assert(NCHT == 8 || (NCHT == 4 && FLAT), "the short register arrays are for small maps of the flat variant");
+    constexpr bool PADFLAT = FLAT && NCHT == 4;    // flat variant with padded LDS planes
     static_assert(!BWD || SAVE, "the reverse sweep saves its state");
     constexpr int E = 16 / (int)sizeof(T);        // elements per 16 B chunk
-    constexpr int NCH = 8;                        // chunks per lane: the wave's channels hold at most 8 KB
+    constexpr int NCH = NCHT;                     // chunks per lane
     constexpr int WSH = 4;                        // weight chunks per thread (shared weights)
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W, HW = H * W, P = a.pitch;
-    const int HP = FLAT ? HW : (H * P + 3) & ~3;       // floats per plane region in LDS (16 B granules when padded)
+    const int HP = (FLAT && !PADFLAT) ? HW : (H * P + 3) & ~3;   // floats per plane region in LDS (16 B granules when padded)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int cpw = a.cpw;
@@ -117,15 +122,30 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
 
     // flat layout: chunk q = k*64 + lane covers elements [q*E, q*E + E) of the wave's channels
     bool vq[NCH];
-    int rc[NCH];          // row*P + col of the chunk's first element
+    int rc[NCH];          // row*P + col of the chunk's first element (padded flat variant: plus its channel's region)
     int ch[NCH];          // channel of the wave (0 / 1) the chunk belongs to
     int row0[NCH], col0[NCH];
+    // padded flat variant: a chunk may run over the end of a row and of a channel: bit e set <=> element e of the chunk is
+    // the last of its row / of its channel, i.e. the next element's place in LDS is further by the row / region padding
+    uint32_t rowend[NCH], chend[NCH];
 #pragma unroll
     for (int k = 0; k < NCH; ++k) {
         const int q = k * 64 + lane;
         vq[k] = q < n16;
         const int idx0 = vq[k] ? q * E : 0;
-        if constexpr (FLAT) {
+        rowend[k] = 0; chend[k] = 0;
+        if constexpr (PADFLAT) {
+            const int c = idx0 / HW, rem = idx0 - c * HW;
+            int row = rem / W, col = rem - row * W;
+            ch[k] = 0; rc[k] = c * HP + row * P + col; row0[k] = 0; col0[k] = 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                if (++col == W) {
+                    col = 0; rowend[k] |= 1u << e;
+                    if (++row == H) { row = 0; chend[k] |= 1u << e; }
+                }
+            }
+        } else if constexpr (FLAT) {
             ch[k] = 0; rc[k] = idx0; row0[k] = 0; col0[k] = 0;     // LDS offset = offset in memory
         } else {
             ch[k] = idx0 >= HW ? 1 : 0;
@@ -136,6 +156,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         }
     }
     const uint32_t flat = (uint32_t)lane * 16u;
+    const uint32_t row_pad4 = 4u * (uint32_t)(P - W), ch_pad4 = 4u * (uint32_t)(HP - H * P);   // padded flat variant: bytes skipped at a row / channel end
     auto ldg = [&](rsrc_t rs, uint32_t vo, int so) -> u32x4 { return __builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0); };
     auto load_planes = [&](const T* basep, u32x4 (&st)[NCH]) {
         const rsrc_t rs = make_rsrc(basep);
@@ -252,7 +273,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                         // a tap that points outside the line is stored as 0, whatever the tensor holds there
                         const int pos = vert ? col : row;
                         const bool outside = (tap == 0 && pos == 0) || (tap == 2 && pos == L - 1) || no_pred(row, col);
-                        plds_st(wreg + 4u * (uint32_t)(chn * 4 * HP + 4 * (row * W + col) + tap),
+                        plds_st(wreg + 4u * (uint32_t)(chn * 4 * HP + 4 * (row * P + col) + tap),
                                 outside ? masked : chunk_elem<T>(v, e));
                         if (++col == W) { col = 0; if (++row == H) { row = 0; if (++tap == 3) { tap = 0; ++chn; } } }
                     }
@@ -320,9 +341,16 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
             if (vq[k]) {
-                const uint32_t o = ahreg + 4u * (uint32_t)(ch[k] * HP + rc[k]);
+                uint32_t o = ahreg + 4u * (uint32_t)(ch[k] * HP + rc[k]);
 #pragma unroll
-                for (int e = 0; e < E; ++e) plds_st(o + 4u * e, chunk_elem<T>(ls[k], e) * chunk_elem<T>(xs[k], e));
+                for (int e = 0; e < E; ++e) {
+                    if constexpr (PADFLAT) {
+                        plds_st(o, chunk_elem<T>(ls[k], e) * chunk_elem<T>(xs[k], e));
+                        o += 4u + (((rowend[k] >> e) & 1u) ? row_pad4 : 0u) + (((chend[k] >> e) & 1u) ? ch_pad4 : 0u);
+                    } else {
+                        plds_st(o + 4u * e, chunk_elem<T>(ls[k], e) * chunk_elem<T>(xs[k], e));
+                    }
+                }
             }
         }
         // requests for after the sweep (u) and for the next direction (lam, shared weights)
@@ -408,11 +436,16 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
 #pragma unroll
             for (int k = 0; k < NCH; ++k) {
                 if (vq[k]) {
-                    const uint32_t o = ahreg + 4u * (uint32_t)(ch[k] * HP + rc[k]);
+                    uint32_t o = ahreg + 4u * (uint32_t)(ch[k] * HP + rc[k]);
                     float hv[E];
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
-                        hv[e] = plds_ld(o + 4u * e);
+                        if constexpr (PADFLAT) {
+                            hv[e] = plds_ld(o);
+                            o += 4u + (((rowend[k] >> e) & 1u) ? row_pad4 : 0u) + (((chend[k] >> e) & 1u) ? ch_pad4 : 0u);
+                        } else {
+                            hv[e] = plds_ld(o + 4u * e);
+                        }
                         y[k][e] = fmaf(chunk_elem<T>(us[k], e), hv[e], y[k][e]);
                     }
                     if constexpr (SAVE) st_b128(hb, flat + k * 1024, chunk_pack<T>(hv));
@@ -436,7 +469,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
 // ---------------------------------------------------------------------------
 static constexpr int FPLANE_LDS_BUDGET = 160 * 1024;
 
-struct FwdPlanePlan { bool ok, flat; int K, cpw, lsh, nwaves, pitch, shared_group, wlw; size_t lds; };
+struct FwdPlanePlan { bool ok, flat, small; int K, cpw, lsh, nwaves, pitch, shared_group, wlw; size_t lds; };
 
 // waves per workgroup and LDS bytes, given the channels per wave and the bytes of one fp32 plane region
 static bool plan_fwd_plane_waves(const FwdParams& p, FwdPlanePlan& t, size_t hp) {
@@ -496,24 +529,34 @@ static FwdPlanePlan plan_fwd_plane(const FwdParams& p, int dtype) {
         break;
     }
     if (!t.cpw) return t;
-    t.pitch = p.W;
+    // small maps (at most four 16 B chunks per lane) get an odd pitch like the padded variant; larger ones keep rows packed
+    t.small = (size_t)t.cpw * HW * es <= 4 * 64 * 16;
+    t.pitch = t.small ? (p.W | 1) : p.W;
     // shared weights: the widest request that divides a group's block (its start is a multiple of its size)
     const size_t wblock = (size_t)3 * HW * es;
     t.wlw = wblock % 16 == 0 ? 16 : wblock % 8 == 0 ? 8 : wblock % 4 == 0 ? 4 : 2;
-    t.ok = plan_fwd_plane_waves(p, t, (size_t)HW * sizeof(float));
+    t.ok = plan_fwd_plane_waves(p, t, t.small ? (((size_t)p.H * t.pitch + 3) & ~(size_t)3) * sizeof(float) : (size_t)HW * sizeof(float));
     return t;
 }
 
 bool fwd_plane_applicable(const FwdParams& p, int dtype) { return plan_fwd_plane(p, dtype).ok; }
 
-template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL, bool BWD = false>
-static hipError_t launch_fplane_kl(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
-    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE, FLAT, LOCAL, BWD>;
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL, bool BWD, int NCH>
+static hipError_t launch_fplane_kn(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    auto k = fwd_plane_kernel<T, SAVE, SHARED, WPRE, FLAT, LOCAL, BWD, NCH>;
     hipError_t e = allow_dynamic_lds((const void*)k, FPLANE_LDS_BUDGET);
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / a.K))), block(64 * a.nwaves);
     hipLaunchKernelGGL(k, grid, block, t.lds, s, a);
     return hipGetLastError();
+}
+
+template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT, bool LOCAL, bool BWD = false>
+static hipError_t launch_fplane_kl(const FwdPlaneArgs& a, const FwdPlanePlan& t, hipStream_t s) {
+    if constexpr (FLAT) {
+        if (t.small) return launch_fplane_kn<T, SAVE, SHARED, WPRE, FLAT, LOCAL, BWD, 4>(a, t, s);
+    }
+    return launch_fplane_kn<T, SAVE, SHARED, WPRE, FLAT, LOCAL, BWD, 8>(a, t, s);
 }
 
 template <typename T, bool SAVE, bool SHARED, bool WPRE, bool FLAT>

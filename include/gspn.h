@@ -189,8 +189,8 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 /* Name of the kernel family the forward / backward call would dispatch to for
  * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
  * merged output fits in LDS), "stream" (larger maps, forward only), "twopass" (backward
- * on maps the forward tile or stream kernels take and the single-launch backward
- * kernels do not: the reverse sweep per channel, then the sum over each group's channels; in bf16
+ * on the maps the forward plane, tile or stream kernels take: the reverse sweep per
+ * channel on those kernels, then the sum over each group's channels; in bf16
  * storage e passes through storage precision between the two), "generic" (any shape);
  * static string, never NULL.  Host only.
  *
@@ -200,7 +200,9 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
  *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps)
  *   GSPN_TILE_K=<n>, GSPN_TILE_HV=<0..3>   forward tile kernel: channels per
- *       workgroup / horizontal-phase variant (ignored when they do not fit) */
+ *       workgroup / horizontal-phase variant (ignored when they do not fit)
+ *   GSPN_BWD_NO_BIG_BURSTS=1   backward tile kernel: 16-byte row bursts only
+ *   GSPN_PROXY_GRADW_WAVES=4|8   gspn_proxy_project_bwd: waves per tile of gP */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);
 const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
 /* the same for the GSPN-local calls */

@@ -151,13 +151,14 @@ __global__ void __launch_bounds__(256) proxy_fma_kernel(const T* __restrict__ in
 
 // ---- gradient w.r.t. the matrix: gP[m][k] = sum over b, n of gout[b][m][n] * in[b][k][n] ----------------------------
 // Both operands are contiguous along the contraction axis n, which is what the matrix cores want.  One workgroup per
-// (image, 32 x 32 tile of gP); its four waves take interleaved 16-pixel steps of n and add their accumulators through
+// (image, 32 x 32 tile of gP); its NW waves take interleaved 16-pixel steps of n and add their accumulators through
 // LDS in wave order; the per-image sums go to the caller's workspace and a small kernel adds the images in order, so the
-// result does not depend on scheduling.
-__global__ void __launch_bounds__(256) proxy_gradw_mfma_kernel(const bf16_t* __restrict__ gout, const bf16_t* __restrict__ in,
+// result does not depend on scheduling.  NW = 8 where four waves per tile would leave the chip short of loads in flight.
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) proxy_gradw_mfma_kernel(const bf16_t* __restrict__ gout, const bf16_t* __restrict__ in,
                                                                float* __restrict__ partial, int K, int M, int N,
                                                                int mtiles, int ktiles) {
-    __shared__ float red[4][16][64];
+    __shared__ float red[NW][16][64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int per_image = mtiles * ktiles;
@@ -175,11 +176,11 @@ __global__ void __launch_bounds__(256) proxy_gradw_mfma_kernel(const bf16_t* __r
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // four 16-pixel steps per trip: their eight loads are requested together (N is a multiple of 16; steps past the end
     // load nothing and multiply zeros)
-    for (int n0 = wave * 16; n0 < N; n0 += 256) {
+    for (int n0 = wave * 16; n0 < N; n0 += 64 * NW) {
         u32x4 av[4], bv[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int n = n0 + 64 * q;
+            const int n = n0 + 16 * NW * q;
             const uint32_t off = row_off + (uint32_t)((n + 8 * nh) * 2);
             av[q] = u32x4{0, 0, 0, 0}; bv[q] = u32x4{0, 0, 0, 0};
             if (m_ok && n < N) av[q] = __builtin_amdgcn_raw_buffer_load_b128(gb, off, 0, 0);
@@ -193,9 +194,11 @@ __global__ void __launch_bounds__(256) proxy_gradw_mfma_kernel(const bf16_t* __r
     for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
     __syncthreads();
     // accumulator register r of a lane: row 8*(r/4) + 4*(lane/32) + r%4 of the tile (m), column lane%32 (k)
-    for (int idx = threadIdx.x; idx < 16 * 64; idx += 256) {
+    for (int idx = threadIdx.x; idx < 16 * 64; idx += 64 * NW) {
         const int r = idx >> 6, l = idx & 63;
-        const float v = ((red[0][r][l] + red[1][r][l]) + red[2][r][l]) + red[3][r][l];
+        float v = red[0][r][l];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) v += red[w][r][l];
         const int m = mt * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3), k = kt * 32 + (l & 31);
         if (m < M && k < K) partial[((size_t)b * M + m) * K + k] = v;
     }
@@ -241,7 +244,14 @@ __global__ void __launch_bounds__(256) proxy_gradw_sum_kernel(const float* __res
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= MK) return;
     float v = 0.f;
-    for (int b = 0; b < B; ++b) v += partial[(size_t)b * MK + i];
+    // sixteen images requested at a time (the loads do not depend on the sum), then added in order
+    for (int b0 = 0; b0 < B; b0 += 16) {
+        float t[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) t[j] = b0 + j < B ? partial[(size_t)(b0 + j) * MK + i] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) if (b0 + j < B) v += t[j];
+    }
     gP[i] = v;
 }
 
@@ -309,8 +319,14 @@ hipError_t launch_proxy_project_bwd(const void* gout, const void* in, const void
         const int ktiles = (K + 31) / 32, mtiles = mfma ? (M + 31) / 32 : (M + 7) / 8;
         const long blocks = (long)B * mtiles * ktiles;
         if (blocks > 0x7fffffffl) return hipErrorInvalidValue;
-        if (mfma)
-            hipLaunchKernelGGL(proxy_gradw_mfma_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
+        const char* nw_v = getenv("GSPN_PROXY_GRADW_WAVES");            // tuning aid: force 4 or 8 waves per tile
+        const int nw_env = nw_v ? atoi(nw_v) : 0;
+        const bool wide = nw_env ? nw_env == 8 : blocks * 4 < 2048;     // fewer than 8 waves per compute unit otherwise
+        if (mfma && wide)
+            hipLaunchKernelGGL(proxy_gradw_mfma_kernel<8>, dim3((unsigned)blocks), dim3(512), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
+                               partial, K, M, N, mtiles, ktiles);
+        else if (mfma)
+            hipLaunchKernelGGL(proxy_gradw_mfma_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
                                partial, K, M, N, mtiles, ktiles);
         else if (dtype == 0)
             hipLaunchKernelGGL(proxy_gradw_fma_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)gout, (const float*)in,

@@ -117,6 +117,23 @@ def test_projection_gradients_match_the_oracle(shape):
     assert rel_inf_err(gP, gP_ref) <= 1e-5, ("gP", rel_inf_err(gP, gP_ref))
 
 
+@pytest.mark.parametrize("waves", ["4", "8"])
+def test_weight_gradient_with_either_wave_count_and_more_images_than_one_batch_of_the_sum(waves, monkeypatch):
+    # 19 images: the kernel that adds the per-image sums asks for 16 at a time and has a ragged second batch;
+    # the tile kernel's two instantiations are forced in turn
+    monkeypatch.setenv("GSPN_PROXY_GRADW_WAVES", waves)
+    B, K, M, H, W = 19, 40, 33, 12, 12
+    rng = np.random.default_rng([19, int(waves)])
+    x = WL.to_storage(rng.standard_normal((B, K, H, W)), "bf16")
+    P = WL.to_storage(rng.standard_normal((M, K)) / np.sqrt(K), "bf16")
+    g = WL.to_storage(rng.standard_normal((B, M, H, W)), "bf16")
+    _, gP_ref = O.proxy_project_bwd(WL.storage_to_f64(g, "bf16"), WL.storage_to_f64(x, "bf16"), WL.storage_to_f64(P, "bf16"))
+    _, gP = run_project_bwd(g, x, P, "bf16", want_gin=False)
+    assert rel_inf_err(gP, gP_ref) <= 1e-5, rel_inf_err(gP, gP_ref)
+    _, gP2 = run_project_bwd(g, x, P, "bf16", want_gin=False)
+    assert np.array_equal(gP, gP2)
+
+
 def test_projection_gradients_one_at_a_time_and_bitwise_repeatable():
     rng = np.random.default_rng(17)
     B, K, M, H, W = 3, 96, 8, 28, 28

@@ -337,7 +337,7 @@ def main():
     ap.add_argument("--proxy", action="store_true",
                     help="also time the compressive proxy projections (table under detail.proxy_projections)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
-    ap.add_argument("--out", default="gpurun_out", help="folder for the --all table, relative to the repository root")
+    ap.add_argument("--out", default="bench_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain 1 GiB device-to-device copies (known traffic, for scaling profiler counters)")

@@ -111,8 +111,8 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
  * (y = sum over directions of u*lam*x).  kchunk < 1 is GSPN_ERR_SHAPE.  Everything else (layouts,
  * ownership, stream semantics, errors) is as for gspn_scan_fwd / gspn_scan_bwd, and h_save written by
  * the local forward call is what the local backward call with the same kchunk expects.
- * Maps with H, W <= 64 (forward) / <= 32 (backward) run on the "plane" kernels at the speed of the
- * global scan; other shapes take the "generic" kernels. */
+ * Every kernel family has local instantiations, so a local call runs on the same family as the global
+ * call of its shape (gspn_fwd_local_plan / gspn_bwd_local_plan name it). */
 int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const void* u,
                         void* y, void* h_save,
                         int B, int C, int H, int W, int G, int kchunk,
@@ -194,15 +194,12 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  * storage e passes through storage precision between the two), "generic" (any shape);
  * static string, never NULL.  Host only.
  *
- * Environment variables read at every call, for tests and tuning (results are the
- * same whichever kernel runs, up to the rounding of the storage type):
+ * Environment variables for tests (results are the same whichever kernel runs, up to the rounding of
+ * the storage type).  They are read once per process, by the first call that dispatches; a process
+ * that changes them afterwards calls gspn_reload_env():
  *   GSPN_FORCE_GENERIC=1   always the generic kernels
  *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
- *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps)
- *   GSPN_TILE_K=<n>, GSPN_TILE_HV=<0..3>   forward tile kernel: channels per
- *       workgroup / horizontal-phase variant (ignored when they do not fit)
- *   GSPN_BWD_NO_BIG_BURSTS=1   backward tile kernel: 16-byte row bursts only
- *   GSPN_PROXY_GRADW_WAVES=4|8   gspn_proxy_project_bwd: waves per tile of gP */
+ *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps) */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);
 const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
 /* the same for the GSPN-local calls */
@@ -221,6 +218,10 @@ const char* gspn_status_string(int status);
 
 /* Library version: major*10000 + minor*100 + patch. */
 int gspn_version(void);
+
+/* Reads the GSPN_* environment variables listed above again (host only, thread-safe; calls already
+ * enqueued are not affected). */
+void gspn_reload_env(void);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,7 @@ EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_b
            "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
            "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_project_bwd", "gspn_proxy_plan",
            "gspn_scan_fwd_transposed", "gspn_fwd_transposed_plan",
-           "gspn_status_string", "gspn_version")
+           "gspn_status_string", "gspn_version", "gspn_reload_env")
 
 
 class GspnError(RuntimeError):
@@ -89,12 +89,19 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_status_string.restype = ctypes.c_char_p
     lib.gspn_version.argtypes = []
     lib.gspn_version.restype = ci
+    lib.gspn_reload_env.argtypes = []
+    lib.gspn_reload_env.restype = None
     _LIB = lib
     return lib
 
 
 def gspn_status_string(status: int) -> str:
     return load_library().gspn_status_string(int(status)).decode()
+
+
+def gspn_reload_env() -> None:
+    """Makes the library read its GSPN_* environment variables again (it reads them once otherwise)."""
+    load_library().gspn_reload_env()
 
 
 def gspn_version() -> int:

@@ -240,6 +240,8 @@ const char* gspn_status_string(int status) {
     }
 }
 
-int gspn_version(void) { return 200; }   // 0.2.0: GSPN-local and logits entry points
+int gspn_version(void) { return 300; }   // 0.3.0: testing aids read once (gspn_reload_env)
+
+void gspn_reload_env(void) { reload_env_knobs(); }
 
 }  // extern "C"

@@ -676,7 +676,7 @@ hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s) {
     // rows that are multiples of 112 B (56 columns of bf16; 28, 56 of fp32) or of 64 / 128 B (32 columns), workgroups
     // of up to 4 waves: 56 / 64 B (bf16) or 112 / 128 B (fp32) per row and request -- the whole register file of a SIMD
     // goes to the one wave it runs
-    const bool big = t.nwaves <= 4 && !p.logits && !getenv("GSPN_BWD_NO_BIG_BURSTS");
+    const bool big = t.nwaves <= 4 && !p.logits;
     const bool burst28 = big && (p.W * (dtype == 0 ? 4 : 2)) % 112 == 0, burst32 = big && !burst28 && p.W % 32 == 0;
     void (*k)(BwdTileArgs);
     if (burst28) {

@@ -127,11 +127,12 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
 #pragma unroll
     for (int v = 0; v < VEC; ++v) { a0[v] = 0.f; a1[v] = 0.f; a2[v] = 0.f; }
     // GSPN-local (Sec. 3.2): a pixel on a line that starts a stretch has no previous line (its taps were never read)
-    bool starts[VEC];
+    bool starts[VEC], first_step[VEC];      // first_step: the first line of the whole scan (no previous line either)
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
         const int r = vert ? i : j0 + v, S = vert ? H : W;        // image line along the scan axis
         starts[v] = p.kchunk > 0 && starts_stretch((d & 1) ? S - 1 - r : r, S, d & 1, p.kchunk);
+        first_step[v] = ((d & 1) ? S - 1 - r : r) == 0;
     }
 
     for (int ci = 0; ci < p.cpg; ++ci) {
@@ -187,6 +188,11 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             const int pos = vert ? j0 + v : i, L = vert ? W : H;      // position on the line
+            // a line without a predecessor never reads its logits: whatever they hold (NaN, Inf) stays out and
+            // their gradient is an exact 0
+            const bool unread = starts[v] || first_step[v];
+            z0[v] = unread ? 0.f : z0[v]; z1[v] = unread ? 0.f : z1[v]; z2[v] = unread ? 0.f : z2[v];
+            a0[v] = unread ? 0.f : a0[v]; a1[v] = unread ? 0.f : a1[v]; a2[v] = unread ? 0.f : a2[v];
             softmax3(z0[v], z1[v], z2[v], pos == 0, pos == L - 1);
             softmax3_grad(a0[v], a1[v], a2[v], z0[v], z1[v], z2[v]);
         }

@@ -191,5 +191,6 @@ hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s);
 const char* fwd_plan_name(const FwdParams& p, int dtype);
 const char* bwd_plan_name(const BwdParams& p, int dtype);
+void reload_env_knobs();   // re-reads the GSPN_* testing aids from the environment (they are read once otherwise)
 
 }  // namespace gspn

@@ -1,27 +1,48 @@
 // Chooses the kernel family for a call.  Host code only.
 #include "gspn_common.hpp"
 #include <stdlib.h>
+#include <atomic>
 
 namespace gspn {
 
 enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1, FWD_STREAM = 2, FWD_PLANE = 3 };
 enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1, BWD_PLANE = 2, BWD_TWOPASS = 3 };
 
+// Testing aids that keep every kernel family reachable on every shape it accepts.  The environment is read once, on
+// the first call of a process (and again only when reload_env_knobs() is called, which the tests do after they change
+// it): a launch costs one atomic load, and no call races with a setenv elsewhere in the process.
+// GSPN_FORCE_GENERIC=1: the generic kernels; GSPN_FWD_NO_PLANE=1 / GSPN_BWD_NO_PLANE=1: skip the plane kernels;
+// GSPN_BWD_NO_TWOPASS=1: skip the two-pass backward.
+enum : unsigned { K_FORCE_GENERIC = 1, K_FWD_NO_PLANE = 2, K_BWD_NO_PLANE = 4, K_BWD_NO_TWOPASS = 8, K_VALID = 1u << 31 };
+static std::atomic<unsigned> g_knobs{0};
+static bool env_flag(const char* name) { const char* v = getenv(name); return v && v[0] == '1'; }
+void reload_env_knobs() {
+    unsigned k = K_VALID;
+    if (env_flag("GSPN_FORCE_GENERIC")) k |= K_FORCE_GENERIC;
+    if (env_flag("GSPN_FWD_NO_PLANE")) k |= K_FWD_NO_PLANE;
+    if (env_flag("GSPN_BWD_NO_PLANE")) k |= K_BWD_NO_PLANE;
+    if (env_flag("GSPN_BWD_NO_TWOPASS")) k |= K_BWD_NO_TWOPASS;
+    g_knobs.store(k, std::memory_order_release);
+}
+struct Knobs { bool force_generic, fwd_no_plane, bwd_no_plane, bwd_no_twopass; };
+static Knobs knobs() {
+    unsigned k = g_knobs.load(std::memory_order_acquire);
+    if (!(k & K_VALID)) { reload_env_knobs(); k = g_knobs.load(std::memory_order_acquire); }
+    return Knobs{(k & K_FORCE_GENERIC) != 0, (k & K_FWD_NO_PLANE) != 0, (k & K_BWD_NO_PLANE) != 0, (k & K_BWD_NO_TWOPASS) != 0};
+}
+
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
-    const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
-    if (f && f[0] == '1') return FWD_GENERIC;
-    const char* np = getenv("GSPN_FWD_NO_PLANE");     // testing aid: keep the tile kernel reachable on small maps
-    if (!(np && np[0] == '1') && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
+    const Knobs k = knobs();
+    if (k.force_generic) return FWD_GENERIC;
+    if (!k.fwd_no_plane && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
     if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
     return fwd_stream_applicable(p, dtype) ? FWD_STREAM : FWD_GENERIC;
 }
 static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
-    const char* f = getenv("GSPN_FORCE_GENERIC");     // testing aid
-    if (f && f[0] == '1') return BWD_GENERIC;
-    const char* nt = getenv("GSPN_BWD_NO_TWOPASS");   // testing aid: keep the plane, tile and generic kernels reachable
-    const bool twopass = !(nt && nt[0] == '1') && bwd_twopass_applicable(p, dtype);
-    const char* np = getenv("GSPN_BWD_NO_PLANE");     // testing aid: keep the other kernels reachable on tiny maps
-    if (!(np && np[0] == '1') && bwd_plane_applicable(p, dtype)) {
+    const Knobs k = knobs();
+    if (k.force_generic) return BWD_GENERIC;
+    const bool twopass = !k.bwd_no_twopass && bwd_twopass_applicable(p, dtype);
+    if (!k.bwd_no_plane && bwd_plane_applicable(p, dtype)) {
         // the single-launch plane kernel, except where the two passes were measured faster: bf16 storage, shared
         // weights, lines of more than 16 positions (28x28x192, B = 64, G = 8: 382 -> 270 us; B = 32, G = 4, where a bf16
         // group cannot be split over workgroups: 1401 -> 177 us; 32x32x256 G = 16: 250 -> 73 us; the shorter lines of

@@ -14,8 +14,9 @@
 //    rows, and each lane reads its rows in bursts of CS scan steps (16..32 B), double
 //    buffered in registers.
 //  * The merged output y = sum_d u_d*h_d (Eq. 2 + sum merge) is accumulated in an fp32 LDS
-//    tile by LDS float atomics and written once, coalesced, rounded once to the storage
-//    type.  x is the only tensor read more than once (once per direction).
+//    tile by plain read-modify-write (every element has one owner wave between two barriers)
+//    and written once, coalesced, rounded once to the storage type.  x is the only tensor
+//    read more than once (once per direction).
 //  * Accumulation order per output element is fixed (vertical pair first -- its two
 //    contributions commute --, then the horizontal pair split at mid-scan by a barrier so
 //    that the two waves never touch the same element in the same half), so results are
@@ -672,15 +673,15 @@ struct TilePlan { bool ok; int hv, vv, vh, cs, K, pitch, lplv, pv, lplh, ph, nwa
 
 static TilePlan plan_tile(const FwdParams& p, int dtype) {
     TilePlan t = {};
-    const char* force_k = getenv("GSPN_TILE_K");          // tuning aid: force the channels per workgroup
-    const int forced = force_k ? atoi(force_k) : 0;
-    const char* force_h = getenv("GSPN_TILE_HV");         // tuning aid: force the horizontal variant
     const int es = dtype == 0 ? 4 : 2;
     // two positions per lane in the vertical passes.  Measured and not adopted on 128x128 in the transposed layout:
     // four positions per lane with half as many waves (0.233 -> 0.294 ms); reading the tile elements of a step one
     // step ahead (0.232 -> 0.229 ms there, 0.299 -> 0.306 ms in the standard layout)
     const int vv = 2;
     if (p.W % vv || p.W / vv > 64) return t;
+    // a map of one row has no mid-scan meeting of the vertical pair (the barrier that separates the two halves sits
+    // before a step both waves take): such maps run the generic kernel
+    if (p.H < 2) return t;
     const int row_bytes = p.W * es;
     int hv;
     const int parts = (p.H + 63) / 64;
@@ -694,12 +695,6 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
     else if (row_bytes % 64 == 0) hv = H_SECTOR;
     else if (row_bytes % 16 == 0) hv = H_SMALL;
     else return t;
-    if (force_h && hv != H_TRANSPOSED) {
-        const int f = atoi(force_h);
-        if (f != H_SPLIT && hv == H_SPLIT) hv = H_SECTOR;
-        if (f == H_SMALL && row_bytes % 16 == 0) hv = H_SMALL;
-        if (f == H_SECTOR && row_bytes % 64 == 0) hv = H_SECTOR;
-    }
     const int vh = hv == H_ROW ? 1 : (hv == H_SPLIT ? 0 : 2);      // image rows per lane (0: one row, rows split over waves)
     const int cs = hv == H_ROW ? 112 / es : (hv == H_SPLIT ? 128 / es : (hv == H_SECTOR ? 64 / es : 16 / es));
     if (vh > 0 && (p.H % vh || p.H / vh > 64)) return t;
@@ -716,7 +711,6 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
     int best = 0;
     for (int K = 1; K <= p.C && K <= 64; ++K) {
         if (p.C % K) continue;
-        if (forced && K != forced) continue;
         if (K * per_channel > (size_t)LDS_BUDGET) break;
         const int wv = ((K + t.pv - 1) / t.pv) * dirs_v, wh = ((K + t.ph - 1) / t.ph) * dirs_h * t.parts;
         const int nw = wv > wh ? wv : wh;

@@ -5,8 +5,9 @@
 // line by line, inside a single launch (the fused-loop structure of Sec. 4.1).
 // The previous line's state lives in LDS (two ping-pong lines) so a position can
 // read its three neighbours (Sec. 3.2); one barrier per line.  The merged
-// outputs (y, gx) are accumulated in place, direction after direction, by the
-// workgroup that owns the plane, so no atomics and no zero-fill are needed and
+// outputs (y, gx) are accumulated direction after direction by the workgroup that
+// owns the plane -- y of a bf16 plane that fits in an fp32 LDS tile, everything
+// else in place in global memory -- so no atomics and no zero-fill are needed and
 // the summation order is fixed.
 //
 // This is the fallback for shapes the specialised kernels do not take; it makes
@@ -15,7 +16,9 @@
 
 namespace gspn {
 
-template <typename T>
+// TILE: the merged output of the plane is accumulated in an fp32 LDS tile behind the two line buffers and meets the
+// storage type once (planes that fit); otherwise it is accumulated in place in global memory, one rounding per direction.
+template <typename T, bool TILE>
 __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
     extern __shared__ float lds[];
     const int H = p.H, W = p.W, HW = H * W;
@@ -27,6 +30,7 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
     const T* U = (const T*)p.u;
     T* Y = (T*)p.y;
     T* HS = (T*)p.hs;
+    float* acc = lds + 2 * Lmax;
 
     for (size_t item = blockIdx.x; item < plane_cnt; item += gridDim.x) {
         const int b = (int)(item / p.C), c = (int)(item % p.C), g = c / p.cpg;
@@ -65,8 +69,13 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
                     }
                     cur[j] = h;
                     float yv = ldf(up + off) * h;
-                    if (!first) yv += ldf(yp + offy);
-                    stf(yp + offy, yv);
+                    if constexpr (TILE) {
+                        if (!first) yv += acc[offy];
+                        acc[offy] = yv;
+                    } else {
+                        if (!first) yv += ldf(yp + offy);
+                        stf(yp + offy, yv);
+                    }
                     if (hp) stf(hp + off, h);
                 }
                 __syncthreads();   // line t complete (LDS) and, after the last line, y visible to the block
@@ -74,11 +83,20 @@ __global__ void __launch_bounds__(256) fwd_generic_kernel(FwdParams p) {
             }
             first = false;
         }
+        if constexpr (TILE) {
+            for (int i = threadIdx.x; i < HW; i += blockDim.x) stf(Y + pc + i, acc[i]);
+            __syncthreads();       // the tile is free for the next plane
+        }
     }
 }
 
+// Backward: one workgroup per (batch, group).  Directions are the outer loop; inside a direction the channels of the
+// group are walked in batches of `nc` whose error lines e_{t+1} fit in LDS side by side, so that the scan steps are the
+// middle loop and the channels the inner one: the sum over the group's channels that gw needs (chain rule on Eq. 1 with
+// the shared weights of Sec. 4.2) is then taken in fp32 registers, position by position, and meets the storage type
+// once per batch (one batch unless lines are very long), and a line costs one barrier for all its channels.
 template <typename T>
-__global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
+__global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p, int nc) {
     extern __shared__ float lds[];
     const int H = p.H, W = p.W, HW = H * W;
     const int Lmax = H > W ? H : W;
@@ -94,40 +112,39 @@ __global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
     T* GW = (T*)p.gw;
     T* GLAM = (T*)p.glam;
     T* GU = (T*)p.gu;
+    // LDS: e of scan step t+1 and of step t for the nc channels of the batch, then (weights as logits) the normalised
+    // taps of the current line and of the next one in scan order
+    float* ebuf0 = lds;
+    float* ebuf1 = lds + (size_t)nc * Lmax;
+    float* wbuf0 = lds + 2 * (size_t)nc * Lmax;
+    float* wbuf1 = wbuf0 + 3 * Lmax;
 
     for (size_t item = blockIdx.x; item < group_cnt; item += gridDim.x) {
         const int b = (int)(item / p.G), g = (int)(item % p.G);
-        for (int ci = 0; ci < p.cpg; ++ci) {
-            const size_t pc = ((size_t)b * p.C + (size_t)g * p.cpg + ci) * HW;
-            bool first = true;
-            for (int d = 0; d < 4; ++d) {
-                if (!((p.mask >> d) & 1u)) continue;
-                const DirGeom q = dir_geom(d, H, W);
-                const size_t out_c = (size_t)d * plane_cnt * HW;
-                const size_t out_w = (size_t)d * group_cnt * 3 * HW;
-                const size_t slot_c = p.shared ? 0 : out_c;
-                const size_t slot_w = p.shared ? 0 : out_w;
-                const T* gyp = GY + pc;
-                const T* xp = X + pc;
-                const T* lp = LAM + slot_c + pc;
-                const T* up = U + slot_c + pc;
-                const T* hp = HS + out_c + pc;
-                const T* wp = WT + slot_w + item * 3 * HW;
-                T* gxp = GX + pc;
-                T* glp = GLAM + out_c + pc;
-                T* gup = GU + out_c + pc;
-                T* gwp = GW + out_w + item * 3 * HW;
-                float* enext = lds;         // e of scan step t+1
-                float* ecur = lds + Lmax;
-                // weights as logits: the normalised taps of the current line and of the next one (scan order)
-                float* wcur = lds + 2 * Lmax;
-                float* wnext = lds + 5 * Lmax;
-                const bool last_channel = ci == p.cpg - 1;
+        const size_t pc0 = ((size_t)b * p.C + (size_t)g * p.cpg) * HW;      // first channel of the group
+        bool first = true;                                                   // first direction: gx is overwritten
+        for (int d = 0; d < 4; ++d) {
+            if (!((p.mask >> d) & 1u)) continue;
+            const DirGeom q = dir_geom(d, H, W);
+            const size_t out_c = (size_t)d * plane_cnt * HW;
+            const size_t out_w = (size_t)d * group_cnt * 3 * HW;
+            const size_t slot_c = p.shared ? 0 : out_c;
+            const size_t slot_w = p.shared ? 0 : out_w;
+            const T* wp = WT + slot_w + item * 3 * HW;
+            T* gwp = GW + out_w + item * 3 * HW;
+            const int step = q.reversed ? -q.stride_s : q.stride_s;          // to the next line in scan order
+            for (int c0 = 0; c0 < p.cpg; c0 += nc) {
+                const int n_here = min(nc, p.cpg - c0);
+                const bool last_batch = c0 + n_here == p.cpg;
+                float* enext = ebuf0;
+                float* ecur = ebuf1;
+                float* wcur = wbuf0;
+                float* wnext = wbuf1;
                 for (int t = q.S - 1; t >= 0; --t) {
                     const int base = (q.reversed ? q.S - 1 - t : t) * q.stride_s;
-                    const int step = q.reversed ? -q.stride_s : q.stride_s;   // to the next line in scan order
                     const bool starts = starts_stretch(t, q.S, q.reversed, p.kchunk);
                     const bool next_starts = t + 1 < q.S && starts_stretch(t + 1, q.S, q.reversed, p.kchunk);
+                    const bool carry = t + 1 < q.S && !next_starts;         // e of the next line (same stretch) comes in
                     if (p.logits) {
                         // this line's taps, normalised (0 where nothing is read: the line has no predecessor)
                         for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
@@ -144,46 +161,60 @@ __global__ void __launch_bounds__(256) bwd_generic_kernel(BwdParams p) {
                     }
                     for (int j = threadIdx.x; j < q.L; j += blockDim.x) {
                         const int off = base + j * q.stride_j;
-                        const float gyv = ldf(gyp + off);
-                        float e = ldf(up + off) * gyv;
-                        if (t + 1 < q.S && !next_starts) {   // transposed tridiagonal of the next line (of the same stretch)
-                            const int offn = off + step;
+                        const int offp = off - step;                        // same position on the previous line
+                        // transposed tridiagonal of the next line: position j is read by tap 1 of j, tap 2 of j-1, tap 0 of j+1
+                        float tc = 0.f, tl = 0.f, tr = 0.f;
+                        if (carry) {
                             if (p.logits) {
-                                e = fmaf(wnext[Lmax + j], enext[j], e);
-                                if (j > 0) e = fmaf(wnext[2 * Lmax + j - 1], enext[j - 1], e);
-                                if (j + 1 < q.L) e = fmaf(wnext[j + 1], enext[j + 1], e);
+                                tc = wnext[Lmax + j];
+                                if (j > 0) tl = wnext[2 * Lmax + j - 1];
+                                if (j + 1 < q.L) tr = wnext[j + 1];
                             } else {
-                                e = fmaf(ldf(wp + HW + offn), enext[j], e);
-                                if (j > 0) e = fmaf(ldf(wp + 2 * HW + offn - q.stride_j), enext[j - 1], e);
-                                if (j + 1 < q.L) e = fmaf(ldf(wp + offn + q.stride_j), enext[j + 1], e);
+                                const int offn = off + step;
+                                tc = ldf(wp + HW + offn);
+                                if (j > 0) tl = ldf(wp + 2 * HW + offn - q.stride_j);
+                                if (j + 1 < q.L) tr = ldf(wp + offn + q.stride_j);
                             }
                         }
-                        ecur[j] = e;
-                        stf(glp + off, ldf(xp + off) * e);
-                        stf(gup + off, gyv * ldf(hp + off));
-                        float gxv = ldf(lp + off) * e;
-                        if (!first) gxv += ldf(gxp + off);
-                        stf(gxp + off, gxv);
-                        const int offp = off - step;   // same position on the previous line
-                        float v[3];
-                        #pragma unroll
-                        for (int k = 0; k < 3; ++k) {
-                            const int jj = j + k - 1;
-                            v[k] = 0.f;
-                            if (!starts && jj >= 0 && jj < q.L) v[k] = e * ldf(hp + offp + (k - 1) * q.stride_j);
-                            if (ci > 0) v[k] += ldf(gwp + k * HW + off);
+                        float v[3] = {0.f, 0.f, 0.f};                       // gw of this position, summed over the batch in fp32
+                        for (int ci = 0; ci < n_here; ++ci) {
+                            const size_t pc = pc0 + (size_t)(c0 + ci) * HW;
+                            const float* en = enext + (size_t)ci * Lmax;
+                            const float gyv = ldf(GY + pc + off);
+                            float e = ldf(U + slot_c + pc + off) * gyv;
+                            if (carry) {
+                                e = fmaf(tc, en[j], e);
+                                if (j > 0) e = fmaf(tl, en[j - 1], e);
+                                if (j + 1 < q.L) e = fmaf(tr, en[j + 1], e);
+                            }
+                            ecur[(size_t)ci * Lmax + j] = e;
+                            const T* hp = HS + out_c + pc;
+                            stf(GLAM + out_c + pc + off, ldf(X + pc + off) * e);
+                            stf(GU + out_c + pc + off, gyv * ldf(hp + off));
+                            float gxv = ldf(LAM + slot_c + pc + off) * e;
+                            if (!first) gxv += ldf(GX + pc + off);
+                            stf(GX + pc + off, gxv);
+                            if (!starts) {
+                                v[1] = fmaf(e, ldf(hp + offp), v[1]);
+                                if (j > 0) v[0] = fmaf(e, ldf(hp + offp - q.stride_j), v[0]);
+                                if (j + 1 < q.L) v[2] = fmaf(e, ldf(hp + offp + q.stride_j), v[2]);
+                            }
+                        }
+                        if (c0 > 0) {
+#pragma unroll
+                            for (int k = 0; k < 3; ++k) v[k] += ldf(gwp + k * HW + off);
                         }
                         // weights as logits: the sum over the group's channels goes through the softmax once, at the end
-                        if (p.logits && last_channel) softmax3_grad(v[0], v[1], v[2], wcur[j], wcur[Lmax + j], wcur[2 * Lmax + j]);
-                        #pragma unroll
+                        if (p.logits && last_batch) softmax3_grad(v[0], v[1], v[2], wcur[j], wcur[Lmax + j], wcur[2 * Lmax + j]);
+#pragma unroll
                         for (int k = 0; k < 3; ++k) stf(gwp + k * HW + off, v[k]);
                     }
                     __syncthreads();
                     float* tmp = enext; enext = ecur; ecur = tmp;
                     tmp = wnext; wnext = wcur; wcur = tmp;
                 }
-                first = false;
             }
+            first = false;
         }
     }
 }
@@ -195,9 +226,15 @@ hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s) {
     const size_t items = (size_t)p.B * p.C;
     const unsigned grid = (unsigned)(items < 65536 ? items : 65536);
     const int block = pick_block(Lmax);
-    const size_t shmem = 2 * (size_t)Lmax * sizeof(float);
-    void (*k)(FwdParams) = dtype == 0 ? fwd_generic_kernel<float> : fwd_generic_kernel<bf16_t>;
-    if (shmem > 48 * 1024) {                                 // long lines: ask for the LDS explicitly
+    const size_t lines = 2 * (size_t)Lmax * sizeof(float);
+    // the fp32 tile of the merged output, when the plane fits beside the line buffers (one rounding of y instead of
+    // one per direction; in fp32 storage the in-place sum is already exact to the storage type)
+    const size_t with_tile = lines + (size_t)p.H * p.W * sizeof(float);
+    const bool tile = dtype == 1 && with_tile <= 160 * 1024;
+    const size_t shmem = tile ? with_tile : lines;
+    void (*k)(FwdParams) = dtype == 0 ? fwd_generic_kernel<float, false>
+                                      : (tile ? fwd_generic_kernel<bf16_t, true> : fwd_generic_kernel<bf16_t, false>);
+    if (shmem > 48 * 1024) {                                 // ask for the LDS explicitly
         const hipError_t e = allow_dynamic_lds((const void*)k, 160 * 1024);
         if (e != hipSuccess) return e;
     }
@@ -205,19 +242,29 @@ hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s) {
     return hipGetLastError();
 }
 
+// channels of a group whose error lines share the LDS in the backward kernel: all of them when they fit in 96 KB
+static int bwd_batch(const BwdParams& p, int Lmax) {
+    const size_t budget = 96 * 1024 / sizeof(float);
+    const size_t taps = p.logits ? 6 * (size_t)Lmax : 0;
+    size_t nc = budget > taps ? (budget - taps) / (2 * (size_t)Lmax) : 0;
+    if (nc < 1) nc = 1;
+    return nc < (size_t)p.cpg ? (int)nc : p.cpg;
+}
+
 hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s) {
     const int Lmax = p.H > p.W ? p.H : p.W;
     const size_t items = (size_t)p.B * p.G;
     const unsigned grid = (unsigned)(items < 65536 ? items : 65536);
     const int block = pick_block(Lmax);
-    const size_t shmem = (p.logits ? 8 : 2) * (size_t)Lmax * sizeof(float);
-    if (shmem > 128 * 1024) return hipErrorInvalidValue;      // checked by the caller (GSPN_MAX_LINE_LOGITS)
-    void (*k)(BwdParams) = dtype == 0 ? bwd_generic_kernel<float> : bwd_generic_kernel<bf16_t>;
-    if (shmem > 48 * 1024) {                                 // long lines: ask for the LDS explicitly
+    const int nc = bwd_batch(p, Lmax);
+    const size_t shmem = (2 * (size_t)nc + (p.logits ? 6 : 0)) * (size_t)Lmax * sizeof(float);
+    if (shmem > 160 * 1024) return hipErrorInvalidValue;      // checked by the caller (GSPN_MAX_LINE_LOGITS)
+    void (*k)(BwdParams, int) = dtype == 0 ? bwd_generic_kernel<float> : bwd_generic_kernel<bf16_t>;
+    if (shmem > 48 * 1024) {                                 // ask for the LDS explicitly
         const hipError_t e = allow_dynamic_lds((const void*)k, 160 * 1024);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k, dim3(grid), dim3(block), shmem, s, p);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(block), shmem, s, p, nc);
     return hipGetLastError();
 }
 

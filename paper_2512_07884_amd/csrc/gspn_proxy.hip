@@ -319,9 +319,7 @@ hipError_t launch_proxy_project_bwd(const void* gout, const void* in, const void
         const int ktiles = (K + 31) / 32, mtiles = mfma ? (M + 31) / 32 : (M + 7) / 8;
         const long blocks = (long)B * mtiles * ktiles;
         if (blocks > 0x7fffffffl) return hipErrorInvalidValue;
-        const char* nw_v = getenv("GSPN_PROXY_GRADW_WAVES");            // tuning aid: force 4 or 8 waves per tile
-        const int nw_env = nw_v ? atoi(nw_v) : 0;
-        const bool wide = nw_env ? nw_env == 8 : blocks * 4 < 2048;     // fewer than 8 waves per compute unit otherwise
+        const bool wide = blocks * 4 < 2048;     // eight waves per tile while four would leave a compute unit under eight
         if (mfma && wide)
             hipLaunchKernelGGL(proxy_gradw_mfma_kernel<8>, dim3((unsigned)blocks), dim3(512), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
                                partial, K, M, N, mtiles, ktiles);

@@ -229,6 +229,20 @@ def test_backward_generic_kernel_bf16(monkeypatch):
     check_bwd(WL.ScanConfig("bwdgenbf16", 2, 6, 24, 20, 6, "bf16", 15, 1.0, 19))
 
 
+@pytest.mark.parametrize("shape", [(2, 24, 57, 57, 2), (1, 64, 33, 70, 1), (1, 8, 1, 56, 2)], ids=lambda s: "x".join(map(str, s)))
+def test_backward_generic_kernel_bf16_large_groups(shape):
+    """Odd widths (and single rows) run the generic kernels; the sum of gw over the 12 / 64 channels of a group is taken
+    in fp32 and rounded once, so the bf16 tolerance holds at any group size."""
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr = shape
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, 1, 0) == "generic", shape
+    check_bwd(WL.ScanConfig("bwdgenbig", B, C, H, W, Gr, "bf16", 15, 1.0, 83))
+
+
+def test_backward_single_row_fp32():
+    check_bwd(WL.ScanConfig("bwdonerow", 1, 8, 1, 28, 2, "f32", 15, 1.0, 89))
+
+
 def test_backward_bf16_per_channel_weights():
     # bf16 storage with one channel per group: every gradient is rounded once
     check_bwd(WL.ScanConfig("bwdbf16", 2, 6, 24, 20, 6, "bf16", 15, 1.0, 19))

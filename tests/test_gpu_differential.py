@@ -73,8 +73,9 @@ def test_fast_kernels_agree_with_the_generic_kernels_on_random_cases(seed, monke
         monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
         ref = _run(G, inp, Gr, mask, kchunk, logits)
         monkeypatch.delenv("GSPN_FORCE_GENERIC", raising=False)
-        # bf16: both sides round (the generic backward sums gw over a group's channels in storage precision)
-        tol = 4e-2 if dtype == "bf16" else 2e-5
+        # bf16: both sides round every stored value once (two storage roundings apart at most, plus the generic
+        # forward's per-direction rounding of y on maps beyond its LDS tile)
+        tol = 2e-2 if dtype == "bf16" else 2e-5
         case = (seed, it, B, C, H, W, Gr, dtype, mask, kchunk, logits)
         for n in fast:
             a, b = fast[n].float(), ref[n].float()

@@ -25,6 +25,16 @@ def check_logits(shape, kchunk=None, mask=15, seed=101, scale=1.5, poison=False,
         z = inp["w"]
         z[0, :, :, 0, :, 0] = nan; z[1, :, :, 2, :, -1] = nan; z[2, :, :, 0, 0, :] = nan; z[3, :, :, 2, -1, :] = nan
         z[0, :, :, :, 0, :] = nan; z[1, :, :, :, -1, :] = nan; z[2, :, :, :, :, 0] = nan; z[3, :, :, :, :, -1] = nan
+        if kchunk:
+            # GSPN-local: the first line of every stretch in scan order (cuts at image lines 0, kchunk, 2*kchunk, ...)
+            for r in range(0, H, kchunk):
+                z[0, :, :, :, r, :] = nan
+                if r > 0:
+                    z[1, :, :, :, r - 1, :] = nan
+            for r in range(0, W, kchunk):
+                z[2, :, :, :, :, r] = nan
+                if r > 0:
+                    z[3, :, :, :, :, r - 1] = nan
     k = kchunk if kchunk else 1 << 14
     dt = int(dtype == "bf16")
     if fwd_plan:
@@ -128,6 +138,16 @@ def test_logits_with_local_stretches_on_the_plane_kernels(shape, kchunk):
                                    (1, 8, 14, 14, 2, "bf16")], ids=lambda s: "x".join(map(str, s)))
 def test_logits_that_are_never_read_may_hold_anything(shape):
     check_logits(shape, poison=True)
+
+
+@pytest.mark.parametrize("shape,kchunk", [((1, 8, 128, 128, 2, "f32"), None), ((2, 24, 56, 56, 2, "bf16"), None),
+                                          ((1, 8, 128, 128, 2, "f32"), 32), ((2, 24, 56, 56, 2, "bf16"), 14),
+                                          ((1, 2, 256, 256, 1, "bf16"), None)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_unread_logits_may_hold_anything_in_the_two_pass_backward(shape, kchunk):
+    """The channel-sum pass of the two-pass backward normalises the logits of every pixel once more; on lines without a
+    predecessor (first line of a scan, of a stretch) the stored logits must stay out of it and gz must be an exact 0."""
+    check_logits(shape, kchunk=kchunk, poison=True, bwd_plan="twopass")
 
 
 @pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9])

@@ -117,13 +117,12 @@ def test_projection_gradients_match_the_oracle(shape):
     assert rel_inf_err(gP, gP_ref) <= 1e-5, ("gP", rel_inf_err(gP, gP_ref))
 
 
-@pytest.mark.parametrize("waves", ["4", "8"])
-def test_weight_gradient_with_either_wave_count_and_more_images_than_one_batch_of_the_sum(waves, monkeypatch):
+@pytest.mark.parametrize("K,M", [(40, 33), (200, 130)], ids=["8_waves_per_tile", "4_waves_per_tile"])
+def test_weight_gradient_with_either_wave_count_and_more_images_than_one_batch_of_the_sum(K, M):
     # 19 images: the kernel that adds the per-image sums asks for 16 at a time and has a ragged second batch;
-    # the tile kernel's two instantiations are forced in turn
-    monkeypatch.setenv("GSPN_PROXY_GRADW_WAVES", waves)
-    B, K, M, H, W = 19, 40, 33, 12, 12
-    rng = np.random.default_rng([19, int(waves)])
+    # 76 tiles run the tile kernel's eight-wave instantiation, 665 tiles (512 and more) the four-wave one
+    B, H, W = 19, 12, 12
+    rng = np.random.default_rng([19, K])
     x = WL.to_storage(rng.standard_normal((B, K, H, W)), "bf16")
     P = WL.to_storage(rng.standard_normal((M, K)) / np.sqrt(K), "bf16")
     g = WL.to_storage(rng.standard_normal((B, M, H, W)), "bf16")

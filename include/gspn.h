@@ -183,6 +183,18 @@ int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, i
  * a multiple of 16) allow, as in the forward call; other shapes and fp32 storage run plain FMA kernels. */
 int gspn_proxy_project_bwd(const void* gout, const void* in, const void* P, void* gin, float* gP, float* partial,
                            int B, int K, int M, int H, int W, int dtype, void* stream);
+/* gspn_proxy_project_bwd for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same kernels and the
+ * same results, bit for bit; the per-image sums go to a static device array of the library's
+ * (GSPN_PROXY_STATIC_MAX_FLOATS floats = 4 MiB, held on every GPU the library runs on until the process
+ * ends) instead of `partial`.  With gP, B*M*K beyond that size is GSPN_ERR_UNSUPPORTED (nothing is launched).
+ * The call allocates and frees nothing.  Every call on a GPU uses that GPU's one array, so two calls that
+ * overlap on one GPU (different streams, no ordering between them) race on it; calls on one stream, or
+ * ordered by events, are safe.  The array needs no clearing: each call overwrites what it reads.  Other
+ * arguments, errors and stream semantics as for gspn_proxy_project_bwd. */
+#define GSPN_PROXY_STATIC_MAX_FLOATS (1 << 20)
+int gspn_proxy_project_bwd_static(const void* gout, const void* in, const void* P, void* gin, float* gP,
+                                  int B, int K, int M, int H, int W, int dtype, void* stream);
 /* "mfma" or "fma": which kernel gspn_proxy_project runs for these arguments ("invalid" for bad ones). */
 const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 

@@ -21,7 +21,7 @@ _LIB = None
 EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_bwd_local",
            "gspn_scan_fwd_logits", "gspn_scan_bwd_logits",
            "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
-           "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_project_bwd", "gspn_proxy_plan",
+           "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_project_bwd", "gspn_proxy_project_bwd_static", "gspn_proxy_plan",
            "gspn_scan_fwd_transposed", "gspn_fwd_transposed_plan",
            "gspn_status_string", "gspn_version", "gspn_reload_env")
 
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_proxy_project.restype = ci
     lib.gspn_proxy_project_bwd.argtypes = [vp] * 6 + [ci] * 6 + [vp]
     lib.gspn_proxy_project_bwd.restype = ci
+    lib.gspn_proxy_project_bwd_static.argtypes = [vp] * 5 + [ci] * 6 + [vp]
+    lib.gspn_proxy_project_bwd_static.restype = ci
     lib.gspn_proxy_plan.argtypes = [ci] * 6
     lib.gspn_proxy_plan.restype = ctypes.c_char_p
     lib.gspn_fwd_local_plan.argtypes = [ci] * 6 + [cu, ci, cu, ci]
@@ -280,6 +282,23 @@ def gspn_proxy_project_bwd(gout, inp, P, gin, gP, partial, *, stream=None) -> No
             raise ValueError(f"{name}: must be a contiguous float32 device tensor of shape {shape}")
         args.append(ctypes.c_void_p(t.data_ptr()))
     _check(load_library().gspn_proxy_project_bwd(*args, B, K, M, H, W, _dtype_code(inp), _stream(stream)))
+
+
+def gspn_proxy_project_bwd_static(gout, inp, P, gin, gP, *, stream=None) -> None:
+    """gspn_proxy_project_bwd without the workspace argument: the per-image sums go to a static device array of the
+    library's (B*M*K <= 2**20 floats, else GspnError); the call allocates nothing.  Calls that overlap on one GPU race."""
+    import torch
+    B, K, H, W = inp.shape
+    M = P.shape[0]
+    args = [_ptr(gout, "gout", (B, M, H, W), inp), _ptr(inp, "inp", (B, K, H, W), inp), _ptr(P, "P", (M, K), inp),
+            _ptr(gin, "gin", (B, K, H, W), inp)]
+    if gP is None:
+        args.append(None)
+    else:
+        if not gP.is_cuda or gP.device != inp.device or gP.dtype != torch.float32 or tuple(gP.shape) != (M, K) or not gP.is_contiguous():
+            raise ValueError(f"gP: must be a contiguous float32 device tensor of shape {(M, K)}")
+        args.append(ctypes.c_void_p(gP.data_ptr()))
+    _check(load_library().gspn_proxy_project_bwd_static(*args, B, K, M, H, W, _dtype_code(inp), _stream(stream)))
 
 
 def gspn_fwd_transposed_plan(B, C, H, W, G, dir_mask=DIR_ALL, dtype=GSPN_F32, flags=0) -> str:

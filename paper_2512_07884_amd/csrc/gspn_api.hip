@@ -4,6 +4,8 @@
 
 using namespace gspn;
 
+static_assert(GSPN_PROXY_STATIC_MAX_FLOATS == PROXY_SCRATCH_FLOATS, "the header states the size of the static workspace");
+
 namespace {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -221,6 +223,19 @@ int gspn_proxy_project_bwd(const void* gout, const void* in, const void* P, void
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
 }
 
+int gspn_proxy_project_bwd_static(const void* gout, const void* in, const void* P, void* gin, float* gP,
+                                  int B, int K, int M, int H, int W, int dtype, void* stream) {
+    if (!gout || !in || !P || (!gin && !gP)) return GSPN_ERR_NULL;
+    if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1) return GSPN_ERR_SHAPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
+    if ((long long)H * W >= (1ll << 31) || (long long)M * K >= (1ll << 31)) return GSPN_ERR_UNSUPPORTED;
+    if (gP && (long long)B * M * K > (long long)GSPN_PROXY_STATIC_MAX_FLOATS) return GSPN_ERR_UNSUPPORTED;
+    if (misaligned(gout) || misaligned(in) || misaligned(P) || misaligned(gin) || misaligned(gP)) return GSPN_ERR_ALIGN;
+    hipError_t e = launch_proxy_project_bwd_static(gout, in, P, gin, gP, B, K, M, H * W, dtype, (hipStream_t)stream);
+    return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
 const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype) {
     if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1 || (dtype != GSPN_F32 && dtype != GSPN_BF16)) return "invalid";
     if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE || (long long)H * W >= (1ll << 31)) return "invalid";
@@ -234,7 +249,7 @@ const char* gspn_status_string(int status) {
         case GSPN_ERR_SHAPE: return "bad shape: dimensions and kchunk must be >= 1, C divisible by G, dir_mask in 1..15";
         case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32 or GSPN_BF16";
         case GSPN_ERR_ALIGN: return "pointers must be 16-byte aligned";
-        case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE (GSPN_MAX_LINE_LOGITS with logits) or unknown flag";
+        case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE (GSPN_MAX_LINE_LOGITS with logits), unknown flag, or B*M*K beyond the static workspace";
         case GSPN_ERR_HIP: return "HIP launch failed";
         default: return "unknown status";
     }

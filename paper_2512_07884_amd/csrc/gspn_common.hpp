@@ -186,6 +186,11 @@ bool proxy_mfma_applicable(int B, int K, int M, int N, int dtype);
 hipError_t launch_proxy_project_bwd(const void* gout, const void* in, const void* P, void* gin, float* gP, float* partial,
                                     int B, int K, int M, int N, int dtype, hipStream_t s);
 
+// ... with the per-image sums in a static device array of PROXY_SCRATCH_FLOATS floats (B*M*K must fit): no workspace argument
+constexpr size_t PROXY_SCRATCH_FLOATS = (size_t)1 << 20;   // 4 MiB per GPU
+hipError_t launch_proxy_project_bwd_static(const void* gout, const void* in, const void* P, void* gin, float* gP,
+                                           int B, int K, int M, int N, int dtype, hipStream_t s);
+
 // dispatch (gspn_dispatch.hip): picks the kernel family for the arguments
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s);

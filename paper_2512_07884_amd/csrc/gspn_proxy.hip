@@ -342,4 +342,42 @@ hipError_t launch_proxy_project_bwd(const void* gout, const void* in, const void
     return hipSuccess;
 }
 
+// ---- the same call for callers that cannot allocate (HIP graph capture, serving loops): the per-image sums go to a
+// static device array instead of a workspace of the caller's.  Each GPU the library runs on holds its own copy of the
+// array at its own address; the array's name is only a host-side handle, so the address is looked up once per device
+// and that pointer is what the kernels get.
+static __device__ __align__(256) float scratch[PROXY_SCRATCH_FLOATS];
+
+static hipError_t scratch_address(float** out) {
+    constexpr int MAX_DEVICES = 64;
+    static float* per_device[MAX_DEVICES] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(mu);
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));      // with device `dev` current: this device's copy
+        if (e != hipSuccess) return e;
+        per_device[dev] = (float*)p;
+    }
+    *out = per_device[dev];
+    return hipSuccess;
+}
+
+// Every element [b][m][k] of the workspace is overwritten by the first kernel before the second reads it, so the array
+// needs no clearing between calls; calls that overlap on one GPU (two streams) would race on it.
+hipError_t launch_proxy_project_bwd_static(const void* gout, const void* in, const void* P, void* gin, float* gP,
+                                           int B, int K, int M, int N, int dtype, hipStream_t s) {
+    float* partial = nullptr;
+    if (gP) {
+        if ((size_t)B * M * K > PROXY_SCRATCH_FLOATS) return hipErrorInvalidValue;     // checked by the caller
+        const hipError_t e = scratch_address(&partial);
+        if (e != hipSuccess) return e;
+    }
+    return launch_proxy_project_bwd(gout, in, P, gin, gP, partial, B, K, M, N, dtype, s);
+}
+
 }  // namespace gspn

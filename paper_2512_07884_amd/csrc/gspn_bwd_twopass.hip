@@ -30,6 +30,8 @@ hipError_t launch_reverse_sweep_plane(const FwdParams& p, int dtype, hipStream_t
 bool reverse_sweep_plane_applicable(const FwdParams& p, int dtype);
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s);    // maps beyond the LDS tile
 bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype);
+hipError_t launch_reverse_sweep_pair(const FwdParams& p, int dtype, hipStream_t s);      // 128x128 bf16, two channels per workgroup
+bool reverse_sweep_pair_applicable(const FwdParams& p, int dtype);
 
 namespace {
 
@@ -233,6 +235,8 @@ hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     hipError_t e;
     if (reverse_sweep_plane_applicable(f, dtype)) {
         e = launch_reverse_sweep_plane(f, dtype, s);
+    } else if (pair_kernels_enabled() && reverse_sweep_pair_applicable(f, dtype)) {
+        e = launch_reverse_sweep_pair(f, dtype, s);
     } else if (fwd_tile_applicable(f, dtype)) {
         if (p.kchunk > 0 || p.logits) e = dtype == 0 ? launch_reverse_sweep_f32_local(f, s) : launch_reverse_sweep_bf16_local(f, s);
         else e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);

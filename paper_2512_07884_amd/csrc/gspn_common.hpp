@@ -169,6 +169,8 @@ hipError_t launch_fwd_plane(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_plane_applicable(const FwdParams& p, int dtype);
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_stream_applicable(const FwdParams& p, int dtype);
+hipError_t launch_fwd_pair(const FwdParams& p, int dtype, hipStream_t s);
+bool fwd_pair_applicable(const FwdParams& p, int dtype);
 hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s);
 bool bwd_tile_applicable(const BwdParams& p, int dtype);
 hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s);
@@ -196,6 +198,7 @@ hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s);
 const char* fwd_plan_name(const FwdParams& p, int dtype);
 const char* bwd_plan_name(const BwdParams& p, int dtype);
+bool pair_kernels_enabled();   // false while GSPN_FWD_NO_PAIR=1 keeps the two-channel kernels out (testing aid)
 void reload_env_knobs();   // re-reads the GSPN_* testing aids from the environment (they are read once otherwise)
 
 }  // namespace gspn

@@ -117,13 +117,13 @@ def test_kernel_family_chosen_for_local_scans(lib, monkeypatch):
 
 def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
     """Host-side dispatch only: which kernel family each workload of the benchmark runs on."""
-    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_BWD_NO_TWOPASS", "GSPN_TILE_K", "GSPN_TILE_HV"):
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_BWD_NO_TWOPASS", "GSPN_FWD_NO_PAIR"):
         monkeypatch.delenv(v, raising=False)
     fwd = lambda *a: lib.gspn_fwd_plan(*a).decode()
     bwd = lambda *a: lib.gspn_bwd_plan(*a).decode()
     assert fwd(1, 8, 16, 16, 1, 1, 0, 0, 0) == "plane"                       # unit16
     assert fwd(64, 96, 56, 56, 8, 15, 1, 0, 0) == "plane"                    # cls56
-    assert fwd(2, 1024, 128, 128, 16, 15, 1, 0, 0) == "tile"                 # diff128
+    assert fwd(2, 1024, 128, 128, 16, 15, 1, 0, 0) == "pair"                 # diff128
     assert fwd(1, 512, 512, 512, 16, 15, 1, 0, 0) == "stream"                # long512
     assert fwd(1, 512, 256, 1024, 16, 15, 1, 0, 0) == "stream"               # long256x1024
     for G in (192, 4):                                                        # train28_gc / train28_g4

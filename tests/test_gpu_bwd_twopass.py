@@ -45,6 +45,19 @@ def test_two_pass_backward_direction_masks(mask, shape):
     check_bwd(WL.ScanConfig("twopassmask", B, C, H, W, Gr, dtype, mask, 1.0, 73))
 
 
+@pytest.mark.parametrize("bcg", [(1, 2, 1), (2, 12, 2)], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("pair", [True, False], ids=["two-channel", "one-channel"])
+def test_two_pass_backward_on_128x128_bf16_maps(bcg, pair, monkeypatch):
+    """The reverse sweep of these maps runs on the two-channel kernel (and on the one-channel tile kernel when that is
+    switched off): both against the oracle."""
+    import paper_2512_07884_amd as G
+    if not pair:
+        monkeypatch.setenv("GSPN_FWD_NO_PAIR", "1")
+    B, C, Gr = bcg
+    assert G.gspn_bwd_plan(B, C, 128, 128, Gr, 15, 1, 0) == "twopass"
+    check_bwd(WL.ScanConfig("twopass128", B, C, 128, 128, Gr, "bf16", 15, 3.0, 83))
+
+
 def test_two_pass_backward_is_bitwise_repeatable():
     import torch
     import paper_2512_07884_amd as G

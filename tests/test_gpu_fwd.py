@@ -91,7 +91,10 @@ def test_benchmark_shapes_with_fewer_channels(cfg):
 
 def test_kernel_families_by_shape():
     import paper_2512_07884_amd as G
-    assert G.gspn_fwd_plan(2, 1024, 128, 128, 16, 15, 1, 0, False) == "tile"
+    assert G.gspn_fwd_plan(2, 1024, 128, 128, 16, 15, 1, 0, False) == "pair"
+    assert G.gspn_fwd_plan(2, 1024, 128, 128, 1024, 15, 1, 0, False) == "tile"      # one channel per group: nothing to share
+    assert G.gspn_fwd_plan(2, 1024, 128, 128, 16, 7, 1, 0, False) == "tile"        # not all four directions
+    assert G.gspn_fwd_plan(2, 1024, 128, 128, 16, 15, 0, 0, False) == "tile"       # fp32 storage
     assert G.gspn_fwd_plan(64, 96, 56, 56, 8, 15, 1, 0, False) == "plane"
     assert G.gspn_fwd_plan(32, 192, 28, 28, 4, 15, 0, 0, True) == "plane"
     assert G.gspn_fwd_plan(32, 192, 28, 28, 192, 15, 0, 0, True) == "plane"
@@ -110,7 +113,8 @@ def test_direction_masks_on_large_maps(mask):
 
 
 @pytest.mark.parametrize("shape", [(1, 4, 12, 10, 2, "f32"), (1, 16, 7, 7, 2, "bf16"), (1, 8, 14, 14, 8, "f32"),
-                                   (1, 4, 28, 24, 2, "bf16"), (1, 2, 40, 40, 1, "f32"), (1, 3, 9, 11, 3, "bf16")],
+                                   (1, 4, 28, 24, 2, "bf16"), (1, 2, 40, 40, 1, "f32"), (1, 3, 9, 11, 3, "bf16"),
+                                   (1, 4, 128, 128, 2, "bf16")],
                          ids=lambda s: "x".join(map(str, s)))
 def test_weights_that_are_never_read_may_hold_anything(shape):
     """The first line of a scan has no predecessor and the end positions of a line have no neighbour outside
@@ -186,7 +190,7 @@ def test_library_reports_shape_errors_through_the_binding():
 def test_generic_kernel_on_shapes_the_fast_kernels_normally_take(cfg, monkeypatch):
     import paper_2512_07884_amd as G
     dt = int(cfg.dtype == "bf16")
-    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) in ("tile", "plane")
+    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) in ("tile", "plane", "pair")
     monkeypatch.setenv("GSPN_FORCE_GENERIC", "1")
     assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, dt, 0, True) == "generic"
     check_case(cfg)
@@ -265,6 +269,40 @@ def test_tile_kernel_on_shapes_the_plane_kernel_normally_takes(shape, monkeypatc
     B, C, H, W, Gr, dtype = shape
     assert G.gspn_fwd_plan(B, C, H, W, Gr, 15, int(dtype == "bf16"), 0, True) == "tile", shape
     cfg = WL.ScanConfig("fwdtile2", B, C, H, W, Gr, dtype, 15, 1.0, 43)
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+
+
+@pytest.mark.parametrize("bcg", [(1, 2, 1), (2, 12, 2), (1, 6, 1), (3, 4, 2)], ids=lambda s: "x".join(map(str, s)))
+def test_two_channel_kernel_on_128x128_maps(bcg):
+    """128x128 bf16 maps with an even number of channels per weight group: two channels of a group per workgroup,
+    the merged output accumulated in storage precision on chip (four roundings, inside the 1e-2 of the tolerance)."""
+    import paper_2512_07884_amd as G
+    B, C, Gr = bcg
+    assert G.gspn_fwd_plan(B, C, 128, 128, Gr, 15, 1, 0, True) == "pair" and G.gspn_fwd_plan(B, C, 128, 128, Gr, 15, 1, 0, False) == "pair"
+    cfg = WL.ScanConfig("pair128", B, C, 128, 128, Gr, "bf16", 15, 3.0, 61)
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+
+
+def test_two_channel_kernel_with_one_parameter_set_for_all_directions():
+    import paper_2512_07884_amd as G
+    cfg = WL.ScanConfig("pairshared", 1, 4, 128, 128, 2, "bf16", 15, 1.0, 67)
+    assert G.gspn_fwd_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, 15, 1, 1, False) == "pair"
+    inp = WL.make_inputs(cfg, with_gy=False)
+    one = {"x": inp["x"], "w": inp["w"][:1].copy(), "lam": inp["lam"][:1].copy(), "u": inp["u"][:1].copy()}
+    rep = {"x": inp["x"], "w": np.repeat(one["w"], 4, 0), "lam": np.repeat(one["lam"], 4, 0), "u": np.repeat(one["u"], 4, 0)}
+    f = WL.inputs_as_f64(rep, "bf16")
+    y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
+    y, *_ = run_fwd_gpu(one, cfg, 15, flags=1)
+    assert rel_inf_err(y, y_ref) <= TOL["bf16"]
+
+
+def test_one_channel_tile_kernel_on_the_maps_the_two_channel_kernel_normally_takes(monkeypatch):
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FWD_NO_PAIR", "1")
+    assert G.gspn_fwd_plan(1, 4, 128, 128, 2, 15, 1, 0, True) == "tile"
+    cfg = WL.ScanConfig("tile128", 1, 4, 128, 128, 2, "bf16", 15, 3.0, 63)
     check_case(cfg)
     check_case(cfg, save_h=False)
 

@@ -177,11 +177,12 @@ def summarise(cfg, r):
     if r.get("logits"):
         d["weights"] = "logits"
     if r.get("transposed"):
+        # the fraction above stays on the algorithmic bytes of the scan; the second copy of x this layout reads is
+        # counted in a figure of its own
         d["layout"] = "horizontal directions stored transposed (x read in both layouts: one more plane per pixel*channel)"
-        fwd_bytes += cfg.pixel_channels * (2 if cfg.dtype == "bf16" else 4)
-        d["fwd_algorithmic_bytes"] = fwd_bytes
-        d["fwd_algorithmic_GBs"] = fwd_bytes / (r["fwd_ms_avg"] * 1e-3) / 1e9
-        d["fwd_frac_of_hbm_peak"] = d["fwd_algorithmic_GBs"] / HBM_PEAK_GBS
+        with_xt = fwd_bytes + cfg.pixel_channels * (2 if cfg.dtype == "bf16" else 4)
+        d["fwd_bytes_incl_second_x"] = with_xt
+        d["fwd_frac_of_hbm_peak_incl_second_x"] = with_xt / (r["fwd_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS
     if training:
         bb = cfg.bwd_algorithmic_bytes()
         d.update({"bwd_kernel": bplan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, kchunk or big, cfg.dir_mask, dt, 0),
@@ -387,16 +388,26 @@ def main():
         "roofline": {"bound": "hbm", "kernel": f"gspn_scan_{dom}", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None if (a.kchunk or a.logits or a.transposed) else load_traffic(cfg.name, dom),
+                     "traffic_source": "stored: profiles/traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier "
+                                       "run of this command, scaled by a 1 GiB copy), not measured in this run",
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "detail": s,
     }
-    if cfg.name == "diff128" and not (a.kchunk or a.logits or a.transposed):
-        # the same shape as a training step (forward with h_save + backward), beside the forward-only headline
-        ct = WL.CONFIGS["train128"]
-        t = summarise(ct, run_workload(ct, max(20, a.steps // 4), a.warmup))
-        line["detail"]["training_step_on_this_shape"] = {k: t[k] for k in (
-            "workload", "step", "ms_per_step", "gpixel_ch_per_s", "fwd_kernel", "fwd_ms_avg", "fwd_algorithmic_GBs",
-            "fwd_frac_of_hbm_peak", "bwd_kernel", "bwd_ms_avg", "bwd_algorithmic_GBs", "bwd_frac_of_hbm_peak")}
+    if cfg.name == DEFAULT_WORKLOAD and not (a.kchunk or a.logits or a.transposed):
+        # The metric names two shapes, 128x128 and 512x512, forward and backward: beside the forward-only headline on
+        # the first, the same figures (algorithmic bytes per launch, mean launch time from events on the launch
+        # stream, fraction of the HBM peak) for the forward on the second and for both shapes as training steps
+        # (forward with h_save + backward)
+        keys = ("workload", "step", "ms_per_step", "gpixel_ch_per_s", "fwd_kernel", "fwd_ms_avg", "fwd_algorithmic_bytes",
+                "fwd_algorithmic_GBs", "fwd_frac_of_hbm_peak", "bwd_kernel", "bwd_ms_avg", "bwd_algorithmic_bytes",
+                "bwd_algorithmic_GBs", "bwd_frac_of_hbm_peak")
+        targets = [{k: s[k] for k in keys if k in s}]
+        for name, div in (("long512", 4), ("train128", 4), ("train512", 8)):
+            ct = WL.CONFIGS[name]
+            t = summarise(ct, run_workload(ct, max(10, a.steps // div), min(a.warmup, 5)))
+            targets.append({k: t[k] for k in keys if k in t})
+        line["detail"]["target_shapes"] = targets
+        line["detail"]["training_step_on_this_shape"] = targets[2]
     if cpu is not None:
         line["cpu_baseline"] = cpu
     if a.proxy:

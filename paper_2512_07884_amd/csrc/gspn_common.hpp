@@ -198,6 +198,7 @@ hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s);
 hipError_t launch_bwd(const BwdParams& p, int dtype, hipStream_t s);
 const char* fwd_plan_name(const FwdParams& p, int dtype);
 const char* bwd_plan_name(const BwdParams& p, int dtype);
+bool staged_stream_enabled();  // false while GSPN_STREAM_NO_STAGED=1 keeps the whole-line stream kernel out (testing aid)
 bool pair_kernels_enabled();   // false while GSPN_FWD_NO_PAIR=1 keeps the two-channel kernels out (testing aid)
 void reload_env_knobs();   // re-reads the GSPN_* testing aids from the environment (they are read once otherwise)
 

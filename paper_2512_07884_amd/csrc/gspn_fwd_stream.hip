@@ -6,15 +6,20 @@ namespace gspn {
 
 hipError_t launch_stream_f32(const FwdParams& p, hipStream_t s, bool reverse);
 hipError_t launch_stream_bf16(const FwdParams& p, hipStream_t s, bool reverse);
+// bf16, global scan: horizontal phases with whole-line requests (gspn_fwd_stream_staged.hip)
+bool stream_staged_applicable(const FwdParams& p, int dtype);
+hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s);
 
 bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok; }
 bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok; }
 
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s) {
+    if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, false, s);
     return dtype == 0 ? launch_stream_f32(p, s, false) : launch_stream_bf16(p, s, false);
 }
 
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s) {
+    if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, true, s);
     return dtype == 0 ? launch_stream_f32(p, s, true) : launch_stream_bf16(p, s, true);
 }
 

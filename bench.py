@@ -311,6 +311,48 @@ def proxy_table(steps: int = 50):
     return rows
 
 
+def unfused_table(steps: int = 3):
+    """Fused against unfused on this hardware: the library's forward call beside the per-line-launch comparator
+    (gspn_scan_fwd_unfused: one launch per line and direction, the state through global memory -- the structure of the
+    first GSPN implementation, Sec. 3.3) on the shape of the paper's step-by-step study (Sec. 5.1: 1024x1024, B = 16,
+    C = 8, where it reports 40x end to end on an A100) and on the two target shapes with few channels (Table 1 regime)."""
+    import torch
+    import paper_2512_07884_amd as G
+    from paper_2512_07884_amd import workloads as WL
+    rows = []
+    for name, B, C, H, W, Gr, dtype in (("step-by-step study shape", 16, 8, 1024, 1024, 1, "f32"),
+                                         ("step-by-step study shape, bf16", 16, 8, 1024, 1024, 1, "bf16"),
+                                         ("512x512, 128 channels", 1, 128, 512, 512, 4, "bf16"),
+                                         ("128x128, 2048 channels (diff128)", 2, 1024, 128, 128, 16, "bf16")):
+        cfg = WL.ScanConfig("unfused_" + name, B, C, H, W, Gr, dtype, 15, 1.0, 7)
+        s = device_inputs(cfg, 77)
+        y = torch.empty_like(s["x"])
+        ws = torch.empty(G.gspn_unfused_workspace_bytes(B, C, H, W), dtype=torch.uint8, device="cuda")
+        dt = 1 if dtype == "bf16" else 0
+        times = {}
+        for kind in ("fused", "unfused"):
+            def call():
+                if kind == "fused":
+                    G.gspn_scan_fwd(s["x"], s["w"], s["lam"], s["u"], y, None, G=Gr)
+                else:
+                    G.gspn_scan_fwd_unfused(s["x"], s["w"], s["lam"], s["u"], y, None, ws, G=Gr)
+            call()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                call()
+            torch.cuda.synchronize()
+            times[kind] = (time.perf_counter() - t0) * 1e3 / steps
+        rows.append({"shape": name, "B": B, "C": C, "H": H, "W": W, "G": Gr, "storage": dtype,
+                     "fused_kernel": G.gspn_fwd_plan(B, C, H, W, Gr, 15, dt, 0, False),
+                     "fused_ms": times["fused"], "unfused_ms": times["unfused"],
+                     "launches_unfused": 2 * (H + W), "ratio": times["unfused"] / times["fused"]})
+        del s, y, ws
+        torch.cuda.empty_cache()
+    return {"rows": rows, "paper_context": "GSPN-2 reports 40x (1024x1024, B=16, C=8), 36.8x and 151x over GSPN-1 on an "
+                                            "NVIDIA A100 (Sec. 5.1): another machine and a tuned baseline; context, not a target"}
+
+
 def copy_calibration(n_bytes: int = 1 << 30, reps: int = 5):
     """Plain copies of a known size: each must read and write exactly n_bytes, which
     fixes the unit in which the profiler's FETCH_SIZE / WRITE_SIZE counters report."""
@@ -337,6 +379,8 @@ def main():
                     help="forward workloads: horizontal directions stored transposed (gspn_scan_fwd_transposed)")
     ap.add_argument("--proxy", action="store_true",
                     help="also time the compressive proxy projections (table under detail.proxy_projections)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="also time the per-line-launch comparator against the fused forward (table under detail.fused_vs_unfused)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
     ap.add_argument("--out", default="bench_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -412,6 +456,8 @@ def main():
         line["cpu_baseline"] = cpu
     if a.proxy:
         line["detail"]["proxy_projections"] = proxy_table()
+    if a.unfused:
+        line["detail"]["fused_vs_unfused"] = unfused_table()
     if a.all:
         table = [s]
         for name, c in WL.CONFIGS.items():

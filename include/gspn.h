@@ -162,6 +162,20 @@ int gspn_scan_fwd_transposed(const void* x, const void* xt, const void* w, const
                              unsigned dir_mask, int dtype, unsigned flags, void* stream);
 const char* gspn_fwd_transposed_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
 
+/* COMPARATOR, not a product path: gspn_scan_fwd computed the way the first GSPN implementation ran it (Sec. 3.3;
+ * the step-by-step optimisation figure and Table 1 of Sec. 5.1): one small kernel launch per line and per
+ * direction, the hidden state of the previous line handed from launch to launch through global memory.  It is
+ * here so that the fused kernels can be timed against the structure they replace on the same hardware; no other
+ * entry point ever dispatches to it.  Arguments as for gspn_scan_fwd, plus a workspace of the caller's of at
+ * least gspn_unfused_workspace_bytes(B, C, H, W) bytes (two fp32 lines per (image, channel); a smaller one is
+ * GSPN_ERR_SHAPE).  The call enqueues (number of directions) x (lines per scan) launches on `stream`.  bf16 y is
+ * accumulated in storage precision direction by direction. */
+int gspn_scan_fwd_unfused(const void* x, const void* w, const void* lam, const void* u, void* y, void* h_save,
+                          void* workspace, unsigned long long workspace_bytes,
+                          int B, int C, int H, int W, int G,
+                          unsigned dir_mask, int dtype, unsigned flags, void* stream);
+unsigned long long gspn_unfused_workspace_bytes(int B, int C, int H, int W);
+
 /* Compressive proxy projection (Sec. 4.2, "Compressive Proxy Dimension"): the 1x1 convolution over the channel
  * axis that takes x from C channels to C_proxy before the scan, and the learned 1x1 projection back to C after it:
  *     out[b][m][h][w] = sum_k P[m][k] * in[b][k][h][w]
@@ -199,8 +213,11 @@ int gspn_proxy_project_bwd_static(const void* gout, const void* in, const void* 
 const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 
 /* Name of the kernel family the forward / backward call would dispatch to for
- * these arguments: "plane" (small maps, whole planes through LDS), "tile" (maps whose
- * merged output fits in LDS), "stream" (larger maps, forward only), "twopass" (backward
+ * these arguments: "plane" (small maps, whole planes through LDS), "pair" (128x128 bf16 maps
+ * with an even number of channels per weight group, all four directions: two channels of a
+ * group per workgroup, the merged output accumulated on chip in storage precision, i.e. rounded
+ * after each of the four additions), "tile" (maps whose merged output fits in LDS), "stream"
+ * (larger maps, forward only), "twopass" (backward
  * on the maps the forward plane, tile or stream kernels take: the reverse sweep per
  * channel on those kernels, then the sum over each group's channels; in bf16
  * storage e passes through storage precision between the two), "generic" (any shape);
@@ -211,7 +228,9 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  * that changes them afterwards calls gspn_reload_env():
  *   GSPN_FORCE_GENERIC=1   always the generic kernels
  *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
- *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps) */
+ *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps)
+ *   GSPN_FWD_NO_PAIR=1   skip the "pair" kernels (forward and the reverse sweep of the two-pass backward)
+ *   GSPN_STREAM_NO_STAGED=1   the "stream" kernel that requests one row per lane instead of whole lines */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);
 const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
 /* the same for the GSPN-local calls */

@@ -12,6 +12,7 @@ def __getattr__(name):
                 "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
                 "gspn_scan_fwd_logits", "gspn_scan_bwd_logits", "gspn_fwd_logits_plan", "gspn_bwd_logits_plan",
                 "gspn_proxy_project", "gspn_proxy_project_bwd", "gspn_proxy_project_bwd_static", "gspn_proxy_plan", "gspn_scan_fwd_transposed", "gspn_fwd_transposed_plan",
+                "gspn_scan_fwd_unfused", "gspn_unfused_workspace_bytes",
                 "gspn_status_string", "gspn_version", "gspn_reload_env", "load_library", "lib_path", "GspnError"):
         from . import binding
         return getattr(binding, name)

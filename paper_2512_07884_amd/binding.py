@@ -22,7 +22,7 @@ EXPORTS = ("gspn_scan_fwd", "gspn_scan_bwd", "gspn_scan_fwd_local", "gspn_scan_b
            "gspn_scan_fwd_logits", "gspn_scan_bwd_logits",
            "gspn_fwd_plan", "gspn_bwd_plan", "gspn_fwd_local_plan", "gspn_bwd_local_plan",
            "gspn_fwd_logits_plan", "gspn_bwd_logits_plan", "gspn_proxy_project", "gspn_proxy_project_bwd", "gspn_proxy_project_bwd_static", "gspn_proxy_plan",
-           "gspn_scan_fwd_transposed", "gspn_fwd_transposed_plan",
+           "gspn_scan_fwd_transposed", "gspn_fwd_transposed_plan", "gspn_scan_fwd_unfused", "gspn_unfused_workspace_bytes",
            "gspn_status_string", "gspn_version", "gspn_reload_env")
 
 
@@ -69,6 +69,10 @@ def load_library() -> ctypes.CDLL:
     lib.gspn_bwd_logits_plan.restype = ctypes.c_char_p
     lib.gspn_scan_fwd_transposed.argtypes = [vp] * 6 + [ci] * 5 + [cu, ci, cu, vp]
     lib.gspn_scan_fwd_transposed.restype = ci
+    lib.gspn_scan_fwd_unfused.argtypes = [vp] * 7 + [ctypes.c_ulonglong] + [ci] * 5 + [cu, ci, cu, vp]
+    lib.gspn_scan_fwd_unfused.restype = ci
+    lib.gspn_unfused_workspace_bytes.argtypes = [ci] * 4
+    lib.gspn_unfused_workspace_bytes.restype = ctypes.c_ulonglong
     lib.gspn_fwd_transposed_plan.argtypes = [ci] * 5 + [cu, ci, cu]
     lib.gspn_fwd_transposed_plan.restype = ctypes.c_char_p
     lib.gspn_proxy_project.argtypes = [vp] * 3 + [ci] * 6 + [vp]
@@ -317,3 +321,18 @@ def gspn_scan_fwd_transposed(x, xt, w, lam, u, y, *, G: Optional[int] = None, di
     args = [_ptr(x, "x", (B, C, H, W), x), _ptr(xt, "xt", (B, C, W, H), x), _ptr(w, "w", (slots, B, G, 3, H, W), x),
             _ptr(lam, "lam", (slots, B, C, H, W), x), _ptr(u, "u", (slots, B, C, H, W), x), _ptr(y, "y", (B, C, H, W), x)]
     _check(load_library().gspn_scan_fwd_transposed(*args, B, C, H, W, G, dir_mask, _dtype_code(x), flags, _stream(stream)))
+
+
+def gspn_unfused_workspace_bytes(B: int, C: int, H: int, W: int) -> int:
+    return int(load_library().gspn_unfused_workspace_bytes(B, C, H, W))
+
+
+def gspn_scan_fwd_unfused(x, w, lam, u, y, h_save, workspace, *, G: Optional[int] = None, dir_mask: int = DIR_ALL,
+                          flags: int = 0, stream=None) -> None:
+    """The comparator of the fused kernels: one launch per line and direction, the state handed on through global
+    memory (`workspace`: a device tensor of at least gspn_unfused_workspace_bytes(B, C, H, W) bytes).  Never dispatched
+    to by the other calls."""
+    ptrs, (B, C, H, W, G) = _fwd_args(x, w, lam, u, y, h_save, G, flags)
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().gspn_scan_fwd_unfused(*ptrs, workspace.data_ptr(), nbytes, B, C, H, W, G, dir_mask,
+                                                _dtype_code(x), flags, _stream(stream)))

@@ -67,6 +67,30 @@ int gspn_scan_fwd_transposed(const void* x, const void* xt, const void* w, const
     return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
 }
 
+int gspn_scan_fwd_unfused(const void* x, const void* w, const void* lam, const void* u, void* y, void* h_save,
+                          void* workspace, unsigned long long workspace_bytes,
+                          int B, int C, int H, int W, int G,
+                          unsigned dir_mask, int dtype, unsigned flags, void* stream) {
+    if (!x || !w || !lam || !u || !y || !workspace) return GSPN_ERR_NULL;
+    int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
+    if (st != GSPN_OK) return st;
+    if (misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y) || misaligned(workspace) ||
+        (h_save && misaligned(h_save)))
+        return GSPN_ERR_ALIGN;
+    if (workspace_bytes < unfused_workspace_bytes(B, C, H, W)) return GSPN_ERR_SHAPE;
+    FwdParams p = {};
+    p.x = x; p.w = w; p.lam = lam; p.u = u; p.y = y; p.hs = h_save;
+    p.B = B; p.C = C; p.H = H; p.W = W; p.G = G; p.cpg = C / G;
+    p.mask = dir_mask; p.shared = (flags & GSPN_FLAG_SHARED_PARAMS) ? 1 : 0;
+    hipError_t e = launch_fwd_unfused(p, dtype, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? GSPN_OK : GSPN_ERR_HIP;
+}
+
+unsigned long long gspn_unfused_workspace_bytes(int B, int C, int H, int W) {
+    if (B < 1 || C < 1 || H < 1 || W < 1) return 0;
+    return unfused_workspace_bytes(B, C, H, W);
+}
+
 const char* gspn_fwd_transposed_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags) {
     if (check_common(B, C, H, W, G, dir_mask, dtype, flags) != GSPN_OK) return "invalid";
     FwdParams p = {};

@@ -180,6 +180,10 @@ bool bwd_twopass_applicable(const BwdParams& p, int dtype);
 // clears `bytes` (a multiple of 16) of device memory with a kernel on stream s (no memset node: capturable)
 hipError_t launch_zero_fill(void* p, size_t bytes, hipStream_t s);
 
+// the per-line-launch comparator (gspn_unfused.hip): never dispatched to, timed against the fused kernels by bench.py
+size_t unfused_workspace_bytes(int B, int C, int H, int W);
+hipError_t launch_fwd_unfused(const FwdParams& p, int dtype, void* workspace, hipStream_t s);
+
 // compressive proxy projection (gspn_proxy.hip): out[b][m][n] = sum_k P[m][k] in[b][k][n]
 hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int N, int dtype, hipStream_t s);
 bool proxy_mfma_applicable(int B, int K, int M, int N, int dtype);

@@ -53,7 +53,6 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
     const int row_bytes = W * 2, nchunks = W / CS;
     const int g = c / p.cpg;
     const bool top_lane = lane == 0, bot_lane = lane == 63;
-    const bool edge = top_lane || bot_lane;
     const bool has_up = part > 0, has_dn = part < parts - 1;
     const bool img_first = top_lane && !has_up, img_last = bot_lane && !has_dn;
     rsrc_t xb, lb, ub, w0b, w1b, w2b, yb, hb;
@@ -71,11 +70,13 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
         yb = make_rsrc((char*)p.y + plane0 * 2);
         hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * 2 : (char*)p.y);
     }
-    // mailbox: [direction slot][part][side: 0 first row, 1 last row][parity]
+    // mailbox: [direction slot][part][parity] pairs (what the part above published for this part's first row, what the
+    // part below published for its last row): a wave reads its own pair with one request; its last row writes into the
+    // pair of the part below, its first row into the pair of the part above
     float* const task = mailbox + dslot * 8 * 4;
-    float* const mb_out = task + part * 4 + (bot_lane ? 2 : 0);
-    const float* const mb_up = task + (has_up ? part - 1 : part) * 4 + 2;
-    const float* const mb_dn = task + (has_dn ? part + 1 : part) * 4 + 0;
+    const f32x2_hw* const mb_in = (const f32x2_hw*)(task + part * 4);
+    float* const mb_out = bot_lane ? task + (part + 1) * 4 : task + (part - 1) * 4 + 1;
+    const bool publishes = (bot_lane && has_dn) || (top_lane && has_up);
     // request order: lane -> (row l / 8 of an instruction's eight rows, bytes 16 * (l % 8) ..); instruction i: rows 8i..
     const uint32_t voff = (uint32_t)(((part * 64 + (lane >> 3)) * W + 8 * (lane & 7)) * 2);
     const int istep = 8 * row_bytes;
@@ -145,8 +146,8 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
             constexpr int k = decltype(kc_)::value;
             constexpr int e = REV ? CS - 1 - k : k;
             constexpr int par = k & 1;
-            const float pu = mb_up[par ^ 1];                     // edge state the neighbouring part published in the previous step
-            const float pd = mb_dn[par ^ 1];
+            const f32x2_hw pin = mb_in[par ^ 1];                 // edge states the neighbouring parts published in the previous step
+            const float pu = pin.x, pd = pin.y;
             if ((k & 1) == 0) yw = yrow[e >> 1];
             const float av = elem<bf16_t>(bl, e) * elem<bf16_t>(bx, e);
             float c0 = elem<bf16_t>(b0, e), c1 = elem<bf16_t>(b1, e), c2 = elem<bf16_t>(b2, e);
@@ -161,7 +162,7 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
                 wp0 = img_first ? 0.f : c0;
                 wp1 = c1;
                 wp2 = img_last ? 0.f : c2;
-                if (edge) mb_out[par] = bot_lane ? wp2 * h : wp0 * h;
+                if (publishes) mb_out[par * 2] = bot_lane ? wp2 * h : wp0 * h;
             } else {
                 if (k == 0) {
                     const bool start = ch == 0;                  // scan step 0: its weights are never read
@@ -173,7 +174,7 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
                 c0 = img_first ? 0.f : c0;
                 c2 = img_last ? 0.f : c2;
                 h = fmaf(c0, up, fmaf(c1, h, fmaf(c2, dn, av)));
-                if (edge) mb_out[par] = h;
+                if (publishes) mb_out[par * 2] = h;
             }
             const float cv = elem<bf16_t>(bu, e) * h;
             if ((k & 1) == 0) { cpair = cv; hpair = h; }
@@ -193,7 +194,7 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
                 if (ch + 1 < nchunks) issue_slot(ch + 1, e >> 3);
                 // ... and towards the end of the chunk the next chunk of y is asked for, unless the other direction is
                 // still to write it
-                if (k == 47 && y_ahead) issue_y(ch + 1);
+                if (k == (BWD ? 55 : 47) && y_ahead) issue_y(ch + 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
         });

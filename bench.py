@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "diff128"   # 128x128 diffusion-latent shape: first of the two target shapes
-TRAINING = ("train28_gc", "train28_g4", "train56", "train128", "train512")
+TRAINING = ("train28_gc", "train28_g4", "train56", "train128", "train512", "occ128_train")
 
 
 def device_inputs(cfg, seed: int, logits: bool = False):
@@ -353,6 +353,29 @@ def unfused_table(steps: int = 3):
                                             "NVIDIA A100 (Sec. 5.1): another machine and a tuned baseline; context, not a target"}
 
 
+def chunk_axis_table(steps: int = 200, kchunk: int = 32):
+    """GSPN-local on a call with few planes (Sec. 3.2, Sec. 4.1: the chunk index is part of the grid): the global scan
+    beside the local one, whose stretches are work items of their own, on the low-occupancy shape of Table 1."""
+    from paper_2512_07884_amd import workloads as WL
+    rows = []
+    for name in ("occ128", "occ128_train"):
+        cfg = WL.CONFIGS[name]
+        for dtype in ("f32", "bf16"):
+            c = WL.shrink(cfg, dtype=dtype)
+            g = summarise(c, run_workload(c, steps, 10))
+            l = summarise(c, run_workload(c, steps, 10, kchunk))
+            row = {"workload": f"{name}: B={c.B} C={c.C} H={c.H} W={c.W} G={c.G} {dtype}", "kchunk": kchunk,
+                   "global_fwd_kernel": g["fwd_kernel"], "local_fwd_kernel": l["fwd_kernel"],
+                   "global_fwd_ms": g["fwd_ms_avg"], "local_fwd_ms": l["fwd_ms_avg"],
+                   "fwd_global_over_local": g["fwd_ms_avg"] / l["fwd_ms_avg"]}
+            if "bwd_ms_avg" in g:
+                row.update(global_bwd_ms=g["bwd_ms_avg"], local_bwd_ms=l["bwd_ms_avg"],
+                           bwd_global_over_local=g["bwd_ms_avg"] / l["bwd_ms_avg"],
+                           global_step_ms=g["ms_per_step"], local_step_ms=l["ms_per_step"])
+            rows.append(row)
+    return rows
+
+
 def copy_calibration(n_bytes: int = 1 << 30, reps: int = 5):
     """Plain copies of a known size: each must read and write exactly n_bytes, which
     fixes the unit in which the profiler's FETCH_SIZE / WRITE_SIZE counters report."""
@@ -381,6 +404,8 @@ def main():
                     help="also time the compressive proxy projections (table under detail.proxy_projections)")
     ap.add_argument("--unfused", action="store_true",
                     help="also time the per-line-launch comparator against the fused forward (table under detail.fused_vs_unfused)")
+    ap.add_argument("--chunk-axis", action="store_true",
+                    help="also time GSPN-local against the global scan on the low-occupancy shape (detail.local_chunk_axis)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
     ap.add_argument("--out", default="bench_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -458,6 +483,8 @@ def main():
         line["detail"]["proxy_projections"] = proxy_table()
     if a.unfused:
         line["detail"]["fused_vs_unfused"] = unfused_table()
+    if a.chunk_axis:
+        line["detail"]["local_chunk_axis"] = chunk_axis_table()
     if a.all:
         table = [s]
         for name, c in WL.CONFIGS.items():

@@ -35,9 +35,10 @@
  * pointer after a call returns, allocates nothing and frees nothing.
  * Arithmetic: inputs are widened to fp32, the carried state and all sums are
  * fp32, each stored value is rounded once to nearest-even -- except the merged
- * bf16 y / gx of feature maps too large to stage on chip, which are accumulated
- * in storage precision direction by direction (at most one extra rounding per
- * direction).
+ * bf16 y / gx where the running sum over the directions is kept in storage
+ * precision (feature maps too large to stage on chip, merged in place in global
+ * memory, and 128x128 maps on the "pair" kernels, whose on-chip tile is bf16):
+ * at most one extra rounding per direction.
  *
  * Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
  * default stream) and return without synchronising.  Outputs are overwritten in
@@ -112,7 +113,12 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
  * ownership, stream semantics, errors) is as for gspn_scan_fwd / gspn_scan_bwd, and h_save written by
  * the local forward call is what the local backward call with the same kchunk expects.
  * Every kernel family has local instantiations, so a local call runs on the same family as the global
- * call of its shape (gspn_fwd_local_plan / gspn_bwd_local_plan name it). */
+ * call of its shape (gspn_fwd_local_plan / gspn_bwd_local_plan name it) -- except calls with few planes
+ * (B*C <= 256) on maps of 64, 128 or 256 rows and columns whose kchunk divides both sides (and is a
+ * multiple of 16 bytes of storage), all four directions, no logits: there the stretches are the work items
+ * (Sec. 4.1: the chunk index is part of the grid; plan "chunk"), one workgroup per (plane, stretch) in two
+ * launches (vertical stretches, then horizontal ones adding onto y: in bf16 storage y is rounded twice),
+ * and the reverse sweep of the backward call runs the same way. */
 int gspn_scan_fwd_local(const void* x, const void* w, const void* lam, const void* u,
                         void* y, void* h_save,
                         int B, int C, int H, int W, int G, int kchunk,
@@ -230,7 +236,8 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
  *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps)
  *   GSPN_FWD_NO_PAIR=1   skip the "pair" kernels (forward and the reverse sweep of the two-pass backward)
- *   GSPN_STREAM_NO_STAGED=1   the "stream" kernel that requests one row per lane instead of whole lines */
+ *   GSPN_STREAM_NO_STAGED=1   the "stream" kernel that requests one row per lane instead of whole lines
+ *   GSPN_FWD_NO_CHUNK=1   skip the "chunk" kernels of GSPN-local (forward and the reverse sweep of the two-pass backward) */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);
 const char* gspn_bwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags);
 /* the same for the GSPN-local calls */

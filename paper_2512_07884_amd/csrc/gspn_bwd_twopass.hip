@@ -32,6 +32,8 @@ hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_
 bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype);
 hipError_t launch_reverse_sweep_pair(const FwdParams& p, int dtype, hipStream_t s);      // 128x128 bf16, two channels per workgroup
 bool reverse_sweep_pair_applicable(const FwdParams& p, int dtype);
+hipError_t launch_reverse_sweep_chunk(const FwdParams& p, int dtype, hipStream_t s);     // GSPN-local, one workgroup per stretch
+bool reverse_sweep_chunk_applicable(const FwdParams& p, int dtype);
 
 namespace {
 
@@ -226,14 +228,17 @@ hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
 bool bwd_twopass_applicable(const BwdParams& p, int dtype) {
     if ((size_t)p.B * p.G * ((size_t)p.H * p.W) * 4 / 256 > 0x7fffffffull) return false;
     const FwdParams f = reverse_sweep_params(p);
-    return reverse_sweep_plane_applicable(f, dtype) || fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype);
+    return reverse_sweep_plane_applicable(f, dtype) || fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype) ||
+           (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype));
 }
 
 hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     if (!bwd_twopass_applicable(p, dtype)) return hipErrorInvalidValue;
     const FwdParams f = reverse_sweep_params(p);
     hipError_t e;
-    if (reverse_sweep_plane_applicable(f, dtype)) {
+    if (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype)) {
+        e = launch_reverse_sweep_chunk(f, dtype, s);
+    } else if (reverse_sweep_plane_applicable(f, dtype)) {
         e = launch_reverse_sweep_plane(f, dtype, s);
     } else if (pair_kernels_enabled() && reverse_sweep_pair_applicable(f, dtype)) {
         e = launch_reverse_sweep_pair(f, dtype, s);

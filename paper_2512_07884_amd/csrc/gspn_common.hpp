@@ -171,6 +171,9 @@ hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_stream_applicable(const FwdParams& p, int dtype);
 hipError_t launch_fwd_pair(const FwdParams& p, int dtype, hipStream_t s);
 bool fwd_pair_applicable(const FwdParams& p, int dtype);
+// GSPN-local with one workgroup per (plane, stretch): for calls with few planes (gspn_fwd_chunk.hip)
+hipError_t launch_fwd_chunk(const FwdParams& p, int dtype, hipStream_t s);
+bool fwd_chunk_applicable(const FwdParams& p, int dtype);
 hipError_t launch_bwd_tile(const BwdParams& p, int dtype, hipStream_t s);
 bool bwd_tile_applicable(const BwdParams& p, int dtype);
 hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s);
@@ -204,6 +207,7 @@ const char* fwd_plan_name(const FwdParams& p, int dtype);
 const char* bwd_plan_name(const BwdParams& p, int dtype);
 bool staged_stream_enabled();  // false while GSPN_STREAM_NO_STAGED=1 keeps the whole-line stream kernel out (testing aid)
 bool pair_kernels_enabled();   // false while GSPN_FWD_NO_PAIR=1 keeps the two-channel kernels out (testing aid)
+bool chunk_kernels_enabled();  // false while GSPN_FWD_NO_CHUNK=1 keeps the per-stretch kernels of GSPN-local out (testing aid)
 void reload_env_knobs();   // re-reads the GSPN_* testing aids from the environment (they are read once otherwise)
 
 }  // namespace gspn

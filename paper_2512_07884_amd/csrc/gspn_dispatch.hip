@@ -5,7 +5,7 @@
 
 namespace gspn {
 
-enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1, FWD_STREAM = 2, FWD_PLANE = 3, FWD_PAIR = 4 };
+enum FwdPlan { FWD_GENERIC = 0, FWD_TILE = 1, FWD_STREAM = 2, FWD_PLANE = 3, FWD_PAIR = 4, FWD_CHUNK = 5 };
 enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1, BWD_PLANE = 2, BWD_TWOPASS = 3 };
 
 // Testing aids that keep every kernel family reachable on every shape it accepts.  The environment is read once, on
@@ -14,8 +14,9 @@ enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1, BWD_PLANE = 2, BWD_TWOPASS = 3 };
 // GSPN_FORCE_GENERIC=1: the generic kernels; GSPN_FWD_NO_PLANE=1 / GSPN_BWD_NO_PLANE=1: skip the plane kernels;
 // GSPN_BWD_NO_TWOPASS=1: skip the two-pass backward; GSPN_FWD_NO_PAIR=1: skip the two-channel kernels (forward and the
 // reverse sweep of the two-pass backward); GSPN_STREAM_NO_STAGED=1: the stream kernel whose horizontal phases request one
-// row per lane instead of the one with whole-line requests.
-enum : unsigned { K_FORCE_GENERIC = 1, K_FWD_NO_PLANE = 2, K_BWD_NO_PLANE = 4, K_BWD_NO_TWOPASS = 8, K_FWD_NO_PAIR = 16, K_STREAM_NO_STAGED = 32, K_VALID = 1u << 31 };
+// row per lane instead of the one with whole-line requests; GSPN_FWD_NO_CHUNK=1: skip the per-stretch kernels of GSPN-local
+// (forward and the reverse sweep of the two-pass backward).
+enum : unsigned { K_FORCE_GENERIC = 1, K_FWD_NO_PLANE = 2, K_BWD_NO_PLANE = 4, K_BWD_NO_TWOPASS = 8, K_FWD_NO_PAIR = 16, K_STREAM_NO_STAGED = 32, K_FWD_NO_CHUNK = 64, K_VALID = 1u << 31 };
 static std::atomic<unsigned> g_knobs{0};
 static bool env_flag(const char* name) { const char* v = getenv(name); return v && v[0] == '1'; }
 void reload_env_knobs() {
@@ -26,21 +27,24 @@ void reload_env_knobs() {
     if (env_flag("GSPN_BWD_NO_TWOPASS")) k |= K_BWD_NO_TWOPASS;
     if (env_flag("GSPN_FWD_NO_PAIR")) k |= K_FWD_NO_PAIR;
     if (env_flag("GSPN_STREAM_NO_STAGED")) k |= K_STREAM_NO_STAGED;
+    if (env_flag("GSPN_FWD_NO_CHUNK")) k |= K_FWD_NO_CHUNK;
     g_knobs.store(k, std::memory_order_release);
 }
-struct Knobs { bool force_generic, fwd_no_plane, bwd_no_plane, bwd_no_twopass, fwd_no_pair, stream_no_staged; };
+struct Knobs { bool force_generic, fwd_no_plane, bwd_no_plane, bwd_no_twopass, fwd_no_pair, stream_no_staged, fwd_no_chunk; };
 static Knobs knobs() {
     unsigned k = g_knobs.load(std::memory_order_acquire);
     if (!(k & K_VALID)) { reload_env_knobs(); k = g_knobs.load(std::memory_order_acquire); }
-    return Knobs{(k & K_FORCE_GENERIC) != 0, (k & K_FWD_NO_PLANE) != 0, (k & K_BWD_NO_PLANE) != 0, (k & K_BWD_NO_TWOPASS) != 0, (k & K_FWD_NO_PAIR) != 0, (k & K_STREAM_NO_STAGED) != 0};
+    return Knobs{(k & K_FORCE_GENERIC) != 0, (k & K_FWD_NO_PLANE) != 0, (k & K_BWD_NO_PLANE) != 0, (k & K_BWD_NO_TWOPASS) != 0, (k & K_FWD_NO_PAIR) != 0, (k & K_STREAM_NO_STAGED) != 0, (k & K_FWD_NO_CHUNK) != 0};
 }
 bool pair_kernels_enabled() { return !knobs().fwd_no_pair; }
-bool staged_stream_enabled() { return !knobs().stream_no_staged;
-}
+bool staged_stream_enabled() { return !knobs().stream_no_staged; }
+bool chunk_kernels_enabled() { return !knobs().fwd_no_chunk; }
 
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const Knobs k = knobs();
     if (k.force_generic) return FWD_GENERIC;
+    // GSPN-local with few planes: the stretches as work items (Sec. 4.1), before any one-workgroup-per-plane kernel
+    if (!k.fwd_no_chunk && fwd_chunk_applicable(p, dtype)) return FWD_CHUNK;
     if (!k.fwd_no_plane && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
     if (!k.fwd_no_pair && fwd_pair_applicable(p, dtype)) return FWD_PAIR;
     if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
@@ -71,6 +75,7 @@ hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {
         case FWD_STREAM: return launch_fwd_stream(p, dtype, s);
         case FWD_PLANE: return launch_fwd_plane(p, dtype, s);
         case FWD_PAIR: return launch_fwd_pair(p, dtype, s);
+        case FWD_CHUNK: return launch_fwd_chunk(p, dtype, s);
         default: return launch_fwd_generic(p, dtype, s);
     }
 }
@@ -90,6 +95,7 @@ const char* fwd_plan_name(const FwdParams& p, int dtype) {
         case FWD_STREAM: return "stream";
         case FWD_PLANE: return "plane";
         case FWD_PAIR: return "pair";
+        case FWD_CHUNK: return "chunk";
         default: return "generic";
     }
 }

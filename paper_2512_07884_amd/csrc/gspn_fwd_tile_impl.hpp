@@ -15,8 +15,9 @@
 //    buffered in registers.
 //  * The merged output y = sum_d u_d*h_d (Eq. 2 + sum merge) is accumulated in an fp32 LDS
 //    tile by plain read-modify-write (every element has one owner wave between two barriers)
-//    and written once, coalesced, rounded once to the storage type.  x is the only tensor
-//    read more than once (once per direction).
+//    and written once, coalesced, rounded once to the storage type.  x is read once per
+//    direction and the weight planes of a group once per channel (the two-channel kernel for
+//    128x128 bf16 maps shares both within a workgroup).
 //  * Accumulation order per output element is fixed (vertical pair first -- its two
 //    contributions commute --, then the horizontal pair split at mid-scan by a barrier so
 //    that the two waves never touch the same element in the same half), so results are

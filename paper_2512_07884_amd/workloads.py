@@ -87,6 +87,10 @@ CONFIGS = {
     "train56":     ScanConfig("train56", 64, 96, 56, 56, 8, "bf16", 15, 1.0, 7),
     "train128":    ScanConfig("train128", 2, 1024, 128, 128, 16, "bf16", 15, 3.0, 5),
     "train512":    ScanConfig("train512", 1, 512, 512, 512, 16, "bf16", 15, 1.0, 6),
+    # the low-occupancy shape of the paper's throughput table (Table 1: 128x128, B = 1, C = 32; the group count is not
+    # stated there): fewer planes than the chip has compute units, where GSPN-local's stretches are the work items
+    "occ128":      ScanConfig("occ128", 1, 32, 128, 128, 4, "f32", 15, 1.0, 8),
+    "occ128_train": ScanConfig("occ128_train", 1, 32, 128, 128, 4, "f32", 15, 1.0, 8),
 }
 
 

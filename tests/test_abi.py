@@ -105,7 +105,7 @@ def test_plan_names(lib):
 
 def test_kernel_family_chosen_for_local_scans(lib, monkeypatch):
     """GSPN-local dispatches like the global scan: every kernel family has its local instantiations."""
-    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE"):
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_FWD_NO_CHUNK"):
         monkeypatch.delenv(v, raising=False)
     fwd = lambda *a: lib.gspn_fwd_local_plan(*a).decode()
     bwd = lambda *a: lib.gspn_bwd_local_plan(*a).decode()
@@ -113,6 +113,9 @@ def test_kernel_family_chosen_for_local_scans(lib, monkeypatch):
     assert fwd(2, 1024, 128, 128, 16, 32, 15, 1, 0, 0) == "tile" and bwd(64, 96, 56, 56, 8, 14, 15, 1, 0) == "twopass"
     assert fwd(1, 512, 512, 512, 16, 64, 15, 1, 0, 0) == "stream" and fwd(1, 2, 130, 67, 1, 9, 15, 0, 0, 0) == "generic"
     assert fwd(1, 8, 16, 16, 1, 0, 15, 0, 0, 0) == "invalid" and bwd(1, 8, 16, 16, 1, 0, 15, 0, 0) == "invalid"
+    # few planes: the stretches are the work items (Sec. 4.1: the chunk index is part of the grid)
+    assert fwd(1, 32, 128, 128, 4, 32, 15, 0, 0, 0) == "chunk" and fwd(1, 32, 128, 128, 4, 32, 15, 1, 0, 1) == "chunk"
+    assert bwd(1, 32, 128, 128, 4, 32, 15, 0, 0) == "twopass"
 
 
 def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):

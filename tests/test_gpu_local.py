@@ -116,6 +116,7 @@ def test_local_scans_on_the_plane_kernels(shape, kchunk, monkeypatch):
     ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_local_scans_on_larger_and_ragged_maps(shape, kchunk, plans, monkeypatch):
     import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FWD_NO_CHUNK", "1")           # (the per-stretch kernels take 128x128 with kchunk 32 first)
     if plans[1] == "tile":
         monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")     # (the two-pass backward takes these maps first)
     B, C, H, W, Gr, dtype = shape
@@ -139,6 +140,59 @@ def test_local_scans_on_the_tile_kernels_for_small_maps(shape, kchunk, monkeypat
     assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, True) == "tile"
     assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0) == "tile"
     check_local(shape, kchunk)
+
+
+# calls with few planes: one workgroup per (plane, stretch) -- the stretch as a work item (Sec. 4.1: grid indexed by
+# (chunk, n, c)); every positions-per-lane / rows-per-lane variant in both storage types, forward with and without
+# h_save and the two-pass backward whose reverse sweep runs on the same kernels
+CHUNK_LOCAL = [((1, 32, 128, 128, 4, "f32"), 32), ((1, 32, 128, 128, 2, "bf16"), 32), ((2, 6, 64, 128, 3, "f32"), 16),
+               ((1, 4, 256, 128, 2, "bf16"), 64), ((1, 3, 128, 256, 1, "bf16"), 8), ((1, 2, 256, 256, 2, "f32"), 64),
+               ((1, 4, 64, 64, 2, "f32"), 4), ((1, 2, 64, 256, 1, "bf16"), 32), ((1, 4, 128, 64, 4, "f32"), 64),
+               ((1, 2, 256, 64, 1, "f32"), 32), ((1, 2, 64, 128, 2, "bf16"), 8)]
+
+
+@pytest.mark.parametrize("shape,kchunk", CHUNK_LOCAL, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_local_scans_with_one_workgroup_per_stretch(shape, kchunk):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    dt = int(dtype == "bf16")
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, True) == "chunk"
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, False) == "chunk"
+    assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0) == "twopass"
+    check_local(shape, kchunk, poison_starts=True)
+
+
+def test_per_stretch_kernels_are_for_calls_with_few_planes(monkeypatch):
+    import paper_2512_07884_amd as G
+    assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 32, 15, 0, 0, False) == "chunk"
+    assert G.gspn_fwd_local_plan(2, 1024, 128, 128, 16, 32, 15, 1, 0, False) == "tile"      # planes fill the chip
+    assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 24, 15, 0, 0, False) == "tile"         # kchunk does not divide
+    assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 128, 15, 0, 0, False) == "tile"        # a single stretch
+    assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 32, 5, 0, 0, False) == "tile"          # not all four directions
+    assert G.gspn_fwd_plan(1, 32, 128, 128, 4, 15, 0, 0, False) == "tile"                   # the global scan
+    monkeypatch.setenv("GSPN_FWD_NO_CHUNK", "1")
+    assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 32, 15, 0, 0, False) == "tile"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_per_stretch_kernels_with_one_parameter_set_for_all_directions(dtype):
+    import torch
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, k = 1, 4, 128, 128, 2, 32
+    cfg = WL.ScanConfig("chunkshared", B, C, H, W, Gr, dtype, 15, 1.0, 93)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    one = {"x": inp["x"], "w": inp["w"][:1].copy(), "lam": inp["lam"][:1].copy(), "u": inp["u"][:1].copy()}
+    rep = {"x": inp["x"], "w": np.repeat(one["w"], 4, 0), "lam": np.repeat(one["lam"], 4, 0), "u": np.repeat(one["u"], 4, 0)}
+    f = WL.inputs_as_f64(rep, dtype)
+    y_ref, h_ref = O.scan_fwd_local(f["x"], f["w"], f["lam"], f["u"], k, 15)
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, k, 15, int(dtype == "bf16"), 1, True) == "chunk"
+    dev = {n: to_device(v, dtype) for n, v in one.items()}
+    y = empty_like_dev((B, C, H, W), dtype, float("nan"))
+    hs = empty_like_dev((4, B, C, H, W), dtype, float("nan"))
+    G.gspn_scan_fwd_local(dev["x"], dev["w"], dev["lam"], dev["u"], y, hs, kchunk=k, G=Gr, flags=1)
+    torch.cuda.synchronize()
+    assert rel_inf_err(to_host_f64(y), y_ref) <= TOL[dtype]
+    assert rel_inf_err(to_host_f64(hs), h_ref) <= TOL[dtype]
 
 
 @pytest.mark.parametrize("shape,kchunk", [((1, 2, 256, 256, 1, "bf16"), 37), ((1, 2, 512, 512, 2, "bf16"), 64),

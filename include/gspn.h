@@ -223,7 +223,9 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  * with an even number of channels per weight group, all four directions: two channels of a
  * group per workgroup, the merged output accumulated on chip in storage precision, i.e. rounded
  * after each of the four additions), "tile" (maps whose merged output fits in LDS), "stream"
- * (larger maps, forward only), "twopass" (backward
+ * (larger maps with rows and columns in multiples of 64: up to 512 rows and lines of 256, 512 or 1024 positions in
+ * one launch; the global scan also on up to 1024 rows and lines of up to 1024 (fp32) / 2048 (bf16) positions, in two
+ * launches -- the vertical pair, then the horizontal pair; the merged output is accumulated in place in y), "twopass" (backward
  * on the maps the forward plane, tile or stream kernels take: the reverse sweep per
  * channel on those kernels, then the sum over each group's channels; in bf16
  * storage e passes through storage precision between the two), "generic" (any shape);

@@ -87,6 +87,10 @@ CONFIGS = {
     "train56":     ScanConfig("train56", 64, 96, 56, 56, 8, "bf16", 15, 1.0, 7),
     "train128":    ScanConfig("train128", 2, 1024, 128, 128, 16, "bf16", 15, 3.0, 5),
     "train512":    ScanConfig("train512", 1, 512, 512, 512, 16, "bf16", 15, 1.0, 6),
+    # the 1024x1024 shapes of the paper's scaling study (Sec. 5.1: B = 16, C = 8) and of high-resolution generation
+    # (App. B: 1152 channels); group counts are not stated there
+    "scale1024":   ScanConfig("scale1024", 16, 8, 1024, 1024, 1, "f32", 15, 1.0, 9),
+    "hires1024":   ScanConfig("hires1024", 1, 1152, 1024, 1024, 16, "bf16", 15, 1.0, 10),
     # the low-occupancy shape of the paper's throughput table (Table 1: 128x128, B = 1, C = 32; the group count is not
     # stated there): fewer planes than the chip has compute units, where GSPN-local's stretches are the work items
     "occ128":      ScanConfig("occ128", 1, 32, 128, 128, 4, "f32", 15, 1.0, 8),

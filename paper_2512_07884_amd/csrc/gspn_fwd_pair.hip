@@ -3,12 +3,11 @@
 // directions of Sec. 3.2 over them inside one launch (Sec. 4.1), built around how few bytes a compute unit can pull
 // through its vector cache per unit time and around a register file of 512 registers per lane for a single wave:
 //
-//  * Vertical pair (rows are contiguous in memory): two waves copy whole bands of eight rows -- x, lam, u of each
-//    (channel, direction) chain and the three weight planes of each direction -- from memory into an LDS ring with
-//    16-byte-per-lane requests (every request is whole cache lines, two bands in flight per wave), and two waves run
-//    the recurrences of Eq. 1 out of that ring: one wave per walk (rows downwards / upwards), both channels side by
-//    side in it, two columns per lane, neighbours by DPP.  The weights of a band are fetched and read once for the
-//    two channels (Sec. 4.2: the channels of a group share them).  One barrier per band.
+//  * Vertical pair (rows are contiguous in memory): one wave per (channel, walk) runs the recurrence of Eq. 1 down or up
+//    the rows, two columns per lane, neighbours by DPP.  It requests the rows of its own x, lam, u itself (256
+//    contiguous bytes per request, four bands of four rows in flight); the weights of a walk serve both channels
+//    (Sec. 4.2: the channels of a group share them), so its two waves request half of a band's weight rows each and
+//    hand them to each other through a small LDS ring.  One barrier per band.
 //  * Horizontal pair (a scan step is an image column): one wave per (channel, direction) holds all 128 image rows, two
 //    adjacent rows per lane, so the three-neighbour read of Eq. 1 is two DPP shifts and in-lane moves and no wave
 //    ever waits for another inside a chunk.  A chunk is 64 scan steps of the six tensors (12 x 32 registers per lane).
@@ -20,6 +19,8 @@
 //    out once at the end.  The running sum is therefore rounded to bf16 after each of the four additions an element
 //    receives (at most 4 * 2^-8 of the largest partial sum in the worst case, about 5e-3 of max|y| observed), which
 //    is what frees the LDS for the staging above.
+//  * The launch has one workgroup per compute unit (its LDS holds one); a workgroup works through its share of the
+//    channel pairs and has the first requests of the next pair on their way before the current one is finished.
 //  * SAVE stores the hidden states per direction (h_save); BWD is the reverse sweep of the two-pass backward scan on the
 //    same machinery (gy as x, u as lam, lam as u, gx as y, e into hs; see gspn_bwd_twopass.hip).
 #include "gspn_tile_common.hpp"
@@ -41,17 +42,16 @@ constexpr int ROW_B = PW * 2;                     // bytes per image row
 constexpr int PLANE_B = HW * 2;
 constexpr int TPITCH = PW / 2 + 1;                // words between two rows of an output tile (odd: see above)
 constexpr int TILE_WORDS = PH * TPITCH;           // one channel's output tile, two columns per word
-constexpr int BAND = 8;                           // rows per band of the vertical pair
-constexpr int NBANDS = PH / BAND;
-constexpr int UNIT_B = 1024;                      // one 16-byte-per-lane request of a wave
-constexpr int BAND_B = BAND * ROW_B;              // one tensor's band: two units
-constexpr int NTB = 4 * 3 + 2 * 3;                // tensor bands per ring slot: (x, lam, u) of four chains, three taps of two walks
-constexpr int SLOT_B = NTB * BAND_B;              // 36 KB
+constexpr int VBAND = 4;                          // rows per band of the vertical pair
+constexpr int VNBANDS = PH / VBAND;
+constexpr int VPF = 4;                            // bands of a chain's own tensors in flight
+constexpr int VSLOT_B = 2 * 3 * VBAND * ROW_B;    // weight ring slot: three taps of two walks, one band
 constexpr int SPITCH = 9;                         // 16-byte units between two rows of a staging block (128 bytes + 16)
 constexpr int STAGE_B = PH * SPITCH * 16;         // horizontal pair: 128 rows of 128 bytes per wave
-constexpr int REGION_B = 2 * SLOT_B > 4 * STAGE_B ? 2 * SLOT_B : 4 * STAGE_B;
+constexpr int REGION_B = 2 * VSLOT_B > 4 * STAGE_B ? 2 * VSLOT_B : 4 * STAGE_B;
 constexpr int CS = 64;                            // scan steps per chunk of the horizontal pair (128 bytes per row)
 constexpr int LDS_BYTES = 2 * TILE_WORDS * 4 + REGION_B;
+constexpr size_t PERSIST_WGS = 256;               // compute units of the chip this is written for
 
 __device__ __forceinline__ float lo16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -62,166 +62,171 @@ __device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t voff, int soff) {
 __device__ __forceinline__ int tile_row(int r) { return (r >> 1) + (PH / 2) * (r & 1); }
 
 // ---------------------------------------------------------------------------
-// vertical pair, loader waves: band s of every tensor -> ring slot s & 1
+// vertical pair: one wave = the chain of one (channel, walk), two columns per lane
 // ---------------------------------------------------------------------------
-// Tensor band tb of a slot (2 KB at byte tb * 2048): 0..11 are x, lam, u of chain 0..3 (chain = channel * 2 + walk,
-// walk 0 = rows downwards), 12..17 the taps 0..2 of the two walks.  Loader j copies half j of every tensor band.  A chain
-// that walks the rows upwards takes its bands from the bottom of the plane.
-template <bool BWD>
-struct BandLoader {
-    const char* src[NTB];
-    uint32_t off_dn, off_up;      // this lane's byte offset into band 0 of a plane for the two walks
-    uint32_t lds_off;
-    u32x4 ra[NTB], rb[NTB];
-
-    __device__ __forceinline__ void init(const FwdParams& p, int b, int c0, int j, int lane) {
-        const int g = c0 / p.cpg;
-        const size_t planes = (size_t)p.B * p.C;
-        off_dn = (uint32_t)(j * UNIT_B + lane * 16);
-        off_up = off_dn + (uint32_t)((NBANDS - 1) * BAND_B);
-        lds_off = off_dn;
-#pragma unroll
-        for (int tb = 0; tb < NTB; ++tb) {
-            if (tb < 12) {
-                const int chain = tb / 3, tensor = tb - chain * 3, ch = chain >> 1, walk = chain & 1;
-                const int d = BWD ? 1 - walk : walk;               // the parameters this chain works on
-                const size_t slot_c = p.shared ? 0 : (size_t)d * planes * HW;
-                const size_t plane = ((size_t)b * p.C + c0 + ch) * HW;
-                src[tb] = tensor == 0 ? (const char*)p.x + plane * 2
-                        : tensor == 1 ? (const char*)p.lam + (slot_c + plane) * 2
-                                      : (const char*)p.u + (slot_c + plane) * 2;
-            } else {
-                const int t = tb - 12, walk = t / 3, tap = t - walk * 3;
-                const int d = BWD ? 1 - walk : walk;
-                const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
-                src[tb] = (const char*)p.w + (slot_w + (((size_t)b * p.G + g) * 3 + tap) * HW) * 2;
-            }
-        }
-    }
-    static __device__ __forceinline__ constexpr bool walks_up(int tb) { return tb < 12 ? ((tb / 3) & 1) != 0 : (tb - 12) / 3 != 0; }
-    __device__ __forceinline__ void issue(u32x4 (&r)[NTB], int s) {
-        const uint32_t dn = off_dn + (uint32_t)(s * BAND_B), up = off_up - (uint32_t)(s * BAND_B);
-#pragma unroll
-        for (int tb = 0; tb < NTB; ++tb) r[tb] = *(const u32x4*)(src[tb] + (walks_up(tb) ? up : dn));
-    }
-    __device__ __forceinline__ void drop(const u32x4 (&r)[NTB], char* slot) {
-#pragma unroll
-        for (int tb = 0; tb < NTB; ++tb) *(u32x4*)(slot + lds_off + tb * BAND_B) = r[tb];
-    }
-    // tail() is called once, when the last band is on its way to LDS (the wave's own requests for what comes next)
-    template <typename F>
-    __device__ __forceinline__ void run(char* region, F& tail) {
-        issue(ra, 0);
-        issue(rb, 1);
-        drop(ra, region);
-        issue(ra, 2);
-        lds_barrier();
-        for (int s = 0; s < NBANDS - 4; s += 2) {
-            // while the chains work on band s (slot 0), band s + 1 goes to slot 1 and band s + 3 is requested
-            drop(rb, region + SLOT_B);
-            issue(rb, s + 3);
-            lds_barrier();
-            drop(ra, region);
-            issue(ra, s + 4);
-            lds_barrier();
-        }
-        // the last four bands: nothing is left to request after the last one
-        drop(rb, region + SLOT_B);
-        issue(rb, NBANDS - 1);
-        lds_barrier();
-        drop(ra, region);
-        lds_barrier();
-        drop(rb, region + SLOT_B);
-        tail();
-        lds_barrier();
-        lds_barrier();
-    }
-};
-
-// ---------------------------------------------------------------------------
-// vertical pair, compute waves: the two channels' chains of one walk out of the ring
-// ---------------------------------------------------------------------------
-// ahead() is called once, V_AHEAD bands before the end (the wave's own requests for what comes next)
-template <bool UP, bool SAVE, bool BWD, typename F>
-__device__ __forceinline__ void vertical_chains(const FwdParams& p, const char* region, uint32_t* tiles, int b, int c0, int lane, F& ahead) {
-    constexpr int d = BWD ? (UP ? 0 : 1) : (UP ? 1 : 0);
-    constexpr int V_AHEAD = 4;
-    const bool first = lane == 0, last = lane == 63;
+// The wave requests the rows of its own x, lam, u itself, one 4-byte-per-lane request per row (256 contiguous bytes:
+// two whole lines), VPF bands of VBAND rows ahead in registers.  The three weight planes of a walk serve both channels
+// (Sec. 4.2): the two waves of a walk request half of a band's rows each and hand them to each other through an LDS
+// ring of two slots (slot = [walk][tap][VBAND rows] of 256 bytes), one workgroup barrier per band.  A walk's first 64
+// rows are rows of the output tile nobody has touched yet; its last 64 hold what the opposite walk of the same channel
+// left there more than a band ago.
+// ahead() is called once, V_AHEAD bands before the end (the wave's own requests for what comes next).
+// The tensors of one chain behind buffer resources.
+struct ChainRefs { rsrc_t xb, lb, ub, w0b, w1b, w2b, hb; };
+template <bool UP, bool SAVE, bool BWD>
+__device__ __forceinline__ ChainRefs chain_refs(const FwdParams& p, int b, int c) {
+    constexpr int d = BWD ? (UP ? 0 : 1) : (UP ? 1 : 0);                      // the parameters this chain works on
+    const int g = c / p.cpg;
     const size_t planes = (size_t)p.B * p.C;
-    // SAVE: the two channels' planes of h_save are adjacent in memory
-    const rsrc_t hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + ((size_t)b * p.C + c0) * HW) * 2 : (char*)p.y);
+    const size_t slot_c = p.shared ? 0 : (size_t)d * planes * HW;
+    const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
+    const size_t plane0 = ((size_t)b * p.C + c) * HW;
+    const char* wbase = (const char*)p.w + (slot_w + ((size_t)b * p.G + g) * 3 * HW) * 2;
+    ChainRefs r;
+    r.xb = make_rsrc((const char*)p.x + plane0 * 2);
+    r.lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * 2);
+    r.ub = make_rsrc((const char*)p.u + (slot_c + plane0) * 2);
+    r.w0b = make_rsrc(wbase); r.w1b = make_rsrc(wbase + PLANE_B); r.w2b = make_rsrc(wbase + 2 * PLANE_B);
+    r.hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * 2 : (char*)p.y);
+    return r;
+}
+// image row of step k of band s
+template <bool UP> __device__ __forceinline__ int chain_row(int s, int k) { return UP ? PH - 1 - (s * VBAND + k) : s * VBAND + k; }
+__device__ __forceinline__ uint32_t ld32(rsrc_t rs, uint32_t voff, int row) {
+    return __builtin_amdgcn_raw_buffer_load_b32(rs, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), 0);
+}
+// band s of the chain's own tensors
+template <bool UP>
+__device__ __forceinline__ void issue_own(const ChainRefs& t, uint32_t voff, int s, uint32_t (&x)[VBAND], uint32_t (&l)[VBAND], uint32_t (&u)[VBAND]) {
+#pragma unroll
+    for (int k = 0; k < VBAND; ++k) {
+        const int row = chain_row<UP>(s, k);
+        x[k] = ld32(t.xb, voff, row); l[k] = ld32(t.lb, voff, row); u[k] = ld32(t.ub, voff, row);
+    }
+}
+// steps kc * VBAND/2 .. of band s: this wave's share of the weight rows
+template <bool UP>
+__device__ __forceinline__ void issue_w(const ChainRefs& t, uint32_t voff, int kc, int s, uint32_t (&w)[3][VBAND / 2]) {
+#pragma unroll
+    for (int k = 0; k < VBAND / 2; ++k) {
+        const int row = chain_row<UP>(s, kc * (VBAND / 2) + k);
+        w[0][k] = ld32(t.w0b, voff, row); w[1][k] = ld32(t.w1b, voff, row); w[2][k] = ld32(t.w2b, voff, row);
+    }
+}
+// ... into the ring slot of band s: word (walk * 3 + tap) * VBAND * 64 + step * 64 + lane
+template <bool UP>
+__device__ __forceinline__ void drop_w(char* region, int kc, int lane, int s, const uint32_t (&w)[3][VBAND / 2]) {
+    uint32_t* to = (uint32_t*)(region + (s & 1) * VSLOT_B) + ((UP ? 1 : 0) * 3) * VBAND * 64 + kc * (VBAND / 2) * 64 + lane;
+#pragma unroll
+    for (int k = 0; k < VBAND / 2; ++k) {
+        to[k * 64] = w[0][k]; to[VBAND * 64 + k * 64] = w[1][k]; to[2 * VBAND * 64 + k * 64] = w[2][k];
+    }
+}
+
+// The first requests of a chain, in the order the band loop would have made them (weights of band s + 3, then own
+// tensors of band s + 4, band after band), so that the counters the compiler keeps for requests in flight look the same
+// on entry to the loop as on its back edge and it waits for no more than it has to.  Touches no LDS: a workgroup calls
+// it for its next pair of channels while the horizontal pair of the current one is still at work.
+// FROM, TO: the requests are numbered 0..4 (own 0, weights 0, own 1, weights 1, own 2); where registers are short the
+// early call makes the first of them only and the chain makes the others when it starts.
+template <bool UP, bool BWD, int FROM, int TO>
+__device__ __forceinline__ void chain_request_first(const FwdParams& p, int b, int c, int kc, int lane,
+                                                    uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
+                                                    uint32_t (&wr)[2][3][VBAND / 2]) {
+    static_assert(VPF == 4, "written out for four bands in flight");
+    const ChainRefs t = chain_refs<UP, false, BWD>(p, b, c);
     const uint32_t voff = (uint32_t)(lane * 4);
-    float h[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+    if constexpr (FROM <= 0 && 0 < TO) issue_own<UP>(t, voff, 0, xr[0], lr[0], ur[0]);
+    if constexpr (FROM <= 1 && 1 < TO) issue_w<UP>(t, voff, kc, 0, wr[0]);
+    if constexpr (FROM <= 2 && 2 < TO) issue_own<UP>(t, voff, 1, xr[1], lr[1], ur[1]);
+    if constexpr (FROM <= 3 && 3 < TO) issue_w<UP>(t, voff, kc, 1, wr[1]);
+    if constexpr (FROM <= 4 && 4 < TO) issue_own<UP>(t, voff, 2, xr[2], lr[2], ur[2]);
+}
+// how many of them are made early: all five in the plain forward scan; with h_save / in the reverse sweep the
+// horizontal tasks hold more registers (the states on their way out), and one or two is what fits beside them
+template <bool SAVE, bool BWD> constexpr int early_requests() { return SAVE ? (BWD ? 2 : 1) : 5; }
+
+// ... and the chain itself, after chain_request_first() for the same (b, c).
+// ahead() is called once, V_AHEAD bands before the end (the wave's own requests for what comes next).
+template <bool UP, bool SAVE, bool BWD, typename F>
+__device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region, uint32_t* tile, int b, int c, int kc, int lane,
+                                               uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
+                                               uint32_t (&wr)[2][3][VBAND / 2], F& ahead) {
+    constexpr int walk = UP ? 1 : 0;
+    constexpr int V_AHEAD = VPF;
+    static_assert(VNBANDS % VPF == 0 && VBAND % 2 == 0, "band loop unrolled by the ring depth; two waves share a band's weight rows");
+    const bool first = lane == 0, last = lane == 63;
+    const ChainRefs t = chain_refs<UP, SAVE, BWD>(p, b, c);
+    const uint32_t voff = (uint32_t)(lane * 4);
+
+    float h[2] = {0.f, 0.f};
     float wp0[2] = {0.f, 0.f}, wp1[2] = {0.f, 0.f}, wp2[2] = {0.f, 0.f};     // BWD: taps of the row swept before
-    lds_barrier();                                                            // band 0 is in slot 0
-    auto band = [&](int s) {
-        const char* slot = region + (s & 1) * SLOT_B;
-        const uint32_t* cw = (const uint32_t*)(slot + (12 + (UP ? 3 : 0)) * BAND_B) + lane;
-        // everything the band needs from LDS is requested before the first row is worked on: the writes to the tiles
-        // below would otherwise fence the reads of the following rows (LDS against LDS), and this wave has its SIMD to
-        // itself, so nothing else would cover their latency
-        uint32_t t0[BAND], t1[BAND], t2[BAND], xw[2][BAND], lw[2][BAND], uw[2][BAND], ow[2][BAND];
+
+    // one band: `slot` = its place in the own ring, `wslot` = where the weight rows of band s + 1 wait in registers
+    auto band = [&](int s, int slot, int wslot, bool more_own, bool more_w) __attribute__((always_inline)) {
+        if (s + 1 < VNBANDS) drop_w<UP>(region, kc, lane, s + 1, wr[wslot]);  // for the band after this one
+        if (more_w) issue_w<UP>(t, voff, kc, s + 3, wr[wslot]);
+        const uint32_t* cw = (const uint32_t*)(region + (s & 1) * VSLOT_B) + (walk * 3) * VBAND * 64 + lane;
+        // everything the band needs from LDS is requested before its first row is worked on: the writes to the tile below
+        // would otherwise fence the reads of the following rows (LDS against LDS)
+        uint32_t t0[VBAND], t1[VBAND], t2[VBAND], ow[VBAND];
 #pragma unroll
-        for (int k = 0; k < BAND; ++k) {
-            const int r = UP ? BAND - 1 - k : k;                              // row inside the band
-            t0[k] = cw[r * 64]; t1[k] = cw[BAND_B / 4 + r * 64]; t2[k] = cw[2 * (BAND_B / 4) + r * 64];
+        for (int k = 0; k < VBAND; ++k) { t0[k] = cw[k * 64]; t1[k] = cw[VBAND * 64 + k * 64]; t2[k] = cw[2 * VBAND * 64 + k * 64]; }
+        if (s >= VNBANDS / 2) {
 #pragma unroll
-            for (int ch = 0; ch < 2; ++ch) {
-                const uint32_t* cx = (const uint32_t*)(slot + (ch * 2 + (UP ? 1 : 0)) * 3 * BAND_B) + lane;
-                xw[ch][k] = cx[r * 64]; lw[ch][k] = cx[BAND_B / 4 + r * 64]; uw[ch][k] = cx[2 * (BAND_B / 4) + r * 64];
-            }
-        }
-        if (s >= NBANDS / 2) {
-            // second half of a walk: these rows hold what the other walk left
-#pragma unroll
-            for (int k = 0; k < BAND; ++k) {
-                const int row = UP ? PH - 1 - (s * BAND + k) : s * BAND + k;
-#pragma unroll
-                for (int ch = 0; ch < 2; ++ch) ow[ch][k] = tiles[ch * TILE_WORDS + tile_row(row) * TPITCH + lane];
-            }
+            for (int k = 0; k < VBAND; ++k) ow[k] = tile[tile_row(chain_row<UP>(s, k)) * TPITCH + lane];
         } else {
 #pragma unroll
-            for (int k = 0; k < BAND; ++k) { ow[0][k] = 0; ow[1][k] = 0; }
+            for (int k = 0; k < VBAND; ++k) ow[k] = 0;
         }
 #pragma unroll
-        for (int k = 0; k < BAND; ++k) {
-            const int row = UP ? PH - 1 - (s * BAND + k) : s * BAND + k;      // image row
+        for (int k = 0; k < VBAND; ++k) {
+            const int row = chain_row<UP>(s, k);
             float c0[2] = {lo16(t0[k]), hi16(t0[k])}, c1[2] = {lo16(t1[k]), hi16(t1[k])}, c2[2] = {lo16(t2[k]), hi16(t2[k])};
-            if constexpr (!BWD) {
+            const uint32_t xw = xr[slot][k], lw = lr[slot][k], uw = ur[slot][k];
+            float av[2] = {lo16(lw) * lo16(xw), hi16(lw) * hi16(xw)};
+            if constexpr (BWD) {
+                line_update_transposed<2>(h, av, wp0, wp1, wp2, first, last);
+                // the taps this row hands on to the row swept next; a tap that points outside the line takes nothing,
+                // whatever the tensor holds there
+                wp0[0] = first ? 0.f : c0[0]; wp0[1] = c0[1];
+                wp1[0] = c1[0]; wp1[1] = c1[1];
+                wp2[0] = c2[0]; wp2[1] = last ? 0.f : c2[1];
+            } else {
                 if (k == 0) {
                     // scan step 0: its weights are never read (they may hold anything) and the state before it is 0
                     const bool start = s == 0;
 #pragma unroll
                     for (int v = 0; v < 2; ++v) { c0[v] = start ? 0.f : c0[v]; c1[v] = start ? 0.f : c1[v]; c2[v] = start ? 0.f : c2[v]; }
                 }
+                line_update<2>(h, av, c0, c1, c2, first, last);
             }
-#pragma unroll
-            for (int ch = 0; ch < 2; ++ch) {
-                float av[2] = {lo16(lw[ch][k]) * lo16(xw[ch][k]), hi16(lw[ch][k]) * hi16(xw[ch][k])};
-                if constexpr (BWD) line_update_transposed<2>(h[ch], av, wp0, wp1, wp2, first, last);
-                else line_update<2>(h[ch], av, c0, c1, c2, first, last);
-                const float y0 = lo16(uw[ch][k]) * h[ch][0], y1 = hi16(uw[ch][k]) * h[ch][1];
-                // the first half of a walk writes rows nobody has touched yet (ow = 0); the second half adds to what the
-                // other walk left
-                tiles[ch * TILE_WORDS + tile_row(row) * TPITCH + lane] = pack_bf16x2(lo16(ow[ch][k]) + y0, hi16(ow[ch][k]) + y1);
-                if constexpr (SAVE) {
-                    const uint32_t hw = pack_bf16x2(h[ch][0], h[ch][1]);
-                    __builtin_amdgcn_raw_buffer_store_b32(hw, hb, voff, __builtin_amdgcn_readfirstlane(ch * PLANE_B + row * ROW_B), 0);
-                }
-            }
-            if constexpr (BWD) {
-                // the taps this row hands on to the row swept next; a tap that points outside the line takes nothing,
-                // whatever the tensor holds there
-                wp0[0] = first ? 0.f : c0[0]; wp0[1] = c0[1];
-                wp1[0] = c1[0]; wp1[1] = c1[1];
-                wp2[0] = c2[0]; wp2[1] = last ? 0.f : c2[1];
+            const float y0 = lo16(uw) * h[0], y1 = hi16(uw) * h[1];
+            tile[tile_row(row) * TPITCH + lane] = pack_bf16x2(lo16(ow[k]) + y0, hi16(ow[k]) + y1);
+            if constexpr (SAVE) {
+                const uint32_t hw = pack_bf16x2(h[0], h[1]);
+                __builtin_amdgcn_raw_buffer_store_b32(hw, t.hb, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), 0);
             }
         }
+        if (more_own) issue_own<UP>(t, voff, s + VPF, xr[slot], lr[slot], ur[slot]);
         lds_barrier();
     };
-    for (int s = 0; s < NBANDS - V_AHEAD; ++s) band(s);
+
+    chain_request_first<UP, BWD, early_requests<SAVE, BWD>(), 5>(p, b, c, kc, lane, xr, lr, ur, wr);
+    // the rest of the first requests: band 0 of the weights goes to the ring (it takes the place band "s + 1" has in
+    // the loop), its registers take band 2
+    drop_w<UP>(region, kc, lane, 0, wr[0]);
+    issue_w<UP>(t, voff, kc, 2, wr[0]);
+    issue_own<UP>(t, voff, 3, xr[3], lr[3], ur[3]);
+    lds_barrier();
+    // weight registers: band s + 1 waits in wr[(s + 1) & 1]; once dropped, the same registers take band s + 3
+    for (int s0 = 0; s0 < VNBANDS - V_AHEAD; s0 += VPF) {
+#pragma unroll
+        for (int q = 0; q < VPF; ++q) band(s0 + q, q, (q + 1) & 1, true, s0 + q + 3 < VNBANDS);
+    }
     ahead();
-    for (int s = NBANDS - V_AHEAD; s < NBANDS; ++s) band(s);
+#pragma unroll
+    for (int q = 0; q < VPF; ++q) band(VNBANDS - VPF + q, q, (q + 1) & 1, false, VNBANDS - VPF + q + 3 < VNBANDS);
 }
 
 // ---------------------------------------------------------------------------
@@ -284,9 +289,17 @@ struct ChunkIO {
 //  * (without h_save) the task that walks from the left and the one that walks from the right hand each other their
 //    chunk of x at half time instead of fetching it a second time;
 //  * the first chunk is requested while the vertical pair is still at work.
+//  * a workgroup works through several pairs of channels, and requests the first bands of the next pair's vertical
+//    chains (has_next: image nb, channels nc0, nc0 + 1) before the last chunk of this pair's horizontal tasks is worked
+//    on -- otherwise nothing would be on its way to the compute unit from there until the next pair's first rows arrive.
+// xr, lr, ur, wr: the first bands of THIS pair's vertical chain on entry (chain_request_first), of the next pair's on exit.
 template <bool REV, bool SAVE, bool BWD>
-__device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, char* region, int b, int c0, int wave, int lane) {
+__device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, char* region, int b, int c0, int wave, int lane,
+                                          bool has_next, int nb, int nc0,
+                                          uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
+                                          uint32_t (&wr)[2][3][VBAND / 2]) {
     constexpr int d = (REV != BWD) ? 3 : 2;
+    constexpr bool UP = REV != BWD;            // the vertical chain of the wave: direction slot 0 walks the rows downwards
     constexpr bool SWAP_X = !SAVE;             // with h_save the staging blocks collect the states while a chunk is worked on
     const int kc = wave >> 1;                  // channel of the horizontal task; its direction slot is wave & 1
     const int twin = kc;
@@ -365,16 +378,9 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
         lds_barrier();                           // before the next tensor lands in the staging blocks
     };
 
-    // ---- vertical pair: wave 0 walks the rows downwards, wave 1 upwards (both channels each), waves 2 and 3 feed the
-    // ring; everybody requests the first chunk of its horizontal task on the way
-    if (wave >= 2) {
-        BandLoader<BWD> ld;
-        ld.init(p, b, c0, wave - 2, lane);
-        ld.run(region, prefetch);
-    } else {
-        if (wave & 1) vertical_chains<true, SAVE, BWD>(p, region, tiles, b, c0, lane, prefetch);
-        else vertical_chains<false, SAVE, BWD>(p, region, tiles, b, c0, lane, prefetch);
-    }
+    // ---- vertical pair: the wave runs the chain of its channel that walks the rows downwards (direction slot 0) or
+    // upwards (slot 1), and requests the first chunk of its horizontal task on the way
+    vertical_chain<UP, SAVE, BWD>(p, region, tiles + kc * TILE_WORDS, b, c0 + kc, kc, lane, xr, lr, ur, wr, prefetch);
 
     // ---- horizontal pair
     float h[2] = {0.f, 0.f};
@@ -397,6 +403,9 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
         share_rows(b10, b11);
         share_rows(b20, b21);
         __builtin_amdgcn_sched_barrier(0);
+
+        // nothing is left to request for this pair: the next pair's vertical chains start theirs
+        if (ch == 1 && has_next) chain_request_first<UP, BWD, 0, early_requests<SAVE, BWD>()>(p, nb, nc0 + kc, kc, lane, xr, lr, ur, wr);
 
         float cpair[2] = {0.f, 0.f}, hpair[2] = {0.f, 0.f};    // first element of the pair of columns that share a word
         uint32_t yw[2] = {0, 0};
@@ -451,24 +460,6 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
         });
         if constexpr (SAVE) io.store_staged(hb, col0 * 2);
     }
-}
-
-template <bool SAVE, bool BWD>
-__global__ void __launch_bounds__(256) fwd_pair_kernel(FwdParams p) {
-    extern __shared__ uint32_t lds[];
-    uint32_t* tiles = lds;
-    char* region = (char*)(lds + 2 * TILE_WORDS);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int pairs = p.C / 2;
-    const unsigned item = xcd_contiguous_item(blockIdx.x, gridDim.x);
-    const int b = item / pairs;
-    const int c0 = (item - b * pairs) * 2;
-
-    // wave -> horizontal task (channel = wave / 2, direction slot = wave % 2); the task of direction slot 0 walks the
-    // columns from the left in the forward scan and from the right in the reverse sweep
-    if (((wave & 1) == 0) != BWD) pair_body<false, SAVE, BWD>(p, tiles, region, b, c0, wave, lane);
-    else pair_body<true, SAVE, BWD>(p, tiles, region, b, c0, wave, lane);
 
     // ---- the tiles hold the rounded output: copy them out, one row per request
     lds_barrier();
@@ -480,6 +471,49 @@ __global__ void __launch_bounds__(256) fwd_pair_kernel(FwdParams p) {
             *(uint32_t*)(Y + (size_t)r * ROW_B + lane * 4) = v;
         }
     }
+}
+
+// The pairs of channels a workgroup works through: items blockIdx.x, blockIdx.x + gridDim.x, ... of B * C/2, dealt so
+// that the workgroups running at any one time hold neighbouring channels of few weight groups per XCD.
+template <bool REV, bool SAVE, bool BWD>
+__device__ __forceinline__ void pair_loop(const FwdParams& p, uint32_t* tiles, char* region, int wave, int lane) {
+    constexpr bool UP = REV != BWD;
+    const int kc = wave >> 1;
+    const unsigned pairs = (unsigned)(p.C / 2), total = (unsigned)p.B * pairs;
+    const unsigned rounds = (total + gridDim.x - 1) / gridDim.x;
+    auto item_of = [&](unsigned round, int& b, int& c0) {
+        // the last round may be short: its items are dealt as a launch of their own
+        const unsigned in_round = round + 1 < rounds ? gridDim.x : total - round * gridDim.x;
+        const unsigned item = round * gridDim.x + xcd_contiguous_item(blockIdx.x, in_round);
+        b = (int)(item / pairs);
+        c0 = (int)(item - (unsigned)b * pairs) * 2;
+    };
+    uint32_t xr[VPF][VBAND], lr[VPF][VBAND], ur[VPF][VBAND], wr[2][3][VBAND / 2];
+    int b, c0;
+    item_of(0, b, c0);
+    chain_request_first<UP, BWD, 0, early_requests<SAVE, BWD>()>(p, b, c0 + kc, kc, lane, xr, lr, ur, wr);
+    for (unsigned round = 0; round < rounds; ++round) {
+        // a workgroup beyond the end of a short last round has nothing left
+        const bool has_next = round + 1 < rounds && (round + 2 < rounds || blockIdx.x < total - (round + 1) * gridDim.x);
+        int nb = b, nc0 = c0;
+        if (has_next) item_of(round + 1, nb, nc0);
+        pair_body<REV, SAVE, BWD>(p, tiles, region, b, c0, wave, lane, has_next, nb, nc0, xr, lr, ur, wr);
+        if (!has_next) break;
+        b = nb; c0 = nc0;
+    }
+}
+
+template <bool SAVE, bool BWD>
+__global__ void __launch_bounds__(256) fwd_pair_kernel(FwdParams p) {
+    extern __shared__ uint32_t lds[];
+    uint32_t* tiles = lds;
+    char* region = (char*)(lds + 2 * TILE_WORDS);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // wave -> horizontal task (channel = wave / 2, direction slot = wave % 2); the task of direction slot 0 walks the
+    // columns from the left in the forward scan and from the right in the reverse sweep
+    if (((wave & 1) == 0) != BWD) pair_loop<false, SAVE, BWD>(p, tiles, region, wave, lane);
+    else pair_loop<true, SAVE, BWD>(p, tiles, region, wave, lane);
 }
 
 bool pair_shape_ok(const FwdParams& p, int dtype) {
@@ -495,7 +529,10 @@ hipError_t launch_pair(const FwdParams& p, hipStream_t s) {
     auto k = fwd_pair_kernel<SAVE, BWD>;
     hipError_t e = allow_dynamic_lds((const void*)k, LDS_BYTES);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k, dim3((unsigned)((size_t)p.B * (p.C / 2))), dim3(256), LDS_BYTES, s, p);
+    // one workgroup fits a compute unit (LDS): as many workgroups as the chip has compute units, each working through
+    // its share of the pairs
+    const size_t total = (size_t)p.B * (p.C / 2);
+    hipLaunchKernelGGL(k, dim3((unsigned)(total < PERSIST_WGS ? total : PERSIST_WGS)), dim3(256), LDS_BYTES, s, p);
     return hipGetLastError();
 }
 

@@ -58,6 +58,11 @@ def test_two_pass_backward_on_128x128_bf16_maps(bcg, pair, monkeypatch):
     check_bwd(WL.ScanConfig("twopass128", B, C, 128, 128, Gr, "bf16", 15, 3.0, 83))
 
 
+def test_two_pass_backward_when_a_workgroup_of_the_reverse_sweep_works_through_several_pairs():
+    """600 channels of 128x128: 300 pairs on 256 workgroups (a short second round) in the reverse sweep."""
+    check_bwd(WL.ScanConfig("twopassrounds", 1, 600, 128, 128, 4, "bf16", 15, 2.0, 85))
+
+
 def test_two_pass_backward_is_bitwise_repeatable():
     import torch
     import paper_2512_07884_amd as G

@@ -285,6 +285,17 @@ def test_two_channel_kernel_on_128x128_maps(bcg):
     check_case(cfg, save_h=False)
 
 
+@pytest.mark.parametrize("bcg", [(1, 600, 4), (3, 344, 2)], ids=lambda s: "x".join(map(str, s)))
+def test_two_channel_kernel_when_a_workgroup_works_through_several_pairs(bcg):
+    """More pairs of channels than workgroups in the launch (one per compute unit): every workgroup works through
+    several pairs, the last round is short (300 and 516 pairs on 256 workgroups), and the requests for the next pair
+    are already on their way while the current one finishes."""
+    B, C, Gr = bcg
+    cfg = WL.ScanConfig("pairrounds", B, C, 128, 128, Gr, "bf16", 15, 2.0, 71)
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+
+
 def test_two_channel_kernel_with_one_parameter_set_for_all_directions():
     import paper_2512_07884_amd as G
     cfg = WL.ScanConfig("pairshared", 1, 4, 128, 128, 2, "bf16", 15, 1.0, 67)

@@ -100,71 +100,79 @@ struct VStream {
             if constexpr (RMW) ld_buf<NB>(yb, voff, so, s.y);
         };
         if (t_begin >= t_end) return;
+        // line after line, as the loop below requests them: the compiler would otherwise group the requests by tensor,
+        // count few requests behind the first line's on entry to the loop, and wait for (nearly) all of them at its head
 #pragma unroll
-        for (int k = 0; k < PF; ++k) issue(slot[k], t_begin + k);
-        for (int t0 = t_begin; t0 < t_end; t0 += PF) {
+        for (int k = 0; k < PF; ++k) { issue(slot[k], t_begin + k); __builtin_amdgcn_sched_barrier(0); }
+        // one line: ring slot k holds it; its slot takes line t + PF
+        auto line = [&](int t, int k) __attribute__((always_inline)) {
+            const Line& cur = slot[k];
+            float av[V], w0[V], w1[V], w2[V], yv[V];
+            if constexpr (BWD) {
+                // GSPN-local: a line that starts a stretch takes nothing from the line before it in scan
+                // order, so its taps hand nothing on to the line swept next
+                bool starts = false;
+                if constexpr (LOCAL) starts = bwalk.start(t == H - 1);
 #pragma unroll
-            for (int k = 0; k < PF; ++k) {
-                const int t = t0 + k;
-                if (t < t_end) {
-                    const Line& cur = slot[k];
-                    float av[V], w0[V], w1[V], w2[V], yv[V];
-                    if constexpr (BWD) {
-                        // GSPN-local: a line that starts a stretch takes nothing from the line before it in scan
-                        // order, so its taps hand nothing on to the line swept next
-                        bool starts = false;
-                        if constexpr (LOCAL) starts = bwalk.start(t == H - 1);
+                for (int v = 0; v < V; ++v) av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
+                line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
 #pragma unroll
-                        for (int v = 0; v < V; ++v) av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
-                        line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
-#pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            float c0 = elem<T>(cur.w0, v), c1 = elem<T>(cur.w1, v), c2 = elem<T>(cur.w2, v);
-                            if constexpr (LOGITS) softmax3(c0, c1, c2, first && v == 0, last && v == V - 1);
-                            // a tap that points outside the line takes nothing, whatever the tensor holds there
-                            wp0[v] = ((first && v == 0) || starts) ? 0.f : c0;
-                            wp1[v] = starts ? 0.f : c1;
-                            wp2[v] = ((last && v == V - 1) || starts) ? 0.f : c2;
-                            yv[v] = elem<T>(cur.u, v) * h[v];
-                            if constexpr (RMW) yv[v] += elem<T>(cur.y, v);
-                        }
-                        uint32_t o[NR];
-                        pack<T, V>(yv, o);
-                        st_buf<NB>(yb, voff, row_off(t), o);
-                        pack<T, V>(h, o);
-                        st_buf<NB>(hb, voff, row_off(t), o);
-                        issue(slot[k], t + PF);
-                        continue;
-                    }
-                    // scan step 0 (only ever in ring slot 0): its weights are never used (the stored values may be
-                    // anything); GSPN-local: the same for the first line of every stretch, any slot
-                    bool start = t == 0;
-                    if constexpr (LOCAL) start = walk.start();
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
-                        w0[v] = elem<T>(cur.w0, v); w1[v] = elem<T>(cur.w1, v); w2[v] = elem<T>(cur.w2, v);
-                        if constexpr (LOGITS) softmax3(w0[v], w1[v], w2[v], first && v == 0, last && v == V - 1);
-                        if (LOCAL || k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
-                        if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
-                    }
-                    line_update<V>(h, av, w0, w1, w2, first, last);
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        yv[v] = elem<T>(cur.u, v) * h[v];
-                        if constexpr (RMW) yv[v] += elem<T>(cur.y, v);
-                    }
-                    uint32_t o[NR];
-                    pack<T, V>(yv, o);
-                    st_buf<NB>(yb, voff, row_off(t), o);
-                    if constexpr (SAVE) {
-                        pack<T, V>(h, o);
-                        st_buf<NB>(hb, voff, row_off(t), o);
-                    }
-                    issue(slot[k], t + PF);
+                for (int v = 0; v < V; ++v) {
+                    float c0 = elem<T>(cur.w0, v), c1 = elem<T>(cur.w1, v), c2 = elem<T>(cur.w2, v);
+                    if constexpr (LOGITS) softmax3(c0, c1, c2, first && v == 0, last && v == V - 1);
+                    // a tap that points outside the line takes nothing, whatever the tensor holds there
+                    wp0[v] = ((first && v == 0) || starts) ? 0.f : c0;
+                    wp1[v] = starts ? 0.f : c1;
+                    wp2[v] = ((last && v == V - 1) || starts) ? 0.f : c2;
+                    yv[v] = elem<T>(cur.u, v) * h[v];
+                    if constexpr (RMW) yv[v] += elem<T>(cur.y, v);
                 }
+                uint32_t o[NR];
+                pack<T, V>(yv, o);
+                st_buf<NB>(yb, voff, row_off(t), o);
+                pack<T, V>(h, o);
+                st_buf<NB>(hb, voff, row_off(t), o);
+                issue(slot[k], t + PF);
+                return;
             }
+            // scan step 0 (only ever in ring slot 0): its weights are never used (the stored values may be
+            // anything); GSPN-local: the same for the first line of every stretch, any slot
+            bool start = t == 0;
+            if constexpr (LOCAL) start = walk.start();
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
+                w0[v] = elem<T>(cur.w0, v); w1[v] = elem<T>(cur.w1, v); w2[v] = elem<T>(cur.w2, v);
+                if constexpr (LOGITS) softmax3(w0[v], w1[v], w2[v], first && v == 0, last && v == V - 1);
+                if (LOCAL || k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
+                if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
+            }
+            line_update<V>(h, av, w0, w1, w2, first, last);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                yv[v] = elem<T>(cur.u, v) * h[v];
+                if constexpr (RMW) yv[v] += elem<T>(cur.y, v);
+            }
+            uint32_t o[NR];
+            pack<T, V>(yv, o);
+            st_buf<NB>(yb, voff, row_off(t), o);
+            if constexpr (SAVE) {
+                pack<T, V>(h, o);
+                st_buf<NB>(hb, voff, row_off(t), o);
+            }
+            issue(slot[k], t + PF);
+        };
+        // whole groups of PF lines without a test inside (a way out of the middle of a group would reach the loop's back
+        // edge with few requests counted behind the next line's, and the compiler would wait for nearly all of them at
+        // the head of every group), then the lines left over
+        const int t_main = t_begin + (t_end - t_begin) / PF * PF;
+        for (int t0 = t_begin; t0 < t_main; t0 += PF) {
+#pragma unroll
+            for (int k = 0; k < PF; ++k) { line(t0 + k, k); __builtin_amdgcn_sched_barrier(0); }   // one line after the other
         }
+#pragma unroll
+        for (int k = 0; k < PF; ++k)
+            if (t_main + k < t_end) line(t_main + k, k);
     }
 };
 

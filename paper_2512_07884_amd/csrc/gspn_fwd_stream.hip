@@ -10,13 +10,13 @@ hipError_t launch_stream_bf16(const FwdParams& p, hipStream_t s, bool reverse);
 bool stream_staged_applicable(const FwdParams& p, int dtype);
 hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s);
 
-// maps of up to 1024 rows / lines of up to 1024 (fp32) or 2048 (bf16) positions, global scan: two launches
+// maps of up to 2048 rows (reverse sweep: 1024) / lines of up to 2048 positions, global scan: two launches
 // (gspn_fwd_stream_big.hip)
-bool stream_big_applicable(const FwdParams& p, int dtype);
+bool stream_big_applicable(const FwdParams& p, int dtype, bool reverse);
 hipError_t launch_stream_big(const FwdParams& p, int dtype, bool reverse, hipStream_t s);
 
-bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || stream_big_applicable(p, dtype); }
-bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return fwd_stream_applicable(p, dtype); }
+bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || stream_big_applicable(p, dtype, false); }
+bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || stream_big_applicable(p, dtype, true); }
 
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s) {
     if (!plan_stream(p, dtype).ok) return launch_stream_big(p, dtype, false, s);

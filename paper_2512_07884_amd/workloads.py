@@ -91,6 +91,7 @@ CONFIGS = {
     # (App. B: 1152 channels); group counts are not stated there
     "scale1024":   ScanConfig("scale1024", 16, 8, 1024, 1024, 1, "f32", 15, 1.0, 9),
     "hires1024":   ScanConfig("hires1024", 1, 1152, 1024, 1024, 16, "bf16", 15, 1.0, 10),
+    "hires2048":   ScanConfig("hires2048", 1, 64, 2048, 2048, 4, "bf16", 15, 1.0, 11),
     # the low-occupancy shape of the paper's throughput table (Table 1: 128x128, B = 1, C = 32; the group count is not
     # stated there): fewer planes than the chip has compute units, where GSPN-local's stretches are the work items
     "occ128":      ScanConfig("occ128", 1, 32, 128, 128, 4, "f32", 15, 1.0, 8),

@@ -129,6 +129,10 @@ def test_kernel_family_chosen_for_the_benchmark_shapes(lib, monkeypatch):
     assert fwd(2, 1024, 128, 128, 16, 15, 1, 0, 0) == "pair"                 # diff128
     assert fwd(1, 512, 512, 512, 16, 15, 1, 0, 0) == "stream"                # long512
     assert fwd(1, 512, 256, 1024, 16, 15, 1, 0, 0) == "stream"               # long256x1024
+    assert fwd(16, 8, 1024, 1024, 1, 15, 0, 0, 0) == "stream"                # scale1024 (Sec. 5.1 scaling study)
+    assert fwd(1, 1152, 1024, 1024, 16, 15, 1, 0, 0) == "stream"             # hires1024 (App. B)
+    assert fwd(1, 64, 2048, 2048, 4, 15, 1, 0, 0) == "stream" and fwd(1, 8, 2048, 2048, 1, 15, 0, 0, 0) == "stream"
+    assert bwd(16, 8, 1024, 1024, 1, 15, 0, 0) == "twopass" and bwd(1, 64, 2048, 2048, 4, 15, 1, 0) == "generic"
     for G in (192, 4):                                                        # train28_gc / train28_g4
         assert fwd(32, 192, 28, 28, G, 15, 0, 0, 1) == "plane"
         assert bwd(32, 192, 28, 28, G, 15, 0, 0) == "plane"

@@ -47,6 +47,27 @@ def test_backward_on_maps_beyond_the_stream_kernel(shape):
     check_bwd(_cfg(shape, 104))
 
 
+# more than 1024 rows: two image rows per lane in the horizontal pair (forward only; the backward call takes the generic kernel)
+TALL = [(1, 2, 2048, 2048, 1, "bf16"), (1, 1, 2048, 1024, 1, "f32"), (1, 2, 1152, 256, 2, "f32"), (1, 2, 1280, 512, 1, "bf16"),
+        (1, 1, 2048, 2048, 1, "f32")]
+
+
+@pytest.mark.parametrize("shape", TALL, ids=lambda v: "x".join(map(str, v)))
+def test_forward_on_maps_of_more_than_1024_rows(shape):
+    import paper_2512_07884_amd as G
+    B, C, H, W, Gr, dtype = shape
+    dt = int(dtype == "bf16")
+    assert G.gspn_fwd_plan(B, C, H, W, Gr, 15, dt, 0, True) == "stream"
+    assert G.gspn_bwd_plan(B, C, H, W, Gr, 15, dt, 0) == "generic"
+    check_case(_cfg(shape, 106), save_h=True)
+    check_case(_cfg(shape, 107), save_h=False)
+
+
+@pytest.mark.parametrize("mask", [4, 8, 12, 7])
+def test_direction_masks_on_maps_of_more_than_1024_rows(mask):
+    check_case(_cfg((1, 2, 1280, 256, 1, "f32"), 108, mask), dir_mask=mask)
+
+
 def test_scaling_shape_1024x1024_on_sampled_slices():
     """1024x1024 with 8 channels per image in fp32 (the shape of the paper's step-by-step comparison, Sec. 5.1; batch 4
     here), launch shape as timed; the oracle computes a few (b, g) slices, which are independent given the group's weights."""

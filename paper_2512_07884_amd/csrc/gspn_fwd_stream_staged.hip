@@ -209,6 +209,178 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
     }
 }
 
+// The same for TWO channels of one weight group (Sec. 4.2: they share the weights), one after the other chunk by chunk:
+// a chunk of the weights is requested and turned into row order once and serves both channels' 64 scan steps.  The
+// registers of x, lam, u take, as they are consumed, channel B's chunk while channel A is worked on and channel A's next
+// chunk while channel B is; those of the weights take the next chunk while channel B is worked on.  One direction at a
+// time (maps of 512 rows: all eight waves hold rows); y of both channels already holds the vertical pair's sum.
+template <bool REV, bool SAVE, bool BWD>
+__device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a, char* blk_b, float* mailbox, int parts, int b, int c,
+                                                 int part, int lane) {
+    constexpr int d = (REV != BWD) ? 3 : 2;
+    const int H = p.H, W = p.W, HW = H * W;
+    const int row_bytes = W * 2, nchunks = W / CS;
+    const int g = c / p.cpg;
+    const bool top_lane = lane == 0, bot_lane = lane == 63;
+    const bool has_up = part > 0, has_dn = part < parts - 1;
+    const bool img_first = top_lane && !has_up, img_last = bot_lane && !has_dn;
+    rsrc_t xb, lb, ub, yb, hb, w0b, w1b, w2b;       // channel A's planes; channel B's are the next ones in memory
+    const int plane_b = HW * 2;
+    {
+        const size_t planes = (size_t)p.B * p.C;
+        const size_t slot_c = p.shared ? 0 : (size_t)d * planes * HW;
+        const size_t slot_w = p.shared ? 0 : (size_t)d * p.B * p.G * 3 * HW;
+        const size_t plane0 = ((size_t)b * p.C + c) * HW;
+        const size_t plane_bytes = (size_t)HW * 2;
+        const char* wbase = (const char*)p.w + (slot_w + ((size_t)b * p.G + g) * 3 * HW) * 2;
+        xb = make_rsrc((const char*)p.x + plane0 * 2);
+        lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * 2);
+        ub = make_rsrc((const char*)p.u + (slot_c + plane0) * 2);
+        yb = make_rsrc((char*)p.y + plane0 * 2);
+        hb = make_rsrc(SAVE ? (char*)p.hs + ((size_t)d * planes * HW + plane0) * 2 : (char*)p.y);
+        w0b = make_rsrc(wbase); w1b = make_rsrc(wbase + plane_bytes); w2b = make_rsrc(wbase + 2 * plane_bytes);
+    }
+    const uint32_t voff = (uint32_t)(((part * 64 + (lane >> 3)) * W + 8 * (lane & 7)) * 2);
+    const int istep = 8 * row_bytes;
+    u32x4* const wr_a = (u32x4*)blk_a + SPITCH * (lane >> 3) + (lane & 7);
+    u32x4* const rd_a = (u32x4*)blk_a + SPITCH * lane;
+    u32x4* const wr_b = (u32x4*)blk_b + SPITCH * (lane >> 3) + (lane & 7);
+    uint32_t* const yrow = (uint32_t*)((u32x4*)blk_b + SPITCH * lane);
+    const bool publishes = (bot_lane && has_dn) || (top_lane && has_up);
+
+    uint32_t bx[32], bl[32], bu[32], b0[32], b1[32], b2[32], ty[32];
+    auto col_bytes = [&](int c_) { return (REV ? nchunks - 1 - c_ : c_) * CS * 2; };
+    auto issue1 = [&](rsrc_t rs, int cb, int i, uint32_t (&r)[32]) {
+        const u32x4 v = ld128(rs, voff, cb + i * istep);
+        r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+    };
+    // chan: 0 = channel A, 1 = channel B
+    auto issue_own = [&](int chan, int c_, int q) {
+        const int cb = col_bytes(c_) + chan * plane_b;
+        issue1(xb, cb, q, bx); issue1(lb, cb, q, bl); issue1(ub, cb, q, bu);
+    };
+    auto issue_w = [&](int c_, int q) {
+        const int cb = col_bytes(c_);
+        issue1(w0b, cb, q, b0); issue1(w1b, cb, q, b1); issue1(w2b, cb, q, b2);
+    };
+    auto issue_y = [&](int chan, int c_) {
+        const int cb = col_bytes(c_) + chan * plane_b;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue1(yb, cb, i, ty);
+    };
+    auto to_rows = [&](uint32_t (&r)[32]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]}; wr_a[8 * SPITCH * i] = v; }
+        __builtin_amdgcn_sched_barrier(0);     // the reads below take the registers the writes above have released
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { const u32x4 v = rd_a[q]; r[4 * q] = v.x; r[4 * q + 1] = v.y; r[4 * q + 2] = v.z; r[4 * q + 3] = v.w; }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    float hA = 0.f, hB = 0.f;
+    float wpA0 = 0.f, wpA1 = 0.f, wpA2 = 0.f, wpB0 = 0.f, wpB1 = 0.f, wpB2 = 0.f;     // BWD: taps of the column swept before, per channel
+
+    // the 64 scan steps of one channel (second: channel B, uniform over the workgroup) on chunk ch
+    auto steps = [&](const bool second, int ch) __attribute__((always_inline)) {
+        float h = second ? hB : hA;
+        float wp0 = second ? wpB0 : wpA0, wp1 = second ? wpB1 : wpA1, wp2 = second ? wpB2 : wpA2;
+        // mailbox: [channel][part][parity] pairs, as in horizontal_rows
+        float* const task = mailbox + (second ? 1 : 0) * 8 * 4;
+        const f32x2_hw* const mb_in = (const f32x2_hw*)(task + part * 4);
+        float* const mb_out = bot_lane ? task + (part + 1) * 4 : task + (part - 1) * 4 + 1;
+        // what the registers of x, lam, u take as they are consumed: channel B's same chunk, or channel A's next one
+        const int next_chan = second ? 0 : 1, next_chunk = second ? ch + 1 : ch;
+        const bool more = next_chunk < nchunks;
+        float cpair = 0.f, hpair = 0.f;          // first element of the pair of columns that share a word
+        uint32_t yw = 0;
+        uint32_t hq[4];                          // SAVE: the states of the eight columns being worked on
+        static_for<CS>([&](auto kc_) __attribute__((always_inline)) {
+            constexpr int k = decltype(kc_)::value;
+            constexpr int e = REV ? CS - 1 - k : k;
+            constexpr int par = k & 1;
+            const f32x2_hw pin = mb_in[par ^ 1];                 // edge states the neighbouring parts published in the previous step
+            const float pu = pin.x, pd = pin.y;
+            if ((k & 1) == 0) yw = yrow[e >> 1];
+            const float av = elem<bf16_t>(bl, e) * elem<bf16_t>(bx, e);
+            float c0 = elem<bf16_t>(b0, e), c1 = elem<bf16_t>(b1, e), c2 = elem<bf16_t>(b2, e);
+            if constexpr (BWD) {
+                const float q0 = wp0 * h, q2 = wp2 * h;
+                float up = from_lane_below(q2), dn = from_lane_above(q0);
+                up = top_lane ? (has_up ? pu : 0.f) : up;
+                dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
+                h = fmaf(wp1, h, av) + (up + dn);
+                wp0 = img_first ? 0.f : c0;
+                wp1 = c1;
+                wp2 = img_last ? 0.f : c2;
+                if (publishes) mb_out[par * 2] = bot_lane ? wp2 * h : wp0 * h;
+            } else {
+                if (k == 0) {
+                    const bool start = ch == 0;                  // scan step 0: its weights are never read
+                    c0 = start ? 0.f : c0; c1 = start ? 0.f : c1; c2 = start ? 0.f : c2;
+                }
+                float up = from_lane_below(h), dn = from_lane_above(h);
+                up = top_lane ? (has_up ? pu : 0.f) : up;
+                dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
+                c0 = img_first ? 0.f : c0;
+                c2 = img_last ? 0.f : c2;
+                h = fmaf(c0, up, fmaf(c1, h, fmaf(c2, dn, av)));
+                if (publishes) mb_out[par * 2] = h;
+            }
+            const float cv = elem<bf16_t>(bu, e) * h;
+            if ((k & 1) == 0) { cpair = cv; hpair = h; }
+            else {
+                const float clo = (e & 1) ? cpair : cv, chi = (e & 1) ? cv : cpair;
+                yrow[e >> 1] = pack_bf16x2(lo16(yw) + clo, hi16(yw) + chi);
+                if constexpr (SAVE) hq[(e >> 1) & 3] = pack_bf16x2((e & 1) ? hpair : h, (e & 1) ? h : hpair);
+            }
+            if constexpr (SAVE) {
+                if ((k & 7) == 7) { const u32x4 v = {hq[0], hq[1], hq[2], hq[3]}; rd_a[e >> 3] = v; }
+            }
+            lds_barrier();
+            if ((k & 7) == 7) {
+                // columns 8q..8q+7 are consumed: the registers of x, lam, u take instruction q of the other channel's chunk,
+                // those of the weights, once channel B is done with them, instruction q of the next chunk
+                if (more) issue_own(next_chan, next_chunk, e >> 3);
+                if (second && more) issue_w(next_chunk, e >> 3);
+                if (k == (BWD ? 55 : 47) && more) issue_y(next_chan, next_chunk);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        if (second) { hB = h; wpB0 = wp0; wpB1 = wp1; wpB2 = wp2; }
+        else { hA = h; wpA0 = wp0; wpA1 = wp1; wpA2 = wp2; }
+    };
+    auto y_to_block = [&]() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const u32x4 v = {ty[4 * i], ty[4 * i + 1], ty[4 * i + 2], ty[4 * i + 3]}; wr_b[8 * SPITCH * i] = v; }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto store_chunk = [&](int chan, int col0) {
+        const uint32_t at = voff + (uint32_t)(col0 * 2 + chan * plane_b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) st_b128(yb, at + (uint32_t)(i * istep), wr_b[8 * SPITCH * i]);
+        if constexpr (SAVE) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) st_b128(hb, at + (uint32_t)(i * istep), wr_a[8 * SPITCH * i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { issue_own(0, 0, q); issue_w(0, q); }
+    issue_y(0, 0);
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int col0 = (REV ? nchunks - 1 - ch : ch) * CS;
+        for (int chan = 0; chan < 2; ++chan) {
+            y_to_block();
+            to_rows(bx); to_rows(bl);
+            if (chan == 0) { to_rows(b0); to_rows(b1); to_rows(b2); }      // channel B: the weights are in row order already
+            to_rows(bu);
+            steps(chan == 1, ch);
+            store_chunk(chan, col0);
+        }
+    }
+}
+
 template <int V, int PF, bool SAVE, bool BWD>
 __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
     extern __shared__ char lds[];
@@ -293,6 +465,51 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
     }
 }
 
+// Two channels of a weight group per workgroup on maps of 512 rows, all four directions: the vertical pairs of both
+// channels at the same time (waves 0, 1 and 2, 3), then the horizontal directions one after the other with the weights
+// shared (horizontal_rows2).
+template <int V, int PF, bool SAVE, bool BWD>
+__global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
+    extern __shared__ char lds[];
+    float* mailbox = (float*)(lds + 8 * 2 * BLOCK_B);
+    const FwdParams& p = a.p;
+    const int H = p.H;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned item = xcd_contiguous_item(blockIdx.x, gridDim.x);
+    const int pairs = p.C / 2;
+    const int b = item / pairs, c = (item - b * pairs) * 2;
+
+    // ---- vertical pairs: each wave first stores its half of its channel's y, then adds to the other half
+    {
+        const int split = (H + 1) / 2;
+        const int cv = c + (wave >> 1);
+        if (wave < 4 && (wave & 1) == 0) {
+            VStream<bf16_t, V, PF, false, false, false, BWD, SAVE> v; v.init(p, b, cv, lane);
+            v.template run<false>(0, split);
+            __syncthreads();
+            v.template run<true>(split, H);
+        } else if (wave < 4) {
+            VStream<bf16_t, V, PF, true, false, false, BWD, SAVE> v; v.init(p, b, cv, lane);
+            v.template run<false>(0, H - split);
+            __syncthreads();
+            v.template run<true>(H - split, H);
+        } else {
+            __syncthreads();
+        }
+    }
+
+    // ---- horizontal directions, one after the other; wave = part
+    char* const blk_a = lds + wave * 2 * BLOCK_B;
+    char* const blk_b = blk_a + BLOCK_B;
+    for (int dsel = 0; dsel < 2; ++dsel) {
+        if (threadIdx.x < MAILBOX_FLOATS) mailbox[threadIdx.x] = 0.f;
+        __syncthreads();                    // y of the previous phase complete, mailbox cleared
+        if ((dsel == 0) != BWD) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, wave, lane);
+        else horizontal_rows2<true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, wave, lane);
+    }
+}
+
 template <int V, int PF>
 hipError_t launch_staged(const StreamArgs& a, bool reverse, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * a.p.C)), block(512);
@@ -309,6 +526,24 @@ hipError_t launch_staged(const StreamArgs& a, bool reverse, hipStream_t s) {
 
 }  // namespace
 
+template <int V, int PF>
+static hipError_t launch_staged2(const StreamArgs& a, bool reverse, hipStream_t s) {
+    const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / 2))), block(512);
+    if (reverse) return hipErrorInvalidValue;
+    const void* k = a.p.hs ? (const void*)fwd_stream_staged2_kernel<V, PF, true, false>
+                           : (const void*)fwd_stream_staged2_kernel<V, PF, false, false>;
+    hipError_t e = allow_dynamic_lds(k, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged2_kernel<V, PF, true, false>), grid, block, LDS_BYTES, s, a);
+    else hipLaunchKernelGGL((fwd_stream_staged2_kernel<V, PF, false, false>), grid, block, LDS_BYTES, s, a);
+    return hipGetLastError();
+}
+
+// two channels of a group per workgroup: maps of 512 rows, all four directions, an even number of channels per group
+static bool two_channels_ok(const FwdParams& p, const StreamPlan& t) {
+    return stream_two_channels_enabled() && t.parts == 8 && p.mask == 15u && p.cpg % 2 == 0 && p.C % 2 == 0;
+}
+
 // bf16 storage, the global scan with normalised weights, every shape the stream plan takes
 bool stream_staged_applicable(const FwdParams& p, int dtype) {
     return dtype == 1 && p.kchunk <= 0 && !p.logits && plan_stream(p, dtype).ok;
@@ -319,6 +554,13 @@ hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s)
     if (!t.ok || !stream_staged_applicable(p, 1) || (reverse && !p.hs)) return hipErrorInvalidValue;
     StreamArgs a;
     a.p = p; a.parts = t.parts; a.nwaves = 8;
+    // (the reverse sweep keeps one channel per workgroup: with the taps of both channels carried along the two-channel
+    // variant no longer fits the registers, and it was measured no faster)
+    if (!reverse && two_channels_ok(p, t)) {
+        if (t.v == 4) return launch_staged2<4, 4>(a, reverse, s);
+        if (t.v == 8) return launch_staged2<8, 4>(a, reverse, s);
+        return launch_staged2<16, 2>(a, reverse, s);
+    }
     if (t.v == 4) return launch_staged<4, 4>(a, reverse, s);
     if (t.v == 8) return launch_staged<8, 4>(a, reverse, s);
     return launch_staged<16, 2>(a, reverse, s);

@@ -68,6 +68,28 @@ def test_direction_masks_on_maps_of_more_than_1024_rows(mask):
     check_case(_cfg((1, 2, 1280, 256, 1, "f32"), 108, mask), dir_mask=mask)
 
 
+# bf16 maps of 512 rows: the whole-line stream kernel with two channels of a weight group per workgroup (the weights of
+# the horizontal phases fetched once for both), with one channel per workgroup, and the row-per-lane stream kernel
+@pytest.mark.parametrize("knob", [None, "GSPN_STREAM_ONE_CHANNEL", "GSPN_STREAM_NO_STAGED"], ids=["two-channel", "one-channel", "row-per-lane"])
+@pytest.mark.parametrize("shape", [(1, 4, 512, 512, 2, "bf16"), (1, 4, 512, 1024, 1, "bf16"), (2, 2, 512, 256, 1, "bf16"),
+                                   (1, 3, 512, 256, 1, "bf16")], ids=lambda v: "x".join(map(str, v)))
+def test_stream_kernel_variants_on_maps_of_512_rows(shape, knob, monkeypatch):
+    import paper_2512_07884_amd as G
+    if knob:
+        monkeypatch.setenv(knob, "1")
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_fwd_plan(B, C, H, W, Gr, 15, 1, 0, True) == "stream"
+    check_case(_cfg(shape, 109), save_h=True)
+    check_case(_cfg(shape, 110), save_h=False)
+
+
+@pytest.mark.parametrize("knob", [None, "GSPN_STREAM_NO_STAGED"], ids=["whole-line", "row-per-lane"])
+def test_backward_on_maps_of_512_rows_bf16(knob, monkeypatch):
+    if knob:
+        monkeypatch.setenv(knob, "1")
+    check_bwd(_cfg((1, 4, 512, 512, 2, "bf16"), 111))
+
+
 def test_scaling_shape_1024x1024_on_sampled_slices():
     """1024x1024 with 8 channels per image in fp32 (the shape of the paper's step-by-step comparison, Sec. 5.1; batch 4
     here), launch shape as timed; the oracle computes a few (b, g) slices, which are independent given the group's weights."""

@@ -464,11 +464,20 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
     // ---- the tiles hold the rounded output: copy them out, one row per request
     lds_barrier();
     {
-        char* Y = (char*)p.y + ((size_t)b * p.C + c0) * PLANE_B;
-        for (int r = wave; r < 2 * PH; r += 4) {
-            const int ch = r >> 7, row = r & (PH - 1);
-            const uint32_t v = tiles[ch * TILE_WORDS + tile_row(row) * TPITCH + lane];
-            *(uint32_t*)(Y + (size_t)r * ROW_B + lane * 4) = v;
+        // sixteen rows at a time: all their LDS reads are on their way before the first store needs its word
+        const rsrc_t yb = make_rsrc((char*)p.y + ((size_t)b * p.C + c0) * PLANE_B);
+        const uint32_t voff = (uint32_t)(lane * 4);
+        constexpr int GROUP = 16;
+        for (int r0 = wave; r0 < 2 * PH; r0 += 4 * GROUP) {
+            uint32_t v[GROUP];
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i) {
+                const int r = r0 + 4 * i, ch = r >> 7, row = r & (PH - 1);
+                v[i] = tiles[ch * TILE_WORDS + tile_row(row) * TPITCH + lane];
+            }
+#pragma unroll
+            for (int i = 0; i < GROUP; ++i)
+                __builtin_amdgcn_raw_buffer_store_b32(v[i], yb, voff, __builtin_amdgcn_readfirstlane((r0 + 4 * i) * ROW_B), 0);
         }
     }
 }

@@ -78,23 +78,28 @@ template <typename T, int VEC> __device__ __forceinline__ void stv(T* p, const f
 
 // h of the previous scan line as the three taps of VEC adjacent pixels see it.  `row` = the image row to read (NULL: it
 // does not exist), j0 = first column of the pixels, `shift` = column offset of the tap (-1, 0, +1); 0 outside the image.
-template <typename T, int VEC>
+// SHUF: the pixel blocks of neighbouring lanes are neighbours in the row (the blocks of a row divide a wave), so the element beside the block comes from the neighbouring lane's registers instead of a request of its own.
+template <typename T, int VEC, bool SHUF>
 __device__ __forceinline__ void tap_window(const T* row, int j0, int W, int shift, const float (&centre)[VEC], float (&out)[VEC]) {
     if (shift == 0) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) out[v] = centre[v];
     } else if (shift < 0) {
-        const float edge = (row && j0 > 0) ? ldf(row + j0 - 1) : 0.f;
+        float edge;
+        if constexpr (SHUF) { const float nb = from_lane_below(centre[VEC - 1]); edge = j0 > 0 ? nb : 0.f; }
+        else edge = (row && j0 > 0) ? ldf(row + j0 - 1) : 0.f;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) out[v] = v > 0 ? centre[v - 1] : edge;
     } else {
-        const float edge = (row && j0 + VEC < W) ? ldf(row + j0 + VEC) : 0.f;
+        float edge;
+        if constexpr (SHUF) { const float nb = from_lane_above(centre[0]); edge = j0 + VEC < W ? nb : 0.f; }
+        else edge = (row && j0 + VEC < W) ? ldf(row + j0 + VEC) : 0.f;
 #pragma unroll
         for (int v = 0; v < VEC; ++v) out[v] = v < VEC - 1 ? centre[v + 1] : edge;
     }
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool SHUF>
 __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs) {
     const int H = p.H, W = p.W, HW = H * W;
     const int npb = HW / VEC;
@@ -154,9 +159,9 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) hv[v] = 0.f;
             if (row) ldv<T, VEC>(row + j0, hv);
-            tap_window<T, VEC>(row, j0, W, -1, hv, t0);
-            tap_window<T, VEC>(row, j0, W, 0, hv, t1);
-            tap_window<T, VEC>(row, j0, W, 1, hv, t2);
+            tap_window<T, VEC, SHUF>(row, j0, W, -1, hv, t0);
+            tap_window<T, VEC, SHUF>(row, j0, W, 0, hv, t1);
+            tap_window<T, VEC, SHUF>(row, j0, W, 1, hv, t2);
         } else {
             float hv[VEC];
 #pragma unroll
@@ -164,9 +169,9 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
                 const int ir = i + k - 1;
                 const T* row = (ir >= 0 && ir < H) ? HS + plane + (size_t)ir * W : nullptr;
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) hv[v] = 0.f;
-                if (row) ldv<T, VEC>(row + j0, hv);
-                tap_window<T, VEC>(row, j0, W, dcol, hv, k == 0 ? t0 : (k == 1 ? t1 : t2));
+                for (int v = 0; v < VEC; ++v) hv[v] = k == 1 ? hc[v] : 0.f;      // the pixels' own row is in registers already
+                if (k != 1 && row) ldv<T, VEC>(row + j0, hv);
+                tap_window<T, VEC, SHUF>(row, j0, W, dcol, hv, k == 0 ? t0 : (k == 1 ? t1 : t2));
             }
         }
         float gl[VEC], gu[VEC];
@@ -219,7 +224,13 @@ hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
     const size_t per_dir = (size_t)p.B * p.G * (p.H * p.W / VEC);
     const size_t blocks = ((per_dir + 255) / 256 + 7) / 8 * 8 * ndirs;      // per direction: a multiple of 8 workgroups
     if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((bwd_finish_kernel<T, VEC>), dim3((unsigned)blocks), dim3(256), 0, s, p, ndirs);
+    // a lane's neighbours hold the neighbouring blocks of its row when the blocks of a row divide a wave (a wave starts at a
+    // multiple of 64 blocks: workgroups are 256 threads, planes whole rows), so that no row continues in another wave
+    const int bpr = p.W / VEC;
+    if (VEC > 1 && 64 % bpr == 0)
+        hipLaunchKernelGGL((bwd_finish_kernel<T, VEC, true>), dim3((unsigned)blocks), dim3(256), 0, s, p, ndirs);
+    else
+        hipLaunchKernelGGL((bwd_finish_kernel<T, VEC, false>), dim3((unsigned)blocks), dim3(256), 0, s, p, ndirs);
     return hipGetLastError();
 }
 

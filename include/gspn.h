@@ -114,7 +114,7 @@ int gspn_scan_bwd(const void* gy, const void* x, const void* w, const void* lam,
  * the local forward call is what the local backward call with the same kchunk expects.
  * Every kernel family has local instantiations, so a local call runs on the same family as the global
  * call of its shape (gspn_fwd_local_plan / gspn_bwd_local_plan name it) -- except calls with few planes
- * (B*C <= 256) on maps of 64, 128 or 256 rows and columns whose kchunk divides both sides (and is a
+ * (B*C <= 256 and B*C*max(H, W)/kchunk <= 512) on maps of 64, 128 or 256 rows and columns whose kchunk divides both sides (and is a
  * multiple of 16 bytes of storage), all four directions, no logits: there the stretches are the work items
  * (Sec. 4.1: the chunk index is part of the grid; plan "chunk"), one workgroup per (plane, stretch) in two
  * launches (vertical stretches, then horizontal ones adding onto y: in bf16 storage y is rounded twice),

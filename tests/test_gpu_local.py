@@ -166,6 +166,8 @@ def test_per_stretch_kernels_are_for_calls_with_few_planes(monkeypatch):
     import paper_2512_07884_amd as G
     assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 32, 15, 0, 0, False) == "chunk"
     assert G.gspn_fwd_local_plan(2, 1024, 128, 128, 16, 32, 15, 1, 0, False) == "tile"      # planes fill the chip
+    assert G.gspn_fwd_local_plan(1, 128, 128, 128, 4, 32, 15, 0, 0, False) == "chunk"       # 512 stretches per launch
+    assert G.gspn_fwd_local_plan(1, 256, 128, 128, 4, 32, 15, 0, 0, False) == "tile"        # 1024: more than two per CU
     assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 24, 15, 0, 0, False) == "tile"         # kchunk does not divide
     assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 128, 15, 0, 0, False) == "tile"        # a single stretch
     assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 32, 5, 0, 0, False) == "tile"          # not all four directions

@@ -240,7 +240,7 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps)
  *   GSPN_FWD_NO_PAIR=1   skip the "pair" kernels (forward and the reverse sweep of the two-pass backward)
  *   GSPN_STREAM_NO_STAGED=1   the "stream" kernel that requests one row per lane instead of whole lines
- *   GSPN_STREAM_ONE_CHANNEL=1   the "stream" kernel with one channel per workgroup on 512-row bf16 maps (two channels of a
+ *   GSPN_STREAM_ONE_CHANNEL=1   the "stream" kernel with one channel per workgroup on 256- and 512-row bf16 maps (two channels of a
  *                               weight group share a workgroup and the weights there otherwise)
  *   GSPN_FWD_NO_CHUNK=1   skip the "chunk" kernels of GSPN-local (forward and the reverse sweep of the two-pass backward) */
 const char* gspn_fwd_plan(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype, unsigned flags, int has_h_save);

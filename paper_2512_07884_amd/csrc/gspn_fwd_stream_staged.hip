@@ -212,11 +212,13 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
 // The same for TWO channels of one weight group (Sec. 4.2: they share the weights), one after the other chunk by chunk:
 // a chunk of the weights is requested and turned into row order once and serves both channels' 64 scan steps.  The
 // registers of x, lam, u take, as they are consumed, channel B's chunk while channel A is worked on and channel A's next
-// chunk while channel B is; those of the weights take the next chunk while channel B is worked on.  One direction at a
-// time (maps of 512 rows: all eight waves hold rows); y of both channels already holds the vertical pair's sum.
+// chunk while channel B is; those of the weights take the next chunk while channel B is worked on.  y of both channels
+// already holds the vertical pair's sum.  Maps of 512 rows run one direction at a time (all eight waves hold rows,
+// sync_at < 0); maps of 256 rows both at once, four waves each (direction slot dslot), each first on the half of the
+// columns it starts in and, after the workgroup has met before chunk sync_at, on the other half.
 template <bool REV, bool SAVE, bool BWD>
 __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a, char* blk_b, float* mailbox, int parts, int b, int c,
-                                                 int part, int lane) {
+                                                 int dslot, int part, int lane, int sync_at) {
     constexpr int d = (REV != BWD) ? 3 : 2;
     const int H = p.H, W = p.W, HW = H * W;
     const int row_bytes = W * 2, nchunks = W / CS;
@@ -285,7 +287,7 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
         float h = second ? hB : hA;
         float wp0 = second ? wpB0 : wpA0, wp1 = second ? wpB1 : wpA1, wp2 = second ? wpB2 : wpA2;
         // mailbox: [channel][part][parity] pairs, as in horizontal_rows
-        float* const task = mailbox + (second ? 1 : 0) * 8 * 4;
+        float* const task = mailbox + (dslot * 2 + (second ? 1 : 0)) * parts * 4;
         const f32x2_hw* const mb_in = (const f32x2_hw*)(task + part * 4);
         float* const mb_out = bot_lane ? task + (part + 1) * 4 : task + (part - 1) * 4 + 1;
         // what the registers of x, lam, u take as they are consumed: channel B's same chunk, or channel A's next one
@@ -342,7 +344,8 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
                 // those of the weights, once channel B is done with them, instruction q of the next chunk
                 if (more) issue_own(next_chan, next_chunk, e >> 3);
                 if (second && more) issue_w(next_chunk, e >> 3);
-                if (k == (BWD ? 55 : 47) && more) issue_y(next_chan, next_chunk);
+                // (channel A's next chunk of y cannot be asked for while the other direction is still to write it)
+                if (k == (BWD ? 55 : 47) && more && !(second && next_chunk == sync_at)) issue_y(next_chan, next_chunk);
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
@@ -371,6 +374,10 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
     for (int ch = 0; ch < nchunks; ++ch) {
         const int col0 = (REV ? nchunks - 1 - ch : ch) * CS;
         for (int chan = 0; chan < 2; ++chan) {
+            if (chan == 0 && ch == sync_at) {
+                __syncthreads();                 // every wave's stores of y are complete: the two directions swap halves
+                issue_y(0, ch);
+            }
             y_to_block();
             to_rows(bx); to_rows(bl);
             if (chan == 0) { to_rows(b0); to_rows(b1); to_rows(b2); }      // channel B: the weights are in row order already
@@ -465,7 +472,7 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
     }
 }
 
-// Two channels of a weight group per workgroup on maps of 512 rows, all four directions: the vertical pairs of both
+// Two channels of a weight group per workgroup on maps of 512 or 256 rows, all four directions: the vertical pairs of both
 // channels at the same time (waves 0, 1 and 2, 3), then the horizontal directions one after the other with the weights
 // shared (horizontal_rows2).
 template <int V, int PF, bool SAVE, bool BWD>
@@ -502,11 +509,21 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
     // ---- horizontal directions, one after the other; wave = part
     char* const blk_a = lds + wave * 2 * BLOCK_B;
     char* const blk_b = blk_a + BLOCK_B;
-    for (int dsel = 0; dsel < 2; ++dsel) {
+    if (a.parts == 8) {
+        for (int dsel = 0; dsel < 2; ++dsel) {
+            if (threadIdx.x < MAILBOX_FLOATS) mailbox[threadIdx.x] = 0.f;
+            __syncthreads();                    // y of the previous phase complete, mailbox cleared
+            if (dsel == 0) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
+            else horizontal_rows2<true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
+        }
+    } else {
+        // 256 rows: both directions at once, wave -> (direction slot, part)
         if (threadIdx.x < MAILBOX_FLOATS) mailbox[threadIdx.x] = 0.f;
-        __syncthreads();                    // y of the previous phase complete, mailbox cleared
-        if ((dsel == 0) != BWD) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, wave, lane);
-        else horizontal_rows2<true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, wave, lane);
+        __syncthreads();                        // y of the vertical pair complete, mailbox cleared
+        const int nchunks = p.W / CS;
+        const int dslot = wave >> 2, part = wave & 3;
+        if (dslot == 0) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, 0, part, lane, nchunks / 2);
+        else horizontal_rows2<true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, 1, part, lane, nchunks / 2);
     }
 }
 
@@ -539,9 +556,10 @@ static hipError_t launch_staged2(const StreamArgs& a, bool reverse, hipStream_t 
     return hipGetLastError();
 }
 
-// two channels of a group per workgroup: maps of 512 rows, all four directions, an even number of channels per group
+// two channels of a group per workgroup: maps of 512 or 256 rows, all four directions, an even number of channels per group
 static bool two_channels_ok(const FwdParams& p, const StreamPlan& t) {
-    return stream_two_channels_enabled() && t.parts == 8 && p.mask == 15u && p.cpg % 2 == 0 && p.C % 2 == 0;
+    const bool rows_ok = t.parts == 8 || (t.parts == 4 && (p.W / CS) % 2 == 0);
+    return stream_two_channels_enabled() && rows_ok && p.mask == 15u && p.cpg % 2 == 0 && p.C % 2 == 0;
 }
 
 // bf16 storage, the global scan with normalised weights, every shape the stream plan takes

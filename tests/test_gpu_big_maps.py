@@ -72,8 +72,9 @@ def test_direction_masks_on_maps_of_more_than_1024_rows(mask):
 # the horizontal phases fetched once for both), with one channel per workgroup, and the row-per-lane stream kernel
 @pytest.mark.parametrize("knob", [None, "GSPN_STREAM_ONE_CHANNEL", "GSPN_STREAM_NO_STAGED"], ids=["two-channel", "one-channel", "row-per-lane"])
 @pytest.mark.parametrize("shape", [(1, 4, 512, 512, 2, "bf16"), (1, 4, 512, 1024, 1, "bf16"), (2, 2, 512, 256, 1, "bf16"),
-                                   (1, 3, 512, 256, 1, "bf16")], ids=lambda v: "x".join(map(str, v)))
-def test_stream_kernel_variants_on_maps_of_512_rows(shape, knob, monkeypatch):
+                                   (1, 3, 512, 256, 1, "bf16"), (1, 4, 256, 1024, 2, "bf16"), (2, 2, 256, 256, 1, "bf16"),
+                                   (1, 4, 256, 512, 1, "bf16")], ids=lambda v: "x".join(map(str, v)))
+def test_stream_kernel_variants_on_maps_of_256_and_512_rows(shape, knob, monkeypatch):
     import paper_2512_07884_amd as G
     if knob:
         monkeypatch.setenv(knob, "1")

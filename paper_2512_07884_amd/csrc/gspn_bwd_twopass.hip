@@ -37,19 +37,20 @@ bool reverse_sweep_chunk_applicable(const FwdParams& p, int dtype);
 
 namespace {
 
-// VEC adjacent elements of storage, widened to fp32 (p aligned to VEC elements)
-template <typename T, int VEC> __device__ __forceinline__ void ldv(const T* p, float (&out)[VEC]) {
+// VEC adjacent elements of storage, widened to fp32 (p aligned to VEC elements).  ONCE: nothing reads these lines again
+// (non-temporal request: the caches give them up first, which leaves more room for x and gy, which the workgroups of all four directions read)
+template <typename T, int VEC, bool ONCE = false> __device__ __forceinline__ void ldv(const T* p, float (&out)[VEC]) {
     if constexpr (VEC == 1) {
         out[0] = ldf(p);
     } else {
         constexpr int NB = VEC * (int)sizeof(T);
         uint32_t r[NB / 4];
-        if constexpr (NB == 4) r[0] = *(const uint32_t*)p;
-        else if constexpr (NB == 8) { const u32x2 v = *(const u32x2*)p; r[0] = v.x; r[1] = v.y; }
+        if constexpr (NB == 4) r[0] = ONCE ? __builtin_nontemporal_load((const uint32_t*)p) : *(const uint32_t*)p;
+        else if constexpr (NB == 8) { const u32x2 v = ONCE ? __builtin_nontemporal_load((const u32x2*)p) : *(const u32x2*)p; r[0] = v.x; r[1] = v.y; }
         else {
 #pragma unroll
             for (int i = 0; i < NB / 16; ++i) {
-                const u32x4 v = ((const u32x4*)p)[i];
+                const u32x4 v = ONCE ? __builtin_nontemporal_load((const u32x4*)p + i) : ((const u32x4*)p)[i];
                 r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
             }
         }
@@ -57,20 +58,20 @@ template <typename T, int VEC> __device__ __forceinline__ void ldv(const T* p, f
         for (int v = 0; v < VEC; ++v) out[v] = elem<T>(r, v);
     }
 }
-template <typename T, int VEC> __device__ __forceinline__ void stv(T* p, const float (&in)[VEC]) {
+template <typename T, int VEC, bool ONCE = false> __device__ __forceinline__ void stv(T* p, const float (&in)[VEC]) {
     if constexpr (VEC == 1) {
         stf(p, in[0]);
     } else {
         constexpr int NB = VEC * (int)sizeof(T);
         uint32_t r[NB / 4];
         pack<T, VEC>(in, r);
-        if constexpr (NB == 4) *(uint32_t*)p = r[0];
-        else if constexpr (NB == 8) { const u32x2 v = {r[0], r[1]}; *(u32x2*)p = v; }
+        if constexpr (NB == 4) { if constexpr (ONCE) __builtin_nontemporal_store(r[0], (uint32_t*)p); else *(uint32_t*)p = r[0]; }
+        else if constexpr (NB == 8) { const u32x2 v = {r[0], r[1]}; if constexpr (ONCE) __builtin_nontemporal_store(v, (u32x2*)p); else *(u32x2*)p = v; }
         else {
 #pragma unroll
             for (int i = 0; i < NB / 16; ++i) {
                 const u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
-                ((u32x4*)p)[i] = v;
+                if constexpr (ONCE) __builtin_nontemporal_store(v, (u32x4*)p + i); else ((u32x4*)p)[i] = v;
             }
         }
     }
@@ -147,7 +148,7 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
     for (int ci = 0; ci < p.cpg; ++ci) {
         const size_t plane = ((size_t)b * p.C + (size_t)g * p.cpg + ci) * HW;
         float e[VEC], xv[VEC], gyv[VEC], hc[VEC];
-        ldv<T, VEC>(GL + plane + pix0, e);
+        ldv<T, VEC, true>(GL + plane + pix0, e);
         ldv<T, VEC>(X + plane + pix0, xv);
         ldv<T, VEC>(GY + plane + pix0, gyv);
         ldv<T, VEC>(HS + plane + pix0, hc);
@@ -184,8 +185,8 @@ __global__ void __launch_bounds__(256) bwd_finish_kernel(BwdParams p, int ndirs)
             gl[v] = xv[v] * e[v];
             gu[v] = gyv[v] * hc[v];
         }
-        stv<T, VEC>(GL + plane + pix0, gl);
-        stv<T, VEC>(GU + plane + pix0, gu);
+        stv<T, VEC, true>(GL + plane + pix0, gl);
+        stv<T, VEC, true>(GU + plane + pix0, gu);
     }
     if (p.logits) {
         // the weights were given as logits: the sum over the group's channels goes through the softmax of its pixel once

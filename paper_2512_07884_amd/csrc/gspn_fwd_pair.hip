@@ -55,8 +55,8 @@ constexpr size_t PERSIST_WGS = 256;               // compute units of the chip t
 
 __device__ __forceinline__ float lo16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-__device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t voff, int soff) {
-    return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, __builtin_amdgcn_readfirstlane(soff), 0);
+template <int CP = 0> __device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t voff, int soff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, __builtin_amdgcn_readfirstlane(soff), CP);
 }
 // where image row r sits in an output tile (in rows of TPITCH words)
 __device__ __forceinline__ int tile_row(int r) { return (r >> 1) + (PH / 2) * (r & 1); }
@@ -92,16 +92,22 @@ __device__ __forceinline__ ChainRefs chain_refs(const FwdParams& p, int b, int c
 }
 // image row of step k of band s
 template <bool UP> __device__ __forceinline__ int chain_row(int s, int k) { return UP ? PH - 1 - (s * VBAND + k) : s * VBAND + k; }
-__device__ __forceinline__ uint32_t ld32(rsrc_t rs, uint32_t voff, int row) {
-    return __builtin_amdgcn_raw_buffer_load_b32(rs, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), 0);
+template <int CP = 0> __device__ __forceinline__ uint32_t ld32(rsrc_t rs, uint32_t voff, int row) {
+    return __builtin_amdgcn_raw_buffer_load_b32(rs, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), CP);
 }
 // band s of the chain's own tensors
-template <bool UP>
+// lam and u of a direction are read by one chain only: their lines go with CP_STREAM, so that the weights, which all
+// channels of the group read, stay in the L2 longer (diff128 0.194 -> 0.186 ms).  Not x, which the horizontal pair reads
+// a second time 25 us later; not with h_save and not in the reverse sweep: there a backward call follows, or the
+// forward call came just before, and what the 256 MB last-level cache still holds of lam and u is worth more
+// (train128: forward 0.243 -> 0.231 ms but the backward call after it 0.500 -> 0.511 ms).
+template <bool SAVE, bool BWD> constexpr int cp_lam_u() { return (SAVE || BWD) ? 0 : CP_STREAM; }
+template <bool UP, int CP>
 __device__ __forceinline__ void issue_own(const ChainRefs& t, uint32_t voff, int s, uint32_t (&x)[VBAND], uint32_t (&l)[VBAND], uint32_t (&u)[VBAND]) {
 #pragma unroll
     for (int k = 0; k < VBAND; ++k) {
         const int row = chain_row<UP>(s, k);
-        x[k] = ld32(t.xb, voff, row); l[k] = ld32(t.lb, voff, row); u[k] = ld32(t.ub, voff, row);
+        x[k] = ld32(t.xb, voff, row); l[k] = ld32<CP>(t.lb, voff, row); u[k] = ld32<CP>(t.ub, voff, row);
     }
 }
 // steps kc * VBAND/2 .. of band s: this wave's share of the weight rows
@@ -129,18 +135,18 @@ __device__ __forceinline__ void drop_w(char* region, int kc, int lane, int s, co
 // it for its next pair of channels while the horizontal pair of the current one is still at work.
 // FROM, TO: the requests are numbered 0..4 (own 0, weights 0, own 1, weights 1, own 2); where registers are short the
 // early call makes the first of them only and the chain makes the others when it starts.
-template <bool UP, bool BWD, int FROM, int TO>
+template <bool UP, bool SAVE, bool BWD, int FROM, int TO>
 __device__ __forceinline__ void chain_request_first(const FwdParams& p, int b, int c, int kc, int lane,
                                                     uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
                                                     uint32_t (&wr)[2][3][VBAND / 2]) {
     static_assert(VPF == 4, "written out for four bands in flight");
     const ChainRefs t = chain_refs<UP, false, BWD>(p, b, c);
     const uint32_t voff = (uint32_t)(lane * 4);
-    if constexpr (FROM <= 0 && 0 < TO) issue_own<UP>(t, voff, 0, xr[0], lr[0], ur[0]);
+    if constexpr (FROM <= 0 && 0 < TO) issue_own<UP, cp_lam_u<SAVE, BWD>()>(t, voff, 0, xr[0], lr[0], ur[0]);
     if constexpr (FROM <= 1 && 1 < TO) issue_w<UP>(t, voff, kc, 0, wr[0]);
-    if constexpr (FROM <= 2 && 2 < TO) issue_own<UP>(t, voff, 1, xr[1], lr[1], ur[1]);
+    if constexpr (FROM <= 2 && 2 < TO) issue_own<UP, cp_lam_u<SAVE, BWD>()>(t, voff, 1, xr[1], lr[1], ur[1]);
     if constexpr (FROM <= 3 && 3 < TO) issue_w<UP>(t, voff, kc, 1, wr[1]);
-    if constexpr (FROM <= 4 && 4 < TO) issue_own<UP>(t, voff, 2, xr[2], lr[2], ur[2]);
+    if constexpr (FROM <= 4 && 4 < TO) issue_own<UP, cp_lam_u<SAVE, BWD>()>(t, voff, 2, xr[2], lr[2], ur[2]);
 }
 // how many of them are made early: all five in the plain forward scan; with h_save / in the reverse sweep the
 // horizontal tasks hold more registers (the states on their way out), and one or two is what fits beside them
@@ -205,19 +211,19 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
             tile[tile_row(row) * TPITCH + lane] = pack_bf16x2(lo16(ow[k]) + y0, hi16(ow[k]) + y1);
             if constexpr (SAVE) {
                 const uint32_t hw = pack_bf16x2(h[0], h[1]);
-                __builtin_amdgcn_raw_buffer_store_b32(hw, t.hb, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), 0);
+                __builtin_amdgcn_raw_buffer_store_b32(hw, t.hb, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), BWD ? 0 : CP_STREAM);
             }
         }
-        if (more_own) issue_own<UP>(t, voff, s + VPF, xr[slot], lr[slot], ur[slot]);
+        if (more_own) issue_own<UP, cp_lam_u<SAVE, BWD>()>(t, voff, s + VPF, xr[slot], lr[slot], ur[slot]);
         lds_barrier();
     };
 
-    chain_request_first<UP, BWD, early_requests<SAVE, BWD>(), 5>(p, b, c, kc, lane, xr, lr, ur, wr);
+    chain_request_first<UP, SAVE, BWD, early_requests<SAVE, BWD>(), 5>(p, b, c, kc, lane, xr, lr, ur, wr);
     // the rest of the first requests: band 0 of the weights goes to the ring (it takes the place band "s + 1" has in
     // the loop), its registers take band 2
     drop_w<UP>(region, kc, lane, 0, wr[0]);
     issue_w<UP>(t, voff, kc, 2, wr[0]);
-    issue_own<UP>(t, voff, 3, xr[3], lr[3], ur[3]);
+    issue_own<UP, cp_lam_u<SAVE, BWD>()>(t, voff, 3, xr[3], lr[3], ur[3]);
     lds_barrier();
     // weight registers: band s + 1 waits in wr[(s + 1) & 1]; once dropped, the same registers take band s + 3
     for (int s0 = 0; s0 < VNBANDS - V_AHEAD; s0 += VPF) {
@@ -248,8 +254,10 @@ struct ChunkIO {
         rd = (u32x4*)stage + SPITCH * 2 * lane;
     }
     // rows 8i..8i+7 of a chunk whose first column sits col_bytes into the row, into registers 4 * slot ..
+    // CP: CP_STREAM for the tensors no other workgroup reads (x, lam, u)
+    template <int CP = 0>
     __device__ __forceinline__ void issue1(rsrc_t rs, int col_bytes, int i, int slot, uint32_t (&r)[32]) const {
-        const u32x4 v = ld128(rs, voff, col_bytes + i * 8 * ROW_B);
+        const u32x4 v = ld128<CP>(rs, voff, col_bytes + i * 8 * ROW_B);
         r[4 * slot] = v.x; r[4 * slot + 1] = v.y; r[4 * slot + 2] = v.z; r[4 * slot + 3] = v.w;
     }
     // ... and from there to their place in a staging block
@@ -274,9 +282,10 @@ struct ChunkIO {
         }
     }
     // ... and back, for stores that cover whole lines: the staging block holds a chunk in row order
+    template <int CP = 0>
     __device__ __forceinline__ void store_staged(rsrc_t rs, int col_bytes) const {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) st_b128(rs, voff + (uint32_t)(col_bytes + i * 8 * ROW_B), wr[8 * SPITCH * i]);
+        for (int i = 0; i < 16; ++i) st_b128<CP>(rs, voff + (uint32_t)(col_bytes + i * 8 * ROW_B), wr[8 * SPITCH * i]);
     }
 };
 
@@ -339,14 +348,14 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
         const int cb = col_bytes(c_);
         const int f = REV ? 7 - q : q;
         if (with_x) { io.issue1(xb, cb, 2 * f, q, bx0); io.issue1(xb, cb, 2 * f + 1, q, bx1); }
-        io.issue1(lb, cb, 2 * f, q, bl0); io.issue1(lb, cb, 2 * f + 1, q, bl1);
+        io.issue1<cp_lam_u<SAVE, BWD>()>(lb, cb, 2 * f, q, bl0); io.issue1<cp_lam_u<SAVE, BWD>()>(lb, cb, 2 * f + 1, q, bl1);
         if ((f & 1) == 0) {
             const int i = 8 * twin + f;
             io.issue1(w0b, cb, i, q, b00); io.issue1(w0b, cb, i + 1, q, b01);
             io.issue1(w1b, cb, i, q, b10); io.issue1(w1b, cb, i + 1, q, b11);
             io.issue1(w2b, cb, i, q, b20); io.issue1(w2b, cb, i + 1, q, b21);
         }
-        io.issue1(ub, cb, 2 * f, q, bu0); io.issue1(ub, cb, 2 * f + 1, q, bu1);
+        io.issue1<cp_lam_u<SAVE, BWD>()>(ub, cb, 2 * f, q, bu0); io.issue1<cp_lam_u<SAVE, BWD>()>(ub, cb, 2 * f + 1, q, bu1);
     };
     auto prefetch = [&]() {
 #pragma unroll
@@ -405,7 +414,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
         __builtin_amdgcn_sched_barrier(0);
 
         // nothing is left to request for this pair: the next pair's vertical chains start theirs
-        if (ch == 1 && has_next) chain_request_first<UP, BWD, 0, early_requests<SAVE, BWD>()>(p, nb, nc0 + kc, kc, lane, xr, lr, ur, wr);
+        if (ch == 1 && has_next) chain_request_first<UP, SAVE, BWD, 0, early_requests<SAVE, BWD>()>(p, nb, nc0 + kc, kc, lane, xr, lr, ur, wr);
 
         float cpair[2] = {0.f, 0.f}, hpair[2] = {0.f, 0.f};    // first element of the pair of columns that share a word
         uint32_t yw[2] = {0, 0};
@@ -458,7 +467,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        if constexpr (SAVE) io.store_staged(hb, col0 * 2);
+        if constexpr (SAVE) io.store_staged<BWD ? 0 : CP_STREAM>(hb, col0 * 2);
     }
 
     // ---- the tiles hold the rounded output: copy them out, one row per request
@@ -477,7 +486,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
             }
 #pragma unroll
             for (int i = 0; i < GROUP; ++i)
-                __builtin_amdgcn_raw_buffer_store_b32(v[i], yb, voff, __builtin_amdgcn_readfirstlane((r0 + 4 * i) * ROW_B), 0);
+                __builtin_amdgcn_raw_buffer_store_b32(v[i], yb, voff, __builtin_amdgcn_readfirstlane((r0 + 4 * i) * ROW_B), CP_STREAM);
         }
     }
 }
@@ -500,7 +509,7 @@ __device__ __forceinline__ void pair_loop(const FwdParams& p, uint32_t* tiles, c
     uint32_t xr[VPF][VBAND], lr[VPF][VBAND], ur[VPF][VBAND], wr[2][3][VBAND / 2];
     int b, c0;
     item_of(0, b, c0);
-    chain_request_first<UP, BWD, 0, early_requests<SAVE, BWD>()>(p, b, c0 + kc, kc, lane, xr, lr, ur, wr);
+    chain_request_first<UP, SAVE, BWD, 0, early_requests<SAVE, BWD>()>(p, b, c0 + kc, kc, lane, xr, lr, ur, wr);
     for (unsigned round = 0; round < rounds; ++round) {
         // a workgroup beyond the end of a short last round has nothing left
         const bool has_next = round + 1 < rounds && (round + 2 < rounds || blockIdx.x < total - (round + 1) * gridDim.x);

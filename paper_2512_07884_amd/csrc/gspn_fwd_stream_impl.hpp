@@ -43,6 +43,8 @@ struct VStream {
     static_assert(!BWD || SAVE, "the reverse sweep saves its state");
     static constexpr int NB = V * (int)sizeof(T);
     static constexpr int NR = NB / 4;
+    // x, lam, u are read once by the launch; with up to 16 bytes per lane a request covers whole lines, each once
+    static constexpr int CP_OWN = NB <= 16 ? CP_STREAM : 0;
     struct Line { uint32_t x[NR], l[NR], u[NR], w0[NR], w1[NR], w2[NR], y[NR]; };
     rsrc_t xb, lb, ub, w0b, w1b, w2b, yb, hb;
     uint32_t voff;
@@ -91,9 +93,9 @@ struct VStream {
         Line slot[PF];
         auto issue = [&](Line& s, int t) {
             const int so = row_off(t < t_end ? t : t_end - 1);    // clamped: redundant but in bounds
-            ld_buf<NB>(xb, voff, so, s.x);
-            ld_buf<NB>(lb, voff, so, s.l);
-            ld_buf<NB>(ub, voff, so, s.u);
+            ld_buf<NB, CP_OWN>(xb, voff, so, s.x);
+            ld_buf<NB, CP_OWN>(lb, voff, so, s.l);
+            ld_buf<NB, CP_OWN>(ub, voff, so, s.u);
             ld_buf<NB>(w0b, voff, so, s.w0);
             ld_buf<NB>(w1b, voff, so, s.w1);
             ld_buf<NB>(w2b, voff, so, s.w2);
@@ -158,7 +160,7 @@ struct VStream {
             st_buf<NB>(yb, voff, row_off(t), o);
             if constexpr (SAVE) {
                 pack<T, V>(h, o);
-                st_buf<NB>(hb, voff, row_off(t), o);
+                st_buf<NB, CP_STREAM>(hb, voff, row_off(t), o);      // h_save: nothing in this call reads it
             }
             issue(slot[k], t + PF);
         };

@@ -38,8 +38,8 @@ constexpr int LDS_BYTES = 8 * 2 * BLOCK_B + MAILBOX_FLOATS * 4;
 
 __device__ __forceinline__ float lo16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-__device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t voff, int soff) {
-    return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, __builtin_amdgcn_readfirstlane(soff), 0);
+template <int CP = 0> __device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t voff, int soff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, __builtin_amdgcn_readfirstlane(soff), CP);
 }
 
 // One horizontal direction for the wave that owns rows 64 * part .. of the plane.  Chunks [0, nchunks) in scan order;
@@ -93,12 +93,17 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
         const u32x4 v = ld128(rs, voff, cb + i * istep);
         r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
     };
+    // ... of a tensor this launch reads once (x, lam, u)
+    auto issue1s = [&](rsrc_t rs, int cb, int i, uint32_t (&r)[32]) {
+        const u32x4 v = ld128<CP_STREAM>(rs, voff, cb + i * istep);
+        r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+    };
     // instruction q of chunk c_ for the six tensors (their registers 4q..4q+3 are free at that point)
     auto issue_slot = [&](int c_, int q) {
         const int cb = col_bytes(c_);
-        issue1(xb, cb, q, bx); issue1(lb, cb, q, bl);
+        issue1s(xb, cb, q, bx); issue1s(lb, cb, q, bl);
         issue1(w0b, cb, q, b0); issue1(w1b, cb, q, b1); issue1(w2b, cb, q, b2);
-        issue1(ub, cb, q, bu);
+        issue1s(ub, cb, q, bu);
     };
     auto issue_y = [&](int c_) {
         const int cb = col_bytes(c_);
@@ -203,7 +208,7 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
         for (int i = 0; i < 8; ++i) st_b128(yb, voff + (uint32_t)(col0 * 2 + i * istep), wr_b[8 * SPITCH * i]);
         if constexpr (SAVE) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) st_b128(hb, voff + (uint32_t)(col0 * 2 + i * istep), wr_a[8 * SPITCH * i]);
+            for (int i = 0; i < 8; ++i) st_b128<BWD ? 0 : CP_STREAM>(hb, voff + (uint32_t)(col0 * 2 + i * istep), wr_a[8 * SPITCH * i]);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -256,10 +261,15 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
         const u32x4 v = ld128(rs, voff, cb + i * istep);
         r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
     };
+    // ... of a tensor this launch reads once (x, lam, u)
+    auto issue1s = [&](rsrc_t rs, int cb, int i, uint32_t (&r)[32]) {
+        const u32x4 v = ld128<CP_STREAM>(rs, voff, cb + i * istep);
+        r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+    };
     // chan: 0 = channel A, 1 = channel B
     auto issue_own = [&](int chan, int c_, int q) {
         const int cb = col_bytes(c_) + chan * plane_b;
-        issue1(xb, cb, q, bx); issue1(lb, cb, q, bl); issue1(ub, cb, q, bu);
+        issue1s(xb, cb, q, bx); issue1s(lb, cb, q, bl); issue1s(ub, cb, q, bu);
     };
     auto issue_w = [&](int c_, int q) {
         const int cb = col_bytes(c_);
@@ -363,7 +373,7 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
         for (int i = 0; i < 8; ++i) st_b128(yb, at + (uint32_t)(i * istep), wr_b[8 * SPITCH * i]);
         if constexpr (SAVE) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) st_b128(hb, at + (uint32_t)(i * istep), wr_a[8 * SPITCH * i]);
+            for (int i = 0; i < 8; ++i) st_b128<BWD ? 0 : CP_STREAM>(hb, at + (uint32_t)(i * istep), wr_a[8 * SPITCH * i]);
         }
         __builtin_amdgcn_sched_barrier(0);
     };

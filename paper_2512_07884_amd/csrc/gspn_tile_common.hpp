@@ -16,19 +16,25 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
 }
-template <int NB> __device__ __forceinline__ void ld_buf(rsrc_t rs, uint32_t voff, int soff, uint32_t* r) {
+// CP: the cache-policy bits of the request.  CP_STREAM marks data this launch reads exactly once ("nt", non-temporal):
+// the caches then give such lines up first, and what several workgroups read again -- the weights of a group
+// (Sec. 4.2), which every channel of the group asks for -- stays in the L2 longer (measured on a 512x512 map with 32
+// channels per group: 1.07 -> 0.96 ms).  Only for requests that cover each 128-byte line once: a line that a later
+// request of the same wave touches again would be fetched twice.
+constexpr int CP_STREAM = 2;
+template <int NB, int CP = 0> __device__ __forceinline__ void ld_buf(rsrc_t rs, uint32_t voff, int soff, uint32_t* r) {
     soff = __builtin_amdgcn_readfirstlane(soff);   // wave-uniform by construction: keep it in an SGPR
-    if constexpr (NB == 4) { r[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, 0); }
-    else if constexpr (NB == 8) { u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, 0); r[0] = v.x; r[1] = v.y; }
+    if constexpr (NB == 4) { r[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, CP); }
+    else if constexpr (NB == 8) { u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, CP); r[0] = v.x; r[1] = v.y; }
     else {
         static_assert(NB % 8 == 0, "vector width");
 #pragma unroll
         for (int i = 0; i < NB / 16; ++i) {
-            u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * i, soff, 0);
+            u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * i, soff, CP);
             r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
         }
         if constexpr (NB % 16 != 0) {                  // bursts of 8 (mod 16) bytes: the rest as one 8 B request
-            u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff + (NB / 16) * 16, soff, 0);
+            u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff + (NB / 16) * 16, soff, CP);
             r[NB / 4 - 2] = v.x; r[NB / 4 - 1] = v.y;
         }
     }
@@ -38,25 +44,25 @@ template <int NB> __device__ __forceinline__ void ld_buf(rsrc_t rs, uint32_t vof
 // on gfx950: with an SGPR offset and the data registers rewritten by the next instruction, the upper
 // half of the stored 16 B was corrupted now and then).  16 B stores therefore carry their whole
 // offset in the vector offset and pass 0 as the scalar one.
-__device__ __forceinline__ void st_b128(rsrc_t rs, uint32_t voff, u32x4 v) {
-    __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff, 0, 0);
+template <int CP = 0> __device__ __forceinline__ void st_b128(rsrc_t rs, uint32_t voff, u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff, 0, CP);
 }
-template <int NB> __device__ __forceinline__ void st_buf(rsrc_t rs, uint32_t voff, int soff, const uint32_t* r) {
-    if constexpr (NB == 4) { __builtin_amdgcn_raw_buffer_store_b32(r[0], rs, voff, __builtin_amdgcn_readfirstlane(soff), 0); }
+template <int NB, int CP = 0> __device__ __forceinline__ void st_buf(rsrc_t rs, uint32_t voff, int soff, const uint32_t* r) {
+    if constexpr (NB == 4) { __builtin_amdgcn_raw_buffer_store_b32(r[0], rs, voff, __builtin_amdgcn_readfirstlane(soff), CP); }
     else if constexpr (NB == 8) {
         u32x2 v = {r[0], r[1]};
-        __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, __builtin_amdgcn_readfirstlane(soff), 0);
+        __builtin_amdgcn_raw_buffer_store_b64(v, rs, voff, __builtin_amdgcn_readfirstlane(soff), CP);
     } else {
         static_assert(NB % 8 == 0, "vector width");
         const uint32_t vo = voff + (uint32_t)soff;
 #pragma unroll
         for (int i = 0; i < NB / 16; ++i) {
             u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
-            st_b128(rs, vo + 16 * i, v);
+            st_b128<CP>(rs, vo + 16 * i, v);
         }
         if constexpr (NB % 16 != 0) {
             u32x2 v = {r[NB / 4 - 2], r[NB / 4 - 1]};
-            __builtin_amdgcn_raw_buffer_store_b64(v, rs, vo + (NB / 16) * 16, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(v, rs, vo + (NB / 16) * 16, 0, CP);
         }
     }
 }

@@ -180,7 +180,7 @@ __device__ __forceinline__ void vertical_band(const FwdParams& p, int b, int c, 
                 if constexpr (SAVE) {
                     uint32_t o[NR];
                     pack<T, V>(h, o);
-                    st_buf<NB>(t.hb, voff, r * row_bytes, o);
+                    st_buf<NB, CP_STREAM>(t.hb, voff, r * row_bytes, o);
                 }
                 issue(slot[q], s + PF);
             }
@@ -308,7 +308,7 @@ __device__ __forceinline__ void horizontal_band(const FwdParams& p, float* mine,
                         uint32_t o[4];
                         pack<T, CS>(hq[r], o);
                         const u32x4 ov = {o[0], o[1], o[2], o[3]};
-                        st_b128(t.hb, voff[r] + (uint32_t)(sub * 16), ov);
+                        st_b128<CP_STREAM>(t.hb, voff[r] + (uint32_t)(sub * 16), ov);
                     }
                 }
                 issue(slot[qq], q + PF);

@@ -211,7 +211,7 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
             tile[tile_row(row) * TPITCH + lane] = pack_bf16x2(lo16(ow[k]) + y0, hi16(ow[k]) + y1);
             if constexpr (SAVE) {
                 const uint32_t hw = pack_bf16x2(h[0], h[1]);
-                __builtin_amdgcn_raw_buffer_store_b32(hw, t.hb, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), BWD ? 0 : CP_STREAM);
+                __builtin_amdgcn_raw_buffer_store_b32(hw, t.hb, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), CP_STREAM);
             }
         }
         if (more_own) issue_own<UP, cp_lam_u<SAVE, BWD>()>(t, voff, s + VPF, xr[slot], lr[slot], ur[slot]);
@@ -467,7 +467,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        if constexpr (SAVE) io.store_staged<BWD ? 0 : CP_STREAM>(hb, col0 * 2);
+        if constexpr (SAVE) io.store_staged<CP_STREAM>(hb, col0 * 2);
     }
 
     // ---- the tiles hold the rounded output: copy them out, one row per request

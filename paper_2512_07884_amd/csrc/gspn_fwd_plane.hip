@@ -158,12 +158,13 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
     const uint32_t flat = (uint32_t)lane * 16u;
     const uint32_t row_pad4 = 4u * (uint32_t)(P - W), ch_pad4 = 4u * (uint32_t)(HP - H * P);   // padded flat variant: bytes skipped at a row / channel end
     auto ldg = [&](rsrc_t rs, uint32_t vo, int so) -> u32x4 { return __builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0); };
+    // x, lam, u: each line is asked for once by the whole launch (CP_STREAM: the caches give it up first)
     auto load_planes = [&](const T* basep, u32x4 (&st)[NCH]) {
         const rsrc_t rs = make_rsrc(basep);
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
             u32x4 v = {0, 0, 0, 0};
-            if (vq[k]) v = ldg(rs, flat, k * 1024);
+            if (vq[k]) v = __builtin_amdgcn_raw_buffer_load_b128(rs, flat, k * 1024, CP_STREAM);
             st[k] = v;
         }
     };
@@ -448,7 +449,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
                         }
                         y[k][e] = fmaf(chunk_elem<T>(us[k], e), hv[e], y[k][e]);
                     }
-                    if constexpr (SAVE) st_b128(hb, flat + k * 1024, chunk_pack<T>(hv));
+                    if constexpr (SAVE) st_b128<CP_STREAM>(hb, flat + k * 1024, chunk_pack<T>(hv));
                 }
             }
         }
@@ -460,7 +461,7 @@ __global__ void __launch_bounds__(SHARED ? 512 : 256) fwd_plane_kernel(FwdPlaneA
         const rsrc_t yb = make_rsrc((T*)p.y + pc);
 #pragma unroll
         for (int k = 0; k < NCH; ++k)
-            if (vq[k]) st_b128(yb, flat + k * 1024, chunk_pack<T>(y[k]));
+            if (vq[k]) st_b128<CP_STREAM>(yb, flat + k * 1024, chunk_pack<T>(y[k]));
     }
 }
 

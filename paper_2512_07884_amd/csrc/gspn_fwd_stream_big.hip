@@ -189,7 +189,7 @@ struct HStream2 {
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             st_buf<16>(yb, voff[r], chunk_col(c) * (int)sizeof(T), by[r]);
-            if constexpr (SAVE) st_buf<16>(hb, voff[r], chunk_col(c) * (int)sizeof(T), bx[r]);
+            if constexpr (SAVE) st_buf<16, CP_STREAM>(hb, voff[r], chunk_col(c) * (int)sizeof(T), bx[r]);
         }
     }
 

@@ -133,7 +133,7 @@ struct VStream {
                 pack<T, V>(yv, o);
                 st_buf<NB>(yb, voff, row_off(t), o);
                 pack<T, V>(h, o);
-                st_buf<NB>(hb, voff, row_off(t), o);
+                st_buf<NB, CP_STREAM>(hb, voff, row_off(t), o);
                 issue(slot[k], t + PF);
                 return;
             }
@@ -319,7 +319,7 @@ struct HStream {
             lds_barrier();
         }
         st_buf<NB>(yb, voff, chunk_col(c) * (int)sizeof(T), by);
-        if constexpr (SAVE) st_buf<NB>(hb, voff, chunk_col(c) * (int)sizeof(T), bx);
+        if constexpr (SAVE) st_buf<NB, CP_STREAM>(hb, voff, chunk_col(c) * (int)sizeof(T), bx);
     }
 
     template <bool RMW>

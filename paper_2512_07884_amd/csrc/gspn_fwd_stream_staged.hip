@@ -208,7 +208,7 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
         for (int i = 0; i < 8; ++i) st_b128(yb, voff + (uint32_t)(col0 * 2 + i * istep), wr_b[8 * SPITCH * i]);
         if constexpr (SAVE) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) st_b128<BWD ? 0 : CP_STREAM>(hb, voff + (uint32_t)(col0 * 2 + i * istep), wr_a[8 * SPITCH * i]);
+            for (int i = 0; i < 8; ++i) st_b128<CP_STREAM>(hb, voff + (uint32_t)(col0 * 2 + i * istep), wr_a[8 * SPITCH * i]);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -373,7 +373,7 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
         for (int i = 0; i < 8; ++i) st_b128(yb, at + (uint32_t)(i * istep), wr_b[8 * SPITCH * i]);
         if constexpr (SAVE) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) st_b128<BWD ? 0 : CP_STREAM>(hb, at + (uint32_t)(i * istep), wr_a[8 * SPITCH * i]);
+            for (int i = 0; i < 8; ++i) st_b128<CP_STREAM>(hb, at + (uint32_t)(i * istep), wr_a[8 * SPITCH * i]);
         }
         __builtin_amdgcn_sched_barrier(0);
     };

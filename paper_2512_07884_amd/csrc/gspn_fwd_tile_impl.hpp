@@ -154,7 +154,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
             tp += tstep;
             uint32_t hr[NR];
             pack<T, V>(h, hr);
-            st_buf<NB>(hb, voff, so_cur, hr);
+            st_buf<NB, CP_STREAM>(hb, voff, so_cur, hr);
             so_cur += sstep;
             return;
         }
@@ -184,7 +184,7 @@ __device__ __forceinline__ void vertical_pass(const TileArgs& a, float* tile, in
         if constexpr (SAVE) {
             uint32_t hr[NR];
             pack<T, V>(h, hr);
-            st_buf<NB>(hb, voff, so_cur, hr);
+            st_buf<NB, CP_STREAM>(hb, voff, so_cur, hr);
             so_cur += sstep;
         }
     };
@@ -345,7 +345,7 @@ struct HorizontalPass {
             for (int v = 0; v < V; ++v) {
                 uint32_t r[NR];
                 pack<T, CS>(hs[v], r);
-                st_buf<NB>(hb, voff, col0 * (int)sizeof(T) + v * row_bytes, r);
+                st_buf<NB, CP_STREAM>(hb, voff, col0 * (int)sizeof(T) + v * row_bytes, r);
             }
         }
     }
@@ -507,7 +507,7 @@ struct HorizontalSplitPass {
         if constexpr (SAVE) {
             uint32_t r[NR];
             pack<T, CS>(hs, r);
-            st_buf<NB>(hb, voff, col0 * (int)sizeof(T), r);
+            st_buf<NB, CP_STREAM>(hb, voff, col0 * (int)sizeof(T), r);
         }
     }
 

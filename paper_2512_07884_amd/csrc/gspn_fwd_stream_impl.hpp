@@ -43,8 +43,10 @@ struct VStream {
     static_assert(!BWD || SAVE, "the reverse sweep saves its state");
     static constexpr int NB = V * (int)sizeof(T);
     static constexpr int NR = NB / 4;
-    // x, lam, u are read once by the launch; with up to 16 bytes per lane a request covers whole lines, each once
-    static constexpr int CP_OWN = NB <= 16 ? CP_STREAM : 0;
+    // more than 16 bytes per lane: as runs of 16 bytes, 1 KB apart, so that every request covers whole lines, each once
+    static constexpr int RUNS = NB > 16 ? NB / 16 : 1;
+    // x, lam, u are read once by the launch
+    static constexpr int CP_OWN = CP_STREAM;
     struct Line { uint32_t x[NR], l[NR], u[NR], w0[NR], w1[NR], w2[NR], y[NR]; };
     rsrc_t xb, lb, ub, w0b, w1b, w2b, yb, hb;
     uint32_t voff;
@@ -69,7 +71,7 @@ struct VStream {
         const size_t plane_bytes = (size_t)HW * sizeof(T);
         const char* wbase = (const char*)p.w + (slot_w + ((size_t)b * p.G + g) * 3 * HW) * sizeof(T);
         row_bytes = W * (int)sizeof(T);
-        voff = (uint32_t)(lane * NB);
+        voff = (uint32_t)(lane * (RUNS > 1 ? 16 : NB));
         first = lane == 0; last = lane == 63;
         xb = make_rsrc((const char*)p.x + plane0 * sizeof(T));
         lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * sizeof(T));
@@ -86,6 +88,20 @@ struct VStream {
     }
 
     __device__ __forceinline__ int row_off(int t) const { return (REV ? H - 1 - t : t) * row_bytes; }
+    template <int CP = 0> __device__ __forceinline__ void ld_line(rsrc_t rs, int so, uint32_t* r) const {
+        if constexpr (RUNS > 1) ld_runs<NB, CP>(rs, voff, so, r); else ld_buf<NB, CP>(rs, voff, so, r);
+    }
+    template <int CP = 0> __device__ __forceinline__ void st_line(rsrc_t rs, int so, const uint32_t* r) const {
+        if constexpr (RUNS > 1) st_runs<NB, CP>(rs, voff, so, r); else st_buf<NB, CP>(rs, voff, so, r);
+    }
+    __device__ __forceinline__ void update(const float (&av)[V], const float (&w0)[V], const float (&w1)[V], const float (&w2)[V]) {
+        if constexpr (RUNS > 1) line_update_runs<V, RUNS>(h, av, w0, w1, w2, first, last);
+        else line_update<V>(h, av, w0, w1, w2, first, last);
+    }
+    __device__ __forceinline__ void update_transposed(const float (&av)[V]) {
+        if constexpr (RUNS > 1) line_update_transposed_runs<V, RUNS>(h, av, wp0, wp1, wp2, first, last);
+        else line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
+    }
 
     // scan steps [t_begin, t_end); RMW: y already holds the other directions' sum for these rows
     template <bool RMW>
@@ -93,13 +109,13 @@ struct VStream {
         Line slot[PF];
         auto issue = [&](Line& s, int t) {
             const int so = row_off(t < t_end ? t : t_end - 1);    // clamped: redundant but in bounds
-            ld_buf<NB, CP_OWN>(xb, voff, so, s.x);
-            ld_buf<NB, CP_OWN>(lb, voff, so, s.l);
-            ld_buf<NB, CP_OWN>(ub, voff, so, s.u);
-            ld_buf<NB>(w0b, voff, so, s.w0);
-            ld_buf<NB>(w1b, voff, so, s.w1);
-            ld_buf<NB>(w2b, voff, so, s.w2);
-            if constexpr (RMW) ld_buf<NB>(yb, voff, so, s.y);
+            ld_line<CP_OWN>(xb, so, s.x);
+            ld_line<CP_OWN>(lb, so, s.l);
+            ld_line<CP_OWN>(ub, so, s.u);
+            ld_line(w0b, so, s.w0);
+            ld_line(w1b, so, s.w1);
+            ld_line(w2b, so, s.w2);
+            if constexpr (RMW) ld_line(yb, so, s.y);
         };
         if (t_begin >= t_end) return;
         // line after line, as the loop below requests them: the compiler would otherwise group the requests by tensor,
@@ -117,7 +133,7 @@ struct VStream {
                 if constexpr (LOCAL) starts = bwalk.start(t == H - 1);
 #pragma unroll
                 for (int v = 0; v < V; ++v) av[v] = elem<T>(cur.l, v) * elem<T>(cur.x, v);
-                line_update_transposed<V>(h, av, wp0, wp1, wp2, first, last);
+                update_transposed(av);
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     float c0 = elem<T>(cur.w0, v), c1 = elem<T>(cur.w1, v), c2 = elem<T>(cur.w2, v);
@@ -131,9 +147,9 @@ struct VStream {
                 }
                 uint32_t o[NR];
                 pack<T, V>(yv, o);
-                st_buf<NB>(yb, voff, row_off(t), o);
+                st_line(yb, row_off(t), o);
                 pack<T, V>(h, o);
-                st_buf<NB, CP_STREAM>(hb, voff, row_off(t), o);
+                st_line<CP_STREAM>(hb, row_off(t), o);
                 issue(slot[k], t + PF);
                 return;
             }
@@ -149,7 +165,7 @@ struct VStream {
                 if (LOCAL || k == 0) { w0[v] = start ? 0.f : w0[v]; w1[v] = start ? 0.f : w1[v]; w2[v] = start ? 0.f : w2[v]; }
                 if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
             }
-            line_update<V>(h, av, w0, w1, w2, first, last);
+            update(av, w0, w1, w2);
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 yv[v] = elem<T>(cur.u, v) * h[v];
@@ -157,10 +173,10 @@ struct VStream {
             }
             uint32_t o[NR];
             pack<T, V>(yv, o);
-            st_buf<NB>(yb, voff, row_off(t), o);
+            st_line(yb, row_off(t), o);
             if constexpr (SAVE) {
                 pack<T, V>(h, o);
-                st_buf<NB, CP_STREAM>(hb, voff, row_off(t), o);      // h_save: nothing in this call reads it
+                st_line<CP_STREAM>(hb, row_off(t), o);      // h_save: nothing in this call reads it
             }
             issue(slot[k], t + PF);
         };

@@ -163,4 +163,87 @@ __device__ __forceinline__ void line_update_transposed(float (&h)[V], const floa
     for (int v = 0; v < V; ++v) h[v] = hn[v];
 }
 
+// ---- a line whose lane holds RUNS separate runs of V / RUNS adjacent positions, run i of lane l at positions
+// (i * 64 + l) * V / RUNS ..: every 16-byte request of the wave then covers 1 KB of whole lines, each line once, where V
+// adjacent positions per lane of more than 16 bytes make every request touch twice or four times as many lines in part.
+// Between the runs the neighbour of lane 0 / lane 63 is the end of the run before / after, held by lane 63 / lane 0.
+template <int NB, int CP = 0> __device__ __forceinline__ void ld_runs(rsrc_t rs, uint32_t voff, int soff, uint32_t* r) {
+    static_assert(NB % 16 == 0, "runs of 16 bytes");
+    soff = __builtin_amdgcn_readfirstlane(soff);
+#pragma unroll
+    for (int i = 0; i < NB / 16; ++i) {
+        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 1024 * i, soff, CP);
+        r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+    }
+}
+template <int NB, int CP = 0> __device__ __forceinline__ void st_runs(rsrc_t rs, uint32_t voff, int soff, const uint32_t* r) {
+    static_assert(NB % 16 == 0, "runs of 16 bytes");
+    const uint32_t vo = voff + (uint32_t)soff;
+#pragma unroll
+    for (int i = 0; i < NB / 16; ++i) {
+        u32x4 v = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
+        st_b128<CP>(rs, vo + 1024 * i, v);
+    }
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {      // lane: compile-time constant
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+// what the positions at the ends of the runs see beside them: lin[i] left of run i, rin[i] right of it; `left_of` /
+// `right_of`: the values the neighbours would read from this lane's run ends
+template <int RUNS>
+__device__ __forceinline__ void run_neighbours(const float (&ends_hi)[RUNS], const float (&ends_lo)[RUNS], bool first, bool last,
+                                               float (&lin)[RUNS], float (&rin)[RUNS]) {
+#pragma unroll
+    for (int i = 0; i < RUNS; ++i) { lin[i] = from_lane_below(ends_hi[i]); rin[i] = from_lane_above(ends_lo[i]); }
+#pragma unroll
+    for (int i = RUNS - 1; i > 0; --i) { const float s = lane_value(ends_hi[i - 1], 63); lin[i] = first ? s : lin[i]; }
+#pragma unroll
+    for (int i = 0; i < RUNS - 1; ++i) { const float s = lane_value(ends_lo[i + 1], 0); rin[i] = last ? s : rin[i]; }
+    lin[0] = first ? 0.f : lin[0];
+    rin[RUNS - 1] = last ? 0.f : rin[RUNS - 1];
+}
+template <int V, int RUNS>
+__device__ __forceinline__ void line_update_runs(float (&h)[V], const float (&a)[V], const float (&w0)[V],
+                                                 const float (&w1)[V], const float (&w2)[V], bool first, bool last) {
+    constexpr int E = V / RUNS;
+    float hi[RUNS], lo[RUNS], lin[RUNS], rin[RUNS];
+#pragma unroll
+    for (int i = 0; i < RUNS; ++i) { hi[i] = h[i * E + E - 1]; lo[i] = h[i * E]; }
+    run_neighbours<RUNS>(hi, lo, first, last, lin, rin);
+    const float wl = first ? 0.f : w0[0];
+    const float wr = last ? 0.f : w2[V - 1];
+    float hn[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float l = v % E == 0 ? lin[v / E] : h[v - 1];
+        const float r = v % E == E - 1 ? rin[v / E] : h[v + 1];
+        const float c0 = v == 0 ? wl : w0[v];
+        const float c2 = v == V - 1 ? wr : w2[v];
+        hn[v] = fmaf(c0, l, fmaf(w1[v], h[v], fmaf(c2, r, a[v])));
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) h[v] = hn[v];
+}
+template <int V, int RUNS>
+__device__ __forceinline__ void line_update_transposed_runs(float (&h)[V], const float (&a)[V], const float (&wp0)[V],
+                                                            const float (&wp1)[V], const float (&wp2)[V], bool first, bool last) {
+    constexpr int E = V / RUNS;
+    float q0[V], q2[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) { q0[v] = wp0[v] * h[v]; q2[v] = wp2[v] * h[v]; }
+    float hi[RUNS], lo[RUNS], lin[RUNS], rin[RUNS];
+#pragma unroll
+    for (int i = 0; i < RUNS; ++i) { hi[i] = q2[i * E + E - 1]; lo[i] = q0[i * E]; }
+    run_neighbours<RUNS>(hi, lo, first, last, lin, rin);
+    float hn[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float l = v % E == 0 ? lin[v / E] : q2[v - 1];
+        const float r = v % E == E - 1 ? rin[v / E] : q0[v + 1];
+        hn[v] = fmaf(wp1[v], h[v], a[v]) + (l + r);
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) h[v] = hn[v];
+}
+
 }  // namespace gspn

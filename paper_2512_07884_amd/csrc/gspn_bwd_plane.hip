@@ -132,7 +132,11 @@ bwd_plane_kernel(BwdPlaneArgs a) {
         chunk_unpack<T, E>(__builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, 0), v);
     };
     auto stg = [&](rsrc_t rs, uint32_t vo, int so, const float (&v)[E]) {
-        st_b128(rs, vo + (uint32_t)so, chunk_pack<T, E>(v));     // whole offset in the vector offset (see st_b128)
+        st_b128<CP_STREAM>(rs, vo + (uint32_t)so, chunk_pack<T, E>(v));     // whole offset in the vector offset (see st_b128)
+    };
+    // the planes of a channel's own tensors are read once, the gradients written once: non-temporal (CP_STREAM)
+    auto ldg_own = [&](rsrc_t rs, uint32_t vo, int so, float (&v)[E]) {
+        chunk_unpack<T, E>(__builtin_amdgcn_raw_buffer_load_b128(rs, vo, so, CP_STREAM), v);
     };
     auto zero = [&](float (&v)[E]) {
 #pragma unroll
@@ -143,7 +147,7 @@ bwd_plane_kernel(BwdPlaneArgs a) {
 #pragma unroll
         for (int k = 0; k < NCH; ++k) {
             zero(st[k]);
-            if (vq[k]) ldg(rs, voff, k * 1024, st[k]);
+            if (vq[k]) ldg_own(rs, voff, k * 1024, st[k]);
         }
     };
     auto load_w = [&](const T* base, float (&st)[NCH][E]) {

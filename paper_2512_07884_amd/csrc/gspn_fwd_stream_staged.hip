@@ -523,7 +523,7 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         for (int dsel = 0; dsel < 2; ++dsel) {
             if (threadIdx.x < MAILBOX_FLOATS) mailbox[threadIdx.x] = 0.f;
             __syncthreads();                    // y of the previous phase complete, mailbox cleared
-            if (dsel == 0) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
+            if ((dsel == 0) != BWD) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
             else horizontal_rows2<true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
         }
     } else {
@@ -532,8 +532,8 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         __syncthreads();                        // y of the vertical pair complete, mailbox cleared
         const int nchunks = p.W / CS;
         const int dslot = wave >> 2, part = wave & 3;
-        if (dslot == 0) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, 0, part, lane, nchunks / 2);
-        else horizontal_rows2<true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, 1, part, lane, nchunks / 2);
+        if ((dslot == 0) != BWD) horizontal_rows2<false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
+        else horizontal_rows2<true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
     }
 }
 
@@ -556,12 +556,13 @@ hipError_t launch_staged(const StreamArgs& a, bool reverse, hipStream_t s) {
 template <int V, int PF>
 static hipError_t launch_staged2(const StreamArgs& a, bool reverse, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / 2))), block(512);
-    if (reverse) return hipErrorInvalidValue;
-    const void* k = a.p.hs ? (const void*)fwd_stream_staged2_kernel<V, PF, true, false>
-                           : (const void*)fwd_stream_staged2_kernel<V, PF, false, false>;
+    const void* k = reverse ? (const void*)fwd_stream_staged2_kernel<V, PF, true, true>
+                  : a.p.hs  ? (const void*)fwd_stream_staged2_kernel<V, PF, true, false>
+                            : (const void*)fwd_stream_staged2_kernel<V, PF, false, false>;
     hipError_t e = allow_dynamic_lds(k, LDS_BYTES);
     if (e != hipSuccess) return e;
-    if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged2_kernel<V, PF, true, false>), grid, block, LDS_BYTES, s, a);
+    if (reverse) hipLaunchKernelGGL((fwd_stream_staged2_kernel<V, PF, true, true>), grid, block, LDS_BYTES, s, a);
+    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged2_kernel<V, PF, true, false>), grid, block, LDS_BYTES, s, a);
     else hipLaunchKernelGGL((fwd_stream_staged2_kernel<V, PF, false, false>), grid, block, LDS_BYTES, s, a);
     return hipGetLastError();
 }
@@ -582,9 +583,7 @@ hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s)
     if (!t.ok || !stream_staged_applicable(p, 1) || (reverse && !p.hs)) return hipErrorInvalidValue;
     StreamArgs a;
     a.p = p; a.parts = t.parts; a.nwaves = 8;
-    // (the reverse sweep keeps one channel per workgroup: with the taps of both channels carried along the two-channel
-    // variant no longer fits the registers, and it was measured no faster)
-    if (!reverse && two_channels_ok(p, t)) {
+    if (two_channels_ok(p, t)) {
         if (t.v == 4) return launch_staged2<4, 4>(a, reverse, s);
         if (t.v == 8) return launch_staged2<8, 4>(a, reverse, s);
         return launch_staged2<16, 2>(a, reverse, s);

@@ -84,11 +84,14 @@ def test_stream_kernel_variants_on_maps_of_256_and_512_rows(shape, knob, monkeyp
     check_case(_cfg(shape, 110), save_h=False)
 
 
-@pytest.mark.parametrize("knob", [None, "GSPN_STREAM_NO_STAGED"], ids=["whole-line", "row-per-lane"])
-def test_backward_on_maps_of_512_rows_bf16(knob, monkeypatch):
+# the reverse sweep of the two-pass backward on the same three kernels (two channels per workgroup: eight waves of rows on
+# 512-row maps, both horizontal directions at once on 256-row maps)
+@pytest.mark.parametrize("knob", [None, "GSPN_STREAM_ONE_CHANNEL", "GSPN_STREAM_NO_STAGED"], ids=["two-channel", "one-channel", "row-per-lane"])
+@pytest.mark.parametrize("shape", [(1, 4, 512, 512, 2, "bf16"), (1, 4, 256, 512, 2, "bf16")], ids=lambda s: "x".join(map(str, s)))
+def test_backward_on_maps_of_256_and_512_rows_bf16(shape, knob, monkeypatch):
     if knob:
         monkeypatch.setenv(knob, "1")
-    check_bwd(_cfg((1, 4, 512, 512, 2, "bf16"), 111))
+    check_bwd(_cfg(shape, 111))
 
 
 def test_scaling_shape_1024x1024_on_sampled_slices():

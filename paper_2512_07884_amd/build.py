@@ -28,10 +28,11 @@ SPILL_ALLOWED = {
     # between the 64-step loops (none inside them); parity-tested on the same maps, train512 backward 2.24 -> 2.15 ms
     "fwd_stream_staged2_kernelILi4ELi4ELb1ELb1": 65, "fwd_stream_staged2_kernelILi8ELi4ELb1ELb1": 65,
     "fwd_stream_staged2_kernelILi16ELi2ELb1ELb1": 65,
-    # sixteen-wave horizontal kernel for maps of up to 1024 rows, bf16, 64 B of a row per request at 128 registers per
-    # lane: one value parked per chunk of 32 scan steps (one scratch store and load per chunk, none per step); the
-    # 32 B variant without spills ran 13.7 ms against 10.1 ms on 1024x1024x1152
-    "stream_big_horizontal_kernelItLi32ELb0": 6,
+    # sixteen-wave horizontal kernel for maps of up to 1024 rows (128 registers per lane), with h_save or as the reverse
+    # sweep: loop-invariant addresses parked before the chunk loop and read back once per chunk of 16 / 32 scan steps,
+    # between the step loops (no scratch access inside them)
+    "stream_big_horizontal_kernelItLi32ELb0ELb1": 7, "stream_big_horizontal_kernelItLi32ELb1ELb1": 5,
+    "stream_big_horizontal_kernelIfLi16ELb1ELb1": 5,
     # fp32 maps with rows of 112 bytes on workgroups of more than four waves, without h_save: off every benchmark shape
     # (the plane kernel takes 28x28, the four-wave instantiation 56x56); kept because the shapes must run somewhere
     "fwd_tile_kernelIfLi2ELi1ELi28ELb0ELi8ELb0ELi8ELb0ELb0ELb0": 259, "fwd_tile_kernelIfLi2ELi1ELi28ELb0ELi8ELb0ELi8ELb1ELb0ELb0": 47,

@@ -271,11 +271,14 @@ struct HStream {
 
     __device__ __forceinline__ int chunk_col(int c) const { return (REV ? nchunks - 1 - c : c) * CS; }
 
+    // x, lam, u are read once: where a request covers whole lines (128 B of a row) it carries the non-temporal bit
+    static constexpr int CP_OWN = (GROUPED && NB == 128) ? CP_STREAM : 0;
+    template <int CP = 0>
     __device__ __forceinline__ void ld_chunk(rsrc_t rs, int so, uint32_t (&r)[NR]) const {
         if constexpr (GROUPED) {
 #pragma unroll
             for (int i = 0; i < LPR; ++i) {
-                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff_g, __builtin_amdgcn_readfirstlane(so + i * istep_g), 0);
+                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff_g, __builtin_amdgcn_readfirstlane(so + i * istep_g), CP);
                 r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
             }
         } else {
@@ -283,8 +286,9 @@ struct HStream {
         }
     }
     // GROUPED: instruction i of a chunk alone, into the registers 4i..4i+3
+    template <int CP = 0>
     __device__ __forceinline__ void ld_piece(rsrc_t rs, int so, int i, uint32_t (&r)[NR]) const {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff_g, __builtin_amdgcn_readfirstlane(so + i * istep_g), 0);
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff_g, __builtin_amdgcn_readfirstlane(so + i * istep_g), CP);
         r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
     }
     // GROUPED: the 16 bytes (EPP columns) of a row that scan step k completes are consumed: their registers take an
@@ -298,9 +302,9 @@ struct HStream {
                 const int e = REV ? CS - 1 - k : k;
                 const int q = e / EPP;
                 const int so = chunk_col(c + 1) * (int)sizeof(T);
-                if constexpr (!SAVE) ld_piece(xb, so, q, bx);
-                ld_piece(lb, so, q, bl);
-                ld_piece(ub, so, q, bu);
+                if constexpr (!SAVE) ld_piece<CP_OWN>(xb, so, q, bx);
+                ld_piece<CP_OWN>(lb, so, q, bl);
+                ld_piece<CP_OWN>(ub, so, q, bu);
                 ld_piece(w0b, so, q, b0);
                 ld_piece(w1b, so, q, b1);
                 ld_piece(w2b, so, q, b2);
@@ -334,9 +338,9 @@ struct HStream {
     template <bool RMW>
     __device__ __forceinline__ void issue(int c) {
         const int so = chunk_col(c) * (int)sizeof(T);
-        ld_chunk(xb, so, bx);
-        ld_chunk(lb, so, bl);
-        ld_chunk(ub, so, bu);
+        ld_chunk<CP_OWN>(xb, so, bx);
+        ld_chunk<CP_OWN>(lb, so, bl);
+        ld_chunk<CP_OWN>(ub, so, bu);
         ld_chunk(w0b, so, b0);
         ld_chunk(w1b, so, b1);
         ld_chunk(w2b, so, b2);
@@ -462,7 +466,7 @@ struct HStream {
                 // the other tensors of the next chunk were requested as this one was consumed
                 if (c + 1 < nchunks) {
                     const int so = chunk_col(c + 1) * (int)sizeof(T);
-                    if constexpr (SAVE) ld_chunk(xb, so, bx);
+                    if constexpr (SAVE) ld_chunk<CP_OWN>(xb, so, bx);
                     if constexpr (RMW) ld_chunk(yb, so, by);
                 }
             } else {

@@ -51,7 +51,7 @@ constexpr int BIG_WAVES = 16;
 template <typename T, int CS, bool BWD, bool SAVE>
 __global__ void __launch_bounds__(64 * BIG_WAVES) stream_big_horizontal_kernel(StreamArgs a, int wrote_in) {
     __shared__ float mailbox[BIG_WAVES * 4];
-    using HS = HStream<T, CS, false, false, false, BWD, SAVE, true>;
+    using HS = HStream<T, CS, false, false, false, BWD, SAVE>;
     __shared__ __attribute__((aligned(16))) char stage[BIG_WAVES * HS::STAGE_BYTES];
     const FwdParams& p = a.p;
     const int W = p.W;
@@ -66,11 +66,11 @@ __global__ void __launch_bounds__(64 * BIG_WAVES) stream_big_horizontal_kernel(S
         __syncthreads();                        // y of the previous direction visible, mailbox cleared
         if (wave < a.parts) {
             if ((dsel == 0) != BWD) {                    // columns walked from the left
-                HStream<T, CS, false, false, false, BWD, SAVE, true> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, false, false, false, BWD, SAVE> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 hs.use_staging(stage + wave * HS::STAGE_BYTES, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             } else {
-                HStream<T, CS, true, false, false, BWD, SAVE, true> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, true, false, false, BWD, SAVE> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 hs.use_staging(stage + wave * HS::STAGE_BYTES, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             }

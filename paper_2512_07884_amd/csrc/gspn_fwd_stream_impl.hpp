@@ -197,16 +197,19 @@ struct VStream {
 // ---------------------------------------------------------------------------
 // horizontal direction, the rows of the image split over `parts` waves, one row per lane
 // ---------------------------------------------------------------------------
-// GROUPED: a chunk is requested so that NB / 16 neighbouring lanes share an image row (an instruction then touches 16 or 8
-// lines instead of 64: the vector cache looks a line up once per lane group, and that rate is what bounds the row-per-lane
-// form) and turned into the row-per-lane order through an LDS block of the wave's own (64 rows of NB + 16 bytes); y and
-// the saved states leave the same way.
-template <typename T, int CS, bool REV, bool LOCAL, bool LOGITS, bool BWD = false, bool SAVE = BWD, bool GROUPED = false>
+// A chunk (CS scan steps: NB = 64 or 128 bytes of every row) is requested so that NB / 16 neighbouring lanes share an image
+// row -- an instruction then touches 16 or 8 lines instead of the 64 it touches when every lane asks for its own row; the
+// vector cache looks a line up once per lane group, and that rate bounded the row-per-lane requests -- and turned into
+// the row-per-lane order through an LDS block of the wave's own (64 rows of NB + 16 bytes).  The chunk of y stays in that
+// block while the chunk is worked on, so that no register holds it, and the registers of the other tensors take the next
+// chunk's requests as their columns are consumed (128 registers per lane are enough for 64 B of a row per tensor).  y and
+// the saved states leave through the block, in request order.
+template <typename T, int CS, bool REV, bool LOCAL, bool LOGITS, bool BWD = false, bool SAVE = BWD>
 struct HStream {
     static_assert(!BWD || SAVE, "the reverse sweep saves its state");
     static constexpr int NB = CS * (int)sizeof(T);
     static constexpr int NR = NB / 4;
-    static constexpr int LPR = NB / 16;          // GROUPED: lanes per row, = instructions per chunk of a tensor
+    static constexpr int LPR = NB / 16;          // lanes per row, = instructions per chunk of a tensor
     static constexpr int RPI = 64 / LPR;         // rows per instruction
     static constexpr int PITCHU = LPR + 1;       // 16-byte units between two rows of the staging block
     static constexpr int STAGE_BYTES = 64 * PITCHU * 16;
@@ -217,7 +220,6 @@ struct HStream {
     rsrc_t xb, lb, ub, w0b, w1b, w2b, yb, hb;
     float wp0, wp1, wp2;   // BWD: taps of the column swept before
     StretchWalkBack bwalk; // BWD, GSPN-local
-    uint32_t voff;
     int nchunks;
     float* mb_out;
     const float* mb_up;
@@ -230,7 +232,6 @@ struct HStream {
     __device__ __forceinline__ void init(const FwdParams& p, float* mailbox, int parts, int b, int c, int part, int lane) {
         constexpr int d = (REV != BWD) ? 3 : 2;
         const int H = p.H, W = p.W, HW = H * W;
-        const int row = part * 64 + lane;
         const int g = c / p.cpg;
         top_lane = lane == 0; bot_lane = lane == 63;
         edge = top_lane || bot_lane;
@@ -242,7 +243,6 @@ struct HStream {
         const size_t plane0 = ((size_t)b * p.C + c) * HW;
         const size_t plane_bytes = (size_t)HW * sizeof(T);
         const char* wbase = (const char*)p.w + (slot_w + ((size_t)b * p.G + g) * 3 * HW) * sizeof(T);
-        voff = (uint32_t)(row * W * (int)sizeof(T));
         xb = make_rsrc((const char*)p.x + plane0 * sizeof(T));
         lb = make_rsrc((const char*)p.lam + (slot_c + plane0) * sizeof(T));
         ub = make_rsrc((const char*)p.u + (slot_c + plane0) * sizeof(T));
@@ -258,12 +258,10 @@ struct HStream {
         h = 0.f;
         if constexpr (LOCAL && !BWD) walk.init(W, REV, p.kchunk);
         if constexpr (LOCAL && BWD) bwalk.init(W, d & 1, p.kchunk);
-        if constexpr (GROUPED) {
-            voff_g = (uint32_t)(((part * 64 + lane / LPR) * W) * (int)sizeof(T) + 16 * (lane % LPR));
-            istep_g = RPI * W * (int)sizeof(T);
-        }
+        voff_g = (uint32_t)(((part * 64 + lane / LPR) * W) * (int)sizeof(T) + 16 * (lane % LPR));
+        istep_g = RPI * W * (int)sizeof(T);
     }
-    // GROUPED: `stage` = the wave's own block of STAGE_BYTES
+    // `stage` = the wave's own block of STAGE_BYTES
     __device__ __forceinline__ void use_staging(char* stage, int lane) {
         g_wr = (u32x4*)stage + PITCHU * (lane / LPR) + (lane % LPR);
         g_rd = (u32x4*)stage + PITCHU * lane;
@@ -272,44 +270,38 @@ struct HStream {
     __device__ __forceinline__ int chunk_col(int c) const { return (REV ? nchunks - 1 - c : c) * CS; }
 
     // x, lam, u are read once: where a request covers whole lines (128 B of a row) it carries the non-temporal bit
-    static constexpr int CP_OWN = (GROUPED && NB == 128) ? CP_STREAM : 0;
+    static constexpr int CP_OWN = NB == 128 ? CP_STREAM : 0;
     template <int CP = 0>
     __device__ __forceinline__ void ld_chunk(rsrc_t rs, int so, uint32_t (&r)[NR]) const {
-        if constexpr (GROUPED) {
 #pragma unroll
-            for (int i = 0; i < LPR; ++i) {
-                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff_g, __builtin_amdgcn_readfirstlane(so + i * istep_g), CP);
-                r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
-            }
-        } else {
-            ld_buf<NB>(rs, voff, so, r);
+        for (int i = 0; i < LPR; ++i) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff_g, __builtin_amdgcn_readfirstlane(so + i * istep_g), CP);
+            r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
         }
     }
-    // GROUPED: instruction i of a chunk alone, into the registers 4i..4i+3
+    // instruction i of a chunk alone, into the registers 4i..4i+3
     template <int CP = 0>
     __device__ __forceinline__ void ld_piece(rsrc_t rs, int so, int i, uint32_t (&r)[NR]) const {
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff_g, __builtin_amdgcn_readfirstlane(so + i * istep_g), CP);
         r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
     }
-    // GROUPED: the 16 bytes (EPP columns) of a row that scan step k completes are consumed: their registers take an
+    // The 16 bytes (EPP columns) of a row that scan step k completes are consumed: their registers take an
     // instruction of the next chunk, so that it arrives while this one is worked on.  Not y, whose registers hold the
     // chunk's output until it is stored, nor -- with SAVE -- x, whose registers hold the states.
     static constexpr int EPP = 16 / (int)sizeof(T);
     __device__ __forceinline__ void refill(int c, int k) {
-        if constexpr (GROUPED) {
-            if ((k % EPP) == EPP - 1 && c + 1 < nchunks) {
-                __builtin_amdgcn_sched_barrier(0);       // not before the step that reads these registers last
-                const int e = REV ? CS - 1 - k : k;
-                const int q = e / EPP;
-                const int so = chunk_col(c + 1) * (int)sizeof(T);
-                if constexpr (!SAVE) ld_piece<CP_OWN>(xb, so, q, bx);
-                ld_piece<CP_OWN>(lb, so, q, bl);
-                ld_piece<CP_OWN>(ub, so, q, bu);
-                ld_piece(w0b, so, q, b0);
-                ld_piece(w1b, so, q, b1);
-                ld_piece(w2b, so, q, b2);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        if ((k % EPP) == EPP - 1 && c + 1 < nchunks) {
+            __builtin_amdgcn_sched_barrier(0);       // not before the step that reads these registers last
+            const int e = REV ? CS - 1 - k : k;
+            const int q = e / EPP;
+            const int so = chunk_col(c + 1) * (int)sizeof(T);
+            if constexpr (!SAVE) ld_piece<CP_OWN>(xb, so, q, bx);
+            ld_piece<CP_OWN>(lb, so, q, bl);
+            ld_piece<CP_OWN>(ub, so, q, bu);
+            ld_piece(w0b, so, q, b0);
+            ld_piece(w1b, so, q, b1);
+            ld_piece(w2b, so, q, b2);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     // request order -> row order, in place
@@ -323,16 +315,12 @@ struct HStream {
     }
     template <int CP = 0>
     __device__ __forceinline__ void st_chunk(rsrc_t rs, int so, const uint32_t (&r)[NR]) const {
-        if constexpr (GROUPED) {
 #pragma unroll
-            for (int q = 0; q < LPR; ++q) { const u32x4 v = {r[4 * q], r[4 * q + 1], r[4 * q + 2], r[4 * q + 3]}; g_rd[q] = v; }
-            __builtin_amdgcn_sched_barrier(0);
+        for (int q = 0; q < LPR; ++q) { const u32x4 v = {r[4 * q], r[4 * q + 1], r[4 * q + 2], r[4 * q + 3]}; g_rd[q] = v; }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < LPR; ++i) st_b128<CP>(rs, voff_g + (uint32_t)(so + i * istep_g), g_wr[RPI * PITCHU * i]);
-            __builtin_amdgcn_sched_barrier(0);
-        } else {
-            st_buf<NB, CP>(rs, voff, so, r);
-        }
+        for (int i = 0; i < LPR; ++i) st_b128<CP>(rs, voff_g + (uint32_t)(so + i * istep_g), g_wr[RPI * PITCHU * i]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     template <bool RMW>
@@ -349,53 +337,35 @@ struct HStream {
 
     template <bool RMW>
     __device__ __forceinline__ void compute(int c) {
-        // GROUPED: the chunk of y stays in the staging block while the chunk is worked on (a lane reads and writes the words of
-        // its own row there), so that no register holds it between the requests: the registers of the other tensors take
-        // the next chunk as they are consumed (refill) and 128 per lane are enough
+        // the six operand tensors into row order; the chunk of y into the staging block, where it stays while the chunk is
+        // worked on (a lane reads and writes the words of its own row there)
         uint32_t* const yrow = (uint32_t*)g_rd;
-        if constexpr (GROUPED) {
-            to_rows(bx); to_rows(bl); to_rows(bu); to_rows(b0); to_rows(b1); to_rows(b2);
-            if constexpr (RMW) {
+        to_rows(bx); to_rows(bl); to_rows(bu); to_rows(b0); to_rows(b1); to_rows(b2);
+        if constexpr (RMW) {
 #pragma unroll
-                for (int i = 0; i < LPR; ++i) { const u32x4 v = {by[4 * i], by[4 * i + 1], by[4 * i + 2], by[4 * i + 3]}; g_wr[RPI * PITCHU * i] = v; }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int i = 0; i < LPR; ++i) { const u32x4 v = {by[4 * i], by[4 * i + 1], by[4 * i + 2], by[4 * i + 3]}; g_wr[RPI * PITCHU * i] = v; }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // otherwise the chunk's outputs replace its y words in place, element by element (no second array)
         float ypair = 0.f;                                   // bf16: first element of the pair being assembled
         float epair = 0.f;                                   // SAVE: the same for the saved state
-        uint32_t yw = 0;                                     // GROUPED, bf16: the word of y the pair adds to
+        uint32_t yw = 0;                                     // bf16: the word of y the pair adds to
         // step k has produced yv = u * h for element e: add it to y and keep the state (SAVE: x of this element is
         // consumed, its word takes h)
         auto emit = [&](int k, int e, float yv) __attribute__((always_inline)) {
-            if constexpr (GROUPED) {
-                if constexpr (sizeof(T) == 4) {
-                    if constexpr (RMW) yv += __uint_as_float(yrow[e]);
-                    yrow[e] = __float_as_uint(yv);
-                    if constexpr (SAVE) bx[e] = __float_as_uint(h);
-                } else {
-                    if ((k & 1) == 0) {
-                        ypair = yv; epair = h;
-                        if constexpr (RMW) yw = yrow[e >> 1];
-                    } else {
-                        float lo = (e & 1) ? ypair : yv, hi = (e & 1) ? yv : ypair;
-                        if constexpr (RMW) { lo += __uint_as_float(yw << 16); hi += __uint_as_float(yw & 0xffff0000u); }
-                        yrow[e >> 1] = pack_bf16x2(lo, hi);
-                        if constexpr (SAVE) bx[e >> 1] = pack_bf16x2((e & 1) ? epair : h, (e & 1) ? h : epair);
-                    }
-                }
+            if constexpr (sizeof(T) == 4) {
+                if constexpr (RMW) yv += __uint_as_float(yrow[e]);
+                yrow[e] = __float_as_uint(yv);
+                if constexpr (SAVE) bx[e] = __float_as_uint(h);
             } else {
-                if constexpr (RMW) yv += elem<T>(by, e);
-                if constexpr (sizeof(T) == 4) {
-                    by[e] = __float_as_uint(yv);
-                    if constexpr (SAVE) bx[e] = __float_as_uint(h);
+                // elements e and e^1 share a word; the pair is complete on every second step
+                if ((k & 1) == 0) {
+                    ypair = yv; epair = h;
+                    if constexpr (RMW) yw = yrow[e >> 1];
                 } else {
-                    // elements e and e^1 share a word; the pair is complete on every second step
-                    if ((k & 1) == 0) { ypair = yv; epair = h; }
-                    else {
-                        by[e >> 1] = pack_bf16x2((e & 1) ? ypair : yv, (e & 1) ? yv : ypair);
-                        if constexpr (SAVE) bx[e >> 1] = pack_bf16x2((e & 1) ? epair : h, (e & 1) ? h : epair);
-                    }
+                    float lo = (e & 1) ? ypair : yv, hi = (e & 1) ? yv : ypair;
+                    if constexpr (RMW) { lo += __uint_as_float(yw << 16); hi += __uint_as_float(yw & 0xffff0000u); }
+                    yrow[e >> 1] = pack_bf16x2(lo, hi);
+                    if constexpr (SAVE) bx[e >> 1] = pack_bf16x2((e & 1) ? epair : h, (e & 1) ? h : epair);
                 }
             }
         };
@@ -444,16 +414,12 @@ struct HStream {
             refill(c, k);
             lds_barrier();
         }
-        if constexpr (GROUPED) {
-            // the chunk of y is in the staging block, in row order: it leaves in request order
-            __builtin_amdgcn_sched_barrier(0);
+        // the chunk of y is in the staging block, in row order: it leaves in request order
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < LPR; ++i)
-                st_b128(yb, voff_g + (uint32_t)(chunk_col(c) * (int)sizeof(T) + i * istep_g), g_wr[RPI * PITCHU * i]);
-            __builtin_amdgcn_sched_barrier(0);
-        } else {
-            st_chunk(yb, chunk_col(c) * (int)sizeof(T), by);
-        }
+        for (int i = 0; i < LPR; ++i)
+            st_b128(yb, voff_g + (uint32_t)(chunk_col(c) * (int)sizeof(T) + i * istep_g), g_wr[RPI * PITCHU * i]);
+        __builtin_amdgcn_sched_barrier(0);
         if constexpr (SAVE) st_chunk<CP_STREAM>(hb, chunk_col(c) * (int)sizeof(T), bx);
     }
 
@@ -462,15 +428,11 @@ struct HStream {
         issue<RMW>(0);
         for (int c = 0; c < nchunks; ++c) {
             compute<RMW>(c);
-            if constexpr (GROUPED) {
-                // the other tensors of the next chunk were requested as this one was consumed
-                if (c + 1 < nchunks) {
-                    const int so = chunk_col(c + 1) * (int)sizeof(T);
-                    if constexpr (SAVE) ld_chunk<CP_OWN>(xb, so, bx);
-                    if constexpr (RMW) ld_chunk(yb, so, by);
-                }
-            } else {
-                issue<RMW>(c + 1 < nchunks ? c + 1 : c);        // clamped: redundant but in bounds at the end
+            // the other tensors of the next chunk were requested as this one was consumed
+            if (c + 1 < nchunks) {
+                const int so = chunk_col(c + 1) * (int)sizeof(T);
+                if constexpr (SAVE) ld_chunk<CP_OWN>(xb, so, bx);
+                if constexpr (RMW) ld_chunk(yb, so, by);
             }
         }
     }
@@ -482,7 +444,7 @@ template <typename T, int V, int CS, int PF, bool LOCAL, bool LOGITS, bool BWD =
 __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
     static_assert(LOCAL || !LOGITS, "logits run on the local instantiations (a global scan is one stretch)");
     __shared__ float mailbox[8 * 4];
-    using HS = HStream<T, CS, false, LOCAL, LOGITS, BWD, SAVE, true>;
+    using HS = HStream<T, CS, false, LOCAL, LOGITS, BWD, SAVE>;
     __shared__ __attribute__((aligned(16))) char stage[8 * HS::STAGE_BYTES];      // horizontal phases: a block per wave
     const FwdParams& p = a.p;
     const int H = p.H, W = p.W;
@@ -528,11 +490,11 @@ __global__ void __launch_bounds__(512) fwd_stream_kernel(StreamArgs a) {
         __syncthreads();                        // y of the previous phase visible, mailbox cleared
         if (wave < a.parts) {
             if ((dsel == 0) != BWD) {                    // columns walked from the left
-                HStream<T, CS, false, LOCAL, LOGITS, BWD, SAVE, true> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, false, LOCAL, LOGITS, BWD, SAVE> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 hs.use_staging(stage + wave * HS::STAGE_BYTES, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             } else {
-                HStream<T, CS, true, LOCAL, LOGITS, BWD, SAVE, true> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
+                HStream<T, CS, true, LOCAL, LOGITS, BWD, SAVE> hs; hs.init(p, mailbox, a.parts, b, c, wave, lane);
                 hs.use_staging(stage + wave * HS::STAGE_BYTES, lane);
                 if (wrote) hs.template run<true>(); else hs.template run<false>();
             }

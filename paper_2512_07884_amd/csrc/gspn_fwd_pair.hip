@@ -22,7 +22,8 @@
 //  * The launch has one workgroup per compute unit (its LDS holds one); a workgroup works through its share of the
 //    channel pairs and has the first requests of the next pair on their way before the current one is finished.
 //  * SAVE stores the hidden states per direction (h_save); BWD is the reverse sweep of the two-pass backward scan on the
-//    same machinery (gy as x, u as lam, lam as u, gx as y, e into hs; see gspn_bwd_twopass.hip).
+//    same machinery (gy as x, u as lam, lam as u, gx as y, e into hs; see gspn_bwd_twopass.hip); LOCAL confines the
+//    propagation to stretches of kchunk lines (GSPN-local, Sec. 3.2).
 #include "gspn_tile_common.hpp"
 #include <utility>
 
@@ -154,7 +155,9 @@ template <bool SAVE, bool BWD> constexpr int early_requests() { return SAVE ? (B
 
 // ... and the chain itself, after chain_request_first() for the same (b, c).
 // ahead() is called once, V_AHEAD bands before the end (the wave's own requests for what comes next).
-template <bool UP, bool SAVE, bool BWD, typename F>
+// LOCAL: GSPN-local (Sec. 3.2): the propagation is confined to stretches of p.kchunk scan lines; a line that starts a
+// stretch takes nothing from the line before it (forward) and hands nothing on to the line swept next (reverse sweep)
+template <bool UP, bool SAVE, bool BWD, bool LOCAL, typename F>
 __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region, uint32_t* tile, int b, int c, int kc, int lane,
                                                uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
                                                uint32_t (&wr)[2][3][VBAND / 2], F& ahead) {
@@ -167,6 +170,11 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
 
     float h[2] = {0.f, 0.f};
     float wp0[2] = {0.f, 0.f}, wp1[2] = {0.f, 0.f}, wp2[2] = {0.f, 0.f};     // BWD: taps of the row swept before
+    // the chain walks in the scan order of direction UP ? 1 : 0 (forward) or against that of direction UP ? 0 : 1
+    StretchWalk stretch;
+    StretchWalkBack bstretch;
+    if constexpr (LOCAL && !BWD) stretch.init(PH, UP ? 1 : 0, p.kchunk);
+    if constexpr (LOCAL && BWD) bstretch.init(PH, UP ? 0 : 1, p.kchunk);
 
     // one band: `slot` = its place in the own ring, `wslot` = where the weight rows of band s + 1 wait in registers
     auto band = [&](int s, int slot, int wslot, bool more_own, bool more_w) __attribute__((always_inline)) {
@@ -193,17 +201,24 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
             float av[2] = {lo16(lw) * lo16(xw), hi16(lw) * hi16(xw)};
             if constexpr (BWD) {
                 line_update_transposed<2>(h, av, wp0, wp1, wp2, first, last);
+                bool starts = false;
+                if constexpr (LOCAL) starts = bstretch.start(s == VNBANDS - 1 && k == VBAND - 1);
                 // the taps this row hands on to the row swept next; a tap that points outside the line takes nothing,
                 // whatever the tensor holds there
-                wp0[0] = first ? 0.f : c0[0]; wp0[1] = c0[1];
-                wp1[0] = c1[0]; wp1[1] = c1[1];
-                wp2[0] = c2[0]; wp2[1] = last ? 0.f : c2[1];
+                wp0[0] = (first || starts) ? 0.f : c0[0]; wp0[1] = starts ? 0.f : c0[1];
+                wp1[0] = starts ? 0.f : c1[0]; wp1[1] = starts ? 0.f : c1[1];
+                wp2[0] = starts ? 0.f : c2[0]; wp2[1] = (last || starts) ? 0.f : c2[1];
             } else {
-                if (k == 0) {
-                    // scan step 0: its weights are never read (they may hold anything) and the state before it is 0
-                    const bool start = s == 0;
+                if (LOCAL || k == 0) {
+                    // scan step 0 (GSPN-local: the first line of a stretch): its weights are never read (they may hold
+                    // anything) and the state before it is 0
+                    bool start = s == 0 && k == 0;
+                    if constexpr (LOCAL) start = stretch.start();
 #pragma unroll
-                    for (int v = 0; v < 2; ++v) { c0[v] = start ? 0.f : c0[v]; c1[v] = start ? 0.f : c1[v]; c2[v] = start ? 0.f : c2[v]; }
+                    for (int v = 0; v < 2; ++v) {
+                        c0[v] = start ? 0.f : c0[v]; c1[v] = start ? 0.f : c1[v]; c2[v] = start ? 0.f : c2[v];
+                        if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
+                    }
                 }
                 line_update<2>(h, av, c0, c1, c2, first, last);
             }
@@ -302,7 +317,7 @@ struct ChunkIO {
 //    chains (has_next: image nb, channels nc0, nc0 + 1) before the last chunk of this pair's horizontal tasks is worked
 //    on -- otherwise nothing would be on its way to the compute unit from there until the next pair's first rows arrive.
 // xr, lr, ur, wr: the first bands of THIS pair's vertical chain on entry (chain_request_first), of the next pair's on exit.
-template <bool REV, bool SAVE, bool BWD>
+template <bool REV, bool SAVE, bool BWD, bool LOCAL>
 __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, char* region, int b, int c0, int wave, int lane,
                                           bool has_next, int nb, int nc0,
                                           uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
@@ -389,11 +404,16 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
 
     // ---- vertical pair: the wave runs the chain of its channel that walks the rows downwards (direction slot 0) or
     // upwards (slot 1), and requests the first chunk of its horizontal task on the way
-    vertical_chain<UP, SAVE, BWD>(p, region, tiles + kc * TILE_WORDS, b, c0 + kc, kc, lane, xr, lr, ur, wr, prefetch);
+    vertical_chain<UP, SAVE, BWD, LOCAL>(p, region, tiles + kc * TILE_WORDS, b, c0 + kc, kc, lane, xr, lr, ur, wr, prefetch);
 
     // ---- horizontal pair
     float h[2] = {0.f, 0.f};
     float wp0[2] = {0.f, 0.f}, wp1[2] = {0.f, 0.f}, wp2[2] = {0.f, 0.f};     // BWD: taps of the column swept before
+    // the task walks in the scan order of direction REV ? 3 : 2 (forward) or against that of direction REV ? 2 : 3
+    StretchWalk walk;
+    StretchWalkBack bwalk;
+    if constexpr (LOCAL && !BWD) walk.init(PW, REV ? 1 : 0, p.kchunk);
+    if constexpr (LOCAL && BWD) bwalk.init(PW, REV ? 0 : 1, p.kchunk);
     for (int ch = 0; ch < 2; ++ch) {
         const int col0 = (REV ? 1 - ch : ch) * CS;
         // registers from request order to row order
@@ -430,15 +450,21 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
             float c2[2] = {elem<bf16_t>(b20, e), elem<bf16_t>(b21, e)};
             if constexpr (BWD) {
                 line_update_transposed<2>(h, av, wp0, wp1, wp2, first, last);
+                bool starts = false;
+                if constexpr (LOCAL) starts = bwalk.start(ch == 1 && k == CS - 1);
                 // the taps this column hands on to the column swept next; a tap that points outside the line takes nothing
-                wp0[0] = first ? 0.f : c0[0]; wp0[1] = c0[1];
-                wp1[0] = c1[0]; wp1[1] = c1[1];
-                wp2[0] = c2[0]; wp2[1] = last ? 0.f : c2[1];
+                wp0[0] = (first || starts) ? 0.f : c0[0]; wp0[1] = starts ? 0.f : c0[1];
+                wp1[0] = starts ? 0.f : c1[0]; wp1[1] = starts ? 0.f : c1[1];
+                wp2[0] = starts ? 0.f : c2[0]; wp2[1] = (last || starts) ? 0.f : c2[1];
             } else {
-                if (k == 0) {
-                    const bool start = ch == 0;                  // scan step 0: its weights are never read
+                if (LOCAL || k == 0) {
+                    bool start = ch == 0 && k == 0;              // scan step 0: its weights are never read
+                    if constexpr (LOCAL) start = walk.start();   // ... nor those of a stretch's first line
 #pragma unroll
-                    for (int v = 0; v < 2; ++v) { c0[v] = start ? 0.f : c0[v]; c1[v] = start ? 0.f : c1[v]; c2[v] = start ? 0.f : c2[v]; }
+                    for (int v = 0; v < 2; ++v) {
+                        c0[v] = start ? 0.f : c0[v]; c1[v] = start ? 0.f : c1[v]; c2[v] = start ? 0.f : c2[v];
+                        if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
+                    }
                 }
                 line_update<2>(h, av, c0, c1, c2, first, last);
             }
@@ -493,7 +519,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
 
 // The pairs of channels a workgroup works through: items blockIdx.x, blockIdx.x + gridDim.x, ... of B * C/2, dealt so
 // that the workgroups running at any one time hold neighbouring channels of few weight groups per XCD.
-template <bool REV, bool SAVE, bool BWD>
+template <bool REV, bool SAVE, bool BWD, bool LOCAL>
 __device__ __forceinline__ void pair_loop(const FwdParams& p, uint32_t* tiles, char* region, int wave, int lane) {
     constexpr bool UP = REV != BWD;
     const int kc = wave >> 1;
@@ -515,13 +541,13 @@ __device__ __forceinline__ void pair_loop(const FwdParams& p, uint32_t* tiles, c
         const bool has_next = round + 1 < rounds && (round + 2 < rounds || blockIdx.x < total - (round + 1) * gridDim.x);
         int nb = b, nc0 = c0;
         if (has_next) item_of(round + 1, nb, nc0);
-        pair_body<REV, SAVE, BWD>(p, tiles, region, b, c0, wave, lane, has_next, nb, nc0, xr, lr, ur, wr);
+        pair_body<REV, SAVE, BWD, LOCAL>(p, tiles, region, b, c0, wave, lane, has_next, nb, nc0, xr, lr, ur, wr);
         if (!has_next) break;
         b = nb; c0 = nc0;
     }
 }
 
-template <bool SAVE, bool BWD>
+template <bool SAVE, bool BWD, bool LOCAL>
 __global__ void __launch_bounds__(256) fwd_pair_kernel(FwdParams p) {
     extern __shared__ uint32_t lds[];
     uint32_t* tiles = lds;
@@ -530,21 +556,21 @@ __global__ void __launch_bounds__(256) fwd_pair_kernel(FwdParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // wave -> horizontal task (channel = wave / 2, direction slot = wave % 2); the task of direction slot 0 walks the
     // columns from the left in the forward scan and from the right in the reverse sweep
-    if (((wave & 1) == 0) != BWD) pair_loop<false, SAVE, BWD>(p, tiles, region, wave, lane);
-    else pair_loop<true, SAVE, BWD>(p, tiles, region, wave, lane);
+    if (((wave & 1) == 0) != BWD) pair_loop<false, SAVE, BWD, LOCAL>(p, tiles, region, wave, lane);
+    else pair_loop<true, SAVE, BWD, LOCAL>(p, tiles, region, wave, lane);
 }
 
 bool pair_shape_ok(const FwdParams& p, int dtype) {
     if (dtype != 1 || p.H != PH || p.W != PW) return false;
-    if (p.mask != 15u || p.kchunk > 0 || p.logits || p.xt) return false;
+    if (p.mask != 15u || p.logits || p.xt) return false;
     if (p.cpg % 2 || p.C % 2) return false;
     if ((size_t)p.B * (p.C / 2) > 0x7fffffffull) return false;
     return true;
 }
 
-template <bool SAVE, bool BWD>
-hipError_t launch_pair(const FwdParams& p, hipStream_t s) {
-    auto k = fwd_pair_kernel<SAVE, BWD>;
+template <bool SAVE, bool BWD, bool LOCAL>
+hipError_t launch_pair_as(const FwdParams& p, hipStream_t s) {
+    auto k = fwd_pair_kernel<SAVE, BWD, LOCAL>;
     hipError_t e = allow_dynamic_lds((const void*)k, LDS_BYTES);
     if (e != hipSuccess) return e;
     // one workgroup fits a compute unit (LDS): as many workgroups as the chip has compute units, each working through
@@ -552,6 +578,11 @@ hipError_t launch_pair(const FwdParams& p, hipStream_t s) {
     const size_t total = (size_t)p.B * (p.C / 2);
     hipLaunchKernelGGL(k, dim3((unsigned)(total < PERSIST_WGS ? total : PERSIST_WGS)), dim3(256), LDS_BYTES, s, p);
     return hipGetLastError();
+}
+
+template <bool SAVE, bool BWD>
+hipError_t launch_pair(const FwdParams& p, hipStream_t s) {
+    return p.kchunk > 0 ? launch_pair_as<SAVE, BWD, true>(p, s) : launch_pair_as<SAVE, BWD, false>(p, s);
 }
 
 }  // namespace

@@ -110,7 +110,8 @@ def test_kernel_family_chosen_for_local_scans(lib, monkeypatch):
     fwd = lambda *a: lib.gspn_fwd_local_plan(*a).decode()
     bwd = lambda *a: lib.gspn_bwd_local_plan(*a).decode()
     assert fwd(64, 96, 56, 56, 8, 14, 15, 1, 0, 0) == "plane" and bwd(32, 192, 28, 28, 4, 7, 15, 0, 0) == "plane"
-    assert fwd(2, 1024, 128, 128, 16, 32, 15, 1, 0, 0) == "tile" and bwd(64, 96, 56, 56, 8, 14, 15, 1, 0) == "twopass"
+    assert fwd(2, 1024, 128, 128, 16, 32, 15, 1, 0, 0) == "pair" and bwd(64, 96, 56, 56, 8, 14, 15, 1, 0) == "twopass"
+    assert fwd(2, 1024, 128, 128, 16, 32, 15, 0, 0, 0) == "tile"
     assert fwd(1, 512, 512, 512, 16, 64, 15, 1, 0, 0) == "stream" and fwd(1, 2, 130, 67, 1, 9, 15, 0, 0, 0) == "generic"
     assert fwd(1, 8, 16, 16, 1, 0, 15, 0, 0, 0) == "invalid" and bwd(1, 8, 16, 16, 1, 0, 15, 0, 0) == "invalid"
     # few planes: the stretches are the work items (Sec. 4.1: the chunk index is part of the grid)

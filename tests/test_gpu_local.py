@@ -107,7 +107,7 @@ def test_local_scans_on_the_plane_kernels(shape, kchunk, monkeypatch):
 @pytest.mark.parametrize("shape,kchunk,plans", [
     ((2, 8, 56, 56, 2, "bf16"), 14, ("plane", "tile")), ((1, 8, 64, 64, 8, "bf16"), 10, ("plane", "tile")),
     ((1, 6, 40, 24, 3, "bf16"), 16, ("plane", "twopass")), ((2, 8, 56, 56, 2, "f32"), 9, ("tile", "tile")),
-    ((1, 4, 128, 128, 2, "bf16"), 32, ("tile", "twopass")), ((1, 4, 128, 128, 4, "bf16"), 5, ("tile", "twopass")),
+    ((1, 4, 128, 128, 2, "bf16"), 32, ("pair", "twopass")), ((1, 4, 128, 128, 4, "bf16"), 5, ("tile", "twopass")),
     ((1, 8, 64, 128, 2, "f32"), 48, ("tile", "tile")), ((1, 24, 16, 40, 2, "f32"), 3, ("plane", "tile")),
     ((2, 8, 40, 32, 8, "f32"), 7, ("plane", "tile")), ((1, 4, 96, 72, 2, "bf16"), 20, ("tile", "twopass")),
     ((1, 4, 33, 70, 2, "f32"), 9, ("generic", "generic")), ((2, 6, 9, 13, 3, "f32"), 4, ("generic", "generic")),
@@ -165,7 +165,7 @@ def test_local_scans_with_one_workgroup_per_stretch(shape, kchunk):
 def test_per_stretch_kernels_are_for_calls_with_few_planes(monkeypatch):
     import paper_2512_07884_amd as G
     assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 32, 15, 0, 0, False) == "chunk"
-    assert G.gspn_fwd_local_plan(2, 1024, 128, 128, 16, 32, 15, 1, 0, False) == "tile"      # planes fill the chip
+    assert G.gspn_fwd_local_plan(2, 1024, 128, 128, 16, 32, 15, 1, 0, False) == "pair"      # planes fill the chip
     assert G.gspn_fwd_local_plan(1, 128, 128, 128, 4, 32, 15, 0, 0, False) == "chunk"       # 512 stretches per launch
     assert G.gspn_fwd_local_plan(1, 256, 128, 128, 4, 32, 15, 0, 0, False) == "tile"        # 1024: more than two per CU
     assert G.gspn_fwd_local_plan(1, 32, 128, 128, 4, 24, 15, 0, 0, False) == "tile"         # kchunk does not divide
@@ -278,3 +278,20 @@ def test_local_training_stage_at_full_size_on_sampled_slices():
         assert rel_inf_err(out["gw"][:, b:b + 1, g:g + 1], gw) <= TOL["f32"]
         assert rel_inf_err(out["glam"][:, b:b + 1, cs], glam) <= TOL["f32"]
         assert rel_inf_err(out["gu"][:, b:b + 1, cs], gu) <= TOL["f32"]
+
+
+# the two-channel kernel of the 128x128 bf16 maps (even channel groups, all four directions) with stretches: lengths that
+# divide the map and that do not, a single line per stretch, a stretch longer than the map; several pairs per workgroup
+@pytest.mark.parametrize("shape,kchunk", [((1, 4, 128, 128, 2, "bf16"), 1), ((1, 4, 128, 128, 2, "bf16"), 7),
+                                          ((2, 8, 128, 128, 4, "bf16"), 32), ((1, 4, 128, 128, 1, "bf16"), 50),
+                                          ((1, 2, 128, 128, 1, "bf16"), 128), ((1, 2, 128, 128, 1, "bf16"), 300),
+                                          ((1, 600, 128, 128, 4, "bf16"), 24)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_local_scans_on_the_two_channel_kernel(shape, kchunk, monkeypatch):
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FWD_NO_CHUNK", "1")           # (the per-stretch kernels take few planes first)
+    B, C, H, W, Gr, dtype = shape
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, 1, 0, True) == "pair"
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, 1, 0, False) == "pair"
+    assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, 1, 0) == "twopass"
+    check_local(shape, kchunk, poison_starts=True)

@@ -220,8 +220,8 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 
 /* Name of the kernel family the forward / backward call would dispatch to for
  * these arguments: "plane" (small maps, whole planes through LDS), "pair" (128x128 bf16 maps
- * with an even number of channels per weight group, all four directions, the global scan or GSPN-local with
- * normalised weights: two channels of a group per workgroup, the merged output accumulated on chip in storage precision, i.e. rounded
+ * with an even number of channels per weight group, all four directions, the global scan or GSPN-local, normalised
+ * weights or logits: two channels of a group per workgroup, the merged output accumulated on chip in storage precision, i.e. rounded
  * after each of the four additions), "tile" (maps whose merged output fits in LDS), "stream"
  * (larger maps with rows and columns in multiples of 64: up to 512 rows and lines of 256, 512 or 1024 positions in
  * one launch; the global scan also on up to 2048 rows (beyond 1024: in multiples of 128) and lines of 256 to 2048

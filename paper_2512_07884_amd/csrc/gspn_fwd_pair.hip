@@ -23,7 +23,7 @@
 //    channel pairs and has the first requests of the next pair on their way before the current one is finished.
 //  * SAVE stores the hidden states per direction (h_save); BWD is the reverse sweep of the two-pass backward scan on the
 //    same machinery (gy as x, u as lam, lam as u, gx as y, e into hs; see gspn_bwd_twopass.hip); LOCAL confines the
-//    propagation to stretches of kchunk lines (GSPN-local, Sec. 3.2).
+//    propagation to stretches of kchunk lines (GSPN-local, Sec. 3.2); LOGITS takes the weights as raw logits.
 #include "gspn_tile_common.hpp"
 #include <utility>
 
@@ -151,13 +151,16 @@ __device__ __forceinline__ void chain_request_first(const FwdParams& p, int b, i
 }
 // how many of them are made early: all five in the plain forward scan; with h_save / in the reverse sweep the
 // horizontal tasks hold more registers (the states on their way out), and one or two is what fits beside them
-template <bool SAVE, bool BWD> constexpr int early_requests() { return SAVE ? (BWD ? 2 : 1) : 5; }
+// (with the logits normalised on the way in, the forward call with h_save has no register left for even one)
+template <bool SAVE, bool BWD, bool LOGITS = false> constexpr int early_requests() { return SAVE ? (BWD ? 2 : (LOGITS ? 0 : 1)) : 5; }
 
 // ... and the chain itself, after chain_request_first() for the same (b, c).
 // ahead() is called once, V_AHEAD bands before the end (the wave's own requests for what comes next).
 // LOCAL: GSPN-local (Sec. 3.2): the propagation is confined to stretches of p.kchunk scan lines; a line that starts a
-// stretch takes nothing from the line before it (forward) and hands nothing on to the line swept next (reverse sweep)
-template <bool UP, bool SAVE, bool BWD, bool LOCAL, typename F>
+// stretch takes nothing from the line before it (forward) and hands nothing on to the line swept next (reverse sweep).
+// LOGITS: w holds raw logits, normalised as they are read (the three taps of a position through softmax3, a tap that points
+// outside the line left out); on the LOCAL instantiations only, where a global scan is one stretch
+template <bool UP, bool SAVE, bool BWD, bool LOCAL, bool LOGITS, typename F>
 __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region, uint32_t* tile, int b, int c, int kc, int lane,
                                                uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
                                                uint32_t (&wr)[2][3][VBAND / 2], F& ahead) {
@@ -197,6 +200,7 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
         for (int k = 0; k < VBAND; ++k) {
             const int row = chain_row<UP>(s, k);
             float c0[2] = {lo16(t0[k]), hi16(t0[k])}, c1[2] = {lo16(t1[k]), hi16(t1[k])}, c2[2] = {lo16(t2[k]), hi16(t2[k])};
+            if constexpr (LOGITS) { softmax3(c0[0], c1[0], c2[0], first, false); softmax3(c0[1], c1[1], c2[1], false, last); }
             const uint32_t xw = xr[slot][k], lw = lr[slot][k], uw = ur[slot][k];
             float av[2] = {lo16(lw) * lo16(xw), hi16(lw) * hi16(xw)};
             if constexpr (BWD) {
@@ -233,7 +237,7 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
         lds_barrier();
     };
 
-    chain_request_first<UP, SAVE, BWD, early_requests<SAVE, BWD>(), 5>(p, b, c, kc, lane, xr, lr, ur, wr);
+    chain_request_first<UP, SAVE, BWD, early_requests<SAVE, BWD, LOGITS>(), 5>(p, b, c, kc, lane, xr, lr, ur, wr);
     // the rest of the first requests: band 0 of the weights goes to the ring (it takes the place band "s + 1" has in
     // the loop), its registers take band 2
     drop_w<UP>(region, kc, lane, 0, wr[0]);
@@ -317,7 +321,7 @@ struct ChunkIO {
 //    chains (has_next: image nb, channels nc0, nc0 + 1) before the last chunk of this pair's horizontal tasks is worked
 //    on -- otherwise nothing would be on its way to the compute unit from there until the next pair's first rows arrive.
 // xr, lr, ur, wr: the first bands of THIS pair's vertical chain on entry (chain_request_first), of the next pair's on exit.
-template <bool REV, bool SAVE, bool BWD, bool LOCAL>
+template <bool REV, bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, char* region, int b, int c0, int wave, int lane,
                                           bool has_next, int nb, int nc0,
                                           uint32_t (&xr)[VPF][VBAND], uint32_t (&lr)[VPF][VBAND], uint32_t (&ur)[VPF][VBAND],
@@ -404,7 +408,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
 
     // ---- vertical pair: the wave runs the chain of its channel that walks the rows downwards (direction slot 0) or
     // upwards (slot 1), and requests the first chunk of its horizontal task on the way
-    vertical_chain<UP, SAVE, BWD, LOCAL>(p, region, tiles + kc * TILE_WORDS, b, c0 + kc, kc, lane, xr, lr, ur, wr, prefetch);
+    vertical_chain<UP, SAVE, BWD, LOCAL, LOGITS>(p, region, tiles + kc * TILE_WORDS, b, c0 + kc, kc, lane, xr, lr, ur, wr, prefetch);
 
     // ---- horizontal pair
     float h[2] = {0.f, 0.f};
@@ -434,7 +438,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
         __builtin_amdgcn_sched_barrier(0);
 
         // nothing is left to request for this pair: the next pair's vertical chains start theirs
-        if (ch == 1 && has_next) chain_request_first<UP, SAVE, BWD, 0, early_requests<SAVE, BWD>()>(p, nb, nc0 + kc, kc, lane, xr, lr, ur, wr);
+        if (ch == 1 && has_next) chain_request_first<UP, SAVE, BWD, 0, early_requests<SAVE, BWD, LOGITS>()>(p, nb, nc0 + kc, kc, lane, xr, lr, ur, wr);
 
         float cpair[2] = {0.f, 0.f}, hpair[2] = {0.f, 0.f};    // first element of the pair of columns that share a word
         uint32_t yw[2] = {0, 0};
@@ -448,6 +452,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
             float c0[2] = {elem<bf16_t>(b00, e), elem<bf16_t>(b01, e)};
             float c1[2] = {elem<bf16_t>(b10, e), elem<bf16_t>(b11, e)};
             float c2[2] = {elem<bf16_t>(b20, e), elem<bf16_t>(b21, e)};
+            if constexpr (LOGITS) { softmax3(c0[0], c1[0], c2[0], first, false); softmax3(c0[1], c1[1], c2[1], false, last); }
             if constexpr (BWD) {
                 line_update_transposed<2>(h, av, wp0, wp1, wp2, first, last);
                 bool starts = false;
@@ -519,7 +524,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
 
 // The pairs of channels a workgroup works through: items blockIdx.x, blockIdx.x + gridDim.x, ... of B * C/2, dealt so
 // that the workgroups running at any one time hold neighbouring channels of few weight groups per XCD.
-template <bool REV, bool SAVE, bool BWD, bool LOCAL>
+template <bool REV, bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 __device__ __forceinline__ void pair_loop(const FwdParams& p, uint32_t* tiles, char* region, int wave, int lane) {
     constexpr bool UP = REV != BWD;
     const int kc = wave >> 1;
@@ -535,20 +540,21 @@ __device__ __forceinline__ void pair_loop(const FwdParams& p, uint32_t* tiles, c
     uint32_t xr[VPF][VBAND], lr[VPF][VBAND], ur[VPF][VBAND], wr[2][3][VBAND / 2];
     int b, c0;
     item_of(0, b, c0);
-    chain_request_first<UP, SAVE, BWD, 0, early_requests<SAVE, BWD>()>(p, b, c0 + kc, kc, lane, xr, lr, ur, wr);
+    chain_request_first<UP, SAVE, BWD, 0, early_requests<SAVE, BWD, LOGITS>()>(p, b, c0 + kc, kc, lane, xr, lr, ur, wr);
     for (unsigned round = 0; round < rounds; ++round) {
         // a workgroup beyond the end of a short last round has nothing left
         const bool has_next = round + 1 < rounds && (round + 2 < rounds || blockIdx.x < total - (round + 1) * gridDim.x);
         int nb = b, nc0 = c0;
         if (has_next) item_of(round + 1, nb, nc0);
-        pair_body<REV, SAVE, BWD, LOCAL>(p, tiles, region, b, c0, wave, lane, has_next, nb, nc0, xr, lr, ur, wr);
+        pair_body<REV, SAVE, BWD, LOCAL, LOGITS>(p, tiles, region, b, c0, wave, lane, has_next, nb, nc0, xr, lr, ur, wr);
         if (!has_next) break;
         b = nb; c0 = nc0;
     }
 }
 
-template <bool SAVE, bool BWD, bool LOCAL>
+template <bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 __global__ void __launch_bounds__(256) fwd_pair_kernel(FwdParams p) {
+    static_assert(LOCAL || !LOGITS, "logits run on the local instantiations (a global scan is one stretch)");
     extern __shared__ uint32_t lds[];
     uint32_t* tiles = lds;
     char* region = (char*)(lds + 2 * TILE_WORDS);
@@ -556,21 +562,21 @@ __global__ void __launch_bounds__(256) fwd_pair_kernel(FwdParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // wave -> horizontal task (channel = wave / 2, direction slot = wave % 2); the task of direction slot 0 walks the
     // columns from the left in the forward scan and from the right in the reverse sweep
-    if (((wave & 1) == 0) != BWD) pair_loop<false, SAVE, BWD, LOCAL>(p, tiles, region, wave, lane);
-    else pair_loop<true, SAVE, BWD, LOCAL>(p, tiles, region, wave, lane);
+    if (((wave & 1) == 0) != BWD) pair_loop<false, SAVE, BWD, LOCAL, LOGITS>(p, tiles, region, wave, lane);
+    else pair_loop<true, SAVE, BWD, LOCAL, LOGITS>(p, tiles, region, wave, lane);
 }
 
 bool pair_shape_ok(const FwdParams& p, int dtype) {
     if (dtype != 1 || p.H != PH || p.W != PW) return false;
-    if (p.mask != 15u || p.logits || p.xt) return false;
+    if (p.mask != 15u || p.xt) return false;
     if (p.cpg % 2 || p.C % 2) return false;
     if ((size_t)p.B * (p.C / 2) > 0x7fffffffull) return false;
     return true;
 }
 
-template <bool SAVE, bool BWD, bool LOCAL>
+template <bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 hipError_t launch_pair_as(const FwdParams& p, hipStream_t s) {
-    auto k = fwd_pair_kernel<SAVE, BWD, LOCAL>;
+    auto k = fwd_pair_kernel<SAVE, BWD, LOCAL, LOGITS>;
     hipError_t e = allow_dynamic_lds((const void*)k, LDS_BYTES);
     if (e != hipSuccess) return e;
     // one workgroup fits a compute unit (LDS): as many workgroups as the chip has compute units, each working through
@@ -582,7 +588,8 @@ hipError_t launch_pair_as(const FwdParams& p, hipStream_t s) {
 
 template <bool SAVE, bool BWD>
 hipError_t launch_pair(const FwdParams& p, hipStream_t s) {
-    return p.kchunk > 0 ? launch_pair_as<SAVE, BWD, true>(p, s) : launch_pair_as<SAVE, BWD, false>(p, s);
+    if (p.logits) return launch_pair_as<SAVE, BWD, true, true>(p, s);
+    return p.kchunk > 0 ? launch_pair_as<SAVE, BWD, true, false>(p, s) : launch_pair_as<SAVE, BWD, false, false>(p, s);
 }
 
 }  // namespace

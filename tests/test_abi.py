@@ -93,7 +93,7 @@ def test_logits_calls_check_their_arguments_and_dispatch_on_the_host(lib, monkey
     assert fwd(32, 192, 28, 28, 192, big, 15, 0, 0, 1) == "plane" and bwd(32, 192, 28, 28, 192, big, 15, 0, 0) == "plane"
     assert fwd(32, 192, 28, 28, 4, 7, 15, 0, 0, 1) == "plane" and bwd(32, 192, 28, 28, 4, 7, 15, 0, 0) == "plane"
     assert fwd(64, 96, 56, 56, 8, big, 15, 1, 0, 0) == "plane" and bwd(64, 96, 56, 56, 8, big, 15, 1, 0) == "twopass"
-    assert fwd(2, 1024, 128, 128, 16, big, 15, 1, 0, 0) == "tile" and fwd(1, 512, 512, 512, 16, big, 15, 1, 0, 0) == "stream"
+    assert fwd(2, 1024, 128, 128, 16, big, 15, 1, 0, 0) == "pair" and fwd(2, 1024, 128, 128, 16, big, 15, 0, 0, 0) == "tile" and fwd(1, 512, 512, 512, 16, big, 15, 1, 0, 0) == "stream"
     assert fwd(1, 2, 8, 5000, 1, big, 15, 0, 0, 0) == "invalid" and bwd(1, 2, 8, 8, 1, 0, 15, 0, 0) == "invalid"
 
 

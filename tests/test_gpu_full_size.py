@@ -145,7 +145,7 @@ def test_full_size_diffusion_shape_in_the_other_call_forms(mode):
         assert G.gspn_fwd_local_plan(B, C, H, W, Gr, 32, 15, 1, 0, False) == "pair"
         G.gspn_scan_fwd_local(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, kchunk=32, G=Gr)
     elif mode == "logits":
-        assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, 1 << 14, 15, 1, 0, False) == "tile"
+        assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, 1 << 14, 15, 1, 0, False) == "pair"
         G.gspn_scan_fwd_logits(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, G=Gr)
     else:
         assert G.gspn_fwd_transposed_plan(B, C, H, W, Gr, 15, 1, 0) == "tile"

@@ -158,7 +158,8 @@ def test_logits_direction_masks(mask):
 # the tile kernels (forward: rows split over waves, 64 B and 16 B bursts; backward: 4 and 8 columns per request,
 # shared and per-channel weights) and the stream kernel (forward without h_save)
 @pytest.mark.parametrize("shape,plans", [
-    ((1, 4, 128, 128, 2, "bf16"), ("tile", "twopass")), ((2, 8, 56, 56, 2, "f32"), ("tile", "tile")),
+    ((1, 4, 128, 128, 2, "bf16"), ("pair", "twopass")), ((1, 4, 128, 128, 2, "bf16"), ("tile", "twopass")),
+    ((2, 8, 56, 56, 2, "f32"), ("tile", "tile")),
     ((1, 8, 64, 128, 2, "f32"), ("tile", "tile")), ((1, 4, 96, 72, 2, "bf16"), ("tile", "twopass")),
     ((2, 8, 56, 56, 2, "bf16"), ("plane", "tile")), ((1, 4, 56, 56, 4, "f32"), ("tile", "tile")),
     ((1, 24, 16, 40, 2, "f32"), ("plane", "tile")), ((2, 8, 40, 32, 8, "f32"), ("plane", "tile")),
@@ -167,7 +168,22 @@ def test_logits_direction_masks(mask):
 def test_logits_on_the_tile_kernels(shape, plans, monkeypatch):
     if plans[1] == "tile":
         monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")     # (the two-pass backward takes these maps first)
+    if plans[0] == "tile" and shape[2:4] == (128, 128) and shape[5] == "bf16":
+        monkeypatch.setenv("GSPN_FWD_NO_PAIR", "1")        # (... and the two-channel kernel the 128 x 128 bf16 maps)
     check_logits(shape, fwd_plan=plans[0], bwd_plan=plans[1])
+
+
+# the two-channel kernel of the 128 x 128 bf16 maps normalises the logits as it unpacks them (forward, forward with
+# h_save, and the reverse sweep of the two-pass backward): global and GSPN-local, stretch lengths that divide the map and
+# that do not, an odd number of pairs, and taps that are never read
+@pytest.mark.parametrize("shape,kchunk,mask", [
+    ((1, 4, 128, 128, 2, "bf16"), None, 15), ((2, 12, 128, 128, 3, "bf16"), None, 15), ((1, 8, 128, 128, 1, "bf16"), 32, 15),
+    ((1, 4, 128, 128, 2, "bf16"), 37, 15), ((1, 4, 128, 128, 2, "bf16"), 1, 15), ((2, 6, 128, 128, 1, "bf16"), 16, 15),
+    ((1, 4, 128, 128, 2, "bf16"), 127, 15)],
+    ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_logits_on_the_two_channel_kernel(shape, kchunk, mask, monkeypatch):
+    monkeypatch.setenv("GSPN_FWD_NO_CHUNK", "1")           # (short stretches would go to the chunk-parallel kernel)
+    check_logits(shape, kchunk=kchunk, mask=mask, poison=True, fwd_plan="pair", bwd_plan="twopass")
 
 
 @pytest.mark.parametrize("shape,kchunk", [((2, 8, 56, 56, 2, "f32"), 9), ((1, 4, 128, 128, 2, "bf16"), 32),

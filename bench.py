@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused 4-direction GSPN scan on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kchunk K] [--logits] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kchunk K] [--logits] [--storage f32|bf16|f16] [--all]
 
 A step is one pass of the whole hot path over one batch of synthetic input:
 one ``gspn_scan_fwd`` call covering all four directions (inference workloads),
@@ -33,7 +33,7 @@ TRAINING = ("train28_gc", "train28_g4", "train56", "train128", "train512", "occ1
 def device_inputs(cfg, seed: int, logits: bool = False):
     """Synthetic inputs with the distributions of workloads.make_slice, drawn on the device."""
     import torch
-    td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[cfg.dtype]
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
     B, C, H, W, G = cfg.B, cfg.C, cfg.H, cfg.W, cfg.G
@@ -152,7 +152,7 @@ def run_workload(cfg, steps: int, warmup: int, kchunk: int = 0, logits: bool = F
 
 def summarise(cfg, r):
     import paper_2512_07884_amd as G
-    dt = 1 if cfg.dtype == "bf16" else 0
+    dt = {"f32": 0, "bf16": 1, "f16": 2}[cfg.dtype]
     training = r["training"]
     kchunk = r.get("kchunk", 0)
     big = 1 << 14                      # a stretch longer than any line: the global scan
@@ -180,7 +180,7 @@ def summarise(cfg, r):
         # the fraction above stays on the algorithmic bytes of the scan; the second copy of x this layout reads is
         # counted in a figure of its own
         d["layout"] = "horizontal directions stored transposed (x read in both layouts: one more plane per pixel*channel)"
-        with_xt = fwd_bytes + cfg.pixel_channels * (2 if cfg.dtype == "bf16" else 4)
+        with_xt = fwd_bytes + cfg.pixel_channels * cfg.elem_bytes
         d["fwd_bytes_incl_second_x"] = with_xt
         d["fwd_frac_of_hbm_peak_incl_second_x"] = with_xt / (r["fwd_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS
     if training:
@@ -400,6 +400,8 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--kchunk", type=int, default=0,
                     help="GSPN-local: confine propagation to stretches of this many lines (0: the global scan)")
+    ap.add_argument("--storage", choices=("f32", "bf16", "f16"), default=None,
+                    help="time the workload in this storage type instead of its own (fp16: the tile, stream and generic kernels)")
     ap.add_argument("--logits", action="store_true",
                     help="weights given as raw logits, normalised inside the call (gspn_scan_*_logits)")
     ap.add_argument("--transposed", action="store_true",
@@ -426,6 +428,9 @@ def main():
         return
     from paper_2512_07884_amd import workloads as WL
     cfg = WL.CONFIGS[a.workload]
+    other_storage = a.storage is not None and a.storage != cfg.dtype
+    if other_storage:
+        cfg = WL.shrink(cfg, dtype=a.storage)
     # the CPU legs fork worker processes: run them before this process touches the GPU
     if a.kchunk < 0:
         print("bench.py: --kchunk must be >= 0", file=sys.stderr)
@@ -460,13 +465,13 @@ def main():
                    "kernel": s[f"{dom}_kernel"], "buffer_sets_rotated": s["buffer_sets_rotated"]},
         "roofline": {"bound": "hbm", "kernel": f"gspn_scan_{dom}", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if (a.kchunk or a.logits or a.transposed) else load_traffic(cfg.name, dom),
+                     "traffic": None if (a.kchunk or a.logits or a.transposed or other_storage) else load_traffic(cfg.name, dom),
                      "traffic_source": "stored: profiles/traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier "
                                        "run of this command, scaled by a 1 GiB copy), not measured in this run",
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_ms},
         "detail": s,
     }
-    if cfg.name == DEFAULT_WORKLOAD and not (a.kchunk or a.logits or a.transposed):
+    if cfg.name == DEFAULT_WORKLOAD and not (a.kchunk or a.logits or a.transposed or other_storage):
         # The metric names two shapes, 128x128 and 512x512, forward and backward: beside the forward-only headline on
         # the first, the same figures (algorithmic bytes per launch, mean launch time from events on the launch
         # stream, fraction of the HBM peak) for the forward on the second and for both shapes as training steps

@@ -33,9 +33,14 @@
  * Pointers are DEVICE pointers (hipMalloc'ed or equivalent), 16-byte aligned,
  * owned by the caller; inputs and outputs must not alias.  The library keeps no
  * pointer after a call returns, allocates nothing and frees nothing.
+ * Element types (`dtype`): GSPN_F32 (fp32), GSPN_BF16 (bfloat16) and GSPN_F16 (IEEE binary16; the scan calls and their
+ * plan queries -- the proxy projections and the per-line-launch comparator take the first two only).  fp16 values are
+ * converted by the hardware: to nearest even, subnormals kept, a result beyond 65504 becomes infinity (the states of a
+ * scan with row-stochastic weights stay within the range of lam * x, so that is a matter of the caller's scaling).
+ *
  * Arithmetic: inputs are widened to fp32, the carried state and all sums are
  * fp32, each stored value is rounded once to nearest-even -- except the merged
- * bf16 y / gx where the running sum over the directions is kept in storage
+ * bf16 / fp16 y / gx where the running sum over the directions is kept in storage
  * precision (feature maps too large to stage on chip, merged in place in global
  * memory, and 128x128 maps on the "pair" kernels, whose on-chip tile is bf16):
  * at most one extra rounding per direction.
@@ -60,13 +65,13 @@ typedef enum {
     GSPN_OK = 0,
     GSPN_ERR_NULL = 1,        /* a required pointer is NULL                              */
     GSPN_ERR_SHAPE = 2,       /* a dimension or kchunk < 1, C % G != 0, dir_mask == 0 or > 15 */
-    GSPN_ERR_DTYPE = 3,       /* dtype is not GSPN_F32 / GSPN_BF16                        */
+    GSPN_ERR_DTYPE = 3,       /* dtype is not one the entry point takes                   */
     GSPN_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                        */
     GSPN_ERR_UNSUPPORTED = 5, /* a line longer than GSPN_MAX_LINE (GSPN_MAX_LINE_LOGITS), unknown flag bits */
     GSPN_ERR_HIP = 6          /* the HIP runtime refused the launch                      */
 } gspn_status;
 
-enum { GSPN_F32 = 0, GSPN_BF16 = 1 };
+enum { GSPN_F32 = 0, GSPN_BF16 = 1, GSPN_F16 = 2 };
 enum { GSPN_DIR_TB = 1, GSPN_DIR_BT = 2, GSPN_DIR_LR = 4, GSPN_DIR_RL = 8, GSPN_DIR_ALL = 15 };
 enum { GSPN_FLAG_SHARED_PARAMS = 1 };
 enum { GSPN_MAX_LINE = 16384 };  /* largest H or W */

@@ -11,7 +11,7 @@ import ctypes
 import os
 from typing import Optional
 
-GSPN_F32, GSPN_BF16 = 0, 1
+GSPN_F32, GSPN_BF16, GSPN_F16 = 0, 1, 2
 GSPN_FLAG_SHARED_PARAMS = 1
 DIR_ALL = 15
 
@@ -148,7 +148,9 @@ def _dtype_code(t) -> int:
         return GSPN_F32
     if t.dtype == torch.bfloat16:
         return GSPN_BF16
-    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16")
+    if t.dtype == torch.float16:
+        return GSPN_F16
+    raise TypeError(f"unsupported dtype {t.dtype}: float32, bfloat16 or float16")
 
 
 def _ptr(t, name, shape, like):

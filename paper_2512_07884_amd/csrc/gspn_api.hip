@@ -14,7 +14,7 @@ int check_common(int B, int C, int H, int W, int G, unsigned dir_mask, int dtype
     if (B < 1 || C < 1 || H < 1 || W < 1 || G < 1) return GSPN_ERR_SHAPE;
     if (C % G != 0) return GSPN_ERR_SHAPE;
     if (dir_mask == 0 || dir_mask > 15u) return GSPN_ERR_SHAPE;
-    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16 && dtype != GSPN_F16) return GSPN_ERR_DTYPE;
     if (flags & ~(unsigned)GSPN_FLAG_SHARED_PARAMS) return GSPN_ERR_UNSUPPORTED;
     if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
     // plane offsets inside a (batch, channel) image are 32-bit in the kernels
@@ -74,6 +74,7 @@ int gspn_scan_fwd_unfused(const void* x, const void* w, const void* lam, const v
     if (!x || !w || !lam || !u || !y || !workspace) return GSPN_ERR_NULL;
     int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
     if (st != GSPN_OK) return st;
+    if (dtype == GSPN_F16) return GSPN_ERR_DTYPE;             // the comparator exists in fp32 and bf16 storage
     if (misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y) || misaligned(workspace) ||
         (h_save && misaligned(h_save)))
         return GSPN_ERR_ALIGN;
@@ -271,7 +272,7 @@ const char* gspn_status_string(int status) {
         case GSPN_OK: return "ok";
         case GSPN_ERR_NULL: return "a required pointer is NULL";
         case GSPN_ERR_SHAPE: return "bad shape: dimensions and kchunk must be >= 1, C divisible by G, dir_mask in 1..15";
-        case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32 or GSPN_BF16";
+        case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32, GSPN_BF16 or GSPN_F16 (the proxy projections: GSPN_F32 or GSPN_BF16)";
         case GSPN_ERR_ALIGN: return "pointers must be 16-byte aligned";
         case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE (GSPN_MAX_LINE_LOGITS with logits), unknown flag, or B*M*K beyond the static workspace";
         case GSPN_ERR_HIP: return "HIP launch failed";

@@ -26,6 +26,8 @@ hipError_t launch_reverse_sweep_f32(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_bf16(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_f32_local(const FwdParams& p, hipStream_t s);     // GSPN-local and logits calls
 hipError_t launch_reverse_sweep_bf16_local(const FwdParams& p, hipStream_t s);
+hipError_t launch_reverse_sweep_f16(const FwdParams& p, hipStream_t s);
+hipError_t launch_reverse_sweep_f16_local(const FwdParams& p, hipStream_t s);
 hipError_t launch_reverse_sweep_plane(const FwdParams& p, int dtype, hipStream_t s);     // small maps: whole planes through LDS
 bool reverse_sweep_plane_applicable(const FwdParams& p, int dtype);
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s);    // maps beyond the LDS tile
@@ -240,6 +242,7 @@ hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
 bool bwd_twopass_applicable(const BwdParams& p, int dtype) {
     if ((size_t)p.B * p.G * ((size_t)p.H * p.W) * 4 / 256 > 0x7fffffffull) return false;
     const FwdParams f = reverse_sweep_params(p);
+    if (dtype == 2) return fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype);   // fp16: these two families only
     return reverse_sweep_plane_applicable(f, dtype) || fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype) ||
            (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype));
 }
@@ -248,7 +251,10 @@ hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     if (!bwd_twopass_applicable(p, dtype)) return hipErrorInvalidValue;
     const FwdParams f = reverse_sweep_params(p);
     hipError_t e;
-    if (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype)) {
+    if (dtype == 2) {
+        if (!fwd_tile_applicable(f, dtype)) e = launch_reverse_sweep_stream(f, dtype, s);
+        else e = (p.kchunk > 0 || p.logits) ? launch_reverse_sweep_f16_local(f, s) : launch_reverse_sweep_f16(f, s);
+    } else if (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype)) {
         e = launch_reverse_sweep_chunk(f, dtype, s);
     } else if (reverse_sweep_plane_applicable(f, dtype)) {
         e = launch_reverse_sweep_plane(f, dtype, s);
@@ -268,6 +274,12 @@ hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
         if (p.W % 4 == 0) return launch_finish<float, 4>(p, ndirs, s);
         if (p.W % 2 == 0) return launch_finish<float, 2>(p, ndirs, s);
         return launch_finish<float, 1>(p, ndirs, s);
+    }
+    if (dtype == 2) {
+        if (p.W % 8 == 0) return launch_finish<f16_t, 8>(p, ndirs, s);
+        if (p.W % 4 == 0) return launch_finish<f16_t, 4>(p, ndirs, s);
+        if (p.W % 2 == 0) return launch_finish<f16_t, 2>(p, ndirs, s);
+        return launch_finish<f16_t, 1>(p, ndirs, s);
     }
     if (p.W % 8 == 0) return launch_finish<bf16_t, 8>(p, ndirs, s);
     if (p.W % 4 == 0) return launch_finish<bf16_t, 4>(p, ndirs, s);

@@ -22,10 +22,38 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw));
 }
 
+
+// IEEE binary16 storage: a type of its own, so that overloads and templates tell it from bf16.  Conversions are the
+// hardware's (v_cvt_f32_f16 / v_cvt_f16_f32: round to nearest even, subnormals kept, beyond 65504 -> inf).
+struct f16_t { uint16_t bits; };
+typedef _Float16 f16x2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float f16_to_f32(f16_t v) { return (float)__builtin_bit_cast(_Float16, v.bits); }
+__device__ __forceinline__ f16_t f32_to_f16(float f) { f16_t r; r.bits = __builtin_bit_cast(uint16_t, (_Float16)f); return r; }
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+    const f32x2_hw v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_hw));
+}
+
+// a 32-bit word of two 16-bit storage values (T = bf16_t or f16_t): the value in bits 0-15 / bits 16-31, and the way back
+template <typename T> __device__ __forceinline__ float word_lo(uint32_t w) {
+    if constexpr (__is_same(T, f16_t)) { f16_t v; v.bits = (uint16_t)w; return f16_to_f32(v); }
+    else return __uint_as_float(w << 16);
+}
+template <typename T> __device__ __forceinline__ float word_hi(uint32_t w) {
+    if constexpr (__is_same(T, f16_t)) { f16_t v; v.bits = (uint16_t)(w >> 16); return f16_to_f32(v); }
+    else return __uint_as_float(w & 0xffff0000u);
+}
+template <typename T> __device__ __forceinline__ uint32_t pack_word(float lo, float hi) {
+    if constexpr (__is_same(T, f16_t)) return pack_f16x2(lo, hi);
+    else return pack_bf16x2(lo, hi);
+}
+
 __device__ __forceinline__ float ldf(const float* p) { return *p; }
 __device__ __forceinline__ float ldf(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ float ldf(const f16_t* p) { return f16_to_f32(*p); }
 __device__ __forceinline__ void stf(float* p, float v) { *p = v; }
 __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+__device__ __forceinline__ void stf(f16_t* p, float v) { *p = f32_to_f16(v); }
 
 // ---- weights from raw logits (Sec. 3.2: the weights are normalised so that every row of T_i sums to 1) ----
 // Softmax over the three taps of one position, in place.  A tap whose neighbour lies outside the line

@@ -46,6 +46,10 @@ bool stream_two_channels_enabled() { return !knobs().stream_one_channel; }
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const Knobs k = knobs();
     if (k.force_generic) return FWD_GENERIC;
+    if (dtype == 2) {   // fp16 storage: the tile kernels, the general stream kernel, the generic kernel
+        if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
+        return fwd_stream_applicable(p, dtype) ? FWD_STREAM : FWD_GENERIC;
+    }
     // GSPN-local with few planes: the stretches as work items (Sec. 4.1), before any one-workgroup-per-plane kernel
     if (!k.fwd_no_chunk && fwd_chunk_applicable(p, dtype)) return FWD_CHUNK;
     if (!k.fwd_no_plane && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
@@ -57,6 +61,7 @@ static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
     const Knobs k = knobs();
     if (k.force_generic) return BWD_GENERIC;
     const bool twopass = !k.bwd_no_twopass && bwd_twopass_applicable(p, dtype);
+    if (dtype == 2) return twopass ? BWD_TWOPASS : BWD_GENERIC;   // fp16 storage: two passes on the tile / stream kernels
     if (!k.bwd_no_plane && bwd_plane_applicable(p, dtype)) {
         // the single-launch plane kernel, except where the two passes were measured faster: bf16 storage, shared
         // weights, lines of more than 16 positions (28x28x192, B = 64, G = 8: 382 -> 270 us; B = 32, G = 4, where a bf16

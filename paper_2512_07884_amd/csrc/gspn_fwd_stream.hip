@@ -1,11 +1,12 @@
 // Stream kernels (maps too large for an on-chip output tile): host-side dispatch.  The kernels live in
-// gspn_fwd_stream_impl.hpp and are compiled in two translation units, by storage type.
+// gspn_fwd_stream_impl.hpp and are compiled in three translation units, by storage type.
 #include "gspn_fwd_stream_impl.hpp"
 
 namespace gspn {
 
 hipError_t launch_stream_f32(const FwdParams& p, hipStream_t s, bool reverse);
 hipError_t launch_stream_bf16(const FwdParams& p, hipStream_t s, bool reverse);
+hipError_t launch_stream_f16(const FwdParams& p, hipStream_t s, bool reverse);
 // bf16, global scan: horizontal phases with whole-line requests (gspn_fwd_stream_staged.hip)
 bool stream_staged_applicable(const FwdParams& p, int dtype);
 hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s);
@@ -15,19 +16,25 @@ hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s)
 bool stream_big_applicable(const FwdParams& p, int dtype, bool reverse);
 hipError_t launch_stream_big(const FwdParams& p, int dtype, bool reverse, hipStream_t s);
 
-bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || stream_big_applicable(p, dtype, false); }
-bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || stream_big_applicable(p, dtype, true); }
+// (fp16 storage runs the general kernels of this file only: its maps end at 512 rows)
+bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || (dtype != 2 && stream_big_applicable(p, dtype, false)); }
+bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || (dtype != 2 && stream_big_applicable(p, dtype, true)); }
+
+static hipError_t launch_stream_general(const FwdParams& p, int dtype, hipStream_t s, bool reverse) {
+    if (dtype == 0) return launch_stream_f32(p, s, reverse);
+    return dtype == 1 ? launch_stream_bf16(p, s, reverse) : launch_stream_f16(p, s, reverse);
+}
 
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s) {
-    if (!plan_stream(p, dtype).ok) return launch_stream_big(p, dtype, false, s);
+    if (!plan_stream(p, dtype).ok) return dtype == 2 ? hipErrorInvalidValue : launch_stream_big(p, dtype, false, s);
     if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, false, s);
-    return dtype == 0 ? launch_stream_f32(p, s, false) : launch_stream_bf16(p, s, false);
+    return launch_stream_general(p, dtype, s, false);
 }
 
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s) {
-    if (!plan_stream(p, dtype).ok) return launch_stream_big(p, dtype, true, s);
+    if (!plan_stream(p, dtype).ok) return dtype == 2 ? hipErrorInvalidValue : launch_stream_big(p, dtype, true, s);
     if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, true, s);
-    return dtype == 0 ? launch_stream_f32(p, s, true) : launch_stream_bf16(p, s, true);
+    return launch_stream_general(p, dtype, s, true);
 }
 
 }  // namespace gspn

@@ -363,9 +363,9 @@ struct HStream {
                     if constexpr (RMW) yw = yrow[e >> 1];
                 } else {
                     float lo = (e & 1) ? ypair : yv, hi = (e & 1) ? yv : ypair;
-                    if constexpr (RMW) { lo += __uint_as_float(yw << 16); hi += __uint_as_float(yw & 0xffff0000u); }
-                    yrow[e >> 1] = pack_bf16x2(lo, hi);
-                    if constexpr (SAVE) bx[e >> 1] = pack_bf16x2((e & 1) ? epair : h, (e & 1) ? h : epair);
+                    if constexpr (RMW) { lo += word_lo<T>(yw); hi += word_hi<T>(yw); }
+                    yrow[e >> 1] = pack_word<T>(lo, hi);
+                    if constexpr (SAVE) bx[e >> 1] = pack_word<T>((e & 1) ? epair : h, (e & 1) ? h : epair);
                 }
             }
         };
@@ -515,7 +515,7 @@ static StreamPlan plan_stream(const FwdParams& p, int dtype) {
     if (p.xt) return t;                                    // transposed-horizontal layout: tile and generic kernels
     if (p.W % 64 || p.H % 64) return t;
     const int v = p.W / 64;
-    if (dtype == 1 && !(v == 4 || v == 8 || v == 16)) return t;
+    if (dtype != 0 && !(v == 4 || v == 8 || v == 16)) return t;
     if (dtype == 0 && !(v == 4 || v == 8)) return t;
     const int parts = p.H / 64;
     if (parts < 1 || parts > 8) return t;

@@ -1,4 +1,4 @@
-// Forward tile kernels, one translation unit of four (see gspn_fwd_tile.hip).
+// Forward tile kernels, one translation unit of six (see gspn_fwd_tile.hip).
 #include "gspn_fwd_tile_impl.hpp"
 
 namespace gspn {

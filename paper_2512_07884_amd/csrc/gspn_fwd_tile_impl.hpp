@@ -706,7 +706,10 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
     const size_t per_channel = (size_t)p.H * t.pitch * sizeof(float) + (hv == H_SPLIT ? 2 * parts * 4 * sizeof(float) : 0);
     // channels per workgroup: the smallest count that fills the lanes of a wave in both phases
     // (several small workgroups per CU overlap each other's barriers and load waits better than
-    // one large one), dividing C, fitting LDS, with at most 8 waves
+    // one large one), dividing C, fitting LDS, with at most 8 waves (fp16 storage: 4 -- its widening and rounding
+    // instructions hold more registers than the shifts of bf16, and the 128 registers per lane of an eight-wave
+    // workgroup do not take them without spilling)
+    const int max_waves = dtype == 2 ? 4 : 8;
     const int dirs_v = ((p.mask >> 0) & 1) + ((p.mask >> 1) & 1), dirs_h = ((p.mask >> 2) & 1) + ((p.mask >> 3) & 1);
     const int want = t.pv > t.ph ? t.pv : t.ph;
     int best = 0;
@@ -715,7 +718,7 @@ static TilePlan plan_tile(const FwdParams& p, int dtype) {
         if (K * per_channel > (size_t)LDS_BUDGET) break;
         const int wv = ((K + t.pv - 1) / t.pv) * dirs_v, wh = ((K + t.ph - 1) / t.ph) * dirs_h * t.parts;
         const int nw = wv > wh ? wv : wh;
-        if (nw > 8) continue;
+        if (nw > max_waves) continue;
         best = K;
         if (K >= want && K % t.pv == 0 && K % t.ph == 0) break;
     }
@@ -758,19 +761,24 @@ static hipError_t launch_one(const TileArgs& a, const TilePlan& t, hipStream_t s
     }
 }
 
+// storage type -> the dtype code of the planners
+template <typename T> constexpr int dtype_code() { return sizeof(T) == 4 ? 0 : (__is_same(T, f16_t) ? 2 : 1); }
+
 template <typename T, int VV, int VH, int CS, bool DB, int PF, bool LOC>
 static hipError_t launch_cfg(const TileArgs& a, const TilePlan& t, bool save, hipStream_t s) {
     if (t.nwaves <= 4)
         return save ? launch_one<T, VV, VH, CS, DB, PF, true, 4, LOC>(a, t, s)
                     : launch_one<T, VV, VH, CS, DB, PF, false, 4, LOC>(a, t, s);
-    return save ? launch_one<T, VV, VH, CS, DB, PF, true, 8, LOC>(a, t, s)
-                : launch_one<T, VV, VH, CS, DB, PF, false, 8, LOC>(a, t, s);
+    if constexpr (__is_same(T, f16_t)) return hipErrorInvalidValue;      // (never planned: see plan_tile)
+    else
+        return save ? launch_one<T, VV, VH, CS, DB, PF, true, 8, LOC>(a, t, s)
+                    : launch_one<T, VV, VH, CS, DB, PF, false, 8, LOC>(a, t, s);
 }
 
 template <typename T, bool LOC>
 static hipError_t launch_fwd_tile_part(const FwdParams& p, hipStream_t s) {
     constexpr int ES = (int)sizeof(T);
-    const TilePlan t = plan_tile(p, ES == 4 ? 0 : 1);
+    const TilePlan t = plan_tile(p, dtype_code<T>());
     if (!t.ok) return hipErrorInvalidValue;
     TileArgs a;
     a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.lplh = t.lplh; a.ph = t.ph;
@@ -799,14 +807,15 @@ static hipError_t launch_one_reverse(const TileArgs& a, const TilePlan& t, hipSt
 template <typename T, int VV, int VH, int CS, bool DB, int PF, bool LOC>
 static hipError_t launch_cfg_reverse(const TileArgs& a, const TilePlan& t, hipStream_t s) {
     if (t.nwaves <= 4) return launch_one_reverse<T, VV, VH, CS, DB, PF, 4, LOC>(a, t, s);
-    return launch_one_reverse<T, VV, VH, CS, DB, PF, 8, LOC>(a, t, s);
+    if constexpr (__is_same(T, f16_t)) return hipErrorInvalidValue;      // (never planned: see plan_tile)
+    else return launch_one_reverse<T, VV, VH, CS, DB, PF, 8, LOC>(a, t, s);
 }
 
 // LOC as in launch_one: the GSPN-local and logits calls on instantiations (and in translation units) of their own
 template <typename T, bool LOC>
 static hipError_t launch_reverse_sweep_part(const FwdParams& p, hipStream_t s) {
     constexpr int ES = (int)sizeof(T);
-    const TilePlan t = plan_tile(p, ES == 4 ? 0 : 1);
+    const TilePlan t = plan_tile(p, dtype_code<T>());
     if (!t.ok || t.hv == H_TRANSPOSED || !p.hs || LOC != (p.kchunk > 0 || p.logits)) return hipErrorInvalidValue;
     TileArgs a;
     a.p = p; a.K = t.K; a.pitch = t.pitch; a.lplv = t.lplv; a.pv = t.pv; a.lplh = t.lplh; a.ph = t.ph;

@@ -230,10 +230,11 @@ hipError_t launch_fwd_generic(const FwdParams& p, int dtype, hipStream_t s) {
     // the fp32 tile of the merged output, when the plane fits beside the line buffers (one rounding of y instead of
     // one per direction; in fp32 storage the in-place sum is already exact to the storage type)
     const size_t with_tile = lines + (size_t)p.H * p.W * sizeof(float);
-    const bool tile = dtype == 1 && with_tile <= 160 * 1024;
+    const bool tile = dtype != 0 && with_tile <= 160 * 1024;
     const size_t shmem = tile ? with_tile : lines;
     void (*k)(FwdParams) = dtype == 0 ? fwd_generic_kernel<float, false>
-                                      : (tile ? fwd_generic_kernel<bf16_t, true> : fwd_generic_kernel<bf16_t, false>);
+                           : dtype == 1 ? (tile ? fwd_generic_kernel<bf16_t, true> : fwd_generic_kernel<bf16_t, false>)
+                                        : (tile ? fwd_generic_kernel<f16_t, true> : fwd_generic_kernel<f16_t, false>);
     if (shmem > 48 * 1024) {                                 // ask for the LDS explicitly
         const hipError_t e = allow_dynamic_lds((const void*)k, 160 * 1024);
         if (e != hipSuccess) return e;
@@ -259,7 +260,7 @@ hipError_t launch_bwd_generic(const BwdParams& p, int dtype, hipStream_t s) {
     const int nc = bwd_batch(p, Lmax);
     const size_t shmem = (2 * (size_t)nc + (p.logits ? 6 : 0)) * (size_t)Lmax * sizeof(float);
     if (shmem > 160 * 1024) return hipErrorInvalidValue;      // checked by the caller (GSPN_MAX_LINE_LOGITS)
-    void (*k)(BwdParams, int) = dtype == 0 ? bwd_generic_kernel<float> : bwd_generic_kernel<bf16_t>;
+    void (*k)(BwdParams, int) = dtype == 0 ? bwd_generic_kernel<float> : dtype == 1 ? bwd_generic_kernel<bf16_t> : bwd_generic_kernel<f16_t>;
     if (shmem > 48 * 1024) {                                 // ask for the LDS explicitly
         const hipError_t e = allow_dynamic_lds((const void*)k, 160 * 1024);
         if (e != hipSuccess) return e;

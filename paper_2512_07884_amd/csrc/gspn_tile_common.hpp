@@ -74,18 +74,18 @@ template <int NB> __device__ __forceinline__ void st_raw(char* p, const uint32_t
 // element e of a packed register vector, widened to fp32 (e is a compile-time constant after unrolling)
 template <typename T> __device__ __forceinline__ float elem(const uint32_t* r, int e) {
     if constexpr (sizeof(T) == 4) return __uint_as_float(r[e]);
-    else return (e & 1) ? __uint_as_float(r[e >> 1] & 0xffff0000u) : __uint_as_float(r[e >> 1] << 16);
+    else return (e & 1) ? word_hi<T>(r[e >> 1]) : word_lo<T>(r[e >> 1]);
 }
-// pack V fp32 values into storage registers (round to nearest even for bf16)
+// pack V fp32 values into storage registers (round to nearest even for the 16-bit types)
 template <typename T, int V> __device__ __forceinline__ void pack(const float* v, uint32_t* r) {
     if constexpr (sizeof(T) == 4) {
 #pragma unroll
         for (int i = 0; i < V; ++i) r[i] = __float_as_uint(v[i]);
     } else {
-        static_assert(V % 2 == 0, "bf16 vectors hold an even number of elements");
+        static_assert(V % 2 == 0, "vectors of 16-bit values hold an even number of elements");
 #pragma unroll
         for (int i = 0; i < V / 2; ++i)
-            r[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+            r[i] = pack_word<T>(v[2 * i], v[2 * i + 1]);
     }
 }
 

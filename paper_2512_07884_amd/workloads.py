@@ -37,7 +37,7 @@ class ScanConfig:
     H: int
     W: int
     G: int
-    dtype: str = "f32"          # storage dtype: "f32" or "bf16"
+    dtype: str = "f32"          # storage dtype: "f32", "bf16" or "f16"
     dir_mask: int = 15          # bit d set = direction d runs
     logit_scale: float = 1.0
     seed: int = 0
@@ -56,7 +56,7 @@ class ScanConfig:
 
     @property
     def elem_bytes(self) -> int:
-        return 2 if self.dtype == "bf16" else 4
+        return 2 if self.dtype in ("bf16", "f16") else 4
 
     def fwd_algorithmic_bytes(self, save_h: bool = False) -> int:
         """Compulsory traffic of one forward call: every distinct input element
@@ -116,11 +116,14 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
 
 
 def to_storage(a: np.ndarray, dtype: str) -> np.ndarray:
-    """fp64/fp32 values -> storage array (float32, or uint16 bf16 bit patterns)."""
+    """fp64/fp32 values -> storage array (float32, or uint16 bit patterns of bf16 / IEEE binary16)."""
     if dtype == "f32":
         return np.ascontiguousarray(a, dtype=np.float32)
     if dtype == "bf16":
         return f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
+    if dtype == "f16":
+        # from fp32, like the bf16 branch (the generators draw fp32 values)
+        return np.ascontiguousarray(np.asarray(a, dtype=np.float32).astype(np.float16)).view(np.uint16)
     raise ValueError(dtype)
 
 
@@ -130,6 +133,8 @@ def storage_to_f64(a: np.ndarray, dtype: str) -> np.ndarray:
         return np.asarray(a, dtype=np.float32).astype(np.float64)
     if dtype == "bf16":
         return bf16_bits_to_f32(a).astype(np.float64)
+    if dtype == "f16":
+        return np.ascontiguousarray(a, dtype=np.uint16).view(np.float16).astype(np.float64)
     raise ValueError(dtype)
 
 

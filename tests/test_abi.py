@@ -55,7 +55,8 @@ def test_argument_errors_are_detected_before_any_launch(lib):
     assert lib.gspn_scan_fwd(p, p, p, p, p, None, 1, 4, 8, 8, 3, 15, 0, 0, None) == 2      # C % G
     assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 0, 0, 0, None) == 2
     assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 16, 0, 0, None) == 2
-    assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 15, 2, 0, None) == 3
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 15, 3, 0, None) == 3          # dtype codes: 0 fp32, 1 bf16, 2 fp16
+    assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 15, -1, 0, None) == 3
     assert lib.gspn_scan_fwd(p, bad, p, p, p, None, *ok_dims, 15, 0, 0, None) == 4
     assert lib.gspn_scan_fwd(p, p, p, p, p, bad, *ok_dims, 15, 0, 0, None) == 4
     assert lib.gspn_scan_fwd(p, p, p, p, p, None, *ok_dims, 15, 0, 8, None) == 5           # unknown flag
@@ -95,6 +96,27 @@ def test_logits_calls_check_their_arguments_and_dispatch_on_the_host(lib, monkey
     assert fwd(64, 96, 56, 56, 8, big, 15, 1, 0, 0) == "plane" and bwd(64, 96, 56, 56, 8, big, 15, 1, 0) == "twopass"
     assert fwd(2, 1024, 128, 128, 16, big, 15, 1, 0, 0) == "pair" and fwd(2, 1024, 128, 128, 16, big, 15, 0, 0, 0) == "tile" and fwd(1, 512, 512, 512, 16, big, 15, 1, 0, 0) == "stream"
     assert fwd(1, 2, 8, 5000, 1, big, 15, 0, 0, 0) == "invalid" and bwd(1, 2, 8, 8, 1, 0, 15, 0, 0) == "invalid"
+
+
+def test_fp16_storage_dispatches_to_the_tile_stream_and_generic_kernels(lib, monkeypatch):
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_BWD_NO_TWOPASS", "GSPN_FWD_NO_PAIR"):
+        monkeypatch.delenv(v, raising=False)
+    lib.gspn_reload_env()
+    fwd = lambda *a: lib.gspn_fwd_plan(*a).decode()
+    bwd = lambda *a: lib.gspn_bwd_plan(*a).decode()
+    F16 = 2
+    assert fwd(2, 1024, 128, 128, 16, 15, F16, 0, 0) == "tile" and bwd(2, 1024, 128, 128, 16, 15, F16, 0) == "twopass"
+    assert fwd(1, 512, 512, 512, 16, 15, F16, 0, 1) == "stream" and bwd(1, 512, 512, 512, 16, 15, F16, 0) == "twopass"
+    assert fwd(64, 96, 56, 56, 8, 15, F16, 0, 1) == "tile"
+    # rows that are no multiple of 16 B, maps of more than 512 rows, odd widths: the generic kernels
+    assert fwd(32, 192, 28, 28, 4, 15, F16, 0, 1) == "generic" and bwd(32, 192, 28, 28, 4, 15, F16, 0) == "generic"
+    assert fwd(1, 8, 1024, 1024, 2, 15, F16, 0, 0) == "generic" and fwd(1, 8, 33, 35, 2, 15, F16, 0, 0) == "generic"
+    assert lib.gspn_fwd_local_plan(1, 32, 128, 128, 2, 32, 15, F16, 0, 0).decode() == "tile"     # (no chunk axis in fp16)
+    # the comparator and the proxy projections exist in fp32 and bf16 storage only
+    p = ctypes.c_void_p(0x1000)
+    assert lib.gspn_scan_fwd_unfused(p, p, p, p, p, None, p, 1 << 30, 1, 4, 8, 8, 2, 15, F16, 0, None) == 3
+    assert lib.gspn_proxy_project(p, p, p, 1, 8, 4, 8, 8, F16, None) == 3
+    assert lib.gspn_proxy_plan(1, 8, 4, 8, 8, F16).decode() == "invalid"
 
 
 def test_plan_names(lib):

@@ -1,0 +1,124 @@
+"""GPU parity of the scan calls in fp16 (IEEE binary16) storage against the fp64 oracle, through the C ABI.
+
+fp16 storage runs the tile kernels (workgroups of at most four waves), the general stream kernel, the two-pass backward on
+those two, and the generic kernels for every other shape.  Tolerance: 1.25e-3 (max|gpu - oracle| / max|oracle| per
+tensor): the bf16 bound scaled by the ratio of the two formats' rounding units; both sides consume the same
+storage-rounded inputs, and the oracle's backward consumes its own states rounded to fp16 like h_save is.
+"""
+import numpy as np
+import pytest
+
+from gpu_util import TOL, rel_inf_err, to_device, to_host_f64, empty_like_dev
+from oracle import gspn_oracle as O
+from paper_2512_07884_amd import workloads as WL
+from test_gpu_fwd import check_case
+from test_gpu_bwd import check_bwd
+from test_gpu_local import check_local
+from test_gpu_logits import check_logits
+
+pytestmark = pytest.mark.gpu
+
+F16 = 2   # GSPN_F16
+
+
+def plans(B, C, H, W, Gr, mask=15):
+    import paper_2512_07884_amd as G
+    return (G.gspn_fwd_plan(B, C, H, W, Gr, mask, F16, 0, True), G.gspn_bwd_plan(B, C, H, W, Gr, mask, F16, 0))
+
+
+# the tile kernels' horizontal variants (rows of 112 B, rows split over waves, 64 B and 16 B bursts), shared and
+# per-channel weights, many small planes per workgroup, maps of two rows, a group of twelve channels
+TILE_SHAPES = [(2, 8, 56, 56, 2), (1, 4, 128, 128, 2), (1, 8, 64, 64, 8), (2, 8, 40, 32, 2), (1, 6, 40, 24, 3),
+               (2, 64, 32, 32, 2), (1, 8, 64, 128, 2), (1, 4, 96, 72, 2), (1, 4, 2, 56, 2), (2, 12, 56, 56, 1)]
+
+
+@pytest.mark.parametrize("shape", TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_f16_on_the_tile_kernels(shape):
+    B, C, H, W, Gr = shape
+    assert plans(B, C, H, W, Gr) == ("tile", "twopass")
+    cfg = WL.ScanConfig("f16tile", B, C, H, W, Gr, "f16", 15, 2.0, 131)
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+    check_bwd(cfg)
+
+
+# the general stream kernel (maps beyond the LDS tile: rows and columns in multiples of 64)
+@pytest.mark.parametrize("shape", [(1, 2, 256, 256, 1), (1, 4, 128, 256, 2), (1, 2, 192, 512, 2), (1, 2, 512, 512, 2),
+                                   (1, 2, 256, 1024, 1)], ids=lambda s: "x".join(map(str, s)))
+def test_f16_on_the_stream_kernel(shape):
+    B, C, H, W, Gr = shape
+    assert plans(B, C, H, W, Gr) == ("stream", "twopass")
+    cfg = WL.ScanConfig("f16stream", B, C, H, W, Gr, "f16", 15, 1.0, 137)
+    check_case(cfg)
+    check_case(cfg, save_h=False)
+    check_bwd(cfg)
+
+
+# every other shape: odd widths, rows that are no multiple of 16 B (28 x 28, 14 x 14), a single row or column, lines
+# longer than a wave, more than 512 rows, 64 channels per group (the channel sum of gw is fp32 and rounded once)
+@pytest.mark.parametrize("shape", [(2, 6, 9, 13, 3), (1, 4, 33, 70, 2), (1, 2, 1, 37, 1), (1, 2, 37, 1, 2), (1, 1, 1, 1, 1),
+                                   (1, 3, 300, 5, 3), (1, 64, 33, 35, 1), (1, 2, 640, 64, 1), (2, 16, 28, 28, 2),
+                                   (2, 8, 14, 14, 8)], ids=lambda s: "x".join(map(str, s)))
+def test_f16_on_the_generic_kernels(shape):
+    B, C, H, W, Gr = shape
+    assert plans(B, C, H, W, Gr) == ("generic", "generic")
+    cfg = WL.ScanConfig("f16generic", B, C, H, W, Gr, "f16", 15, 1.0, 139)
+    check_case(cfg)
+    check_bwd(cfg)
+
+
+@pytest.mark.parametrize("mask", [1, 2, 4, 8, 6, 9, 14])
+@pytest.mark.parametrize("hw", [(56, 56), (128, 256), (9, 13)], ids=lambda v: "x".join(map(str, v)))
+def test_f16_direction_masks(mask, hw):
+    cfg = WL.ScanConfig("f16mask", 1, 4, hw[0], hw[1], 2, "f16", mask, 1.0, 149)
+    check_case(cfg)
+    check_bwd(cfg)
+
+
+def test_f16_with_shared_parameter_slots():
+    import paper_2512_07884_amd as G
+    cfg = WL.ScanConfig("f16shared", 1, 4, 56, 56, 2, "f16", 15, 1.0, 151)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    one = {k: (v[:1].copy() if k in ("w", "lam", "u") else v) for k, v in inp.items()}
+    rep = {k: (np.repeat(v, 4, axis=0) if k in ("w", "lam", "u") else v) for k, v in one.items()}
+    f = WL.inputs_as_f64(rep, "f16")
+    y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
+    import torch
+    dev = {k: to_device(v, "f16") for k, v in one.items()}
+    y = empty_like_dev((1, 4, 56, 56), "f16", float("nan"))
+    G.gspn_scan_fwd(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, G=2, dir_mask=15, flags=1)   # GSPN_FLAG_SHARED_PARAMS
+    torch.cuda.synchronize()
+    assert rel_inf_err(to_host_f64(y), y_ref) <= TOL["f16"]
+
+
+# GSPN-local and weights as logits: the local instantiations of the tile and stream kernels, the generic kernels;
+# stretch lengths that divide the map and that do not; the first line of every stretch never read
+@pytest.mark.parametrize("shape,kchunk", [((2, 8, 56, 56, 2, "f16"), 14), ((1, 4, 128, 128, 2, "f16"), 37), ((1, 2, 256, 256, 1, "f16"), 64),
+                                          ((2, 6, 9, 13, 3, "f16"), 4), ((2, 8, 28, 28, 8, "f16"), 1)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_f16_local_scans(shape, kchunk):
+    check_local(shape, kchunk, poison_starts=True)
+
+
+@pytest.mark.parametrize("shape,kchunk", [((2, 8, 56, 56, 2, "f16"), None), ((1, 4, 128, 128, 2, "f16"), 32), ((1, 2, 128, 256, 2, "f16"), None),
+                                          ((2, 6, 9, 13, 3, "f16"), None), ((2, 8, 28, 28, 8, "f16"), 9)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_f16_weights_as_logits(shape, kchunk):
+    check_logits(shape, kchunk=kchunk, poison=True)
+
+
+def test_f16_values_beyond_bf16_resolution_survive():
+    """Inputs that differ only below bf16's resolution give different outputs: the call does not pass through bf16."""
+    cfg = WL.ScanConfig("f16res", 1, 2, 56, 56, 1, "f16", 15, 1.0, 157)
+    inp = WL.make_inputs(cfg, with_gy=False)
+    x = WL.storage_to_f64(inp["x"], "f16")
+    inp2 = dict(inp)
+    inp2["x"] = WL.to_storage(x * (1.0 + 2.0 ** -9), "f16")            # one or two fp16 steps, half a bf16 step
+    assert np.any(inp2["x"] != inp["x"])
+    from gpu_util import run_fwd_gpu
+    y1, *_ = run_fwd_gpu(inp, cfg, 15)
+    y2, *_ = run_fwd_gpu(inp2, cfg, 15)
+    f2 = WL.inputs_as_f64(inp2, "f16")
+    y2_ref, _ = O.scan_fwd(f2["x"], f2["w"], f2["lam"], f2["u"], 15)
+    assert rel_inf_err(y2, y2_ref) <= TOL["f16"]
+    assert np.any(y1 != y2)

@@ -64,6 +64,19 @@ def test_bf16_rounding_is_nearest_even_and_roundtrips():
     assert np.array_equal(t, back)
 
 
+def test_fp16_storage_is_ieee_binary16_rounded_to_nearest_even():
+    v = np.array([1.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -2.5, 3.1415927, 6.0e-8, 65504.0, 0.0], dtype=np.float32)
+    bits = WL.to_storage(v, "f16")
+    back = WL.storage_to_f64(bits, "f16")
+    # 1 + 2^-11 is a tie between 1.0 and 1 + 2^-10: goes to even (1.0); 1 + 3*2^-11 ties up to 1 + 2^-9
+    assert bits.dtype == np.uint16 and bits[0] == 0x3C00 and back[1] == 1.0 and back[2] == 1.0 + 2.0 ** -9
+    assert back[3] == -2.5 and back[5] == 2.0 ** -24 and back[6] == 65504.0 and back[7] == 0.0     # a subnormal, the largest value
+    import torch
+    t = torch.from_numpy(v).to(torch.float16).double().numpy()
+    assert np.array_equal(t, back)
+    assert WL.ScanConfig("e", 1, 2, 4, 4, 1, "f16", 15, 1.0, 1).elem_bytes == 2
+
+
 def test_slices_reassemble_into_the_full_tensors():
     cfg = WL.shrink(WL.CONFIGS["cls56"], B=2, C=8, H=6, W=5, G=4)
     full = WL.make_inputs(cfg)

@@ -11,7 +11,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgspn.so")
-SOURCES = ["gspn_api.hip", "gspn_dispatch.hip", "gspn_generic.hip", "gspn_unfused.hip", "gspn_fwd_tile.hip", "gspn_fwd_tile_f32_global.hip", "gspn_fwd_tile_f32_local.hip", "gspn_fwd_tile_bf16_global.hip", "gspn_fwd_tile_bf16_local.hip", "gspn_fwd_tile_f16_global.hip", "gspn_fwd_tile_f16_local.hip", "gspn_fwd_stream.hip", "gspn_fwd_stream_f32.hip", "gspn_fwd_stream_bf16.hip", "gspn_fwd_stream_f16.hip", "gspn_fwd_stream_staged.hip", "gspn_fwd_stream_big.hip", "gspn_fwd_plane.hip", "gspn_fwd_pair.hip", "gspn_fwd_chunk.hip", "gspn_bwd_tile.hip", "gspn_bwd_plane.hip", "gspn_bwd_twopass.hip", "gspn_bwd_twopass_f32.hip", "gspn_bwd_twopass_bf16.hip", "gspn_bwd_twopass_f32_local.hip", "gspn_bwd_twopass_bf16_local.hip", "gspn_bwd_twopass_f16.hip", "gspn_bwd_twopass_f16_local.hip", "gspn_proxy.hip"]
+SOURCES = ["gspn_api.hip", "gspn_dispatch.hip", "gspn_generic.hip", "gspn_unfused.hip", "gspn_fwd_tile.hip", "gspn_fwd_tile_f32_global.hip", "gspn_fwd_tile_f32_local.hip", "gspn_fwd_tile_bf16_global.hip", "gspn_fwd_tile_bf16_local.hip", "gspn_fwd_tile_f16_global.hip", "gspn_fwd_tile_f16_local.hip", "gspn_fwd_stream.hip", "gspn_fwd_stream_f32.hip", "gspn_fwd_stream_bf16.hip", "gspn_fwd_stream_f16.hip", "gspn_fwd_stream_staged.hip", "gspn_fwd_stream_big.hip", "gspn_fwd_plane.hip", "gspn_fwd_pair.hip", "gspn_fwd_pair_bf16.hip", "gspn_fwd_pair_f16.hip", "gspn_fwd_chunk.hip", "gspn_bwd_tile.hip", "gspn_bwd_plane.hip", "gspn_bwd_twopass.hip", "gspn_bwd_twopass_f32.hip", "gspn_bwd_twopass_bf16.hip", "gspn_bwd_twopass_f32_local.hip", "gspn_bwd_twopass_bf16_local.hip", "gspn_bwd_twopass_f16.hip", "gspn_bwd_twopass_f16_local.hip", "gspn_proxy.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -33,11 +33,15 @@ SPILL_ALLOWED = {
     # between the step loops (no scratch access inside them)
     "stream_big_horizontal_kernelItLi32ELb0ELb1": 7, "stream_big_horizontal_kernelItLi32ELb1ELb1": 5,
     "stream_big_horizontal_kernelIfLi16ELb1ELb1": 5,
+    "stream_big_horizontal_kernelINS_5f16_tELi32ELb0ELb1": 5, "stream_big_horizontal_kernelINS_5f16_tELi32ELb1ELb1": 1,
     # two-channel kernel, forward with h_save on raw logits: values parked in the accumulation registers (no scratch
     # memory: the kernel's ScratchSize is 0), none in the loop over the bands of the vertical phases, 4 to 16 moves per
     # step of the horizontal ones beside six exponentials; parity-tested at full size, train128 forward on logits
     # 0.569 ms on the one-channel tile kernel -> 0.426 ms
-    "fwd_pair_kernelILb1ELb0ELb1ELb1": 144,
+    "fwd_pair_kernelItLb1ELb0ELb1ELb1": 144,
+    # the same in fp16 storage, and its GSPN-local forward with h_save (84 values, none in the band loop either; the
+    # hardware conversions hold a few registers more than the shifts of bf16): parity-tested at full size
+    "fwd_pair_kernelINS_5f16_tELb1ELb0ELb1ELb1": 144, "fwd_pair_kernelINS_5f16_tELb1ELb0ELb1ELb0": 84,
     # fp32 maps with rows of 112 bytes on workgroups of more than four waves, without h_save: off every benchmark shape
     # (the plane kernel takes 28x28, the four-wave instantiation 56x56); kept because the shapes must run somewhere
     "fwd_tile_kernelIfLi2ELi1ELi28ELb0ELi8ELb0ELi8ELb0ELb0ELb0": 259, "fwd_tile_kernelIfLi2ELi1ELi28ELb0ELi8ELb0ELi8ELb1ELb0ELb0": 47,

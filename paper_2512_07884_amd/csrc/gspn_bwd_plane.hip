@@ -55,10 +55,10 @@ template <typename T, int E> __device__ __forceinline__ void store_piece(T* dst,
         else if (ew == 2) { const u32x2 c = {__float_as_uint(v[0]), __float_as_uint(v[1])}; *(u32x2*)dst = c; }
         else *(float*)dst = v[0];
     } else {
-        if (ew == 8) { const u32x4 c = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7])}; *(u32x4*)dst = c; }
-        else if (ew == 4) { const u32x2 c = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; *(u32x2*)dst = c; }
-        else if (ew == 2) *(uint32_t*)dst = pack_bf16x2(v[0], v[1]);
-        else *(bf16_t*)dst = f32_to_bf16(v[0]);
+        if (ew == 8) { const u32x4 c = {pack_word<T>(v[0], v[1]), pack_word<T>(v[2], v[3]), pack_word<T>(v[4], v[5]), pack_word<T>(v[6], v[7])}; *(u32x4*)dst = c; }
+        else if (ew == 4) { const u32x2 c = {pack_word<T>(v[0], v[1]), pack_word<T>(v[2], v[3])}; *(u32x2*)dst = c; }
+        else if (ew == 2) *(uint32_t*)dst = pack_word<T>(v[0], v[1]);
+        else stf(dst, v[0]);
     }
 }
 
@@ -69,7 +69,7 @@ template <typename T, int E> __device__ __forceinline__ void chunk_unpack(const 
         for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(c[e]);
     } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { v[2 * e] = __uint_as_float(c[e] << 16); v[2 * e + 1] = __uint_as_float(c[e] & 0xffff0000u); }
+        for (int e = 0; e < 4; ++e) { v[2 * e] = word_lo<T>(c[e]); v[2 * e + 1] = word_hi<T>(c[e]); }
     }
 }
 template <typename T, int E> __device__ __forceinline__ u32x4 chunk_pack(const float (&v)[E]) {
@@ -79,7 +79,7 @@ template <typename T, int E> __device__ __forceinline__ u32x4 chunk_pack(const f
         for (int e = 0; e < 4; ++e) c[e] = __float_as_uint(v[e]);
     } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) c[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+        for (int e = 0; e < 4; ++e) c[e] = pack_word<T>(v[2 * e], v[2 * e + 1]);
     }
     return c;
 }
@@ -662,6 +662,7 @@ hipError_t launch_bwd_plane(const BwdParams& p, int dtype, hipStream_t s) {
             d = d1;
         }
     }
+    if (dtype == 2) return launch_plane_t<f16_t>(a, t, s);
     return dtype == 0 ? launch_plane_t<float>(a, t, s) : launch_plane_t<bf16_t>(a, t, s);
 }
 

@@ -242,7 +242,6 @@ hipError_t launch_finish(const BwdParams& p, int ndirs, hipStream_t s) {
 bool bwd_twopass_applicable(const BwdParams& p, int dtype) {
     if ((size_t)p.B * p.G * ((size_t)p.H * p.W) * 4 / 256 > 0x7fffffffull) return false;
     const FwdParams f = reverse_sweep_params(p);
-    if (dtype == 2) return fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype);   // fp16: these two families only
     return reverse_sweep_plane_applicable(f, dtype) || fwd_tile_applicable(f, dtype) || reverse_sweep_stream_applicable(f, dtype) ||
            (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype));
 }
@@ -251,18 +250,17 @@ hipError_t launch_bwd_twopass(const BwdParams& p, int dtype, hipStream_t s) {
     if (!bwd_twopass_applicable(p, dtype)) return hipErrorInvalidValue;
     const FwdParams f = reverse_sweep_params(p);
     hipError_t e;
-    if (dtype == 2) {
-        if (!fwd_tile_applicable(f, dtype)) e = launch_reverse_sweep_stream(f, dtype, s);
-        else e = (p.kchunk > 0 || p.logits) ? launch_reverse_sweep_f16_local(f, s) : launch_reverse_sweep_f16(f, s);
-    } else if (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype)) {
+    if (chunk_kernels_enabled() && reverse_sweep_chunk_applicable(f, dtype)) {
         e = launch_reverse_sweep_chunk(f, dtype, s);
     } else if (reverse_sweep_plane_applicable(f, dtype)) {
         e = launch_reverse_sweep_plane(f, dtype, s);
     } else if (pair_kernels_enabled() && reverse_sweep_pair_applicable(f, dtype)) {
         e = launch_reverse_sweep_pair(f, dtype, s);
     } else if (fwd_tile_applicable(f, dtype)) {
-        if (p.kchunk > 0 || p.logits) e = dtype == 0 ? launch_reverse_sweep_f32_local(f, s) : launch_reverse_sweep_bf16_local(f, s);
-        else e = dtype == 0 ? launch_reverse_sweep_f32(f, s) : launch_reverse_sweep_bf16(f, s);
+        const bool local = p.kchunk > 0 || p.logits;
+        if (dtype == 0) e = local ? launch_reverse_sweep_f32_local(f, s) : launch_reverse_sweep_f32(f, s);
+        else if (dtype == 1) e = local ? launch_reverse_sweep_bf16_local(f, s) : launch_reverse_sweep_bf16(f, s);
+        else e = local ? launch_reverse_sweep_f16_local(f, s) : launch_reverse_sweep_f16(f, s);
     } else {
         e = launch_reverse_sweep_stream(f, dtype, s);
     }

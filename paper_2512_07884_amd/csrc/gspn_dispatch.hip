@@ -46,10 +46,6 @@ bool stream_two_channels_enabled() { return !knobs().stream_one_channel; }
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const Knobs k = knobs();
     if (k.force_generic) return FWD_GENERIC;
-    if (dtype == 2) {   // fp16 storage: the tile kernels, the general stream kernel, the generic kernel
-        if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
-        return fwd_stream_applicable(p, dtype) ? FWD_STREAM : FWD_GENERIC;
-    }
     // GSPN-local with few planes: the stretches as work items (Sec. 4.1), before any one-workgroup-per-plane kernel
     if (!k.fwd_no_chunk && fwd_chunk_applicable(p, dtype)) return FWD_CHUNK;
     if (!k.fwd_no_plane && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
@@ -61,20 +57,20 @@ static BwdPlan choose_bwd(const BwdParams& p, int dtype) {
     const Knobs k = knobs();
     if (k.force_generic) return BWD_GENERIC;
     const bool twopass = !k.bwd_no_twopass && bwd_twopass_applicable(p, dtype);
-    if (dtype == 2) return twopass ? BWD_TWOPASS : BWD_GENERIC;   // fp16 storage: two passes on the tile / stream kernels
     if (!k.bwd_no_plane && bwd_plane_applicable(p, dtype)) {
         // the single-launch plane kernel, except where the two passes were measured faster: bf16 storage, shared
         // weights, lines of more than 16 positions (28x28x192, B = 64, G = 8: 382 -> 270 us; B = 32, G = 4, where a bf16
         // group cannot be split over workgroups: 1401 -> 177 us; 32x32x256 G = 16: 250 -> 73 us; the shorter lines of
         // the later classifier stages and the fp32 maps run as fast or faster on the plane kernel)
         const int m = p.H > p.W ? p.H : p.W;
-        if (twopass && dtype == 1 && p.cpg > 1 && m > 16) return BWD_TWOPASS;
+        if (twopass && dtype != 0 && p.cpg > 1 && m > 16) return BWD_TWOPASS;
         return BWD_PLANE;
     }
     // the two-pass backward before the single-launch tile kernel: measured faster on every map both take (56x56x96
     // 506 -> 365 us bf16, 64x64x256 457 -> 186 us, 64x128x256 438 -> 193 us)
     if (twopass) return BWD_TWOPASS;
-    return bwd_tile_applicable(p, dtype) ? BWD_TILE : BWD_GENERIC;
+    // (the single-launch tile kernel exists in fp32 and bf16 storage)
+    return (dtype != 2 && bwd_tile_applicable(p, dtype)) ? BWD_TILE : BWD_GENERIC;
 }
 
 hipError_t launch_fwd(const FwdParams& p, int dtype, hipStream_t s) {

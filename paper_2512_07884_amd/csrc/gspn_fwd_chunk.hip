@@ -84,7 +84,9 @@ __device__ __forceinline__ void request_y(rsrc_t yb, int nseg, int tid, int nthr
 #pragma unroll
     for (int i = 0; i < NPRE; ++i) {
         const int s = tid + i * nthreads;
-        ld_buf<16>(yb, (uint32_t)seg_off(s < nseg ? s : tid), 0, pre[i]);     // clamped: redundant but in bounds
+        // clamped to segment 0: redundant but in bounds (a band of fewer segments than threads -- 64 rows of one
+        // segment -- leaves threads without any segment of their own)
+        ld_buf<16>(yb, (uint32_t)seg_off(s < nseg ? s : 0), 0, pre[i]);
     }
 }
 template <typename T, int NPRE, typename SegOff, typename TileOff>
@@ -421,6 +423,7 @@ bool fwd_chunk_applicable(const FwdParams& p, int dtype) {
 hipError_t launch_fwd_chunk(const FwdParams& p, int dtype, hipStream_t s) {
     if (!fwd_chunk_applicable(p, dtype)) return hipErrorInvalidValue;
     if (dtype == 0) return p.hs ? launch_chunk<float, true, false>(p, s) : launch_chunk<float, false, false>(p, s);
+    if (dtype == 2) return p.hs ? launch_chunk<f16_t, true, false>(p, s) : launch_chunk<f16_t, false, false>(p, s);
     return p.hs ? launch_chunk<bf16_t, true, false>(p, s) : launch_chunk<bf16_t, false, false>(p, s);
 }
 bool reverse_sweep_chunk_applicable(const FwdParams& p, int dtype) {
@@ -428,6 +431,7 @@ bool reverse_sweep_chunk_applicable(const FwdParams& p, int dtype) {
 }
 hipError_t launch_reverse_sweep_chunk(const FwdParams& p, int dtype, hipStream_t s) {
     if (!reverse_sweep_chunk_applicable(p, dtype)) return hipErrorInvalidValue;
+    if (dtype == 2) return launch_chunk<f16_t, true, true>(p, s);
     return dtype == 0 ? launch_chunk<float, true, true>(p, s) : launch_chunk<bf16_t, true, true>(p, s);
 }
 

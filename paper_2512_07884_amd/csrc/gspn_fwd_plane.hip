@@ -46,7 +46,7 @@ __device__ __forceinline__ void plds_st4(uint32_t a, pf32x4a v) { *(plds_f32x4*)
 // element e of a 16 B chunk of storage, widened to fp32
 template <typename T> __device__ __forceinline__ float chunk_elem(const u32x4& c, int e) {
     if constexpr (sizeof(T) == 4) return __uint_as_float(c[e]);
-    else return (e & 1) ? __uint_as_float(c[e >> 1] & 0xffff0000u) : __uint_as_float(c[e >> 1] << 16);
+    else return (e & 1) ? word_hi<T>(c[e >> 1]) : word_lo<T>(c[e >> 1]);
 }
 template <typename T> __device__ __forceinline__ u32x4 chunk_pack(const float* v) {
     u32x4 c;
@@ -55,7 +55,7 @@ template <typename T> __device__ __forceinline__ u32x4 chunk_pack(const float* v
         for (int e = 0; e < 4; ++e) c[e] = __float_as_uint(v[e]);
     } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) c[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+        for (int e = 0; e < 4; ++e) c[e] = pack_word<T>(v[2 * e], v[2 * e + 1]);
     }
     return c;
 }
@@ -613,6 +613,7 @@ hipError_t launch_reverse_sweep_plane(const FwdParams& p, int dtype, hipStream_t
     a.p = p; a.K = t.K; a.cpw = t.cpw; a.lsh = t.lsh; a.nwaves = t.nwaves; a.pitch = t.pitch; a.wlw = t.wlw;
     for (int d = 0; d < 4; ++d) a.seg[d] = stretch_start_bits(d < 2 ? p.H : p.W, d & 1, p.kchunk, false);
     if (dtype == 0) return t.shared_group ? launch_fplane_rev<float, true>(a, t, s) : launch_fplane_rev<float, false>(a, t, s);
+    if (dtype == 2) return t.shared_group ? launch_fplane_rev<f16_t, true>(a, t, s) : launch_fplane_rev<f16_t, false>(a, t, s);
     return t.shared_group ? launch_fplane_rev<bf16_t, true>(a, t, s) : launch_fplane_rev<bf16_t, false>(a, t, s);
 }
 
@@ -622,6 +623,7 @@ hipError_t launch_fwd_plane(const FwdParams& p, int dtype, hipStream_t s) {
     FwdPlaneArgs a;
     a.p = p; a.K = t.K; a.cpw = t.cpw; a.lsh = t.lsh; a.nwaves = t.nwaves; a.pitch = t.pitch; a.wlw = t.wlw;
     for (int d = 0; d < 4; ++d) a.seg[d] = stretch_start_bits(d < 2 ? p.H : p.W, d & 1, p.kchunk, false);
+    if (dtype == 2) return launch_fplane_t<f16_t>(a, t, s);
     return dtype == 0 ? launch_fplane_t<float>(a, t, s) : launch_fplane_t<bf16_t>(a, t, s);
 }
 

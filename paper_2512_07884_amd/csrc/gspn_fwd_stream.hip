@@ -16,9 +16,8 @@ hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s)
 bool stream_big_applicable(const FwdParams& p, int dtype, bool reverse);
 hipError_t launch_stream_big(const FwdParams& p, int dtype, bool reverse, hipStream_t s);
 
-// (fp16 storage runs the general kernels of this file only: its maps end at 512 rows)
-bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || (dtype != 2 && stream_big_applicable(p, dtype, false)); }
-bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || (dtype != 2 && stream_big_applicable(p, dtype, true)); }
+bool fwd_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || stream_big_applicable(p, dtype, false); }
+bool reverse_sweep_stream_applicable(const FwdParams& p, int dtype) { return plan_stream(p, dtype).ok || stream_big_applicable(p, dtype, true); }
 
 static hipError_t launch_stream_general(const FwdParams& p, int dtype, hipStream_t s, bool reverse) {
     if (dtype == 0) return launch_stream_f32(p, s, reverse);
@@ -26,13 +25,13 @@ static hipError_t launch_stream_general(const FwdParams& p, int dtype, hipStream
 }
 
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s) {
-    if (!plan_stream(p, dtype).ok) return dtype == 2 ? hipErrorInvalidValue : launch_stream_big(p, dtype, false, s);
+    if (!plan_stream(p, dtype).ok) return launch_stream_big(p, dtype, false, s);
     if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, false, s);
     return launch_stream_general(p, dtype, s, false);
 }
 
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s) {
-    if (!plan_stream(p, dtype).ok) return dtype == 2 ? hipErrorInvalidValue : launch_stream_big(p, dtype, true, s);
+    if (!plan_stream(p, dtype).ok) return launch_stream_big(p, dtype, true, s);
     if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, true, s);
     return launch_stream_general(p, dtype, s, true);
 }

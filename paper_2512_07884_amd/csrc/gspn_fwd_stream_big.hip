@@ -182,8 +182,8 @@ struct HStream2 {
                     // elements e and e^1 share a word; the pair is complete on every second step
                     if ((k & 1) == 0) { ypair[r] = yv; epair[r] = h[r]; }
                     else {
-                        by[r][e >> 1] = pack_bf16x2((e & 1) ? ypair[r] : yv, (e & 1) ? yv : ypair[r]);
-                        if constexpr (SAVE) bx[r][e >> 1] = pack_bf16x2((e & 1) ? epair[r] : h[r], (e & 1) ? h[r] : epair[r]);
+                        by[r][e >> 1] = pack_word<T>((e & 1) ? ypair[r] : yv, (e & 1) ? yv : ypair[r]);
+                        if constexpr (SAVE) bx[r][e >> 1] = pack_word<T>((e & 1) ? epair[r] : h[r], (e & 1) ? h[r] : epair[r]);
                     }
                 }
             }
@@ -308,6 +308,10 @@ hipError_t launch_stream_big(const FwdParams& p, int dtype, bool reverse, hipStr
     if (dtype == 0) {
         if (reverse) return launch_big<float, true, true>(p, t, s);
         return p.hs ? launch_big<float, false, true>(p, t, s) : launch_big<float, false, false>(p, t, s);
+    }
+    if (dtype == 2) {
+        if (reverse) return launch_big<f16_t, true, true>(p, t, s);
+        return p.hs ? launch_big<f16_t, false, true>(p, t, s) : launch_big<f16_t, false, false>(p, t, s);
     }
     if (reverse) return launch_big<bf16_t, true, true>(p, t, s);
     return p.hs ? launch_big<bf16_t, false, true>(p, t, s) : launch_big<bf16_t, false, false>(p, t, s);

@@ -98,20 +98,24 @@ def test_logits_calls_check_their_arguments_and_dispatch_on_the_host(lib, monkey
     assert fwd(1, 2, 8, 5000, 1, big, 15, 0, 0, 0) == "invalid" and bwd(1, 2, 8, 8, 1, 0, 15, 0, 0) == "invalid"
 
 
-def test_fp16_storage_dispatches_to_the_tile_stream_and_generic_kernels(lib, monkeypatch):
-    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_BWD_NO_TWOPASS", "GSPN_FWD_NO_PAIR"):
+def test_fp16_storage_dispatches_like_bf16_storage(lib, monkeypatch):
+    for v in ("GSPN_FORCE_GENERIC", "GSPN_FWD_NO_PLANE", "GSPN_BWD_NO_PLANE", "GSPN_BWD_NO_TWOPASS", "GSPN_FWD_NO_PAIR", "GSPN_FWD_NO_CHUNK"):
         monkeypatch.delenv(v, raising=False)
     lib.gspn_reload_env()
-    fwd = lambda *a: lib.gspn_fwd_plan(*a).decode()
-    bwd = lambda *a: lib.gspn_bwd_plan(*a).decode()
-    F16 = 2
-    assert fwd(2, 1024, 128, 128, 16, 15, F16, 0, 0) == "tile" and bwd(2, 1024, 128, 128, 16, 15, F16, 0) == "twopass"
-    assert fwd(1, 512, 512, 512, 16, 15, F16, 0, 1) == "stream" and bwd(1, 512, 512, 512, 16, 15, F16, 0) == "twopass"
-    assert fwd(64, 96, 56, 56, 8, 15, F16, 0, 1) == "tile"
-    # rows that are no multiple of 16 B, maps of more than 512 rows, odd widths: the generic kernels
-    assert fwd(32, 192, 28, 28, 4, 15, F16, 0, 1) == "generic" and bwd(32, 192, 28, 28, 4, 15, F16, 0) == "generic"
-    assert fwd(1, 8, 1024, 1024, 2, 15, F16, 0, 0) == "generic" and fwd(1, 8, 33, 35, 2, 15, F16, 0, 0) == "generic"
-    assert lib.gspn_fwd_local_plan(1, 32, 128, 128, 2, 32, 15, F16, 0, 0).decode() == "tile"     # (no chunk axis in fp16)
+    BF16, F16 = 1, 2
+    for shape in ((2, 1024, 128, 128, 16), (1, 512, 512, 512, 16), (64, 96, 56, 56, 8), (32, 192, 28, 28, 4), (32, 192, 28, 28, 192),
+                  (1, 8, 1024, 1024, 2), (1, 8, 33, 35, 2), (1, 3, 128, 128, 1), (2, 768, 7, 7, 8)):
+        for has_h in (0, 1):
+            assert lib.gspn_fwd_plan(*shape, 15, F16, 0, has_h) == lib.gspn_fwd_plan(*shape, 15, BF16, 0, has_h), shape
+            assert lib.gspn_fwd_local_plan(*shape, 32, 15, F16, 0, has_h) == lib.gspn_fwd_local_plan(*shape, 32, 15, BF16, 0, has_h), shape
+        assert lib.gspn_bwd_plan(*shape, 15, F16, 0) == lib.gspn_bwd_plan(*shape, 15, BF16, 0), shape
+    assert lib.gspn_fwd_plan(2, 1024, 128, 128, 16, 15, F16, 0, 0).decode() == "pair"
+    # the single-launch backward tile kernel exists in fp32 and bf16 storage: without the two passes fp16 goes generic
+    monkeypatch.setenv("GSPN_BWD_NO_TWOPASS", "1")
+    lib.gspn_reload_env()
+    assert lib.gspn_bwd_plan(2, 8, 56, 56, 2, 15, BF16, 0).decode() == "tile" and lib.gspn_bwd_plan(2, 8, 56, 56, 2, 15, F16, 0).decode() == "generic"
+    monkeypatch.delenv("GSPN_BWD_NO_TWOPASS")
+    lib.gspn_reload_env()
     # the comparator and the proxy projections exist in fp32 and bf16 storage only
     p = ctypes.c_void_p(0x1000)
     assert lib.gspn_scan_fwd_unfused(p, p, p, p, p, None, p, 1 << 30, 1, 4, 8, 8, 2, 15, F16, 0, None) == 3

@@ -148,7 +148,7 @@ def test_local_scans_on_the_tile_kernels_for_small_maps(shape, kchunk, monkeypat
 CHUNK_LOCAL = [((1, 32, 128, 128, 4, "f32"), 32), ((1, 32, 128, 128, 2, "bf16"), 32), ((2, 6, 64, 128, 3, "f32"), 16),
                ((1, 4, 256, 128, 2, "bf16"), 64), ((1, 3, 128, 256, 1, "bf16"), 8), ((1, 2, 256, 256, 2, "f32"), 64),
                ((1, 4, 64, 64, 2, "f32"), 4), ((1, 2, 64, 256, 1, "bf16"), 32), ((1, 4, 128, 64, 4, "f32"), 64),
-               ((1, 2, 256, 64, 1, "f32"), 32), ((1, 2, 64, 128, 2, "bf16"), 8)]
+               ((1, 2, 256, 64, 1, "f32"), 32), ((1, 2, 64, 128, 2, "bf16"), 8), ((1, 8, 64, 128, 2, "bf16"), 8)]
 
 
 @pytest.mark.parametrize("shape,kchunk", CHUNK_LOCAL, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))

@@ -224,7 +224,7 @@ int gspn_proxy_project_bwd_static(const void* gout, const void* in, const void* 
 const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
 
 /* Name of the kernel family the forward / backward call would dispatch to for
- * these arguments: "plane" (small maps, whole planes through LDS), "pair" (128x128 bf16 maps
+ * these arguments: "plane" (small maps, whole planes through LDS), "pair" (128x128 maps in 16-bit storage
  * with an even number of channels per weight group, all four directions, the global scan or GSPN-local, normalised
  * weights or logits: two channels of a group per workgroup, the merged output accumulated on chip in storage precision, i.e. rounded
  * after each of the four additions), "tile" (maps whose merged output fits in LDS), "stream"

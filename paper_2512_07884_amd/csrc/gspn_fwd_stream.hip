@@ -7,9 +7,9 @@ namespace gspn {
 hipError_t launch_stream_f32(const FwdParams& p, hipStream_t s, bool reverse);
 hipError_t launch_stream_bf16(const FwdParams& p, hipStream_t s, bool reverse);
 hipError_t launch_stream_f16(const FwdParams& p, hipStream_t s, bool reverse);
-// bf16, global scan: horizontal phases with whole-line requests (gspn_fwd_stream_staged.hip)
+// 16-bit storage, global scan: horizontal phases with whole-line requests (gspn_fwd_stream_staged.hip)
 bool stream_staged_applicable(const FwdParams& p, int dtype);
-hipError_t launch_stream_staged(const FwdParams& p, bool reverse, hipStream_t s);
+hipError_t launch_stream_staged(const FwdParams& p, int dtype, bool reverse, hipStream_t s);
 
 // maps of up to 2048 rows (reverse sweep: 1024) / lines of up to 2048 positions, global scan: two launches
 // (gspn_fwd_stream_big.hip)
@@ -26,13 +26,13 @@ static hipError_t launch_stream_general(const FwdParams& p, int dtype, hipStream
 
 hipError_t launch_fwd_stream(const FwdParams& p, int dtype, hipStream_t s) {
     if (!plan_stream(p, dtype).ok) return launch_stream_big(p, dtype, false, s);
-    if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, false, s);
+    if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, dtype, false, s);
     return launch_stream_general(p, dtype, s, false);
 }
 
 hipError_t launch_reverse_sweep_stream(const FwdParams& p, int dtype, hipStream_t s) {
     if (!plan_stream(p, dtype).ok) return launch_stream_big(p, dtype, true, s);
-    if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, true, s);
+    if (staged_stream_enabled() && stream_staged_applicable(p, dtype)) return launch_stream_staged(p, dtype, true, s);
     return launch_stream_general(p, dtype, s, true);
 }
 

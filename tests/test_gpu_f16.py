@@ -1,8 +1,7 @@
 """GPU parity of the scan calls in fp16 (IEEE binary16) storage against the fp64 oracle, through the C ABI.
 
-fp16 storage runs every kernel family bf16 storage does except the whole-line variant of the stream kernel (its maps
-take the general stream kernel) and the single-launch backward tile kernel (the two passes, else the generic kernel);
-the tile kernels in workgroups of at most four waves.  Tolerance: 1.25e-3 (max|gpu - oracle| / max|oracle| per
+fp16 storage runs every kernel family bf16 storage does except the single-launch backward tile kernel (the two passes,
+else the generic kernel); the tile kernels in workgroups of at most four waves.  Tolerance: 1.25e-3 (max|gpu - oracle| / max|oracle| per
 tensor): the bf16 bound scaled by the ratio of the two formats' rounding units; both sides consume the same
 storage-rounded inputs, and the oracle's backward consumes its own states rounded to fp16 like h_save is.
 """
@@ -97,10 +96,14 @@ def test_f16_on_the_tile_kernel_for_128_rows(monkeypatch):
     check_bwd(cfg)
 
 
-# the general stream kernel (maps beyond the LDS tile: rows and columns in multiples of 64)
+# the stream kernels (maps beyond the LDS tile: rows and columns in multiples of 64): the whole-line variant with one and
+# with two channels per workgroup, on 512, 256 and fewer rows; the general kernel with the variant switched off
+@pytest.mark.parametrize("general", [False, True], ids=["whole-line", "general"])
 @pytest.mark.parametrize("shape", [(1, 2, 256, 256, 1), (1, 4, 128, 256, 2), (1, 2, 192, 512, 2), (1, 2, 512, 512, 2),
-                                   (1, 2, 256, 1024, 1)], ids=lambda s: "x".join(map(str, s)))
-def test_f16_on_the_stream_kernel(shape):
+                                   (1, 2, 256, 1024, 1), (1, 3, 512, 512, 1), (1, 2, 256, 512, 2)], ids=lambda s: "x".join(map(str, s)))
+def test_f16_on_the_stream_kernels(shape, general, monkeypatch):
+    if general:
+        monkeypatch.setenv("GSPN_STREAM_NO_STAGED", "1")
     B, C, H, W, Gr = shape
     assert plans(B, C, H, W, Gr) == ("stream", "twopass")
     cfg = WL.ScanConfig("f16stream", B, C, H, W, Gr, "f16", 15, 1.0, 137)

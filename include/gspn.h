@@ -33,8 +33,8 @@
  * Pointers are DEVICE pointers (hipMalloc'ed or equivalent), 16-byte aligned,
  * owned by the caller; inputs and outputs must not alias.  The library keeps no
  * pointer after a call returns, allocates nothing and frees nothing.
- * Element types (`dtype`): GSPN_F32 (fp32), GSPN_BF16 (bfloat16) and GSPN_F16 (IEEE binary16; the scan calls and their
- * plan queries -- the proxy projections and the per-line-launch comparator take the first two only).  fp16 values are
+ * Element types (`dtype`): GSPN_F32 (fp32), GSPN_BF16 (bfloat16) and GSPN_F16 (IEEE binary16), in every entry point.
+ * fp16 values are
  * converted by the hardware: to nearest even, subnormals kept, a result beyond 65504 becomes infinity (the states of a
  * scan with row-stochastic weights stay within the range of lam * x, so that is a matter of the caller's scaling).
  *
@@ -191,7 +191,7 @@ unsigned long long gspn_unfused_workspace_bytes(int B, int C, int H, int W);
  * axis that takes x from C channels to C_proxy before the scan, and the learned 1x1 projection back to C after it:
  *     out[b][m][h][w] = sum_k P[m][k] * in[b][k][h][w]
  *   in  [B,K,H,W]   P [M,K] row-major   out [B,M,H,W]   (down: K = C, M = C_proxy; up: K = C_proxy, M = C)
- * The scan in the proxy space is an ordinary gspn_scan_fwd on [B,C_proxy,H,W].  bf16 storage with K and H*W
+ * The scan in the proxy space is an ordinary gspn_scan_fwd on [B,C_proxy,H,W].  16-bit storage (bf16, fp16) with K and H*W
  * multiples of 8 runs on the matrix cores (fp32 accumulation, one rounding per output); other shapes and fp32
  * storage run a plain FMA kernel.  Pointers, stream and errors as for the scan calls. */
 int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int H, int W, int dtype,
@@ -204,7 +204,7 @@ int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, i
  *   gP      out [M,K] in fp32 whatever the storage type, or NULL (not computed; at least one of gin, gP is required)
  *   partial workspace of the caller's, B*M*K floats, required with gP (NULL otherwise): it receives the per-image
  *           sums, which a second small kernel adds in image order -- no atomics, the result is bitwise repeatable.
- * The library still allocates nothing.  bf16 storage runs on the matrix cores when M (for gin) and H*W (both; for gP
+ * The library still allocates nothing.  16-bit storage runs on the matrix cores when M (for gin) and H*W (both; for gP
  * a multiple of 16) allow, as in the forward call; other shapes and fp32 storage run plain FMA kernels. */
 int gspn_proxy_project_bwd(const void* gout, const void* in, const void* P, void* gin, float* gP, float* partial,
                            int B, int K, int M, int H, int W, int dtype, void* stream);

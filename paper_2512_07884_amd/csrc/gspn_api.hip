@@ -74,7 +74,6 @@ int gspn_scan_fwd_unfused(const void* x, const void* w, const void* lam, const v
     if (!x || !w || !lam || !u || !y || !workspace) return GSPN_ERR_NULL;
     int st = check_common(B, C, H, W, G, dir_mask, dtype, flags);
     if (st != GSPN_OK) return st;
-    if (dtype == GSPN_F16) return GSPN_ERR_DTYPE;             // the comparator exists in fp32 and bf16 storage
     if (misaligned(x) || misaligned(w) || misaligned(lam) || misaligned(u) || misaligned(y) || misaligned(workspace) ||
         (h_save && misaligned(h_save)))
         return GSPN_ERR_ALIGN;
@@ -227,7 +226,7 @@ int gspn_proxy_project(const void* in, const void* P, void* out, int B, int K, i
                        void* stream) {
     if (!in || !P || !out) return GSPN_ERR_NULL;
     if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1) return GSPN_ERR_SHAPE;
-    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16 && dtype != GSPN_F16) return GSPN_ERR_DTYPE;
     if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
     if ((long long)H * W >= (1ll << 31)) return GSPN_ERR_UNSUPPORTED;
     if (misaligned(in) || misaligned(P) || misaligned(out)) return GSPN_ERR_ALIGN;
@@ -239,7 +238,7 @@ int gspn_proxy_project_bwd(const void* gout, const void* in, const void* P, void
                            int B, int K, int M, int H, int W, int dtype, void* stream) {
     if (!gout || !in || !P || (!gin && !gP) || (gP && !partial)) return GSPN_ERR_NULL;
     if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1) return GSPN_ERR_SHAPE;
-    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16 && dtype != GSPN_F16) return GSPN_ERR_DTYPE;
     if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
     if ((long long)H * W >= (1ll << 31) || (long long)M * K >= (1ll << 31)) return GSPN_ERR_UNSUPPORTED;
     if (misaligned(gout) || misaligned(in) || misaligned(P) || misaligned(gin) || misaligned(gP) || misaligned(partial))
@@ -252,7 +251,7 @@ int gspn_proxy_project_bwd_static(const void* gout, const void* in, const void* 
                                   int B, int K, int M, int H, int W, int dtype, void* stream) {
     if (!gout || !in || !P || (!gin && !gP)) return GSPN_ERR_NULL;
     if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1) return GSPN_ERR_SHAPE;
-    if (dtype != GSPN_F32 && dtype != GSPN_BF16) return GSPN_ERR_DTYPE;
+    if (dtype != GSPN_F32 && dtype != GSPN_BF16 && dtype != GSPN_F16) return GSPN_ERR_DTYPE;
     if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE) return GSPN_ERR_UNSUPPORTED;
     if ((long long)H * W >= (1ll << 31) || (long long)M * K >= (1ll << 31)) return GSPN_ERR_UNSUPPORTED;
     if (gP && (long long)B * M * K > (long long)GSPN_PROXY_STATIC_MAX_FLOATS) return GSPN_ERR_UNSUPPORTED;
@@ -262,7 +261,7 @@ int gspn_proxy_project_bwd_static(const void* gout, const void* in, const void* 
 }
 
 const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype) {
-    if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1 || (dtype != GSPN_F32 && dtype != GSPN_BF16)) return "invalid";
+    if (B < 1 || K < 1 || M < 1 || H < 1 || W < 1 || (dtype != GSPN_F32 && dtype != GSPN_BF16 && dtype != GSPN_F16)) return "invalid";
     if (H > GSPN_MAX_LINE || W > GSPN_MAX_LINE || (long long)H * W >= (1ll << 31)) return "invalid";
     return proxy_mfma_applicable(B, K, M, H * W, dtype) ? "mfma" : "fma";
 }
@@ -272,7 +271,7 @@ const char* gspn_status_string(int status) {
         case GSPN_OK: return "ok";
         case GSPN_ERR_NULL: return "a required pointer is NULL";
         case GSPN_ERR_SHAPE: return "bad shape: dimensions and kchunk must be >= 1, C divisible by G, dir_mask in 1..15";
-        case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32, GSPN_BF16 or GSPN_F16 (the proxy projections: GSPN_F32 or GSPN_BF16)";
+        case GSPN_ERR_DTYPE: return "dtype must be GSPN_F32, GSPN_BF16 or GSPN_F16";
         case GSPN_ERR_ALIGN: return "pointers must be 16-byte aligned";
         case GSPN_ERR_UNSUPPORTED: return "unsupported: line longer than GSPN_MAX_LINE (GSPN_MAX_LINE_LOGITS with logits), unknown flag, or B*M*K beyond the static workspace";
         case GSPN_ERR_HIP: return "HIP launch failed";

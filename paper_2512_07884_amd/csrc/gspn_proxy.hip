@@ -23,15 +23,28 @@ namespace {
 typedef short bf16x4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+// one 32x32 matrix-core step over 8 / 16 k values of 16-bit operands (T = bf16_t or f16_t; the two formats share the
+// operand layout), fp32 accumulation
+template <typename T> __device__ __forceinline__ f32x16_t mfma_k8(const u32x2& a, const u32x2& b, const f32x16_t& c) {
+    if constexpr (__is_same(T, f16_t)) return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(f16x4_t, a), __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(bf16x4_t, a), __builtin_bit_cast(bf16x4_t, b), c, 0, 0, 0);
+}
+template <typename T> __device__ __forceinline__ f32x16_t mfma_k16(const u32x4& a, const u32x4& b, const f32x16_t& c) {
+    if constexpr (__is_same(T, f16_t)) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
 
 // KS = k values per MFMA: 8 (v_mfma_f32_32x32x8_bf16_1k) or 16 (v_mfma_f32_32x32x16_bf16, K a multiple of 16).
 // A lane feeds KS/2 consecutive k: lanes 0-31 the first half of the k-step, lanes 32-63 the second.
 // PT: the matrix is applied transposed, out[b][m][n] = sum_k P[k][m] * in[b][k][n] with P stored [K][M] (the gradient of
 // the projection w.r.t. its input): a lane then gathers its KS/2 values of P with 2-byte loads a row apart (P is small
 // and stays in cache).
-template <int KS, bool PT = false>
-__global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restrict__ in, const bf16_t* __restrict__ P,
-                                                         bf16_t* __restrict__ out, int B, int K, int M, int N,
+template <typename T, int KS, bool PT = false>
+__global__ void __launch_bounds__(256) proxy_mfma_kernel(const T* __restrict__ in, const T* __restrict__ P,
+                                                         T* __restrict__ out, int B, int K, int M, int N,
                                                          int ntiles, int mtiles) {
     constexpr int KL = KS / 2;                                 // k-rows per lane and k-step
     const int lane = threadIdx.x & 63;
@@ -92,12 +105,10 @@ __global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restric
             for (int i = 0; i < KL / 2; ++i) bb[i] = __builtin_amdgcn_perm(t.q[2 * i + 1][v >> 1], t.q[2 * i][v >> 1], sel);
             if constexpr (KS == 8) {
                 const u32x2 av = {t.pa[0], t.pa[1]}, bv = {bb[0], bb[1]};
-                acc[v] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(bf16x4_t, av), __builtin_bit_cast(bf16x4_t, bv),
-                                                                  acc[v], 0, 0, 0);
+                acc[v] = mfma_k8<T>(av, bv, acc[v]);
             } else {
                 const u32x4 av = {t.pa[0], t.pa[1], t.pa[2], t.pa[3]}, bv = {bb[0], bb[1], bb[2], bb[3]};
-                acc[v] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av), __builtin_bit_cast(bf16x8_t, bv),
-                                                                 acc[v], 0, 0, 0);
+                acc[v] = mfma_k16<T>(av, bv, acc[v]);
             }
         }
     };
@@ -119,8 +130,8 @@ __global__ void __launch_bounds__(256) proxy_mfma_kernel(const bf16_t* __restric
     for (int r = 0; r < 16; ++r) {
         const int m = mt * 32 + 8 * (r >> 2) + 4 * kh + (r & 3);
         if (m < M) {
-            const u32x4 o = {pack_bf16x2(acc[0][r], acc[1][r]), pack_bf16x2(acc[2][r], acc[3][r]),
-                             pack_bf16x2(acc[4][r], acc[5][r]), pack_bf16x2(acc[6][r], acc[7][r])};
+            const u32x4 o = {pack_word<T>(acc[0][r], acc[1][r]), pack_word<T>(acc[2][r], acc[3][r]),
+                             pack_word<T>(acc[4][r], acc[5][r]), pack_word<T>(acc[6][r], acc[7][r])};
             st_b128(ob, (uint32_t)(((size_t)m * N + n_lane) * 2), o);
         }
     }
@@ -154,8 +165,8 @@ __global__ void __launch_bounds__(256) proxy_fma_kernel(const T* __restrict__ in
 // (image, 32 x 32 tile of gP); its NW waves take interleaved 16-pixel steps of n and add their accumulators through
 // LDS in wave order; the per-image sums go to the caller's workspace and a small kernel adds the images in order, so the
 // result does not depend on scheduling.  NW = 8 where four waves per tile would leave the chip short of loads in flight.
-template <int NW>
-__global__ void __launch_bounds__(64 * NW) proxy_gradw_mfma_kernel(const bf16_t* __restrict__ gout, const bf16_t* __restrict__ in,
+template <typename T, int NW>
+__global__ void __launch_bounds__(64 * NW) proxy_gradw_mfma_kernel(const T* __restrict__ gout, const T* __restrict__ in,
                                                                float* __restrict__ partial, int K, int M, int N,
                                                                int mtiles, int ktiles) {
     __shared__ float red[NW][16][64];
@@ -188,7 +199,7 @@ __global__ void __launch_bounds__(64 * NW) proxy_gradw_mfma_kernel(const bf16_t*
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av[q]), __builtin_bit_cast(bf16x8_t, bv[q]), acc, 0, 0, 0);
+            acc = mfma_k16<T>(av[q], bv[q], acc);
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
@@ -258,31 +269,61 @@ __global__ void __launch_bounds__(256) proxy_gradw_sum_kernel(const float* __res
 }  // namespace
 
 bool proxy_mfma_applicable(int B, int K, int M, int N, int dtype) {
-    if (dtype != 1 || K % 8 || N % 8) return false;
+    if (dtype == 0 || K % 8 || N % 8) return false;
     // 32-bit byte offsets inside one image of `in` / `out` and inside P
     return (size_t)K * N * 2 < (1ull << 31) && (size_t)M * N * 2 < (1ull << 31) && (size_t)M * K * 2 < (1ull << 31);
 }
 
-hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int N, int dtype,
-                                hipStream_t s) {
-    if (proxy_mfma_applicable(B, K, M, N, dtype)) {
-        const int ntiles = (N + 255) / 256, mtiles = (M + 31) / 32;
-        const long items = (long)B * ntiles * mtiles;
-        if ((items + 3) / 4 > 0x7fffffffl) return hipErrorInvalidValue;
-        const dim3 grid((unsigned)((items + 3) / 4)), block(256);
-        if (K % 16 == 0)
-            hipLaunchKernelGGL(proxy_mfma_kernel<16>, grid, block, 0, s, (const bf16_t*)in, (const bf16_t*)P, (bf16_t*)out,
-                               B, K, M, N, ntiles, mtiles);
-        else
-            hipLaunchKernelGGL(proxy_mfma_kernel<8>, grid, block, 0, s, (const bf16_t*)in, (const bf16_t*)P, (bf16_t*)out,
-                               B, K, M, N, ntiles, mtiles);
-        return hipGetLastError();
+// out = P in (PT = false) or P^T in (PT = true: the gradient w.r.t. the projection's input) in storage type T
+template <typename T, bool PT>
+static hipError_t launch_project_as(const void* in, const void* P, void* out, int B, int K, int M, int N, bool mfma, hipStream_t s) {
+    if constexpr (sizeof(T) == 2) {
+        if (mfma) {
+            const int ntiles = (N + 255) / 256, mtiles = (M + 31) / 32;
+            const long items = (long)B * ntiles * mtiles;
+            if ((items + 3) / 4 > 0x7fffffffl) return hipErrorInvalidValue;
+            const dim3 grid((unsigned)((items + 3) / 4)), block(256);
+            if (K % 16 == 0)
+                hipLaunchKernelGGL((proxy_mfma_kernel<T, 16, PT>), grid, block, 0, s, (const T*)in, (const T*)P, (T*)out, B, K, M, N, ntiles, mtiles);
+            else
+                hipLaunchKernelGGL((proxy_mfma_kernel<T, 8, PT>), grid, block, 0, s, (const T*)in, (const T*)P, (T*)out, B, K, M, N, ntiles, mtiles);
+            return hipGetLastError();
+        }
     }
     const long threads = (long)B * N;
     if ((threads + 255) / 256 > 0x7fffffffl) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
-    if (dtype == 0) hipLaunchKernelGGL(proxy_fma_kernel<float>, grid, block, 0, s, (const float*)in, (const float*)P, (float*)out, B, K, M, N);
-    else hipLaunchKernelGGL(proxy_fma_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)in, (const bf16_t*)P, (bf16_t*)out, B, K, M, N);
+    hipLaunchKernelGGL((proxy_fma_kernel<T, PT>), grid, block, 0, s, (const T*)in, (const T*)P, (T*)out, B, K, M, N);
+    return hipGetLastError();
+}
+
+hipError_t launch_proxy_project(const void* in, const void* P, void* out, int B, int K, int M, int N, int dtype,
+                                hipStream_t s) {
+    const bool mfma = proxy_mfma_applicable(B, K, M, N, dtype);
+    if (dtype == 0) return launch_project_as<float, false>(in, P, out, B, K, M, N, false, s);
+    if (dtype == 1) return launch_project_as<bf16_t, false>(in, P, out, B, K, M, N, mfma, s);
+    return launch_project_as<f16_t, false>(in, P, out, B, K, M, N, mfma, s);
+}
+
+// per-image sums of gout in^T into `partial` (B*M*K floats), storage type T
+template <typename T>
+static hipError_t launch_gradw_as(const void* gout, const void* in, float* partial, int B, int K, int M, int N, hipStream_t s) {
+    const bool mfma = sizeof(T) == 2 && N % 16 == 0 && (size_t)N * 2 * 32 < (1ull << 31);
+    const int ktiles = (K + 31) / 32, mtiles = mfma ? (M + 31) / 32 : (M + 7) / 8;
+    const long blocks = (long)B * mtiles * ktiles;
+    if (blocks > 0x7fffffffl) return hipErrorInvalidValue;
+    const bool wide = blocks * 4 < 2048;     // eight waves per tile while four would leave a compute unit under eight
+    if constexpr (sizeof(T) == 2) {
+        if (mfma && wide)
+            hipLaunchKernelGGL((proxy_gradw_mfma_kernel<T, 8>), dim3((unsigned)blocks), dim3(512), 0, s, (const T*)gout, (const T*)in,
+                               partial, K, M, N, mtiles, ktiles);
+        else if (mfma)
+            hipLaunchKernelGGL((proxy_gradw_mfma_kernel<T, 4>), dim3((unsigned)blocks), dim3(256), 0, s, (const T*)gout, (const T*)in,
+                               partial, K, M, N, mtiles, ktiles);
+        if (mfma) return hipGetLastError();
+    }
+    hipLaunchKernelGGL(proxy_gradw_fma_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, (const T*)gout, (const T*)in,
+                       partial, K, M, N, mtiles, ktiles);
     return hipGetLastError();
 }
 
@@ -292,47 +333,17 @@ hipError_t launch_proxy_project_bwd(const void* gout, const void* in, const void
                                     int B, int K, int M, int N, int dtype, hipStream_t s) {
     if (gin) {
         // the forward kernels with the matrix read transposed: K output channels, contraction over the M channels of gout
-        if (proxy_mfma_applicable(B, M, K, N, dtype)) {
-            const int ntiles = (N + 255) / 256, mtiles = (K + 31) / 32;
-            const long items = (long)B * ntiles * mtiles;
-            if ((items + 3) / 4 > 0x7fffffffl) return hipErrorInvalidValue;
-            const dim3 grid((unsigned)((items + 3) / 4)), block(256);
-            if (M % 16 == 0)
-                hipLaunchKernelGGL((proxy_mfma_kernel<16, true>), grid, block, 0, s, (const bf16_t*)gout, (const bf16_t*)P,
-                                   (bf16_t*)gin, B, M, K, N, ntiles, mtiles);
-            else
-                hipLaunchKernelGGL((proxy_mfma_kernel<8, true>), grid, block, 0, s, (const bf16_t*)gout, (const bf16_t*)P,
-                                   (bf16_t*)gin, B, M, K, N, ntiles, mtiles);
-        } else {
-            const long threads = (long)B * N;
-            if ((threads + 255) / 256 > 0x7fffffffl) return hipErrorInvalidValue;
-            const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
-            if (dtype == 0) hipLaunchKernelGGL((proxy_fma_kernel<float, true>), grid, block, 0, s, (const float*)gout, (const float*)P, (float*)gin, B, M, K, N);
-            else hipLaunchKernelGGL((proxy_fma_kernel<bf16_t, true>), grid, block, 0, s, (const bf16_t*)gout, (const bf16_t*)P, (bf16_t*)gin, B, M, K, N);
-        }
-        const hipError_t e = hipGetLastError();
+        const bool mfma = proxy_mfma_applicable(B, M, K, N, dtype);
+        const hipError_t e = dtype == 0 ? launch_project_as<float, true>(gout, P, gin, B, M, K, N, false, s)
+                           : dtype == 1 ? launch_project_as<bf16_t, true>(gout, P, gin, B, M, K, N, mfma, s)
+                                        : launch_project_as<f16_t, true>(gout, P, gin, B, M, K, N, mfma, s);
         if (e != hipSuccess) return e;
     }
     if (gP) {
         if (!partial) return hipErrorInvalidValue;
-        const bool mfma = dtype == 1 && N % 16 == 0 && (size_t)N * 2 * 32 < (1ull << 31);
-        const int ktiles = (K + 31) / 32, mtiles = mfma ? (M + 31) / 32 : (M + 7) / 8;
-        const long blocks = (long)B * mtiles * ktiles;
-        if (blocks > 0x7fffffffl) return hipErrorInvalidValue;
-        const bool wide = blocks * 4 < 2048;     // eight waves per tile while four would leave a compute unit under eight
-        if (mfma && wide)
-            hipLaunchKernelGGL(proxy_gradw_mfma_kernel<8>, dim3((unsigned)blocks), dim3(512), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
-                               partial, K, M, N, mtiles, ktiles);
-        else if (mfma)
-            hipLaunchKernelGGL(proxy_gradw_mfma_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
-                               partial, K, M, N, mtiles, ktiles);
-        else if (dtype == 0)
-            hipLaunchKernelGGL(proxy_gradw_fma_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)gout, (const float*)in,
-                               partial, K, M, N, mtiles, ktiles);
-        else
-            hipLaunchKernelGGL(proxy_gradw_fma_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)gout, (const bf16_t*)in,
-                               partial, K, M, N, mtiles, ktiles);
-        hipError_t e = hipGetLastError();
+        hipError_t e = dtype == 0 ? launch_gradw_as<float>(gout, in, partial, B, K, M, N, s)
+                     : dtype == 1 ? launch_gradw_as<bf16_t>(gout, in, partial, B, K, M, N, s)
+                                  : launch_gradw_as<f16_t>(gout, in, partial, B, K, M, N, s);
         if (e != hipSuccess) return e;
         const int MK = M * K;
         hipLaunchKernelGGL(proxy_gradw_sum_kernel, dim3((unsigned)((MK + 255) / 256)), dim3(256), 0, s, partial, gP, B, MK);

@@ -70,7 +70,8 @@ hipError_t launch_fwd_unfused(const FwdParams& p, int dtype, void* workspace, hi
             float* prev = (t & 1) ? buf0 : buf1;
             float* cur = (t & 1) ? buf1 : buf0;
             if (dtype == 0) hipLaunchKernelGGL((line_step_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, p, prev, cur, d, t, first_dir);
-            else hipLaunchKernelGGL((line_step_kernel<bf16_t>), dim3((unsigned)blocks), dim3(256), 0, s, p, prev, cur, d, t, first_dir);
+            else if (dtype == 1) hipLaunchKernelGGL((line_step_kernel<bf16_t>), dim3((unsigned)blocks), dim3(256), 0, s, p, prev, cur, d, t, first_dir);
+            else hipLaunchKernelGGL((line_step_kernel<f16_t>), dim3((unsigned)blocks), dim3(256), 0, s, p, prev, cur, d, t, first_dir);
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -116,11 +116,9 @@ def test_fp16_storage_dispatches_like_bf16_storage(lib, monkeypatch):
     assert lib.gspn_bwd_plan(2, 8, 56, 56, 2, 15, BF16, 0).decode() == "tile" and lib.gspn_bwd_plan(2, 8, 56, 56, 2, 15, F16, 0).decode() == "generic"
     monkeypatch.delenv("GSPN_BWD_NO_TWOPASS")
     lib.gspn_reload_env()
-    # the comparator and the proxy projections exist in fp32 and bf16 storage only
-    p = ctypes.c_void_p(0x1000)
-    assert lib.gspn_scan_fwd_unfused(p, p, p, p, p, None, p, 1 << 30, 1, 4, 8, 8, 2, 15, F16, 0, None) == 3
-    assert lib.gspn_proxy_project(p, p, p, 1, 8, 4, 8, 8, F16, None) == 3
-    assert lib.gspn_proxy_plan(1, 8, 4, 8, 8, F16).decode() == "invalid"
+    # the proxy projections run on the matrix cores in either 16-bit type
+    assert lib.gspn_proxy_plan(2, 96, 8, 56, 56, F16).decode() == "mfma" and lib.gspn_proxy_plan(1, 12, 3, 5, 7, F16).decode() == "fma"
+    assert lib.gspn_proxy_plan(1, 8, 4, 8, 8, 3).decode() == "invalid"
 
 
 def test_plan_names(lib):

@@ -26,7 +26,9 @@ def run_project(x_st, P_st, dtype):
 # 1152 -> 144 of the diffusion study, Sec. 4.2 / App. "low rank"), several row tiles, ragged pixel and row tiles
 SHAPES = [(2, 96, 8, 56, 56, "bf16"), (2, 8, 96, 56, 56, "bf16"), (1, 96, 2, 28, 28, "bf16"), (1, 1152, 144, 16, 16, "bf16"),
           (1, 144, 1152, 16, 16, "bf16"), (3, 40, 33, 12, 10, "bf16"), (1, 8, 1, 2, 4, "bf16"), (1, 64, 70, 24, 40, "bf16"),
-          (2, 96, 8, 28, 28, "f32"), (1, 7, 5, 9, 13, "f32"), (1, 12, 3, 5, 7, "bf16"), (1, 10, 4, 8, 8, "bf16")]
+          (2, 96, 8, 28, 28, "f32"), (1, 7, 5, 9, 13, "f32"), (1, 12, 3, 5, 7, "bf16"), (1, 10, 4, 8, 8, "bf16"),
+          (2, 96, 8, 56, 56, "f16"), (2, 8, 96, 56, 56, "f16"), (1, 1152, 144, 16, 16, "f16"), (3, 40, 33, 12, 10, "f16"),
+          (1, 12, 3, 5, 7, "f16")]
 
 
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -36,8 +38,8 @@ def test_projection_matches_the_oracle(shape):
     rng = np.random.default_rng([11, K, M, H])
     x = WL.to_storage(rng.standard_normal((B, K, H, W)), dtype)
     P = WL.to_storage(rng.standard_normal((M, K)) / np.sqrt(K), dtype)
-    want = "mfma" if dtype == "bf16" and K % 8 == 0 and (H * W) % 8 == 0 else "fma"
-    assert G.gspn_proxy_plan(B, K, M, H, W, int(dtype == "bf16")) == want
+    want = "mfma" if dtype != "f32" and K % 8 == 0 and (H * W) % 8 == 0 else "fma"
+    assert G.gspn_proxy_plan(B, K, M, H, W, {"f32": 0, "bf16": 1, "f16": 2}[dtype]) == want
     ref = O.proxy_project(WL.storage_to_f64(x, dtype), WL.storage_to_f64(P, dtype))
     got = run_project(x, P, dtype)
     assert rel_inf_err(got, ref) <= TOL[dtype], rel_inf_err(got, ref)
@@ -100,7 +102,9 @@ def run_project_bwd(g_st, x_st, P_st, dtype, want_gin=True, want_gp=True):
 # plain kernels (fp32, C_proxy = 2, ragged pixel counts), several tiles of gP with ragged edges
 BWD_SHAPES = [(2, 96, 8, 56, 56, "bf16"), (2, 8, 96, 56, 56, "bf16"), (1, 96, 2, 28, 28, "bf16"), (1, 1152, 144, 16, 16, "bf16"),
               (1, 144, 1152, 16, 16, "bf16"), (3, 40, 33, 12, 10, "bf16"), (1, 64, 70, 24, 40, "bf16"), (2, 96, 8, 28, 28, "f32"),
-              (1, 7, 5, 9, 13, "f32"), (1, 12, 3, 5, 7, "bf16"), (2, 40, 16, 12, 12, "bf16"), (2, 70, 24, 8, 6, "f32")]
+              (1, 7, 5, 9, 13, "f32"), (1, 12, 3, 5, 7, "bf16"), (2, 40, 16, 12, 12, "bf16"), (2, 70, 24, 8, 6, "f32"),
+              (2, 96, 8, 56, 56, "f16"), (2, 8, 96, 56, 56, "f16"), (1, 144, 1152, 16, 16, "f16"), (3, 40, 33, 12, 10, "f16"),
+              (1, 12, 3, 5, 7, "f16")]
 
 
 @pytest.mark.parametrize("shape", BWD_SHAPES, ids=lambda s: "x".join(map(str, s)))

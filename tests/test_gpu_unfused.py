@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("shape", [(2, 6, 9, 13, 3, "f32", 15), (1, 4, 33, 70, 2, "bf16", 15), (1, 2, 64, 64, 1, "f32", 5),
-                                   (1, 3, 40, 24, 3, "bf16", 10)], ids=lambda s: "x".join(map(str, s)))
+                                   (1, 3, 40, 24, 3, "bf16", 10), (1, 4, 33, 70, 2, "f16", 15)], ids=lambda s: "x".join(map(str, s)))
 def test_per_line_launch_comparator_matches_the_oracle(shape):
     import torch
     import paper_2512_07884_amd as G

@@ -151,6 +151,10 @@ __device__ __forceinline__ void chain_request_first(const FwdParams& p, int b, i
 // how many of them are made early: all five in the plain forward scan; with h_save / in the reverse sweep the
 // horizontal tasks hold more registers (the states on their way out), and one or two is what fits beside them
 // (with the logits normalised on the way in, the forward call with h_save has no register left for even one)
+// a line is a whole wave here, so the lane shifts deliver the zeros at its ends (see line_update); the GSPN-local forward
+// call with h_save in fp16 storage keeps the explicit selects: without them its register allocation went to scratch memory
+template <typename T, bool SAVE, bool BWD, bool LOCAL> constexpr bool wave_line() { return !(__is_same(T, f16_t) && SAVE && !BWD && LOCAL); }
+
 template <bool SAVE, bool BWD, bool LOGITS = false> constexpr int early_requests() { return SAVE ? (BWD ? 2 : (LOGITS ? 0 : 1)) : 5; }
 
 // ... and the chain itself, after chain_request_first() for the same (b, c).
@@ -203,7 +207,7 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
             const uint32_t xw = xr[slot][k], lw = lr[slot][k], uw = ur[slot][k];
             float av[2] = {word_lo<T>(lw) * word_lo<T>(xw), word_hi<T>(lw) * word_hi<T>(xw)};
             if constexpr (BWD) {
-                line_update_transposed<2>(h, av, wp0, wp1, wp2, first, last);
+                line_update_transposed<2, wave_line<T, SAVE, BWD, LOCAL>()>(h, av, wp0, wp1, wp2, first, last);
                 bool starts = false;
                 if constexpr (LOCAL) starts = bstretch.start(s == VNBANDS - 1 && k == VBAND - 1);
                 // the taps this row hands on to the row swept next; a tap that points outside the line takes nothing,
@@ -223,7 +227,7 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
                         if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
                     }
                 }
-                line_update<2>(h, av, c0, c1, c2, first, last);
+                line_update<2, wave_line<T, SAVE, BWD, LOCAL>()>(h, av, c0, c1, c2, first, last);
             }
             const float y0 = word_lo<T>(uw) * h[0], y1 = word_hi<T>(uw) * h[1];
             tile[tile_row(row) * TPITCH + lane] = pack_word<T>(word_lo<T>(ow[k]) + y0, word_hi<T>(ow[k]) + y1);
@@ -453,7 +457,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
             float c2[2] = {elem<T>(b20, e), elem<T>(b21, e)};
             if constexpr (LOGITS) { softmax3(c0[0], c1[0], c2[0], first, false); softmax3(c0[1], c1[1], c2[1], false, last); }
             if constexpr (BWD) {
-                line_update_transposed<2>(h, av, wp0, wp1, wp2, first, last);
+                line_update_transposed<2, wave_line<T, SAVE, BWD, LOCAL>()>(h, av, wp0, wp1, wp2, first, last);
                 bool starts = false;
                 if constexpr (LOCAL) starts = bwalk.start(ch == 1 && k == CS - 1);
                 // the taps this column hands on to the column swept next; a tap that points outside the line takes nothing
@@ -470,7 +474,7 @@ __device__ __forceinline__ void pair_body(const FwdParams& p, uint32_t* tiles, c
                         if constexpr (LOCAL) h[v] = start ? 0.f : h[v];
                     }
                 }
-                line_update<2>(h, av, c0, c1, c2, first, last);
+                line_update<2, wave_line<T, SAVE, BWD, LOCAL>()>(h, av, c0, c1, c2, first, last);
             }
             const float cv[2] = {elem<T>(bu0, e) * h[0], elem<T>(bu1, e) * h[1]};
             if ((k & 1) == 0) { cpair[0] = cv[0]; cpair[1] = cv[1]; hpair[0] = h[0]; hpair[1] = h[1]; }

@@ -117,13 +117,17 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // One line of Eq. 1 for the lane's V positions.  `first`/`last`: the lane holds the first/last
 // positions of its line, whose outer neighbour does not exist: both the neighbour value and its
 // weight are forced to 0 so that nothing stored for it (NaN, Inf) can leak in.
-template <int V>
+// WAVE_LINE: the line spans the whole wave (first = lane 0, last = lane 63), so the lane shifts themselves deliver the
+// zeros at its ends and only the weights need the selects.
+template <int V, bool WAVE_LINE = false>
 __device__ __forceinline__ void line_update(float (&h)[V], const float (&a)[V], const float (&w0)[V],
                                             const float (&w1)[V], const float (&w2)[V], bool first, bool last) {
     float lin = from_lane_below(h[V - 1]);
     float rin = from_lane_above(h[0]);
-    lin = first ? 0.f : lin;
-    rin = last ? 0.f : rin;
+    if constexpr (!WAVE_LINE) {
+        lin = first ? 0.f : lin;
+        rin = last ? 0.f : rin;
+    }
     const float wl = first ? 0.f : w0[0];
     const float wr = last ? 0.f : w2[V - 1];
     float hn[V];
@@ -142,7 +146,7 @@ __device__ __forceinline__ void line_update(float (&h)[V], const float (&a)[V], 
 // The same for the reverse sweep of the backward pass, e_t = a_t + T_{t+1}^T e_{t+1} (chain rule on Eq. 1): every position
 // multiplies its own state by the three taps of the line swept before (`wp*`, the line after it in scan order) and hands
 // the products to the positions those taps read from.  h holds e of that line on entry and of this line on exit.
-template <int V>
+template <int V, bool WAVE_LINE = false>
 __device__ __forceinline__ void line_update_transposed(float (&h)[V], const float (&a)[V], const float (&wp0)[V],
                                                        const float (&wp1)[V], const float (&wp2)[V], bool first, bool last) {
     float q0[V], q2[V];
@@ -150,8 +154,10 @@ __device__ __forceinline__ void line_update_transposed(float (&h)[V], const floa
     for (int v = 0; v < V; ++v) { q0[v] = wp0[v] * h[v]; q2[v] = wp2[v] * h[v]; }
     float lin = from_lane_below(q2[V - 1]);      // tap 2 of position j-1 reads position j
     float rin = from_lane_above(q0[0]);          // tap 0 of position j+1 reads position j
-    lin = first ? 0.f : lin;
-    rin = last ? 0.f : rin;
+    if constexpr (!WAVE_LINE) {
+        lin = first ? 0.f : lin;
+        rin = last ? 0.f : rin;
+    }
     float hn[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) {

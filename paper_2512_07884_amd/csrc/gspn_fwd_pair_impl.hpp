@@ -192,9 +192,17 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
         uint32_t t0[VBAND], t1[VBAND], t2[VBAND], ow[VBAND];
 #pragma unroll
         for (int k = 0; k < VBAND; ++k) { t0[k] = cw[k * 64]; t1[k] = cw[VBAND * 64 + k * 64]; t2[k] = cw[2 * VBAND * 64 + k * 64]; }
+        // the band's four image rows sit at fixed distances in the tile (tile_row of a multiple of four plus 0..3): one
+        // address per band, the rows through constant offsets -- in the calls that save states (measured: train128
+        // backward 0.469 -> 0.459 ms; the plain forward scan is 1.5 % faster with an address per row, 0.178 / 0.175 ms)
+        uint32_t* const band_tile = tile + (UP ? PH / 2 - 2 - 2 * s : 2 * s) * TPITCH + lane;
+        auto tile_word = [&](int k) -> uint32_t& {
+            if constexpr (SAVE) return band_tile[tile_row(UP ? VBAND - 1 - k : k) * TPITCH];
+            else return tile[tile_row(chain_row<UP>(s, k)) * TPITCH + lane];
+        };
         if (s >= VNBANDS / 2) {
 #pragma unroll
-            for (int k = 0; k < VBAND; ++k) ow[k] = tile[tile_row(chain_row<UP>(s, k)) * TPITCH + lane];
+            for (int k = 0; k < VBAND; ++k) ow[k] = tile_word(k);
         } else {
 #pragma unroll
             for (int k = 0; k < VBAND; ++k) ow[k] = 0;
@@ -230,7 +238,7 @@ __device__ __forceinline__ void vertical_chain(const FwdParams& p, char* region,
                 line_update<2, wave_line<T, SAVE, BWD, LOCAL>()>(h, av, c0, c1, c2, first, last);
             }
             const float y0 = word_lo<T>(uw) * h[0], y1 = word_hi<T>(uw) * h[1];
-            tile[tile_row(row) * TPITCH + lane] = pack_word<T>(word_lo<T>(ow[k]) + y0, word_hi<T>(ow[k]) + y1);
+            tile_word(k) = pack_word<T>(word_lo<T>(ow[k]) + y0, word_hi<T>(ow[k]) + y1);
             if constexpr (SAVE) {
                 const uint32_t hw = pack_word<T>(h[0], h[1]);
                 __builtin_amdgcn_raw_buffer_store_b32(hw, t.hb, voff, __builtin_amdgcn_readfirstlane(row * ROW_B), CP_STREAM);

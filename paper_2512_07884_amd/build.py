@@ -46,8 +46,6 @@ SPILL_ALLOWED = {
     # the same in fp16 storage, and its GSPN-local forward with h_save (96 values, none in the band loop either; the
     # hardware conversions hold a few registers more than the shifts of bf16): parity-tested at full size
     "fwd_pair_kernelINS_5f16_tELb1ELb0ELb1ELb1": 144, "fwd_pair_kernelINS_5f16_tELb1ELb0ELb1ELb0": 96,
-    # fp16 reverse sweep of the global scan: 24 values parked in the accumulation registers between the phases (no scratch)
-    "fwd_pair_kernelINS_5f16_tELb1ELb1ELb0ELb0": 24,
     # fp32 maps with rows of 112 bytes on workgroups of more than four waves, without h_save: off every benchmark shape
     # (the plane kernel takes 28x28, the four-wave instantiation 56x56); kept because the shapes must run somewhere
     "fwd_tile_kernelIfLi2ELi1ELi28ELb0ELi8ELb0ELi8ELb0ELb0ELb0": 259, "fwd_tile_kernelIfLi2ELi1ELi28ELb0ELi8ELb0ELi8ELb1ELb0ELb0": 47,

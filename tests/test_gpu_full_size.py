@@ -17,13 +17,22 @@ from paper_2512_07884_amd import workloads as WL
 pytestmark = pytest.mark.gpu
 
 FULL = ["cls56", "diff128", "long512", "long256x1024", "train28_gc", "train28_g4"]
+# ... and the two target shapes in fp16 storage ("name:f16")
+FULL_F16 = ["diff128:f16", "long512:f16"]
 
 
-@pytest.mark.parametrize("name", FULL)
+def config_of(name):
+    """A benchmark configuration by name; "name:f16" = the same shape and inputs in fp16 storage."""
+    base, _, storage = name.partition(":")
+    cfg = WL.CONFIGS[base]
+    return WL.shrink(cfg, dtype=storage) if storage else cfg
+
+
+@pytest.mark.parametrize("name", FULL + FULL_F16)
 def test_full_size_sampled_slices_match_the_oracle(name):
     import torch
     import paper_2512_07884_amd as G
-    cfg = WL.CONFIGS[name]
+    cfg = config_of(name)
     inp = WL.make_inputs(cfg, with_gy=False)
     dev = {k: to_device(v, cfg.dtype) for k, v in inp.items()}
     y = empty_like_dev(inp["x"].shape, cfg.dtype, float("nan"))
@@ -78,14 +87,14 @@ def test_full_size_constant_line_invariant(name):
     assert err <= TOL[cfg.dtype], (name, err)
 
 
-@pytest.mark.parametrize("name", ["train28_gc", "train28_g4", "train56", "train128", "train512"])
+@pytest.mark.parametrize("name", ["train28_gc", "train28_g4", "train56", "train128", "train512", "train128:f16"])
 def test_full_size_training_step_sampled_slices_match_the_oracle(name):
     """Forward with h_save + backward at the benchmark's size; sampled (batch, group) slices of every
     gradient are recomputed by the oracle from the same stored inputs (its own hidden states).  On the 512x512 map a
     slice is 32 channels of 2^18 pixels, about 15 s of oracle time, so three slices are taken there instead of six."""
     import torch
     import paper_2512_07884_amd as G
-    cfg = WL.CONFIGS[name]
+    cfg = config_of(name)
     inp = WL.make_inputs(cfg, with_gy=True)
     dev = {k: to_device(v, cfg.dtype) for k, v in inp.items()}
     nan = float("nan")

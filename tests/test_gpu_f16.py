@@ -15,6 +15,7 @@ from test_gpu_fwd import check_case
 from test_gpu_bwd import check_bwd
 from test_gpu_local import check_local
 from test_gpu_logits import check_logits
+from test_gpu_transposed import check as check_transposed
 
 pytestmark = pytest.mark.gpu
 
@@ -188,6 +189,13 @@ def test_f16_local_scans(shape, kchunk, monkeypatch):
                          ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
 def test_f16_weights_as_logits(shape, kchunk):
     check_logits(shape, kchunk=kchunk, poison=True)
+
+
+# the forward scan with the horizontal directions stored transposed (tile kernel in its transposed layout, generic kernel)
+@pytest.mark.parametrize("shape", [(1, 4, 128, 128, 2, "f16"), (2, 8, 56, 56, 2, "f16"), (1, 4, 33, 70, 2, "f16")],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_f16_with_the_horizontal_directions_stored_transposed(shape):
+    check_transposed(shape)
 
 
 def test_f16_values_beyond_bf16_resolution_survive():

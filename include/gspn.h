@@ -229,11 +229,11 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  * weights or logits: two channels of a group per workgroup, the merged output accumulated on chip in storage precision, i.e. rounded
  * after each of the four additions), "tile" (maps whose merged output fits in LDS), "stream"
  * (larger maps with rows and columns in multiples of 64: up to 512 rows and lines of 256, 512 or 1024 positions in
- * one launch; the global scan also on up to 2048 rows (beyond 1024: in multiples of 128) and lines of 256 to 2048
- * positions, in two launches -- the vertical pair, then the horizontal pair; the merged output is accumulated in
- * place in y), "twopass" (backward
+ * one launch; also up to 1024 rows and lines of 256 to 2048 positions -- and, for the global scan with normalised
+ * weights, up to 2048 rows in multiples of 128 -- in two launches: the vertical pair, then the horizontal pair; the
+ * merged output is accumulated in place in y), "twopass" (backward
  * on the maps the forward plane, tile or stream kernels take: the reverse sweep per
- * channel on those kernels, then the sum over each group's channels; in bf16
+ * channel on those kernels, then the sum over each group's channels; in 16-bit
  * storage e passes through storage precision between the two), "generic" (any shape);
  * static string, never NULL.  Host only.
  *

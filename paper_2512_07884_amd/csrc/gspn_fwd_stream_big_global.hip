@@ -1,0 +1,10 @@
+// Maps beyond 512 rows, the global scan with normalised weights (see gspn_fwd_stream_big.hip).
+#include "gspn_fwd_stream_big_impl.hpp"
+
+namespace gspn {
+
+hipError_t launch_stream_big_global(const FwdParams& p, int dtype, bool reverse, hipStream_t s) {
+    return launch_big_family<false, false>(p, dtype, reverse, s);
+}
+
+}  // namespace gspn

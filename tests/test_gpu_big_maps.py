@@ -110,3 +110,27 @@ def test_scaling_shape_1024x1024_on_sampled_slices():
              for n in ("x", "w", "lam", "u")}
         y_ref, _ = O.scan_fwd(f["x"], f["w"], f["lam"], f["u"], 15)
         assert rel_inf_err(y[b:b + 1, cs], y_ref) <= TOL["f32"], (b, g)
+
+
+# GSPN-local and logits calls on maps of 513 to 1024 rows: the same two launches with the stretch bookkeeping and the
+# softmax of the line objects; forward with and without h_save and the two-pass backward; stretch lengths that divide
+# the map and that do not; the first line of every stretch and the taps that point outside a line never read
+@pytest.mark.parametrize("shape,kchunk", [((1, 2, 1024, 256, 1, "bf16"), 64), ((1, 2, 640, 512, 2, "f32"), 100),
+                                          ((1, 2, 1024, 256, 1, "f16"), 37), ((1, 4, 576, 256, 2, "bf16"), 1)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_local_scans_on_maps_beyond_512_rows(shape, kchunk):
+    import paper_2512_07884_amd as G
+    from test_gpu_local import check_local
+    B, C, H, W, Gr, dtype = shape
+    dt = {"f32": 0, "bf16": 1, "f16": 2}[dtype]
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, True) == "stream"
+    assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0) == "twopass"
+    check_local(shape, kchunk, poison_starts=True)
+
+
+@pytest.mark.parametrize("shape,kchunk", [((1, 2, 1024, 256, 1, "bf16"), None), ((1, 2, 640, 256, 2, "f32"), None),
+                                          ((1, 2, 1024, 256, 1, "f16"), 128), ((1, 4, 576, 256, 2, "bf16"), 50)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_logits_on_maps_beyond_512_rows(shape, kchunk):
+    from test_gpu_logits import check_logits
+    check_logits(shape, kchunk=kchunk, poison=True, fwd_plan="stream", bwd_plan="twopass")

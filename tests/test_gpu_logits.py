@@ -36,7 +36,7 @@ def check_logits(shape, kchunk=None, mask=15, seed=101, scale=1.5, poison=False,
                 if r > 0:
                     z[3, :, :, :, :, r - 1] = nan
     k = kchunk if kchunk else 1 << 14
-    dt = int(dtype == "bf16")
+    dt = {"f32": 0, "bf16": 1, "f16": 2}[dtype]
     if fwd_plan:
         assert G.gspn_fwd_logits_plan(B, C, H, W, Gr, k, mask, dt, 0, True) == fwd_plan
     if bwd_plan:

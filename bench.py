@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused 4-direction GSPN scan on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kchunk K] [--logits] [--storage f32|bf16|f16] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--kchunk K] [--logits] [--storage f32|bf16|f16] [--throughput-table] [--all]
 
 A step is one pass of the whole hot path over one batch of synthetic input:
 one ``gspn_scan_fwd`` call covering all four directions (inference workloads),
@@ -380,6 +380,34 @@ def chunk_axis_table(steps: int = 200, kchunk: int = 32):
     return rows
 
 
+# the eight shapes of the paper's global-memory throughput table (Table 1): (H = W, B, C).  The table gives neither the
+# group count nor the storage type; eight channels per weight group (the ratio of the benchmark's classifier stage) and
+# bf16 storage are taken here, and fp32 beside it
+THROUGHPUT_TABLE_SHAPES = ((32, 32, 196), (64, 1, 768), (64, 1, 1152), (64, 1, 32), (128, 1, 32), (256, 1, 64), (256, 8, 64),
+                           (512, 1, 128))
+
+
+def throughput_table(steps: int = 100):
+    """Forward scan on the shapes of Table 1: time per launch and the algorithmic bytes it moves per second.  (The paper's
+    column is the memory throughput a profiler reports while its kernel runs; the figure here is the end-to-end one --
+    compulsory bytes over launch time -- so shapes with fewer planes than the chip has compute units show their idle
+    units in it.)"""
+    from paper_2512_07884_amd import workloads as WL
+    rows = []
+    for hw, B, C in THROUGHPUT_TABLE_SHAPES:
+        for dtype in ("bf16", "f32"):
+            G_ = max(1, C // 8)
+            while C % G_:
+                G_ -= 1
+            cfg = WL.ScanConfig(f"table1_{hw}_{B}_{C}", B, C, hw, hw, G_, dtype, 15, 1.0, 17)
+            s = summarise(cfg, run_workload(cfg, steps, 10))
+            rows.append({"shape": f"{hw}x{hw}, B={B}, C={C}, G={G_}, {dtype}", "planes": B * C, "kernel": s["fwd_kernel"],
+                         "fwd_ms": s["fwd_ms_avg"], "algorithmic_bytes": s["fwd_algorithmic_bytes"],
+                         "GBs": s["fwd_algorithmic_bytes"] / (s["fwd_ms_avg"] * 1e-3) / 1e9,
+                         "frac_of_hbm_peak": s["fwd_algorithmic_bytes"] / (s["fwd_ms_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS})
+    return rows
+
+
 def copy_calibration(n_bytes: int = 1 << 30, reps: int = 5):
     """Plain copies of a known size: each must read and write exactly n_bytes, which
     fixes the unit in which the profiler's FETCH_SIZE / WRITE_SIZE counters report."""
@@ -412,6 +440,8 @@ def main():
                     help="also time the per-line-launch comparator against the fused forward (table under detail.fused_vs_unfused)")
     ap.add_argument("--chunk-axis", action="store_true",
                     help="also time GSPN-local against the global scan on the low-occupancy shape (detail.local_chunk_axis)")
+    ap.add_argument("--throughput-table", action="store_true",
+                    help="also time the forward scan on the eight shapes of the paper's throughput table (detail.throughput_table)")
     ap.add_argument("--all", action="store_true", help="also time every other workload (table in the --out folder)")
     ap.add_argument("--out", default="bench_out", help="folder for the --all table, relative to the repository root")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -494,6 +524,8 @@ def main():
         line["detail"]["fused_vs_unfused"] = unfused_table()
     if a.chunk_axis:
         line["detail"]["local_chunk_axis"] = chunk_axis_table()
+    if a.throughput_table:
+        line["detail"]["throughput_table"] = throughput_table()
     if a.all:
         table = [s]
         for name, c in WL.CONFIGS.items():

@@ -246,6 +246,8 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  *   GSPN_FWD_NO_PAIR=1   skip the "pair" kernels (forward and the reverse sweep of the two-pass backward)
  *   GSPN_STREAM_NO_STAGED=1   the general "stream" kernel (the one fp32 maps, GSPN-local and logits calls take) on the bf16 maps
  *                             that have a kernel of their own
+ *   GSPN_STREAM_TWO_CHANNELS=1  two channels of a weight group per workgroup on those maps also in calls with at most 256
+ *                               planes (which normally keep one channel per workgroup: a compute unit holds one workgroup)
  *   GSPN_STREAM_ONE_CHANNEL=1   the "stream" kernel with one channel per workgroup on 256- and 512-row bf16 maps (two channels of a
  *                               weight group share a workgroup and the weights there otherwise)
  *   GSPN_FWD_NO_CHUNK=1   skip the "chunk" kernels of GSPN-local (forward and the reverse sweep of the two-pass backward) */

@@ -235,6 +235,7 @@ const char* fwd_plan_name(const FwdParams& p, int dtype);
 const char* bwd_plan_name(const BwdParams& p, int dtype);
 bool staged_stream_enabled();  // false while GSPN_STREAM_NO_STAGED=1 keeps the whole-line stream kernel out (testing aid)
 bool pair_kernels_enabled();   // false while GSPN_FWD_NO_PAIR=1 keeps the two-channel kernels out (testing aid)
+bool stream_two_channels_forced();   // true while GSPN_STREAM_TWO_CHANNELS=1 pairs the channels whatever the number of planes (testing aid)
 bool stream_two_channels_enabled();  // false while GSPN_STREAM_ONE_CHANNEL=1 keeps the stream kernel that shares a group's weights between two channels out (testing aid)
 bool chunk_kernels_enabled();  // false while GSPN_FWD_NO_CHUNK=1 keeps the per-stretch kernels of GSPN-local out (testing aid)
 void reload_env_knobs();   // re-reads the GSPN_* testing aids from the environment (they are read once otherwise)

@@ -16,8 +16,9 @@ enum BwdPlan { BWD_GENERIC = 0, BWD_TILE = 1, BWD_PLANE = 2, BWD_TWOPASS = 3 };
 // reverse sweep of the two-pass backward); GSPN_STREAM_NO_STAGED=1: the stream kernel whose horizontal phases request one
 // row per lane instead of the one with whole-line requests; GSPN_FWD_NO_CHUNK=1: skip the per-stretch kernels of GSPN-local
 // (forward and the reverse sweep of the two-pass backward); GSPN_STREAM_ONE_CHANNEL=1: the whole-line stream kernel with one
-// channel per workgroup on the maps where two channels of a group normally share a workgroup.
-enum : unsigned { K_FORCE_GENERIC = 1, K_FWD_NO_PLANE = 2, K_BWD_NO_PLANE = 4, K_BWD_NO_TWOPASS = 8, K_FWD_NO_PAIR = 16, K_STREAM_NO_STAGED = 32, K_FWD_NO_CHUNK = 64, K_STREAM_ONE_CHANNEL = 128, K_VALID = 1u << 31 };
+// channel per workgroup on the maps where two channels of a group normally share a workgroup; GSPN_STREAM_TWO_CHANNELS=1:
+// two channels per workgroup there also in calls with too few planes to fill the chip that way.
+enum : unsigned { K_FORCE_GENERIC = 1, K_FWD_NO_PLANE = 2, K_BWD_NO_PLANE = 4, K_BWD_NO_TWOPASS = 8, K_FWD_NO_PAIR = 16, K_STREAM_NO_STAGED = 32, K_FWD_NO_CHUNK = 64, K_STREAM_ONE_CHANNEL = 128, K_STREAM_TWO_CHANNELS = 256, K_VALID = 1u << 31 };
 static std::atomic<unsigned> g_knobs{0};
 static bool env_flag(const char* name) { const char* v = getenv(name); return v && v[0] == '1'; }
 void reload_env_knobs() {
@@ -30,18 +31,20 @@ void reload_env_knobs() {
     if (env_flag("GSPN_STREAM_NO_STAGED")) k |= K_STREAM_NO_STAGED;
     if (env_flag("GSPN_FWD_NO_CHUNK")) k |= K_FWD_NO_CHUNK;
     if (env_flag("GSPN_STREAM_ONE_CHANNEL")) k |= K_STREAM_ONE_CHANNEL;
+    if (env_flag("GSPN_STREAM_TWO_CHANNELS")) k |= K_STREAM_TWO_CHANNELS;
     g_knobs.store(k, std::memory_order_release);
 }
-struct Knobs { bool force_generic, fwd_no_plane, bwd_no_plane, bwd_no_twopass, fwd_no_pair, stream_no_staged, fwd_no_chunk, stream_one_channel; };
+struct Knobs { bool force_generic, fwd_no_plane, bwd_no_plane, bwd_no_twopass, fwd_no_pair, stream_no_staged, fwd_no_chunk, stream_one_channel, stream_two_channels; };
 static Knobs knobs() {
     unsigned k = g_knobs.load(std::memory_order_acquire);
     if (!(k & K_VALID)) { reload_env_knobs(); k = g_knobs.load(std::memory_order_acquire); }
-    return Knobs{(k & K_FORCE_GENERIC) != 0, (k & K_FWD_NO_PLANE) != 0, (k & K_BWD_NO_PLANE) != 0, (k & K_BWD_NO_TWOPASS) != 0, (k & K_FWD_NO_PAIR) != 0, (k & K_STREAM_NO_STAGED) != 0, (k & K_FWD_NO_CHUNK) != 0, (k & K_STREAM_ONE_CHANNEL) != 0};
+    return Knobs{(k & K_FORCE_GENERIC) != 0, (k & K_FWD_NO_PLANE) != 0, (k & K_BWD_NO_PLANE) != 0, (k & K_BWD_NO_TWOPASS) != 0, (k & K_FWD_NO_PAIR) != 0, (k & K_STREAM_NO_STAGED) != 0, (k & K_FWD_NO_CHUNK) != 0, (k & K_STREAM_ONE_CHANNEL) != 0, (k & K_STREAM_TWO_CHANNELS) != 0};
 }
 bool pair_kernels_enabled() { return !knobs().fwd_no_pair; }
 bool staged_stream_enabled() { return !knobs().stream_no_staged; }
 bool chunk_kernels_enabled() { return !knobs().fwd_no_chunk; }
 bool stream_two_channels_enabled() { return !knobs().stream_one_channel; }
+bool stream_two_channels_forced() { return knobs().stream_two_channels; }
 
 static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     const Knobs k = knobs();

@@ -69,8 +69,9 @@ def test_direction_masks_on_maps_of_more_than_1024_rows(mask):
 
 
 # bf16 maps of 512 rows: the whole-line stream kernel with two channels of a weight group per workgroup (the weights of
-# the horizontal phases fetched once for both), with one channel per workgroup, and the row-per-lane stream kernel
-@pytest.mark.parametrize("knob", [None, "GSPN_STREAM_ONE_CHANNEL", "GSPN_STREAM_NO_STAGED"], ids=["two-channel", "one-channel", "row-per-lane"])
+# the horizontal phases fetched once for both; calls with at most 256 planes pair their channels only under the knob),
+# with one channel per workgroup, and the row-per-lane stream kernel
+@pytest.mark.parametrize("knob", ["GSPN_STREAM_TWO_CHANNELS", None, "GSPN_STREAM_NO_STAGED"], ids=["two-channel", "one-channel", "row-per-lane"])
 @pytest.mark.parametrize("shape", [(1, 4, 512, 512, 2, "bf16"), (1, 4, 512, 1024, 1, "bf16"), (2, 2, 512, 256, 1, "bf16"),
                                    (1, 3, 512, 256, 1, "bf16"), (1, 4, 256, 1024, 2, "bf16"), (2, 2, 256, 256, 1, "bf16"),
                                    (1, 4, 256, 512, 1, "bf16")], ids=lambda v: "x".join(map(str, v)))
@@ -86,7 +87,7 @@ def test_stream_kernel_variants_on_maps_of_256_and_512_rows(shape, knob, monkeyp
 
 # the reverse sweep of the two-pass backward on the same three kernels (two channels per workgroup: eight waves of rows on
 # 512-row maps, both horizontal directions at once on 256-row maps)
-@pytest.mark.parametrize("knob", [None, "GSPN_STREAM_ONE_CHANNEL", "GSPN_STREAM_NO_STAGED"], ids=["two-channel", "one-channel", "row-per-lane"])
+@pytest.mark.parametrize("knob", ["GSPN_STREAM_TWO_CHANNELS", None, "GSPN_STREAM_NO_STAGED"], ids=["two-channel", "one-channel", "row-per-lane"])
 @pytest.mark.parametrize("shape", [(1, 4, 512, 512, 2, "bf16"), (1, 4, 256, 512, 2, "bf16")], ids=lambda s: "x".join(map(str, s)))
 def test_backward_on_maps_of_256_and_512_rows_bf16(shape, knob, monkeypatch):
     if knob:

@@ -99,12 +99,14 @@ def test_f16_on_the_tile_kernel_for_128_rows(monkeypatch):
 
 # the stream kernels (maps beyond the LDS tile: rows and columns in multiples of 64): the whole-line variant with one and
 # with two channels per workgroup, on 512, 256 and fewer rows; the general kernel with the variant switched off
-@pytest.mark.parametrize("general", [False, True], ids=["whole-line", "general"])
+@pytest.mark.parametrize("general", [False, None, True], ids=["whole-line-two-channels", "whole-line", "general"])
 @pytest.mark.parametrize("shape", [(1, 2, 256, 256, 1), (1, 4, 128, 256, 2), (1, 2, 192, 512, 2), (1, 2, 512, 512, 2),
                                    (1, 2, 256, 1024, 1), (1, 3, 512, 512, 1), (1, 2, 256, 512, 2)], ids=lambda s: "x".join(map(str, s)))
 def test_f16_on_the_stream_kernels(shape, general, monkeypatch):
     if general:
         monkeypatch.setenv("GSPN_STREAM_NO_STAGED", "1")
+    elif general is False:
+        monkeypatch.setenv("GSPN_STREAM_TWO_CHANNELS", "1")    # (so few planes keep one channel per workgroup otherwise)
     B, C, H, W, Gr = shape
     assert plans(B, C, H, W, Gr) == ("stream", "twopass")
     cfg = WL.ScanConfig("f16stream", B, C, H, W, Gr, "f16", 15, 1.0, 137)

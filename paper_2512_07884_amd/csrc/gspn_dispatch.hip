@@ -51,7 +51,13 @@ static FwdPlan choose_fwd(const FwdParams& p, int dtype) {
     if (k.force_generic) return FWD_GENERIC;
     // GSPN-local with few planes: the stretches as work items (Sec. 4.1), before any one-workgroup-per-plane kernel
     if (!k.fwd_no_chunk && fwd_chunk_applicable(p, dtype)) return FWD_CHUNK;
-    if (!k.fwd_no_plane && fwd_plane_applicable(p, dtype)) return FWD_PLANE;
+    if (!k.fwd_no_plane && fwd_plane_applicable(p, dtype)) {
+        // the largest planes the plane kernel takes in 16-bit storage (more than 6.5 KB: 64x56, 64x64), forward without
+        // h_save: the tile kernel was measured faster (B = 8, C = 768: 64x64 0.250 -> 0.207 ms, 64x56 0.233 -> 0.193 ms;
+        // one image with 1152 channels 85 -> 56 us); with h_save, and from 56x56 down, the plane kernel is
+        if (dtype != 0 && !p.hs && (size_t)p.H * p.W * 2 > 6656 && fwd_tile_applicable(p, dtype)) return FWD_TILE;
+        return FWD_PLANE;
+    }
     if (!k.fwd_no_pair && fwd_pair_applicable(p, dtype)) return FWD_PAIR;
     if (fwd_tile_applicable(p, dtype)) return FWD_TILE;
     return fwd_stream_applicable(p, dtype) ? FWD_STREAM : FWD_GENERIC;

@@ -34,15 +34,15 @@
  * owned by the caller; inputs and outputs must not alias.  The library keeps no
  * pointer after a call returns, allocates nothing and frees nothing.
  * Element types (`dtype`): GSPN_F32 (fp32), GSPN_BF16 (bfloat16) and GSPN_F16 (IEEE binary16), in every entry point.
- * fp16 values are
- * converted by the hardware: to nearest even, subnormals kept, a result beyond 65504 becomes infinity (the states of a
- * scan with row-stochastic weights stay within the range of lam * x, so that is a matter of the caller's scaling).
+ * fp16 values are converted by the hardware: to nearest even, subnormals kept, a result beyond 65504 becomes infinity
+ * (with row-stochastic weights the states of a scan are running sums of lam * x, so that is a matter of the caller's
+ * scaling).
  *
  * Arithmetic: inputs are widened to fp32, the carried state and all sums are
  * fp32, each stored value is rounded once to nearest-even -- except the merged
  * bf16 / fp16 y / gx where the running sum over the directions is kept in storage
  * precision (feature maps too large to stage on chip, merged in place in global
- * memory, and 128x128 maps on the "pair" kernels, whose on-chip tile is bf16):
+ * memory, and 128x128 maps on the "pair" kernels, whose on-chip tile is in storage precision):
  * at most one extra rounding per direction.
  *
  * Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL = the

@@ -11,7 +11,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgspn.so")
-SOURCES = ["gspn_api.hip", "gspn_dispatch.hip", "gspn_generic.hip", "gspn_unfused.hip", "gspn_fwd_tile.hip", "gspn_fwd_tile_f32_global.hip", "gspn_fwd_tile_f32_local.hip", "gspn_fwd_tile_bf16_global.hip", "gspn_fwd_tile_bf16_local.hip", "gspn_fwd_tile_f16_global.hip", "gspn_fwd_tile_f16_local.hip", "gspn_fwd_stream.hip", "gspn_fwd_stream_f32.hip", "gspn_fwd_stream_bf16.hip", "gspn_fwd_stream_f16.hip", "gspn_fwd_stream_staged.hip", "gspn_fwd_stream_staged_bf16.hip", "gspn_fwd_stream_staged_f16.hip", "gspn_fwd_stream_big.hip", "gspn_fwd_stream_big_global.hip", "gspn_fwd_stream_big_local.hip", "gspn_fwd_plane.hip", "gspn_fwd_pair.hip", "gspn_fwd_pair_bf16.hip", "gspn_fwd_pair_f16.hip", "gspn_fwd_chunk.hip", "gspn_bwd_tile.hip", "gspn_bwd_plane.hip", "gspn_bwd_twopass.hip", "gspn_bwd_twopass_f32.hip", "gspn_bwd_twopass_bf16.hip", "gspn_bwd_twopass_f32_local.hip", "gspn_bwd_twopass_bf16_local.hip", "gspn_bwd_twopass_f16.hip", "gspn_bwd_twopass_f16_local.hip", "gspn_proxy.hip"]
+SOURCES = ["gspn_api.hip", "gspn_dispatch.hip", "gspn_generic.hip", "gspn_unfused.hip", "gspn_fwd_tile.hip", "gspn_fwd_tile_f32_global.hip", "gspn_fwd_tile_f32_local.hip", "gspn_fwd_tile_bf16_global.hip", "gspn_fwd_tile_bf16_local.hip", "gspn_fwd_tile_f16_global.hip", "gspn_fwd_tile_f16_local.hip", "gspn_fwd_stream.hip", "gspn_fwd_stream_f32.hip", "gspn_fwd_stream_bf16.hip", "gspn_fwd_stream_f16.hip", "gspn_fwd_stream_staged.hip", "gspn_fwd_stream_staged_bf16.hip", "gspn_fwd_stream_staged_f16.hip", "gspn_fwd_stream_big.hip", "gspn_fwd_stream_big_global.hip", "gspn_fwd_stream_big_local.hip", "gspn_fwd_stream_big_logits.hip", "gspn_fwd_plane.hip", "gspn_fwd_pair.hip", "gspn_fwd_pair_bf16.hip", "gspn_fwd_pair_f16.hip", "gspn_fwd_chunk.hip", "gspn_bwd_tile.hip", "gspn_bwd_plane.hip", "gspn_bwd_twopass.hip", "gspn_bwd_twopass_f32.hip", "gspn_bwd_twopass_bf16.hip", "gspn_bwd_twopass_f32_local.hip", "gspn_bwd_twopass_bf16_local.hip", "gspn_bwd_twopass_f16.hip", "gspn_bwd_twopass_f16_local.hip", "gspn_proxy.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -199,7 +199,7 @@ def gspn_scan_fwd(x, w, lam, u, y, h_save=None, *, G: Optional[int] = None, dir_
 
     x [B,C,H,W]; w [4,B,G,3,H,W]; lam, u [4,B,C,H,W] ([1,...] with
     GSPN_FLAG_SHARED_PARAMS); y [B,C,H,W]; h_save [4,B,C,H,W] or None.
-    All device tensors of one dtype (float32 / bfloat16), contiguous.
+    All device tensors of one dtype (float32 / bfloat16 / float16), contiguous.
     """
     ptrs, dims = _fwd_args(x, w, lam, u, y, h_save, G, flags)
     _check(load_library().gspn_scan_fwd(*ptrs, *dims, dir_mask, _dtype_code(x), flags, _stream(stream)))

@@ -1,4 +1,4 @@
-// Backward GSPN scan for very small feature maps (fp32 or bf16 storage, H, W <= 32: the 28x28
+// Backward GSPN scan for very small feature maps (fp32 or 16-bit storage, H, W <= 32: the 28x28
 // training stage): every tensor crosses the memory system exactly once, as whole planes.
 //
 // The paper gives timings but no algorithm for the backward pass (Sec. 5.1); this is the chain rule

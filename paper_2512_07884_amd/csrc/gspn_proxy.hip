@@ -137,7 +137,7 @@ __global__ void __launch_bounds__(256) proxy_mfma_kernel(const T* __restrict__ i
     }
 }
 
-// any shape, either storage type: one thread per pixel, eight output channels at a time
+// any shape, any storage type: one thread per pixel, eight output channels at a time
 template <typename T, bool PT = false>
 __global__ void __launch_bounds__(256) proxy_fma_kernel(const T* __restrict__ in, const T* __restrict__ P, T* __restrict__ out,
                                                         int B, int K, int M, int N) {
@@ -215,7 +215,7 @@ __global__ void __launch_bounds__(64 * NW) proxy_gradw_mfma_kernel(const T* __re
     }
 }
 
-// any shape, either storage type: a workgroup owns 8 rows x 32 columns of gP for one image and walks n in chunks of 64
+// any shape, any storage type: a workgroup owns 8 rows x 32 columns of gP for one image and walks n in chunks of 64
 // staged through LDS (coalesced loads along n; pitch 65 keeps the per-thread walks conflict-free)
 template <typename T>
 __global__ void __launch_bounds__(256) proxy_gradw_fma_kernel(const T* __restrict__ gout, const T* __restrict__ in,

@@ -98,3 +98,13 @@ def test_unit_config_distributions():
     assert inp["x"].shape == (1, 8, 16, 16) and inp["w"].shape == (4, 1, 1, 3, 16, 16)
     assert 0 <= inp["lam"].min() and inp["lam"].max() < 1 and 0 <= inp["u"].min() and inp["u"].max() < 1
     assert abs(inp["x"].mean()) < 0.1 and 0.9 < inp["x"].std() < 1.1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU: bench.py says so and exits before it touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and not r.stdout.strip()

@@ -37,6 +37,26 @@ constexpr int BLOCK_B = 64 * SPITCH * 16;         // 64 rows of 128 bytes
 constexpr int MAILBOX_FLOATS = 2 * 8 * 4;         // [direction slot][part][side][parity]
 constexpr int LDS_BYTES = 8 * 2 * BLOCK_B + MAILBOX_FLOATS * 4;
 
+// the stretch bookkeeping of GSPN-local, or nothing at all: the global scan's instantiations carry no trace of it
+template <bool ON> struct WalkIf {
+    StretchWalk w;
+    __device__ __forceinline__ void init(int S, int reversed, int kchunk) { w.init(S, reversed, kchunk); }
+    __device__ __forceinline__ bool start() { return w.start(); }
+};
+template <> struct WalkIf<false> {
+    __device__ __forceinline__ void init(int, int, int) {}
+    __device__ __forceinline__ bool start() { return false; }
+};
+template <bool ON> struct WalkBackIf {
+    StretchWalkBack w;
+    __device__ __forceinline__ void init(int S, int reversed, int kchunk) { w.init(S, reversed, kchunk); }
+    __device__ __forceinline__ bool start(bool at_step0) { return w.start(at_step0); }
+};
+template <> struct WalkBackIf<false> {
+    __device__ __forceinline__ void init(int, int, int) {}
+    __device__ __forceinline__ bool start(bool) { return false; }
+};
+
 template <int CP = 0> __device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t voff, int soff) {
     return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, __builtin_amdgcn_readfirstlane(soff), CP);
 }
@@ -44,7 +64,7 @@ template <int CP = 0> __device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t
 // One horizontal direction for the wave that owns rows 64 * part .. of the plane.  Chunks [0, nchunks) in scan order;
 // `sync_at`: chunk before which the whole workgroup meets (the two directions swap halves there; -1: never);
 // `rmw_from`: first chunk (in scan order) whose y already holds a partial sum.
-template <typename T, bool REV, bool SAVE, bool BWD>
+template <typename T, bool REV, bool SAVE, bool BWD, bool LOCAL>
 __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a, char* blk_b, float* mailbox, int parts, int b, int c,
                                                 int dslot, int part, int lane, int sync_at, int rmw_from) {
     constexpr int d = (REV != BWD) ? 3 : 2;
@@ -119,6 +139,12 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
     };
 
     float h = 0.f, wp0 = 0.f, wp1 = 0.f, wp2 = 0.f;
+    // GSPN-local (Sec. 3.2): the wave walks in the scan order of direction REV ? 3 : 2 (forward) or against that of
+    // direction REV ? 2 : 3 (reverse sweep); a column that starts a stretch takes nothing from the column before it
+    WalkIf<LOCAL && !BWD> walk;
+    WalkBackIf<LOCAL && BWD> bwalk;
+    walk.init(W, REV ? 1 : 0, p.kchunk);
+    bwalk.init(W, REV ? 0 : 1, p.kchunk);
 #pragma unroll
     for (int q = 0; q < 8; ++q) issue_slot(0, q);
     if (0 >= rmw_from && 0 != sync_at) issue_y(0);
@@ -163,14 +189,18 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
                 up = top_lane ? (has_up ? pu : 0.f) : up;
                 dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
                 h = fmaf(wp1, h, av) + (up + dn);
-                wp0 = img_first ? 0.f : c0;
-                wp1 = c1;
-                wp2 = img_last ? 0.f : c2;
+                bool starts = false;
+                if constexpr (LOCAL) starts = bwalk.start(ch == nchunks - 1 && k == CS - 1);     // hands nothing on to the column swept next
+                wp0 = (img_first || starts) ? 0.f : c0;
+                wp1 = starts ? 0.f : c1;
+                wp2 = (img_last || starts) ? 0.f : c2;
                 if (publishes) mb_out[par * 2] = bot_lane ? wp2 * h : wp0 * h;
             } else {
-                if (k == 0) {
-                    const bool start = ch == 0;                  // scan step 0: its weights are never read
+                if (LOCAL || k == 0) {
+                    bool start = ch == 0 && k == 0;              // scan step 0: its weights are never read
+                    if constexpr (LOCAL) start = walk.start();      // ... nor those of a stretch's first column
                     c0 = start ? 0.f : c0; c1 = start ? 0.f : c1; c2 = start ? 0.f : c2;
+                    if constexpr (LOCAL) h = start ? 0.f : h;
                 }
                 float up = from_lane_below(h), dn = from_lane_above(h);
                 up = top_lane ? (has_up ? pu : 0.f) : up;
@@ -220,7 +250,7 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
 // already holds the vertical pair's sum.  Maps of 512 rows run one direction at a time (all eight waves hold rows,
 // sync_at < 0); maps of 256 rows both at once, four waves each (direction slot dslot), each first on the half of the
 // columns it starts in and, after the workgroup has met before chunk sync_at, on the other half.
-template <typename T, bool REV, bool SAVE, bool BWD>
+template <typename T, bool REV, bool SAVE, bool BWD, bool LOCAL>
 __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a, char* blk_b, float* mailbox, int parts, int b, int c,
                                                  int dslot, int part, int lane, int sync_at) {
     constexpr int d = (REV != BWD) ? 3 : 2;
@@ -288,6 +318,12 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
         __builtin_amdgcn_sched_barrier(0);
     };
 
+    // GSPN-local: the two channels take the same 64 steps of a chunk, so both start from the walk's state at the chunk's
+    // first step, and the state after them is kept once channel B is through
+    WalkIf<LOCAL && !BWD> walk;
+    WalkBackIf<LOCAL && BWD> bwalk;
+    walk.init(W, REV ? 1 : 0, p.kchunk);
+    bwalk.init(W, REV ? 0 : 1, p.kchunk);
     float hA = 0.f, hB = 0.f;
     float wpA0 = 0.f, wpA1 = 0.f, wpA2 = 0.f, wpB0 = 0.f, wpB1 = 0.f, wpB2 = 0.f;     // BWD: taps of the column swept before, per channel
 
@@ -295,6 +331,8 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
     auto steps = [&](const bool second, int ch) __attribute__((always_inline)) {
         float h = second ? hB : hA;
         float wp0 = second ? wpB0 : wpA0, wp1 = second ? wpB1 : wpA1, wp2 = second ? wpB2 : wpA2;
+        auto wk = walk;
+        auto bwk = bwalk;
         // mailbox: [channel][part][parity] pairs, as in horizontal_rows
         float* const task = mailbox + (dslot * 2 + (second ? 1 : 0)) * parts * 4;
         const f32x2_hw* const mb_in = (const f32x2_hw*)(task + part * 4);
@@ -320,14 +358,18 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
                 up = top_lane ? (has_up ? pu : 0.f) : up;
                 dn = bot_lane ? (has_dn ? pd : 0.f) : dn;
                 h = fmaf(wp1, h, av) + (up + dn);
-                wp0 = img_first ? 0.f : c0;
-                wp1 = c1;
-                wp2 = img_last ? 0.f : c2;
+                bool starts = false;
+                if constexpr (LOCAL) starts = bwk.start(ch == nchunks - 1 && k == CS - 1);     // hands nothing on to the column swept next
+                wp0 = (img_first || starts) ? 0.f : c0;
+                wp1 = starts ? 0.f : c1;
+                wp2 = (img_last || starts) ? 0.f : c2;
                 if (publishes) mb_out[par * 2] = bot_lane ? wp2 * h : wp0 * h;
             } else {
-                if (k == 0) {
-                    const bool start = ch == 0;                  // scan step 0: its weights are never read
+                if (LOCAL || k == 0) {
+                    bool start = ch == 0 && k == 0;              // scan step 0: its weights are never read
+                    if constexpr (LOCAL) start = wk.start();      // ... nor those of a stretch's first column
                     c0 = start ? 0.f : c0; c1 = start ? 0.f : c1; c2 = start ? 0.f : c2;
+                    if constexpr (LOCAL) h = start ? 0.f : h;
                 }
                 float up = from_lane_below(h), dn = from_lane_above(h);
                 up = top_lane ? (has_up ? pu : 0.f) : up;
@@ -358,7 +400,7 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        if (second) { hB = h; wpB0 = wp0; wpB1 = wp1; wpB2 = wp2; }
+        if (second) { hB = h; wpB0 = wp0; wpB1 = wp1; wpB2 = wp2; walk = wk; bwalk = bwk; }
         else { hA = h; wpA0 = wp0; wpA1 = wp1; wpA2 = wp2; }
     };
     auto y_to_block = [&]() {
@@ -397,7 +439,7 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
     }
 }
 
-template <typename T, int V, int PF, bool SAVE, bool BWD>
+template <typename T, int V, int PF, bool SAVE, bool BWD, bool LOCAL>
 __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
     extern __shared__ char lds[];
     float* mailbox = (float*)(lds + 8 * 2 * BLOCK_B);
@@ -416,12 +458,12 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
         if (nd == 2) {
             const int split = (H + 1) / 2;
             if (wave == 0) {
-                VStream<T, V, PF, false, false, false, BWD, SAVE> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, false, LOCAL, false, BWD, SAVE> v; v.init(p, b, c, lane);
                 v.template run<false>(0, split);
                 __syncthreads();
                 v.template run<true>(split, H);
             } else if (wave == 1) {
-                VStream<T, V, PF, true, false, false, BWD, SAVE> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, true, LOCAL, false, BWD, SAVE> v; v.init(p, b, c, lane);
                 v.template run<false>(0, H - split);
                 __syncthreads();
                 v.template run<true>(H - split, H);
@@ -431,8 +473,8 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
             wrote = true;
         } else if (nd == 1) {
             if (wave == 0) {
-                if ((has_tb != 0) != BWD) { VStream<T, V, PF, false, false, false, BWD, SAVE> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
-                else                      { VStream<T, V, PF, true, false, false, BWD, SAVE> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
+                if ((has_tb != 0) != BWD) { VStream<T, V, PF, false, LOCAL, false, BWD, SAVE> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
+                else                      { VStream<T, V, PF, true, LOCAL, false, BWD, SAVE> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
             }
             wrote = true;
         }
@@ -458,9 +500,9 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
                 for (int st = 0; st < CS; ++st) lds_barrier();      // idle wave: keep the barrier count
             }
         } else if ((dslot == 0) != BWD) {
-            horizontal_rows<T, false, SAVE, BWD>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
+            horizontal_rows<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
         } else {
-            horizontal_rows<T, true, SAVE, BWD>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
+            horizontal_rows<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
         }
     } else {
         // one after the other; waves 0..parts-1 hold the rows
@@ -472,9 +514,9 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
             if (wave >= parts) {
                 for (int st = 0; st < W; ++st) lds_barrier();       // idle wave: keep the barrier count
             } else if ((dsel == 0) != BWD) {
-                horizontal_rows<T, false, SAVE, BWD>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
+                horizontal_rows<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
             } else {
-                horizontal_rows<T, true, SAVE, BWD>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
+                horizontal_rows<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
             }
             wrote = true;
         }
@@ -484,7 +526,7 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
 // Two channels of a weight group per workgroup on maps of 512 or 256 rows, all four directions: the vertical pairs of both
 // channels at the same time (waves 0, 1 and 2, 3), then the horizontal directions one after the other with the weights
 // shared (horizontal_rows2).
-template <typename T, int V, int PF, bool SAVE, bool BWD>
+template <typename T, int V, int PF, bool SAVE, bool BWD, bool LOCAL>
 __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
     extern __shared__ char lds[];
     float* mailbox = (float*)(lds + 8 * 2 * BLOCK_B);
@@ -501,12 +543,12 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         const int split = (H + 1) / 2;
         const int cv = c + (wave >> 1);
         if (wave < 4 && (wave & 1) == 0) {
-            VStream<T, V, PF, false, false, false, BWD, SAVE> v; v.init(p, b, cv, lane);
+            VStream<T, V, PF, false, LOCAL, false, BWD, SAVE> v; v.init(p, b, cv, lane);
             v.template run<false>(0, split);
             __syncthreads();
             v.template run<true>(split, H);
         } else if (wave < 4) {
-            VStream<T, V, PF, true, false, false, BWD, SAVE> v; v.init(p, b, cv, lane);
+            VStream<T, V, PF, true, LOCAL, false, BWD, SAVE> v; v.init(p, b, cv, lane);
             v.template run<false>(0, H - split);
             __syncthreads();
             v.template run<true>(H - split, H);
@@ -522,8 +564,8 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         for (int dsel = 0; dsel < 2; ++dsel) {
             if (threadIdx.x < MAILBOX_FLOATS) mailbox[threadIdx.x] = 0.f;
             __syncthreads();                    // y of the previous phase complete, mailbox cleared
-            if ((dsel == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
-            else horizontal_rows2<T, true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
+            if ((dsel == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
+            else horizontal_rows2<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
         }
     } else {
         // 256 rows: both directions at once, wave -> (direction slot, part)
@@ -531,38 +573,38 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         __syncthreads();                        // y of the vertical pair complete, mailbox cleared
         const int nchunks = p.W / CS;
         const int dslot = wave >> 2, part = wave & 3;
-        if ((dslot == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
-        else horizontal_rows2<T, true, SAVE, BWD>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
+        if ((dslot == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
+        else horizontal_rows2<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
     }
 }
 
-template <typename T, int V, int PF>
+template <typename T, int V, int PF, bool LOCAL>
 static hipError_t launch_staged(const StreamArgs& a, bool reverse, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * a.p.C)), block(512);
-    const void* k = reverse ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, true>
-                  : a.p.hs  ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, false>
-                            : (const void*)fwd_stream_staged_kernel<T, V, PF, false, false>;
+    const void* k = reverse ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, true, LOCAL>
+                  : a.p.hs  ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, false, LOCAL>
+                            : (const void*)fwd_stream_staged_kernel<T, V, PF, false, false, LOCAL>;
     hipError_t e = allow_dynamic_lds(k, LDS_BYTES);
     if (e != hipSuccess) return e;
-    if (reverse) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, true>), grid, block, LDS_BYTES, s, a);
-    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, false>), grid, block, LDS_BYTES, s, a);
-    else hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, false, false>), grid, block, LDS_BYTES, s, a);
+    if (reverse) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, true, LOCAL>), grid, block, LDS_BYTES, s, a);
+    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, false, LOCAL>), grid, block, LDS_BYTES, s, a);
+    else hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, false, false, LOCAL>), grid, block, LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-template <typename T, int V, int PF>
+template <typename T, int V, int PF, bool LOCAL>
 static hipError_t launch_staged2(const StreamArgs& a, bool reverse, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / 2))), block(512);
-    const void* k = reverse ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, true>
-                  : a.p.hs  ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, false>
-                            : (const void*)fwd_stream_staged2_kernel<T, V, PF, false, false>;
+    const void* k = reverse ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, true, LOCAL>
+                  : a.p.hs  ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, false, LOCAL>
+                            : (const void*)fwd_stream_staged2_kernel<T, V, PF, false, false, LOCAL>;
     hipError_t e = allow_dynamic_lds(k, LDS_BYTES);
     if (e != hipSuccess) return e;
-    if (reverse) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, true>), grid, block, LDS_BYTES, s, a);
-    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, false>), grid, block, LDS_BYTES, s, a);
-    else hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, false, false>), grid, block, LDS_BYTES, s, a);
+    if (reverse) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, true, LOCAL>), grid, block, LDS_BYTES, s, a);
+    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, false, LOCAL>), grid, block, LDS_BYTES, s, a);
+    else hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, false, false, LOCAL>), grid, block, LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
@@ -578,25 +620,25 @@ static bool two_channels_ok(const FwdParams& p, const StreamPlan& t) {
            ((size_t)p.B * p.C > CHIP_CUS || stream_two_channels_forced());
 }
 
-// 16-bit storage, the global scan with normalised weights, every shape the stream plan takes
+// 16-bit storage, normalised weights (the global scan or GSPN-local), every shape the stream plan takes
 static bool staged_shape_ok(const FwdParams& p, int dtype) {
-    return dtype != 0 && p.kchunk <= 0 && !p.logits && plan_stream(p, dtype).ok;
+    return dtype != 0 && !p.logits && plan_stream(p, dtype).ok;
 }
 
-template <typename T>
-static hipError_t launch_stream_staged_typed(const FwdParams& p, bool reverse, hipStream_t s) {
+template <typename T, bool LOCAL>
+static hipError_t launch_stream_staged_family(const FwdParams& p, bool reverse, hipStream_t s) {
     const StreamPlan t = plan_stream(p, 1);
     if (!t.ok || !staged_shape_ok(p, 1) || (reverse && !p.hs)) return hipErrorInvalidValue;
     StreamArgs a;
     a.p = p; a.parts = t.parts; a.nwaves = 8;
     if (two_channels_ok(p, t)) {
-        if (t.v == 4) return launch_staged2<T, 4, 4>(a, reverse, s);
-        if (t.v == 8) return launch_staged2<T, 8, 4>(a, reverse, s);
-        return launch_staged2<T, 16, 2>(a, reverse, s);
+        if (t.v == 4) return launch_staged2<T, 4, 4, LOCAL>(a, reverse, s);
+        if (t.v == 8) return launch_staged2<T, 8, 4, LOCAL>(a, reverse, s);
+        return launch_staged2<T, 16, 2, LOCAL>(a, reverse, s);
     }
-    if (t.v == 4) return launch_staged<T, 4, 4>(a, reverse, s);
-    if (t.v == 8) return launch_staged<T, 8, 4>(a, reverse, s);
-    return launch_staged<T, 16, 2>(a, reverse, s);
+    if (t.v == 4) return launch_staged<T, 4, 4, LOCAL>(a, reverse, s);
+    if (t.v == 8) return launch_staged<T, 8, 4, LOCAL>(a, reverse, s);
+    return launch_staged<T, 16, 2, LOCAL>(a, reverse, s);
 }
 
 }  // namespace gspn

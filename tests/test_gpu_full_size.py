@@ -173,3 +173,26 @@ def test_full_size_diffusion_shape_in_the_other_call_forms(mode):
             y_ref, _ = O.scan_fwd(*a, 15)
         err = rel_inf_err(to_host_f64(y[b, cs]), y_ref[0])
         assert err <= TOL[dtype], (mode, b, g, err)
+
+
+def test_full_size_long_scan_shape_with_local_stretches():
+    """long512 (B=1, C=512, 512x512, G=16, bf16) through the GSPN-local call with kchunk = 64, in the launch shape
+    bench.py --workload long512 --kchunk 64 times (two channels of a group per workgroup on the whole-line stream
+    kernel); two (batch, group) slices recomputed by the oracle."""
+    import torch
+    import paper_2512_07884_amd as G
+    cfg = WL.CONFIGS["long512"]
+    k = 64
+    assert G.gspn_fwd_local_plan(cfg.B, cfg.C, cfg.H, cfg.W, cfg.G, k, 15, 1, 0, False) == "stream"
+    inp = WL.make_inputs(cfg, with_gy=False)
+    dev = {n: to_device(v, cfg.dtype) for n, v in inp.items()}
+    y = empty_like_dev(inp["x"].shape, cfg.dtype, float("nan"))
+    G.gspn_scan_fwd_local(dev["x"], dev["w"], dev["lam"], dev["u"], y, None, kchunk=k, G=cfg.G, dir_mask=15)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y.float()).all())
+    for b, g in ((0, 0), (0, cfg.G - 1)):
+        s = WL.inputs_as_f64(WL.make_slice(cfg, b, g, with_gy=False), cfg.dtype)
+        cs = slice(g * cfg.cpg, (g + 1) * cfg.cpg)
+        y_ref, _ = O.scan_fwd_local(s["x"][None], s["w"][:, None, None], s["lam"][:, None], s["u"][:, None], k, 15)
+        err = rel_inf_err(to_host_f64(y[b, cs]), y_ref[0])
+        assert err <= TOL[cfg.dtype], (b, g, err)

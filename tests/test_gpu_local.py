@@ -295,3 +295,24 @@ def test_local_scans_on_the_two_channel_kernel(shape, kchunk, monkeypatch):
     assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, 1, 0, False) == "pair"
     assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, 1, 0) == "twopass"
     check_local(shape, kchunk, poison_starts=True)
+
+
+# GSPN-local on the whole-line stream kernel of the 16-bit maps: one channel per workgroup (calls with few planes) and
+# two channels of a group per workgroup (forced here: both take the same 64 steps of a chunk and share the walk's state);
+# maps of 512 rows (one horizontal direction at a time) and of 256 rows (both at once, each first on its own half of the
+# columns); forward with and without h_save and the two-pass backward; stretches that divide the map and that do not
+@pytest.mark.parametrize("two_channels", [False, True], ids=["one-channel", "two-channels"])
+@pytest.mark.parametrize("shape,kchunk", [((1, 4, 512, 512, 2, "bf16"), 64), ((1, 2, 256, 512, 1, "bf16"), 100),
+                                          ((1, 4, 256, 1024, 2, "f16"), 37), ((1, 2, 512, 256, 1, "f16"), 1),
+                                          ((1, 2, 256, 256, 1, "bf16"), 255)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_local_scans_on_the_whole_line_stream_kernel(shape, kchunk, two_channels, monkeypatch):
+    import paper_2512_07884_amd as G
+    monkeypatch.setenv("GSPN_FWD_NO_CHUNK", "1")           # (short stretches on few planes would go to the chunk-axis kernels)
+    if two_channels:
+        monkeypatch.setenv("GSPN_STREAM_TWO_CHANNELS", "1")
+    B, C, H, W, Gr, dtype = shape
+    dt = {"f32": 0, "bf16": 1, "f16": 2}[dtype]
+    assert G.gspn_fwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0, True) == "stream"
+    assert G.gspn_bwd_local_plan(B, C, H, W, Gr, kchunk, 15, dt, 0) == "twopass"
+    check_local(shape, kchunk, poison_starts=True)

@@ -16,7 +16,8 @@
 //  * Maps of at most 256 rows with an even number of chunks run both horizontal directions at the same time, each on
 //    the half of the columns the other one is not working on.
 //  * SAVE stores the hidden states per direction (h_save); BWD is the reverse sweep of the two-pass backward scan on the
-//    same machinery (gy as x, u as lam, lam as u, gx as y, e into hs; see gspn_bwd_twopass.hip).
+//    same machinery (gy as x, u as lam, lam as u, gx as y, e into hs; see gspn_bwd_twopass.hip); LOCAL confines the
+//    propagation to stretches of kchunk lines (GSPN-local, Sec. 3.2).
 #pragma once
 #include "gspn_fwd_stream_impl.hpp"
 #include <utility>

@@ -244,7 +244,7 @@ const char* gspn_proxy_plan(int B, int K, int M, int H, int W, int dtype);
  *   GSPN_FWD_NO_PLANE=1, GSPN_BWD_NO_PLANE=1   skip the "plane" kernels
  *   GSPN_BWD_NO_TWOPASS=1   skip the "twopass" backward (the "tile" / "generic" kernels take its maps)
  *   GSPN_FWD_NO_PAIR=1   skip the "pair" kernels (forward and the reverse sweep of the two-pass backward)
- *   GSPN_STREAM_NO_STAGED=1   the general "stream" kernel (the one fp32 maps and logits calls take) on the 16-bit maps
+ *   GSPN_STREAM_NO_STAGED=1   the general "stream" kernel (the one fp32 maps take) on the 16-bit maps
  *                             that have a kernel of their own
  *   GSPN_STREAM_TWO_CHANNELS=1  two channels of a weight group per workgroup on those maps also in calls with at most 256
  *                               planes (which normally keep one channel per workgroup: a compute unit holds one workgroup)

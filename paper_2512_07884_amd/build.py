@@ -11,7 +11,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgspn.so")
-SOURCES = ["gspn_api.hip", "gspn_dispatch.hip", "gspn_generic.hip", "gspn_unfused.hip", "gspn_fwd_tile.hip", "gspn_fwd_tile_f32_global.hip", "gspn_fwd_tile_f32_local.hip", "gspn_fwd_tile_bf16_global.hip", "gspn_fwd_tile_bf16_local.hip", "gspn_fwd_tile_f16_global.hip", "gspn_fwd_tile_f16_local.hip", "gspn_fwd_stream.hip", "gspn_fwd_stream_f32.hip", "gspn_fwd_stream_bf16.hip", "gspn_fwd_stream_f16.hip", "gspn_fwd_stream_staged.hip", "gspn_fwd_stream_staged_bf16.hip", "gspn_fwd_stream_staged_f16.hip", "gspn_fwd_stream_staged_bf16_local.hip", "gspn_fwd_stream_staged_f16_local.hip", "gspn_fwd_stream_big.hip", "gspn_fwd_stream_big_global.hip", "gspn_fwd_stream_big_local.hip", "gspn_fwd_stream_big_logits.hip", "gspn_fwd_plane.hip", "gspn_fwd_pair.hip", "gspn_fwd_pair_bf16.hip", "gspn_fwd_pair_f16.hip", "gspn_fwd_chunk.hip", "gspn_bwd_tile.hip", "gspn_bwd_plane.hip", "gspn_bwd_twopass.hip", "gspn_bwd_twopass_f32.hip", "gspn_bwd_twopass_bf16.hip", "gspn_bwd_twopass_f32_local.hip", "gspn_bwd_twopass_bf16_local.hip", "gspn_bwd_twopass_f16.hip", "gspn_bwd_twopass_f16_local.hip", "gspn_proxy.hip"]
+SOURCES = ["gspn_api.hip", "gspn_dispatch.hip", "gspn_generic.hip", "gspn_unfused.hip", "gspn_fwd_tile.hip", "gspn_fwd_tile_f32_global.hip", "gspn_fwd_tile_f32_local.hip", "gspn_fwd_tile_bf16_global.hip", "gspn_fwd_tile_bf16_local.hip", "gspn_fwd_tile_f16_global.hip", "gspn_fwd_tile_f16_local.hip", "gspn_fwd_stream.hip", "gspn_fwd_stream_f32.hip", "gspn_fwd_stream_bf16.hip", "gspn_fwd_stream_f16.hip", "gspn_fwd_stream_staged.hip", "gspn_fwd_stream_staged_bf16.hip", "gspn_fwd_stream_staged_f16.hip", "gspn_fwd_stream_staged_bf16_local.hip", "gspn_fwd_stream_staged_f16_local.hip", "gspn_fwd_stream_staged_bf16_logits.hip", "gspn_fwd_stream_staged_f16_logits.hip", "gspn_fwd_stream_big.hip", "gspn_fwd_stream_big_global.hip", "gspn_fwd_stream_big_local.hip", "gspn_fwd_stream_big_logits.hip", "gspn_fwd_plane.hip", "gspn_fwd_pair.hip", "gspn_fwd_pair_bf16.hip", "gspn_fwd_pair_f16.hip", "gspn_fwd_chunk.hip", "gspn_bwd_tile.hip", "gspn_bwd_plane.hip", "gspn_bwd_twopass.hip", "gspn_bwd_twopass_f32.hip", "gspn_bwd_twopass_bf16.hip", "gspn_bwd_twopass_f32_local.hip", "gspn_bwd_twopass_bf16_local.hip", "gspn_bwd_twopass_f16.hip", "gspn_bwd_twopass_f16_local.hip", "gspn_proxy.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -33,6 +33,16 @@ SPILL_ALLOWED = {
     "fwd_stream_staged2_kernelINS_5f16_tELi4ELi4ELb1ELb1": 67, "fwd_stream_staged2_kernelINS_5f16_tELi8ELi4ELb1ELb1": 67,
     "fwd_stream_staged2_kernelINS_5f16_tELi16ELi2ELb1ELb1": 67,
     # (65 values in the global scan's reverse sweep in bf16, 67 in fp16 and in GSPN-local's)
+    # ... with the weights as logits (a softmax per scan step beside the chunk registers): values parked in scratch memory
+    # around the step loops of the forward call with h_save (36) and of the reverse sweep (99 with one channel per
+    # workgroup, 84 with two); these calls ran the general stream kernel before (long512 with logits 1.55 -> 1.13 ms);
+    # parity-tested on 256- and 512-row maps in bf16 and fp16
+    "fwd_stream_staged2_kernelItLi4ELi4ELb1ELb1ELb1ELb1": 84, "fwd_stream_staged_kernelItLi4ELi4ELb1ELb1ELb1ELb1": 99, "fwd_stream_staged_kernelItLi4ELi4ELb1ELb0ELb1ELb1": 36,
+    "fwd_stream_staged2_kernelItLi8ELi4ELb1ELb1ELb1ELb1": 84, "fwd_stream_staged_kernelItLi8ELi4ELb1ELb1ELb1ELb1": 99, "fwd_stream_staged_kernelItLi8ELi4ELb1ELb0ELb1ELb1": 36,
+    "fwd_stream_staged2_kernelItLi16ELi2ELb1ELb1ELb1ELb1": 84, "fwd_stream_staged_kernelItLi16ELi2ELb1ELb1ELb1ELb1": 99, "fwd_stream_staged_kernelItLi16ELi2ELb1ELb0ELb1ELb1": 36,
+    "fwd_stream_staged2_kernelINS_5f16_tELi4ELi4ELb1ELb1ELb1ELb1": 84, "fwd_stream_staged_kernelINS_5f16_tELi4ELi4ELb1ELb1ELb1ELb1": 99, "fwd_stream_staged_kernelINS_5f16_tELi4ELi4ELb1ELb0ELb1ELb1": 36,
+    "fwd_stream_staged2_kernelINS_5f16_tELi8ELi4ELb1ELb1ELb1ELb1": 84, "fwd_stream_staged_kernelINS_5f16_tELi8ELi4ELb1ELb1ELb1ELb1": 99, "fwd_stream_staged_kernelINS_5f16_tELi8ELi4ELb1ELb0ELb1ELb1": 36,
+    "fwd_stream_staged2_kernelINS_5f16_tELi16ELi2ELb1ELb1ELb1ELb1": 84, "fwd_stream_staged_kernelINS_5f16_tELi16ELi2ELb1ELb1ELb1ELb1": 99, "fwd_stream_staged_kernelINS_5f16_tELi16ELi2ELb1ELb0ELb1ELb1": 36,
     # sixteen-wave horizontal kernel for maps of up to 1024 rows (128 registers per lane), with h_save or as the reverse
     # sweep: loop-invariant addresses parked before the chunk loop and read back once per chunk of 16 / 32 scan steps,
     # between the step loops (no scratch access inside them)

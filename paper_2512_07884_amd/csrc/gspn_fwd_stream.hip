@@ -7,7 +7,7 @@ namespace gspn {
 hipError_t launch_stream_f32(const FwdParams& p, hipStream_t s, bool reverse);
 hipError_t launch_stream_bf16(const FwdParams& p, hipStream_t s, bool reverse);
 hipError_t launch_stream_f16(const FwdParams& p, hipStream_t s, bool reverse);
-// 16-bit storage, normalised weights (global scan or GSPN-local): horizontal phases with whole-line requests
+// 16-bit storage (global scan, GSPN-local, logits): horizontal phases with whole-line requests
 // (gspn_fwd_stream_staged.hip)
 bool stream_staged_applicable(const FwdParams& p, int dtype);
 hipError_t launch_stream_staged(const FwdParams& p, int dtype, bool reverse, hipStream_t s);

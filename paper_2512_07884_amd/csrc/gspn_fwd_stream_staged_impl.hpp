@@ -65,7 +65,7 @@ template <int CP = 0> __device__ __forceinline__ u32x4 ld128(rsrc_t rs, uint32_t
 // One horizontal direction for the wave that owns rows 64 * part .. of the plane.  Chunks [0, nchunks) in scan order;
 // `sync_at`: chunk before which the whole workgroup meets (the two directions swap halves there; -1: never);
 // `rmw_from`: first chunk (in scan order) whose y already holds a partial sum.
-template <typename T, bool REV, bool SAVE, bool BWD, bool LOCAL>
+template <typename T, bool REV, bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a, char* blk_b, float* mailbox, int parts, int b, int c,
                                                 int dslot, int part, int lane, int sync_at, int rmw_from) {
     constexpr int d = (REV != BWD) ? 3 : 2;
@@ -182,6 +182,8 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
             if ((k & 1) == 0) yw = yrow[e >> 1];
             const float av = elem<T>(bl, e) * elem<T>(bx, e);
             float c0 = elem<T>(b0, e), c1 = elem<T>(b1, e), c2 = elem<T>(b2, e);
+            // raw logits: normalised here over the taps whose neighbour row exists (Sec. 3.2)
+            if constexpr (LOGITS) softmax3(c0, c1, c2, img_first, img_last);
             if constexpr (BWD) {
                 // the edge rows publish the products that cross into the neighbouring part: tap 0 of a part's first row
                 // reads the row above it, tap 2 of its last row the row below
@@ -251,7 +253,7 @@ __device__ __forceinline__ void horizontal_rows(const FwdParams& p, char* blk_a,
 // already holds the vertical pair's sum.  Maps of 512 rows run one direction at a time (all eight waves hold rows,
 // sync_at < 0); maps of 256 rows both at once, four waves each (direction slot dslot), each first on the half of the
 // columns it starts in and, after the workgroup has met before chunk sync_at, on the other half.
-template <typename T, bool REV, bool SAVE, bool BWD, bool LOCAL>
+template <typename T, bool REV, bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a, char* blk_b, float* mailbox, int parts, int b, int c,
                                                  int dslot, int part, int lane, int sync_at) {
     constexpr int d = (REV != BWD) ? 3 : 2;
@@ -353,6 +355,8 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
             if ((k & 1) == 0) yw = yrow[e >> 1];
             const float av = elem<T>(bl, e) * elem<T>(bx, e);
             float c0 = elem<T>(b0, e), c1 = elem<T>(b1, e), c2 = elem<T>(b2, e);
+            // raw logits: normalised here over the taps whose neighbour row exists (Sec. 3.2)
+            if constexpr (LOGITS) softmax3(c0, c1, c2, img_first, img_last);
             if constexpr (BWD) {
                 const float q0 = wp0 * h, q2 = wp2 * h;
                 float up = from_lane_below(q2), dn = from_lane_above(q0);
@@ -440,7 +444,7 @@ __device__ __forceinline__ void horizontal_rows2(const FwdParams& p, char* blk_a
     }
 }
 
-template <typename T, int V, int PF, bool SAVE, bool BWD, bool LOCAL>
+template <typename T, int V, int PF, bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
     extern __shared__ char lds[];
     float* mailbox = (float*)(lds + 8 * 2 * BLOCK_B);
@@ -459,12 +463,12 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
         if (nd == 2) {
             const int split = (H + 1) / 2;
             if (wave == 0) {
-                VStream<T, V, PF, false, LOCAL, false, BWD, SAVE> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, false, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, c, lane);
                 v.template run<false>(0, split);
                 __syncthreads();
                 v.template run<true>(split, H);
             } else if (wave == 1) {
-                VStream<T, V, PF, true, LOCAL, false, BWD, SAVE> v; v.init(p, b, c, lane);
+                VStream<T, V, PF, true, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, c, lane);
                 v.template run<false>(0, H - split);
                 __syncthreads();
                 v.template run<true>(H - split, H);
@@ -474,8 +478,8 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
             wrote = true;
         } else if (nd == 1) {
             if (wave == 0) {
-                if ((has_tb != 0) != BWD) { VStream<T, V, PF, false, LOCAL, false, BWD, SAVE> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
-                else                      { VStream<T, V, PF, true, LOCAL, false, BWD, SAVE> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
+                if ((has_tb != 0) != BWD) { VStream<T, V, PF, false, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, c, lane); v.template run<false>(0, H); }
+                else                      { VStream<T, V, PF, true, LOCAL, LOGITS, BWD, SAVE> v;  v.init(p, b, c, lane); v.template run<false>(0, H); }
             }
             wrote = true;
         }
@@ -501,9 +505,9 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
                 for (int st = 0; st < CS; ++st) lds_barrier();      // idle wave: keep the barrier count
             }
         } else if ((dslot == 0) != BWD) {
-            horizontal_rows<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
+            horizontal_rows<T, false, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
         } else {
-            horizontal_rows<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
+            horizontal_rows<T, true, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, parts, b, c, dslot, part, lane, nchunks / 2, rmw_from);
         }
     } else {
         // one after the other; waves 0..parts-1 hold the rows
@@ -515,9 +519,9 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
             if (wave >= parts) {
                 for (int st = 0; st < W; ++st) lds_barrier();       // idle wave: keep the barrier count
             } else if ((dsel == 0) != BWD) {
-                horizontal_rows<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
+                horizontal_rows<T, false, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
             } else {
-                horizontal_rows<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
+                horizontal_rows<T, true, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, parts, b, c, 0, wave, lane, never, rmw_from);
             }
             wrote = true;
         }
@@ -527,7 +531,7 @@ __global__ void __launch_bounds__(512) fwd_stream_staged_kernel(StreamArgs a) {
 // Two channels of a weight group per workgroup on maps of 512 or 256 rows, all four directions: the vertical pairs of both
 // channels at the same time (waves 0, 1 and 2, 3), then the horizontal directions one after the other with the weights
 // shared (horizontal_rows2).
-template <typename T, int V, int PF, bool SAVE, bool BWD, bool LOCAL>
+template <typename T, int V, int PF, bool SAVE, bool BWD, bool LOCAL, bool LOGITS>
 __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
     extern __shared__ char lds[];
     float* mailbox = (float*)(lds + 8 * 2 * BLOCK_B);
@@ -544,12 +548,12 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         const int split = (H + 1) / 2;
         const int cv = c + (wave >> 1);
         if (wave < 4 && (wave & 1) == 0) {
-            VStream<T, V, PF, false, LOCAL, false, BWD, SAVE> v; v.init(p, b, cv, lane);
+            VStream<T, V, PF, false, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, cv, lane);
             v.template run<false>(0, split);
             __syncthreads();
             v.template run<true>(split, H);
         } else if (wave < 4) {
-            VStream<T, V, PF, true, LOCAL, false, BWD, SAVE> v; v.init(p, b, cv, lane);
+            VStream<T, V, PF, true, LOCAL, LOGITS, BWD, SAVE> v; v.init(p, b, cv, lane);
             v.template run<false>(0, H - split);
             __syncthreads();
             v.template run<true>(H - split, H);
@@ -565,8 +569,8 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         for (int dsel = 0; dsel < 2; ++dsel) {
             if (threadIdx.x < MAILBOX_FLOATS) mailbox[threadIdx.x] = 0.f;
             __syncthreads();                    // y of the previous phase complete, mailbox cleared
-            if ((dsel == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
-            else horizontal_rows2<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
+            if ((dsel == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
+            else horizontal_rows2<T, true, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, 8, b, c, 0, wave, lane, -1);
         }
     } else {
         // 256 rows: both directions at once, wave -> (direction slot, part)
@@ -574,38 +578,38 @@ __global__ void __launch_bounds__(512) fwd_stream_staged2_kernel(StreamArgs a) {
         __syncthreads();                        // y of the vertical pair complete, mailbox cleared
         const int nchunks = p.W / CS;
         const int dslot = wave >> 2, part = wave & 3;
-        if ((dslot == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
-        else horizontal_rows2<T, true, SAVE, BWD, LOCAL>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
+        if ((dslot == 0) != BWD) horizontal_rows2<T, false, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
+        else horizontal_rows2<T, true, SAVE, BWD, LOCAL, LOGITS>(p, blk_a, blk_b, mailbox, 4, b, c, dslot, part, lane, nchunks / 2);
     }
 }
 
-template <typename T, int V, int PF, bool LOCAL>
+template <typename T, int V, int PF, bool LOCAL, bool LOGITS>
 static hipError_t launch_staged(const StreamArgs& a, bool reverse, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * a.p.C)), block(512);
-    const void* k = reverse ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, true, LOCAL>
-                  : a.p.hs  ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, false, LOCAL>
-                            : (const void*)fwd_stream_staged_kernel<T, V, PF, false, false, LOCAL>;
+    const void* k = reverse ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, true, LOCAL, LOGITS>
+                  : a.p.hs  ? (const void*)fwd_stream_staged_kernel<T, V, PF, true, false, LOCAL, LOGITS>
+                            : (const void*)fwd_stream_staged_kernel<T, V, PF, false, false, LOCAL, LOGITS>;
     hipError_t e = allow_dynamic_lds(k, LDS_BYTES);
     if (e != hipSuccess) return e;
-    if (reverse) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, true, LOCAL>), grid, block, LDS_BYTES, s, a);
-    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, false, LOCAL>), grid, block, LDS_BYTES, s, a);
-    else hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, false, false, LOCAL>), grid, block, LDS_BYTES, s, a);
+    if (reverse) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, true, LOCAL, LOGITS>), grid, block, LDS_BYTES, s, a);
+    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, true, false, LOCAL, LOGITS>), grid, block, LDS_BYTES, s, a);
+    else hipLaunchKernelGGL((fwd_stream_staged_kernel<T, V, PF, false, false, LOCAL, LOGITS>), grid, block, LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-template <typename T, int V, int PF, bool LOCAL>
+template <typename T, int V, int PF, bool LOCAL, bool LOGITS>
 static hipError_t launch_staged2(const StreamArgs& a, bool reverse, hipStream_t s) {
     const dim3 grid((unsigned)((size_t)a.p.B * (a.p.C / 2))), block(512);
-    const void* k = reverse ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, true, LOCAL>
-                  : a.p.hs  ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, false, LOCAL>
-                            : (const void*)fwd_stream_staged2_kernel<T, V, PF, false, false, LOCAL>;
+    const void* k = reverse ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, true, LOCAL, LOGITS>
+                  : a.p.hs  ? (const void*)fwd_stream_staged2_kernel<T, V, PF, true, false, LOCAL, LOGITS>
+                            : (const void*)fwd_stream_staged2_kernel<T, V, PF, false, false, LOCAL, LOGITS>;
     hipError_t e = allow_dynamic_lds(k, LDS_BYTES);
     if (e != hipSuccess) return e;
-    if (reverse) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, true, LOCAL>), grid, block, LDS_BYTES, s, a);
-    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, false, LOCAL>), grid, block, LDS_BYTES, s, a);
-    else hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, false, false, LOCAL>), grid, block, LDS_BYTES, s, a);
+    if (reverse) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, true, LOCAL, LOGITS>), grid, block, LDS_BYTES, s, a);
+    else if (a.p.hs) hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, true, false, LOCAL, LOGITS>), grid, block, LDS_BYTES, s, a);
+    else hipLaunchKernelGGL((fwd_stream_staged2_kernel<T, V, PF, false, false, LOCAL, LOGITS>), grid, block, LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
@@ -621,25 +625,25 @@ static bool two_channels_ok(const FwdParams& p, const StreamPlan& t) {
            ((size_t)p.B * p.C > CHIP_CUS || stream_two_channels_forced());
 }
 
-// 16-bit storage, normalised weights (the global scan or GSPN-local), every shape the stream plan takes
+// 16-bit storage, every shape the stream plan takes
 static bool staged_shape_ok(const FwdParams& p, int dtype) {
-    return dtype != 0 && !p.logits && plan_stream(p, dtype).ok;
+    return dtype != 0 && plan_stream(p, dtype).ok;
 }
 
-template <typename T, bool LOCAL>
+template <typename T, bool LOCAL, bool LOGITS = false>
 static hipError_t launch_stream_staged_family(const FwdParams& p, bool reverse, hipStream_t s) {
     const StreamPlan t = plan_stream(p, 1);
     if (!t.ok || !staged_shape_ok(p, 1) || (reverse && !p.hs)) return hipErrorInvalidValue;
     StreamArgs a;
     a.p = p; a.parts = t.parts; a.nwaves = 8;
     if (two_channels_ok(p, t)) {
-        if (t.v == 4) return launch_staged2<T, 4, 4, LOCAL>(a, reverse, s);
-        if (t.v == 8) return launch_staged2<T, 8, 4, LOCAL>(a, reverse, s);
-        return launch_staged2<T, 16, 2, LOCAL>(a, reverse, s);
+        if (t.v == 4) return launch_staged2<T, 4, 4, LOCAL, LOGITS>(a, reverse, s);
+        if (t.v == 8) return launch_staged2<T, 8, 4, LOCAL, LOGITS>(a, reverse, s);
+        return launch_staged2<T, 16, 2, LOCAL, LOGITS>(a, reverse, s);
     }
-    if (t.v == 4) return launch_staged<T, 4, 4, LOCAL>(a, reverse, s);
-    if (t.v == 8) return launch_staged<T, 8, 4, LOCAL>(a, reverse, s);
-    return launch_staged<T, 16, 2, LOCAL>(a, reverse, s);
+    if (t.v == 4) return launch_staged<T, 4, 4, LOCAL, LOGITS>(a, reverse, s);
+    if (t.v == 8) return launch_staged<T, 8, 4, LOCAL, LOGITS>(a, reverse, s);
+    return launch_staged<T, 16, 2, LOCAL, LOGITS>(a, reverse, s);
 }
 
 }  // namespace gspn

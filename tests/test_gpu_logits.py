@@ -292,3 +292,17 @@ def test_logits_at_the_longest_supported_line(shape):
     assert rel_inf_err(to_host_f64(gx), gx_r) <= tol
     assert rel_inf_err(to_host_f64(gz), gz_r) <= tol
     assert rel_inf_err(to_host_f64(glam), glam_r) <= tol and rel_inf_err(to_host_f64(gu), gu_r) <= tol
+
+
+# the whole-line stream kernel of the 16-bit maps normalises the logits where it unpacks a step's taps: one channel per
+# workgroup (calls with few planes) and two channels of a group per workgroup (forced here); maps of 512 and of 256 rows;
+# global and GSPN-local; forward with and without h_save and the two-pass backward; taps that are never read poisoned
+@pytest.mark.parametrize("two_channels", [False, True], ids=["one-channel", "two-channels"])
+@pytest.mark.parametrize("shape,kchunk", [((1, 4, 512, 512, 2, "bf16"), None), ((1, 2, 256, 512, 1, "bf16"), 100),
+                                          ((1, 4, 256, 1024, 2, "f16"), None), ((1, 2, 512, 256, 1, "f16"), 64)],
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_logits_on_the_whole_line_stream_kernel(shape, kchunk, two_channels, monkeypatch):
+    monkeypatch.setenv("GSPN_FWD_NO_CHUNK", "1")
+    if two_channels:
+        monkeypatch.setenv("GSPN_STREAM_TWO_CHANNELS", "1")
+    check_logits(shape, kchunk=kchunk, poison=True, fwd_plan="stream", bwd_plan="twopass")
